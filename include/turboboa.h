@@ -1,0 +1,174 @@
+/*
+ * turboboa.h — C ABI of the TurboBoA quantization hot path for one attention block on MI355X.
+ *
+ * The library quantizes the projection weights of one attention block (W_Q, W_K, W_V, W_O) with the
+ * TurboBoA procedure (Algorithm 1 of the paper): Kronecker-factored attention-aware Hessians
+ * H = H_in (x) H_out (Table 1), U = Chol(H^-1)^T (eq. 3), joint quantization of N out-channels per
+ * sequential step with the closed-form compensation of the remaining out-channels (Prop. 3.1), the
+ * correction for errors propagated from earlier quantized layers (Prop. 3.2, R = alpha dX X^T), a grid
+ * recomputed for the rows of each step (Sec. 3.3), the in-channel sweep of Algorithm 3 and the
+ * coordinate-descent scale refinement of Prop. 3.3 / Algorithm 2.
+ *
+ * Conventions
+ *   - Every tensor pointer is DEVICE memory owned by the caller unless marked "host".  Inputs are never
+ *     modified; the library keeps no pointer after a call returns.  Temporary storage belongs to the
+ *     context (grown on demand, released by tboa_destroy).
+ *   - Matrices are dense row-major.  Activations are token-major: X[t, c] is channel c of token t, so the
+ *     paper's X (channels x tokens) is the transpose and H_in = X X^T = sum_t x_t x_t^T.
+ *     Weights are [out-channels, in-channels]; head h of a projection owns rows h*d_h .. (h+1)*d_h-1.
+ *   - All work is enqueued on the stream given to tboa_create; a call that returns a status read from the
+ *     device (factorisation breakdown) synchronises that stream once before returning.
+ *   - Every function returns 0 on success or a negative tboa_status; tboa_last_error() then describes it.
+ *     No exceptions, no abort, nothing printed.  One context per host thread.
+ */
+#ifndef TURBOBOA_H
+#define TURBOBOA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tboa_ctx tboa_ctx;
+
+enum tboa_status {
+    TBOA_OK = 0,
+    TBOA_EINVAL = -1,   /* null pointer, bad shape, unsupported parameter              */
+    TBOA_ENOTSPD = -2,  /* a Hessian is not positive definite (non-positive pivot)     */
+    TBOA_ENOMEM = -3,   /* workspace allocation failed                                  */
+    TBOA_EHIP = -4,     /* a HIP call failed (message carries hipGetErrorString)        */
+    TBOA_ENAN = -5      /* non-finite value met where a finite one is required          */
+};
+
+enum tboa_dtype { TBOA_F32 = 0, TBOA_BF16 = 1, TBOA_F64 = 2 };
+
+/* Creates a context bound to HIP device `hip_device`; all kernels run on `hip_stream`
+ * (a hipStream_t, e.g. torch.cuda.current_stream().cuda_stream; NULL = the default stream). */
+int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream);
+void tboa_destroy(tboa_ctx* ctx);
+/* Text of the last error on this context; owned by the context, valid until the next call on it. */
+const char* tboa_last_error(const tboa_ctx* ctx);
+/* Bytes of context-owned workspace currently allocated (host value). */
+size_t tboa_workspace_bytes(const tboa_ctx* ctx);
+
+/* ------------------------------------------------------------------------------------------------
+ * Attention block description (Algorithm 1 inputs).  T = n_seqs * seq_len tokens.
+ * GQA: query head h uses KV head h / (n_q_heads / n_kv_heads).
+ */
+typedef struct {
+    int d_model, n_q_heads, n_kv_heads, head_dim, n_seqs, seq_len;
+    int x_dtype;   /* tboa_dtype of X, X_fp and of the weights: TBOA_F32 or TBOA_BF16.
+                      TBOA_BF16: contractions run on bf16 MFMA with fp32 accumulation (operands are exact).
+                      TBOA_F32: contractions run on fp64 MFMA (small problems, reference-grade accuracy). */
+    int causal;    /* 1: causal mask inside A_h = softmax(Q_h K_h^T / sqrt(d_h)) */
+    double alpha;  /* stabilisation coefficient of Algorithm 1 line 5; R = alpha (X - X_fp) X^T */
+    int seq_chunk; /* sequences processed per pass of the W_V Hessian (0 = library default) */
+} tboa_attn_desc;
+
+/* Table 1 Hessian factors of W_Q,h / W_K,g / W_V,g and the deviation correlations R (Algorithm 1,
+ * lines 4-5).  Literal sums over all tokens, no normalisation, no damping.
+ *   X      [T, d_model]  input of the (partly quantized) model            (x_dtype)
+ *   X_fp   [T, d_model]  input of the full-precision model, or NULL: then R_qk and R_v are not written
+ *   Wq [Hq*dh, d], Wk, Wv [Hkv*dh, d], Wo [d, Hq*dh]                     (x_dtype)
+ * Outputs (fp32, caller-allocated):
+ *   Hin_qk [d, d]        = sum_t x_t x_t^T                    (H_in of W_Q and W_K)
+ *   R_qk   [d, d]        = alpha * sum_t (x_t - x~_t) x_t^T   (rows index the deviation)
+ *   Hout_q [Hq, dh, dh]  = K_g(h)^T K_g(h)
+ *   Hout_k [Hkv, dh, dh] = sum over query heads of the group of Q_h^T Q_h
+ *   Hin_v  [Hkv, d, d]   = sum over query heads of the group and sequences of (A_h X_s)^T (A_h X_s)
+ *   R_v    [Hkv, d, d]   = alpha * sum (A_h X_s - A~_h X~_s)^T (A_h X_s), or NULL to skip
+ *   Hout_v [Hkv, dh, dh] = sum over query heads of the group of W_out,h^T W_out,h
+ */
+int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* desc,
+                        const void* X, const void* X_fp,
+                        const void* Wq, const void* Wk, const void* Wv, const void* Wo,
+                        float* Hin_qk, float* R_qk, float* Hout_q, float* Hout_k,
+                        float* Hin_v, float* R_v, float* Hout_v);
+
+/* Hessian of the output projection: the layer-wise row of Table 1, X_o X_o^T (x) I, with X_o the
+ * attention output concat_h(A_h V_h) computed from the DEQUANTIZED W_Q, W_K, W_V (fp32 [.., d]) on X;
+ * R_o = alpha (X_o - X~_o) X_o^T with X~_o from the full-precision weights (x_dtype) on X_fp.
+ *   Hin_o [Hq*dh, Hq*dh] fp32;  R_o same shape or NULL (then X_fp, Wq, Wk, Wv may be NULL).
+ */
+int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* desc,
+                                const void* X, const void* X_fp,
+                                const float* Wq_deq, const float* Wk_deq, const float* Wv_deq,
+                                const void* Wq, const void* Wk, const void* Wv,
+                                float* Hin_o, float* R_o);
+
+/* Min-Max dynamic per-token activation quantizer (weight-activation experiments): one asymmetric
+ * (scale, zero) per token from that token's min and max, `bits` levels; writes the dequantized
+ * activations.  X_in, X_out [T, d] in `dtype` (TBOA_F32 or TBOA_BF16); may alias. */
+int tboa_act_fakequant(tboa_ctx* ctx, int64_t n_tokens, int d, int bits, int dtype,
+                       const void* X_in, void* X_out);
+
+/* ------------------------------------------------------------------------------------------------
+ * One projection weight (Algorithm 1 lines 2-13).
+ */
+typedef struct {
+    int d_out, d_in;
+    int n_heads;        /* d_out = n_heads * d_h; heads are independent                               */
+    int hin_per_head;   /* 0: H_in, R are [d_in, d_in]; 1: [n_heads, d_in, d_in] (W_V)                */
+    int bits;           /* 2, 3, 4 or 8                                                               */
+    int block;          /* N: out-channels quantized jointly per sequential step (ragged last block)  */
+    int group;          /* 0: one (scale, zero) per row; g > 0: per g consecutive in-channels, g | d_in */
+    int w_dtype;        /* tboa_dtype of W: TBOA_F32 or TBOA_BF16                                      */
+    int cd_iters;       /* n_iter of Algorithm 2 (paper: 1); 0 disables the refinement                */
+    int adaptive_grid;  /* 1: grid recomputed for the rows of each step (Algorithm 1 line 9);
+                           0: one grid from the original weights, kept fixed (BoA)                    */
+    int grid_points;    /* candidates per unit shrink (100)                                           */
+    double max_shrink;  /* candidates k = 0 .. ceil(max_shrink*grid_points)-1, range scaled by 1-k/grid_points */
+    double damp;        /* every Hessian gets damp * mean(diag) added to its diagonal at entry        */
+} tboa_layer_desc;
+
+/*   W      [d_out, d_in]            (w_dtype)
+ *   H_in   fp32, shape per hin_per_head
+ *   H_out  [n_heads, d_h, d_h] fp32, or NULL = identity (output projection / GPTQ: rows decouple,
+ *          no compensation between out-channels)
+ *   R      fp32, same shape as H_in, already scaled by alpha, or NULL = 0 (first block / BoA)
+ * Outputs:
+ *   codes  [d_out, d_in] uint8, one code per byte, 0 .. 2^bits-1
+ *   scales, zeros [d_out, n_groups] fp32 (n_groups = 1 or d_in/group); zeros hold integer values
+ *   W_deq  [d_out, d_in] fp32 = scales * (codes - zeros)
+ *   loss   host double[2] or NULL: {tr(H_out D H_in D^T), 2 tr(H_out W R D^T)} summed over heads, D = W_deq - W,
+ *          on the damped Hessians (the D-dependent part of the attention reconstruction error)
+ *   loss_per_head  host double[n_heads] or NULL: the sum of the two terms per head
+ */
+int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* desc,
+                        const void* W, const float* H_in, const float* H_out, const float* R,
+                        uint8_t* codes, float* scales, float* zeros, float* W_deq,
+                        double* loss, double* loss_per_head);
+
+/* ------------------------------------------------------------------------------------------------
+ * Building blocks, exported for stage-isolated checks and for roofline measurement.
+ */
+
+/* U = Chol(H^-1)^T (eq. 3): upper triangular, H^-1 = U^T U, for `batch` matrices of order n.
+ * H fp32 [batch, n, n] (only read); damp as in tboa_layer_desc; U fp64 [batch, n, n] (strict lower part zero). */
+int tboa_chol_inv_upper(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* U);
+
+/* C[b] = alpha * A[b] B[b] + beta * C[b] in fp64 on the fp64 matrix cores.
+ * A(m,k) = A[m*sam + k*sak], B(k,n) = B[k*sbk + n*sbn]; in each pair one stride must be 1. C row-major, ldc. */
+int tboa_gemm_f64(tboa_ctx* ctx, int M, int N, int K, double alpha,
+                  const double* A, int64_t sam, int64_t sak, const double* B, int64_t sbk, int64_t sbn,
+                  double beta, double* C, int64_t ldc,
+                  int batch, int64_t strideA, int64_t strideB, int64_t strideC);
+
+/* C[b] = alpha * A[b] B[b]^T (+ C[b] if accumulate) with bf16 operands, fp32 accumulation on the bf16
+ * matrix cores.  A [M, K] row-major lda, B [N, K] row-major ldb (both K-contiguous; lda, ldb multiples of 8,
+ * pointers 16-byte aligned).  C [M, N] ldc, fp32 (c_dtype = TBOA_F32) or bf16 (TBOA_BF16, accumulate must be 0).
+ * flags: TBOA_GEMM_LOWER computes only tiles on or below the diagonal (M == N; a symmetric product),
+ *        TBOA_GEMM_CAUSAL_K limits the contraction of output column n to k <= n rounded up to the tile
+ *        (B is lower triangular: causal attention probabilities). */
+enum { TBOA_GEMM_LOWER = 1, TBOA_GEMM_CAUSAL_K = 2 };
+int tboa_gemm_bf16_nt(tboa_ctx* ctx, int M, int N, int K, float alpha,
+                      const void* A, int64_t lda, const void* B, int64_t ldb,
+                      void* C, int64_t ldc, int c_dtype, int accumulate, int flags,
+                      int batch, int64_t strideA, int64_t strideB, int64_t strideC);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TURBOBOA_H */

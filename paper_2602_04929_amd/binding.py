@@ -1,0 +1,221 @@
+"""ctypes binding of libturboboa.so: argument marshalling only.
+
+Tensors are torch CUDA tensors (device memory and the stream come from PyTorch-ROCm); every
+computation happens inside the library's HIP kernels.  Importing this module without the built
+library raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libturboboa.so")
+
+F32, BF16, F64 = 0, 1, 2
+GEMM_LOWER, GEMM_CAUSAL_K = 1, 2
+
+STATUS = {0: "OK", -1: "EINVAL", -2: "ENOTSPD", -3: "ENOMEM", -4: "EHIP", -5: "ENAN"}
+
+
+class TurboBoAError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("%s: %s" % (STATUS.get(code, code), msg))
+        self.code = code
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("d_model", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
+                ("n_seqs", C.c_int), ("seq_len", C.c_int), ("x_dtype", C.c_int), ("causal", C.c_int),
+                ("alpha", C.c_double), ("seq_chunk", C.c_int)]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("d_out", C.c_int), ("d_in", C.c_int), ("n_heads", C.c_int), ("hin_per_head", C.c_int),
+                ("bits", C.c_int), ("block", C.c_int), ("group", C.c_int), ("w_dtype", C.c_int),
+                ("cd_iters", C.c_int), ("adaptive_grid", C.c_int), ("grid_points", C.c_int),
+                ("max_shrink", C.c_double), ("damp", C.c_double)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libturboboa.so is not built (run `python -c 'import __graft_entry__ as g; g.build()'`): "
+                          + LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32, f64 = C.c_void_p, C.c_int, C.c_int64, C.c_float, C.c_double
+    sigs = {
+        "tboa_create": ([C.POINTER(vp), i32, vp], i32),
+        "tboa_destroy": ([vp], None),
+        "tboa_last_error": ([vp], C.c_char_p),
+        "tboa_workspace_bytes": ([vp], C.c_size_t),
+        "tboa_gemm_f64": ([vp, i32, i32, i32, f64, vp, i64, i64, vp, i64, i64, f64, vp, i64, i32, i64, i64, i64], i32),
+        "tboa_gemm_bf16_nt": ([vp, i32, i32, i32, f32, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i64, i64, i64], i32),
+        "tboa_chol_inv_upper": ([vp, i32, i32, vp, f64, vp], i32),
+        "tboa_build_hessians": ([vp, C.POINTER(AttnDesc)] + [vp] * 13, i32),
+        "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 10, i32),
+        "tboa_act_fakequant": ([vp, i64, i32, i32, i32, vp, vp], i32),
+        "tboa_quantize_layer": ([vp, C.POINTER(LayerDesc)] + [vp] * 8 + [C.POINTER(f64), C.POINTER(f64)], i32),
+    }
+    missing = [n for n in sigs if not hasattr(lib, n)]
+    if missing:
+        raise ImportError("libturboboa.so lacks %s: rebuild it" % ", ".join(missing))
+    for name, (args, res) in sigs.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = res
+    return lib
+
+
+_lib = _load()
+
+
+
+def _dtype_code(t):
+    return {torch.float32: F32, torch.bfloat16: BF16, torch.float64: F64}[t.dtype]
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _dev(t, dtype=None):
+    assert t.is_cuda and t.is_contiguous(), "expected a contiguous CUDA tensor"
+    if dtype is not None:
+        assert t.dtype == dtype, "expected %s, got %s" % (dtype, t.dtype)
+    return t
+
+
+class Context:
+    """One library context on the current torch device and stream."""
+
+    def __init__(self, device=None, stream=None):
+        dev = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
+        self.device = dev
+        st = torch.cuda.current_stream(dev) if stream is None else stream
+        self._stream = st
+        h = C.c_void_p()
+        rc = _lib.tboa_create(C.byref(h), dev.index or 0, C.c_void_p(st.cuda_stream))
+        if rc != 0:
+            raise TurboBoAError(rc, "tboa_create failed")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.tboa_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def _check(self, rc):
+        if rc != 0:
+            raise TurboBoAError(rc, _lib.tboa_last_error(self._h).decode())
+
+    def workspace_bytes(self):
+        return int(_lib.tboa_workspace_bytes(self._h))
+
+    # ---- building blocks
+    def gemm_f64(self, A, B, C_out=None, alpha=1.0, beta=0.0, transA=False, transB=False):
+        """C = alpha op(A) op(B) + beta C for 2-D or batched 3-D fp64 tensors."""
+        batched = A.dim() == 3
+        A3 = A if batched else A[None]; B3 = B if batched else B[None]
+        _dev(A3, torch.float64); _dev(B3, torch.float64)
+        bs = A3.shape[0]
+        M, K = (A3.shape[2], A3.shape[1]) if transA else (A3.shape[1], A3.shape[2])
+        N = B3.shape[1] if transB else B3.shape[2]
+        if C_out is None:
+            C_out = torch.empty((bs, M, N) if batched else (M, N), dtype=torch.float64, device=A.device)
+        lda, ldb = A3.shape[2], B3.shape[2]
+        sam, sak = (1, lda) if transA else (lda, 1)
+        sbk, sbn = (1, ldb) if transB else (ldb, 1)
+        self._check(_lib.tboa_gemm_f64(self._h, M, N, K, alpha, _ptr(A3), sam, sak, _ptr(B3), sbk, sbn, beta,
+                                       _ptr(C_out), N, bs, A3.shape[1] * A3.shape[2], B3.shape[1] * B3.shape[2], M * N))
+        return C_out
+
+    def gemm_bf16_nt(self, A, B, out_dtype=torch.float32, alpha=1.0, C_out=None, accumulate=False, flags=0):
+        """C = alpha A B^T (+ C) for bf16 A [.., M, K], B [.., N, K]."""
+        batched = A.dim() == 3
+        A3 = A if batched else A[None]; B3 = B if batched else B[None]
+        _dev(A3, torch.bfloat16); _dev(B3, torch.bfloat16)
+        bs, M, K = A3.shape; N = B3.shape[1]
+        if C_out is None:
+            C_out = torch.zeros((bs, M, N) if batched else (M, N), dtype=out_dtype, device=A.device)
+        self._check(_lib.tboa_gemm_bf16_nt(self._h, M, N, K, alpha, _ptr(A3), K, _ptr(B3), K, _ptr(C_out), N,
+                                           _dtype_code(C_out), int(accumulate), flags, bs, M * K, N * K, M * N))
+        return C_out
+
+    def chol_inv_upper(self, H, damp=0.0):
+        """U = Chol(H^-1)^T for fp32 H [n, n] or [batch, n, n]; returns fp64."""
+        H3 = _dev(H if H.dim() == 3 else H[None], torch.float32)
+        U = torch.empty(H3.shape, dtype=torch.float64, device=H.device)
+        self._check(_lib.tboa_chol_inv_upper(self._h, H3.shape[1], H3.shape[0], _ptr(H3), damp, _ptr(U)))
+        return U if H.dim() == 3 else U[0]
+
+    # ---- the method
+    def build_hessians(self, X, X_fp, Wq, Wk, Wv, Wo, n_q_heads, n_kv_heads, head_dim, alpha=0.0, causal=True,
+                       with_R_v=True, seq_chunk=0):
+        S, L, d = X.shape
+        dt = X.dtype
+        for t in (X, Wq, Wk, Wv, Wo):
+            _dev(t, dt)
+        if X_fp is not None:
+            _dev(X_fp, dt)
+        desc = AttnDesc(d, n_q_heads, n_kv_heads, head_dim, S, L, _dtype_code(X), int(causal), alpha, seq_chunk)
+        f = dict(dtype=torch.float32, device=X.device)
+        dh = head_dim
+        out = dict(Hin_qk=torch.empty(d, d, **f), Hout_q=torch.empty(n_q_heads, dh, dh, **f),
+                   Hout_k=torch.empty(n_kv_heads, dh, dh, **f), Hin_v=torch.empty(n_kv_heads, d, d, **f),
+                   Hout_v=torch.empty(n_kv_heads, dh, dh, **f), R_qk=None, R_v=None)
+        if X_fp is not None:
+            out["R_qk"] = torch.empty(d, d, **f)
+            if with_R_v:
+                out["R_v"] = torch.empty(n_kv_heads, d, d, **f)
+        self._check(_lib.tboa_build_hessians(self._h, C.byref(desc), _ptr(X), _ptr(X_fp), _ptr(Wq), _ptr(Wk), _ptr(Wv),
+                                             _ptr(Wo), _ptr(out["Hin_qk"]), _ptr(out["R_qk"]), _ptr(out["Hout_q"]),
+                                             _ptr(out["Hout_k"]), _ptr(out["Hin_v"]), _ptr(out["R_v"]), _ptr(out["Hout_v"])))
+        return out
+
+    def build_hessian_out_proj(self, X, X_fp, Wq_deq, Wk_deq, Wv_deq, Wq, Wk, Wv, n_q_heads, n_kv_heads, head_dim,
+                               alpha=0.0, causal=True, seq_chunk=0):
+        S, L, d = X.shape
+        for t in (Wq_deq, Wk_deq, Wv_deq):
+            _dev(t, torch.float32)
+        desc = AttnDesc(d, n_q_heads, n_kv_heads, head_dim, S, L, _dtype_code(X), int(causal), alpha, seq_chunk)
+        dq = n_q_heads * head_dim
+        Hin_o = torch.empty(dq, dq, dtype=torch.float32, device=X.device)
+        R_o = torch.empty_like(Hin_o) if X_fp is not None else None
+        self._check(_lib.tboa_build_hessian_out_proj(self._h, C.byref(desc), _ptr(_dev(X)), _ptr(X_fp), _ptr(Wq_deq),
+                                                     _ptr(Wk_deq), _ptr(Wv_deq), _ptr(Wq), _ptr(Wk), _ptr(Wv),
+                                                     _ptr(Hin_o), _ptr(R_o)))
+        return Hin_o, R_o
+
+    def act_fakequant(self, X, bits, out=None):
+        _dev(X)
+        out = torch.empty_like(X) if out is None else out
+        d = X.shape[-1]
+        self._check(_lib.tboa_act_fakequant(self._h, X.numel() // d, d, bits, _dtype_code(X), _ptr(X), _ptr(out)))
+        return out
+
+    def quantize_layer(self, W, H_in, H_out, R, n_heads, bits, block, group=0, cd_iters=1, adaptive_grid=True,
+                       grid_points=100, max_shrink=0.8, damp=0.01):
+        _dev(W); _dev(H_in, torch.float32)
+        d_out, d_in = W.shape
+        ng = d_in // group if group else 1
+        desc = LayerDesc(d_out, d_in, n_heads, int(H_in.dim() == 3), bits, block, group, _dtype_code(W), cd_iters,
+                         int(adaptive_grid), grid_points, max_shrink, damp)
+        dev = W.device
+        codes = torch.empty(d_out, d_in, dtype=torch.uint8, device=dev)
+        scales = torch.empty(d_out, ng, dtype=torch.float32, device=dev)
+        zeros = torch.empty(d_out, ng, dtype=torch.float32, device=dev)
+        W_deq = torch.empty(d_out, d_in, dtype=torch.float32, device=dev)
+        loss = (C.c_double * 2)()
+        lph = (C.c_double * n_heads)()
+        if H_out is not None:
+            _dev(H_out, torch.float32)
+        if R is not None:
+            _dev(R, torch.float32)
+        self._check(_lib.tboa_quantize_layer(self._h, C.byref(desc), _ptr(W), _ptr(H_in), _ptr(H_out), _ptr(R),
+                                             _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(W_deq), loss, lph))
+        return dict(codes=codes, scales=scales, zeros=zeros, W_deq=W_deq, loss_quad=loss[0], loss_cross=loss[1],
+                    loss=loss[0] + loss[1], loss_per_head=list(lph))

@@ -1,0 +1,156 @@
+// Context, error reporting, workspace, and small elementwise kernels.
+#include "internal.h"
+
+int tboa_fail(tboa_ctx* ctx, int code, const char* fmt, ...) {
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+int tboa_ws_reserve(tboa_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->ws_bytes) return 0;
+    TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->ws) { TB_HIP(ctx, hipFree(ctx->ws)); ctx->ws = nullptr; ctx->ws_bytes = 0; }
+    hipError_t e = hipMalloc(&ctx->ws, bytes);
+    if (e != hipSuccess) {
+        ctx->ws = nullptr;
+        (void)hipGetLastError();
+        return tboa_fail(ctx, TBOA_ENOMEM, "workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
+    }
+    ctx->ws_bytes = bytes;
+    return 0;
+}
+
+extern "C" int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream) {
+    if (!out) return TBOA_EINVAL;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || hip_device < 0 || hip_device >= n) return TBOA_EINVAL;
+    if (hipSetDevice(hip_device) != hipSuccess) return TBOA_EHIP;
+    tboa_ctx* c = new tboa_ctx();
+    c->device = hip_device;
+    c->stream = (hipStream_t)hip_stream;
+    c->err[0] = 0;
+    c->ws = nullptr; c->ws_bytes = 0;
+    c->d_status = nullptr; c->h_status = nullptr;
+    if (hipMalloc(&c->d_status, 64 * sizeof(int)) != hipSuccess ||
+        hipHostMalloc(&c->h_status, 64 * sizeof(int)) != hipSuccess) {
+        if (c->d_status) (void)hipFree(c->d_status);
+        delete c;
+        return TBOA_ENOMEM;
+    }
+    *out = c;
+    return 0;
+}
+
+extern "C" void tboa_destroy(tboa_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->d_status) (void)hipFree(ctx->d_status);
+    if (ctx->h_status) (void)hipHostFree(ctx->h_status);
+    delete ctx;
+}
+
+extern "C" const char* tboa_last_error(const tboa_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+extern "C" size_t tboa_workspace_bytes(const tboa_ctx* ctx) { return ctx ? ctx->ws_bytes : 0; }
+
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+template <typename T>
+__global__ void fill_kernel(T* p, long long n, T v) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) p[i] = v;
+}
+
+template <typename S>
+__device__ __forceinline__ double to_f64(S v);
+template <> __device__ __forceinline__ double to_f64<float>(float v) { return (double)v; }
+template <> __device__ __forceinline__ double to_f64<double>(double v) { return v; }
+template <> __device__ __forceinline__ double to_f64<__hip_bfloat16>(__hip_bfloat16 v) { return (double)__bfloat162float(v); }
+
+template <typename S>
+__global__ void cvt_to_f64_kernel(const S* src, double* dst, long long n) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+        dst[i] = to_f64<S>(src[i]);
+}
+
+__global__ void cvt_f64_to_f32_kernel(const double* src, float* dst, long long n) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+        dst[i] = (float)src[i];
+}
+
+__global__ void strict_upper_kernel(double* a, int n) {
+    double* m = a + (long long)blockIdx.z * n * n;
+    const long long tot = (long long)n * n;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
+        const int r = (int)(i / n), c = (int)(i % n);
+        if (c <= r) m[i] = 0.0;
+    }
+}
+
+__global__ void mirror_lower_kernel(float* a, int n) {
+    float* m = a + (long long)blockIdx.z * n * n;
+    const long long tot = (long long)n * n;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
+        const int r = (int)(i / n), c = (int)(i % n);
+        if (c > r) m[i] = m[(long long)c * n + r];
+    }
+}
+
+__global__ void sub_kernel(const double* a, const double* b, double* o, long long n) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) o[i] = a[i] - b[i];
+}
+
+inline unsigned grid_for(long long n) {
+    long long g = (n + 255) / 256;
+    return (unsigned)(g < 1 ? 1 : (g > 16384 ? 16384 : g));
+}
+
+}  // namespace
+
+int launch_fill_f64(tboa_ctx* ctx, double* p, int64_t n, double v) {
+    if (n <= 0) return 0;
+    hipLaunchKernelGGL(fill_kernel<double>, dim3(grid_for(n)), dim3(256), 0, ctx->stream, p, (long long)n, v);
+    TB_KERNEL_CHECK(ctx); return 0;
+}
+int launch_fill_f32(tboa_ctx* ctx, float* p, int64_t n, float v) {
+    if (n <= 0) return 0;
+    hipLaunchKernelGGL(fill_kernel<float>, dim3(grid_for(n)), dim3(256), 0, ctx->stream, p, (long long)n, v);
+    TB_KERNEL_CHECK(ctx); return 0;
+}
+int launch_cvt_to_f64(tboa_ctx* ctx, const void* src, int dtype, double* dst, int64_t n) {
+    if (n <= 0) return 0;
+    if (dtype == TBOA_F32)
+        hipLaunchKernelGGL(cvt_to_f64_kernel<float>, dim3(grid_for(n)), dim3(256), 0, ctx->stream, (const float*)src, dst, (long long)n);
+    else if (dtype == TBOA_BF16)
+        hipLaunchKernelGGL(cvt_to_f64_kernel<__hip_bfloat16>, dim3(grid_for(n)), dim3(256), 0, ctx->stream, (const __hip_bfloat16*)src, dst, (long long)n);
+    else if (dtype == TBOA_F64)
+        hipLaunchKernelGGL(cvt_to_f64_kernel<double>, dim3(grid_for(n)), dim3(256), 0, ctx->stream, (const double*)src, dst, (long long)n);
+    else return tboa_fail(ctx, TBOA_EINVAL, "unsupported dtype %d", dtype);
+    TB_KERNEL_CHECK(ctx); return 0;
+}
+int launch_cvt_f32_to_f64(tboa_ctx* ctx, const float* src, double* dst, int64_t n) { return launch_cvt_to_f64(ctx, src, TBOA_F32, dst, n); }
+int launch_cvt_f64_to_f32(tboa_ctx* ctx, const double* src, float* dst, int64_t n) {
+    if (n <= 0) return 0;
+    hipLaunchKernelGGL(cvt_f64_to_f32_kernel, dim3(grid_for(n)), dim3(256), 0, ctx->stream, src, dst, (long long)n);
+    TB_KERNEL_CHECK(ctx); return 0;
+}
+int launch_strict_upper_f64(tboa_ctx* ctx, double* a, int n, int batch) {
+    hipLaunchKernelGGL(strict_upper_kernel, dim3(grid_for((long long)n * n), 1, batch), dim3(256), 0, ctx->stream, a, n);
+    TB_KERNEL_CHECK(ctx); return 0;
+}
+int launch_mirror_lower_f32(tboa_ctx* ctx, float* a, int n, int batch) {
+    hipLaunchKernelGGL(mirror_lower_kernel, dim3(grid_for((long long)n * n), 1, batch), dim3(256), 0, ctx->stream, a, n);
+    TB_KERNEL_CHECK(ctx); return 0;
+}
+int launch_sub_f64(tboa_ctx* ctx, const double* a, const double* b, double* out, int64_t n) {
+    if (n <= 0) return 0;
+    hipLaunchKernelGGL(sub_kernel, dim3(grid_for(n)), dim3(256), 0, ctx->stream, a, b, out, (long long)n);
+    TB_KERNEL_CHECK(ctx); return 0;
+}

@@ -1,0 +1,182 @@
+// U = Chol(H^-1)^T (eq. 3) without forming H^-1.
+//
+// With V upper triangular and H = V V^T (the Cholesky factorisation taken from the last index backwards),
+// H^-1 = V^-T V^-1, so U = V^-1 is upper triangular with positive diagonal and U^T U = H^-1: by uniqueness of
+// the Cholesky factor it is Chol(H^-1)^T.  One blocked factorisation plus one blocked triangular inverse, all in
+// fp64: diagonal blocks are factored and inverted inside LDS by one workgroup per matrix, the panel and trailing
+// updates are fp64-MFMA GEMMs batched over the matrices (the per-head Hessians of W_V factor in lockstep).
+#include "internal.h"
+
+namespace {
+
+constexpr int NB = TB_FACT_NB;
+
+// status[0] = 1 + column of the first non-positive pivot (0 = fine), status[1] = batch index
+__global__ __launch_bounds__(256) void diag_factor_kernel(double* __restrict__ H, int n, int j0, int bs,
+                                                          double* __restrict__ dinv, int blk, int nblk, int* status) {
+    __shared__ double V[NB][NB + 1];
+    __shared__ double W[NB][NB + 1];
+    const int b = blockIdx.x, t = threadIdx.x;
+    double* Hb = H + (long long)b * n * n;
+    for (int i = t; i < bs * bs; i += 256) {
+        const int r = i / bs, c = i % bs;
+        V[r][c] = (c >= r) ? Hb[(long long)(j0 + r) * n + j0 + c] : 0.0;
+    }
+    __syncthreads();
+    // H_jj = V V^T, V upper: columns from the last to the first
+    for (int c = bs - 1; c >= 0; --c) {
+        const double piv = V[c][c];
+        __syncthreads();
+        if (!(piv > 0.0)) {
+            if (t == 0) { if (atomicCAS(&status[0], 0, 1 + j0 + c) == 0) status[1] = b; }
+        }
+        const double dv = (piv > 0.0) ? sqrt(piv) : 1.0;
+        if (t < c) V[t][c] = V[t][c] / dv;
+        if (t == c) V[c][c] = dv;
+        __syncthreads();
+        // trailing (upper part): V[r][r2] -= V[r][c] * V[r2][c] for r <= r2 < c
+        for (int i = t; i < c * c; i += 256) {
+            const int r = i / c, r2 = i % c;
+            if (r2 >= r) V[r][r2] -= V[r][c] * V[r2][c];
+        }
+        __syncthreads();
+    }
+    // W = V^-1 (upper): one column per thread, back substitution
+    if (t < bs) {
+        const int c = t;
+        for (int r = bs - 1; r > c; --r) W[r][c] = 0.0;
+        W[c][c] = 1.0 / V[c][c];
+        for (int r = c - 1; r >= 0; --r) {
+            double s = 0.0;
+            for (int k = r + 1; k <= c; ++k) s += V[r][k] * W[k][c];
+            W[r][c] = -s / V[r][r];
+        }
+    }
+    __syncthreads();
+    double* D = dinv + ((long long)b * nblk + blk) * NB * NB;
+    for (int i = t; i < NB * NB; i += 256) {
+        const int r = i / NB, c = i % NB;
+        D[i] = (r < bs && c < bs) ? W[r][c] : 0.0;
+    }
+    for (int i = t; i < bs * bs; i += 256) {
+        const int r = i / bs, c = i % bs;
+        Hb[(long long)(j0 + r) * n + j0 + c] = V[r][c];   // lower part of the block becomes zero
+    }
+}
+
+__global__ void place_diag_inverse_kernel(double* __restrict__ U, int n, const double* __restrict__ dinv, int nblk) {
+    const int b = blockIdx.y, blk = blockIdx.x;
+    const int j0 = blk * NB, bs = min(NB, n - j0);
+    const double* D = dinv + ((long long)b * nblk + blk) * NB * NB;
+    double* Ub = U + (long long)b * n * n;
+    for (int i = threadIdx.x; i < bs * bs; i += blockDim.x) {
+        const int r = i / bs, c = i % bs;
+        Ub[(long long)(j0 + r) * n + j0 + c] = D[r * NB + c];
+    }
+}
+
+__global__ __launch_bounds__(256) void cvt_damp_kernel(const float* __restrict__ H, double* __restrict__ out, int n, double damp) {
+    __shared__ double red[256];
+    const int b = blockIdx.x, t = threadIdx.x;
+    const float* Hb = H + (long long)b * n * n;
+    double* Ob = out + (long long)b * n * n;
+    double s = 0.0;
+    for (int i = t; i < n; i += 256) s += (double)Hb[(long long)i * n + i];
+    red[t] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) { if (t < o) red[t] += red[t + o]; __syncthreads(); }
+    const double add = damp * (red[0] / (double)n);
+    for (int i = t; i < n; i += 256) Ob[(long long)i * n + i] = (double)Hb[(long long)i * n + i] + add;
+}
+
+__global__ void cvt_offdiag_kernel(const float* __restrict__ H, double* __restrict__ out, int n, long long total) {
+    const long long nn = (long long)n * n;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const long long e = i % nn;
+        const int r = (int)(e / n), c = (int)(e % n);
+        if (r != c) out[i] = (double)H[i];
+    }
+}
+
+}  // namespace
+
+int launch_f32_to_f64_damp(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* out) {
+    const long long total = (long long)batch * n * n;
+    long long g = (total + 255) / 256; if (g > 16384) g = 16384;
+    hipLaunchKernelGGL(cvt_offdiag_kernel, dim3((unsigned)g), dim3(256), 0, ctx->stream, H, out, n, total);
+    hipLaunchKernelGGL(cvt_damp_kernel, dim3(batch), dim3(256), 0, ctx->stream, H, out, n, damp);
+    TB_KERNEL_CHECK(ctx);
+    return 0;
+}
+
+int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H, double* U, double* tmp, double* dinv) {
+    const int nblk = (n + NB - 1) / NB;
+    const long long nn = (long long)n * n;
+    TB_HIP(ctx, hipMemsetAsync(ctx->d_status, 0, 2 * sizeof(int), ctx->stream));
+    for (int blk = nblk - 1; blk >= 0; --blk) {
+        const int j0 = blk * NB, bs = (n - j0 < NB) ? n - j0 : NB;
+        hipLaunchKernelGGL(diag_factor_kernel, dim3(batch), dim3(256), 0, ctx->stream, H, n, j0, bs, dinv, blk, nblk, ctx->d_status);
+        TB_KERNEL_CHECK(ctx);
+        if (j0 == 0) break;
+        // panel: V[0:j0, blk] = H[0:j0, blk] Vinv_jj^T   (in place: one column tile, each workgroup owns its rows)
+        GemmF64 p{};
+        p.M = j0; p.N = bs; p.K = bs; p.alpha = 1.0; p.beta = 0.0;
+        p.A = H + j0; p.sam = n; p.sak = 1;
+        p.B = dinv + (long long)blk * NB * NB; p.sbk = 1; p.sbn = NB;
+        p.C = H + j0; p.ldc = n;
+        p.batch = batch; p.strideA = nn; p.strideB = (long long)nblk * NB * NB; p.strideC = nn;
+        TB_TRY(gemm_f64(ctx, p));
+        // trailing: H[0:j0, 0:j0] -= V[0:j0, blk] V[0:j0, blk]^T  (upper part only)
+        GemmF64 s{};
+        s.M = j0; s.N = j0; s.K = bs; s.alpha = -1.0; s.beta = 1.0;
+        s.A = H + j0; s.sam = n; s.sak = 1;
+        s.B = H + j0; s.sbk = 1; s.sbn = n;
+        s.C = H; s.ldc = n; s.skip_lower = 1;
+        s.batch = batch; s.strideA = nn; s.strideB = nn; s.strideC = nn;
+        TB_TRY(gemm_f64(ctx, s));
+    }
+    // U = V^-1, block column by block column
+    TB_TRY(launch_fill_f64(ctx, U, (int64_t)batch * nn, 0.0));
+    hipLaunchKernelGGL(place_diag_inverse_kernel, dim3(nblk, batch), dim3(256), 0, ctx->stream, U, n, dinv, nblk);
+    TB_KERNEL_CHECK(ctx);
+    for (int blk = 1; blk < nblk; ++blk) {
+        const int j0 = blk * NB, bs = (n - j0 < NB) ? n - j0 : NB;
+        GemmF64 a{};   // tmp = U[0:j0, 0:j0] V[0:j0, blk]
+        a.M = j0; a.N = bs; a.K = j0; a.alpha = 1.0; a.beta = 0.0;
+        a.A = U; a.sam = n; a.sak = 1; a.klo_m = 1;
+        a.B = H + j0; a.sbk = n; a.sbn = 1;
+        a.C = tmp; a.ldc = NB;
+        a.batch = batch; a.strideA = nn; a.strideB = nn; a.strideC = (long long)n * NB;
+        TB_TRY(gemm_f64(ctx, a));
+        GemmF64 c{};   // U[0:j0, blk] = -tmp Vinv_jj
+        c.M = j0; c.N = bs; c.K = bs; c.alpha = -1.0; c.beta = 0.0;
+        c.A = tmp; c.sam = NB; c.sak = 1;
+        c.B = dinv + (long long)blk * NB * NB; c.sbk = NB; c.sbn = 1;
+        c.C = U + j0; c.ldc = n;
+        c.batch = batch; c.strideA = (long long)n * NB; c.strideB = (long long)nblk * NB * NB; c.strideC = nn;
+        TB_TRY(gemm_f64(ctx, c));
+    }
+    TB_HIP(ctx, hipMemcpyAsync(ctx->h_status, ctx->d_status, 2 * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->h_status[0] != 0)
+        return tboa_fail(ctx, TBOA_ENOTSPD, "Hessian %d of the batch is not positive definite: pivot %d is not positive",
+                         ctx->h_status[1], ctx->h_status[0] - 1);
+    return 0;
+}
+
+extern "C" int tboa_chol_inv_upper(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* U) {
+    if (!ctx) return TBOA_EINVAL;
+    if (n <= 0 || batch <= 0 || !H || !U) return tboa_fail(ctx, TBOA_EINVAL, "chol_inv_upper: bad arguments");
+    const int nblk = (n + NB - 1) / NB;
+    Arena plan(nullptr);
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        double* H64 = ar.get<double>((size_t)batch * n * n);
+        double* tmp = ar.get<double>((size_t)batch * n * NB);
+        double* dinv = ar.get<double>((size_t)batch * nblk * NB * NB);
+        if (!pass) { TB_TRY(tboa_ws_reserve(ctx, ar.off)); continue; }
+        TB_TRY(launch_f32_to_f64_damp(ctx, n, batch, H, damp, H64));
+        TB_TRY(chol_inv_upper_f64(ctx, n, batch, H64, U, tmp, dinv));
+    }
+    return 0;
+}

@@ -1,0 +1,104 @@
+// Internal declarations shared by the translation units of libturboboa (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+#include <string.h>
+#include "../../include/turboboa.h"
+
+struct tboa_ctx {
+    int device;
+    hipStream_t stream;
+    char err[768];
+    void* ws;            // context-owned workspace
+    size_t ws_bytes;
+    int* d_status;       // device status words (factorisation breakdown etc.)
+    int* h_status;       // pinned host mirror
+};
+
+int tboa_fail(tboa_ctx* ctx, int code, const char* fmt, ...);
+
+#define TB_HIP(ctx, call)                                                                          \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess)                                                                      \
+            return tboa_fail(ctx, TBOA_EHIP, "%s:%d %s: %s", __FILE__, __LINE__, #call,            \
+                             hipGetErrorString(e_));                                               \
+    } while (0)
+
+#define TB_TRY(expr)                                                                               \
+    do {                                                                                           \
+        int rc_ = (expr);                                                                          \
+        if (rc_ != 0) return rc_;                                                                  \
+    } while (0)
+
+#define TB_KERNEL_CHECK(ctx) TB_HIP(ctx, hipGetLastError())
+
+// Bump allocator over the context workspace.  With base == nullptr it only counts bytes, so the same
+// planning code sizes the workspace and then carves it.
+struct Arena {
+    char* base;
+    size_t off;
+    explicit Arena(void* b) : base((char*)b), off(0) {}
+    template <typename T>
+    T* get(size_t n) {
+        size_t bytes = (n * sizeof(T) + 255) & ~(size_t)255;
+        T* p = base ? (T*)(base + off) : nullptr;
+        off += bytes;
+        return p;
+    }
+};
+int tboa_ws_reserve(tboa_ctx* ctx, size_t bytes);
+
+static inline int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---------------------------------------------------------------- gemm_f64.hip
+struct GemmF64 {
+    int M, N, K;
+    double alpha, beta;
+    const double* A; int64_t sam, sak;
+    const double* B; int64_t sbk, sbn;
+    double* C; int64_t ldc;
+    int batch; int64_t strideA, strideB, strideC;
+    // optional restriction of the contraction range per output tile (operands with triangular zeros):
+    // k_lo = max(klo_m ? tile row start : 0, klo_n ? tile col start : 0)
+    // k_hi = min(khi_m ? tile row end : K, khi_n ? tile col end : K); tiles with k_lo >= k_hi write beta*C.
+    int klo_m = 0, klo_n = 0, khi_m = 0, khi_n = 0;
+    int skip_lower = 0;  // skip tiles entirely below the diagonal (col end <= row start): left untouched
+    int skip_upper = 0;  // skip tiles entirely above the diagonal (row end <= col start)
+};
+int gemm_f64(tboa_ctx* ctx, const GemmF64& g);
+
+// ---------------------------------------------------------------- gemm_bf16.hip
+struct GemmBf16 {
+    int M, N, K;
+    float alpha;
+    const __hip_bfloat16* A; int64_t lda;
+    const __hip_bfloat16* B; int64_t ldb;
+    void* C; int64_t ldc; int c_dtype; int accumulate; int flags;
+    int batch; int64_t strideA, strideB, strideC;
+    // two-level batch: z -> (z / batch_inner, z % batch_inner); the *2 strides apply to the inner index
+    int batch_inner = 1; int64_t strideA2 = 0, strideB2 = 0, strideC2 = 0;
+};
+int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
+
+// ---------------------------------------------------------------- factor.hip
+// H64 [batch, n, n] fp64, overwritten; U [batch, n, n] fp64 out.  Checks the device status and
+// returns TBOA_ENOTSPD on breakdown (synchronises).  tmp: workspace of batch*n*TB_FACT_NB doubles.
+#define TB_FACT_NB 64
+int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H64, double* U, double* tmp, double* dinv);
+int launch_f32_to_f64_damp(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* out);
+
+// ---------------------------------------------------------------- misc elementwise (elementwise.hip)
+int launch_fill_f64(tboa_ctx* ctx, double* p, int64_t n, double v);
+int launch_fill_f32(tboa_ctx* ctx, float* p, int64_t n, float v);
+int launch_cvt_to_f64(tboa_ctx* ctx, const void* src, int dtype, double* dst, int64_t n);
+int launch_cvt_f64_to_f32(tboa_ctx* ctx, const double* src, float* dst, int64_t n);
+int launch_cvt_f32_to_f64(tboa_ctx* ctx, const float* src, double* dst, int64_t n);
+// out[r, c] = in[r, c] for c > r else 0 (square n x n, batch)
+int launch_strict_upper_f64(tboa_ctx* ctx, double* a, int n, int batch);
+// symmetrise: upper <- lower (fp32, n x n, batch)
+int launch_mirror_lower_f32(tboa_ctx* ctx, float* a, int n, int batch);
+int launch_sub_f64(tboa_ctx* ctx, const double* a, const double* b, double* out, int64_t n);

@@ -1,0 +1,594 @@
+// tboa_quantize_layer: Algorithm 1 (lines 2-13) for one projection weight, all arithmetic in fp64.
+//
+// Heads are independent and run side by side: the N rows of the current step of every head form one
+// "block" of n_heads*N rows (block row R = h*nbr + r  <->  layer row h*d_h + i0 + r).  Per step:
+//   grid search   (Alg. 1 line 9)  candidates -> delta matrix -> one fp64 GEMM with H_in -> row dots -> argmin
+//   in-channel sweep (Algorithm 3) panels of 64 columns: a wavefront owns a row, lane k holds column k, the 64
+//                                  sequential column steps run inside the kernel with U/P panel rows in LDS;
+//                                  columns right of the panel get one rank-64 GEMM update per term
+//   compensation  (Prop. 3.1/3.2)  T = [U_out^T]_{i1:,B} [U_out^T]_{B,B}^-1 per head, then W~[i1:] -= T E as a
+//                                  batched GEMM, E = (W_B - Q_B) - ((W_B R) U_in^T) U_in
+// and after the last step the coordinate descent of Algorithm 2 on precomputed d_h x d_h Gram matrices.
+#include "internal.h"
+#include <math.h>
+
+namespace {
+
+struct BlockMap { int nbr, dh, i0; };
+__device__ __forceinline__ long long layer_row(const BlockMap& m, int R) {
+    return (long long)(R / m.nbr) * m.dh + m.i0 + (R % m.nbr);
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int l) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_readlane(lo, l);
+    hi = __builtin_amdgcn_readlane(hi, l);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ double quant_code(double w, double s, double z, double maxq) {
+    return fmin(fmax(rint(w / s) + z, 0.0), maxq);
+}
+
+// ------------------------------------------------------------------------------------------------ rows
+__global__ void gather_rows_kernel(const double* __restrict__ src, double* __restrict__ dst, BlockMap m, int n) {
+    const int R = blockIdx.y;
+    const double* s = src + layer_row(m, R) * n;
+    double* d = dst + (long long)R * n;
+    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < n; c += gridDim.x * blockDim.x) d[c] = s[c];
+}
+
+// ------------------------------------------------------------------------------------------------ grid search
+// one wavefront per row: range of the row, then the candidate list (s_k, z_k)
+__global__ __launch_bounds__(256) void grid_candidates_kernel(const double* __restrict__ Wk, long long ldw, int c0, int ncols,
+                                                              int rows, int ncand, int grid_points, double maxq,
+                                                              double* __restrict__ cand_s, double* __restrict__ cand_z) {
+    const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const double* w = Wk + (long long)row * ldw + c0;
+    double lo = 0.0, hi = 0.0;
+    for (int c = lane; c < ncols; c += 64) { const double v = w[c]; lo = fmin(lo, v); hi = fmax(hi, v); }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { lo = fmin(lo, __shfl_xor(lo, o, 64)); hi = fmax(hi, __shfl_xor(hi, o, 64)); }
+    if (lo == hi) { lo = -1.0; hi = 1.0; }
+    for (int k = lane; k < ncand; k += 64) {
+        const double p = 1.0 - (double)k / (double)grid_points;
+        const double s = (p * hi - p * lo) / maxq;
+        const double z = rint(-(p * lo) / s);
+        cand_s[(long long)row * ncand + k] = s;
+        cand_z[(long long)row * ncand + k] = z;
+    }
+}
+
+// Delta[(row, k), c] = s_k (clamp(round(w_c / s_k) + z_k) - z_k) - w_c
+__global__ __launch_bounds__(256) void grid_delta_kernel(const double* __restrict__ Wk, long long ldw, int c0, int ncols, int ncand,
+                                                         double maxq, const double* __restrict__ cand_s,
+                                                         const double* __restrict__ cand_z, double* __restrict__ Delta) {
+    const int row = blockIdx.y;
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= ncols) return;
+    const double w = Wk[(long long)row * ldw + c0 + c];
+    const double* cs = cand_s + (long long)row * ncand;
+    const double* cz = cand_z + (long long)row * ncand;
+    double* out = Delta + (long long)row * ncand * ncols + c;
+    for (int k = 0; k < ncand; ++k) {
+        const double s = cs[k], z = cz[k];
+        const double q = quant_code(w, s, z, maxq);
+        out[(long long)k * ncols] = s * (q - z) - w;
+    }
+}
+
+// out[i] = sum_c A[i, c] B[i, c], one wavefront per row
+__global__ __launch_bounds__(256) void rowdot_kernel(const double* __restrict__ A, long long lda, const double* __restrict__ B,
+                                                     long long ldb, long long rows, int ncols, double* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const double* a = A + row * lda; const double* b = B + row * ldb;
+    double s = 0.0;
+    for (int c = lane; c < ncols; c += 64) s += a[c] * b[c];
+    s = wave_sum(s);
+    if (lane == 0) out[row] = s;
+}
+
+// lowest k among the minima of cost[row, :] -> (s, z) of that candidate
+__global__ void grid_argmin_kernel(const double* __restrict__ cost, const double* __restrict__ cand_s,
+                                   const double* __restrict__ cand_z, int rows, int ncand, BlockMap m, int r_off,
+                                   double* __restrict__ s_out, double* __restrict__ z_out, int ng, int gi) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    const double* c = cost + (long long)row * ncand;
+    int best = 0; double bc = c[0];
+    for (int k = 1; k < ncand; ++k) if (c[k] < bc) { bc = c[k]; best = k; }
+    const long long lr = layer_row(m, r_off + row);
+    s_out[lr * ng + gi] = cand_s[(long long)row * ncand + best];
+    z_out[lr * ng + gi] = cand_z[(long long)row * ncand + best];
+}
+
+// ------------------------------------------------------------------------------------------------ Algorithm 3
+struct SweepArgs {
+    double* Wk; int n; int nbr; BlockMap map;
+    const double* U; const double* P; int per_head;   // U, P: [n, n] or [n_heads, n, n]
+    int c0, pw;
+    const double* s; const double* z; int ng, gi; double maxq;
+    uint8_t* codes; double* Q;       // layer arrays [d_out, n]
+    double* Epan; double* Wsnap;     // block arrays [rows, 64]
+};
+
+template <int RPW>
+__global__ __launch_bounds__(256) void sweep_panel_kernel(SweepArgs a) {
+    __shared__ double Us[64][64];
+    __shared__ double Ps[64][64];
+    const int h = blockIdx.y, n = a.n, c0 = a.c0, pw = a.pw;
+    const double* U = a.U + (a.per_head ? (long long)h * n * n : 0);
+    const double* P = a.P ? a.P + (a.per_head ? (long long)h * n * n : 0) : nullptr;
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int j = i >> 6, k = i & 63;
+        const bool in = (j < pw && k < pw);
+        Us[j][k] = in ? U[(long long)(c0 + j) * n + c0 + k] : 0.0;
+        Ps[j][k] = (in && P) ? P[(long long)(c0 + j) * n + c0 + k] : 0.0;
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double w[RPW], s[RPW], z[RPW], qv[RPW], Qv[RPW], ev[RPW], wsv[RPW];
+    int R[RPW]; bool valid[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const int r = (blockIdx.x * 4 + wave) * RPW + i;
+        valid[i] = r < a.nbr;
+        R[i] = h * a.nbr + (valid[i] ? r : 0);
+        const long long lr = layer_row(a.map, R[i]);
+        w[i] = (valid[i] && lane < pw) ? a.Wk[(long long)R[i] * n + c0 + lane] : 0.0;
+        s[i] = a.s[lr * a.ng + a.gi]; z[i] = a.z[lr * a.ng + a.gi];
+        qv[i] = Qv[i] = ev[i] = wsv[i] = 0.0;
+    }
+    const bool hasP = (P != nullptr);
+    for (int j = 0; j < pw; ++j) {
+        const double urow = Us[j][lane], prow = Ps[j][lane], ujj = Us[j][j];
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const double wj = readlane_f64(w[i], j);
+            const double q = quant_code(wj, s[i], z[i], a.maxq);
+            const double Qj = s[i] * (q - z[i]);
+            const double e = (wj - Qj) / ujj;
+            if (lane == j) { qv[i] = q; Qv[i] = Qj; ev[i] = e; wsv[i] = wj; }
+            w[i] = w[i] - e * urow;
+            if (hasP) w[i] = w[i] - wj * prow;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        if (!valid[i]) continue;
+        a.Epan[(long long)R[i] * 64 + lane] = ev[i];
+        a.Wsnap[(long long)R[i] * 64 + lane] = wsv[i];
+        if (lane < pw) {
+            const long long lr = layer_row(a.map, R[i]);
+            a.codes[lr * n + c0 + lane] = (uint8_t)qv[i];
+            a.Q[lr * n + c0 + lane] = Qv[i];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ Prop. 3.1 / 3.2
+// E[R, c] = Wb[R, c] - Q[layer_row(R), c] (- S3[R, c])
+__global__ void comp_error_kernel(const double* __restrict__ Wb, const double* __restrict__ Q, const double* __restrict__ S3,
+                                  double* __restrict__ E, BlockMap m, int n) {
+    const int R = blockIdx.y;
+    const double* q = Q + layer_row(m, R) * n;
+    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < n; c += gridDim.x * blockDim.x) {
+        const long long i = (long long)R * n + c;
+        double e = Wb[i] - q[c];
+        if (S3) e -= S3[i];
+        E[i] = e;
+    }
+}
+
+// T[h, a, :] = Lo[a, B] Lo[B, B]^-1 for a = i1 .. dh-1, Lo = U_out[h]^T (lower): right-hand triangular solve,
+// one thread per remaining row, columns from the last to the first.
+__global__ void comp_T_kernel(const double* __restrict__ Uout, int dh, int i0, int i1, double* __restrict__ T, int TP) {
+    const int h = blockIdx.y;
+    const int a = i1 + blockIdx.x * blockDim.x + threadIdx.x;
+    if (a >= dh) return;
+    const double* U = Uout + (long long)h * dh * dh;
+    double* t = T + ((long long)h * dh + a) * TP;
+    const int nb = i1 - i0;
+    for (int c = nb - 1; c >= 0; --c) {
+        double acc = U[(long long)(i0 + c) * dh + a];                 // Lo[a, i0+c]
+        for (int k = c + 1; k < nb; ++k) acc -= t[k] * U[(long long)(i0 + c) * dh + i0 + k];   // Lo[i0+k, i0+c]
+        t[c] = acc / U[(long long)(i0 + c) * dh + i0 + c];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ Algorithm 2
+// Wbar = codes - z (per group)
+__global__ void wbar_kernel(const uint8_t* __restrict__ codes, const double* __restrict__ z, int ng, int gsz, int n,
+                            double* __restrict__ Wbar) {
+    const int r = blockIdx.y;
+    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < n; c += gridDim.x * blockDim.x)
+        Wbar[(long long)r * n + c] = (double)codes[(long long)r * n + c] - z[(long long)r * ng + c / gsz];
+}
+
+// Per head: s_j += sum_k (F[j,k] - s_k C[j,k]) Ho[k,j] / (C[j,j] Ho[j,j]) in order j = 0..dh-1,
+// F = Wbar (W (H_in - R))^T, C = Wbar H_in Wbar^T   (Prop. 3.3 with Q = diag(s) Wbar)
+__global__ __launch_bounds__(256) void cd_head_kernel(const double* __restrict__ F, const double* __restrict__ Cm,
+                                                      const double* __restrict__ Ho, int dh, int iters, double* __restrict__ s_all) {
+    extern __shared__ double sh[];
+    double* s = sh; double* red = sh + dh;
+    const int h = blockIdx.x, t = threadIdx.x;
+    const double* Fh = F + (long long)h * dh * dh; const double* Ch = Cm + (long long)h * dh * dh;
+    const double* Hh = Ho + (long long)h * dh * dh;
+    double* sg = s_all + (long long)h * dh;
+    for (int i = t; i < dh; i += 256) s[i] = sg[i];
+    __syncthreads();
+    for (int it = 0; it < iters; ++it)
+        for (int j = 0; j < dh; ++j) {
+            double acc = 0.0;
+            for (int k = t; k < dh; k += 256) acc += (Fh[(long long)j * dh + k] - s[k] * Ch[(long long)j * dh + k]) * Hh[(long long)k * dh + j];
+            acc = wave_sum(acc);
+            if ((t & 63) == 0) red[t >> 6] = acc;
+            __syncthreads();
+            if (t == 0) {
+                const double num = (red[0] + red[1]) + (red[2] + red[3]);
+                const double den = Ch[(long long)j * dh + j] * Hh[(long long)j * dh + j];
+                if (den > 0.0) s[j] = s[j] + num / den;
+            }
+            __syncthreads();
+        }
+    for (int i = t; i < dh; i += 256) sg[i] = s[i];
+}
+
+// identity H_out: rows decouple, s_j += (F_jj - s_j C_jj) / C_jj
+__global__ void cd_diag_kernel(const double* __restrict__ Fd, const double* __restrict__ Cd, int rows, int iters, double* __restrict__ s) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= rows) return;
+    double v = s[j];
+    for (int it = 0; it < iters; ++it) if (Cd[j] > 0.0) v = v + (Fd[j] - v * Cd[j]) / Cd[j];
+    s[j] = v;
+}
+
+// Q = s * Wbar, plus the fp32 outputs
+__global__ void finalize_kernel(const double* __restrict__ Wbar, const double* __restrict__ s, const double* __restrict__ z,
+                                int ng, int gsz, int n, double* __restrict__ Q, float* __restrict__ Wdeq,
+                                float* __restrict__ scales, float* __restrict__ zeros) {
+    const int r = blockIdx.y;
+    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < n; c += gridDim.x * blockDim.x) {
+        const double q = s[(long long)r * ng + c / gsz] * Wbar[(long long)r * n + c];
+        Q[(long long)r * n + c] = q;
+        Wdeq[(long long)r * n + c] = (float)q;
+    }
+    if (blockIdx.x == 0)
+        for (int g = threadIdx.x; g < ng; g += blockDim.x) {
+            scales[(long long)r * ng + g] = (float)s[(long long)r * ng + g];
+            zeros[(long long)r * ng + g] = (float)z[(long long)r * ng + g];
+        }
+}
+
+// out[h] = scale * sum_{j,k} Ho[h][j,k] M[h][k,j]
+__global__ __launch_bounds__(256) void head_trace_kernel(const double* __restrict__ Ho, const double* __restrict__ M, int dh,
+                                                         double scale, double* __restrict__ out) {
+    __shared__ double red[4];
+    const int h = blockIdx.x, t = threadIdx.x;
+    const double* Hh = Ho + (long long)h * dh * dh; const double* Mh = M + (long long)h * dh * dh;
+    double acc = 0.0;
+    for (int i = t; i < dh * dh; i += 256) { const int j = i / dh, k = i % dh; acc += Hh[i] * Mh[(long long)k * dh + j]; }
+    acc = wave_sum(acc);
+    if ((t & 63) == 0) red[t >> 6] = acc;
+    __syncthreads();
+    if (t == 0) out[h] = scale * ((red[0] + red[1]) + (red[2] + red[3]));
+}
+
+// out[h] = scale * sum over the rows of head h of v[row]
+__global__ __launch_bounds__(256) void head_sum_kernel(const double* __restrict__ v, int dh, double scale, double* __restrict__ out) {
+    __shared__ double red[4];
+    const int h = blockIdx.x, t = threadIdx.x;
+    double acc = 0.0;
+    for (int i = t; i < dh; i += 256) acc += v[(long long)h * dh + i];
+    acc = wave_sum(acc);
+    if ((t & 63) == 0) red[t >> 6] = acc;
+    __syncthreads();
+    if (t == 0) out[h] = scale * ((red[0] + red[1]) + (red[2] + red[3]));
+}
+
+inline unsigned gx(long long n) { long long g = (n + 255) / 256; return (unsigned)(g < 1 ? 1 : (g > 64 ? 64 : g)); }
+
+// ------------------------------------------------------------------------------------------------ host side
+struct Layer {
+    tboa_ctx* ctx; const tboa_layer_desc* d;
+    int n, nh, dh, ng, gsz, nhin, ncand; double maxq;
+    // workspace
+    double *W64, *Wt, *Hi, *Hfac, *Uin, *Rd, *P, *Ho, *Hofac, *Uout, *ftmp, *fdinv;
+    double *Q64, *s64, *z64;
+    double *Wb, *Wk, *Epan, *Wsnap, *E, *S1, *S2, *T;
+    double *cand_s, *cand_z, *Delta, *G, *cost;
+    double *Wbar, *Abar, *Z, *WR, *Cm, *Fm, *dvec, *lossbuf;
+    int grid_chunk;     // block rows (shared H_in) or heads (per-head H_in) per grid-search pass
+    long long nn;
+};
+
+int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head, BlockMap map, int c0, int ncols, int gi) {
+    tboa_ctx* ctx = L.ctx;
+    const int nh = L.nh, ncand = L.ncand;
+    const bool ph = L.nhin > 1;
+    const int total_rows = nh * rows_per_head;
+    const int units = ph ? nh : total_rows;                 // chunk unit: a head or a row
+    const int rows_per_unit = ph ? rows_per_head : 1;
+    for (int u0 = 0; u0 < units; u0 += L.grid_chunk) {
+        const int nu = (units - u0 < L.grid_chunk) ? units - u0 : L.grid_chunk;
+        const int r0 = u0 * rows_per_unit, rows = nu * rows_per_unit;
+        const double* Wc = Wrows + (long long)r0 * ldw;
+        hipLaunchKernelGGL(grid_candidates_kernel, dim3((rows + 3) / 4), dim3(256), 0, ctx->stream, Wc, ldw, c0, ncols, rows,
+                           ncand, L.d->grid_points, L.maxq, L.cand_s, L.cand_z);
+        hipLaunchKernelGGL(grid_delta_kernel, dim3((ncols + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, c0, ncols, ncand,
+                           L.maxq, L.cand_s, L.cand_z, L.Delta);
+        TB_KERNEL_CHECK(ctx);
+        GemmF64 g{};
+        g.N = ncols; g.K = ncols; g.alpha = 1.0; g.beta = 0.0;
+        g.A = L.Delta; g.sam = ncols; g.sak = 1;
+        g.sbk = L.n; g.sbn = 1; g.C = L.G; g.ldc = ncols;
+        if (ph) {
+            g.M = rows_per_head * ncand; g.batch = nu;
+            g.B = L.Hi + (long long)u0 * L.nn + (long long)c0 * L.n + c0;
+            g.strideA = (long long)g.M * ncols; g.strideB = L.nn; g.strideC = g.strideA;
+        } else {
+            g.M = rows * ncand; g.batch = 1;
+            g.B = L.Hi + (long long)c0 * L.n + c0;
+        }
+        TB_TRY(gemm_f64(ctx, g));
+        const long long crow = (long long)rows * ncand;
+        hipLaunchKernelGGL(rowdot_kernel, dim3((unsigned)((crow + 3) / 4)), dim3(256), 0, ctx->stream, L.G, (long long)ncols, L.Delta,
+                           (long long)ncols, crow, ncols, L.cost);
+        hipLaunchKernelGGL(grid_argmin_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.cost, L.cand_s, L.cand_z, rows,
+                           ncand, map, r0, L.s64, L.z64, L.ng, gi);
+        TB_KERNEL_CHECK(ctx);
+    }
+    return 0;
+}
+
+// one GEMM over all block rows (shared H_in) or batched per head (per-head H_in): C = alpha A op(B) + beta C,
+// A, C block arrays [nh*nbr, *]; B a d_in x d_in matrix (or one per head) addressed by (sbk, sbn) at offset boff.
+int block_gemm(Layer& L, int nbr, int N, int K, double alpha, const double* A, long long lda, const double* B, long long boff,
+               long long sbk, long long sbn, double beta, double* C, long long ldc, const GemmF64* flags = nullptr) {
+    GemmF64 g{};
+    if (flags) g = *flags;
+    g.N = N; g.K = K; g.alpha = alpha; g.beta = beta;
+    g.A = A; g.sam = lda; g.sak = 1; g.B = B + boff; g.sbk = sbk; g.sbn = sbn; g.C = C; g.ldc = ldc;
+    if (L.nhin > 1) { g.M = nbr; g.batch = L.nh; g.strideA = (long long)nbr * lda; g.strideB = L.nn; g.strideC = (long long)nbr * ldc; }
+    else { g.M = L.nh * nbr; g.batch = 1; }
+    return gemm_f64(L.ctx, g);
+}
+
+int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, const float* R, uint8_t* codes, float* scales,
+              float* zeros, float* W_deq, double* loss, double* loss_per_head) {
+    tboa_ctx* ctx = L.ctx; const tboa_layer_desc* d = L.d;
+    const int n = L.n, nh = L.nh, dh = L.dh, ng = L.ng, nhin = L.nhin;
+    const long long nn = L.nn, wn = (long long)d->d_out * n;
+    hipStream_t st = ctx->stream;
+
+    TB_TRY(launch_cvt_to_f64(ctx, W, d->w_dtype, L.W64, wn));
+    TB_HIP(ctx, hipMemcpyAsync(L.Wt, L.W64, wn * sizeof(double), hipMemcpyDeviceToDevice, st));
+    // eq. 3 for H_in (and H_out)
+    TB_TRY(launch_f32_to_f64_damp(ctx, n, nhin, H_in, d->damp, L.Hi));
+    TB_HIP(ctx, hipMemcpyAsync(L.Hfac, L.Hi, nhin * nn * sizeof(double), hipMemcpyDeviceToDevice, st));
+    TB_TRY(chol_inv_upper_f64(ctx, n, nhin, L.Hfac, L.Uin, L.ftmp, L.fdinv));
+    if (R) {   // Algorithm 3 line 2: P = ((R U^T) * M_U) U
+        TB_TRY(launch_cvt_f32_to_f64(ctx, R, L.Rd, nhin * nn));
+        GemmF64 a{};
+        a.M = n; a.N = n; a.K = n; a.alpha = 1.0; a.beta = 0.0;
+        a.A = L.Rd; a.sam = n; a.sak = 1; a.B = L.Uin; a.sbk = 1; a.sbn = n; a.klo_n = 1;   // U[c, k] = 0 for k < c
+        a.C = L.Hfac; a.ldc = n; a.batch = nhin; a.strideA = nn; a.strideB = nn; a.strideC = nn;
+        TB_TRY(gemm_f64(ctx, a));
+        TB_TRY(launch_strict_upper_f64(ctx, L.Hfac, n, nhin));
+        GemmF64 b{};
+        b.M = n; b.N = n; b.K = n; b.alpha = 1.0; b.beta = 0.0;
+        b.A = L.Hfac; b.sam = n; b.sak = 1; b.klo_m = 1;       // (R U^T)_masked[j, m] = 0 for m <= j
+        b.B = L.Uin; b.sbk = n; b.sbn = 1; b.khi_n = 1;        // U[m, k] = 0 for m > k
+        b.C = L.P; b.ldc = n; b.batch = nhin; b.strideA = nn; b.strideB = nn; b.strideC = nn;
+        TB_TRY(gemm_f64(ctx, b));
+    }
+    if (H_out) {
+        TB_TRY(launch_f32_to_f64_damp(ctx, dh, nh, H_out, d->damp, L.Ho));
+        TB_HIP(ctx, hipMemcpyAsync(L.Hofac, L.Ho, (size_t)nh * dh * dh * sizeof(double), hipMemcpyDeviceToDevice, st));
+        TB_TRY(chol_inv_upper_f64(ctx, dh, nh, L.Hofac, L.Uout, L.ftmp, L.fdinv));
+    }
+    const double* Pp = R ? L.P : nullptr;
+    const int pw_max = L.gsz < 64 ? L.gsz : 64;
+
+    if (!d->adaptive_grid) {   // BoA: one grid from the original weights
+        BlockMap id{dh, dh, 0};
+        for (int gi = 0; gi < ng; ++gi) TB_TRY(grid_search(L, L.W64, n, dh, id, gi * L.gsz, L.gsz, gi));
+    }
+    for (int i0 = 0; i0 < dh; i0 += d->block) {
+        const int i1 = (i0 + d->block < dh) ? i0 + d->block : dh;
+        const int nbr = i1 - i0, rows = nh * nbr;
+        BlockMap map{nbr, dh, i0};
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(gx(n), rows), dim3(256), 0, st, L.Wt, L.Wb, map, n);
+        TB_KERNEL_CHECK(ctx);
+        TB_HIP(ctx, hipMemcpyAsync(L.Wk, L.Wb, (size_t)rows * n * sizeof(double), hipMemcpyDeviceToDevice, st));
+        if (d->adaptive_grid && !d->group) TB_TRY(grid_search(L, L.Wk, n, nbr, map, 0, n, 0));
+        for (int c0 = 0; c0 < n; c0 += pw_max) {
+            const int pw = (n - c0 < pw_max) ? n - c0 : pw_max, c1 = c0 + pw;
+            const int gi = c0 / L.gsz;
+            if (d->group && d->adaptive_grid && c0 % L.gsz == 0) TB_TRY(grid_search(L, L.Wk, n, nbr, map, c0, L.gsz, gi));
+            SweepArgs a;
+            a.Wk = L.Wk; a.n = n; a.nbr = nbr; a.map = map; a.U = L.Uin; a.P = Pp; a.per_head = nhin > 1;
+            a.c0 = c0; a.pw = pw; a.s = L.s64; a.z = L.z64; a.ng = ng; a.gi = gi; a.maxq = L.maxq;
+            a.codes = codes; a.Q = L.Q64; a.Epan = L.Epan; a.Wsnap = L.Wsnap;
+            hipLaunchKernelGGL((sweep_panel_kernel<2>), dim3((nbr + 7) / 8, nh), dim3(256), 0, st, a);
+            TB_KERNEL_CHECK(ctx);
+            if (c1 < n) {   // columns right of the panel: W[:, c1:] -= E U[c0:c1, c1:] + Wsnap P[c0:c1, c1:]
+                TB_TRY(block_gemm(L, nbr, n - c1, pw, -1.0, L.Epan, 64, L.Uin, (long long)c0 * n + c1, n, 1, 1.0, L.Wk + c1, n));
+                if (Pp) TB_TRY(block_gemm(L, nbr, n - c1, pw, -1.0, L.Wsnap, 64, L.P, (long long)c0 * n + c1, n, 1, 1.0, L.Wk + c1, n));
+            }
+        }
+        if (H_out && i1 < dh) {
+            const double* S3 = nullptr;
+            if (R) {   // W_B R H_in^-1 = ((W_B R) U^T) U
+                GemmF64 f1{}; f1.klo_n = 1;
+                GemmF64 f2{}; f2.khi_n = 1;
+                TB_TRY(block_gemm(L, nbr, n, n, 1.0, L.Wb, n, L.Rd, 0, n, 1, 0.0, L.S1, n));
+                TB_TRY(block_gemm(L, nbr, n, n, 1.0, L.S1, n, L.Uin, 0, 1, n, 0.0, L.S2, n, &f1));
+                TB_TRY(block_gemm(L, nbr, n, n, 1.0, L.S2, n, L.Uin, 0, n, 1, 0.0, L.S1, n, &f2));
+                S3 = L.S1;
+            }
+            hipLaunchKernelGGL(comp_error_kernel, dim3(gx(n), rows), dim3(256), 0, st, L.Wb, L.Q64, S3, L.E, map, n);
+            const int rem = dh - i1;
+            hipLaunchKernelGGL(comp_T_kernel, dim3((rem + 63) / 64, nh), dim3(64), 0, st, L.Uout, dh, i0, i1, L.T, d->block);
+            TB_KERNEL_CHECK(ctx);
+            GemmF64 u{};   // W~[i1:, :] -= T E per head
+            u.M = rem; u.N = n; u.K = nbr; u.alpha = -1.0; u.beta = 1.0;
+            u.A = L.T + (long long)i1 * d->block; u.sam = d->block; u.sak = 1;
+            u.B = L.E; u.sbk = n; u.sbn = 1;
+            u.C = L.Wt + (long long)i1 * n; u.ldc = n;
+            u.batch = nh; u.strideA = (long long)dh * d->block; u.strideB = (long long)nbr * n; u.strideC = (long long)dh * n;
+            TB_TRY(gemm_f64(ctx, u));
+        }
+    }
+
+    // Algorithm 2 + outputs + loss
+    const int rows_all = d->d_out;
+    hipLaunchKernelGGL(wbar_kernel, dim3(gx(n), rows_all), dim3(256), 0, st, codes, L.z64, ng, L.gsz, n, L.Wbar);
+    TB_KERNEL_CHECK(ctx);
+    if (R) TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Rd, 0, n, 1, 0.0, L.WR, n));
+    if (d->cd_iters > 0) {
+        if (d->group) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: scale refinement with group > 0 is not implemented");
+        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.Wbar, n, L.Hi, 0, n, 1, 0.0, L.Abar, n));
+        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Hi, 0, n, 1, 0.0, L.Z, n));
+        if (R) TB_TRY(launch_sub_f64(ctx, L.Z, L.WR, L.Z, wn));
+        if (H_out) {
+            GemmF64 c{};
+            c.M = dh; c.N = dh; c.K = n; c.alpha = 1.0; c.beta = 0.0;
+            c.A = L.Abar; c.sam = n; c.sak = 1; c.B = L.Wbar; c.sbk = 1; c.sbn = n; c.C = L.Cm; c.ldc = dh;
+            c.batch = nh; c.strideA = (long long)dh * n; c.strideB = c.strideA; c.strideC = (long long)dh * dh;
+            TB_TRY(gemm_f64(ctx, c));
+            c.A = L.Wbar; c.B = L.Z; c.C = L.Fm;
+            TB_TRY(gemm_f64(ctx, c));
+            hipLaunchKernelGGL(cd_head_kernel, dim3(nh), dim3(256), (dh + 8) * sizeof(double), st, L.Fm, L.Cm, L.Ho, dh, d->cd_iters, L.s64);
+        } else {
+            hipLaunchKernelGGL(rowdot_kernel, dim3((rows_all + 3) / 4), dim3(256), 0, st, L.Abar, (long long)n, L.Wbar, (long long)n,
+                               (long long)rows_all, n, L.dvec);
+            hipLaunchKernelGGL(rowdot_kernel, dim3((rows_all + 3) / 4), dim3(256), 0, st, L.Wbar, (long long)n, L.Z, (long long)n,
+                               (long long)rows_all, n, L.dvec + rows_all);
+            hipLaunchKernelGGL(cd_diag_kernel, dim3((rows_all + 255) / 256), dim3(256), 0, st, L.dvec + rows_all, L.dvec, rows_all,
+                               d->cd_iters, L.s64);
+        }
+        TB_KERNEL_CHECK(ctx);
+    }
+    hipLaunchKernelGGL(finalize_kernel, dim3(gx(n), rows_all), dim3(256), 0, st, L.Wbar, L.s64, L.z64, ng, L.gsz, n, L.Q64, W_deq,
+                       scales, zeros);
+    TB_KERNEL_CHECK(ctx);
+    if (loss || loss_per_head) {
+        // D = Q - W (into Wbar), D H_in (into Abar)
+        TB_TRY(launch_sub_f64(ctx, L.Q64, L.W64, L.Wbar, wn));
+        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.Wbar, n, L.Hi, 0, n, 1, 0.0, L.Abar, n));
+        double* lq = L.lossbuf; double* lc = L.lossbuf + nh;
+        TB_TRY(launch_fill_f64(ctx, L.lossbuf, 2 * nh, 0.0));
+        if (H_out) {
+            GemmF64 c{};
+            c.M = dh; c.N = dh; c.K = n; c.alpha = 1.0; c.beta = 0.0;
+            c.A = L.Abar; c.sam = n; c.sak = 1; c.B = L.Wbar; c.sbk = 1; c.sbn = n; c.C = L.Cm; c.ldc = dh;
+            c.batch = nh; c.strideA = (long long)dh * n; c.strideB = c.strideA; c.strideC = (long long)dh * dh;
+            TB_TRY(gemm_f64(ctx, c));
+            hipLaunchKernelGGL(head_trace_kernel, dim3(nh), dim3(256), 0, st, L.Ho, L.Cm, dh, 1.0, lq);
+            if (R) {
+                c.A = L.WR; c.B = L.Wbar; c.C = L.Fm;
+                TB_TRY(gemm_f64(ctx, c));
+                hipLaunchKernelGGL(head_trace_kernel, dim3(nh), dim3(256), 0, st, L.Ho, L.Fm, dh, 2.0, lc);
+            }
+        } else {
+            hipLaunchKernelGGL(rowdot_kernel, dim3((rows_all + 3) / 4), dim3(256), 0, st, L.Abar, (long long)n, L.Wbar, (long long)n,
+                               (long long)rows_all, n, L.dvec);
+            hipLaunchKernelGGL(head_sum_kernel, dim3(nh), dim3(256), 0, st, L.dvec, dh, 1.0, lq);
+            if (R) {
+                hipLaunchKernelGGL(rowdot_kernel, dim3((rows_all + 3) / 4), dim3(256), 0, st, L.WR, (long long)n, L.Wbar, (long long)n,
+                                   (long long)rows_all, n, L.dvec);
+                hipLaunchKernelGGL(head_sum_kernel, dim3(nh), dim3(256), 0, st, L.dvec, dh, 2.0, lc);
+            }
+        }
+        TB_KERNEL_CHECK(ctx);
+        double* host = (double*)malloc(2 * nh * sizeof(double));
+        if (!host) return tboa_fail(ctx, TBOA_ENOMEM, "host buffer");
+        hipError_t e = hipMemcpyAsync(host, L.lossbuf, 2 * nh * sizeof(double), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) { free(host); return tboa_fail(ctx, TBOA_EHIP, "loss copy: %s", hipGetErrorString(e)); }
+        double q = 0.0, c = 0.0;
+        for (int h = 0; h < nh; ++h) { q += host[h]; c += host[nh + h]; if (loss_per_head) loss_per_head[h] = host[h] + host[nh + h]; }
+        if (loss) { loss[0] = q; loss[1] = c; }
+        free(host);
+        if (!(q == q) || !(c == c)) return tboa_fail(ctx, TBOA_ENAN, "quantize_layer: loss is not finite (non-finite input?)");
+    }
+    return 0;
+}
+
+}  // namespace
+
+extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, const void* W, const float* H_in, const float* H_out,
+                                   const float* R, uint8_t* codes, float* scales, float* zeros, float* W_deq, double* loss,
+                                   double* loss_per_head) {
+    if (!ctx) return TBOA_EINVAL;
+    if (!d || !W || !H_in || !codes || !scales || !zeros || !W_deq) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: null argument");
+    if (d->d_out <= 0 || d->d_in <= 0 || d->n_heads <= 0 || d->d_out % d->n_heads != 0)
+        return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: d_out=%d must be a positive multiple of n_heads=%d", d->d_out, d->n_heads);
+    if (!(d->bits == 2 || d->bits == 3 || d->bits == 4 || d->bits == 8)) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: bits=%d not in {2,3,4,8}", d->bits);
+    if (d->block <= 0) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: block must be positive");
+    if (d->group < 0 || (d->group > 0 && d->d_in % d->group != 0)) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: group=%d must divide d_in=%d", d->group, d->d_in);
+    if (d->group > 0 && !(d->group % 64 == 0 || 64 % d->group == 0)) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: group=%d must divide or be a multiple of 64", d->group);
+    if (d->w_dtype != TBOA_F32 && d->w_dtype != TBOA_BF16) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: w_dtype");
+    if (d->grid_points <= 0 || !(d->max_shrink > 0.0) || d->max_shrink > 1.0 || d->damp < 0.0 || d->cd_iters < 0)
+        return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: grid_points/max_shrink/damp/cd_iters out of range");
+    if (d->hin_per_head && d->n_heads > 1 && !H_out) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: per-head H_in needs H_out");
+
+    Layer L{};
+    L.ctx = ctx; L.d = d;
+    L.n = d->d_in; L.nh = d->n_heads; L.dh = d->d_out / d->n_heads;
+    L.ng = d->group ? d->d_in / d->group : 1; L.gsz = d->group ? d->group : d->d_in;
+    L.nhin = d->hin_per_head ? d->n_heads : 1;
+    L.ncand = (int)ceil(d->max_shrink * (double)d->grid_points);
+    if (L.ncand < 1) L.ncand = 1;
+    L.maxq = (double)((1 << d->bits) - 1);
+    L.nn = (long long)L.n * L.n;
+    const int n = L.n, nh = L.nh, dh = L.dh;
+    const int blk = d->block < dh ? d->block : dh;
+    const size_t wn = (size_t)d->d_out * n, brows = (size_t)nh * blk;
+    // grid-search pass size: keep Delta and G near 2 GiB each
+    {
+        const double cap = 2147483648.0;
+        const double per_row = (double)L.ncand * L.gsz * 8.0;
+        const int max_rows_block = d->adaptive_grid ? blk : dh;
+        if (L.nhin > 1) { int c = (int)(cap / (per_row * max_rows_block)); L.grid_chunk = c < 1 ? 1 : (c > nh ? nh : c); }
+        else { int c = (int)(cap / per_row); const int tot = nh * max_rows_block; L.grid_chunk = c < 1 ? 1 : (c > tot ? tot : c); }
+    }
+    const size_t grows = (size_t)L.grid_chunk * (L.nhin > 1 ? (d->adaptive_grid ? blk : dh) : 1);
+    const int fmax = n > dh ? n : dh;
+    const int fb = (L.nhin > nh) ? L.nhin : nh;
+    const int nblk_f = (fmax + TB_FACT_NB - 1) / TB_FACT_NB;
+
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        L.W64 = ar.get<double>(wn); L.Wt = ar.get<double>(wn); L.Q64 = ar.get<double>(wn);
+        L.s64 = ar.get<double>((size_t)d->d_out * L.ng); L.z64 = ar.get<double>((size_t)d->d_out * L.ng);
+        L.Hi = ar.get<double>((size_t)L.nhin * L.nn); L.Hfac = ar.get<double>((size_t)L.nhin * L.nn); L.Uin = ar.get<double>((size_t)L.nhin * L.nn);
+        L.Rd = R ? ar.get<double>((size_t)L.nhin * L.nn) : nullptr; L.P = R ? ar.get<double>((size_t)L.nhin * L.nn) : nullptr;
+        L.Ho = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr; L.Hofac = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
+        L.Uout = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
+        L.ftmp = ar.get<double>((size_t)fb * fmax * TB_FACT_NB); L.fdinv = ar.get<double>((size_t)fb * nblk_f * TB_FACT_NB * TB_FACT_NB);
+        L.Wb = ar.get<double>(brows * n); L.Wk = ar.get<double>(brows * n);
+        L.Epan = ar.get<double>(brows * 64); L.Wsnap = ar.get<double>(brows * 64);
+        L.E = H_out ? ar.get<double>(brows * n) : nullptr;
+        L.S1 = (H_out && R) ? ar.get<double>(brows * n) : nullptr; L.S2 = (H_out && R) ? ar.get<double>(brows * n) : nullptr;
+        L.T = H_out ? ar.get<double>((size_t)nh * dh * d->block) : nullptr;
+        L.cand_s = ar.get<double>(grows * L.ncand); L.cand_z = ar.get<double>(grows * L.ncand); L.cost = ar.get<double>(grows * L.ncand);
+        L.Delta = ar.get<double>(grows * L.ncand * L.gsz); L.G = ar.get<double>(grows * L.ncand * L.gsz);
+        L.Wbar = ar.get<double>(wn); L.Abar = ar.get<double>(wn); L.Z = ar.get<double>(wn);
+        L.WR = R ? ar.get<double>(wn) : nullptr;
+        L.Cm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr; L.Fm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
+        L.dvec = ar.get<double>(2 * (size_t)d->d_out); L.lossbuf = ar.get<double>(2 * (size_t)nh);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    return run_layer(L, W, H_in, H_out, R, codes, scales, zeros, W_deq, loss, loss_per_head);
+}

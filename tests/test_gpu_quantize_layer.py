@@ -1,0 +1,100 @@
+"""tboa_quantize_layer against the fp64 oracle on the same seeded inputs (GPU)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import turboboa_ref as O
+from tests.parity import compare_layer
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    c = lib.Context()
+    yield c
+    c.close()
+
+
+def make_case(seed, n_heads, dh, n, T, per_head_in=False, corr=0.5):
+    r = np.random.default_rng(seed)
+    def acts():
+        X = r.standard_normal((T, n)) + corr * r.standard_normal((T, 1))
+        X[:, r.integers(0, n, 3)] *= 10
+        return X
+    W = (r.standard_normal((n_heads * dh, n)) * 0.02).astype(np.float32)
+    if per_head_in:
+        Xs = [acts() for _ in range(n_heads)]
+        Hin = np.stack([x.T @ x for x in Xs]).astype(np.float32)
+        R = np.stack([0.25 * (0.1 * r.standard_normal((T, n))).T @ x for x in Xs]).astype(np.float32)
+    else:
+        X = acts()
+        Hin = (X.T @ X).astype(np.float32)
+        R = (0.25 * (0.1 * r.standard_normal((T, n))).T @ X).astype(np.float32)
+    G = [r.standard_normal((T, dh)) + 0.7 * r.standard_normal((T, 1)) for _ in range(n_heads)]
+    Hout = np.stack([g.T @ g for g in G]).astype(np.float32)
+    return W, Hin, Hout, R
+
+
+def run_both(ctx, W, Hin, Hout, R, n_heads, **kw):
+    dev = lambda a: None if a is None else torch.tensor(a, device="cuda")
+    got = ctx.quantize_layer(dev(W), dev(Hin), dev(Hout), dev(R), n_heads, **kw)
+    f64 = lambda a: None if a is None else a.astype(np.float64)
+    want = O.quantize_layer(f64(W), f64(Hin), f64(Hout), f64(R), n_heads, **kw)
+    return got, want
+
+
+CASES = [
+    # name, n_heads, dh, n, per_head_in, use_Hout, use_R, kwargs
+    ("q-like", 3, 40, 200, False, True, True, dict(bits=2, block=16)),
+    ("q-like-noR", 2, 64, 256, False, True, False, dict(bits=2, block=4)),
+    ("v-like", 3, 32, 136, True, True, True, dict(bits=2, block=8)),
+    ("o-like", 1, 96, 192, False, False, True, dict(bits=2, block=96)),
+    ("boa", 2, 24, 128, False, True, False, dict(bits=2, block=1, adaptive_grid=False, cd_iters=0)),
+    ("int3", 2, 32, 160, False, True, True, dict(bits=3, block=32)),
+    ("int4-cd2", 2, 32, 130, False, True, True, dict(bits=4, block=12, cd_iters=2)),
+    ("nodamp", 2, 16, 96, False, True, True, dict(bits=2, block=8, damp=0.0)),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_quantize_layer_matches_oracle(ctx, case):
+    name, nh, dh, n, ph, use_ho, use_r, kw = case
+    print("quantize_layer case", name, flush=True)
+    W, Hin, Hout, R = make_case(hash(name) % 1000, nh, dh, n, T=4 * n, per_head_in=ph)
+    got, want = run_both(ctx, W, Hin, Hout if use_ho else None, R if use_r else None, nh, **kw)
+    frac = compare_layer(got, want, label=name)
+    print("codes identical: %.4f%%" % (100 * frac), flush=True)
+    codes = got["codes"].cpu().numpy()
+    assert codes.max() <= 2 ** kw["bits"] - 1
+    s = got["scales"].cpu().numpy(); z = got["zeros"].cpu().numpy()
+    assert np.allclose(got["W_deq"].cpu().numpy(), s * (codes.astype(np.float32) - z), rtol=1e-6)
+
+
+def test_bf16_weights_and_determinism(ctx):
+    W, Hin, Hout, R = make_case(7, 2, 32, 128, T=512)
+    Wb = torch.tensor(W, device="cuda").to(torch.bfloat16)
+    args = (torch.tensor(Hin, device="cuda"), torch.tensor(Hout, device="cuda"), torch.tensor(R, device="cuda"), 2)
+    a = ctx.quantize_layer(Wb, *args, bits=2, block=8)
+    b = ctx.quantize_layer(Wb, *args, bits=2, block=8)
+    assert torch.equal(a["codes"], b["codes"]) and torch.equal(a["scales"], b["scales"]) and a["loss"] == b["loss"]
+    want = O.quantize_layer(Wb.float().cpu().numpy().astype(np.float64), Hin.astype(np.float64), Hout.astype(np.float64),
+                            R.astype(np.float64), 2, bits=2, block=8)
+    compare_layer(a, want, label="bf16")
+
+
+def test_error_paths(ctx, lib):
+    W, Hin, Hout, R = make_case(8, 2, 16, 64, T=256)
+    t = lambda a: torch.tensor(a, device="cuda")
+    with pytest.raises(lib.TurboBoAError) as e:
+        ctx.quantize_layer(t(W), t(Hin), t(Hout), None, 2, bits=5, block=4)
+    assert e.value.code == -1
+    with pytest.raises(lib.TurboBoAError) as e:
+        ctx.quantize_layer(t(W), t(Hin), t(Hout), None, 2, bits=2, block=4, group=48)
+    assert e.value.code == -1
+    Hbad = Hin.copy(); Hbad[:, 5] = 0; Hbad[5, :] = 0      # a dead input channel, no damping: not SPD
+    with pytest.raises(lib.TurboBoAError) as e:
+        ctx.quantize_layer(t(W), t(Hbad), t(Hout), None, 2, bits=2, block=4, damp=0.0)
+    assert e.value.code == -2
+    ok = ctx.quantize_layer(t(W), t(Hbad), t(Hout), None, 2, bits=2, block=4, damp=0.01)   # damping repairs it
+    assert np.isfinite(ok["loss"])
