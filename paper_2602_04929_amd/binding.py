@@ -102,9 +102,9 @@ class Context:
         self._h = h
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:
             _lib.tboa_destroy(self._h)
-            self._h = None
+        self._h = None
 
     __del__ = close
 

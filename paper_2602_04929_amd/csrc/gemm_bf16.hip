@@ -1,0 +1,203 @@
+// bf16 x bf16 -> fp32 GEMM, C = alpha A B^T, on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16).
+//
+// Both operands are K-contiguous ("NT"): every contraction of the Hessian build is arranged that way (activations
+// are kept in a transposed copy where the token axis is the contraction axis), so one kernel shape serves X^T X,
+// the projections, Q K^T, A X and the dominant Y^T Y.
+//
+// Workgroup: 256 threads = 4 wavefronts (2 x 2) on a 256 x 256 x 64 tile; each wavefront owns 128 x 128 as 4 x 4
+// MFMA tiles of 32 x 32 (256 fp32 accumulators per lane, one workgroup per CU).  Per 16-wide k-step a wavefront reads
+// 8 fragments of 16 bytes per lane from LDS for 16 MFMAs.  LDS rows are 128 bytes (64 bf16) and the 16-byte chunks of
+// a row are XOR-swizzled with the row number so that fragment reads and tile writes are bank-conflict free.
+// Global -> register -> LDS software pipeline over two LDS stages, one barrier per 64-wide k-step.
+// Tiles are numbered so that the eight XCDs (workgroups are dealt to them round-robin) each work on a compact
+// band of the output and share operand panels through their own L2.
+#include "internal.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int BM = 256, BN = 256, BK = 64;
+
+struct Args {
+    int M, N, K;
+    float alpha;
+    const __hip_bfloat16* A; long long lda;
+    const __hip_bfloat16* B; long long ldb;
+    void* C; long long ldc;
+    int c_bf16, accumulate, flags;
+    int batch_inner, kseg;
+    long long sA1, sA2, sB1, sB2, sC1, sC2;
+    int tiles_m, tiles_n;
+};
+
+__device__ __forceinline__ void load_tile(const __hip_bfloat16* __restrict__ base, long long ld, int r0, int k0, int r_lim, int k_lim,
+                                          uint4 (&reg)[8]) {
+    const int t = threadIdx.x, c = t & 7, rr = t >> 3;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const int r = r0 + rr + 32 * p, k = k0 + 8 * c;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (r < r_lim && k < k_lim) v = *(const uint4*)(base + (long long)r * ld + k);
+        reg[p] = v;
+    }
+}
+
+__device__ __forceinline__ void store_tile(__hip_bfloat16* __restrict__ lds, const uint4 (&reg)[8]) {
+    const int t = threadIdx.x, c = t & 7, rr = t >> 3;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const int r = rr + 32 * p;
+        *(uint4*)(lds + r * BK + ((c ^ (r & 7)) * 8)) = reg[p];
+    }
+}
+
+__device__ __forceinline__ bf16x8 read_frag(const __hip_bfloat16* __restrict__ lds, int row, int chunk) {
+    return *(const bf16x8*)(lds + row * BK + ((chunk ^ (row & 7)) * 8));
+}
+
+__global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __hip_bfloat16* As = (__hip_bfloat16*)smem;                 // [2][BM*BK]
+    __hip_bfloat16* Bs = As + 2 * BM * BK;                      // [2][BN*BK]
+
+    // tile numbering: workgroup w runs on XCD w % 8; give each XCD a contiguous run of tiles, and walk the tiles
+    // of a run in bands of 4 tile rows so that neighbours in time share A or B panels
+    const int ntiles = g.tiles_m * g.tiles_n;
+    int tile = blockIdx.x;
+    if (ntiles % 8 == 0) tile = (tile & 7) * (ntiles / 8) + (tile >> 3);
+    const int band = 4;
+    const int band_tiles = band * g.tiles_n;
+    const int bi = tile / band_tiles, in = tile % band_tiles;
+    const int rows_in_band = min(band, g.tiles_m - bi * band);
+    const int tm = bi * band + in % rows_in_band, tn = in / rows_in_band;
+    const int m0 = tm * BM, n0 = tn * BN;
+    if ((g.flags & TBOA_GEMM_LOWER) && n0 >= m0 + BM) return;
+
+    const int z = blockIdx.y, z1 = z / g.batch_inner, z2 = z % g.batch_inner;
+    const __hip_bfloat16* A = g.A + z1 * g.sA1 + z2 * g.sA2;
+    const __hip_bfloat16* B = g.B + z1 * g.sB1 + z2 * g.sB2;
+
+    // the contraction axis may be a concatenation of equal segments (kseg > 0); the causal limit applies inside each
+    const int seg_len = g.kseg > 0 ? g.kseg : g.K;
+    const int nseg = g.kseg > 0 ? g.K / g.kseg : 1;
+    int kend = seg_len;
+    if (g.flags & TBOA_GEMM_CAUSAL_K) kend = min(kend, n0 + BN);
+    const int nk_seg = (kend + BK - 1) / BK;
+    const int nk = nk_seg * nseg;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    uint4 ra[8], rb[8];
+    if (nk > 0) {
+        load_tile(A, g.lda, m0, 0, g.M, kend, ra);
+        load_tile(B, g.ldb, n0, 0, g.N, kend, rb);   // first tile of segment 0
+        store_tile(As, ra);
+        store_tile(Bs, rb);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const __hip_bfloat16* a_s = As + cur * BM * BK;
+        const __hip_bfloat16* b_s = Bs + cur * BN * BK;
+        if (kt + 1 < nk) {
+            const int sg = (kt + 1) / nk_seg, kb = sg * seg_len;
+            const int k0 = kb + ((kt + 1) - sg * nk_seg) * BK;
+            load_tile(A, g.lda, m0, k0, g.M, kb + kend, ra);
+            load_tile(B, g.ldb, n0, k0, g.N, kb + kend, rb);
+        }
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 af[4], bfr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) af[i] = read_frag(a_s, wm + 32 * i + l32, 2 * ks + lh);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bfr[j] = read_frag(b_s, wn + 32 * j + l32, 2 * ks + lh);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) {
+            store_tile(As + (cur ^ 1) * BM * BK, ra);
+            store_tile(Bs + (cur ^ 1) * BN * BK, rb);
+        }
+        __syncthreads();
+    }
+
+    // accumulator v of tile (i, j): row 32 i + 8 (v / 4) + 4 (lane / 32) + v % 4, column 32 j + lane % 32
+    const long long coff = z1 * g.sC1 + z2 * g.sC2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lh + (v & 3);
+            if (row >= g.M) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = n0 + wn + 32 * j + l32;
+                if (col >= g.N) continue;
+                const long long idx = coff + (long long)row * g.ldc + col;
+                float r = g.alpha * acc[i][j][v];
+                if (g.c_bf16) ((__hip_bfloat16*)g.C)[idx] = __float2bfloat16(r);
+                else { float* c = (float*)g.C + idx; if (g.accumulate) r += *c; *c = r; }
+            }
+        }
+}
+
+}  // namespace
+
+int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
+    if (q.M <= 0 || q.N <= 0 || q.batch <= 0) return 0;
+    if (!q.A || !q.B || !q.C || q.K < 0) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: null operand or negative K");
+    if (q.K % 8 || q.lda % 8 || q.ldb % 8 || ((uintptr_t)q.A & 15) || ((uintptr_t)q.B & 15) || q.strideA % 8 || q.strideB % 8 ||
+        q.strideA2 % 8 || q.strideB2 % 8)
+        return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: K, leading dimensions and batch strides must be multiples of 8 and pointers 16-byte aligned");
+    if (q.c_dtype == TBOA_BF16 && q.accumulate) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: accumulate needs an fp32 C");
+    if (q.c_dtype != TBOA_BF16 && q.c_dtype != TBOA_F32) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: C must be fp32 or bf16");
+    if ((q.flags & TBOA_GEMM_LOWER) && q.M != q.N) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: LOWER needs M == N");
+    static bool attr_set = false;
+    const int smem = 2 * (BM + BN) * BK * (int)sizeof(__hip_bfloat16);
+    if (!attr_set) {
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        attr_set = true;
+    }
+    Args a;
+    a.M = q.M; a.N = q.N; a.K = q.K; a.alpha = q.alpha;
+    a.A = q.A; a.lda = q.lda; a.B = q.B; a.ldb = q.ldb; a.C = q.C; a.ldc = q.ldc;
+    a.c_bf16 = (q.c_dtype == TBOA_BF16); a.accumulate = q.accumulate; a.flags = q.flags;
+    a.batch_inner = q.batch_inner > 0 ? q.batch_inner : 1;
+    a.kseg = q.kseg;
+    if (q.kseg < 0 || (q.kseg > 0 && (q.K % q.kseg || q.kseg % 8))) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: kseg must divide K and be a multiple of 8");
+    a.sA1 = q.strideA; a.sB1 = q.strideB; a.sC1 = q.strideC; a.sA2 = q.strideA2; a.sB2 = q.strideB2; a.sC2 = q.strideC2;
+    a.tiles_m = (int)cdiv64(q.M, BM); a.tiles_n = (int)cdiv64(q.N, BN);
+    const long long ntiles = (long long)a.tiles_m * a.tiles_n;
+    if (ntiles > 2147483647LL || q.batch > 65535) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: grid too large");
+    hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((unsigned)ntiles, (unsigned)q.batch), dim3(256), smem, ctx->stream, a);
+    TB_KERNEL_CHECK(ctx);
+    return 0;
+}
+
+extern "C" int tboa_gemm_bf16_nt(tboa_ctx* ctx, int M, int N, int K, float alpha, const void* A, int64_t lda, const void* B,
+                                 int64_t ldb, void* C, int64_t ldc, int c_dtype, int accumulate, int flags, int batch,
+                                 int64_t strideA, int64_t strideB, int64_t strideC) {
+    if (!ctx) return TBOA_EINVAL;
+    GemmBf16 g{};
+    g.M = M; g.N = N; g.K = K; g.alpha = alpha;
+    g.A = (const __hip_bfloat16*)A; g.lda = lda; g.B = (const __hip_bfloat16*)B; g.ldb = ldb;
+    g.C = C; g.ldc = ldc; g.c_dtype = c_dtype; g.accumulate = accumulate; g.flags = flags;
+    g.batch = batch; g.strideA = strideA; g.strideB = strideB; g.strideC = strideC;
+    return gemm_bf16_nt(ctx, g);
+}

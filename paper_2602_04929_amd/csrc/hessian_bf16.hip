@@ -1,0 +1,472 @@
+// Table 1 Hessians for bf16 inputs, on the bf16 matrix cores, and the public entry points of the Hessian build.
+//
+// Every contraction is brought into the one shape the bf16 GEMM kernel has (both operands contiguous along the
+// contraction axis):
+//   H_in = X X^T            A = B = X^T [d, T]                     (split over T, partial sums reduced in fp64)
+//   R    = alpha dX X^T     A = dX^T as an exact hi + lo bf16 pair, B = X^T
+//   Q, K projections        A = X rows [tokens, d], B = W [out, d]  -> fp32, then an exact 3-term bf16 split so that
+//   scores Q_h K_h^T        runs as one GEMM over [hi | lo | hi] . [hi | hi | lo] (peaked softmaxes need the accuracy)
+//   Y_h^T = X_s^T A_h^T     A = X_s^T [d, L], B = A_h [L, L] (lower triangular: the k-loop stops at the diagonal tile)
+//   H_in^V += Y^T (Y^T)^T   A = B = Y^T [d, rep*G*L] for G sequences at a time, lower tiles only
+//   R_v += alpha dY^T (Y^T)^T with dY^T = [X_s^T | X~_s^T] . [A | -A~]^T taken from ONE fp32 accumulator
+// The L x L probabilities are materialised per sequence (bf16, a few hundred MB for all heads): with 288 GB of HBM
+// and a value dimension of d_model the traffic is negligible next to the flops.
+// H_out of W_Q / W_K / W_V are tiny Gram matrices, computed in fp64 from H_in and the weights
+// (K_h^T K_h = W_K,h H_in W_K,h^T exactly, there being no positional rotation in the block).
+#include "internal.h"
+#include <math.h>
+
+int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
+
+namespace {
+
+typedef __hip_bfloat16 bf16;
+
+// out[c, r] = in[r, c] (optionally also the exact hi/lo split of in - in2), 64 x 64 tiles through LDS
+__global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__ in, const bf16* __restrict__ in2, long long ld_in,
+                                                        int rows, int cols, bf16* __restrict__ out, bf16* __restrict__ out_hi,
+                                                        bf16* __restrict__ out_lo, long long ld_out) {
+    __shared__ float t0[64][65];
+    __shared__ float t1[64][65];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int r = i >> 6, c = i & 63;
+        float v = 0.f, w = 0.f;
+        if (r0 + r < rows && c0 + c < cols) {
+            v = __bfloat162float(in[(long long)(r0 + r) * ld_in + c0 + c]);
+            if (in2) w = __bfloat162float(in2[(long long)(r0 + r) * ld_in + c0 + c]);
+        }
+        t0[r][c] = v; t1[r][c] = v - w;     // the difference of two bf16 values is exact in fp32
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int c = i >> 6, r = i & 63;
+        if (r0 + r < rows && c0 + c < cols) {
+            const long long o = (long long)(c0 + c) * ld_out + r0 + r;
+            if (out) out[o] = __float2bfloat16(t0[r][c]);
+            if (out_hi) {
+                const float dlt = t1[r][c];
+                const bf16 hi = __float2bfloat16(dlt);
+                out_hi[o] = hi;
+                if (out_lo) out_lo[o] = __float2bfloat16(dlt - __bfloat162float(hi));
+            }
+        }
+    }
+}
+
+// fp32 [rows, H*dh] -> bf16 [rows, H, 3*dh]: (hi, lo, hi) for the left operand, (hi, hi, lo) for the right one
+__global__ void split3_kernel(const float* __restrict__ in, bf16* __restrict__ out, long long rows, int hd, int dh, int right) {
+    const long long tot = rows * hd;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
+        const long long row = i / hd; const int c = (int)(i % hd), h = c / dh, e = c % dh;
+        const float v = in[i];
+        const bf16 hi = __float2bfloat16(v);
+        const bf16 lo = __float2bfloat16(v - __bfloat162float(hi));
+        bf16* o = out + (row * (hd / dh) + h) * 3 * dh;
+        o[e] = hi; o[dh + e] = right ? hi : lo; o[2 * dh + e] = right ? lo : hi;
+    }
+}
+
+// fp32 [n] -> exact-to-16-bits pair of bf16
+__global__ void split_hilo_kernel(const float* __restrict__ in, bf16* __restrict__ hi, bf16* __restrict__ lo, long long n) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+        const float v = in[i];
+        const bf16 h = __float2bfloat16(v);
+        hi[i] = h; lo[i] = __float2bfloat16(v - __bfloat162float(h));
+    }
+}
+
+// V^T fp32 [rows, G*L] -> per-sequence segments of length L: (hi, lo) of V^T in segments 0, 1 and, when the
+// full-precision V~^T is given, V^T - V~^T in segment 2 and V~^T in segment 3
+__global__ void vt_segments_kernel(const float* __restrict__ in, const float* __restrict__ in_fp, bf16* __restrict__ out, int rows,
+                                   int G, int L, int nseg) {
+    const long long tot = (long long)rows * G * L;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
+        const long long row = i / ((long long)G * L); const int s = (int)((i / L) % G), t = (int)(i % L);
+        const float v = in[i];
+        const bf16 h = __float2bfloat16(v);
+        bf16* o = out + ((row * G + s) * nseg) * L + t;
+        o[0] = h; o[L] = __float2bfloat16(v - __bfloat162float(h));
+        if (in_fp) { const float w = in_fp[i]; o[2 * L] = __float2bfloat16(v - w); o[3 * L] = __float2bfloat16(w); }
+    }
+}
+
+// P[t, c*L + k] = A[t, k] for c < copies, A = softmax over the first t+1 (causal) or L entries of the score row; with a
+// second score matrix S2 also P[t, dcol + k] = A[t, k] - A2[t, k], the difference taken in fp32 before rounding.
+// Zero up to the next multiple of 256 (the k-loop of the consumer stops there).  One wavefront per row, y = head.
+__global__ __launch_bounds__(256) void softmax_bf16_kernel(const float* __restrict__ S, const float* __restrict__ S2, int L, int causal,
+                                                           bf16* __restrict__ P, long long ldp, long long head_stride, int copies, int dcol) {
+    const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= L) return;
+    const long long so = ((long long)blockIdx.y * L + t) * L;
+    const float* s = S + so; const float* s2 = S2 ? S2 + so : nullptr;
+    bf16* p = P + blockIdx.y * head_stride + (long long)t * ldp;
+    const int kend = causal ? t + 1 : L;
+    int kz = ((kend + 255) / 256) * 256; if (kz > L) kz = L;
+    float m = -INFINITY, m2 = -INFINITY;
+    for (int k = lane; k < kend; k += 64) { m = fmaxf(m, s[k]); if (s2) m2 = fmaxf(m2, s2[k]); }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { m = fmaxf(m, __shfl_xor(m, o, 64)); m2 = fmaxf(m2, __shfl_xor(m2, o, 64)); }
+    float sum = 0.f, sum2 = 0.f;
+    for (int k = lane; k < kend; k += 64) { sum += __expf(s[k] - m); if (s2) sum2 += __expf(s2[k] - m2); }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { sum += __shfl_xor(sum, o, 64); sum2 += __shfl_xor(sum2, o, 64); }
+    const float inv = 1.f / sum, inv2 = s2 ? 1.f / sum2 : 0.f;
+    for (int k = lane; k < kz; k += 64) {
+        const float a = k < kend ? __expf(s[k] - m) * inv : 0.f;
+        const bf16 v = __float2bfloat16(a);
+        for (int c = 0; c < copies; ++c) p[(long long)c * L + k] = v;
+        if (s2) p[dcol + k] = __float2bfloat16(k < kend ? a - __expf(s2[k] - m2) * inv2 : 0.f);
+    }
+}
+
+// out = scale * sum_s partial[s] (fp64 accumulation); lower: only r >= c is read, the result is mirrored
+__global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits, int n, double scale, int lower, float* __restrict__ out) {
+    const long long nn = (long long)n * n;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < nn; i += (long long)gridDim.x * blockDim.x) {
+        const int r = (int)(i / n), c = (int)(i % n);
+        const long long src = (lower && c > r) ? (long long)c * n + r : i;
+        double acc = 0.0;
+        for (int s = 0; s < splits; ++s) acc += (double)part[s * nn + src];
+        out[i] = (float)(scale * acc);
+    }
+}
+
+__global__ void bcast_heads_kernel(const double* __restrict__ src, float* __restrict__ dst, int rep, long long per, long long total) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const long long h = i / per, e = i % per;
+        dst[i] = (float)src[(h / rep) * per + e];
+    }
+}
+
+inline unsigned g1(long long n) { long long g = (n + 255) / 256; return (unsigned)(g < 1 ? 1 : (g > 32768 ? 32768 : g)); }
+
+struct Dims {
+    tboa_ctx* ctx; const tboa_attn_desc* d;
+    int T, dm, Hq, Hkv, dh, L, S, rep, dq, dkv;
+};
+
+Dims dims_of(tboa_ctx* ctx, const tboa_attn_desc* d) {
+    return Dims{ctx, d, d->n_seqs * d->seq_len, d->d_model, d->n_q_heads, d->n_kv_heads, d->head_dim, d->seq_len, d->n_seqs,
+                d->n_q_heads / d->n_kv_heads, d->n_q_heads * d->head_dim, d->n_kv_heads * d->head_dim};
+}
+
+int pick_splits(int n_seqs) {
+    for (int s = 16; s > 1; --s) if (n_seqs % s == 0) return s;
+    return 1;
+}
+
+int transpose(const Dims& D, const bf16* in, const bf16* in2, long long ld_in, int rows, int cols, bf16* out, bf16* hi, bf16* lo, long long ld_out) {
+    hipLaunchKernelGGL(transpose_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, D.ctx->stream, in, in2, ld_in, rows, cols,
+                       out, hi, lo, ld_out);
+    TB_HIP(D.ctx, hipGetLastError());
+    return 0;
+}
+
+GemmBf16 nt(int M, int N, int K, float alpha, const bf16* A, long long lda, const bf16* B, long long ldb, void* C, long long ldc,
+            int c_dtype, int accumulate, int flags) {
+    GemmBf16 g{};
+    g.M = M; g.N = N; g.K = K; g.alpha = alpha; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+    g.c_dtype = c_dtype; g.accumulate = accumulate; g.flags = flags; g.batch = 1;
+    return g;
+}
+
+// out[n, n] = scale * A B^T with the contraction over all T tokens split into `splits` chunks
+int gram_splitk(const Dims& D, int n, const bf16* A, const bf16* A_lo, const bf16* B, long long ld, int K, double scale, int lower,
+                float* part, float* out) {
+    const int splits = pick_splits(D.S), Kc = K / splits;
+    GemmBf16 g = nt(n, n, Kc, 1.f, A, ld, B, ld, part, n, TBOA_F32, 0, lower ? TBOA_GEMM_LOWER : 0);
+    g.batch = splits; g.strideA = Kc; g.strideB = Kc; g.strideC = (long long)n * n;
+    if (lower) TB_TRY(launch_fill_f32(D.ctx, part, (int64_t)splits * n * n, 0.f));
+    TB_TRY(gemm_bf16_nt(D.ctx, g));
+    if (A_lo) { g.A = A_lo; g.accumulate = 1; TB_TRY(gemm_bf16_nt(D.ctx, g)); }
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(g1((long long)n * n)), dim3(256), 0, D.ctx->stream, part, splits, n, scale, lower, out);
+    TB_HIP(D.ctx, hipGetLastError());
+    return 0;
+}
+
+// Q^ [rows, Hq, 3 dh] and K^ [rows, Hkv, 3 dh] of `rows` tokens Xr [rows, d]; weights as one or two (hi, lo) bf16 terms
+int project_qk(const Dims& D, const bf16* Xr, int rows, const bf16* Wq, const bf16* Wq_lo, const bf16* Wk, const bf16* Wk_lo,
+               float* Qf, float* Kf, bf16* Qh, bf16* Kh) {
+    TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, Wq, D.dm, Qf, D.dq, TBOA_F32, 0, 0)));
+    if (Wq_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, Wq_lo, D.dm, Qf, D.dq, TBOA_F32, 1, 0)));
+    TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk, D.dm, Kf, D.dkv, TBOA_F32, 0, 0)));
+    if (Wk_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk_lo, D.dm, Kf, D.dkv, TBOA_F32, 1, 0)));
+    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dq)), dim3(256), 0, D.ctx->stream, Qf, Qh, (long long)rows, D.dq, D.dh, 0);
+    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dkv)), dim3(256), 0, D.ctx->stream, Kf, Kh, (long long)rows, D.dkv, D.dh, 1);
+    TB_HIP(D.ctx, hipGetLastError());
+    return 0;
+}
+
+// scaled scores Q_h K_g^T / sqrt(d_h) of all heads of local sequence sl -> Sc [Hq, L, L] (lower tiles when causal)
+int scores(const Dims& D, const bf16* Qh, const bf16* Kh, int sl, float* Sc) {
+    const int L = D.L, dh3 = 3 * D.dh;
+    GemmBf16 g = nt(L, L, dh3, (float)(1.0 / sqrt((double)D.dh)), Qh + (long long)sl * L * D.Hq * dh3, (long long)D.Hq * dh3,
+                    Kh + (long long)sl * L * D.Hkv * dh3, (long long)D.Hkv * dh3, Sc, L, TBOA_F32, 0, D.d->causal ? TBOA_GEMM_LOWER : 0);
+    g.batch = D.Hq; g.batch_inner = D.rep;
+    g.strideA = (long long)D.rep * dh3; g.strideA2 = dh3; g.strideB = dh3; g.strideB2 = 0;
+    g.strideC = (long long)D.rep * L * L; g.strideC2 = (long long)L * L;
+    return gemm_bf16_nt(D.ctx, g);
+}
+
+int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long ldp, int copies, int dcol) {
+    hipLaunchKernelGGL(softmax_bf16_kernel, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P, ldp,
+                       (long long)D.L * ldp, copies, dcol);
+    TB_HIP(D.ctx, hipGetLastError());
+    return 0;
+}
+
+int check_bf16_dims(const Dims& D) {
+    if (D.L % 8 || D.dm % 8 || D.dh % 8)
+        return tboa_fail(D.ctx, TBOA_EINVAL, "bf16 Hessian build needs seq_len, d_model and head_dim to be multiples of 8");
+    return 0;
+}
+
+int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, const bf16* X_fp, const bf16* Wq, const bf16* Wk,
+                        const bf16* Wo, float* Hin_qk, float* R_qk, float* Hout_q, float* Hout_k, float* Hin_v, float* R_v, float* Hout_v) {
+    const Dims D = dims_of(ctx, d);
+    TB_TRY(check_bf16_dims(D));
+    const int T = D.T, dm = D.dm, Hq = D.Hq, Hkv = D.Hkv, dh = D.dh, L = D.L, dq = D.dq, dkv = D.dkv, rep = D.rep;
+    const bool fp = X_fp != nullptr, rv = fp && R_v;
+    int G = d->seq_chunk > 0 ? d->seq_chunk : 8; if (G > D.S) G = D.S;
+    const int nsg = rv ? 2 : 1, nsx = rv ? 3 : 1, splits = pick_splits(D.S);   // segments of P / of the transposed chunk
+    const long long dd = (long long)dm * dm, hh = (long long)dh * dh;
+    bf16 *XT, *dXh, *dXl, *Qh, *Kh, *Qhf, *Khf, *P, *XcT, *YT, *dYT;
+    float *part, *Qf, *Kf, *Sc, *Scf;
+    double *Hin64, *Wq64, *Wk64, *Wo64, *Tq, *Tk, *Ho;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        XT = ar.get<bf16>((size_t)dm * T);
+        dXh = fp ? ar.get<bf16>((size_t)dm * T) : nullptr; dXl = fp ? ar.get<bf16>((size_t)dm * T) : nullptr;
+        part = ar.get<float>((size_t)splits * dd);
+        Qf = ar.get<float>((size_t)G * L * dq); Kf = ar.get<float>((size_t)G * L * dkv);
+        Qh = ar.get<bf16>((size_t)G * L * dq * 3); Kh = ar.get<bf16>((size_t)G * L * dkv * 3);
+        Qhf = rv ? ar.get<bf16>((size_t)G * L * dq * 3) : nullptr; Khf = rv ? ar.get<bf16>((size_t)G * L * dkv * 3) : nullptr;
+        Sc = ar.get<float>((size_t)Hq * L * L); Scf = rv ? ar.get<float>((size_t)Hq * L * L) : nullptr;
+        P = ar.get<bf16>((size_t)Hq * L * nsg * L);
+        XcT = ar.get<bf16>((size_t)dm * G * nsx * L);
+        YT = ar.get<bf16>((size_t)Hq * dm * G * L); dYT = rv ? ar.get<bf16>((size_t)Hq * dm * G * L) : nullptr;
+        Hin64 = ar.get<double>((size_t)dd); Wq64 = ar.get<double>((size_t)dq * dm); Wk64 = ar.get<double>((size_t)dkv * dm);
+        Wo64 = ar.get<double>((size_t)dm * dq); Tq = ar.get<double>((size_t)dq * dm); Tk = ar.get<double>((size_t)dkv * dm);
+        Ho = ar.get<double>((size_t)Hkv * hh);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    hipStream_t st = ctx->stream;
+    // ---- H_in and R for W_Q / W_K
+    TB_TRY(transpose(D, X, fp ? X_fp : nullptr, dm, T, dm, XT, fp ? dXh : nullptr, dXl, T));
+    TB_TRY(gram_splitk(D, dm, XT, nullptr, XT, T, T, 1.0, 1, part, Hin_qk));
+    if (fp && R_qk) TB_TRY(gram_splitk(D, dm, dXh, dXl, XT, T, T, d->alpha, 0, part, R_qk));
+    // ---- H_out: K_g^T K_g = W_K,g H_in W_K,g^T ; sum_h Q_h^T Q_h ; sum_h W_out,h^T W_out,h   (fp64)
+    TB_TRY(launch_cvt_f32_to_f64(ctx, Hin_qk, Hin64, dd));
+    TB_TRY(launch_cvt_to_f64(ctx, Wq, TBOA_BF16, Wq64, (int64_t)dq * dm));
+    TB_TRY(launch_cvt_to_f64(ctx, Wk, TBOA_BF16, Wk64, (int64_t)dkv * dm));
+    TB_TRY(launch_cvt_to_f64(ctx, Wo, TBOA_BF16, Wo64, (int64_t)dm * dq));
+    {
+        GemmF64 a{};
+        a.M = dq; a.N = dm; a.K = dm; a.alpha = 1.0; a.beta = 0.0; a.A = Wq64; a.sam = dm; a.sak = 1; a.B = Hin64; a.sbk = dm; a.sbn = 1;
+        a.C = Tq; a.ldc = dm; a.batch = 1;
+        TB_TRY(gemm_f64(ctx, a));
+        a.M = dkv; a.A = Wk64; a.C = Tk;
+        TB_TRY(gemm_f64(ctx, a));
+        GemmF64 b{};   // per KV head: Tk_g Wk_g^T
+        b.M = dh; b.N = dh; b.K = dm; b.alpha = 1.0; b.beta = 0.0; b.A = Tk; b.sam = dm; b.sak = 1; b.B = Wk64; b.sbk = 1; b.sbn = dm;
+        b.C = Ho; b.ldc = dh; b.batch = Hkv; b.strideA = (long long)dh * dm; b.strideB = b.strideA; b.strideC = hh;
+        TB_TRY(gemm_f64(ctx, b));
+        hipLaunchKernelGGL(bcast_heads_kernel, dim3(g1(Hq * hh)), dim3(256), 0, st, Ho, Hout_q, rep, hh, Hq * hh);
+        for (int r = 0; r < rep; ++r) {   // sum over the query heads of a group
+            b.A = Tq + (long long)r * dh * dm; b.B = Wq64 + (long long)r * dh * dm; b.beta = r ? 1.0 : 0.0;
+            b.strideA = (long long)rep * dh * dm; b.strideB = b.strideA;
+            TB_TRY(gemm_f64(ctx, b));
+        }
+        hipLaunchKernelGGL(bcast_heads_kernel, dim3(g1(Hkv * hh)), dim3(256), 0, st, Ho, Hout_k, 1, hh, Hkv * hh);
+        GemmF64 c{};   // W_out,h^T W_out,h, W_out,h = Wo[:, h dh : (h+1) dh]
+        c.M = dh; c.N = dh; c.K = dm; c.alpha = 1.0; c.sam = 1; c.sak = dq; c.sbk = dq; c.sbn = 1; c.C = Ho; c.ldc = dh;
+        c.batch = Hkv; c.strideA = (long long)rep * dh; c.strideB = c.strideA; c.strideC = hh;
+        for (int r = 0; r < rep; ++r) {
+            c.A = Wo64 + (long long)r * dh; c.B = c.A; c.beta = r ? 1.0 : 0.0;
+            TB_TRY(gemm_f64(ctx, c));
+        }
+        hipLaunchKernelGGL(bcast_heads_kernel, dim3(g1(Hkv * hh)), dim3(256), 0, st, Ho, Hout_v, 1, hh, Hkv * hh);
+        TB_KERNEL_CHECK(ctx);
+    }
+    // ---- H_in (and R) of W_V
+    TB_TRY(launch_fill_f32(ctx, Hin_v, (int64_t)Hkv * dd, 0.f));
+    if (rv) TB_TRY(launch_fill_f32(ctx, R_v, (int64_t)Hkv * dd, 0.f));
+    const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
+    for (int s0 = 0; s0 < D.S; s0 += G) {
+        const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
+        const long long t0 = (long long)s0 * L;
+        const long long ldx = (long long)Gc * nsx * L, ldy = (long long)rep * Gc * L;
+        TB_TRY(project_qk(D, X + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qh, Kh));
+        if (rv) TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
+        for (int sl = 0; sl < Gc; ++sl) {   // XcT[:, sl, :, :] = X_s^T | (X_s - X~_s)^T | X~_s^T
+            const bf16* xs = X + (t0 + (long long)sl * L) * dm;
+            bf16* o = XcT + (long long)sl * nsx * L;
+            if (!rv) TB_TRY(transpose(D, xs, nullptr, dm, L, dm, o, nullptr, nullptr, ldx));
+            else {
+                const bf16* xf = X_fp + (t0 + (long long)sl * L) * dm;
+                TB_TRY(transpose(D, xs, xf, dm, L, dm, o, o + L, nullptr, ldx));
+                TB_TRY(transpose(D, xf, nullptr, dm, L, dm, o + 2 * L, nullptr, nullptr, ldx));
+            }
+        }
+        for (int sl = 0; sl < Gc; ++sl) {
+            // P = [A | A - A~];  Y^T = X_s^T A^T;  (Y - Y~)^T = [dX_s^T | X~_s^T] [A | A - A~]^T  since  A X - A~ X~ = A dX + (A - A~) X~
+            TB_TRY(scores(D, Qh, Kh, sl, Sc));
+            if (rv) TB_TRY(scores(D, Qhf, Khf, sl, Scf));
+            TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, (long long)nsg * L, 1, L));
+            GemmBf16 y = nt(dm, L, L, 1.f, XcT + (long long)sl * nsx * L, ldx, P, (long long)nsg * L, YT + (long long)sl * L, ldy, TBOA_BF16, 0, cflag);
+            y.batch = Hq; y.batch_inner = rep;
+            y.strideB = (long long)rep * L * nsg * L; y.strideB2 = (long long)L * nsg * L;
+            y.strideC = (long long)dm * ldy; y.strideC2 = (long long)Gc * L;
+            TB_TRY(gemm_bf16_nt(ctx, y));
+            if (rv) { y.A = XcT + ((long long)sl * nsx + 1) * L; y.K = 2 * L; y.kseg = L; y.C = dYT + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, y)); }
+        }
+        GemmBf16 h = nt(dm, dm, (int)ldy, 1.f, YT, ldy, YT, ldy, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER);
+        h.batch = Hkv; h.strideA = (long long)dm * ldy; h.strideB = h.strideA; h.strideC = dd;
+        TB_TRY(gemm_bf16_nt(ctx, h));
+        if (rv) { h.A = dYT; h.C = R_v; h.flags = 0; h.alpha = (float)d->alpha; TB_TRY(gemm_bf16_nt(ctx, h)); }
+    }
+    TB_TRY(launch_mirror_lower_f32(ctx, Hin_v, dm, Hkv));
+    return 0;
+}
+
+int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, const bf16* X_fp, const float* Wq_deq,
+                                const float* Wk_deq, const float* Wv_deq, const bf16* Wq, const bf16* Wk, const bf16* Wv, float* Hin_o,
+                                float* R_o) {
+    const Dims D = dims_of(ctx, d);
+    TB_TRY(check_bf16_dims(D));
+    const int T = D.T, dm = D.dm, Hq = D.Hq, dh = D.dh, L = D.L, dq = D.dq, dkv = D.dkv, rep = D.rep;
+    const bool fp = X_fp && R_o;
+    int G = d->seq_chunk > 0 ? d->seq_chunk : 8; if (G > D.S) G = D.S;
+    const int nsg = fp ? 4 : 2, nsp = fp ? 3 : 2, splits = pick_splits(D.S);   // segments of V^T / of P
+    bf16 *Wqh, *Wql, *Wkh, *Wkl, *Wvh, *Wvl, *Qh, *Kh, *Qhf, *Khf, *P, *VTc, *OT, *dOT;
+    float *Qf, *Kf, *VT32, *VT32f, *Sc, *Scf, *part;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        Wqh = ar.get<bf16>((size_t)dq * dm); Wql = ar.get<bf16>((size_t)dq * dm);
+        Wkh = ar.get<bf16>((size_t)dkv * dm); Wkl = ar.get<bf16>((size_t)dkv * dm);
+        Wvh = ar.get<bf16>((size_t)dkv * dm); Wvl = ar.get<bf16>((size_t)dkv * dm);
+        Qf = ar.get<float>((size_t)G * L * dq); Kf = ar.get<float>((size_t)G * L * dkv); VT32 = ar.get<float>((size_t)dkv * G * L);
+        VT32f = fp ? ar.get<float>((size_t)dkv * G * L) : nullptr; Scf = fp ? ar.get<float>((size_t)Hq * L * L) : nullptr;
+        Qh = ar.get<bf16>((size_t)G * L * dq * 3); Kh = ar.get<bf16>((size_t)G * L * dkv * 3);
+        Qhf = fp ? ar.get<bf16>((size_t)G * L * dq * 3) : nullptr; Khf = fp ? ar.get<bf16>((size_t)G * L * dkv * 3) : nullptr;
+        Sc = ar.get<float>((size_t)Hq * L * L); P = ar.get<bf16>((size_t)Hq * L * nsp * L);
+        VTc = ar.get<bf16>((size_t)dkv * G * nsg * L);
+        OT = ar.get<bf16>((size_t)dq * T); dOT = fp ? ar.get<bf16>((size_t)dq * T) : nullptr;
+        part = ar.get<float>((size_t)splits * dq * dq);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    hipStream_t st = ctx->stream;
+    // dequantized weights as exact-to-16-bits (hi, lo) bf16 pairs
+    hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dq * dm)), dim3(256), 0, st, Wq_deq, Wqh, Wql, (long long)dq * dm);
+    hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dkv * dm)), dim3(256), 0, st, Wk_deq, Wkh, Wkl, (long long)dkv * dm);
+    hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dkv * dm)), dim3(256), 0, st, Wv_deq, Wvh, Wvl, (long long)dkv * dm);
+    TB_KERNEL_CHECK(ctx);
+    const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
+    for (int s0 = 0; s0 < D.S; s0 += G) {
+        const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
+        const long long t0 = (long long)s0 * L, ldv = (long long)Gc * nsg * L;
+        const bf16* Xc = X + t0 * dm;
+        // V'^T = Wv_deq Xc^T (fp32, from the (hi, lo) weight pair) and the full-precision V~^T = Wv X~c^T
+        TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvh, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 0, 0)));
+        TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvl, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 1, 0)));
+        TB_TRY(project_qk(D, Xc, Gc * L, Wqh, Wql, Wkh, Wkl, Qf, Kf, Qh, Kh));
+        if (fp) {
+            TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wv, dm, X_fp + t0 * dm, dm, VT32f, (long long)Gc * L, TBOA_F32, 0, 0)));
+            TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
+        }
+        hipLaunchKernelGGL(vt_segments_kernel, dim3(g1((long long)dkv * Gc * L)), dim3(256), 0, st, VT32, fp ? VT32f : nullptr, VTc, dkv, Gc, L, nsg);
+        TB_KERNEL_CHECK(ctx);
+        for (int sl = 0; sl < Gc; ++sl) {
+            // V^T segments [V'hi | V'lo | V' - V~ | V~], P = [A' | A' | A' - A~]:
+            // O^T_h = [V'hi | V'lo] [A' | A']^T ;  (O - O~)^T_h = [V' - V~ | V~] [A' | A' - A~]^T
+            TB_TRY(scores(D, Qh, Kh, sl, Sc));
+            if (fp) TB_TRY(scores(D, Qhf, Khf, sl, Scf));
+            TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, (long long)nsp * L, 2, 2 * L));
+            GemmBf16 o = nt(dh, L, 2 * L, 1.f, VTc + (long long)sl * nsg * L, ldv, P, (long long)nsp * L, OT + t0 + (long long)sl * L, T,
+                            TBOA_BF16, 0, cflag);
+            o.kseg = L; o.batch = Hq; o.batch_inner = rep;
+            o.strideA = (long long)dh * ldv; o.strideA2 = 0;
+            o.strideB = (long long)rep * L * nsp * L; o.strideB2 = (long long)L * nsp * L;
+            o.strideC = (long long)rep * dh * T; o.strideC2 = (long long)dh * T;
+            TB_TRY(gemm_bf16_nt(ctx, o));
+            if (fp) { o.A = VTc + ((long long)sl * nsg + 2) * L; o.B = P + L; o.C = dOT + t0 + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, o)); }
+        }
+    }
+    TB_TRY(gram_splitk(D, dq, OT, nullptr, OT, T, T, 1.0, 1, part, Hin_o));
+    if (fp) TB_TRY(gram_splitk(D, dq, dOT, nullptr, OT, T, T, d->alpha, 0, part, R_o));
+    return 0;
+}
+
+// Min-Max per-token fake quantization: one wavefront per token
+template <typename T>
+__global__ __launch_bounds__(256) void act_fakequant_kernel(const T* __restrict__ in, T* __restrict__ out, long long ntok, int d, float maxq) {
+    const int lane = threadIdx.x & 63;
+    const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= ntok) return;
+    const T* x = in + t * d; T* y = out + t * d;
+    float lo = 0.f, hi = 0.f;
+    for (int c = lane; c < d; c += 64) { const float v = (float)x[c]; lo = fminf(lo, v); hi = fmaxf(hi, v); }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { lo = fminf(lo, __shfl_xor(lo, o, 64)); hi = fmaxf(hi, __shfl_xor(hi, o, 64)); }
+    if (lo == hi) { lo = -1.f; hi = 1.f; }
+    // the decision (which level) is taken in fp64 from the exact input values
+    const double s = ((double)hi - (double)lo) / (double)maxq;
+    const double z = rint(-(double)lo / s);
+    for (int c = lane; c < d; c += 64) {
+        const double v = (double)(float)x[c];
+        const double q = fmin(fmax(rint(v / s) + z, 0.0), (double)maxq);
+        y[c] = (T)(float)(s * (q - z));
+    }
+}
+
+}  // namespace
+
+static int check_attn_desc(tboa_ctx* ctx, const tboa_attn_desc* d) {
+    if (!d) return tboa_fail(ctx, TBOA_EINVAL, "null descriptor");
+    if (d->d_model <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0 || d->n_seqs <= 0 || d->seq_len <= 0)
+        return tboa_fail(ctx, TBOA_EINVAL, "attention descriptor: non-positive dimension");
+    if (d->n_q_heads % d->n_kv_heads) return tboa_fail(ctx, TBOA_EINVAL, "n_q_heads=%d must be a multiple of n_kv_heads=%d", d->n_q_heads, d->n_kv_heads);
+    if (d->x_dtype != TBOA_F32 && d->x_dtype != TBOA_BF16) return tboa_fail(ctx, TBOA_EINVAL, "x_dtype must be fp32 or bf16");
+    if ((long long)d->n_seqs * d->seq_len > 2147483647LL) return tboa_fail(ctx, TBOA_EINVAL, "too many tokens");
+    return 0;
+}
+
+extern "C" int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, const void* X_fp, const void* Wq,
+                                   const void* Wk, const void* Wv, const void* Wo, float* Hin_qk, float* R_qk, float* Hout_q,
+                                   float* Hout_k, float* Hin_v, float* R_v, float* Hout_v) {
+    if (!ctx) return TBOA_EINVAL;
+    TB_TRY(check_attn_desc(ctx, d));
+    if (!X || !Wq || !Wk || !Wo || !Hin_qk || !Hout_q || !Hout_k || !Hin_v || !Hout_v) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: null argument");
+    if (X_fp && !R_qk) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: X_fp given without R_qk");
+    if (d->x_dtype == TBOA_F32) return build_hessians_f64(ctx, d, X, X_fp, Wq, Wk, Wv, Wo, Hin_qk, R_qk, Hout_q, Hout_k, Hin_v, R_v, Hout_v);
+    return build_hessians_bf16(ctx, d, (const bf16*)X, (const bf16*)X_fp, (const bf16*)Wq, (const bf16*)Wk, (const bf16*)Wo, Hin_qk, R_qk,
+                               Hout_q, Hout_k, Hin_v, R_v, Hout_v);
+}
+
+extern "C" int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, const void* X_fp, const float* Wq_deq,
+                                           const float* Wk_deq, const float* Wv_deq, const void* Wq, const void* Wk, const void* Wv,
+                                           float* Hin_o, float* R_o) {
+    if (!ctx) return TBOA_EINVAL;
+    TB_TRY(check_attn_desc(ctx, d));
+    if (!X || !Wq_deq || !Wk_deq || !Wv_deq || !Hin_o) return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_out_proj: null argument");
+    if (R_o && (!X_fp || !Wq || !Wk || !Wv)) return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_out_proj: R_o needs X_fp and the full-precision weights");
+    if (d->x_dtype == TBOA_F32) return build_hessian_out_proj_f64(ctx, d, X, X_fp, Wq_deq, Wk_deq, Wv_deq, Wq, Wk, Wv, Hin_o, R_o);
+    return build_hessian_out_proj_bf16(ctx, d, (const bf16*)X, (const bf16*)X_fp, Wq_deq, Wk_deq, Wv_deq, (const bf16*)Wq, (const bf16*)Wk,
+                                       (const bf16*)Wv, Hin_o, R_o);
+}
+
+extern "C" int tboa_act_fakequant(tboa_ctx* ctx, int64_t n_tokens, int d, int bits, int dtype, const void* X_in, void* X_out) {
+    if (!ctx) return TBOA_EINVAL;
+    if (n_tokens < 0 || d <= 0 || bits < 2 || bits > 8 || !X_in || !X_out) return tboa_fail(ctx, TBOA_EINVAL, "act_fakequant: bad arguments");
+    if (n_tokens == 0) return 0;
+    const float maxq = (float)((1 << bits) - 1);
+    const unsigned grid = (unsigned)((n_tokens + 3) / 4);
+    if (dtype == TBOA_F32)
+        hipLaunchKernelGGL(act_fakequant_kernel<float>, dim3(grid), dim3(256), 0, ctx->stream, (const float*)X_in, (float*)X_out, (long long)n_tokens, d, maxq);
+    else if (dtype == TBOA_BF16)
+        hipLaunchKernelGGL(act_fakequant_kernel<bf16>, dim3(grid), dim3(256), 0, ctx->stream, (const bf16*)X_in, (bf16*)X_out, (long long)n_tokens, d, maxq);
+    else return tboa_fail(ctx, TBOA_EINVAL, "act_fakequant: dtype must be fp32 or bf16");
+    TB_KERNEL_CHECK(ctx);
+    return 0;
+}

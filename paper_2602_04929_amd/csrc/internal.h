@@ -81,6 +81,7 @@ struct GemmBf16 {
     int batch; int64_t strideA, strideB, strideC;
     // two-level batch: z -> (z / batch_inner, z % batch_inner); the *2 strides apply to the inner index
     int batch_inner = 1; int64_t strideA2 = 0, strideB2 = 0, strideC2 = 0;
+    int kseg = 0;   // > 0: K is a concatenation of K/kseg segments; TBOA_GEMM_CAUSAL_K then limits each segment
 };
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
 
@@ -102,3 +103,11 @@ int launch_strict_upper_f64(tboa_ctx* ctx, double* a, int n, int batch);
 // symmetrise: upper <- lower (fp32, n x n, batch)
 int launch_mirror_lower_f32(tboa_ctx* ctx, float* a, int n, int batch);
 int launch_sub_f64(tboa_ctx* ctx, const double* a, const double* b, double* out, int64_t n);
+
+// ---------------------------------------------------------------- hessian_f64.hip
+int build_hessians_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, const void* X_fp, const void* Wq, const void* Wk,
+                       const void* Wv, const void* Wo, float* Hin_qk, float* R_qk, float* Hout_q, float* Hout_k, float* Hin_v,
+                       float* R_v, float* Hout_v);
+int build_hessian_out_proj_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, const void* X_fp, const float* Wq_deq,
+                               const float* Wk_deq, const float* Wv_deq, const void* Wq, const void* Wk, const void* Wv,
+                               float* Hin_o, float* R_o);

@@ -57,3 +57,36 @@ def test_chol_inv_upper_rejects_indefinite(ctx, lib):
     with pytest.raises(lib.TurboBoAError) as e:
         ctx.chol_inv_upper(H)
     assert e.value.code == -2 and "40" in str(e.value)
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (512, 768, 256), (300, 200, 72), (32, 40, 8), (1024, 1024, 1024)])
+def test_gemm_bf16_nt(ctx, M, N, K):
+    print("gemm_bf16_nt", M, N, K, flush=True)
+    g = torch.Generator(device="cuda"); g.manual_seed(M + N + K)
+    A = torch.randn(M, K, generator=g, device="cuda").to(torch.bfloat16)
+    B = torch.randn(N, K, generator=g, device="cuda").to(torch.bfloat16)
+    want = A.double().cpu().numpy() @ B.double().cpu().numpy().T
+    got = ctx.gemm_bf16_nt(A, B, alpha=0.5).cpu().numpy()
+    assert np.allclose(got, 0.5 * want, rtol=0, atol=1e-5 * np.sqrt(K) * 4)
+    got16 = ctx.gemm_bf16_nt(A, B, out_dtype=torch.bfloat16).float().cpu().numpy()
+    assert np.allclose(got16, want, rtol=2 ** -8, atol=1e-3)
+    C0 = torch.ones(M, N, device="cuda")
+    acc = ctx.gemm_bf16_nt(A, B, C_out=C0, accumulate=True).cpu().numpy()
+    assert np.allclose(acc, want + 1.0, rtol=0, atol=1e-5 * np.sqrt(K) * 4)
+
+
+def test_gemm_bf16_flags_and_batch(ctx, lib):
+    g = torch.Generator(device="cuda"); g.manual_seed(3)
+    n, K = 768, 512
+    A = torch.randn(2, n, K, generator=g, device="cuda").to(torch.bfloat16)
+    want = np.einsum("bik,bjk->bij", A.double().cpu().numpy(), A.double().cpu().numpy())
+    low = ctx.gemm_bf16_nt(A, A, flags=lib.GEMM_LOWER).cpu().numpy()
+    for b in range(2):
+        assert np.allclose(np.tril(low[b]), np.tril(want[b]), atol=1e-3)
+        assert np.all(low[b][:256, 512:] == 0)             # tiles above the diagonal are not touched
+    # causal: B lower triangular [N, K] with K == N
+    P = torch.tril(torch.rand(n, n, generator=g, device="cuda")).to(torch.bfloat16)
+    Xt = torch.randn(300, n, generator=g, device="cuda").to(torch.bfloat16)
+    want2 = Xt.double().cpu().numpy() @ P.double().cpu().numpy().T
+    got2 = ctx.gemm_bf16_nt(Xt, P, flags=lib.GEMM_CAUSAL_K).cpu().numpy()
+    assert np.allclose(got2, want2, atol=1e-3)

@@ -1,0 +1,105 @@
+"""tboa_build_hessians / tboa_build_hessian_out_proj / tboa_act_fakequant against the oracle (GPU)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import turboboa_ref as O
+from paper_2602_04929_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    c = lib.Context()
+    yield c
+    c.close()
+
+
+def np64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def rel_err(got, want):
+    """max |got - want| scaled by sqrt(diag_i diag_j)-like magnitude: the largest entry of want."""
+    return np.abs(got - want).max() / np.abs(want).max()
+
+
+def check_all(got, want, tol, tol_v, tol_r):
+    for k, t in (("Hin_qk", tol), ("Hout_q", tol), ("Hout_k", tol), ("Hout_v", tol), ("Hin_v", tol_v)):
+        e = rel_err(np64(got[k]), want[k]); print(k, "rel err %.2e" % e, flush=True)
+        assert e <= t, (k, e)
+    for k in ("R_qk", "R_v"):
+        if want[k] is not None and got[k] is not None:
+            e = rel_err(np64(got[k]), want[k]); print(k, "rel err %.2e" % e, flush=True)
+            assert e <= tol_r, (k, e)
+
+
+def test_fp32_path_small_gqa(ctx):
+    """fp64-MFMA path: ragged sizes, grouped-query heads, both R."""
+    cfg = synth.scaled(synth.CONFIGS["tiny"], d_model=72, n_q_heads=4, n_kv_heads=2, head_dim=12, n_seqs=3, seq_len=50, n_outlier=2)
+    b = synth.make_block(cfg, seed=1, device="cuda")
+    got = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 4, 2, 12, alpha=0.25)
+    want = O.build_hessians(np64(b["X"]), np64(b["X_fp"]), np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), 4, 2, 12, alpha=0.25)
+    check_all(got, want, 1e-6, 1e-6, 1e-6)       # fp32 storage of the outputs
+    got2 = ctx.build_hessians(b["X"], None, b["Wq"], b["Wk"], b["Wv"], b["Wo"], 4, 2, 12)
+    assert got2["R_qk"] is None and torch.equal(got2["Hin_v"], got["Hin_v"])
+
+
+def test_fp32_path_tiny_config(ctx):
+    cfg = synth.scaled(synth.CONFIGS["tiny"], n_seqs=2)
+    b = synth.make_block(cfg, seed=0, device="cuda")
+    got = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 4, 4, 64, alpha=0.25)
+    want = O.build_hessians(np64(b["X"]), np64(b["X_fp"]), np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), 4, 4, 64, alpha=0.25)
+    check_all(got, want, 1e-6, 1e-6, 1e-6)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("hq,hkv", [(2, 2), (4, 2)])
+def test_bf16_path_small(ctx, causal, hq, hkv):
+    """bf16-MFMA path at sizes that span several 256-tiles with ragged edges (L = 320, d = 264)."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=264, n_q_heads=hq, n_kv_heads=hkv, head_dim=32, n_seqs=3, seq_len=320, n_outlier=3)
+    b = synth.make_block(cfg, seed=2, device="cuda")
+    got = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], hq, hkv, 32, alpha=0.25, causal=causal, seq_chunk=2)
+    want = O.build_hessians(np64(b["X"]), np64(b["X_fp"]), np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), hq, hkv, 32,
+                            alpha=0.25, causal=causal)
+    # X, W exact in bf16 and fp32 accumulation: 1e-5; probabilities and Y rounded to bf16 (2^-9, unbiased): 2e-3
+    check_all(got, want, 1e-5, 2e-3, 2e-2)
+    assert torch.equal(got["Hin_v"], got["Hin_v"].transpose(1, 2))
+
+
+def test_out_proj_fp32(ctx):
+    cfg = synth.scaled(synth.CONFIGS["tiny"], d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, n_seqs=2, seq_len=40, n_outlier=2)
+    b = synth.make_block(cfg, seed=3, device="cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    deq = [w.float() * (1 + 0.05 * torch.randn(w.shape, generator=g, device="cuda")) for w in (b["Wq"], b["Wk"], b["Wv"])]
+    Hin_o, R_o = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, b["Wq"], b["Wk"], b["Wv"], 4, 2, 16, alpha=0.25)
+    wH, wR = O.build_hessian_out_proj(np64(b["X"]), np64(b["X_fp"]), *[np64(w) for w in deq], np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]),
+                                      4, 2, 16, alpha=0.25)
+    assert rel_err(np64(Hin_o), wH) <= 1e-6 and rel_err(np64(R_o), wR) <= 1e-6
+
+
+def test_out_proj_bf16(ctx):
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=264, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=3, seq_len=320, n_outlier=3)
+    b = synth.make_block(cfg, seed=4, device="cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    deq = [w.float() * (1 + 0.05 * torch.randn(w.shape, generator=g, device="cuda")) for w in (b["Wq"], b["Wk"], b["Wv"])]
+    Hin_o, R_o = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, b["Wq"], b["Wk"], b["Wv"], 4, 2, 32, alpha=0.25, seq_chunk=2)
+    wH, wR = O.build_hessian_out_proj(np64(b["X"]), np64(b["X_fp"]), *[np64(w) for w in deq], np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]),
+                                      4, 2, 32, alpha=0.25)
+    eH, eR = rel_err(np64(Hin_o), wH), rel_err(np64(R_o), wR)
+    print("Hin_o %.2e R_o %.2e" % (eH, eR), flush=True)
+    assert eH <= 2e-3 and eR <= 2e-2
+    H2, R2 = ctx.build_hessian_out_proj(b["X"], None, *deq, None, None, None, 4, 2, 32, seq_chunk=3)
+    assert R2 is None and rel_err(np64(H2), wH) <= 2e-3
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_act_fakequant(ctx, dtype):
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    X = (torch.randn(37, 200, generator=g, device="cuda") * torch.rand(37, 1, generator=g, device="cuda") * 4).to(dtype)
+    X[5] = 0
+    got = ctx.act_fakequant(X, 4)
+    want = O.act_fakequant_per_token(np64(X), 4)
+    want_t = torch.tensor(want).to(dtype).float().numpy()          # the output is stored in the input's type
+    assert np.array_equal(got.float().cpu().numpy(), want_t)
