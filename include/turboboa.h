@@ -168,6 +168,25 @@ int tboa_gemm_bf16_nt(tboa_ctx* ctx, int M, int N, int K, float alpha,
                       void* C, int64_t ldc, int c_dtype, int accumulate, int flags,
                       int batch, int64_t strideA, int64_t strideB, int64_t strideC);
 
+/* ------------------------------------------------------------------------------------------------
+ * Live kernel timing.  With profiling on, every bf16 GEMM launch of the Hessian build that carries one of the tags
+ * below is bracketed by HIP events on the context's stream.  tboa_profile_read synchronises the stream and returns,
+ * for one tag, the summed kernel time, the number of launches and the summed algorithmic flops of those launches
+ * (2 M N K per batch entry; a symmetric product counts its M(M+1)/2 unique outputs, a product with a lower
+ * triangular factor the k <= n part).  tboa_profile_reset drops the records.
+ */
+enum tboa_prof_tag {
+    TBOA_PROF_HV_SYRK = 0,   /* H_in^V += Y^T (Y^T)^T                 */
+    TBOA_PROF_AX = 1,        /* Y^T = X_s^T A_h^T (and the dY^T form) */
+    TBOA_PROF_RV = 2,        /* R_v += alpha dY^T (Y^T)^T             */
+    TBOA_PROF_GRAM = 3,      /* X X^T, dX X^T, O O^T over all tokens  */
+    TBOA_PROF_PROJ = 4,      /* projections and scores                */
+    TBOA_PROF_NTAGS = 5
+};
+int tboa_profile_enable(tboa_ctx* ctx, int on);
+int tboa_profile_reset(tboa_ctx* ctx);
+int tboa_profile_read(tboa_ctx* ctx, int tag, double* ms_total, int64_t* launches, double* flops_total);
+
 #ifdef __cplusplus
 }
 #endif

@@ -57,6 +57,9 @@ def _load():
         "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 10, i32),
         "tboa_act_fakequant": ([vp, i64, i32, i32, i32, vp, vp], i32),
         "tboa_quantize_layer": ([vp, C.POINTER(LayerDesc)] + [vp] * 8 + [C.POINTER(f64), C.POINTER(f64)], i32),
+        "tboa_profile_enable": ([vp, i32], i32),
+        "tboa_profile_reset": ([vp], i32),
+        "tboa_profile_read": ([vp, i32, C.POINTER(f64), C.POINTER(i64), C.POINTER(f64)], i32),
     }
     missing = [n for n in sigs if not hasattr(lib, n)]
     if missing:
@@ -114,6 +117,18 @@ class Context:
 
     def workspace_bytes(self):
         return int(_lib.tboa_workspace_bytes(self._h))
+
+    # ---- live kernel timing
+    PROF_TAGS = {"hv_syrk": 0, "ax": 1, "rv": 2, "gram": 3, "proj": 4}
+
+    def profile(self, on=True):
+        self._check(_lib.tboa_profile_enable(self._h, int(on)))
+        self._check(_lib.tboa_profile_reset(self._h))
+
+    def profile_read(self, tag):
+        ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
+        self._check(_lib.tboa_profile_read(self._h, self.PROF_TAGS[tag], C.byref(ms), C.byref(n), C.byref(fl)))
+        return dict(ms=ms.value, launches=n.value, flops=fl.value)
 
     # ---- building blocks
     def gemm_f64(self, A, B, C_out=None, alpha=1.0, beta=0.0, transA=False, transB=False):

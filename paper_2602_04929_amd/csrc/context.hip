@@ -36,7 +36,7 @@ extern "C" int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream) {
     c->stream = (hipStream_t)hip_stream;
     c->err[0] = 0;
     c->ws = nullptr; c->ws_bytes = 0;
-    c->d_status = nullptr; c->h_status = nullptr;
+    c->d_status = nullptr; c->h_status = nullptr; c->prof_on = 0;
     if (hipMalloc(&c->d_status, 64 * sizeof(int)) != hipSuccess ||
         hipHostMalloc(&c->h_status, 64 * sizeof(int)) != hipSuccess) {
         if (c->d_status) (void)hipFree(c->d_status);
@@ -47,10 +47,41 @@ extern "C" int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream) {
     return 0;
 }
 
+extern "C" int tboa_profile_enable(tboa_ctx* ctx, int on) {
+    if (!ctx) return TBOA_EINVAL;
+    ctx->prof_on = on ? 1 : 0;
+    return 0;
+}
+
+extern "C" int tboa_profile_reset(tboa_ctx* ctx) {
+    if (!ctx) return TBOA_EINVAL;
+    TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    ctx->prof.clear();
+    return 0;
+}
+
+extern "C" int tboa_profile_read(tboa_ctx* ctx, int tag, double* ms_total, int64_t* launches, double* flops_total) {
+    if (!ctx) return TBOA_EINVAL;
+    TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    double ms = 0.0, fl = 0.0; int64_t n = 0;
+    for (auto& r : ctx->prof) {
+        if (r.tag != tag) continue;
+        float t = 0.f;
+        TB_HIP(ctx, hipEventElapsedTime(&t, r.a, r.b));
+        ms += t; fl += r.flops; ++n;
+    }
+    if (ms_total) *ms_total = ms;
+    if (launches) *launches = n;
+    if (flops_total) *flops_total = fl;
+    return 0;
+}
+
 extern "C" void tboa_destroy(tboa_ctx* ctx) {
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
+    for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);

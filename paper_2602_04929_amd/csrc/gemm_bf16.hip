@@ -185,8 +185,22 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     a.tiles_m = (int)cdiv64(q.M, BM); a.tiles_n = (int)cdiv64(q.N, BN);
     const long long ntiles = (long long)a.tiles_m * a.tiles_n;
     if (ntiles > 2147483647LL || q.batch > 65535) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: grid too large");
+    const bool timed = ctx->prof_on && q.tag >= 0;
+    ProfRec rec{};
+    if (timed) {
+        TB_HIP(ctx, hipEventCreate(&rec.a)); TB_HIP(ctx, hipEventCreate(&rec.b));
+        rec.tag = q.tag;
+        const int nseg = q.kseg > 0 ? q.K / q.kseg : 1;
+        const double ks = q.kseg > 0 ? q.kseg : q.K;
+        double mnk = (double)q.M * q.N * ks;
+        if (q.flags & TBOA_GEMM_LOWER) mnk = 0.5 * (double)q.M * (q.M + 1.0) * ks;
+        else if ((q.flags & TBOA_GEMM_CAUSAL_K) && ks >= q.N) mnk = 0.5 * (double)q.M * q.N * (q.N + 1.0);
+        rec.flops = 2.0 * mnk * nseg * q.batch;
+        TB_HIP(ctx, hipEventRecord(rec.a, ctx->stream));
+    }
     hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((unsigned)ntiles, (unsigned)q.batch), dim3(256), smem, ctx->stream, a);
     TB_KERNEL_CHECK(ctx);
+    if (timed) { TB_HIP(ctx, hipEventRecord(rec.b, ctx->stream)); ctx->prof.push_back(rec); }
     return 0;
 }
 

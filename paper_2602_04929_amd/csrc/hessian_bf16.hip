@@ -167,7 +167,7 @@ GemmBf16 nt(int M, int N, int K, float alpha, const bf16* A, long long lda, cons
             int c_dtype, int accumulate, int flags) {
     GemmBf16 g{};
     g.M = M; g.N = N; g.K = K; g.alpha = alpha; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
-    g.c_dtype = c_dtype; g.accumulate = accumulate; g.flags = flags; g.batch = 1;
+    g.c_dtype = c_dtype; g.accumulate = accumulate; g.flags = flags; g.batch = 1; g.tag = TBOA_PROF_PROJ;
     return g;
 }
 
@@ -176,6 +176,7 @@ int gram_splitk(const Dims& D, int n, const bf16* A, const bf16* A_lo, const bf1
                 float* part, float* out) {
     const int splits = pick_splits(D.S), Kc = K / splits;
     GemmBf16 g = nt(n, n, Kc, 1.f, A, ld, B, ld, part, n, TBOA_F32, 0, lower ? TBOA_GEMM_LOWER : 0);
+    g.tag = TBOA_PROF_GRAM;
     g.batch = splits; g.strideA = Kc; g.strideB = Kc; g.strideC = (long long)n * n;
     if (lower) TB_TRY(launch_fill_f32(D.ctx, part, (int64_t)splits * n * n, 0.f));
     TB_TRY(gemm_bf16_nt(D.ctx, g));
@@ -315,16 +316,16 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
             if (rv) TB_TRY(scores(D, Qhf, Khf, sl, Scf));
             TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, (long long)nsg * L, 1, L));
             GemmBf16 y = nt(dm, L, L, 1.f, XcT + (long long)sl * nsx * L, ldx, P, (long long)nsg * L, YT + (long long)sl * L, ldy, TBOA_BF16, 0, cflag);
-            y.batch = Hq; y.batch_inner = rep;
+            y.batch = Hq; y.batch_inner = rep; y.tag = TBOA_PROF_AX;
             y.strideB = (long long)rep * L * nsg * L; y.strideB2 = (long long)L * nsg * L;
             y.strideC = (long long)dm * ldy; y.strideC2 = (long long)Gc * L;
             TB_TRY(gemm_bf16_nt(ctx, y));
             if (rv) { y.A = XcT + ((long long)sl * nsx + 1) * L; y.K = 2 * L; y.kseg = L; y.C = dYT + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, y)); }
         }
         GemmBf16 h = nt(dm, dm, (int)ldy, 1.f, YT, ldy, YT, ldy, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER);
-        h.batch = Hkv; h.strideA = (long long)dm * ldy; h.strideB = h.strideA; h.strideC = dd;
+        h.batch = Hkv; h.strideA = (long long)dm * ldy; h.strideB = h.strideA; h.strideC = dd; h.tag = TBOA_PROF_HV_SYRK;
         TB_TRY(gemm_bf16_nt(ctx, h));
-        if (rv) { h.A = dYT; h.C = R_v; h.flags = 0; h.alpha = (float)d->alpha; TB_TRY(gemm_bf16_nt(ctx, h)); }
+        if (rv) { h.tag = TBOA_PROF_RV; h.A = dYT; h.C = R_v; h.flags = 0; h.alpha = (float)d->alpha; TB_TRY(gemm_bf16_nt(ctx, h)); }
     }
     TB_TRY(launch_mirror_lower_f32(ctx, Hin_v, dm, Hkv));
     return 0;

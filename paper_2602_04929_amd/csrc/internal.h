@@ -6,7 +6,10 @@
 #include <stdio.h>
 #include <stdarg.h>
 #include <string.h>
+#include <vector>
 #include "../../include/turboboa.h"
+
+struct ProfRec { hipEvent_t a, b; int tag; double flops; };
 
 struct tboa_ctx {
     int device;
@@ -16,6 +19,8 @@ struct tboa_ctx {
     size_t ws_bytes;
     int* d_status;       // device status words (factorisation breakdown etc.)
     int* h_status;       // pinned host mirror
+    int prof_on;         // record HIP events around tagged GEMM launches
+    std::vector<ProfRec> prof;
 };
 
 int tboa_fail(tboa_ctx* ctx, int code, const char* fmt, ...);
@@ -81,6 +86,7 @@ struct GemmBf16 {
     int batch; int64_t strideA, strideB, strideC;
     // two-level batch: z -> (z / batch_inner, z % batch_inner); the *2 strides apply to the inner index
     int batch_inner = 1; int64_t strideA2 = 0, strideB2 = 0, strideC2 = 0;
+    int tag = -1;   // tboa_prof_tag of this launch (timed with HIP events when profiling is on)
     int kseg = 0;   // > 0: K is a concatenation of K/kseg segments; TBOA_GEMM_CAUSAL_K then limits each segment
 };
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);

@@ -1,0 +1,45 @@
+"""One attention block through the library: the sequence of C-ABI calls of the hot path, nothing else."""
+from __future__ import annotations
+
+import time
+
+import torch
+
+
+def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=True, cd_iters=1, adaptive_grid=True,
+                             damp=0.01, seq_chunk=0, timings=None):
+    """Hessians -> W_Q, W_K, W_V -> output-projection Hessian -> W_O.
+
+    blk: dict from synth.make_block (device tensors); cfg: synth.BlockConfig.  Returns dict of per-layer results
+    and the Hessians.  `timings` (a dict) receives per-stage seconds measured with stream synchronisation."""
+    Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    X_fp = blk["X_fp"]
+    X = blk["X"]
+
+    def stage(name, fn):
+        if timings is None:
+            return fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        out = fn()
+        torch.cuda.synchronize()
+        timings[name] = timings.get(name, 0.0) + time.perf_counter() - t
+        return out
+
+    if X is None:      # weight-activation setting: the quantized path sees per-token fake-quantized activations
+        X = stage("act_fakequant", lambda: ctx.act_fakequant(X_fp, cfg.act_bits))
+    Xf = X_fp if use_R else None
+    Hs = stage("build_hessians", lambda: ctx.build_hessians(X, Xf, blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], Hq, Hkv, dh,
+                                                            alpha=alpha, with_R_v=with_R_v, seq_chunk=seq_chunk))
+    kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp)
+    out = {"hessians": Hs, "X": X}
+    out["q"] = stage("quantize_q", lambda: ctx.quantize_layer(blk["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq, **kw))
+    out["k"] = stage("quantize_k", lambda: ctx.quantize_layer(blk["Wk"], Hs["Hin_qk"], Hs["Hout_k"], Hs["R_qk"], Hkv, **kw))
+    out["v"] = stage("quantize_v", lambda: ctx.quantize_layer(blk["Wv"], Hs["Hin_v"], Hs["Hout_v"], Hs["R_v"], Hkv, **kw))
+    Ho = stage("build_hessian_out_proj", lambda: ctx.build_hessian_out_proj(
+        X, Xf, out["q"]["W_deq"], out["k"]["W_deq"], out["v"]["W_deq"], blk["Wq"], blk["Wk"], blk["Wv"], Hq, Hkv, dh,
+        alpha=alpha, seq_chunk=seq_chunk))
+    out["Hin_o"], out["R_o"] = Ho
+    kwo = dict(kw, block=cfg.d_model)      # H_out = I: all rows form one step
+    out["o"] = stage("quantize_o", lambda: ctx.quantize_layer(blk["Wo"], Ho[0], None, Ho[1], 1, **kwo))
+    return out

@@ -1,0 +1,46 @@
+"""Whole hot path on the tiny configuration, end to end against the oracle (GPU)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import turboboa_ref as O
+from paper_2602_04929_amd import synth
+from tests.parity import compare_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def f64(t):
+    return None if t is None else t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def oracle_block(blk, cfg, alpha=0.25, use_R=True):
+    Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    X, Xf = f64(blk["X"]), f64(blk["X_fp"]) if use_R else None
+    W = {k: f64(blk[k]) for k in ("Wq", "Wk", "Wv", "Wo")}
+    Hs = O.build_hessians(X, Xf, W["Wq"], W["Wk"], W["Wv"], W["Wo"], Hq, Hkv, dh, alpha=alpha)
+    kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group)
+    out = {"hessians": Hs}
+    out["q"] = O.quantize_layer(W["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq, **kw)
+    out["k"] = O.quantize_layer(W["Wk"], Hs["Hin_qk"], Hs["Hout_k"], Hs["R_qk"], Hkv, **kw)
+    out["v"] = O.quantize_layer(W["Wv"], Hs["Hin_v"], Hs["Hout_v"], Hs["R_v"], Hkv, **kw)
+    Hin_o, R_o = O.build_hessian_out_proj(X, Xf, out["q"]["W_deq"], out["k"]["W_deq"], out["v"]["W_deq"], W["Wq"], W["Wk"], W["Wv"],
+                                          Hq, Hkv, dh, alpha=alpha)
+    out["o"] = O.quantize_layer(W["Wo"], Hin_o, None, R_o, 1, **dict(kw, block=cfg.d_model))
+    return out
+
+
+@pytest.mark.parametrize("use_R", [True, False])
+def test_tiny_config_end_to_end(lib, use_R):
+    """Config 1 (d_model 256, 4 heads x 64, 8 x 128 tokens, INT2, N = 4, seed 0): every layer against the oracle,
+    each side building its own Hessians from the same X."""
+    from paper_2602_04929_amd.pipeline import quantize_attention_block
+    cfg = synth.CONFIGS["tiny"]
+    blk = synth.make_block(cfg, seed=0, device="cuda")
+    ctx = lib.Context()
+    got = quantize_attention_block(ctx, blk, cfg, use_R=use_R)
+    want = oracle_block(blk, cfg, use_R=use_R)
+    for layer in ("q", "k", "v", "o"):
+        frac = compare_layer(got[layer], want[layer], label=layer)
+        print("tiny R=%s layer %s: codes identical %.4f%%" % (use_R, layer, 100 * frac), flush=True)
+    ctx.close()
