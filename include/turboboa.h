@@ -50,6 +50,12 @@ int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream);
 void tboa_destroy(tboa_ctx* ctx);
 /* Text of the last error on this context; owned by the context, valid until the next call on it. */
 const char* tboa_last_error(const tboa_ctx* ctx);
+/* Event counters of this context since its creation (host values).
+ * TBOA_CTR_GRID_PASSES: grid-search passes that used the two-phase search (approximate costs of all candidates on the
+ * bf16 matrix cores, exact fp64 costs of the near-minimal ones); TBOA_CTR_GRID_FALLBACKS: those among them that met a
+ * row with more near-minimal candidates than are re-evaluated and therefore evaluated every candidate in fp64. */
+enum tboa_counter_id { TBOA_CTR_GRID_PASSES = 0, TBOA_CTR_GRID_FALLBACKS = 1 };
+int64_t tboa_counter(const tboa_ctx* ctx, int which);
 /* Bytes of context-owned workspace currently allocated (host value). */
 size_t tboa_workspace_bytes(const tboa_ctx* ctx);
 
@@ -169,7 +175,7 @@ int tboa_gemm_bf16_nt(tboa_ctx* ctx, int M, int N, int K, float alpha,
                       int batch, int64_t strideA, int64_t strideB, int64_t strideC);
 
 /* ------------------------------------------------------------------------------------------------
- * Live kernel timing.  With profiling on, every bf16 GEMM launch of the Hessian build that carries one of the tags
+ * Live kernel timing.  With profiling on, every bf16 GEMM launch that carries one of the tags
  * below is bracketed by HIP events on the context's stream.  tboa_profile_read synchronises the stream and returns,
  * for one tag, the summed kernel time, the number of launches and the summed algorithmic flops of those launches
  * (2 M N K per batch entry; a symmetric product counts its M(M+1)/2 unique outputs, a product with a lower
@@ -181,7 +187,8 @@ enum tboa_prof_tag {
     TBOA_PROF_RV = 2,        /* R_v += alpha dY^T (Y^T)^T             */
     TBOA_PROF_GRAM = 3,      /* X X^T, dX X^T, O O^T over all tokens  */
     TBOA_PROF_PROJ = 4,      /* projections and scores                */
-    TBOA_PROF_NTAGS = 5
+    TBOA_PROF_GRID = 5,      /* approximate grid-search costs (quantize_layer) */
+    TBOA_PROF_NTAGS = 6
 };
 int tboa_profile_enable(tboa_ctx* ctx, int on);
 int tboa_profile_reset(tboa_ctx* ctx);

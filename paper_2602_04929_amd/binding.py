@@ -57,6 +57,7 @@ def _load():
         "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 10, i32),
         "tboa_act_fakequant": ([vp, i64, i32, i32, i32, vp, vp], i32),
         "tboa_quantize_layer": ([vp, C.POINTER(LayerDesc)] + [vp] * 8 + [C.POINTER(f64), C.POINTER(f64)], i32),
+        "tboa_counter": ([vp, i32], i64),
         "tboa_profile_enable": ([vp, i32], i32),
         "tboa_profile_reset": ([vp], i32),
         "tboa_profile_read": ([vp, i32, C.POINTER(f64), C.POINTER(i64), C.POINTER(f64)], i32),
@@ -115,11 +116,15 @@ class Context:
         if rc != 0:
             raise TurboBoAError(rc, _lib.tboa_last_error(self._h).decode())
 
+    def counter(self, which):
+        """0: two-phase grid-search passes, 1: passes that fell back to exact evaluation of every candidate."""
+        return int(_lib.tboa_counter(self._h, which))
+
     def workspace_bytes(self):
         return int(_lib.tboa_workspace_bytes(self._h))
 
     # ---- live kernel timing
-    PROF_TAGS = {"hv_syrk": 0, "ax": 1, "rv": 2, "gram": 3, "proj": 4}
+    PROF_TAGS = {"hv_syrk": 0, "ax": 1, "rv": 2, "gram": 3, "proj": 4, "grid": 5}
 
     def profile(self, on=True):
         self._check(_lib.tboa_profile_enable(self._h, int(on)))

@@ -37,6 +37,7 @@ extern "C" int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream) {
     c->err[0] = 0;
     c->ws = nullptr; c->ws_bytes = 0;
     c->d_status = nullptr; c->h_status = nullptr; c->prof_on = 0;
+    for (auto& v : c->counters) v = 0;
     if (hipMalloc(&c->d_status, 64 * sizeof(int)) != hipSuccess ||
         hipHostMalloc(&c->h_status, 64 * sizeof(int)) != hipSuccess) {
         if (c->d_status) (void)hipFree(c->d_status);
@@ -88,6 +89,7 @@ extern "C" void tboa_destroy(tboa_ctx* ctx) {
     delete ctx;
 }
 
+extern "C" int64_t tboa_counter(const tboa_ctx* ctx, int which) { return (ctx && which >= 0 && which < 4) ? ctx->counters[which] : -1; }
 extern "C" const char* tboa_last_error(const tboa_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 extern "C" size_t tboa_workspace_bytes(const tboa_ctx* ctx) { return ctx ? ctx->ws_bytes : 0; }
 

@@ -62,18 +62,32 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
     __hip_bfloat16* As = (__hip_bfloat16*)smem;                 // [2][BM*BK]
     __hip_bfloat16* Bs = As + 2 * BM * BK;                      // [2][BN*BK]
 
-    // tile numbering: workgroup w runs on XCD w % 8; give each XCD a contiguous run of tiles, and walk the tiles
-    // of a run in bands of 4 tile rows so that neighbours in time share A or B panels
-    const int ntiles = g.tiles_m * g.tiles_n;
-    int tile = blockIdx.x;
-    if (ntiles % 8 == 0) tile = (tile & 7) * (ntiles / 8) + (tile >> 3);
-    const int band = 4;
-    const int band_tiles = band * g.tiles_n;
-    const int bi = tile / band_tiles, in = tile % band_tiles;
-    const int rows_in_band = min(band, g.tiles_m - bi * band);
-    const int tm = bi * band + in % rows_in_band, tn = in / rows_in_band;
+    // Tile numbering.  Workgroup w runs on XCD w % 8 (round-robin dispatch), so XCD x takes the contiguous run
+    // [x*per, (x+1)*per) of the tile list and its workgroups share operand panels through that XCD's L2.  The list has
+    // only the tiles that do work (the lower triangle of a symmetric product), and for a causal contraction a run
+    // holds every tile column the same number of times, long columns first: all XCDs get equal work.
+    const bool lower = g.flags & TBOA_GEMM_LOWER, causal = g.flags & TBOA_GEMM_CAUSAL_K;
+    const int ntiles = lower ? g.tiles_m * (g.tiles_m + 1) / 2 : g.tiles_m * g.tiles_n;
+    const int per = (ntiles + 7) / 8;
+    const int loc = blockIdx.x >> 3;
+    const int tile = (blockIdx.x & 7) * per + loc;
+    if (loc >= per || tile >= ntiles) return;
+    int tm, tn;
+    if (lower) {
+        tm = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
+        while ((tm + 1) * (tm + 2) / 2 <= tile) ++tm;
+        while (tm * (tm + 1) / 2 > tile) --tm;
+        tn = tile - tm * (tm + 1) / 2;
+    } else {
+        int band = 4;
+        if (causal) { band = per / g.tiles_n; band = band < 1 ? 1 : (band > g.tiles_m ? g.tiles_m : band); }
+        const int band_tiles = band * g.tiles_n;
+        const int bi = tile / band_tiles, in = tile % band_tiles;
+        const int rows_in_band = min(band, g.tiles_m - bi * band);
+        tm = bi * band + in % rows_in_band; tn = in / rows_in_band;
+        if (causal) tn = g.tiles_n - 1 - tn;
+    }
     const int m0 = tm * BM, n0 = tn * BN;
-    if ((g.flags & TBOA_GEMM_LOWER) && n0 >= m0 + BM) return;
 
     const int z = blockIdx.y, z1 = z / g.batch_inner, z2 = z % g.batch_inner;
     const __hip_bfloat16* A = g.A + z1 * g.sA1 + z2 * g.sA2;
@@ -183,8 +197,10 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     if (q.kseg < 0 || (q.kseg > 0 && (q.K % q.kseg || q.kseg % 8))) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: kseg must divide K and be a multiple of 8");
     a.sA1 = q.strideA; a.sB1 = q.strideB; a.sC1 = q.strideC; a.sA2 = q.strideA2; a.sB2 = q.strideB2; a.sC2 = q.strideC2;
     a.tiles_m = (int)cdiv64(q.M, BM); a.tiles_n = (int)cdiv64(q.N, BN);
-    const long long ntiles = (long long)a.tiles_m * a.tiles_n;
-    if (ntiles > 2147483647LL || q.batch > 65535) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: grid too large");
+    long long ntiles = (long long)a.tiles_m * a.tiles_n;
+    if (q.flags & TBOA_GEMM_LOWER) ntiles = (long long)a.tiles_m * (a.tiles_m + 1) / 2;
+    if (ntiles > 200000000LL || q.batch > 65535) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: grid too large");
+    ntiles = 8 * ((ntiles + 7) / 8);
     const bool timed = ctx->prof_on && q.tag >= 0;
     ProfRec rec{};
     if (timed) {

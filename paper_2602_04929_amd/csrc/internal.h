@@ -21,6 +21,7 @@ struct tboa_ctx {
     int* h_status;       // pinned host mirror
     int prof_on;         // record HIP events around tagged GEMM launches
     std::vector<ProfRec> prof;
+    long long counters[4];   // tboa_counter_id
 };
 
 int tboa_fail(tboa_ctx* ctx, int code, const char* fmt, ...);

@@ -111,6 +111,110 @@ __global__ void grid_argmin_kernel(const double* __restrict__ cost, const double
     z_out[lr * ng + gi] = cand_z[(long long)row * ncand + best];
 }
 
+// ---- two-phase search: approximate costs of all candidates on the bf16 matrix cores, exact fp64 costs of the few
+// candidates within GRID_TAU of the approximate minimum.  delta and H_in are each split into an exact-to-16-bits
+// (hi, lo) bf16 pair and  delta H  ~  hi.hi + lo.hi + hi.lo  is one GEMM over the concatenated axis.
+constexpr int GRID_KS = 6;          // exact re-evaluations per row
+constexpr double GRID_TAU = 2e-3;   // survivors: approximate cost <= (1 + tau) * approximate minimum
+
+typedef __hip_bfloat16 bf16;
+
+// Hcat[b, r, :] = [hi(H[r,:]) | hi(H[r,:]) | lo(H[r,:])]
+__global__ void hcat_kernel(const double* __restrict__ H, bf16* __restrict__ out, int n, long long total) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const long long row = i / n; const int c = (int)(i % n);
+        const float v = (float)H[i];
+        const bf16 hi = __float2bfloat16(v);
+        bf16* o = out + row * 3 * n + c;
+        o[0] = hi; o[n] = hi; o[2 * n] = __float2bfloat16(v - __bfloat162float(hi));
+    }
+}
+
+// Acat[(row, k), :] = [hi(delta) | lo(delta) | hi(delta)], delta as in grid_delta_kernel
+__global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
+                                                               const double* __restrict__ cand_s, const double* __restrict__ cand_z,
+                                                               bf16* __restrict__ Acat) {
+    const int row = blockIdx.y;
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= n) return;
+    const double w = Wk[(long long)row * ldw + c];
+    const double* cs = cand_s + (long long)row * ncand;
+    const double* cz = cand_z + (long long)row * ncand;
+    bf16* out = Acat + (long long)row * ncand * 3 * n + c;
+    for (int k = 0; k < ncand; ++k) {
+        const double s = cs[k], z = cz[k];
+        const float dl = (float)(s * (quant_code(w, s, z, maxq) - z) - w);
+        const bf16 hi = __float2bfloat16(dl);
+        bf16* o = out + (long long)k * 3 * n;
+        o[0] = hi; o[n] = __float2bfloat16(dl - __bfloat162float(hi)); o[2 * n] = hi;
+    }
+}
+
+// cost[i] = sum_c G[i, c] (hi + lo)[i, c], one wavefront per row
+__global__ __launch_bounds__(256) void rowdot_split_kernel(const float* __restrict__ G, const bf16* __restrict__ Acat, long long rows, int n,
+                                                           double* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float* g = G + row * n; const bf16* a = Acat + row * 3 * n;
+    double s = 0.0;
+    for (int c = lane; c < n; c += 64) s += (double)g[c] * ((double)__bfloat162float(a[c]) + (double)__bfloat162float(a[n + c]));
+    s = wave_sum(s);
+    if (lane == 0) out[row] = s;
+}
+
+// per row: the candidates within tau of the approximate minimum, in increasing k (unused slots repeat the first);
+// more than GRID_KS of them raises the overflow flag
+__global__ void grid_select_kernel(const double* __restrict__ cost, int rows, int ncand, double tau, int* __restrict__ sel,
+                                   int* __restrict__ overflow) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    const double* c = cost + (long long)row * ncand;
+    double m = c[0];
+    for (int k = 1; k < ncand; ++k) m = fmin(m, c[k]);
+    const double lim = m + tau * fabs(m);
+    int cnt = 0, first = 0;
+    int* o = sel + (long long)row * GRID_KS;
+    for (int k = 0; k < ncand; ++k)
+        if (c[k] <= lim || !(c[k] == c[k])) {
+            if (cnt == 0) first = k;
+            if (cnt < GRID_KS) o[cnt] = k;
+            ++cnt;
+        }
+    if (cnt > GRID_KS || !(m == m)) atomicAdd(overflow, 1);
+    for (int j = cnt; j < GRID_KS; ++j) o[j] = first;
+}
+
+// exact delta of the selected candidates: DeltaS[(row, j), c]
+__global__ __launch_bounds__(256) void grid_delta_sel_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
+                                                             const double* __restrict__ cand_s, const double* __restrict__ cand_z,
+                                                             const int* __restrict__ sel, double* __restrict__ DeltaS) {
+    const int row = blockIdx.y;
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= n) return;
+    const double w = Wk[(long long)row * ldw + c];
+    for (int j = 0; j < GRID_KS; ++j) {
+        const int k = sel[(long long)row * GRID_KS + j];
+        const double s = cand_s[(long long)row * ncand + k], z = cand_z[(long long)row * ncand + k];
+        DeltaS[((long long)row * GRID_KS + j) * n + c] = s * (quant_code(w, s, z, maxq) - z) - w;
+    }
+}
+
+// lowest exact cost among the selected (lowest k among equals: the slots are in increasing k)
+__global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const int* __restrict__ sel, const double* __restrict__ cand_s,
+                                       const double* __restrict__ cand_z, int rows, int ncand, BlockMap m, int r_off,
+                                       double* __restrict__ s_out, double* __restrict__ z_out, int ng, int gi) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    const double* c = costS + (long long)row * GRID_KS;
+    int best = 0; double bc = c[0];
+    for (int j = 1; j < GRID_KS; ++j) if (c[j] < bc) { bc = c[j]; best = j; }
+    const int k = sel[(long long)row * GRID_KS + best];
+    const long long lr = layer_row(m, r_off + row);
+    s_out[lr * ng + gi] = cand_s[(long long)row * ncand + k];
+    z_out[lr * ng + gi] = cand_z[(long long)row * ncand + k];
+}
+
 // ------------------------------------------------------------------------------------------------ Algorithm 3
 struct SweepArgs {
     double* Wk; int n; int nbr; BlockMap map;
@@ -305,7 +409,8 @@ struct Layer {
     double *W64, *Wt, *Hi, *Hfac, *Uin, *Rd, *P, *Ho, *Hofac, *Uout, *ftmp, *fdinv;
     double *Q64, *s64, *z64;
     double *Wb, *Wk, *Epan, *Wsnap, *E, *S1, *S2, *T;
-    double *cand_s, *cand_z, *Delta, *G, *cost;
+    double *cand_s, *cand_z, *Delta, *G, *cost, *DeltaS, *GS, *costS;
+    __hip_bfloat16* Hcat; int* sel; int fast_grid;
     double *Wbar, *Abar, *Z, *WR, *Cm, *Fm, *dvec, *lossbuf;
     int grid_chunk;     // block rows (shared H_in) or heads (per-head H_in) per grid-search pass
     long long nn;
@@ -324,6 +429,48 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
         const double* Wc = Wrows + (long long)r0 * ldw;
         hipLaunchKernelGGL(grid_candidates_kernel, dim3((rows + 3) / 4), dim3(256), 0, ctx->stream, Wc, ldw, c0, ncols, rows,
                            ncand, L.d->grid_points, L.maxq, L.cand_s, L.cand_z);
+        TB_KERNEL_CHECK(ctx);
+        bool done = false;
+        if (L.fast_grid && c0 == 0 && ncols == L.n) {
+            const int n = L.n;
+            __hip_bfloat16* Acat = (__hip_bfloat16*)L.Delta; float* G32 = (float*)L.G;
+            int* ovf = ctx->d_status + 8;
+            TB_HIP(ctx, hipMemsetAsync(ovf, 0, sizeof(int), ctx->stream));
+            hipLaunchKernelGGL(grid_delta_split_kernel, dim3((n + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, n, ncand, L.maxq,
+                               L.cand_s, L.cand_z, Acat);
+            TB_KERNEL_CHECK(ctx);
+            GemmBf16 a{};
+            a.N = n; a.K = 3 * n; a.alpha = 1.f; a.A = Acat; a.lda = 3LL * n; a.ldb = 3LL * n; a.C = G32; a.ldc = n;
+            a.c_dtype = TBOA_F32; a.accumulate = 0; a.flags = 0; a.tag = TBOA_PROF_GRID;
+            if (ph) { a.M = rows_per_head * ncand; a.batch = nu; a.B = L.Hcat + (long long)u0 * n * 3 * n;
+                      a.strideA = (long long)a.M * 3 * n; a.strideB = (long long)n * 3 * n; a.strideC = (long long)a.M * n; }
+            else { a.M = rows * ncand; a.batch = 1; a.B = L.Hcat; }
+            TB_TRY(gemm_bf16_nt(ctx, a));
+            const long long crow = (long long)rows * ncand;
+            hipLaunchKernelGGL(rowdot_split_kernel, dim3((unsigned)((crow + 3) / 4)), dim3(256), 0, ctx->stream, G32, Acat, crow, n, L.cost);
+            hipLaunchKernelGGL(grid_select_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.cost, rows, ncand, GRID_TAU, L.sel, ovf);
+            hipLaunchKernelGGL(grid_delta_sel_kernel, dim3((n + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, n, ncand, L.maxq,
+                               L.cand_s, L.cand_z, L.sel, L.DeltaS);
+            TB_KERNEL_CHECK(ctx);
+            GemmF64 g{};
+            g.N = n; g.K = n; g.alpha = 1.0; g.beta = 0.0; g.A = L.DeltaS; g.sam = n; g.sak = 1; g.sbk = n; g.sbn = 1; g.C = L.GS; g.ldc = n;
+            if (ph) { g.M = rows_per_head * GRID_KS; g.batch = nu; g.B = L.Hi + (long long)u0 * L.nn;
+                      g.strideA = (long long)g.M * n; g.strideB = L.nn; g.strideC = g.strideA; }
+            else { g.M = rows * GRID_KS; g.batch = 1; g.B = L.Hi; }
+            TB_TRY(gemm_f64(ctx, g));
+            const long long srow = (long long)rows * GRID_KS;
+            hipLaunchKernelGGL(rowdot_kernel, dim3((unsigned)((srow + 3) / 4)), dim3(256), 0, ctx->stream, L.GS, (long long)n, L.DeltaS,
+                               (long long)n, srow, n, L.costS);
+            hipLaunchKernelGGL(grid_argmin_sel_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.costS, L.sel, L.cand_s, L.cand_z,
+                               rows, ncand, map, r0, L.s64, L.z64, L.ng, gi);
+            TB_KERNEL_CHECK(ctx);
+            TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 8, ovf, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+            TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+            done = (ctx->h_status[8] == 0);
+            ++ctx->counters[TBOA_CTR_GRID_PASSES];
+            if (!done) ++ctx->counters[TBOA_CTR_GRID_FALLBACKS];     // too many near-minimal candidates in some row: evaluate all exactly
+        }
+        if (done) continue;
         hipLaunchKernelGGL(grid_delta_kernel, dim3((ncols + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, c0, ncols, ncand,
                            L.maxq, L.cand_s, L.cand_z, L.Delta);
         TB_KERNEL_CHECK(ctx);
@@ -375,6 +522,11 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     // eq. 3 for H_in (and H_out)
     TB_TRY(launch_f32_to_f64_damp(ctx, n, nhin, H_in, d->damp, L.Hi));
     TB_HIP(ctx, hipMemcpyAsync(L.Hfac, L.Hi, nhin * nn * sizeof(double), hipMemcpyDeviceToDevice, st));
+    if (L.fast_grid) {
+        long long tot = nhin * nn, gb = (tot + 255) / 256; if (gb > 32768) gb = 32768;
+        hipLaunchKernelGGL(hcat_kernel, dim3((unsigned)gb), dim3(256), 0, st, L.Hi, L.Hcat, n, tot);
+        TB_KERNEL_CHECK(ctx);
+    }
     TB_TRY(chol_inv_upper_f64(ctx, n, nhin, L.Hfac, L.Uin, L.ftmp, L.fdinv));
     if (R) {   // Algorithm 3 line 2: P = ((R U^T) * M_U) U
         TB_TRY(launch_cvt_f32_to_f64(ctx, R, L.Rd, nhin * nn));
@@ -563,6 +715,7 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
         if (L.nhin > 1) { int c = (int)(cap / (per_row * max_rows_block)); L.grid_chunk = c < 1 ? 1 : (c > nh ? nh : c); }
         else { int c = (int)(cap / per_row); const int tot = nh * max_rows_block; L.grid_chunk = c < 1 ? 1 : (c > tot ? tot : c); }
     }
+    L.fast_grid = (!d->group && n % 8 == 0 && n >= 256) ? 1 : 0;   // per-row grids of wide layers: two-phase search
     const size_t grows = (size_t)L.grid_chunk * (L.nhin > 1 ? (d->adaptive_grid ? blk : dh) : 1);
     const int fmax = n > dh ? n : dh;
     const int fb = (L.nhin > nh) ? L.nhin : nh;
@@ -584,6 +737,11 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
         L.T = H_out ? ar.get<double>((size_t)nh * dh * d->block) : nullptr;
         L.cand_s = ar.get<double>(grows * L.ncand); L.cand_z = ar.get<double>(grows * L.ncand); L.cost = ar.get<double>(grows * L.ncand);
         L.Delta = ar.get<double>(grows * L.ncand * L.gsz); L.G = ar.get<double>(grows * L.ncand * L.gsz);
+        if (L.fast_grid) {
+            L.DeltaS = ar.get<double>(grows * GRID_KS * n); L.GS = ar.get<double>(grows * GRID_KS * n);
+            L.costS = ar.get<double>(grows * GRID_KS); L.sel = ar.get<int>(grows * GRID_KS);
+            L.Hcat = ar.get<__hip_bfloat16>((size_t)L.nhin * L.nn * 3);
+        }
         L.Wbar = ar.get<double>(wn); L.Abar = ar.get<double>(wn); L.Z = ar.get<double>(wn);
         L.WR = R ? ar.get<double>(wn) : nullptr;
         L.Cm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr; L.Fm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
