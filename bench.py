@@ -113,6 +113,7 @@ def main():
         "kernels": kernels,
         "losses": {k: out[k]["loss"] for k in ("q", "k", "v", "o")},
         "workspace_gib": ctx.workspace_bytes() / 2 ** 30,
+        "grid_search": {"two_phase_passes": ctx.counter(0), "passes_fully_exact": ctx.counter(1), "rows_fully_exact": ctx.counter(2)},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

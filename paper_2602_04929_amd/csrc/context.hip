@@ -38,8 +38,8 @@ extern "C" int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream) {
     c->ws = nullptr; c->ws_bytes = 0;
     c->d_status = nullptr; c->h_status = nullptr; c->prof_on = 0;
     for (auto& v : c->counters) v = 0;
-    if (hipMalloc(&c->d_status, 64 * sizeof(int)) != hipSuccess ||
-        hipHostMalloc(&c->h_status, 64 * sizeof(int)) != hipSuccess) {
+    if (hipMalloc(&c->d_status, 256 * sizeof(int)) != hipSuccess ||
+        hipHostMalloc(&c->h_status, 256 * sizeof(int)) != hipSuccess) {
         if (c->d_status) (void)hipFree(c->d_status);
         delete c;
         return TBOA_ENOMEM;

@@ -164,7 +164,9 @@ __global__ __launch_bounds__(256) void rowdot_split_kernel(const float* __restri
 }
 
 // per row: the candidates within tau of the approximate minimum, in increasing k (unused slots repeat the first);
-// more than GRID_KS of them raises the overflow flag
+// a row with more than GRID_KS of them is appended to the overflow list (overflow[0] = count, then row numbers)
+constexpr int GRID_MAX_OVF = 96;    // rows per pass that may be re-evaluated exactly one by one
+
 __global__ void grid_select_kernel(const double* __restrict__ cost, int rows, int ncand, double tau, int* __restrict__ sel,
                                    int* __restrict__ overflow) {
     const int row = blockIdx.x * blockDim.x + threadIdx.x;
@@ -181,7 +183,7 @@ __global__ void grid_select_kernel(const double* __restrict__ cost, int rows, in
             if (cnt < GRID_KS) o[cnt] = k;
             ++cnt;
         }
-    if (cnt > GRID_KS || !(m == m)) atomicAdd(overflow, 1);
+    if (cnt > GRID_KS || !(m == m)) { const int i = atomicAdd(overflow, 1); if (i < GRID_MAX_OVF) overflow[1 + i] = row; }
     for (int j = cnt; j < GRID_KS; ++j) o[j] = first;
 }
 
@@ -434,8 +436,9 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
         if (L.fast_grid && c0 == 0 && ncols == L.n) {
             const int n = L.n;
             __hip_bfloat16* Acat = (__hip_bfloat16*)L.Delta; float* G32 = (float*)L.G;
-            int* ovf = ctx->d_status + 8;
+            int* ovf = ctx->d_status + 8;   // [0] count, [1..] rows
             TB_HIP(ctx, hipMemsetAsync(ovf, 0, sizeof(int), ctx->stream));
+            static_assert(9 + GRID_MAX_OVF <= 256, "status words");
             hipLaunchKernelGGL(grid_delta_split_kernel, dim3((n + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, n, ncand, L.maxq,
                                L.cand_s, L.cand_z, Acat);
             TB_KERNEL_CHECK(ctx);
@@ -464,11 +467,29 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             hipLaunchKernelGGL(grid_argmin_sel_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.costS, L.sel, L.cand_s, L.cand_z,
                                rows, ncand, map, r0, L.s64, L.z64, L.ng, gi);
             TB_KERNEL_CHECK(ctx);
-            TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 8, ovf, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+            TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 8, ovf, (1 + GRID_MAX_OVF) * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
             TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
-            done = (ctx->h_status[8] == 0);
             ++ctx->counters[TBOA_CTR_GRID_PASSES];
-            if (!done) ++ctx->counters[TBOA_CTR_GRID_FALLBACKS];     // too many near-minimal candidates in some row: evaluate all exactly
+            const int novf = ctx->h_status[8];
+            done = novf <= GRID_MAX_OVF;
+            if (!done) ++ctx->counters[TBOA_CTR_GRID_FALLBACKS];
+            for (int i = 0; done && i < novf; ++i) {
+                // a row with many near-minimal candidates: every candidate exactly, for this row alone
+                const int r = ctx->h_status[9 + i];
+                ++ctx->counters[TBOA_CTR_GRID_EXACT_ROWS];
+                hipLaunchKernelGGL(grid_delta_kernel, dim3((n + 255) / 256, 1), dim3(256), 0, ctx->stream, Wc + (long long)r * ldw, ldw, 0, n,
+                                   ncand, L.maxq, L.cand_s + (long long)r * ncand, L.cand_z + (long long)r * ncand, L.Delta);
+                TB_KERNEL_CHECK(ctx);
+                GemmF64 e{};
+                e.M = ncand; e.N = n; e.K = n; e.alpha = 1.0; e.beta = 0.0; e.A = L.Delta; e.sam = n; e.sak = 1;
+                e.B = L.Hi + (ph ? (long long)(u0 + r / rows_per_head) * L.nn : 0); e.sbk = n; e.sbn = 1; e.C = L.G; e.ldc = n; e.batch = 1;
+                TB_TRY(gemm_f64(ctx, e));
+                hipLaunchKernelGGL(rowdot_kernel, dim3((ncand + 3) / 4), dim3(256), 0, ctx->stream, L.G, (long long)n, L.Delta, (long long)n,
+                                   (long long)ncand, n, L.cost);
+                hipLaunchKernelGGL(grid_argmin_kernel, dim3(1), dim3(64), 0, ctx->stream, L.cost, L.cand_s + (long long)r * ncand,
+                                   L.cand_z + (long long)r * ncand, 1, ncand, map, r0 + r, L.s64, L.z64, L.ng, gi);
+                TB_KERNEL_CHECK(ctx);
+            }
         }
         if (done) continue;
         hipLaunchKernelGGL(grid_delta_kernel, dim3((ncols + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, c0, ncols, ncand,

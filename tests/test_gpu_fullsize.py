@@ -116,7 +116,7 @@ def test_quantize_layer_sampled_heads(full, layer):
         frac = compare_layer(sub, dict(want, loss=want["loss"]), label="%s head %d" % (name, h))
         print("  %s head %d: codes identical %.4f%%, loss %.6g vs %.6g" % (name, h, 100 * frac, sub["loss"], want["loss"]), flush=True)
     full[name] = got
-    print("  grid-search passes %d, fallbacks to exact evaluation %d" % (ctx.counter(0), ctx.counter(1)), flush=True)
+    print("  grid-search passes %d, fully exact passes %d, fully exact rows %d" % (ctx.counter(0), ctx.counter(1), ctx.counter(2)), flush=True)
 
 
 def test_quantize_out_proj_sampled_rows(full):

@@ -1,0 +1,69 @@
+"""The C-ABI library loads and exports every symbol the header declares (no GPU needed, no compute calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "turboboa.h")
+LIB = os.path.join(ROOT, "paper_2602_04929_amd", "libturboboa.so")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tboa_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.fail("libturboboa.so is not built: run __graft_entry__.build()")
+    return ctypes.CDLL(LIB)
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for must in ("tboa_create", "tboa_destroy", "tboa_last_error", "tboa_build_hessians", "tboa_build_hessian_out_proj",
+                 "tboa_quantize_layer", "tboa_act_fakequant", "tboa_chol_inv_upper", "tboa_gemm_f64", "tboa_gemm_bf16_nt"):
+        assert must in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    missing = [n for n in declared_functions() if not hasattr(lib, n)]
+    assert not missing, missing
+
+
+def test_binding_signatures_cover_the_header():
+    import paper_2602_04929_amd as tb
+    src = open(os.path.join(ROOT, "paper_2602_04929_amd", "binding.py")).read()
+    assert tb.LIB_PATH == LIB
+    for n in declared_functions():
+        assert '"%s"' % n in src, "binding.py has no signature for " + n
+
+
+def test_null_context_is_rejected_without_touching_a_device(lib):
+    lib.tboa_last_error.restype = ctypes.c_char_p
+    assert lib.tboa_last_error(None) == b"null context"
+    assert lib.tboa_workspace_bytes(None) == 0
+    lib.tboa_counter.restype = ctypes.c_int64
+    assert lib.tboa_counter(None, 0) == -1
+    assert lib.tboa_profile_enable(None, 1) == -1
+    assert lib.tboa_create(None, 0, None) == -1
+
+
+def test_descriptor_structs_match_the_header():
+    """Field order of the ctypes mirrors equals the order in the header's typedefs."""
+    import paper_2602_04929_amd as tb
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    for cname, cls in (("tboa_attn_desc", tb.AttnDesc), ("tboa_layer_desc", tb.LayerDesc)):
+        body = re.search(r"typedef struct \{([^}]*)\} %s;" % cname, text).group(1)
+        fields = []
+        for decl in body.split(";"):
+            decl = decl.strip()
+            if decl:
+                ctype, names = decl.split(None, 1)
+                fields += [(n.strip(), ctype) for n in names.split(",")]
+        got = [(n, {"c_int": "int", "c_double": "double", "c_float": "float"}[t.__name__]) for n, t in cls._fields_]
+        assert got == fields
