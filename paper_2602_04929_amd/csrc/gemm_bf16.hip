@@ -6,12 +6,15 @@
 //
 // Workgroup: 256 threads = 4 wavefronts (2 x 2) on a 256 x 256 x 64 tile; each wavefront owns 128 x 128 as 4 x 4
 // MFMA tiles of 32 x 32 (256 fp32 accumulators per lane, one workgroup per CU).  Per 16-wide k-step a wavefront reads
-// 8 fragments of 16 bytes per lane from LDS for 16 MFMAs.  LDS rows are 128 bytes (64 bf16) and the 16-byte chunks of
-// a row are XOR-swizzled with the row number so that fragment reads and tile writes are bank-conflict free.
+// 8 fragments of 16 bytes per lane from LDS for 16 MFMAs.  LDS rows are 128 bytes (64 bf16); the LDS has 64 banks
+// (256 bytes), so two consecutive rows fill one bank line and a 128-bit access is served 16 lanes at a time: the
+// 16-byte chunks of a row are XOR-swizzled with (row / 2) % 8, which makes the 16 rows read by 16 consecutive lanes
+// (and the two rows written by them) hit 16 different bank groups (measured: SQ_LDS_BANK_CONFLICT = 0).
 // Global -> register -> LDS software pipeline over two LDS stages, one barrier per 64-wide k-step.
 // Tiles are numbered so that the eight XCDs (workgroups are dealt to them round-robin) each work on a compact
 // band of the output and share operand panels through their own L2.
 #include "internal.h"
+#include <stdlib.h>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -49,12 +52,12 @@ __device__ __forceinline__ void store_tile(__hip_bfloat16* __restrict__ lds, con
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
         const int r = rr + 32 * p;
-        *(uint4*)(lds + r * BK + ((c ^ (r & 7)) * 8)) = reg[p];
+        *(uint4*)(lds + r * BK + ((c ^ ((r >> 1) & 7)) * 8)) = reg[p];
     }
 }
 
 __device__ __forceinline__ bf16x8 read_frag(const __hip_bfloat16* __restrict__ lds, int row, int chunk) {
-    return *(const bf16x8*)(lds + row * BK + ((chunk ^ (row & 7)) * 8));
+    return *(const bf16x8*)(lds + row * BK + ((chunk ^ ((row >> 1) & 7)) * 8));
 }
 
 __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
@@ -171,6 +174,222 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
         }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Fast path (K a multiple of 32): same tiling, but global memory is copied straight into LDS by
+// global_load_lds_dwordx4 (no staging registers, no ds_write) through a ring of 4 stages of 32 k each, so that
+// loads for stage kt+3 are in flight while stage kt is multiplied: three stage-times (about 3 x 1024 MFMA cycles) to
+// cover HBM latency, against one with the register-staged pipeline above.
+// An LDS-direct wavefront load writes lane p's 16 bytes at base + 16 p: a 1 KB block = 16 rows x 64 bytes.  Lane p
+// therefore fetches, for row p / 4, the logical chunk (p % 4) ^ ((row / 4) % 4): the XOR swizzle (four rows fill one
+// 256-byte bank line here) is applied on the global side.  Rows beyond M or N are clamped (their products are never stored).
+constexpr int FK = 32, NS = 4;
+constexpr int STAGE_ELEMS = (BM + BN) * FK;     // bf16 elements per stage: A tile then B tile
+
+// One stage = 8 LDS-direct loads per wavefront (4 blocks of the A tile, 4 of the B tile).  The per-lane byte offsets
+// are loop-invariant; the tile's k position lives in the uniform base pointers; M0 carries the LDS address of the
+// 1 KB block.  Written as inline assembly so that the compiler does not pair every later LDS read with a wait for
+// ALL outstanding loads (it cannot tell that the ring slot being filled is not the one being read); the explicit
+// s_waitcnt vmcnt(N) + barrier in the main loop is the synchronisation.
+__device__ __forceinline__ void lds_direct_16(unsigned voff, const char* base, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" ::"v"(voff), "s"(lds_addr), "s"(base) : "memory", "m0");
+}
+
+__device__ __forceinline__ bf16x8 read_frag32(const __hip_bfloat16* __restrict__ t, int row, int chunk) {
+    return *(const bf16x8*)(t + row * FK + ((chunk ^ ((row >> 2) & 3)) * 8));
+}
+
+// WAVES = 8: 512 threads, two wavefronts per SIMD, each owning 128 x 64 of the tile (128 accumulators, at most 256
+// registers).  With one wavefront per SIMD every cycle it spends issuing an LDS read or an LDS-direct load is a cycle
+// in which no MFMA is issued; with two, one wavefront's issue stalls fall into the shadow of the other's MFMAs.
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
+    constexpr int TJ = (WAVES == 8) ? 2 : 4;         // 32-wide MFMA tile columns per wavefront
+    constexpr int LPW = 16 / WAVES;                  // 1 KB blocks of the A tile (and of the B tile) per wavefront and stage
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    __hip_bfloat16* ring = (__hip_bfloat16*)smem;     // [NS][STAGE_ELEMS]
+
+    const bool lower = g.flags & TBOA_GEMM_LOWER, causal = g.flags & TBOA_GEMM_CAUSAL_K;
+    const int ntiles = lower ? g.tiles_m * (g.tiles_m + 1) / 2 : g.tiles_m * g.tiles_n;
+    const int per = (ntiles + 7) / 8;
+    const int loc = blockIdx.x >> 3;
+    const int tile = (blockIdx.x & 7) * per + loc;
+    if (loc >= per || tile >= ntiles) return;
+    int tm, tn;
+    if (lower) {
+        tm = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
+        while ((tm + 1) * (tm + 2) / 2 <= tile) ++tm;
+        while (tm * (tm + 1) / 2 > tile) --tm;
+        tn = tile - tm * (tm + 1) / 2;
+    } else {
+        int band = 4;
+        if (causal) { band = per / g.tiles_n; band = band < 1 ? 1 : (band > g.tiles_m ? g.tiles_m : band); }
+        const int band_tiles = band * g.tiles_n;
+        const int bi = tile / band_tiles, in = tile % band_tiles;
+        const int rows_in_band = min(band, g.tiles_m - bi * band);
+        tm = bi * band + in % rows_in_band; tn = in / rows_in_band;
+        if (causal) tn = g.tiles_n - 1 - tn;
+    }
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int z = blockIdx.y, z1 = z / g.batch_inner, z2 = z % g.batch_inner;
+    const __hip_bfloat16* A = g.A + z1 * g.sA1 + z2 * g.sA2;
+    const __hip_bfloat16* B = g.B + z1 * g.sB1 + z2 * g.sB2;
+
+    const int seg_len = g.kseg > 0 ? g.kseg : g.K;
+    const int nseg = g.kseg > 0 ? g.K / g.kseg : 1;
+    int kend = seg_len;
+    if (causal) kend = min(kend, n0 + BN);
+    const int nk_seg = kend / FK;                  // kend is a multiple of 32 on this path
+    const int nk = nk_seg * nseg;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave / (WAVES / 2)) * 128, wn = (wave % (WAVES / 2)) * (32 * TJ);
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    f32x16 acc[4][TJ];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // loop-invariant per-lane byte offsets of this wavefront's loads of a stage, relative to the tile's first row
+    unsigned offA[LPW], offB[LPW];
+    {
+        const int pr = lane >> 2, ph = lane & 3;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int row = 16 * (wave * LPW + i) + pr;
+            const int lc = ph ^ ((row >> 2) & 3);
+            offA[i] = (unsigned)(((long long)min(row, g.M - 1 - m0) * g.lda + lc * 8) * 2);
+            offB[i] = (unsigned)(((long long)min(row, g.N - 1 - n0) * g.ldb + lc * 8) * 2);
+        }
+    }
+    const char* Arow = (const char*)(A + (long long)m0 * g.lda);
+    const char* Brow = (const char*)(B + (long long)n0 * g.ldb);
+    auto k_of = [&](int kt) { const int sg = kt / nk_seg; return sg * seg_len + (kt - sg * nk_seg) * FK; };
+    const unsigned ring_lds = (unsigned)(unsigned long long)((__attribute__((address_space(3))) void*)ring);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    auto issue = [&](int kt, int slot) {
+        const long long kb = 2LL * k_of(kt);
+        const unsigned st = ring_lds + (unsigned)(slot * STAGE_ELEMS * 2);
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const unsigned blk = (unsigned)(wave_s * LPW + i) * 1024u;
+            lds_direct_16(offA[i], Arow + kb, st + blk);
+            lds_direct_16(offB[i], Brow + kb, st + (unsigned)(BM * FK * 2) + blk);
+        }
+    };
+    // Fragments are double-buffered in registers at k-step granularity: while the MFMAs of one k-step run, the
+    // fragments of the next k-step are read from LDS; LDS-direct loads are issued one by one between MFMAs.
+    bf16x8 fa[2][4], fb[2][TJ];
+#define TB_LOAD_FRAGS(SET, SLOT, KS)                                                                        \
+    {                                                                                                       \
+        const __hip_bfloat16* a_s = ring + (SLOT) * STAGE_ELEMS;                                            \
+        const __hip_bfloat16* b_s = a_s + BM * FK;                                                          \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) fa[SET][i] = read_frag32(a_s, wm + 32 * i + l32, 2 * (KS) + lh); \
+        _Pragma("unroll") for (int i = 0; i < TJ; ++i) fb[SET][i] = read_frag32(b_s, wn + 32 * i + l32, 2 * (KS) + lh); \
+    }
+#define TB_MMA(SET)                                                                                         \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                           \
+        _Pragma("unroll") for (int jj = 0; jj < TJ; ++jj)                                                   \
+            acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[SET][i], fb[SET][jj], acc[i][jj], 0, 0, 0);
+#define TB_INTERLEAVE_DS                                                                                    \
+    _Pragma("unroll") for (int r_ = 0; r_ < 4 + TJ; ++r_) {                                                 \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                  \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                  \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                  \
+    }
+    // Stage kt sits in ring slot SLOT, its k-step 0 in register set 0.  Phase 1: read k-step 1 into set 1, multiply
+    // set 0.  Phase 2: make stage kt+1 visible (its loads were issued three stages ago), read k-step 0 of stage kt+1
+    // into set 0, multiply set 1 and, between the MFMAs, refill slot SLOT (every wavefront has finished reading it)
+    // with stage kt+NS.
+#define TB_STAGE_STEADY(KT, SLOT, NEXTSLOT)                                                                 \
+    {                                                                                                       \
+        TB_LOAD_FRAGS(1, SLOT, 1)                                                                           \
+        TB_MMA(0)                                                                                           \
+        TB_INTERLEAVE_DS                                                                                    \
+        if (WAVES == 8) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");                         \
+        else asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");                                   \
+        __syncthreads();                                                                                    \
+        TB_LOAD_FRAGS(0, NEXTSLOT, 0)                                                                       \
+        {                                                                                                   \
+            const long long kb_ = 2LL * k_of((KT) + NS);                                                    \
+            const char* pa_ = Arow + kb_; const char* pb_ = Brow + kb_;                                     \
+            const unsigned st_ = ring_lds + (unsigned)((SLOT) * STAGE_ELEMS * 2);                           \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
+                _Pragma("unroll") for (int jj = 0; jj < TJ; jj += 2) {                                      \
+                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][jj], acc[i][jj], 0, 0, 0); \
+                    acc[i][jj + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][jj + 1], acc[i][jj + 1], 0, 0, 0); \
+                    const int q_ = (i * TJ + jj) / 2;              /* 0 .. 2 LPW - 1 */                       \
+                    const unsigned blk_ = (unsigned)(wave_s * LPW + q_ / 2) * 1024u;                        \
+                    __builtin_amdgcn_sched_barrier(0);                                                      \
+                    if (q_ % 2 == 0) lds_direct_16(offA[q_ / 2], pa_, st_ + blk_);                          \
+                    else lds_direct_16(offB[q_ / 2], pb_, st_ + (unsigned)(BM * FK * 2) + blk_);            \
+                    __builtin_amdgcn_sched_barrier(0);                                                      \
+                }                                                                                           \
+            }                                                                                               \
+        }                                                                                                   \
+    }
+#define TB_STAGE_TAIL(KT, SLOT, NEXTSLOT)                                                                   \
+    {                                                                                                       \
+        TB_LOAD_FRAGS(1, SLOT, 1)                                                                           \
+        TB_MMA(0)                                                                                           \
+        if ((KT) + 1 < nk) {                                                                                \
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                     \
+            __syncthreads();                                                                                \
+            if ((KT) + NS < nk) issue((KT) + NS, SLOT);                                                     \
+            TB_LOAD_FRAGS(0, NEXTSLOT, 0)                                                                   \
+        }                                                                                                   \
+        TB_MMA(1)                                                                                           \
+    }
+
+    if (nk > 0) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            if (s < nk) issue(s, s);
+        if (nk < NS) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (WAVES == 8) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+        __syncthreads();
+        TB_LOAD_FRAGS(0, 0, 0)
+        int kt = 0;
+        // steady state, unrolled over the ring so that slot numbers are constants: the loads of stages kt+2 and kt+3 may
+        // stay in flight while stage kt+1 is awaited
+        for (; kt + NS + 3 < nk; kt += 4) {
+            TB_STAGE_STEADY(kt, 0, 1)
+            TB_STAGE_STEADY(kt + 1, 1, 2)
+            TB_STAGE_STEADY(kt + 2, 2, 3)
+            TB_STAGE_STEADY(kt + 3, 3, 0)
+        }
+        for (; kt < nk; ++kt) TB_STAGE_TAIL(kt, kt % NS, (kt + 1) % NS)
+    }
+#undef TB_STAGE_STEADY
+#undef TB_STAGE_TAIL
+#undef TB_MMA
+#undef TB_LOAD_FRAGS
+#undef TB_INTERLEAVE_DS
+
+    const long long coff = z1 * g.sC1 + z2 * g.sC2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lh + (v & 3);
+            if (row >= g.M) continue;
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) {
+                const int col = n0 + wn + 32 * j + l32;
+                if (col >= g.N) continue;
+                const long long idx = coff + (long long)row * g.ldc + col;
+                float r = g.alpha * acc[i][j][v];
+                if (g.c_bf16) ((__hip_bfloat16*)g.C)[idx] = __float2bfloat16(r);
+                else { float* c = (float*)g.C + idx; if (g.accumulate) r += *c; *c = r; }
+            }
+        }
+}
+
 }  // namespace
 
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
@@ -184,10 +403,14 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     if ((q.flags & TBOA_GEMM_LOWER) && q.M != q.N) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: LOWER needs M == N");
     static bool attr_set = false;
     const int smem = 2 * (BM + BN) * BK * (int)sizeof(__hip_bfloat16);
+    const int smem_fast = NS * STAGE_ELEMS * (int)sizeof(__hip_bfloat16);
     if (!attr_set) {
         TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
         attr_set = true;
     }
+    const bool fast = (q.kseg > 0 ? q.kseg : q.K) % FK == 0 && q.K > 0 && !getenv("TBOA_GEMM_GENERIC");
     Args a;
     a.M = q.M; a.N = q.N; a.K = q.K; a.alpha = q.alpha;
     a.A = q.A; a.lda = q.lda; a.B = q.B; a.ldb = q.ldb; a.C = q.C; a.ldc = q.ldc;
@@ -214,7 +437,10 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
         rec.flops = 2.0 * mnk * nseg * q.batch;
         TB_HIP(ctx, hipEventRecord(rec.a, ctx->stream));
     }
-    hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((unsigned)ntiles, (unsigned)q.batch), dim3(256), smem, ctx->stream, a);
+    static const int waves = getenv("TBOA_GEMM_WAVES") ? atoi(getenv("TBOA_GEMM_WAVES")) : 8;
+    if (fast && waves == 8) hipLaunchKernelGGL(gemm_bf16_nt_fast_kernel<8>, dim3((unsigned)ntiles, (unsigned)q.batch), dim3(512), smem_fast, ctx->stream, a);
+    else if (fast) hipLaunchKernelGGL(gemm_bf16_nt_fast_kernel<4>, dim3((unsigned)ntiles, (unsigned)q.batch), dim3(256), smem_fast, ctx->stream, a);
+    else hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((unsigned)ntiles, (unsigned)q.batch), dim3(256), smem, ctx->stream, a);
     TB_KERNEL_CHECK(ctx);
     if (timed) { TB_HIP(ctx, hipEventRecord(rec.b, ctx->stream)); ctx->prof.push_back(rec); }
     return 0;

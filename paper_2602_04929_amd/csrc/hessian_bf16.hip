@@ -79,13 +79,13 @@ __global__ void split_hilo_kernel(const float* __restrict__ in, bf16* __restrict
 // V^T fp32 [rows, G*L] -> per-sequence segments of length L: (hi, lo) of V^T in segments 0, 1 and, when the
 // full-precision V~^T is given, V^T - V~^T in segment 2 and V~^T in segment 3
 __global__ void vt_segments_kernel(const float* __restrict__ in, const float* __restrict__ in_fp, bf16* __restrict__ out, int rows,
-                                   int G, int L, int nseg) {
+                                   int G, int L, int nseg, long long ld) {
     const long long tot = (long long)rows * G * L;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
         const long long row = i / ((long long)G * L); const int s = (int)((i / L) % G), t = (int)(i % L);
         const float v = in[i];
         const bf16 h = __float2bfloat16(v);
-        bf16* o = out + ((row * G + s) * nseg) * L + t;
+        bf16* o = out + row * ld + ((long long)s * nseg) * L + t;
         o[0] = h; o[L] = __float2bfloat16(v - __bfloat162float(h));
         if (in_fp) { const float w = in_fp[i]; o[2 * L] = __float2bfloat16(v - w); o[3 * L] = __float2bfloat16(w); }
     }
@@ -138,6 +138,10 @@ __global__ void bcast_heads_kernel(const double* __restrict__ src, float* __rest
         dst[i] = (float)src[(h / rep) * per + e];
     }
 }
+
+// Row pitches that are multiples of a few KB put every row of a tile into the same memory channel; 256 extra
+// elements per row spread them (measured: +10..20 % on the GEMMs).
+constexpr int PADE = 256;
 
 inline unsigned g1(long long n) { long long g = (n + 255) / 256; return (unsigned)(g < 1 ? 1 : (g > 32768 ? 32768 : g)); }
 
@@ -231,22 +235,22 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     const bool fp = X_fp != nullptr, rv = fp && R_v;
     int G = d->seq_chunk > 0 ? d->seq_chunk : 8; if (G > D.S) G = D.S;
     const int nsg = rv ? 2 : 1, nsx = rv ? 3 : 1, splits = pick_splits(D.S);   // segments of P / of the transposed chunk
-    const long long dd = (long long)dm * dm, hh = (long long)dh * dh;
+    const long long dd = (long long)dm * dm, hh = (long long)dh * dh, TP = (long long)T + PADE;
     bf16 *XT, *dXh, *dXl, *Qh, *Kh, *Qhf, *Khf, *P, *XcT, *YT, *dYT;
     float *part, *Qf, *Kf, *Sc, *Scf;
     double *Hin64, *Wq64, *Wk64, *Wo64, *Tq, *Tk, *Ho;
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
-        XT = ar.get<bf16>((size_t)dm * T);
-        dXh = fp ? ar.get<bf16>((size_t)dm * T) : nullptr; dXl = fp ? ar.get<bf16>((size_t)dm * T) : nullptr;
+        XT = ar.get<bf16>((size_t)dm * TP);
+        dXh = fp ? ar.get<bf16>((size_t)dm * TP) : nullptr; dXl = fp ? ar.get<bf16>((size_t)dm * TP) : nullptr;
         part = ar.get<float>((size_t)splits * dd);
         Qf = ar.get<float>((size_t)G * L * dq); Kf = ar.get<float>((size_t)G * L * dkv);
         Qh = ar.get<bf16>((size_t)G * L * dq * 3); Kh = ar.get<bf16>((size_t)G * L * dkv * 3);
         Qhf = rv ? ar.get<bf16>((size_t)G * L * dq * 3) : nullptr; Khf = rv ? ar.get<bf16>((size_t)G * L * dkv * 3) : nullptr;
         Sc = ar.get<float>((size_t)Hq * L * L); Scf = rv ? ar.get<float>((size_t)Hq * L * L) : nullptr;
-        P = ar.get<bf16>((size_t)Hq * L * nsg * L);
-        XcT = ar.get<bf16>((size_t)dm * G * nsx * L);
-        YT = ar.get<bf16>((size_t)Hq * dm * G * L); dYT = rv ? ar.get<bf16>((size_t)Hq * dm * G * L) : nullptr;
+        P = ar.get<bf16>((size_t)Hq * L * (nsg * L + PADE));
+        XcT = ar.get<bf16>((size_t)dm * (G * nsx * L + PADE));
+        YT = ar.get<bf16>((size_t)Hkv * dm * (rep * G * L + PADE)); dYT = rv ? ar.get<bf16>((size_t)Hkv * dm * (rep * G * L + PADE)) : nullptr;
         Hin64 = ar.get<double>((size_t)dd); Wq64 = ar.get<double>((size_t)dq * dm); Wk64 = ar.get<double>((size_t)dkv * dm);
         Wo64 = ar.get<double>((size_t)dm * dq); Tq = ar.get<double>((size_t)dq * dm); Tk = ar.get<double>((size_t)dkv * dm);
         Ho = ar.get<double>((size_t)Hkv * hh);
@@ -254,9 +258,9 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     }
     hipStream_t st = ctx->stream;
     // ---- H_in and R for W_Q / W_K
-    TB_TRY(transpose(D, X, fp ? X_fp : nullptr, dm, T, dm, XT, fp ? dXh : nullptr, dXl, T));
-    TB_TRY(gram_splitk(D, dm, XT, nullptr, XT, T, T, 1.0, 1, part, Hin_qk));
-    if (fp && R_qk) TB_TRY(gram_splitk(D, dm, dXh, dXl, XT, T, T, d->alpha, 0, part, R_qk));
+    TB_TRY(transpose(D, X, fp ? X_fp : nullptr, dm, T, dm, XT, fp ? dXh : nullptr, dXl, TP));
+    TB_TRY(gram_splitk(D, dm, XT, nullptr, XT, TP, T, 1.0, 1, part, Hin_qk));
+    if (fp && R_qk) TB_TRY(gram_splitk(D, dm, dXh, dXl, XT, TP, T, d->alpha, 0, part, R_qk));
     // ---- H_out: K_g^T K_g = W_K,g H_in W_K,g^T ; sum_h Q_h^T Q_h ; sum_h W_out,h^T W_out,h   (fp64)
     TB_TRY(launch_cvt_f32_to_f64(ctx, Hin_qk, Hin64, dd));
     TB_TRY(launch_cvt_to_f64(ctx, Wq, TBOA_BF16, Wq64, (int64_t)dq * dm));
@@ -297,7 +301,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     for (int s0 = 0; s0 < D.S; s0 += G) {
         const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
         const long long t0 = (long long)s0 * L;
-        const long long ldx = (long long)Gc * nsx * L, ldy = (long long)rep * Gc * L;
+        const long long ldx = (long long)Gc * nsx * L + PADE, ky = (long long)rep * Gc * L, ldy = ky + PADE, ldp = (long long)nsg * L + PADE;
         TB_TRY(project_qk(D, X + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qh, Kh));
         if (rv) TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
         for (int sl = 0; sl < Gc; ++sl) {   // XcT[:, sl, :, :] = X_s^T | (X_s - X~_s)^T | X~_s^T
@@ -314,15 +318,15 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
             // P = [A | A - A~];  Y^T = X_s^T A^T;  (Y - Y~)^T = [dX_s^T | X~_s^T] [A | A - A~]^T  since  A X - A~ X~ = A dX + (A - A~) X~
             TB_TRY(scores(D, Qh, Kh, sl, Sc));
             if (rv) TB_TRY(scores(D, Qhf, Khf, sl, Scf));
-            TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, (long long)nsg * L, 1, L));
-            GemmBf16 y = nt(dm, L, L, 1.f, XcT + (long long)sl * nsx * L, ldx, P, (long long)nsg * L, YT + (long long)sl * L, ldy, TBOA_BF16, 0, cflag);
+            TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, ldp, 1, L));
+            GemmBf16 y = nt(dm, L, L, 1.f, XcT + (long long)sl * nsx * L, ldx, P, ldp, YT + (long long)sl * L, ldy, TBOA_BF16, 0, cflag);
             y.batch = Hq; y.batch_inner = rep; y.tag = TBOA_PROF_AX;
-            y.strideB = (long long)rep * L * nsg * L; y.strideB2 = (long long)L * nsg * L;
+            y.strideB = (long long)rep * L * ldp; y.strideB2 = (long long)L * ldp;
             y.strideC = (long long)dm * ldy; y.strideC2 = (long long)Gc * L;
             TB_TRY(gemm_bf16_nt(ctx, y));
             if (rv) { y.A = XcT + ((long long)sl * nsx + 1) * L; y.K = 2 * L; y.kseg = L; y.C = dYT + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, y)); }
         }
-        GemmBf16 h = nt(dm, dm, (int)ldy, 1.f, YT, ldy, YT, ldy, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER);
+        GemmBf16 h = nt(dm, dm, (int)ky, 1.f, YT, ldy, YT, ldy, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER);
         h.batch = Hkv; h.strideA = (long long)dm * ldy; h.strideB = h.strideA; h.strideC = dd; h.tag = TBOA_PROF_HV_SYRK;
         TB_TRY(gemm_bf16_nt(ctx, h));
         if (rv) { h.tag = TBOA_PROF_RV; h.A = dYT; h.C = R_v; h.flags = 0; h.alpha = (float)d->alpha; TB_TRY(gemm_bf16_nt(ctx, h)); }
@@ -340,6 +344,7 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
     const bool fp = X_fp && R_o;
     int G = d->seq_chunk > 0 ? d->seq_chunk : 8; if (G > D.S) G = D.S;
     const int nsg = fp ? 4 : 2, nsp = fp ? 3 : 2, splits = pick_splits(D.S);   // segments of V^T / of P
+    const long long TP = (long long)T + PADE, ldp = (long long)nsp * L + PADE;
     bf16 *Wqh, *Wql, *Wkh, *Wkl, *Wvh, *Wvl, *Qh, *Kh, *Qhf, *Khf, *P, *VTc, *OT, *dOT;
     float *Qf, *Kf, *VT32, *VT32f, *Sc, *Scf, *part;
     for (int pass = 0; pass < 2; ++pass) {
@@ -351,9 +356,9 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         VT32f = fp ? ar.get<float>((size_t)dkv * G * L) : nullptr; Scf = fp ? ar.get<float>((size_t)Hq * L * L) : nullptr;
         Qh = ar.get<bf16>((size_t)G * L * dq * 3); Kh = ar.get<bf16>((size_t)G * L * dkv * 3);
         Qhf = fp ? ar.get<bf16>((size_t)G * L * dq * 3) : nullptr; Khf = fp ? ar.get<bf16>((size_t)G * L * dkv * 3) : nullptr;
-        Sc = ar.get<float>((size_t)Hq * L * L); P = ar.get<bf16>((size_t)Hq * L * nsp * L);
-        VTc = ar.get<bf16>((size_t)dkv * G * nsg * L);
-        OT = ar.get<bf16>((size_t)dq * T); dOT = fp ? ar.get<bf16>((size_t)dq * T) : nullptr;
+        Sc = ar.get<float>((size_t)Hq * L * L); P = ar.get<bf16>((size_t)Hq * L * ldp);
+        VTc = ar.get<bf16>((size_t)dkv * (G * nsg * L + PADE));
+        OT = ar.get<bf16>((size_t)dq * TP); dOT = fp ? ar.get<bf16>((size_t)dq * TP) : nullptr;
         part = ar.get<float>((size_t)splits * dq * dq);
         if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
     }
@@ -366,7 +371,7 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
     const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
     for (int s0 = 0; s0 < D.S; s0 += G) {
         const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
-        const long long t0 = (long long)s0 * L, ldv = (long long)Gc * nsg * L;
+        const long long t0 = (long long)s0 * L, ldv = (long long)Gc * nsg * L + PADE;
         const bf16* Xc = X + t0 * dm;
         // V'^T = Wv_deq Xc^T (fp32, from the (hi, lo) weight pair) and the full-precision V~^T = Wv X~c^T
         TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvh, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 0, 0)));
@@ -376,26 +381,26 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wv, dm, X_fp + t0 * dm, dm, VT32f, (long long)Gc * L, TBOA_F32, 0, 0)));
             TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
         }
-        hipLaunchKernelGGL(vt_segments_kernel, dim3(g1((long long)dkv * Gc * L)), dim3(256), 0, st, VT32, fp ? VT32f : nullptr, VTc, dkv, Gc, L, nsg);
+        hipLaunchKernelGGL(vt_segments_kernel, dim3(g1((long long)dkv * Gc * L)), dim3(256), 0, st, VT32, fp ? VT32f : nullptr, VTc, dkv, Gc, L, nsg, ldv);
         TB_KERNEL_CHECK(ctx);
         for (int sl = 0; sl < Gc; ++sl) {
             // V^T segments [V'hi | V'lo | V' - V~ | V~], P = [A' | A' | A' - A~]:
             // O^T_h = [V'hi | V'lo] [A' | A']^T ;  (O - O~)^T_h = [V' - V~ | V~] [A' | A' - A~]^T
             TB_TRY(scores(D, Qh, Kh, sl, Sc));
             if (fp) TB_TRY(scores(D, Qhf, Khf, sl, Scf));
-            TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, (long long)nsp * L, 2, 2 * L));
-            GemmBf16 o = nt(dh, L, 2 * L, 1.f, VTc + (long long)sl * nsg * L, ldv, P, (long long)nsp * L, OT + t0 + (long long)sl * L, T,
+            TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, ldp, 2, 2 * L));
+            GemmBf16 o = nt(dh, L, 2 * L, 1.f, VTc + (long long)sl * nsg * L, ldv, P, ldp, OT + t0 + (long long)sl * L, TP,
                             TBOA_BF16, 0, cflag);
             o.kseg = L; o.batch = Hq; o.batch_inner = rep;
             o.strideA = (long long)dh * ldv; o.strideA2 = 0;
-            o.strideB = (long long)rep * L * nsp * L; o.strideB2 = (long long)L * nsp * L;
-            o.strideC = (long long)rep * dh * T; o.strideC2 = (long long)dh * T;
+            o.strideB = (long long)rep * L * ldp; o.strideB2 = (long long)L * ldp;
+            o.strideC = (long long)rep * dh * TP; o.strideC2 = (long long)dh * TP;
             TB_TRY(gemm_bf16_nt(ctx, o));
             if (fp) { o.A = VTc + ((long long)sl * nsg + 2) * L; o.B = P + L; o.C = dOT + t0 + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, o)); }
         }
     }
-    TB_TRY(gram_splitk(D, dq, OT, nullptr, OT, T, T, 1.0, 1, part, Hin_o));
-    if (fp) TB_TRY(gram_splitk(D, dq, dOT, nullptr, OT, T, T, d->alpha, 0, part, R_o));
+    TB_TRY(gram_splitk(D, dq, OT, nullptr, OT, TP, T, 1.0, 1, part, Hin_o));
+    if (fp) TB_TRY(gram_splitk(D, dq, dOT, nullptr, OT, TP, T, d->alpha, 0, part, R_o));
     return 0;
 }
 
