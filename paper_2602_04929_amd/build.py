@@ -18,9 +18,14 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=o
          "-Wno-unused-result", "-Wno-unknown-warning-option"]
 
 
+# Per-file flags.  gemm_f64: keep the 128 fp64 accumulators in ordinary VGPRs (the kernel fits in 256 registers); with the
+# default AGPR form the compiler copies all of them between the two register files on every k-step.
+EXTRA = {"gemm_f64.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _compile(src):
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA.get(os.path.basename(src), []), "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))

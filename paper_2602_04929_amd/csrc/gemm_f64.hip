@@ -14,7 +14,7 @@ namespace {
 
 constexpr int BM = 128, BN = 128, BK = 16;
 constexpr int PKC = BK + 1;   // pitch of a [row][k] tile (k-contiguous operand); odd -> conflict-free 16-lane reads
-constexpr int PMC = BM;       // pitch of a [k][row] tile (row-contiguous operand)
+constexpr int PMC = BM + 16;  // pitch of a [k][row] tile (row-contiguous operand): k and k+1 land 32 of the 64 LDS banks apart
 constexpr int TILE = (BM * PKC > BK * PMC) ? BM * PKC : BK * PMC;
 
 struct Args {

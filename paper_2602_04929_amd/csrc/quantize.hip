@@ -556,6 +556,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
         GemmF64 a{};
         a.M = n; a.N = n; a.K = n; a.alpha = 1.0; a.beta = 0.0;
         a.A = L.Rd; a.sam = n; a.sak = 1; a.B = L.Uin; a.sbk = 1; a.sbn = n; a.klo_n = 1;   // U[c, k] = 0 for k < c
+        a.skip_lower = 1;   // only the part above the diagonal survives the mask below
         a.C = L.Hfac; a.ldc = n; a.batch = nhin; a.strideA = nn; a.strideB = nn; a.strideC = nn;
         TB_TRY(gemm_f64(ctx, a));
         TB_TRY(launch_strict_upper_f64(ctx, L.Hfac, n, nhin));
