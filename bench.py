@@ -41,6 +41,33 @@ def cpu_baseline(blk, cfg, hessians, budget_note):
                       "in W_Q, W_K, W_V, W_O; CPU Hessian build excluded%s" % (dh, cfg.d_model, dt, heads_equiv, budget_note)}
 
 
+def roofline_probe(ctx, cfg, torch):
+    """The command the HBM-traffic counter runs are made with: one plain copy of 1 GiB (a kernel of known traffic, to scale
+    the counters), then ONE launch of the dominant kernel in the launch shape the benchmark times: H_in^V += Y^T (Y^T)^T for
+    all KV heads over a chunk of 8 sequences (lower tiles, accumulating into fp32), operands at the benchmark's row pitch."""
+    import paper_2602_04929_amd as tb
+    rep, G = cfg.n_q_heads // cfg.n_kv_heads, 8
+    ky = rep * G * cfg.seq_len
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    src = torch.randn(1 << 28, generator=g, device="cuda")                    # 1 GiB
+    dst = torch.empty_like(src)
+    YT = torch.empty(cfg.n_kv_heads, cfg.d_model, ky + 256, dtype=torch.bfloat16, device="cuda")
+    for h in range(cfg.n_kv_heads):
+        YT[h] = torch.randn(cfg.d_model, ky + 256, generator=g, device="cuda").to(torch.bfloat16)
+    Hv = torch.zeros(cfg.n_kv_heads, cfg.d_model, cfg.d_model, device="cuda")
+    torch.cuda.synchronize()
+    torch.mul(src, 1.0, out=dst)                                              # reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    Y = YT[:, :, :ky]
+    ctx.gemm_bf16_nt(Y, Y, C_out=Hv, accumulate=True, flags=tb.GEMM_LOWER)
+    torch.cuda.synchronize()
+    n = cfg.d_model
+    alg = cfg.n_kv_heads * (n * ky * 2 + 2 * 4 * n * (n + 1) // 2)            # Y^T read once, lower half of H read + written
+    print(json.dumps({"probe": "copy 1 GiB, then gemm_bf16_nt LOWER accumulate", "copy_bytes_read": src.numel() * 4,
+                      "copy_bytes_written": src.numel() * 4, "gemm_batch": cfg.n_kv_heads, "gemm_M": n, "gemm_K": ky,
+                      "gemm_algorithmic_bytes": alg}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +77,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-R", action="store_true", help="first-block setting: no upstream deviation (R = 0)")
     ap.add_argument("--n-seqs", type=int, default=0, help="override the number of calibration sequences (profiling runs)")
+    ap.add_argument("--roofline-probe", action="store_true",
+                    help="run one plain 1 GiB copy and one launch of the dominant kernel in the benchmark's launch shape, nothing else "
+                         "(the command for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (heads would shard across GPUs, see DESIGN.md); use --gpus 1", file=sys.stderr)
@@ -67,6 +97,11 @@ def main():
     if args.n_seqs:
         cfg = synth.scaled(cfg, n_seqs=args.n_seqs)
     torch.cuda.set_device(0)
+    if args.roofline_probe:
+        ctx = tb.Context()
+        roofline_probe(ctx, cfg, torch)
+        ctx.close()
+        return
     blk = synth.make_block(cfg, seed=0, device="cuda:0")
     ctx = tb.Context()
     use_R = not args.no_R

@@ -154,15 +154,16 @@ class Context:
         return C_out
 
     def gemm_bf16_nt(self, A, B, out_dtype=torch.float32, alpha=1.0, C_out=None, accumulate=False, flags=0):
-        """C = alpha A B^T (+ C) for bf16 A [.., M, K], B [.., N, K]."""
+        """C = alpha A B^T (+ C) for bf16 A [.., M, K], B [.., N, K]; rows may be pitched (views of a wider tensor)."""
         batched = A.dim() == 3
         A3 = A if batched else A[None]; B3 = B if batched else B[None]
-        _dev(A3, torch.bfloat16); _dev(B3, torch.bfloat16)
+        for t in (A3, B3):
+            assert t.is_cuda and t.dtype == torch.bfloat16 and t.stride(2) == 1, "expected K-contiguous bf16 CUDA tensors"
         bs, M, K = A3.shape; N = B3.shape[1]
         if C_out is None:
             C_out = torch.zeros((bs, M, N) if batched else (M, N), dtype=out_dtype, device=A.device)
-        self._check(_lib.tboa_gemm_bf16_nt(self._h, M, N, K, alpha, _ptr(A3), K, _ptr(B3), K, _ptr(C_out), N,
-                                           _dtype_code(C_out), int(accumulate), flags, bs, M * K, N * K, M * N))
+        self._check(_lib.tboa_gemm_bf16_nt(self._h, M, N, K, alpha, _ptr(A3), A3.stride(1), _ptr(B3), B3.stride(1), _ptr(C_out), N,
+                                           _dtype_code(C_out), int(accumulate), flags, bs, A3.stride(0), B3.stride(0), M * N))
         return C_out
 
     def chol_inv_upper(self, H, damp=0.0):

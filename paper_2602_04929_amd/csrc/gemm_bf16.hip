@@ -32,8 +32,25 @@ struct Args {
     int c_bf16, accumulate, flags;
     int batch_inner, kseg;
     long long sA1, sA2, sB1, sB2, sC1, sC2;
-    int tiles_m, tiles_n;
+    const int* tile_order;      // (tm << 16 | tn) of the tiles of one batch entry, in launch order
+    int ntiles;                 // tiles per batch entry
+    long long nitems, per;      // batch * ntiles work items; per = items per XCD
 };
+
+// Work item of this workgroup.  Workgroups are dealt to the eight XCDs round-robin by their linear number, so workgroup
+// w runs on XCD w % 8.  XCD x takes the contiguous run [x * per, (x + 1) * per) of the item list, which is batch-major:
+// with a batch of 8 or more an XCD works through whole batch entries one after the other, its 32 CUs on 32 consecutive
+// tiles of the host-built order (a compact block of the output sharing few operand panels through that XCD's L2).
+__device__ __forceinline__ bool work_item(const Args& g, int& z, int& tm, int& tn) {
+    const long long loc = blockIdx.x >> 3;
+    const long long item = (long long)(blockIdx.x & 7) * g.per + loc;
+    if (loc >= g.per || item >= g.nitems) return false;
+    z = (int)(item / g.ntiles);
+    const int packed = g.tile_order[(int)(item - (long long)z * g.ntiles)];
+    tm = __builtin_amdgcn_readfirstlane(packed >> 16); tn = __builtin_amdgcn_readfirstlane(packed & 0xffff);
+    z = __builtin_amdgcn_readfirstlane(z);
+    return true;
+}
 
 __device__ __forceinline__ void load_tile(const __hip_bfloat16* __restrict__ base, long long ld, int r0, int k0, int r_lim, int k_lim,
                                           uint4 (&reg)[8]) {
@@ -65,34 +82,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
     __hip_bfloat16* As = (__hip_bfloat16*)smem;                 // [2][BM*BK]
     __hip_bfloat16* Bs = As + 2 * BM * BK;                      // [2][BN*BK]
 
-    // Tile numbering.  Workgroup w runs on XCD w % 8 (round-robin dispatch), so XCD x takes the contiguous run
-    // [x*per, (x+1)*per) of the tile list and its workgroups share operand panels through that XCD's L2.  The list has
-    // only the tiles that do work (the lower triangle of a symmetric product), and for a causal contraction a run
-    // holds every tile column the same number of times, long columns first: all XCDs get equal work.
-    const bool lower = g.flags & TBOA_GEMM_LOWER, causal = g.flags & TBOA_GEMM_CAUSAL_K;
-    const int ntiles = lower ? g.tiles_m * (g.tiles_m + 1) / 2 : g.tiles_m * g.tiles_n;
-    const int per = (ntiles + 7) / 8;
-    const int loc = blockIdx.x >> 3;
-    const int tile = (blockIdx.x & 7) * per + loc;
-    if (loc >= per || tile >= ntiles) return;
-    int tm, tn;
-    if (lower) {
-        tm = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
-        while ((tm + 1) * (tm + 2) / 2 <= tile) ++tm;
-        while (tm * (tm + 1) / 2 > tile) --tm;
-        tn = tile - tm * (tm + 1) / 2;
-    } else {
-        int band = 4;
-        if (causal) { band = per / g.tiles_n; band = band < 1 ? 1 : (band > g.tiles_m ? g.tiles_m : band); }
-        const int band_tiles = band * g.tiles_n;
-        const int bi = tile / band_tiles, in = tile % band_tiles;
-        const int rows_in_band = min(band, g.tiles_m - bi * band);
-        tm = bi * band + in % rows_in_band; tn = in / rows_in_band;
-        if (causal) tn = g.tiles_n - 1 - tn;
-    }
+    int z, tm, tn;
+    if (!work_item(g, z, tm, tn)) return;
     const int m0 = tm * BM, n0 = tn * BN;
 
-    const int z = blockIdx.y, z1 = z / g.batch_inner, z2 = z % g.batch_inner;
+    const int z1 = z / g.batch_inner, z2 = z % g.batch_inner;
     const __hip_bfloat16* A = g.A + z1 * g.sA1 + z2 * g.sA2;
     const __hip_bfloat16* B = g.B + z1 * g.sB1 + z2 * g.sB2;
 
@@ -182,7 +176,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
 // An LDS-direct wavefront load writes lane p's 16 bytes at base + 16 p: a 1 KB block = 16 rows x 64 bytes.  Lane p
 // therefore fetches, for row p / 4, the logical chunk (p % 4) ^ ((row / 4) % 4): the XOR swizzle (four rows fill one
 // 256-byte bank line here) is applied on the global side.  Rows beyond M or N are clamped (their products are never stored).
-constexpr int FK = 32, NS = 4;
+constexpr int FK = 32;
 constexpr int STAGE_ELEMS = (BM + BN) * FK;     // bf16 elements per stage: A tile then B tile
 
 // One stage = 8 LDS-direct loads per wavefront (4 blocks of the A tile, 4 of the B tile).  The per-lane byte offsets
@@ -201,37 +195,23 @@ __device__ __forceinline__ bf16x8 read_frag32(const __hip_bfloat16* __restrict__
 // WAVES = 8: 512 threads, two wavefronts per SIMD, each owning 128 x 64 of the tile (128 accumulators, at most 256
 // registers).  With one wavefront per SIMD every cycle it spends issuing an LDS read or an LDS-direct load is a cycle
 // in which no MFMA is issued; with two, one wavefront's issue stalls fall into the shadow of the other's MFMAs.
-template <int WAVES>
+template <int N>
+__device__ __forceinline__ void wait_loads_but() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(N) : "memory"); }
+
+// NS: stages in the LDS ring (NS - 1 of them in flight while one is multiplied)
+template <int WAVES, int NS>
 __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
     constexpr int TJ = (WAVES == 8) ? 2 : 4;         // 32-wide MFMA tile columns per wavefront
     constexpr int LPW = 16 / WAVES;                  // 1 KB blocks of the A tile (and of the B tile) per wavefront and stage
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     __hip_bfloat16* ring = (__hip_bfloat16*)smem;     // [NS][STAGE_ELEMS]
 
-    const bool lower = g.flags & TBOA_GEMM_LOWER, causal = g.flags & TBOA_GEMM_CAUSAL_K;
-    const int ntiles = lower ? g.tiles_m * (g.tiles_m + 1) / 2 : g.tiles_m * g.tiles_n;
-    const int per = (ntiles + 7) / 8;
-    const int loc = blockIdx.x >> 3;
-    const int tile = (blockIdx.x & 7) * per + loc;
-    if (loc >= per || tile >= ntiles) return;
-    int tm, tn;
-    if (lower) {
-        tm = (int)((sqrtf(8.0f * (float)tile + 1.0f) - 1.0f) * 0.5f);
-        while ((tm + 1) * (tm + 2) / 2 <= tile) ++tm;
-        while (tm * (tm + 1) / 2 > tile) --tm;
-        tn = tile - tm * (tm + 1) / 2;
-    } else {
-        int band = 4;
-        if (causal) { band = per / g.tiles_n; band = band < 1 ? 1 : (band > g.tiles_m ? g.tiles_m : band); }
-        const int band_tiles = band * g.tiles_n;
-        const int bi = tile / band_tiles, in = tile % band_tiles;
-        const int rows_in_band = min(band, g.tiles_m - bi * band);
-        tm = bi * band + in % rows_in_band; tn = in / rows_in_band;
-        if (causal) tn = g.tiles_n - 1 - tn;
-    }
+    const bool causal = g.flags & TBOA_GEMM_CAUSAL_K;
+    int z, tm, tn;
+    if (!work_item(g, z, tm, tn)) return;
     const int m0 = tm * BM, n0 = tn * BN;
 
-    const int z = blockIdx.y, z1 = z / g.batch_inner, z2 = z % g.batch_inner;
+    const int z1 = z / g.batch_inner, z2 = z % g.batch_inner;
     const __hip_bfloat16* A = g.A + z1 * g.sA1 + z2 * g.sA2;
     const __hip_bfloat16* B = g.B + z1 * g.sB1 + z2 * g.sB2;
 
@@ -268,11 +248,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
     }
     const char* Arow = (const char*)(A + (long long)m0 * g.lda);
     const char* Brow = (const char*)(B + (long long)n0 * g.ldb);
-    auto k_of = [&](int kt) { const int sg = kt / nk_seg; return sg * seg_len + (kt - sg * nk_seg) * FK; };
+    // byte offset along k of the next stage to be issued (stages are issued strictly in order), kept incrementally
+    long long koff_next = 0; int kin_next = 0;
+    auto advance = [&]() { kin_next += FK; koff_next += 2 * FK; if (kin_next == kend) { kin_next = 0; koff_next += 2LL * (seg_len - kend); } };
     const unsigned ring_lds = (unsigned)(unsigned long long)((__attribute__((address_space(3))) void*)ring);
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-    auto issue = [&](int kt, int slot) {
-        const long long kb = 2LL * k_of(kt);
+    auto issue = [&](int slot) {
+        const long long kb = koff_next;
+        advance();
         const unsigned st = ring_lds + (unsigned)(slot * STAGE_ELEMS * 2);
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
@@ -296,28 +279,27 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
         _Pragma("unroll") for (int jj = 0; jj < TJ; ++jj)                                                   \
             acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[SET][i], fb[SET][jj], acc[i][jj], 0, 0, 0);
 #define TB_INTERLEAVE_DS                                                                                    \
-    _Pragma("unroll") for (int r_ = 0; r_ < 4 + TJ; ++r_) {                                                 \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                  \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                  \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                  \
-    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4 + TJ, 0);                                                 \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4 * TJ, 0);
     // Stage kt sits in ring slot SLOT, its k-step 0 in register set 0.  Phase 1: read k-step 1 into set 1, multiply
     // set 0.  Phase 2: make stage kt+1 visible (its loads were issued three stages ago), read k-step 0 of stage kt+1
     // into set 0, multiply set 1 and, between the MFMAs, refill slot SLOT (every wavefront has finished reading it)
     // with stage kt+NS.
 #define TB_STAGE_STEADY(KT, SLOT, NEXTSLOT)                                                                 \
     {                                                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        const char* pa_ = Arow + koff_next; const char* pb_ = Brow + koff_next;                             \
+        const unsigned st_ = ring_lds + (unsigned)((SLOT) * STAGE_ELEMS * 2);                               \
+        advance();                                                                                          \
         TB_LOAD_FRAGS(1, SLOT, 1)                                                                           \
         TB_MMA(0)                                                                                           \
         TB_INTERLEAVE_DS                                                                                    \
-        if (WAVES == 8) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");                         \
-        else asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");                                   \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        wait_loads_but<(NS - 2) * 2 * LPW>();                                                               \
         __syncthreads();                                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
         TB_LOAD_FRAGS(0, NEXTSLOT, 0)                                                                       \
         {                                                                                                   \
-            const long long kb_ = 2LL * k_of((KT) + NS);                                                    \
-            const char* pa_ = Arow + kb_; const char* pb_ = Brow + kb_;                                     \
-            const unsigned st_ = ring_lds + (unsigned)((SLOT) * STAGE_ELEMS * 2);                           \
             _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
                 _Pragma("unroll") for (int jj = 0; jj < TJ; jj += 2) {                                      \
                     acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][jj], acc[i][jj], 0, 0, 0); \
@@ -339,7 +321,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
         if ((KT) + 1 < nk) {                                                                                \
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                     \
             __syncthreads();                                                                                \
-            if ((KT) + NS < nk) issue((KT) + NS, SLOT);                                                     \
+            if ((KT) + NS < nk) issue(SLOT);                                                     \
             TB_LOAD_FRAGS(0, NEXTSLOT, 0)                                                                   \
         }                                                                                                   \
         TB_MMA(1)                                                                                           \
@@ -348,20 +330,17 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
     if (nk > 0) {
 #pragma unroll
         for (int s = 0; s < NS; ++s)
-            if (s < nk) issue(s, s);
-        if (nk < NS) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else if (WAVES == 8) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+            if (s < nk) issue(s);
+        if (nk < NS) wait_loads_but<0>();
+        else wait_loads_but<(NS - 1) * 2 * LPW>();
         __syncthreads();
         TB_LOAD_FRAGS(0, 0, 0)
         int kt = 0;
         // steady state, unrolled over the ring so that slot numbers are constants: the loads of stages kt+2 and kt+3 may
         // stay in flight while stage kt+1 is awaited
-        for (; kt + NS + 3 < nk; kt += 4) {
-            TB_STAGE_STEADY(kt, 0, 1)
-            TB_STAGE_STEADY(kt + 1, 1, 2)
-            TB_STAGE_STEADY(kt + 2, 2, 3)
-            TB_STAGE_STEADY(kt + 3, 3, 0)
+        for (; kt + 2 * NS - 1 < nk; kt += NS) {
+#pragma unroll
+            for (int u = 0; u < NS; ++u) TB_STAGE_STEADY(kt + u, u, (u + 1) % NS)
         }
         for (; kt < nk; ++kt) TB_STAGE_TAIL(kt, kt % NS, (kt + 1) % NS)
     }
@@ -390,6 +369,34 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
         }
 }
 
+// Launch order of the output tiles of one batch entry, built once per (tile counts, flags) and kept on the device.
+// 32 consecutive tiles run side by side on one XCD, so the order walks compact blocks: row bands of 8 tile rows,
+// column by column inside a band (a column's tiles share the B panel, a band's rows the 8 A panels).  A symmetric
+// product lists only the tiles on or below the diagonal.  With a causal contraction limit the k-range grows with the
+// column, so a band takes its columns from the longest to the shortest (the short ones fill the tail of the launch).
+int tile_order(tboa_ctx* ctx, int tiles_m, int tiles_n, int flags, const int** dev, int* count) {
+    for (const TileOrder& t : ctx->tile_orders)
+        if (t.tiles_m == tiles_m && t.tiles_n == tiles_n && t.flags == flags) { *dev = t.dev; *count = t.count; return 0; }
+    const bool lower = flags & TBOA_GEMM_LOWER, causal = flags & TBOA_GEMM_CAUSAL_K;
+    const int band = (causal && !lower) ? 16 : 8;
+    std::vector<int> h;
+    for (int m0 = 0; m0 < tiles_m; m0 += band) {
+        const int m1 = m0 + band < tiles_m ? m0 + band : tiles_m;
+        for (int c = 0; c < tiles_n; ++c) {
+            const int tn = (causal && !lower) ? tiles_n - 1 - c : c;
+            for (int tm = m0; tm < m1; ++tm)
+                if (!lower || tn <= tm) h.push_back((tm << 16) | tn);
+        }
+    }
+    TileOrder t{tiles_m, tiles_n, flags, nullptr, (int)h.size()};
+    TB_HIP(ctx, hipMalloc(&t.dev, h.size() * sizeof(int)));
+    hipError_t e = hipMemcpy(t.dev, h.data(), h.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(t.dev); return tboa_fail(ctx, TBOA_EHIP, "tile order upload: %s", hipGetErrorString(e)); }
+    ctx->tile_orders.push_back(t);
+    *dev = t.dev; *count = t.count;
+    return 0;
+}
+
 }  // namespace
 
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
@@ -403,11 +410,12 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     if ((q.flags & TBOA_GEMM_LOWER) && q.M != q.N) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: LOWER needs M == N");
     static bool attr_set = false;
     const int smem = 2 * (BM + BN) * BK * (int)sizeof(__hip_bfloat16);
-    const int smem_fast = NS * STAGE_ELEMS * (int)sizeof(__hip_bfloat16);
+    const int smem_fast = 4 * STAGE_ELEMS * (int)sizeof(__hip_bfloat16), smem_fast5 = 5 * STAGE_ELEMS * (int)sizeof(__hip_bfloat16);
     if (!attr_set) {
         TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
-        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<4, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8, 5>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast5));
         attr_set = true;
     }
     const bool fast = (q.kseg > 0 ? q.kseg : q.K) % FK == 0 && q.K > 0 && !getenv("TBOA_GEMM_GENERIC");
@@ -419,11 +427,13 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     a.kseg = q.kseg;
     if (q.kseg < 0 || (q.kseg > 0 && (q.K % q.kseg || q.kseg % 8))) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: kseg must divide K and be a multiple of 8");
     a.sA1 = q.strideA; a.sB1 = q.strideB; a.sC1 = q.strideC; a.sA2 = q.strideA2; a.sB2 = q.strideB2; a.sC2 = q.strideC2;
-    a.tiles_m = (int)cdiv64(q.M, BM); a.tiles_n = (int)cdiv64(q.N, BN);
-    long long ntiles = (long long)a.tiles_m * a.tiles_n;
-    if (q.flags & TBOA_GEMM_LOWER) ntiles = (long long)a.tiles_m * (a.tiles_m + 1) / 2;
-    if (ntiles > 200000000LL || q.batch > 65535) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: grid too large");
-    ntiles = 8 * ((ntiles + 7) / 8);
+    const int tiles_m = (int)cdiv64(q.M, BM), tiles_n = (int)cdiv64(q.N, BN);
+    if (tiles_m > 32767 || tiles_n > 32767) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: more than 32767 tiles along one axis");
+    TB_TRY(tile_order(ctx, tiles_m, tiles_n, q.flags & (TBOA_GEMM_LOWER | TBOA_GEMM_CAUSAL_K), &a.tile_order, &a.ntiles));
+    a.nitems = (long long)a.ntiles * q.batch;
+    a.per = (a.nitems + 7) / 8;
+    if (a.per > 200000000LL) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: grid too large");
+    const unsigned nwg = (unsigned)(8 * a.per);
     const bool timed = ctx->prof_on && q.tag >= 0;
     ProfRec rec{};
     if (timed) {
@@ -438,9 +448,11 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
         TB_HIP(ctx, hipEventRecord(rec.a, ctx->stream));
     }
     static const int waves = getenv("TBOA_GEMM_WAVES") ? atoi(getenv("TBOA_GEMM_WAVES")) : 8;
-    if (fast && waves == 8) hipLaunchKernelGGL(gemm_bf16_nt_fast_kernel<8>, dim3((unsigned)ntiles, (unsigned)q.batch), dim3(512), smem_fast, ctx->stream, a);
-    else if (fast) hipLaunchKernelGGL(gemm_bf16_nt_fast_kernel<4>, dim3((unsigned)ntiles, (unsigned)q.batch), dim3(256), smem_fast, ctx->stream, a);
-    else hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((unsigned)ntiles, (unsigned)q.batch), dim3(256), smem, ctx->stream, a);
+    static const int ring = getenv("TBOA_GEMM_RING") ? atoi(getenv("TBOA_GEMM_RING")) : 4;
+    if (fast && waves == 8 && ring == 5) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<8, 5>), dim3(nwg), dim3(512), smem_fast5, ctx->stream, a);
+    else if (fast && waves == 8) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<8, 4>), dim3(nwg), dim3(512), smem_fast, ctx->stream, a);
+    else if (fast) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<4, 4>), dim3(nwg), dim3(256), smem_fast, ctx->stream, a);
+    else hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(nwg), dim3(256), smem, ctx->stream, a);
     TB_KERNEL_CHECK(ctx);
     if (timed) { TB_HIP(ctx, hipEventRecord(rec.b, ctx->stream)); ctx->prof.push_back(rec); }
     return 0;

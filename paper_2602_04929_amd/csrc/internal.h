@@ -11,6 +11,8 @@
 
 struct ProfRec { hipEvent_t a, b; int tag; double flops; };
 
+struct TileOrder { int tiles_m, tiles_n, flags; int* dev; int count; };   // gemm_bf16: launch order of the output tiles
+
 struct tboa_ctx {
     int device;
     hipStream_t stream;
@@ -22,6 +24,7 @@ struct tboa_ctx {
     int prof_on;         // record HIP events around tagged GEMM launches
     std::vector<ProfRec> prof;
     long long counters[4];   // tboa_counter_id
+    std::vector<TileOrder> tile_orders;   // device tables owned by the context
 };
 
 int tboa_fail(tboa_ctx* ctx, int code, const char* fmt, ...);
