@@ -15,6 +15,18 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_bf16_hv_syrk_llama2-7b_hbm_traffic.txt")
+
+
+def measured_traffic(cfg_name):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary of
+    `bench.py --roofline-probe` (counters cannot be read from inside the timed run); None for other workloads."""
+    if cfg_name != "llama2-7b" or not os.path.exists(TRAFFIC_FILE):
+        return None
+    for line in open(TRAFFIC_FILE):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
 
 
 def cpu_baseline(blk, cfg, hessians, budget_note):
@@ -126,9 +138,10 @@ def main():
     ctx.profile(False)
     dom = prof["hv_syrk"]
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel (H_in^V += Y^T Y, lower tiles)", "achieved": achieved,
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_nt_fast_kernel (H_in^V += Y^T Y, lower tiles)", "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "avg_launch_ms": dom["ms"] / max(1, dom["launches"]), "launches": dom["launches"], "traffic": None}
+                "avg_launch_ms": dom["ms"] / max(1, dom["launches"]), "launches": dom["launches"], "traffic": measured_traffic(cfg.name if not args.n_seqs else ""),
+                "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy)"}
     kernels = {k: {"ms_per_step": v["ms"] / args.steps, "launches_per_step": v["launches"] // args.steps,
                    "tflops": (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["ms"] > 0 else 0.0} for k, v in prof.items()}
     mfma_ms = sum(v["ms"] for v in prof.values()) / args.steps

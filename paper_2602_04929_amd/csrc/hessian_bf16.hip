@@ -120,6 +120,63 @@ __global__ __launch_bounds__(256) void softmax_bf16_kernel(const float* __restri
     }
 }
 
+// Same result layout as softmax_bf16_kernel for rows of at most 256 * NCH scores (L a multiple of 4): the row is read
+// once with 16-byte loads and kept in registers (lane l holds scores 256 c + 4 l .. + 3 of chunk c), each exponential
+// is taken once, and the probabilities leave as 8-byte stores.
+template <int NCH>
+__global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __restrict__ S, const float* __restrict__ S2, int L, int causal,
+                                                                bf16* __restrict__ P, long long ldp, long long head_stride, int copies, int dcol) {
+    const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= L) return;
+    const long long so = ((long long)blockIdx.y * L + t) * L;
+    const float* s = S + so; const float* s2 = S2 ? S2 + so : nullptr;
+    bf16* p = P + blockIdx.y * head_stride + (long long)t * ldp;
+    const int kend = causal ? t + 1 : L;
+    int kz = ((kend + 255) / 256) * 256; if (kz > L) kz = L;
+    float v[NCH][4], w[NCH][4];
+    float m = -INFINITY, m2 = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int k = c * 256 + lane * 4;
+        float4 a = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY), b = a;
+        if (k < kz) { a = *(const float4*)(s + k); if (s2) b = *(const float4*)(s2 + k); }
+        v[c][0] = a.x; v[c][1] = a.y; v[c][2] = a.z; v[c][3] = a.w;
+        w[c][0] = b.x; w[c][1] = b.y; w[c][2] = b.z; w[c][3] = b.w;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (k + i >= kend) { v[c][i] = -INFINITY; w[c][i] = -INFINITY; }
+            m = fmaxf(m, v[c][i]); m2 = fmaxf(m2, w[c][i]);
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { m = fmaxf(m, __shfl_xor(m, o, 64)); m2 = fmaxf(m2, __shfl_xor(m2, o, 64)); }
+    float sum = 0.f, sum2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[c][i] = __expf(v[c][i] - m); sum += v[c][i];
+            if (s2) { w[c][i] = __expf(w[c][i] - m2); sum2 += w[c][i]; }
+        }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { sum += __shfl_xor(sum, o, 64); sum2 += __shfl_xor(sum2, o, 64); }
+    const float inv = 1.f / sum, inv2 = s2 ? 1.f / sum2 : 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int k = c * 256 + lane * 4;
+        if (k >= kz) continue;
+        union { bf16 h[4]; uint2 u; } pa, pd;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = v[c][i] * inv;
+            pa.h[i] = __float2bfloat16(a);
+            pd.h[i] = __float2bfloat16(s2 ? a - w[c][i] * inv2 : 0.f);
+        }
+        for (int cp = 0; cp < copies; ++cp) *(uint2*)(p + (long long)cp * L + k) = pa.u;
+        if (s2) *(uint2*)(p + dcol + k) = pd.u;
+    }
+}
+
 // out = scale * sum_s partial[s] (fp64 accumulation); lower: only r >= c is read, the result is mirrored
 __global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits, int n, double scale, int lower, float* __restrict__ out) {
     const long long nn = (long long)n * n;
@@ -215,8 +272,12 @@ int scores(const Dims& D, const bf16* Qh, const bf16* Kh, int sl, float* Sc) {
 }
 
 int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long ldp, int copies, int dcol) {
-    hipLaunchKernelGGL(softmax_bf16_kernel, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P, ldp,
-                       (long long)D.L * ldp, copies, dcol);
+    if (D.L % 4 == 0 && D.L <= 2048 && ldp % 4 == 0 && dcol % 4 == 0)
+        hipLaunchKernelGGL(softmax_bf16_regs_kernel<8>, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P,
+                           ldp, (long long)D.L * ldp, copies, dcol);
+    else
+        hipLaunchKernelGGL(softmax_bf16_kernel, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P, ldp,
+                           (long long)D.L * ldp, copies, dcol);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
 }

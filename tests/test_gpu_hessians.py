@@ -68,6 +68,15 @@ def test_bf16_path_small(ctx, causal, hq, hkv):
     assert torch.equal(got["Hin_v"], got["Hin_v"].transpose(1, 2))
 
 
+def test_bf16_path_long_sequence(ctx):
+    """One sequence longer than 2048 tokens: the softmax rows no longer fit the register-resident kernel."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=64, n_q_heads=1, n_kv_heads=1, head_dim=32, n_seqs=1, seq_len=2312, n_outlier=1)
+    b = synth.make_block(cfg, seed=4, device="cuda")
+    got = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 1, 1, 32, alpha=0.25)
+    want = O.build_hessians(np64(b["X"]), np64(b["X_fp"]), np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), 1, 1, 32, alpha=0.25)
+    check_all(got, want, 1e-5, 2e-3, 2e-2)
+
+
 def test_out_proj_fp32(ctx):
     cfg = synth.scaled(synth.CONFIGS["tiny"], d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, n_seqs=2, seq_len=40, n_outlier=2)
     b = synth.make_block(cfg, seed=3, device="cuda")
