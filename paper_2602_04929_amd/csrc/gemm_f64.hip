@@ -23,7 +23,8 @@ struct Args {
     const double* A; long long sa_r, sa_k;
     const double* B; long long sb_k, sb_r;
     double* C; long long ldc;
-    long long strideA, strideB, strideC;
+    long long strideA, strideB, strideC, strideA2, strideB2, strideC2;
+    int batch_inner;
     int klo_m, klo_n, khi_m, khi_n, skip_lower, skip_upper;
 };
 
@@ -86,10 +87,10 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(Args g, bool vecA, bool v
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     if (g.skip_lower && n0 + BN <= m0) return;
     if (g.skip_upper && m0 + BM <= n0) return;
-    const long long b = blockIdx.z;
-    const double* A = g.A + b * g.strideA;
-    const double* B = g.B + b * g.strideB;
-    double* C = g.C + b * g.strideC;
+    const long long b = blockIdx.z / g.batch_inner, b2 = blockIdx.z % g.batch_inner;
+    const double* A = g.A + b * g.strideA + b2 * g.strideA2;
+    const double* B = g.B + b * g.strideB + b2 * g.strideB2;
+    double* C = g.C + b * g.strideC + b2 * g.strideC2;
 
     int klo = 0, khi = g.K;
     if (g.klo_m) klo = max(klo, m0);
@@ -178,11 +179,13 @@ int gemm_f64(tboa_ctx* ctx, const GemmF64& q) {
     a.B = q.B; a.sb_k = q.sbk; a.sb_r = q.sbn;
     a.C = q.C; a.ldc = q.ldc;
     a.strideA = q.strideA; a.strideB = q.strideB; a.strideC = q.strideC;
+    a.strideA2 = q.strideA2; a.strideB2 = q.strideB2; a.strideC2 = q.strideC2;
+    a.batch_inner = q.batch_inner > 0 ? q.batch_inner : 1;
     a.klo_m = q.klo_m; a.klo_n = q.klo_n; a.khi_m = q.khi_m; a.khi_n = q.khi_n;
     a.skip_lower = q.skip_lower; a.skip_upper = q.skip_upper;
     // 16-byte vector loads need every row start and the tile offsets (even) to stay 16-byte aligned
-    const bool vecA = ((uintptr_t)q.A % 16 == 0) && (q.strideA % 2 == 0) && ((akc ? q.sam : q.sak) % 2 == 0);
-    const bool vecB = ((uintptr_t)q.B % 16 == 0) && (q.strideB % 2 == 0) && ((bkc ? q.sbn : q.sbk) % 2 == 0);
+    const bool vecA = ((uintptr_t)q.A % 16 == 0) && (q.strideA % 2 == 0) && (q.strideA2 % 2 == 0) && ((akc ? q.sam : q.sak) % 2 == 0);
+    const bool vecB = ((uintptr_t)q.B % 16 == 0) && (q.strideB % 2 == 0) && (q.strideB2 % 2 == 0) && ((bkc ? q.sbn : q.sbk) % 2 == 0);
     dim3 grid((unsigned)cdiv64(q.N, BN), (unsigned)cdiv64(q.M, BM), (unsigned)q.batch);
     if (grid.y > 65535 || grid.z > 65535) return tboa_fail(ctx, TBOA_EINVAL, "gemm_f64: grid too large");
     if (akc && bkc) hipLaunchKernelGGL((gemm_f64_kernel<true, true>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);

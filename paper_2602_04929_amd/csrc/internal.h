@@ -71,6 +71,8 @@ struct GemmF64 {
     const double* B; int64_t sbk, sbn;
     double* C; int64_t ldc;
     int batch; int64_t strideA, strideB, strideC;
+    // two-level batch: b -> (b / batch_inner, b % batch_inner); the *2 strides apply to the inner index
+    int batch_inner = 1; int64_t strideA2 = 0, strideB2 = 0, strideC2 = 0;
     // optional restriction of the contraction range per output tile (operands with triangular zeros):
     // k_lo = max(klo_m ? tile row start : 0, klo_n ? tile col start : 0)
     // k_hi = min(khi_m ? tile row end : K, khi_n ? tile col end : K); tiles with k_lo >= k_hi write beta*C.

@@ -351,6 +351,87 @@ __global__ __launch_bounds__(256) void cd_head_kernel(const double* __restrict__
     for (int i = t; i < dh; i += 256) sg[i] = s[i];
 }
 
+// Group-wise form of the same sweep: the coordinate is (row j, group g), visited in the order j = 0 .. dh-1,
+// g = 0 .. ng-1, and Q = sum over (k, g') of s[k, g'] Wbar[k, G'] (rows masked to one group).  With
+//   Cg[g][g'][j][k] = Wbar[j, G] H_in[G, G'] Wbar[k, G']^T      Fg[g][j][k] = Wbar[j, G] (W (H_in - R))[k, G]^T
+// the step is  s[j, g] += sum_k Ho[k, j] (Fg[g][j][k] - sum_g' s[k, g'] Cg[g][g'][j][k]) / (Cg[g][g][j][j] Ho[j, j]).
+// One workgroup per head; the scales of the head live in LDS.
+__global__ __launch_bounds__(256) void cd_group_head_kernel(const double* __restrict__ Fg, const double* __restrict__ Cg,
+                                                            const double* __restrict__ Ho, int dh, int ng, int iters,
+                                                            double* __restrict__ s_all) {
+    extern __shared__ double sh[];
+    double* s = sh; double* hoj = sh + (size_t)dh * ng; double* red = hoj + dh;
+    const int h = blockIdx.x, t = threadIdx.x;
+    const long long rr = (long long)dh * dh;
+    const double* Fh = Fg + (long long)h * ng * rr; const double* Ch = Cg + (long long)h * ng * ng * rr;
+    const double* Hh = Ho + (long long)h * rr;
+    double* sg = s_all + (long long)h * dh * ng;
+    for (int i = t; i < dh * ng; i += 256) s[i] = sg[i];
+    __syncthreads();
+    for (int it = 0; it < iters; ++it)
+        for (int j = 0; j < dh; ++j) {
+            for (int k = t; k < dh; k += 256) hoj[k] = Hh[(long long)k * dh + j];
+            __syncthreads();
+            for (int g = 0; g < ng; ++g) {
+                double acc = 0.0;
+                for (int k = t; k < dh; k += 256) acc += Fh[((long long)g * dh + j) * dh + k] * hoj[k];
+                for (int i = t; i < ng * dh; i += 256) {
+                    const int g2 = i / dh, k = i - g2 * dh;
+                    acc -= s[k * ng + g2] * Ch[(((long long)g * ng + g2) * dh + j) * dh + k] * hoj[k];
+                }
+                acc = wave_sum(acc);
+                if ((t & 63) == 0) red[t >> 6] = acc;
+                __syncthreads();
+                if (t == 0) {
+                    const double num = (red[0] + red[1]) + (red[2] + red[3]);
+                    const double den = Ch[(((long long)g * ng + g) * dh + j) * dh + j] * hoj[j];
+                    if (den > 0.0) s[j * ng + g] = s[j * ng + g] + num / den;
+                }
+                __syncthreads();
+            }
+        }
+    for (int i = t; i < dh * ng; i += 256) sg[i] = s[i];
+}
+
+// out[row, seg] = sum over the columns c of segment seg of A[row, c] B[row, c]; one wavefront per (row, segment)
+__global__ __launch_bounds__(256) void segdot_kernel(const double* __restrict__ A, const double* __restrict__ B, long long rows, int n, int gsz,
+                                                     int ng, double* __restrict__ out, long long out_row_stride) {
+    const int lane = threadIdx.x & 63;
+    const long long w = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= rows * ng) return;
+    const long long row = w / ng; const int seg = (int)(w - row * ng);
+    const double* a = A + row * n + (long long)seg * gsz; const double* b = B + row * n + (long long)seg * gsz;
+    double s = 0.0;
+    for (int c = lane; c < gsz; c += 64) s += a[c] * b[c];
+    s = wave_sum(s);
+    if (lane == 0) out[row * out_row_stride + seg] = s;
+}
+
+// identity H_out with groups: per row, s[g] += (Fd[g] - sum_g' s[g'] Cd[g][g']) / Cd[g][g] in the order g = 0 .. ng-1.
+// Cd [rows, ng, ng], Fd [rows, ng].  One wavefront per row, its scales in LDS.
+__global__ __launch_bounds__(256) void cd_group_diag_kernel(const double* __restrict__ Fd, const double* __restrict__ Cd, long long rows, int ng,
+                                                            int iters, double* __restrict__ s_all) {
+    extern __shared__ double sh[];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const long long row_raw = (long long)blockIdx.x * 4 + wv;
+    const bool live = row_raw < rows;
+    const long long row = live ? row_raw : rows - 1;
+    double* s = sh + (size_t)wv * ng;
+    for (int g = lane; g < ng; g += 64) s[g] = s_all[row * ng + g];
+    __syncthreads();
+    const double* C = Cd + row * ng * ng; const double* F = Fd + row * ng;
+    for (int it = 0; it < iters; ++it)
+        for (int g = 0; g < ng; ++g) {
+            double acc = 0.0;
+            for (int g2 = lane; g2 < ng; g2 += 64) acc += s[g2] * C[(long long)g * ng + g2];
+            acc = wave_sum(acc);
+            __syncthreads();
+            if (lane == 0) { const double den = C[(long long)g * ng + g]; if (den > 0.0) s[g] = s[g] + (F[g] - acc) / den; }
+            __syncthreads();
+        }
+    if (live) for (int g = lane; g < ng; g += 64) s_all[row * ng + g] = s[g];
+}
+
 // identity H_out: rows decouple, s_j += (F_jj - s_j C_jj) / C_jj
 __global__ void cd_diag_kernel(const double* __restrict__ Fd, const double* __restrict__ Cd, int rows, int iters, double* __restrict__ s) {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -416,6 +497,7 @@ struct Layer {
     double *cand_s, *cand_z, *Delta, *G, *cost, *DeltaS, *GS, *costS;
     __hip_bfloat16* Hcat; int* sel; int fast_grid;
     double *Wbar, *Abar, *Z, *WR, *Cm, *Fm, *dvec, *lossbuf;
+    double *Cg, *Fg;    // group-wise refinement: Gram blocks per (group, group) pair
     int grid_chunk;     // block rows (shared H_in) or heads (per-head H_in) per grid-search pass
     long long nn;
 };
@@ -631,8 +713,53 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     hipLaunchKernelGGL(wbar_kernel, dim3(gx(n), rows_all), dim3(256), 0, st, codes, L.z64, ng, L.gsz, n, L.Wbar);
     TB_KERNEL_CHECK(ctx);
     if (R) TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Rd, 0, n, 1, 0.0, L.WR, n));
-    if (d->cd_iters > 0) {
-        if (d->group) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: scale refinement with group > 0 is not implemented");
+    if (d->cd_iters > 0 && d->group) {
+        // Z = W (H_in - R); per group g: AH = Wbar[:, G] H_in[G, :] (into Abar), then the Gram blocks against every group
+        const int gsz = L.gsz;
+        const long long rr = (long long)dh * dh;
+        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Hi, 0, n, 1, 0.0, L.Z, n));
+        if (R) TB_TRY(launch_sub_f64(ctx, L.Z, L.WR, L.Z, wn));
+        if (H_out) {
+            GemmF64 f{};   // Fg[h][g] = Wbar_h[:, G] Z_h[:, G]^T
+            f.M = dh; f.N = dh; f.K = gsz; f.alpha = 1.0; f.beta = 0.0;
+            f.A = L.Wbar; f.sam = n; f.sak = 1; f.B = L.Z; f.sbk = 1; f.sbn = n; f.C = L.Fg; f.ldc = dh;
+            f.batch = nh * ng; f.batch_inner = ng;
+            f.strideA = (long long)dh * n; f.strideB = f.strideA; f.strideC = ng * rr;
+            f.strideA2 = gsz; f.strideB2 = gsz; f.strideC2 = rr;
+            TB_TRY(gemm_f64(ctx, f));
+        } else {
+            hipLaunchKernelGGL(segdot_kernel, dim3((unsigned)(((long long)rows_all * ng + 3) / 4)), dim3(256), 0, st, L.Wbar, L.Z,
+                               (long long)rows_all, n, gsz, ng, L.Fg, (long long)ng);
+            TB_KERNEL_CHECK(ctx);
+        }
+        for (int g = 0; g < ng; ++g) {
+            TB_TRY(block_gemm(L, dh, n, gsz, 1.0, L.Wbar + (long long)g * gsz, n, L.Hi, (long long)g * gsz * n, n, 1, 0.0, L.Abar, n));
+            if (H_out) {
+                GemmF64 c{};   // Cg[h][g][g'] = AH_h[:, G'] Wbar_h[:, G']^T
+                c.M = dh; c.N = dh; c.K = gsz; c.alpha = 1.0; c.beta = 0.0;
+                c.A = L.Abar; c.sam = n; c.sak = 1; c.B = L.Wbar; c.sbk = 1; c.sbn = n; c.C = L.Cg + (long long)g * ng * rr; c.ldc = dh;
+                c.batch = nh * ng; c.batch_inner = ng;
+                c.strideA = (long long)dh * n; c.strideB = c.strideA; c.strideC = (long long)ng * ng * rr;
+                c.strideA2 = gsz; c.strideB2 = gsz; c.strideC2 = rr;
+                TB_TRY(gemm_f64(ctx, c));
+            } else {   // Cd[row][g][g'] = AH[row, G'] . Wbar[row, G']
+                hipLaunchKernelGGL(segdot_kernel, dim3((unsigned)(((long long)rows_all * ng + 3) / 4)), dim3(256), 0, st, L.Abar, L.Wbar,
+                                   (long long)rows_all, n, gsz, ng, L.Cg + (long long)g * ng, (long long)ng * ng);
+                TB_KERNEL_CHECK(ctx);
+            }
+        }
+        if (H_out) {
+            const size_t smem = ((size_t)dh * ng + dh + 8) * sizeof(double);
+            if (smem > 160 * 1024) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: %d scales per head exceed the LDS of the group-wise refinement", dh * ng);
+            TB_HIP(ctx, hipFuncSetAttribute((const void*)cd_group_head_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+            hipLaunchKernelGGL(cd_group_head_kernel, dim3(nh), dim3(256), smem, st, L.Fg, L.Cg, L.Ho, dh, ng, d->cd_iters, L.s64);
+        } else {
+            const size_t smem = (size_t)4 * ng * sizeof(double);
+            hipLaunchKernelGGL(cd_group_diag_kernel, dim3((rows_all + 3) / 4), dim3(256), smem, st, L.Fg, L.Cg, (long long)rows_all, ng,
+                               d->cd_iters, L.s64);
+        }
+        TB_KERNEL_CHECK(ctx);
+    } else if (d->cd_iters > 0) {
         TB_TRY(block_gemm(L, dh, n, n, 1.0, L.Wbar, n, L.Hi, 0, n, 1, 0.0, L.Abar, n));
         TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Hi, 0, n, 1, 0.0, L.Z, n));
         if (R) TB_TRY(launch_sub_f64(ctx, L.Z, L.WR, L.Z, wn));
@@ -770,6 +897,12 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
         L.WR = R ? ar.get<double>(wn) : nullptr;
         L.Cm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr; L.Fm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
         L.dvec = ar.get<double>(2 * (size_t)d->d_out); L.lossbuf = ar.get<double>(2 * (size_t)nh);
+        L.Cg = L.Fg = nullptr;
+        if (d->group && d->cd_iters > 0) {
+            const size_t ng = (size_t)L.ng;
+            L.Cg = ar.get<double>(H_out ? (size_t)nh * ng * ng * dh * dh : (size_t)d->d_out * ng * ng);
+            L.Fg = ar.get<double>(H_out ? (size_t)nh * ng * dh * dh : (size_t)d->d_out * ng);
+        }
         if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
     }
     return run_layer(L, W, H_in, H_out, R, codes, scales, zeros, W_deq, loss, loss_per_head);

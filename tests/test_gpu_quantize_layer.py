@@ -54,6 +54,14 @@ CASES = [
     ("int3", 2, 32, 160, False, True, True, dict(bits=3, block=32)),
     ("int4-cd2", 2, 32, 130, False, True, True, dict(bits=4, block=12, cd_iters=2)),
     ("nodamp", 2, 16, 96, False, True, True, dict(bits=2, block=8, damp=0.0)),
+    # group-wise grids: (scale, zero) per (row, group), found when the sweep enters the group; refinement per (row, group)
+    ("group-sweep-only", 2, 32, 256, False, True, True, dict(bits=3, block=8, group=64, cd_iters=0)),
+    ("group-q", 2, 32, 256, False, True, True, dict(bits=3, block=8, group=64)),
+    ("group-q-noR-cd2", 3, 24, 192, False, True, False, dict(bits=3, block=24, group=64, cd_iters=2)),
+    ("group-v", 2, 16, 128, True, True, True, dict(bits=3, block=8, group=64)),
+    ("group-o", 1, 48, 256, False, False, True, dict(bits=3, block=48, group=128, cd_iters=2)),
+    ("group-32", 2, 16, 96, False, True, True, dict(bits=4, block=4, group=32)),
+    ("group-fixed-grid", 2, 16, 128, False, True, False, dict(bits=3, block=4, group=64, adaptive_grid=False)),
 ]
 
 
@@ -67,7 +75,8 @@ def test_quantize_layer_matches_oracle(ctx, case):
     print("codes identical: %.4f%%" % (100 * frac), flush=True)
     codes = got["codes"].cpu().numpy()
     assert codes.max() <= 2 ** kw["bits"] - 1
-    s = got["scales"].cpu().numpy(); z = got["zeros"].cpu().numpy()
+    gsz = kw.get("group", 0) or n
+    s = np.repeat(got["scales"].cpu().numpy(), gsz, axis=1); z = np.repeat(got["zeros"].cpu().numpy(), gsz, axis=1)
     assert np.allclose(got["W_deq"].cpu().numpy(), s * (codes.astype(np.float32) - z), rtol=1e-6)
 
 
