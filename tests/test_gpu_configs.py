@@ -1,0 +1,146 @@
+"""The other workload shapes (13B-shaped with group-wise INT3, 70B-shaped grouped-query block, weight-activation
+setting on the 7B shape) through the library at their real widths, against the oracle on sampled outputs (GPU).
+
+Model width, head layout, bits, block and group sizes are the configs'; the number of calibration sequences is cut
+to 16 (two passes of the 8-sequence chunks the Hessian build works in) so that the fp64 oracle can follow.
+Hessians: sampled entries recomputed in fp64 from X.  quantize_layer: one sampled head (heads are independent) with
+the oracle consuming the GPU-built, spot-checked Hessians."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import turboboa_ref as O
+from paper_2602_04929_amd import synth
+from tests.parity import compare_layer
+
+pytestmark = pytest.mark.gpu
+
+ALPHA = 0.25
+N_SEQS = 16
+
+
+def f64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def build(lib, name):
+    cfg = synth.scaled(synth.CONFIGS[name], n_seqs=N_SEQS)
+    print("building the %s-shaped block (%d sequences) and its Hessians" % (name, N_SEQS), flush=True)
+    blk = synth.make_block(cfg, seed=0, device="cuda")
+    ctx = lib.Context()
+    if blk["X"] is None:
+        blk["X"] = ctx.act_fakequant(blk["X_fp"], cfg.act_bits)
+    Hs = ctx.build_hessians(blk["X"], blk["X_fp"], blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], cfg.n_q_heads, cfg.n_kv_heads,
+                            cfg.head_dim, alpha=ALPHA)
+    torch.cuda.synchronize()
+    return dict(cfg=cfg, blk=blk, ctx=ctx, Hs=Hs)
+
+
+def release(c):
+    c["ctx"].close()
+    c.clear()
+    torch.cuda.empty_cache()
+
+
+def check_qk_entries(c, seed):
+    cfg, blk, Hs = c["cfg"], c["blk"], c["Hs"]
+    d = cfg.d_model
+    ch = np.sort(np.random.default_rng(seed).choice(d, 8, replace=False))
+    Xc = f64(blk["X"].reshape(-1, d)[:, ch]); dXc = Xc - f64(blk["X_fp"].reshape(-1, d)[:, ch])
+    want = Xc.T @ Xc
+    e = (np.abs(f64(Hs["Hin_qk"][ch][:, ch]) - want) / np.sqrt(np.outer(np.diag(want), np.diag(want)))).max()
+    wantR = ALPHA * dXc.T @ Xc
+    eR = (np.abs(f64(Hs["R_qk"][ch][:, ch]) - wantR) / (ALPHA * np.sqrt(np.outer(np.diag(dXc.T @ dXc), np.diag(want))))).max()
+    print("  Hin_qk sampled rel err %.2e, R_qk %.2e" % (e, eR), flush=True)
+    assert e <= 1e-5 and eR <= 1e-4
+
+
+def check_group_entries(c, g, seed):
+    """KV group g: H_out of W_Q (K^T K), of W_K (sum over the group's query heads of Q^T Q), of W_V, and sampled
+    entries of H_in / R of W_V (sum over the group's query heads and all sequences)."""
+    cfg, blk, Hs = c["cfg"], c["blk"], c["Hs"]
+    d, dh, rep = cfg.d_model, cfg.head_dim, cfg.n_q_heads // cfg.n_kv_heads
+    ch = np.sort(np.random.default_rng(seed).choice(d, 6, replace=False))
+    cols = [0, 17, dh - 1]
+    wk = f64(blk["Wk"][g * dh:(g + 1) * dh])
+    KK = np.zeros((3, 3)); QQ = np.zeros((3, 3))
+    Hv = np.zeros((6, 6)); Rv = np.zeros((6, 6)); dYY = np.zeros((6, 6))
+    for h in range(g * rep, (g + 1) * rep):
+        wq = f64(blk["Wq"][h * dh:(h + 1) * dh])
+        for s in range(cfg.n_seqs):
+            xs, xf = f64(blk["X"][s]), f64(blk["X_fp"][s])
+            A, Q, K = O.attention_probs(xs, wq, wk)
+            Af, _, _ = O.attention_probs(xf, wq, wk)
+            Y = A @ xs[:, ch]; dY = Y - Af @ xf[:, ch]
+            Hv += Y.T @ Y; Rv += ALPHA * dY.T @ Y; dYY += dY.T @ dY
+            QQ += Q[:, cols].T @ Q[:, cols]
+            if h == g * rep:
+                KK += K[:, cols].T @ K[:, cols]
+        print("  oracle sums: query head", h, flush=True)
+    rel = lambda got, want: (np.abs(got - want) / np.sqrt(np.outer(np.diag(want), np.diag(want)))).max()
+    e_q = rel(f64(Hs["Hout_q"][g * rep][cols][:, cols]), KK)
+    e_k = rel(f64(Hs["Hout_k"][g][cols][:, cols]), QQ)
+    Wo = f64(blk["Wo"])
+    want_v = sum(Wo[:, h * dh:(h + 1) * dh].T @ Wo[:, h * dh:(h + 1) * dh] for h in range(g * rep, (g + 1) * rep))
+    e_hv = rel(f64(Hs["Hin_v"][g][ch][:, ch]), Hv)
+    e_rv = (np.abs(f64(Hs["R_v"][g][ch][:, ch]) - Rv) / (ALPHA * np.sqrt(np.outer(np.diag(dYY), np.diag(Hv))))).max()
+    print("  group %d: Hout_q %.2e, Hout_k %.2e, Hin_v %.2e, R_v %.2e" % (g, e_q, e_k, e_hv, e_rv), flush=True)
+    assert e_q <= 1e-5 and e_k <= 1e-5
+    assert np.allclose(f64(Hs["Hout_v"][g]), want_v, rtol=1e-6, atol=1e-9)
+    assert e_hv <= 5e-4 and e_rv <= 5e-3          # probabilities and A X are rounded to bf16 before the last contraction
+
+
+def check_layer_head(c, wkey, hin, hout, rkey, n_heads, h, per_head=False):
+    cfg, blk, Hs, ctx = c["cfg"], c["blk"], c["Hs"], c["ctx"]
+    dh = cfg.head_dim
+    kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group)
+    print("  quantize_layer %s (%d heads) on the GPU" % (wkey, n_heads), flush=True)
+    got = ctx.quantize_layer(blk[wkey], Hs[hin], Hs[hout], Hs[rkey], n_heads, **kw)
+    rows = slice(h * dh, (h + 1) * dh)
+    Hi = f64(Hs[hin][h:h + 1]) if per_head else f64(Hs[hin])
+    Rr = f64(Hs[rkey][h:h + 1]) if per_head else f64(Hs[rkey])
+    print("  oracle quantize_layer on head", h, flush=True)
+    want = O.quantize_layer(f64(blk[wkey][rows]), Hi, f64(Hs[hout][h:h + 1]), Rr, 1, **kw)
+    sub = dict(codes=got["codes"][rows], scales=got["scales"][rows], zeros=got["zeros"][rows], W_deq=got["W_deq"][rows],
+               loss_per_head=[got["loss_per_head"][h]], loss=got["loss_per_head"][h], loss_quad=want["loss_quad"],
+               loss_cross=want["loss_cross"])
+    frac = compare_layer(sub, want, label="%s head %d" % (wkey, h))
+    print("  %s head %d: codes identical %.4f%%, loss %.6g vs %.6g" % (wkey, h, 100 * frac, sub["loss"], want["loss"]), flush=True)
+    assert np.isfinite(got["loss"])
+    return got
+
+
+def test_llama2_13b_shape_groupwise_int3(lib):
+    c = build(lib, "llama2-13b")
+    try:
+        check_qk_entries(c, 11)
+        check_layer_head(c, "Wq", "Hin_qk", "Hout_q", "R_qk", c["cfg"].n_q_heads, 21)
+    finally:
+        release(c)
+
+
+def test_llama2_70b_shape_grouped_query(lib):
+    c = build(lib, "llama2-70b")
+    try:
+        check_qk_entries(c, 12)
+        check_group_entries(c, 5, 13)
+        # W_K: 8 KV heads, H_out summed over the 8 query heads of each group
+        check_layer_head(c, "Wk", "Hin_qk", "Hout_k", "R_qk", c["cfg"].n_kv_heads, 5)
+    finally:
+        release(c)
+
+
+def test_llama2_7b_w4a4_shape(lib):
+    c = build(lib, "llama2-7b-w4a4")
+    try:
+        cfg, blk = c["cfg"], c["blk"]
+        # the quantized-path input is the per-token INT4 fake-quant of the rotated activations: sampled tokens, bit for bit
+        tok = np.sort(np.random.default_rng(14).choice(cfg.n_tokens, 64, replace=False))
+        xf = f64(blk["X_fp"].reshape(-1, cfg.d_model)[torch.tensor(tok, device="cuda")])
+        want = torch.tensor(O.act_fakequant_per_token(xf, cfg.act_bits)).to(torch.bfloat16).float().numpy()
+        got = blk["X"].reshape(-1, cfg.d_model)[torch.tensor(tok, device="cuda")].float().cpu().numpy()
+        assert np.array_equal(got, want)
+        check_qk_entries(c, 15)
+        check_layer_head(c, "Wv", "Hin_v", "Hout_v", "R_v", cfg.n_kv_heads, 9, per_head=True)
+    finally:
+        release(c)
