@@ -109,52 +109,93 @@ int launch_f32_to_f64_damp(tboa_ctx* ctx, int n, int batch, const float* H, doub
     return 0;
 }
 
+// Two levels of blocking.  Diagonal blocks of NB columns are factored (and inverted) in LDS; an outer block of OB columns
+// is finished block by block with updates confined to its own columns, after which ONE update with an OB-deep
+// contraction carries it into the rest of the matrix: the large updates are bound by the matrix cores, not by reading
+// and writing the trailing matrix once per NB columns.  The inverse is assembled the same way, OB columns at a time.
 int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H, double* U, double* tmp, double* dinv) {
-    const int nblk = (n + NB - 1) / NB;
-    const long long nn = (long long)n * n;
+    constexpr int OB = TB_FACT_OB, IPB = OB / NB;
+    const int nblk = (n + NB - 1) / NB, nob = (n + OB - 1) / OB;
+    const long long nn = (long long)n * n, dstride = (long long)nblk * NB * NB;
     TB_HIP(ctx, hipMemsetAsync(ctx->d_status, 0, 2 * sizeof(int), ctx->stream));
-    for (int blk = nblk - 1; blk >= 0; --blk) {
-        const int j0 = blk * NB, bs = (n - j0 < NB) ? n - j0 : NB;
-        hipLaunchKernelGGL(diag_factor_kernel, dim3(batch), dim3(256), 0, ctx->stream, H, n, j0, bs, dinv, blk, nblk, ctx->d_status);
-        TB_KERNEL_CHECK(ctx);
-        if (j0 == 0) break;
-        // panel: V[0:j0, blk] = H[0:j0, blk] Vinv_jj^T   (in place: one column tile, each workgroup owns its rows)
-        GemmF64 p{};
-        p.M = j0; p.N = bs; p.K = bs; p.alpha = 1.0; p.beta = 0.0;
-        p.A = H + j0; p.sam = n; p.sak = 1;
-        p.B = dinv + (long long)blk * NB * NB; p.sbk = 1; p.sbn = NB;
-        p.C = H + j0; p.ldc = n;
-        p.batch = batch; p.strideA = nn; p.strideB = (long long)nblk * NB * NB; p.strideC = nn;
-        TB_TRY(gemm_f64(ctx, p));
-        // trailing: H[0:j0, 0:j0] -= V[0:j0, blk] V[0:j0, blk]^T  (upper part only)
-        GemmF64 s{};
-        s.M = j0; s.N = j0; s.K = bs; s.alpha = -1.0; s.beta = 1.0;
-        s.A = H + j0; s.sam = n; s.sak = 1;
-        s.B = H + j0; s.sbk = 1; s.sbn = n;
-        s.C = H; s.ldc = n; s.skip_lower = 1;
-        s.batch = batch; s.strideA = nn; s.strideB = nn; s.strideC = nn;
-        TB_TRY(gemm_f64(ctx, s));
+    // ---- H = V V^T from the last column to the first
+    for (int ob = nob - 1; ob >= 0; --ob) {
+        const int J0 = ob * OB, J1 = (J0 + OB < n) ? J0 + OB : n;
+        const int blk_hi = (J1 + NB - 1) / NB - 1, blk_lo = ob * IPB;
+        for (int blk = blk_hi; blk >= blk_lo; --blk) {
+            const int j0 = blk * NB, bs = (n - j0 < NB) ? n - j0 : NB;
+            hipLaunchKernelGGL(diag_factor_kernel, dim3(batch), dim3(256), 0, ctx->stream, H, n, j0, bs, dinv, blk, nblk, ctx->d_status);
+            TB_KERNEL_CHECK(ctx);
+            if (j0 == 0) break;
+            // panel: V[0:j0, blk] = H[0:j0, blk] Vinv_jj^T   (in place: one column tile, each workgroup owns its rows)
+            GemmF64 p{};
+            p.M = j0; p.N = bs; p.K = bs; p.alpha = 1.0; p.beta = 0.0;
+            p.A = H + j0; p.sam = n; p.sak = 1;
+            p.B = dinv + (long long)blk * NB * NB; p.sbk = 1; p.sbn = NB;
+            p.C = H + j0; p.ldc = n;
+            p.batch = batch; p.strideA = nn; p.strideB = dstride; p.strideC = nn;
+            TB_TRY(gemm_f64(ctx, p));
+            if (j0 > J0) {   // inside the outer block: H[0:j0, J0:j0] -= V[0:j0, blk] V[J0:j0, blk]^T  (upper part)
+                GemmF64 s{};
+                s.M = j0; s.N = j0 - J0; s.K = bs; s.alpha = -1.0; s.beta = 1.0;
+                s.A = H + j0; s.sam = n; s.sak = 1;
+                s.B = H + (long long)J0 * n + j0; s.sbk = 1; s.sbn = n;
+                s.C = H + J0; s.ldc = n; s.skip_lower = 1; s.skip_col0 = J0;
+                s.batch = batch; s.strideA = nn; s.strideB = nn; s.strideC = nn;
+                TB_TRY(gemm_f64(ctx, s));
+            }
+        }
+        if (J0 > 0) {   // H[0:J0, 0:J0] -= V[0:J0, ob] V[0:J0, ob]^T  (upper part)
+            GemmF64 s{};
+            s.M = J0; s.N = J0; s.K = J1 - J0; s.alpha = -1.0; s.beta = 1.0;
+            s.A = H + J0; s.sam = n; s.sak = 1;
+            s.B = H + J0; s.sbk = 1; s.sbn = n;
+            s.C = H; s.ldc = n; s.skip_lower = 1;
+            s.batch = batch; s.strideA = nn; s.strideB = nn; s.strideC = nn;
+            TB_TRY(gemm_f64(ctx, s));
+        }
     }
-    // U = V^-1, block column by block column
+    // ---- U = V^-1
     TB_TRY(launch_fill_f64(ctx, U, (int64_t)batch * nn, 0.0));
     hipLaunchKernelGGL(place_diag_inverse_kernel, dim3(nblk, batch), dim3(256), 0, ctx->stream, U, n, dinv, nblk);
     TB_KERNEL_CHECK(ctx);
-    for (int blk = 1; blk < nblk; ++blk) {
-        const int j0 = blk * NB, bs = (n - j0 < NB) ? n - j0 : NB;
-        GemmF64 a{};   // tmp = U[0:j0, 0:j0] V[0:j0, blk]
-        a.M = j0; a.N = bs; a.K = j0; a.alpha = 1.0; a.beta = 0.0;
-        a.A = U; a.sam = n; a.sak = 1; a.klo_m = 1;
-        a.B = H + j0; a.sbk = n; a.sbn = 1;
-        a.C = tmp; a.ldc = NB;
-        a.batch = batch; a.strideA = nn; a.strideB = nn; a.strideC = (long long)n * NB;
-        TB_TRY(gemm_f64(ctx, a));
-        GemmF64 c{};   // U[0:j0, blk] = -tmp Vinv_jj
-        c.M = j0; c.N = bs; c.K = bs; c.alpha = -1.0; c.beta = 0.0;
-        c.A = tmp; c.sam = NB; c.sak = 1;
-        c.B = dinv + (long long)blk * NB * NB; c.sbk = NB; c.sbn = 1;
-        c.C = U + j0; c.ldc = n;
-        c.batch = batch; c.strideA = (long long)n * NB; c.strideB = (long long)nblk * NB * NB; c.strideC = nn;
-        TB_TRY(gemm_f64(ctx, c));
+    for (int ob = 0; ob < nob; ++ob) {
+        const int J0 = ob * OB, J1 = (J0 + OB < n) ? J0 + OB : n;
+        const int blk_hi = (J1 + NB - 1) / NB - 1, blk_lo = ob * IPB;
+        for (int blk = blk_lo + 1; blk <= blk_hi; ++blk) {   // the diagonal block of the outer block: U[J0:j0, blk]
+            const int j0 = blk * NB, bs = (n - j0 < NB) ? n - j0 : NB, m = j0 - J0;
+            GemmF64 a{};   // tmp = U[J0:j0, J0:j0] V[J0:j0, blk]
+            a.M = m; a.N = bs; a.K = m; a.alpha = 1.0; a.beta = 0.0;
+            a.A = U + (long long)J0 * n + J0; a.sam = n; a.sak = 1; a.klo_m = 1;
+            a.B = H + (long long)J0 * n + j0; a.sbk = n; a.sbn = 1;
+            a.C = tmp; a.ldc = OB;
+            a.batch = batch; a.strideA = nn; a.strideB = nn; a.strideC = (long long)n * OB;
+            TB_TRY(gemm_f64(ctx, a));
+            GemmF64 c{};   // U[J0:j0, blk] = -tmp Vinv_jj
+            c.M = m; c.N = bs; c.K = bs; c.alpha = -1.0; c.beta = 0.0;
+            c.A = tmp; c.sam = OB; c.sak = 1;
+            c.B = dinv + (long long)blk * NB * NB; c.sbk = NB; c.sbn = 1;
+            c.C = U + (long long)J0 * n + j0; c.ldc = n;
+            c.batch = batch; c.strideA = (long long)n * OB; c.strideB = dstride; c.strideC = nn;
+            TB_TRY(gemm_f64(ctx, c));
+        }
+        if (J0 > 0) {
+            const int w = J1 - J0;
+            GemmF64 a{};   // tmp = U[0:J0, 0:J0] V[0:J0, ob]
+            a.M = J0; a.N = w; a.K = J0; a.alpha = 1.0; a.beta = 0.0;
+            a.A = U; a.sam = n; a.sak = 1; a.klo_m = 1;
+            a.B = H + J0; a.sbk = n; a.sbn = 1;
+            a.C = tmp; a.ldc = OB;
+            a.batch = batch; a.strideA = nn; a.strideB = nn; a.strideC = (long long)n * OB;
+            TB_TRY(gemm_f64(ctx, a));
+            GemmF64 c{};   // U[0:J0, ob] = -tmp U[ob, ob]   (U[ob, ob] upper: k <= column)
+            c.M = J0; c.N = w; c.K = w; c.alpha = -1.0; c.beta = 0.0;
+            c.A = tmp; c.sam = OB; c.sak = 1;
+            c.B = U + (long long)J0 * n + J0; c.sbk = n; c.sbn = 1; c.khi_n = 1;
+            c.C = U + J0; c.ldc = n;
+            c.batch = batch; c.strideA = (long long)n * OB; c.strideB = nn; c.strideC = nn;
+            TB_TRY(gemm_f64(ctx, c));
+        }
     }
     TB_HIP(ctx, hipMemcpyAsync(ctx->h_status, ctx->d_status, 2 * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
     TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -172,7 +213,7 @@ extern "C" int tboa_chol_inv_upper(tboa_ctx* ctx, int n, int batch, const float*
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
         double* H64 = ar.get<double>((size_t)batch * n * n);
-        double* tmp = ar.get<double>((size_t)batch * n * NB);
+        double* tmp = ar.get<double>((size_t)batch * n * TB_FACT_OB);
         double* dinv = ar.get<double>((size_t)batch * nblk * NB * NB);
         if (!pass) { TB_TRY(tboa_ws_reserve(ctx, ar.off)); continue; }
         TB_TRY(launch_f32_to_f64_damp(ctx, n, batch, H, damp, H64));

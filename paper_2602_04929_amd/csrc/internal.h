@@ -79,6 +79,7 @@ struct GemmF64 {
     int klo_m = 0, klo_n = 0, khi_m = 0, khi_n = 0;
     int skip_lower = 0;  // skip tiles entirely below the diagonal (col end <= row start): left untouched
     int skip_upper = 0;  // skip tiles entirely above the diagonal (row end <= col start)
+    int skip_col0 = 0;   // column of C's first column relative to its first row, for the two tests above
 };
 int gemm_f64(tboa_ctx* ctx, const GemmF64& g);
 
@@ -99,8 +100,10 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
 
 // ---------------------------------------------------------------- factor.hip
 // H64 [batch, n, n] fp64, overwritten; U [batch, n, n] fp64 out.  Checks the device status and
-// returns TBOA_ENOTSPD on breakdown (synchronises).  tmp: workspace of batch*n*TB_FACT_NB doubles.
-#define TB_FACT_NB 64
+// returns TBOA_ENOTSPD on breakdown (synchronises).  tmp: workspace of batch*n*TB_FACT_OB doubles,
+// dinv: batch * ceil(n / TB_FACT_NB) * TB_FACT_NB^2 doubles.
+#define TB_FACT_NB 64     // diagonal blocks factored inside LDS
+#define TB_FACT_OB 256    // outer blocks: width of the large trailing updates
 int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H64, double* U, double* tmp, double* dinv);
 int launch_f32_to_f64_damp(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* out);
 

@@ -880,7 +880,7 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
         L.Rd = R ? ar.get<double>((size_t)L.nhin * L.nn) : nullptr; L.P = R ? ar.get<double>((size_t)L.nhin * L.nn) : nullptr;
         L.Ho = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr; L.Hofac = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
         L.Uout = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
-        L.ftmp = ar.get<double>((size_t)fb * fmax * TB_FACT_NB); L.fdinv = ar.get<double>((size_t)fb * nblk_f * TB_FACT_NB * TB_FACT_NB);
+        L.ftmp = ar.get<double>((size_t)fb * fmax * TB_FACT_OB); L.fdinv = ar.get<double>((size_t)fb * nblk_f * TB_FACT_NB * TB_FACT_NB);
         L.Wb = ar.get<double>(brows * n); L.Wk = ar.get<double>(brows * n);
         L.Epan = ar.get<double>(brows * 64); L.Wsnap = ar.get<double>(brows * 64);
         L.E = H_out ? ar.get<double>(brows * n) : nullptr;
