@@ -4,15 +4,18 @@
 // are kept in a transposed copy where the token axis is the contraction axis), so one kernel shape serves X^T X,
 // the projections, Q K^T, A X and the dominant Y^T Y.
 //
-// Workgroup: 256 threads = 4 wavefronts (2 x 2) on a 256 x 256 x 64 tile; each wavefront owns 128 x 128 as 4 x 4
-// MFMA tiles of 32 x 32 (256 fp32 accumulators per lane, one workgroup per CU).  Per 16-wide k-step a wavefront reads
-// 8 fragments of 16 bytes per lane from LDS for 16 MFMAs.  LDS rows are 128 bytes (64 bf16); the LDS has 64 banks
-// (256 bytes), so two consecutive rows fill one bank line and a 128-bit access is served 16 lanes at a time: the
-// 16-byte chunks of a row are XOR-swizzled with (row / 2) % 8, which makes the 16 rows read by 16 consecutive lanes
-// (and the two rows written by them) hit 16 different bank groups (measured: SQ_LDS_BANK_CONFLICT = 0).
-// Global -> register -> LDS software pipeline over two LDS stages, one barrier per 64-wide k-step.
-// Tiles are numbered so that the eight XCDs (workgroups are dealt to them round-robin) each work on a compact
-// band of the output and share operand panels through their own L2.
+// Two kernels share the 256 x 256 output tile per workgroup, the MFMA shape and the launch order of the tiles:
+//   gemm_bf16_nt_fast_kernel  (K a multiple of 32: every launch of the Hessian build and of the grid search) copies global
+//                             memory straight into a ring of LDS stages and runs 8 wavefronts; described at its definition;
+//   gemm_bf16_nt_kernel       (any K that is a multiple of 8) stages through registers: 4 wavefronts (2 x 2), each owning
+//                             128 x 128 as 4 x 4 MFMA tiles of 32 x 32 (256 fp32 accumulators per lane), 64-deep k-steps,
+//                             two LDS stages, one barrier per k-step.
+// LDS rows of the register-staged kernel are 128 bytes (64 bf16); the LDS has 64 banks (256 bytes), so two consecutive rows
+// fill one bank line and a 128-bit access is served 16 lanes at a time: the 16-byte chunks of a row are XOR-swizzled with
+// (row / 2) % 8, which makes the 16 rows read by 16 consecutive lanes (and the two rows written by them) hit 16 different
+// bank groups (measured: SQ_LDS_BANK_CONFLICT = 0).
+// The tiles of a launch are handed out so that the 32 CUs of an XCD (workgroups are dealt to the eight XCDs round-robin)
+// work on a compact block of ONE batch entry and share operand panels through that XCD's L2: see work_item / tile_order.
 #include "internal.h"
 #include <stdlib.h>
 
