@@ -30,9 +30,12 @@ def measured_traffic(cfg_name):
 
 
 def cpu_baseline(blk, cfg, hessians, budget_note):
-    """The fp64 oracle, as it stands, on a bounded sample: Algorithm 1 for ONE head of W_Q (128 out-channels, all d
-    in-channels) with the Hessians already built.  Scaled to a whole block by the number of 128-row heads in the four
-    layers (Hq + 2 Hkv + d/dh); the oracle's own Hessian build (about 4e14 fp64 multiply-adds) is NOT included."""
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload, scaled to one attention block:
+    (1) Algorithm 1 for ONE head of W_Q (128 out-channels, all d in-channels) with the Hessians given, times the number of
+        head-sized row groups in the four layers (Hq + 2 Hkv + d/dh);
+    (2) the Table 1 sums of ONE (sequence, query head) pair (A_h, Y = A_h X_s, Y^T Y, and the same for the deviation term),
+        times n_seqs * Hq, plus X_s^T X_s and dX_s^T X_s of one sequence times n_seqs.  The output-projection Hessian
+        (another attention forward per sequence and head) is not sampled and not counted."""
     import numpy as np
     from oracle import turboboa_ref as O
     try:
@@ -46,11 +49,29 @@ def cpu_baseline(blk, cfg, hessians, budget_note):
     R = f(hessians["R_qk"]) if hessians["R_qk"] is not None else None
     t = time.perf_counter()
     O.quantize_layer(W, Hin, Hout, R, 1, bits=cfg.bits, block=cfg.block, group=cfg.group)
-    dt = time.perf_counter() - t
+    dt_q = time.perf_counter() - t
     heads_equiv = cfg.n_q_heads + 2 * cfg.n_kv_heads + cfg.d_model // dh
-    return {"value": dt * heads_equiv, "unit": "s per attention block (extrapolated)", "cores": int(cores), "kind": "oracle",
-            "sample": "oracle quantize_layer on head 0 of W_Q (%d x %d, Hessians given): %.1f s measured, x %d head-sized row groups "
-                      "in W_Q, W_K, W_V, W_O; CPU Hessian build excluded%s" % (dh, cfg.d_model, dt, heads_equiv, budget_note)}
+    xs = f(blk["X"][0]) if blk["X"] is not None else f(blk["X_fp"][0])
+    xf = f(blk["X_fp"][0]); wq = f(blk["Wq"][:dh]); wk = f(blk["Wk"][:dh])
+    t = time.perf_counter()
+    A, _, _ = O.attention_probs(xs, wq, wk)
+    Y = A @ xs; Hv = Y.T @ Y
+    if R is not None:
+        Af, _, _ = O.attention_probs(xf, wq, wk)
+        Rv = (Y - Af @ xf).T @ Y
+    dt_pair = time.perf_counter() - t
+    t = time.perf_counter()
+    Hs = xs.T @ xs
+    if R is not None:
+        Rs = (xs - xf).T @ xs
+    dt_seq = time.perf_counter() - t
+    hess = dt_pair * cfg.n_seqs * cfg.n_q_heads + dt_seq * cfg.n_seqs
+    return {"value": dt_q * heads_equiv + hess, "unit": "s per attention block (extrapolated)", "cores": int(cores), "kind": "oracle",
+            "sample": "oracle quantize_layer on head 0 of W_Q (%d x %d, Hessians given): %.1f s measured, x %d head-sized row groups in "
+                      "W_Q, W_K, W_V, W_O = %.0f s; oracle Table 1 sums of one (sequence, head) pair: %.1f s, x %d pairs, and of one "
+                      "sequence for H_in, R: %.2f s, x %d = %.0f s; output-projection Hessian not counted%s"
+                      % (dh, cfg.d_model, dt_q, heads_equiv, dt_q * heads_equiv, dt_pair, cfg.n_seqs * cfg.n_q_heads, dt_seq, cfg.n_seqs, hess,
+                         budget_note)}
 
 
 def roofline_probe(ctx, cfg, torch):
