@@ -111,6 +111,13 @@ int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* desc,
 int tboa_act_fakequant(tboa_ctx* ctx, int64_t n_tokens, int d, int bits, int dtype,
                        const void* X_in, void* X_out);
 
+/* Randomised Hadamard rotation of activations, the fixed training-free transform that the weight-activation
+ * experiments apply before quantization to spread outlier channels (Sec. 4.2 with App. B):
+ *   X_out[t, :] = (X_in[t, :] * signs) H_d / sqrt(d),  H_d[i, j] = (-1)^popcount(i & j)  (Sylvester-Hadamard, d = 2^k).
+ * X_in, X_out [n_tokens, d] in `dtype` (TBOA_F32 or TBOA_BF16; may alias; 16-byte aligned, signs too), arithmetic in fp32;
+ * signs: d floats, each +1 or -1, or NULL (all +1).  d must be a power of two in 16 .. 16384. */
+int tboa_hadamard_rotate(tboa_ctx* ctx, int64_t n_tokens, int d, int dtype, const void* X_in, const float* signs, void* X_out);
+
 /* ------------------------------------------------------------------------------------------------
  * One projection weight (Algorithm 1 lines 2-13).
  */

@@ -149,6 +149,25 @@ def act_fakequant_per_token(X, bits):
     return s * (q - z)
 
 
+def hadamard_matrix(d):
+    """Sylvester-Hadamard matrix of order d = 2^k: H_1 = [1], H_2n = [[H_n, H_n], [H_n, -H_n]]."""
+    H = np.ones((1, 1), F64)
+    while H.shape[0] < d:
+        H = np.block([[H, H], [H, -H]])
+    assert H.shape[0] == d, "d must be a power of two"
+    return H
+
+
+def hadamard_rotate(X, signs=None):
+    """Randomised Hadamard rotation of activation rows (the fixed transform of App. B used in the weight-activation
+    setting): (X * signs) H_d / sqrt(d).  X [..., d], signs [d] of +-1 or None."""
+    X = np.asarray(X, F64)
+    d = X.shape[-1]
+    if signs is not None:
+        X = X * np.asarray(signs, F64)
+    return X @ hadamard_matrix(d) / np.sqrt(F64(d))
+
+
 # --------------------------------------------------------------------------
 # eq. 3: U = Chol(H^-1)^T
 # --------------------------------------------------------------------------

@@ -56,6 +56,7 @@ def _load():
         "tboa_build_hessians": ([vp, C.POINTER(AttnDesc)] + [vp] * 13, i32),
         "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 10, i32),
         "tboa_act_fakequant": ([vp, i64, i32, i32, i32, vp, vp], i32),
+        "tboa_hadamard_rotate": ([vp, i64, i32, i32, vp, vp, vp], i32),
         "tboa_quantize_layer": ([vp, C.POINTER(LayerDesc)] + [vp] * 8 + [C.POINTER(f64), C.POINTER(f64)], i32),
         "tboa_counter": ([vp, i32], i64),
         "tboa_profile_enable": ([vp, i32], i32),
@@ -216,6 +217,15 @@ class Context:
         out = torch.empty_like(X) if out is None else out
         d = X.shape[-1]
         self._check(_lib.tboa_act_fakequant(self._h, X.numel() // d, d, bits, _dtype_code(X), _ptr(X), _ptr(out)))
+        return out
+
+    def hadamard_rotate(self, X, signs=None, out=None):
+        _dev(X)
+        if signs is not None:
+            _dev(signs, torch.float32)
+        out = torch.empty_like(X) if out is None else out
+        d = X.shape[-1]
+        self._check(_lib.tboa_hadamard_rotate(self._h, X.numel() // d, d, _dtype_code(X), _ptr(X), _ptr(signs), _ptr(out)))
         return out
 
     def quantize_layer(self, W, H_in, H_out, R, n_heads, bits, block, group=0, cd_iters=1, adaptive_grid=True,

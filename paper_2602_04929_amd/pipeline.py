@@ -8,7 +8,7 @@ import torch
 
 def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=True, cd_iters=1, adaptive_grid=True,
                              damp=0.01, seq_chunk=0, timings=None):
-    """Hessians -> W_Q, W_K, W_V -> output-projection Hessian -> W_O.
+    """(rotation, activation fake-quant ->) Hessians -> W_Q, W_K, W_V -> output-projection Hessian -> W_O.
 
     blk: dict from synth.make_block (device tensors); cfg: synth.BlockConfig.  Returns dict of per-layer results
     and the Hessians.  `timings` (a dict) receives per-stage seconds measured with stream synchronisation."""
@@ -26,13 +26,17 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
         timings[name] = timings.get(name, 0.0) + time.perf_counter() - t
         return out
 
+    if blk.get("signs") is not None:      # randomised Hadamard rotation ahead of everything else (outlier suppression)
+        X_fp = stage("hadamard_rotate", lambda: ctx.hadamard_rotate(X_fp, blk["signs"]))
+        if X is not None:
+            X = ctx.hadamard_rotate(X, blk["signs"])
     if X is None:      # weight-activation setting: the quantized path sees per-token fake-quantized activations
         X = stage("act_fakequant", lambda: ctx.act_fakequant(X_fp, cfg.act_bits))
     Xf = X_fp if use_R else None
     Hs = stage("build_hessians", lambda: ctx.build_hessians(X, Xf, blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], Hq, Hkv, dh,
                                                             alpha=alpha, with_R_v=with_R_v, seq_chunk=seq_chunk))
     kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp)
-    out = {"hessians": Hs, "X": X}
+    out = {"hessians": Hs, "X": X, "X_fp": X_fp}
     out["q"] = stage("quantize_q", lambda: ctx.quantize_layer(blk["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq, **kw))
     out["k"] = stage("quantize_k", lambda: ctx.quantize_layer(blk["Wk"], Hs["Hin_qk"], Hs["Hout_k"], Hs["R_qk"], Hkv, **kw))
     out["v"] = stage("quantize_v", lambda: ctx.quantize_layer(blk["Wv"], Hs["Hin_v"], Hs["Hout_v"], Hs["R_v"], Hkv, **kw))

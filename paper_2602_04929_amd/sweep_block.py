@@ -31,8 +31,9 @@ def main():
         cfg = synth.scaled(cfg, n_seqs=args.n_seqs)
     blk = synth.make_block(cfg, seed=0, device="cuda:0")
     ctx = tb.Context()
-    X = blk["X"] if blk["X"] is not None else ctx.act_fakequant(blk["X_fp"], cfg.act_bits)
-    Hs = ctx.build_hessians(X, blk["X_fp"], blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, alpha=0.25)
+    X_fp = blk["X_fp"] if blk["signs"] is None else ctx.hadamard_rotate(blk["X_fp"], blk["signs"])
+    X = blk["X"] if blk["X"] is not None else ctx.act_fakequant(X_fp, cfg.act_bits)
+    Hs = ctx.build_hessians(X, X_fp, blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, alpha=0.25)
     layers = (("q", "Wq", "Hin_qk", "Hout_q", "R_qk", cfg.n_q_heads), ("k", "Wk", "Hin_qk", "Hout_k", "R_qk", cfg.n_kv_heads),
               ("v", "Wv", "Hin_v", "Hout_v", "R_v", cfg.n_kv_heads))
 

@@ -27,7 +27,8 @@ class BlockConfig:
     n_outlier: int = 0               # 0 -> 1% of d_model
     outlier_scale: float = 20.0
     noise: float = 0.05              # X = X_fp + noise * rms(X_fp) * N(0,1)
-    rotate: bool = False             # config 5: X_fp <- X_fp diag(+-1) H / sqrt(d)
+    rotate: bool = False             # config 5: the block comes with random signs; X_fp <- X_fp diag(signs) H / sqrt(d) is a step
+                                     # of the method (the library's tboa_hadamard_rotate) applied by the pipeline
     act_bits: int = 0                # config 5: X is the per-token fake-quant of X_fp (done by the library)
     bits: int = 2
     block: int = 32
@@ -66,25 +67,13 @@ def _torch_dtype(name):
     return {"fp32": torch.float32, "bf16": torch.bfloat16}[name]
 
 
-def _fwht_last(x):
-    """Unnormalised Walsh-Hadamard transform along the last axis (length a power of two)."""
-    n = x.shape[-1]
-    h = 1
-    y = x
-    while h < n:
-        y = y.reshape(*x.shape[:-1], n // (2 * h), 2, h)
-        y = torch.stack((y[..., 0, :] + y[..., 1, :], y[..., 0, :] - y[..., 1, :]), dim=-2)
-        y = y.reshape(*x.shape[:-1], n)
-        h *= 2
-    return y
-
-
 def make_block(cfg: BlockConfig, seed: int = 0, device="cpu"):
     """Weights and calibration activations of one attention block.
 
-    Returns dict(Wq [Hq*dh,d], Wk, Wv [Hkv*dh,d], Wo [d,Hq*dh], X_fp [S,L,d], X [S,L,d] or None).
+    Returns dict(Wq [Hq*dh,d], Wk, Wv [Hkv*dh,d], Wo [d,Hq*dh], X_fp [S,L,d], X [S,L,d] or None, signs [d] or None).
     X is None when cfg.act_bits > 0: then the quantized-path input is the fake-quantized X_fp,
-    which is a step of the method and is left to the library."""
+    which is a step of the method and is left to the library.  signs (+-1, fp32) is given when
+    cfg.rotate: X_fp is then the activation BEFORE the randomised Hadamard rotation."""
     dev = torch.device(device)
     g = torch.Generator(device=dev)
     g.manual_seed(1000003 * seed + 17)
@@ -115,14 +104,13 @@ def make_block(cfg: BlockConfig, seed: int = 0, device="cpu"):
             num = normal(cfg.seq_len, n_out)
             den = (normal(cfg.seq_len, n_out, 3) ** 2).sum(-1).div(3.0).sqrt()
             x[:, ch] = cfg.outlier_scale * num / den
-        if cfg.rotate:
-            x = _fwht_last(x * signs) / math.sqrt(d)
         X_fp[s] = x.to(dt)
         if X is not None:
             rms = x.pow(2).mean().sqrt()
             X[s] = (x + cfg.noise * rms * normal(cfg.seq_len, d)).to(dt)
     out["X_fp"] = X_fp
     out["X"] = X
+    out["signs"] = signs
     return out
 
 

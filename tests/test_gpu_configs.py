@@ -28,6 +28,13 @@ def build(lib, name):
     print("building the %s-shaped block (%d sequences) and its Hessians" % (name, N_SEQS), flush=True)
     blk = synth.make_block(cfg, seed=0, device="cuda")
     ctx = lib.Context()
+    if blk["signs"] is not None:     # the library's rotation: sampled tokens against the explicit Hadamard product
+        rot = ctx.hadamard_rotate(blk["X_fp"], blk["signs"])
+        tok = torch.tensor(np.sort(np.random.default_rng(16).choice(cfg.n_tokens, 16, replace=False)), device="cuda")
+        want = O.hadamard_rotate(f64(blk["X_fp"].reshape(-1, cfg.d_model)[tok]), f64(blk["signs"]))
+        got = f64(rot.reshape(-1, cfg.d_model)[tok])
+        assert np.abs(got - want).max() <= 2.0 ** -8 * np.abs(want).max()
+        blk["X_fp"] = rot
     if blk["X"] is None:
         blk["X"] = ctx.act_fakequant(blk["X_fp"], cfg.act_bits)
     Hs = ctx.build_hessians(blk["X"], blk["X_fp"], blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], cfg.n_q_heads, cfg.n_kv_heads,

@@ -112,3 +112,31 @@ def test_act_fakequant(ctx, dtype):
     want = O.act_fakequant_per_token(np64(X), 4)
     want_t = torch.tensor(want).to(dtype).float().numpy()          # the output is stored in the input's type
     assert np.array_equal(got.float().cpu().numpy(), want_t)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("d", [16, 32, 64, 128, 256, 512, 2048, 4096, 8192, 16384])
+def test_hadamard_rotate(ctx, dtype, d):
+    """Every decomposition of the index bits into rounds (partial first round, 1 .. 3 full rounds) against the oracle."""
+    g = torch.Generator(device="cuda"); g.manual_seed(d)
+    n_tok = 37 if d <= 4096 else 5
+    X = torch.randn(n_tok, d, generator=g, device="cuda")
+    X[:, 3] *= 50
+    X = X.to(dtype)
+    signs = (torch.randint(0, 2, (d,), generator=g, device="cuda").float() * 2 - 1)
+    got = ctx.hadamard_rotate(X, signs)
+    want = O.hadamard_rotate(np64(X), np64(signs))
+    err = np.abs(np64(got) - want).max() / np.abs(want).max()
+    print("hadamard d=%d %s: max err / max |y| = %.2e" % (d, dtype, err), flush=True)
+    assert err <= (1e-6 if dtype == torch.float32 else 2.0 ** -8)           # fp32 butterflies; bf16 storage of the result
+    plain = ctx.hadamard_rotate(X)                                            # no signs; in place
+    buf = X.clone(); ctx.hadamard_rotate(buf, None, out=buf)
+    assert torch.equal(plain, buf)
+    assert np.abs(np64(plain) - O.hadamard_rotate(np64(X))).max() / np.abs(want).max() <= (1e-6 if dtype == torch.float32 else 2.0 ** -8)
+
+
+def test_hadamard_rotate_rejects_bad_sizes(ctx, lib):
+    X = torch.zeros(4, 48, device="cuda")
+    with pytest.raises(lib.TurboBoAError) as e:
+        ctx.hadamard_rotate(X)
+    assert e.value.code == -1

@@ -216,6 +216,35 @@ def test_act_fakequant():
     assert np.allclose(O.act_fakequant_per_token(np.zeros((2, 8)), 4), 0.0)
 
 
+def test_hadamard_rotation_is_the_sylvester_transform():
+    """Pins of the rotation: entries (-1)^popcount(i & j), orthogonality, a brute-force butterfly, one-hot inputs."""
+    d = 64
+    H = O.hadamard_matrix(d)
+    pc = np.array([[bin(i & j).count("1") for j in range(d)] for i in range(d)])
+    assert np.array_equal(H, (-1.0) ** pc)
+    assert np.array_equal(H @ H.T, d * np.eye(d))
+    X = rng(21).standard_normal((7, d)); sg = np.where(rng(22).random(d) < 0.5, -1.0, 1.0)
+    Y = O.hadamard_rotate(X, sg)
+    assert np.allclose(np.linalg.norm(Y, axis=1), np.linalg.norm(X, axis=1), rtol=1e-12)          # orthogonal: norms kept
+    assert np.allclose(O.hadamard_rotate(Y) * sg, X, atol=1e-12)                                   # H / sqrt(d) is an involution
+    # textbook in-place butterfly network written out on plain lists
+    def fwht(v):
+        v = list(v); h = 1
+        while h < len(v):
+            for i in range(0, len(v), 2 * h):
+                for j in range(i, i + h):
+                    v[j], v[j + h] = v[j] + v[j + h], v[j] - v[j + h]
+            h *= 2
+        return np.array(v) / np.sqrt(len(v))
+    for t in range(3):
+        assert np.allclose(Y[t], fwht(X[t] * sg), atol=1e-12)
+    e = np.zeros(d); e[5] = 1.0
+    assert np.allclose(O.hadamard_rotate(e[None])[0], H[5] / 8.0)
+    # outlier channels are spread: the largest |entry| of a row with one dominant channel drops by about sqrt(d)
+    Xo = rng(23).standard_normal((4, d)); Xo[:, 3] *= 100
+    assert np.abs(O.hadamard_rotate(Xo)).max() < np.abs(Xo).max() / 4
+
+
 # ---------------------------------------------------------------- eq. 3
 
 def test_chol_inv_upper_textbook():
