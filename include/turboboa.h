@@ -156,6 +156,22 @@ int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* desc,
                         double* loss, double* loss_per_head);
 
 /* ------------------------------------------------------------------------------------------------
+ * Deployable form of the result (the reduced memory footprint is the purpose of weight quantization, Sec. 1).
+ * The codes of a row form a little-endian bit stream: code c occupies bits [bits*c, bits*c + bits) of the stream, which is
+ * stored as 32-bit words (bit i of the stream = bit i % 32 of word i / 32); every row starts on a word and is padded
+ * with zero bits to tboa_packed_words_per_row(d_in, bits) = ceil(d_in * bits / 32) words.  A 3-bit code may straddle two
+ * words.  bits in {2, 3, 4, 8}.
+ */
+int64_t tboa_packed_words_per_row(int d_in, int bits);   /* host value, no context needed; 0 for non-positive arguments */
+/*   codes  [d_out, d_in] uint8 (as written by tboa_quantize_layer)  ->  packed [d_out, words_per_row] uint32 */
+int tboa_pack_codes(tboa_ctx* ctx, int d_out, int d_in, int bits, const uint8_t* codes, uint32_t* packed);
+/* y = W_deq x from the packed form alone: y[r] = sum_c scales[r, c/g] (code[r, c] - zeros[r, c/g]) x[c].
+ *   packed as above; scales, zeros [d_out, n_groups] fp32 (group = 0: one group per row); x [d_in], y [d_out] fp32.
+ * A check that the packed codes, scales and zeros carry the quantized layer; accumulation in fp64. */
+int tboa_dequant_gemv(tboa_ctx* ctx, int d_out, int d_in, int bits, int group, const uint32_t* packed,
+                      const float* scales, const float* zeros, const float* x, float* y);
+
+/* ------------------------------------------------------------------------------------------------
  * Building blocks, exported for stage-isolated checks and for roofline measurement.
  */
 

@@ -330,6 +330,31 @@ def cd_refine(W, Wbar_int, s, H_in, H_out, R, n_iter, group=0):
 
 
 # --------------------------------------------------------------------------
+# packed form of the codes
+# --------------------------------------------------------------------------
+
+def pack_codes(codes, bits):
+    """Row-wise little-endian bit stream: code c occupies bits [bits*c, bits*c + bits); stored as uint32 words
+    (bit i of the stream is bit i % 32 of word i // 32), each row padded with zero bits to whole words."""
+    codes = np.asarray(codes)
+    d_out, d_in = codes.shape
+    wpr = (d_in * bits + 31) // 32
+    stream = np.zeros((d_out, wpr * 32), np.uint8)
+    for b in range(bits):
+        stream[:, b:d_in * bits:bits] = (codes >> b) & 1
+    weights = (np.uint64(1) << np.arange(32, dtype=np.uint64))
+    return (stream.reshape(d_out, wpr, 32).astype(np.uint64) * weights).sum(axis=2).astype(np.uint32)
+
+
+def dequant_matvec(codes, scales, zeros, x, group=0):
+    """y = W_deq x with W_deq = scales (codes - zeros), (scale, zero) per row and group of in-channels."""
+    codes = np.asarray(codes, F64)
+    gsz = group if group else codes.shape[1]
+    Wd = np.repeat(np.asarray(scales, F64), gsz, axis=1) * (codes - np.repeat(np.asarray(zeros, F64), gsz, axis=1))
+    return Wd @ np.asarray(x, F64)
+
+
+# --------------------------------------------------------------------------
 # losses
 # --------------------------------------------------------------------------
 

@@ -57,6 +57,9 @@ def _load():
         "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 10, i32),
         "tboa_act_fakequant": ([vp, i64, i32, i32, i32, vp, vp], i32),
         "tboa_hadamard_rotate": ([vp, i64, i32, i32, vp, vp, vp], i32),
+        "tboa_packed_words_per_row": ([i32, i32], i64),
+        "tboa_pack_codes": ([vp, i32, i32, i32, vp, vp], i32),
+        "tboa_dequant_gemv": ([vp, i32, i32, i32, i32, vp, vp, vp, vp, vp], i32),
         "tboa_quantize_layer": ([vp, C.POINTER(LayerDesc)] + [vp] * 8 + [C.POINTER(f64), C.POINTER(f64)], i32),
         "tboa_counter": ([vp, i32], i64),
         "tboa_profile_enable": ([vp, i32], i32),
@@ -227,6 +230,22 @@ class Context:
         d = X.shape[-1]
         self._check(_lib.tboa_hadamard_rotate(self._h, X.numel() // d, d, _dtype_code(X), _ptr(X), _ptr(signs), _ptr(out)))
         return out
+
+    def pack_codes(self, codes, bits):
+        """uint8 codes [d_out, d_in] -> int32 tensor [d_out, ceil(d_in * bits / 32)] holding the little-endian bit stream."""
+        _dev(codes, torch.uint8)
+        d_out, d_in = codes.shape
+        wpr = int(_lib.tboa_packed_words_per_row(d_in, bits))
+        packed = torch.empty(d_out, max(wpr, 1), dtype=torch.int32, device=codes.device)
+        self._check(_lib.tboa_pack_codes(self._h, d_out, d_in, bits, _ptr(codes), _ptr(packed)))
+        return packed
+
+    def dequant_gemv(self, packed, scales, zeros, x, d_in, bits, group=0):
+        _dev(packed, torch.int32); _dev(scales, torch.float32); _dev(zeros, torch.float32); _dev(x, torch.float32)
+        d_out = packed.shape[0]
+        y = torch.empty(d_out, dtype=torch.float32, device=x.device)
+        self._check(_lib.tboa_dequant_gemv(self._h, d_out, d_in, bits, group, _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(x), _ptr(y)))
+        return y
 
     def quantize_layer(self, W, H_in, H_out, R, n_heads, bits, block, group=0, cd_iters=1, adaptive_grid=True,
                        grid_points=100, max_shrink=0.8, damp=0.01):

@@ -107,3 +107,35 @@ def test_error_paths(ctx, lib):
     assert e.value.code == -2
     ok = ctx.quantize_layer(t(W), t(Hbad), t(Hout), None, 2, bits=2, block=4, damp=0.01)   # damping repairs it
     assert np.isfinite(ok["loss"])
+
+
+@pytest.mark.parametrize("bits,group", [(2, 0), (3, 0), (3, 64), (4, 32), (8, 0)])
+def test_packed_codes_and_dequant_gemv(ctx, bits, group):
+    """Packing is bit-exact against the oracle's bit stream (ragged row lengths); the packed form reproduces W_deq x."""
+    r = np.random.default_rng(100 + bits)
+    for d_out, d_in in ((37, 200), (64, 136), (5, 4096)):
+        if group and d_in % group:
+            continue
+        codes = r.integers(0, 2 ** bits, size=(d_out, d_in)).astype(np.uint8)
+        packed = ctx.pack_codes(torch.tensor(codes, device="cuda"), bits)
+        want = O.pack_codes(codes, bits)
+        assert np.array_equal(packed.cpu().numpy().view(np.uint32), want), (bits, d_out, d_in)
+        ng = d_in // group if group else 1
+        scales = (r.random((d_out, ng)) * 0.01 + 0.001).astype(np.float32); zeros = r.integers(0, 2 ** bits, size=(d_out, ng)).astype(np.float32)
+        x = r.standard_normal(d_in).astype(np.float32)
+        y = ctx.dequant_gemv(packed, torch.tensor(scales, device="cuda"), torch.tensor(zeros, device="cuda"), torch.tensor(x, device="cuda"),
+                             d_in, bits, group)
+        ref = O.dequant_matvec(codes, scales, zeros, x, group)
+        assert np.allclose(y.cpu().numpy(), ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+
+
+def test_packed_layer_carries_the_quantized_weights(ctx):
+    """quantize_layer -> pack -> GEMV from the packed form equals W_deq x."""
+    W, Hin, Hout, R = make_case(11, 2, 32, 256, T=1024)
+    t = lambda a: torch.tensor(a, device="cuda")
+    got = ctx.quantize_layer(t(W), t(Hin), t(Hout), t(R), 2, bits=3, block=8, group=64)
+    packed = ctx.pack_codes(got["codes"], 3)
+    x = torch.randn(256, device="cuda")
+    y = ctx.dequant_gemv(packed, got["scales"], got["zeros"], x, 256, 3, 64)
+    ref = got["W_deq"].double() @ x.double()
+    assert torch.allclose(y.double(), ref, rtol=1e-5, atol=1e-6 * ref.abs().max().item())

@@ -245,6 +245,25 @@ def test_hadamard_rotation_is_the_sylvester_transform():
     assert np.abs(O.hadamard_rotate(Xo)).max() < np.abs(Xo).max() / 4
 
 
+def test_pack_codes_bit_stream():
+    """Hand-computed words, and an independent unpacking through Python integers."""
+    assert O.pack_codes(np.array([[1, 2, 3, 0]]), 2).tolist() == [[1 | 2 << 2 | 3 << 4]]
+    assert O.pack_codes(np.array([[7, 0, 5]]), 3).tolist() == [[7 | 5 << 6]]
+    assert O.pack_codes(np.array([[0xAB, 0xCD, 0xEF, 0x01, 0x23]]), 8).tolist() == [[0x01EFCDAB, 0x23]]
+    # eleven 3-bit codes: the eleventh (bits 30..32) straddles the word boundary
+    c = np.array([[1, 2, 3, 4, 5, 6, 7, 0, 1, 2, 5, 3]])
+    big = sum(int(v) << (3 * i) for i, v in enumerate(c[0]))
+    assert O.pack_codes(c, 3).tolist() == [[big & 0xFFFFFFFF, big >> 32]]
+    for bits in (2, 3, 4, 8):
+        codes = rng(30 + bits).integers(0, 2 ** bits, size=(5, 77))
+        P = O.pack_codes(codes, bits)
+        assert P.shape == (5, (77 * bits + 31) // 32) and P.dtype == np.uint32
+        for r in range(5):
+            big = sum(int(w) << (32 * i) for i, w in enumerate(P[r]))
+            assert [(big >> (bits * k)) & (2 ** bits - 1) for k in range(77)] == codes[r].tolist()
+            assert big >> (bits * 77) == 0                      # padding bits are zero
+
+
 # ---------------------------------------------------------------- eq. 3
 
 def test_chol_inv_upper_textbook():
