@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-R", action="store_true", help="first-block setting: no upstream deviation (R = 0)")
     ap.add_argument("--n-seqs", type=int, default=0, help="override the number of calibration sequences (profiling runs)")
+    ap.add_argument("--with-mlp", action="store_true",
+                    help="also time the gated MLP of the same transformer block (reported beside the metric, never inside `value`)")
     ap.add_argument("--roofline-probe", action="store_true",
                     help="run one plain 1 GiB copy and one launch of the dominant kernel in the benchmark's launch shape, nothing else "
                          "(the command for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
@@ -185,6 +187,18 @@ def main():
         "grid_search": {"two_phase_passes": ctx.counter(0), "passes_fully_exact": ctx.counter(1), "rows_fully_exact": ctx.counter(2)},
         "roofline": roofline,
     }
+    if args.with_mlp:
+        from paper_2602_04929_amd.pipeline import quantize_mlp
+        mlp = synth.make_mlp(cfg, seed=0, device="cuda:0")
+        quantize_mlp(ctx, mlp, cfg, use_R=use_R)
+        tm = {}
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        quantize_mlp(ctx, mlp, cfg, use_R=use_R, timings=tm)
+        torch.cuda.synchronize()
+        rec["mlp"] = {"seconds": time.perf_counter() - t0, "d_ff": cfg.d_ff, "stage_seconds": tm,
+                      "note": "gate, up, down projections of the same block (H_out = I), outside `value`"}
+        del mlp
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(blk, cfg, out["hessians"], "")
     print(json.dumps(rec))

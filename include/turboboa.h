@@ -105,6 +105,20 @@ int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* desc,
                                 const void* Wq, const void* Wk, const void* Wv,
                                 float* Hin_o, float* R_o);
 
+/* Gated MLP of the same transformer block (W_gate, W_up: [d_ff, d]; W_down: [d, d_ff]).  Its three projections are plain
+ * linear layers: the layer-wise row of Table 1 (H = X X^T (x) I, no out-channel coupling), quantized by
+ * tboa_quantize_layer with H_out = NULL, and with the deviation correlation R of Prop. 3.2 when the input of the
+ * full-precision model is given.
+ *   X, X_fp [n_tokens, d_in] (x_dtype; X_fp and R both NULL or both given)
+ *   H_in [d_in, d_in] = sum_t x_t x_t^T,  R [d_in, d_in] = alpha sum_t (x_t - x~_t) x_t^T   (fp32, caller-allocated) */
+int tboa_build_hessian_linear(tboa_ctx* ctx, int64_t n_tokens, int d_in, int x_dtype, double alpha,
+                              const void* X, const void* X_fp, float* H_in, float* R);
+/* Input of the down projection: Act = silu(X W_gate^T) * (X W_up^T), silu(g) = g / (1 + exp(-g)).
+ *   X [n_tokens, d] (x_dtype); W_gate, W_up [d_ff, d] in w_dtype: x_dtype, or TBOA_F32 for dequantized weights (then used
+ *   as exact-to-16-bit (hi, lo) bf16 pairs on the bf16 path); Act [n_tokens, d_ff] (x_dtype). */
+int tboa_swiglu_forward(tboa_ctx* ctx, int64_t n_tokens, int d, int d_ff, int x_dtype, const void* X,
+                        int w_dtype, const void* W_gate, const void* W_up, void* Act);
+
 /* Min-Max dynamic per-token activation quantizer (weight-activation experiments): one asymmetric
  * (scale, zero) per token from that token's min and max, `bits` levels; writes the dequantized
  * activations.  X_in, X_out [T, d] in `dtype` (TBOA_F32 or TBOA_BF16); may alias. */

@@ -134,6 +134,24 @@ def build_hessian_out_proj(X, X_fp, Wq_deq, Wk_deq, Wv_deq, Wq, Wk, Wv,
     return Hin_o, R_o
 
 
+def build_hessian_linear(X, X_fp=None, alpha=0.0):
+    """Layer-wise row of Table 1 for a plain linear layer (the MLP projections): H_in = sum_t x_t x_t^T and, with the
+    full-precision input given, R = alpha sum_t (x_t - x~_t) x_t^T (Algorithm 1, line 5).  X [.., d_in]."""
+    X2 = np.asarray(X, F64).reshape(-1, np.shape(X)[-1])
+    H = X2.T @ X2
+    if X_fp is None:
+        return H, None
+    Xf2 = np.asarray(X_fp, F64).reshape(X2.shape)
+    return H, alpha * (X2 - Xf2).T @ X2
+
+
+def swiglu(X, Wg, Wu):
+    """Input of the down projection of a gated MLP: silu(X Wg^T) * (X Wu^T), silu(g) = g / (1 + exp(-g))."""
+    G = np.asarray(X, F64) @ np.asarray(Wg, F64).T
+    U = np.asarray(X, F64) @ np.asarray(Wu, F64).T
+    return G / (1.0 + np.exp(-G)) * U
+
+
 def act_fakequant_per_token(X, bits):
     """Min-Max dynamic per-token activation quantizer (asymmetric), returned dequantized.
     One (scale, zero) per token from that token's own min and max."""

@@ -57,6 +57,8 @@ def _load():
         "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 10, i32),
         "tboa_act_fakequant": ([vp, i64, i32, i32, i32, vp, vp], i32),
         "tboa_hadamard_rotate": ([vp, i64, i32, i32, vp, vp, vp], i32),
+        "tboa_build_hessian_linear": ([vp, i64, i32, i32, f64, vp, vp, vp, vp], i32),
+        "tboa_swiglu_forward": ([vp, i64, i32, i32, i32, vp, i32, vp, vp, vp], i32),
         "tboa_packed_words_per_row": ([i32, i32], i64),
         "tboa_pack_codes": ([vp, i32, i32, i32, vp, vp], i32),
         "tboa_dequant_gemv": ([vp, i32, i32, i32, i32, vp, vp, vp, vp, vp], i32),
@@ -229,6 +231,26 @@ class Context:
         out = torch.empty_like(X) if out is None else out
         d = X.shape[-1]
         self._check(_lib.tboa_hadamard_rotate(self._h, X.numel() // d, d, _dtype_code(X), _ptr(X), _ptr(signs), _ptr(out)))
+        return out
+
+    def build_hessian_linear(self, X, X_fp=None, alpha=0.0):
+        """H_in = X^T X and R = alpha (X - X_fp)^T X of a plain linear layer; X [.., d_in]."""
+        _dev(X)
+        d = X.shape[-1]
+        H = torch.empty(d, d, dtype=torch.float32, device=X.device)
+        R = None
+        if X_fp is not None:
+            _dev(X_fp, X.dtype)
+            R = torch.empty_like(H)
+        self._check(_lib.tboa_build_hessian_linear(self._h, X.numel() // d, d, _dtype_code(X), alpha, _ptr(X), _ptr(X_fp), _ptr(H), _ptr(R)))
+        return H, R
+
+    def swiglu_forward(self, X, Wg, Wu):
+        """silu(X Wg^T) * (X Wu^T); Wg, Wu [d_ff, d] in X's type or fp32 (dequantized)."""
+        _dev(X); _dev(Wg); _dev(Wu, Wg.dtype)
+        d = X.shape[-1]; dff = Wg.shape[0]
+        out = torch.empty(*X.shape[:-1], dff, dtype=X.dtype, device=X.device)
+        self._check(_lib.tboa_swiglu_forward(self._h, X.numel() // d, d, dff, _dtype_code(X), _ptr(X), _dtype_code(Wg), _ptr(Wg), _ptr(Wu), _ptr(out)))
         return out
 
     def pack_codes(self, codes, bits):

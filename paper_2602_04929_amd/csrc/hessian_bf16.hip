@@ -233,17 +233,17 @@ GemmBf16 nt(int M, int N, int K, float alpha, const bf16* A, long long lda, cons
 }
 
 // out[n, n] = scale * A B^T with the contraction over all T tokens split into `splits` chunks
-int gram_splitk(const Dims& D, int n, const bf16* A, const bf16* A_lo, const bf16* B, long long ld, int K, double scale, int lower,
+int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_lo, const bf16* B, long long ld, int K, double scale, int lower,
                 float* part, float* out) {
-    const int splits = pick_splits(D.S), Kc = K / splits;
+    const int Kc = K / splits;
     GemmBf16 g = nt(n, n, Kc, 1.f, A, ld, B, ld, part, n, TBOA_F32, 0, lower ? TBOA_GEMM_LOWER : 0);
     g.tag = TBOA_PROF_GRAM;
     g.batch = splits; g.strideA = Kc; g.strideB = Kc; g.strideC = (long long)n * n;
-    if (lower) TB_TRY(launch_fill_f32(D.ctx, part, (int64_t)splits * n * n, 0.f));
-    TB_TRY(gemm_bf16_nt(D.ctx, g));
-    if (A_lo) { g.A = A_lo; g.accumulate = 1; TB_TRY(gemm_bf16_nt(D.ctx, g)); }
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(g1((long long)n * n)), dim3(256), 0, D.ctx->stream, part, splits, n, scale, lower, out);
-    TB_HIP(D.ctx, hipGetLastError());
+    if (lower) TB_TRY(launch_fill_f32(ctx, part, (int64_t)splits * n * n, 0.f));
+    TB_TRY(gemm_bf16_nt(ctx, g));
+    if (A_lo) { g.A = A_lo; g.accumulate = 1; TB_TRY(gemm_bf16_nt(ctx, g)); }
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(g1((long long)n * n)), dim3(256), 0, ctx->stream, part, splits, n, scale, lower, out);
+    TB_HIP(ctx, hipGetLastError());
     return 0;
 }
 
@@ -320,8 +320,8 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     hipStream_t st = ctx->stream;
     // ---- H_in and R for W_Q / W_K
     TB_TRY(transpose(D, X, fp ? X_fp : nullptr, dm, T, dm, XT, fp ? dXh : nullptr, dXl, TP));
-    TB_TRY(gram_splitk(D, dm, XT, nullptr, XT, TP, T, 1.0, 1, part, Hin_qk));
-    if (fp && R_qk) TB_TRY(gram_splitk(D, dm, dXh, dXl, XT, TP, T, d->alpha, 0, part, R_qk));
+    TB_TRY(gram_splitk(ctx, splits, dm, XT, nullptr, XT, TP, T, 1.0, 1, part, Hin_qk));
+    if (fp && R_qk) TB_TRY(gram_splitk(ctx, splits, dm, dXh, dXl, XT, TP, T, d->alpha, 0, part, R_qk));
     // ---- H_out: K_g^T K_g = W_K,g H_in W_K,g^T ; sum_h Q_h^T Q_h ; sum_h W_out,h^T W_out,h   (fp64)
     TB_TRY(launch_cvt_f32_to_f64(ctx, Hin_qk, Hin64, dd));
     TB_TRY(launch_cvt_to_f64(ctx, Wq, TBOA_BF16, Wq64, (int64_t)dq * dm));
@@ -460,8 +460,74 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             if (fp) { o.A = VTc + ((long long)sl * nsg + 2) * L; o.B = P + L; o.C = dOT + t0 + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, o)); }
         }
     }
-    TB_TRY(gram_splitk(D, dq, OT, nullptr, OT, TP, T, 1.0, 1, part, Hin_o));
-    if (fp) TB_TRY(gram_splitk(D, dq, dOT, nullptr, OT, TP, T, d->alpha, 0, part, R_o));
+    TB_TRY(gram_splitk(ctx, splits, dq, OT, nullptr, OT, TP, T, 1.0, 1, part, Hin_o));
+    if (fp) TB_TRY(gram_splitk(ctx, splits, dq, dOT, nullptr, OT, TP, T, d->alpha, 0, part, R_o));
+    return 0;
+}
+
+// Act[t, c] = silu(G[t, c]) U[t, c], silu(g) = g / (1 + exp(-g))
+template <typename TO>
+__global__ void swiglu_kernel(const float* __restrict__ G, const float* __restrict__ U, TO* __restrict__ out, long long n) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+        const float g = G[i];
+        out[i] = (TO)((g / (1.0f + __expf(-g))) * U[i]);
+    }
+}
+
+// layer-wise Hessian of a plain linear layer from bf16 activations: H = X^T X, R = alpha (X - X~)^T X
+int build_hessian_linear_bf16(tboa_ctx* ctx, long long T, int n, double alpha, const bf16* X, const bf16* X_fp, float* H_in, float* R) {
+    if (T % 8 || n % 8) return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_linear: n_tokens and d_in must be multiples of 8 for bf16 inputs");
+    int splits = 1;
+    for (int sp = 16; sp > 1; --sp) if (T % ((long long)sp * 256) == 0) { splits = sp; break; }
+    const bool fp = X_fp && R;
+    const long long TP = T + PADE;
+    bf16 *XT, *dXh, *dXl; float* part;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        XT = ar.get<bf16>((size_t)n * TP);
+        dXh = fp ? ar.get<bf16>((size_t)n * TP) : nullptr; dXl = fp ? ar.get<bf16>((size_t)n * TP) : nullptr;
+        part = ar.get<float>((size_t)splits * n * n);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    Dims D{}; D.ctx = ctx;
+    TB_TRY(transpose(D, X, fp ? X_fp : nullptr, n, (int)T, n, XT, fp ? dXh : nullptr, dXl, TP));
+    TB_TRY(gram_splitk(ctx, splits, n, XT, nullptr, XT, TP, (int)T, 1.0, 1, part, H_in));
+    if (fp) TB_TRY(gram_splitk(ctx, splits, n, dXh, dXl, XT, TP, (int)T, alpha, 0, part, R));
+    return 0;
+}
+
+// Act = silu(X Wg^T) * (X Wu^T) for bf16 activations; weights bf16, or fp32 taken as exact-to-16-bits (hi, lo) bf16 pairs
+int swiglu_forward_bf16(tboa_ctx* ctx, long long T, int d, int dff, const bf16* X, int w_dtype, const void* Wg, const void* Wu, bf16* Act) {
+    if (d % 8 || dff % 8) return tboa_fail(ctx, TBOA_EINVAL, "swiglu_forward: d and d_ff must be multiples of 8 for bf16 inputs");
+    const bool split = (w_dtype == TBOA_F32);
+    const long long chunk = 16384;
+    bf16 *Wgh = nullptr, *Wgl = nullptr, *Wuh = nullptr, *Wul = nullptr; float *G, *U;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        if (split) { Wgh = ar.get<bf16>((size_t)dff * d); Wgl = ar.get<bf16>((size_t)dff * d); Wuh = ar.get<bf16>((size_t)dff * d); Wul = ar.get<bf16>((size_t)dff * d); }
+        G = ar.get<float>((size_t)chunk * dff); U = ar.get<float>((size_t)chunk * dff);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    hipStream_t st = ctx->stream;
+    const bf16* g_hi = (const bf16*)Wg; const bf16* u_hi = (const bf16*)Wu;
+    if (split) {
+        hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dff * d)), dim3(256), 0, st, (const float*)Wg, Wgh, Wgl, (long long)dff * d);
+        hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dff * d)), dim3(256), 0, st, (const float*)Wu, Wuh, Wul, (long long)dff * d);
+        TB_KERNEL_CHECK(ctx);
+        g_hi = Wgh; u_hi = Wuh;
+    }
+    for (long long t0 = 0; t0 < T; t0 += chunk) {
+        const int rows = (int)((T - t0 < chunk) ? T - t0 : chunk);
+        const bf16* Xc = X + t0 * d;
+        TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, g_hi, d, G, dff, TBOA_F32, 0, 0)));
+        TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, u_hi, d, U, dff, TBOA_F32, 0, 0)));
+        if (split) {
+            TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, Wgl, d, G, dff, TBOA_F32, 1, 0)));
+            TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, Wul, d, U, dff, TBOA_F32, 1, 0)));
+        }
+        hipLaunchKernelGGL(swiglu_kernel<bf16>, dim3(g1((long long)rows * dff)), dim3(256), 0, st, G, U, Act + t0 * dff, (long long)rows * dff);
+        TB_KERNEL_CHECK(ctx);
+    }
     return 0;
 }
 
@@ -536,4 +602,24 @@ extern "C" int tboa_act_fakequant(tboa_ctx* ctx, int64_t n_tokens, int d, int bi
     else return tboa_fail(ctx, TBOA_EINVAL, "act_fakequant: dtype must be fp32 or bf16");
     TB_KERNEL_CHECK(ctx);
     return 0;
+}
+
+extern "C" int tboa_build_hessian_linear(tboa_ctx* ctx, int64_t n_tokens, int d_in, int x_dtype, double alpha, const void* X, const void* X_fp,
+                                         float* H_in, float* R) {
+    if (!ctx) return TBOA_EINVAL;
+    if (n_tokens <= 0 || n_tokens > 2147483647LL || d_in <= 0 || !X || !H_in) return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_linear: bad arguments");
+    if ((X_fp != nullptr) != (R != nullptr)) return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_linear: X_fp and R go together");
+    if (x_dtype == TBOA_F32) return build_hessian_linear_f64(ctx, n_tokens, d_in, alpha, (const float*)X, (const float*)X_fp, H_in, R);
+    if (x_dtype == TBOA_BF16) return build_hessian_linear_bf16(ctx, n_tokens, d_in, alpha, (const bf16*)X, (const bf16*)X_fp, H_in, R);
+    return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_linear: x_dtype must be fp32 or bf16");
+}
+
+extern "C" int tboa_swiglu_forward(tboa_ctx* ctx, int64_t n_tokens, int d, int d_ff, int x_dtype, const void* X, int w_dtype, const void* Wg,
+                                   const void* Wu, void* Act) {
+    if (!ctx) return TBOA_EINVAL;
+    if (n_tokens <= 0 || n_tokens > 2147483647LL || d <= 0 || d_ff <= 0 || !X || !Wg || !Wu || !Act) return tboa_fail(ctx, TBOA_EINVAL, "swiglu_forward: bad arguments");
+    if (w_dtype != TBOA_F32 && w_dtype != x_dtype) return tboa_fail(ctx, TBOA_EINVAL, "swiglu_forward: weights must be fp32 or of the activations' type");
+    if (x_dtype == TBOA_F32) return swiglu_forward_f64(ctx, n_tokens, d, d_ff, (const float*)X, (const float*)Wg, (const float*)Wu, (float*)Act);
+    if (x_dtype == TBOA_BF16) return swiglu_forward_bf16(ctx, n_tokens, d, d_ff, (const bf16*)X, w_dtype, Wg, Wu, (bf16*)Act);
+    return tboa_fail(ctx, TBOA_EINVAL, "swiglu_forward: x_dtype must be fp32 or bf16");
 }

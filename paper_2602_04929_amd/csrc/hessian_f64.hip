@@ -180,3 +180,52 @@ int build_hessian_out_proj_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const voi
     }
     return 0;
 }
+
+namespace {
+__global__ void swiglu_f64_kernel(const double* __restrict__ G, const double* __restrict__ U, float* __restrict__ out, long long n) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+        const double g = G[i];
+        out[i] = (float)((g / (1.0 + exp(-g))) * U[i]);
+    }
+}
+}  // namespace
+
+// fp32 inputs: H = X^T X and R = alpha (X - X~)^T X on the fp64 matrix cores
+int build_hessian_linear_f64(tboa_ctx* ctx, long long T, int n, double alpha, const float* X, const float* X_fp, float* H_in, float* R) {
+    const bool fp = X_fp && R;
+    double *X64, *Xf64, *H64;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        X64 = ar.get<double>((size_t)T * n); Xf64 = fp ? ar.get<double>((size_t)T * n) : nullptr; H64 = ar.get<double>((size_t)n * n);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    TB_TRY(launch_cvt_to_f64(ctx, X, TBOA_F32, X64, (int64_t)T * n));
+    TB_TRY(gemm_f64(ctx, mk(n, n, (int)T, 1.0, X64, 1, n, X64, n, 1, 0.0, H64, n)));
+    TB_TRY(launch_cvt_f64_to_f32(ctx, H64, H_in, (int64_t)n * n));
+    if (fp) {
+        TB_TRY(launch_cvt_to_f64(ctx, X_fp, TBOA_F32, Xf64, (int64_t)T * n));
+        TB_TRY(launch_sub_f64(ctx, X64, Xf64, Xf64, (int64_t)T * n));
+        TB_TRY(gemm_f64(ctx, mk(n, n, (int)T, alpha, Xf64, 1, n, X64, n, 1, 0.0, H64, n)));
+        TB_TRY(launch_cvt_f64_to_f32(ctx, H64, R, (int64_t)n * n));
+    }
+    return 0;
+}
+
+int swiglu_forward_f64(tboa_ctx* ctx, long long T, int d, int dff, const float* X, const float* Wg, const float* Wu, float* Act) {
+    double *X64, *Wg64, *Wu64, *G, *U;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        X64 = ar.get<double>((size_t)T * d); Wg64 = ar.get<double>((size_t)dff * d); Wu64 = ar.get<double>((size_t)dff * d);
+        G = ar.get<double>((size_t)T * dff); U = ar.get<double>((size_t)T * dff);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    TB_TRY(launch_cvt_to_f64(ctx, X, TBOA_F32, X64, (int64_t)T * d));
+    TB_TRY(launch_cvt_to_f64(ctx, Wg, TBOA_F32, Wg64, (int64_t)dff * d));
+    TB_TRY(launch_cvt_to_f64(ctx, Wu, TBOA_F32, Wu64, (int64_t)dff * d));
+    TB_TRY(gemm_f64(ctx, mk((int)T, dff, d, 1.0, X64, d, 1, Wg64, 1, d, 0.0, G, dff)));
+    TB_TRY(gemm_f64(ctx, mk((int)T, dff, d, 1.0, X64, d, 1, Wu64, 1, d, 0.0, U, dff)));
+    long long n = T * dff, gb = (n + 255) / 256; if (gb > 16384) gb = 16384;
+    hipLaunchKernelGGL(swiglu_f64_kernel, dim3((unsigned)gb), dim3(256), 0, ctx->stream, G, U, Act, n);
+    TB_HIP(ctx, hipGetLastError());
+    return 0;
+}

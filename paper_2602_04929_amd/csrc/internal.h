@@ -126,3 +126,5 @@ int build_hessians_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, co
 int build_hessian_out_proj_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, const void* X_fp, const float* Wq_deq,
                                const float* Wk_deq, const float* Wv_deq, const void* Wq, const void* Wk, const void* Wv,
                                float* Hin_o, float* R_o);
+int build_hessian_linear_f64(tboa_ctx* ctx, long long T, int n, double alpha, const float* X, const float* X_fp, float* H_in, float* R);
+int swiglu_forward_f64(tboa_ctx* ctx, long long T, int d, int dff, const float* X, const float* Wg, const float* Wu, float* Act);

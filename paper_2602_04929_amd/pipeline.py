@@ -47,3 +47,33 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     kwo = dict(kw, block=cfg.d_model)      # H_out = I: all rows form one step
     out["o"] = stage("quantize_o", lambda: ctx.quantize_layer(blk["Wo"], Ho[0], None, Ho[1], 1, **kwo))
     return out
+
+
+def quantize_mlp(ctx, mlp, cfg, alpha=0.25, use_R=True, cd_iters=1, adaptive_grid=True, damp=0.01, timings=None):
+    """The gated MLP of the block: W_gate and W_up share their input (one Hessian), W_down sees silu(gate) * up computed
+    from the dequantized W_gate, W_up on the quantized-path input (and from the full-precision weights on the
+    full-precision input for its deviation correlation).  Every layer: tboa_quantize_layer with H_out = NULL."""
+    def stage(name, fn):
+        if timings is None:
+            return fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        out = fn()
+        torch.cuda.synchronize()
+        timings[name] = timings.get(name, 0.0) + time.perf_counter() - t
+        return out
+
+    M, M_fp = mlp["M"], mlp["M_fp"]
+    Mf = M_fp if use_R else None
+    kw = dict(bits=cfg.bits, group=cfg.group, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp)
+    out = {}
+    H, R = stage("hessian_gate_up", lambda: ctx.build_hessian_linear(M, Mf, alpha))
+    out["gate"] = stage("quantize_gate", lambda: ctx.quantize_layer(mlp["Wg"], H, None, R, 1, block=cfg.d_ff, **kw))
+    out["up"] = stage("quantize_up", lambda: ctx.quantize_layer(mlp["Wu"], H, None, R, 1, block=cfg.d_ff, **kw))
+    act = stage("swiglu", lambda: ctx.swiglu_forward(M, out["gate"]["W_deq"], out["up"]["W_deq"]))
+    act_fp = stage("swiglu", lambda: ctx.swiglu_forward(M_fp, mlp["Wg"], mlp["Wu"])) if use_R else None
+    Hd, Rd = stage("hessian_down", lambda: ctx.build_hessian_linear(act, act_fp, alpha))
+    out["down"] = stage("quantize_down", lambda: ctx.quantize_layer(mlp["Wd"], Hd, None, Rd, 1, block=cfg.d_model, **kw))
+    out["hessians"] = dict(H_gate_up=H, R_gate_up=R, H_down=Hd, R_down=Rd)
+    out["act"], out["act_fp"] = act, act_fp
+    return out

@@ -33,6 +33,7 @@ class BlockConfig:
     bits: int = 2
     block: int = 32
     group: int = 0
+    d_ff: int = 0                    # width of the gated MLP of the same transformer block (make_mlp)
 
     @property
     def d_q(self):
@@ -49,12 +50,12 @@ class BlockConfig:
 
 CONFIGS = {
     "tiny": BlockConfig("tiny", 256, 4, 4, 64, 8, 128, dtype="fp32", outlier="scale", n_outlier=4,
-                        bits=2, block=4),
-    "llama2-7b": BlockConfig("llama2-7b", 4096, 32, 32, 128, 128, 2048, bits=2, block=32),
-    "llama2-13b": BlockConfig("llama2-13b", 5120, 40, 40, 128, 128, 2048, bits=3, block=32, group=128),
-    "llama2-70b": BlockConfig("llama2-70b", 8192, 64, 8, 128, 128, 2048, bits=2, block=64),
+                        bits=2, block=4, d_ff=512),
+    "llama2-7b": BlockConfig("llama2-7b", 4096, 32, 32, 128, 128, 2048, bits=2, block=32, d_ff=11008),
+    "llama2-13b": BlockConfig("llama2-13b", 5120, 40, 40, 128, 128, 2048, bits=3, block=32, group=128, d_ff=13824),
+    "llama2-70b": BlockConfig("llama2-70b", 8192, 64, 8, 128, 128, 2048, bits=2, block=64, d_ff=28672),
     "llama2-7b-w4a4": BlockConfig("llama2-7b-w4a4", 4096, 32, 32, 128, 128, 2048, rotate=True, act_bits=4,
-                                  bits=4, block=32),
+                                  bits=4, block=32, d_ff=11008),
 }
 
 
@@ -112,6 +113,19 @@ def make_block(cfg: BlockConfig, seed: int = 0, device="cpu"):
     out["X"] = X
     out["signs"] = signs
     return out
+
+
+def make_mlp(cfg: BlockConfig, seed: int = 0, device="cpu"):
+    """Weights and calibration inputs of the gated MLP of the block: Wg, Wu [d_ff, d], Wd [d, d_ff] ~ N(0, 0.02^2),
+    M_fp [S, L, d] with the same activation recipe as make_block (Gaussian, outlier channels), M = M_fp + noise."""
+    sub = make_block(dataclasses.replace(cfg, rotate=False, act_bits=0), seed=seed + 7919, device=device)
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(1000003 * seed + 31)
+    dt = _torch_dtype(cfg.dtype)
+    w = lambda *shape: (torch.randn(*shape, generator=g, device=dev, dtype=torch.float32) * 0.02).to(dt)
+    return {"Wg": w(cfg.d_ff, cfg.d_model), "Wu": w(cfg.d_ff, cfg.d_model), "Wd": w(cfg.d_model, cfg.d_ff),
+            "M_fp": sub["X_fp"], "M": sub["X"]}
 
 
 def correlated_mix(d, rank=8, strength=0.3, seed=0, device="cpu"):

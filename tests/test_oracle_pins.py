@@ -245,6 +245,29 @@ def test_hadamard_rotation_is_the_sylvester_transform():
     assert np.abs(O.hadamard_rotate(Xo)).max() < np.abs(Xo).max() / 4
 
 
+def test_mlp_pieces():
+    """Layer-wise Hessian of a plain linear layer and the SwiGLU activation."""
+    from scipy.special import expit
+    X = rng(40).standard_normal((3, 20, 12)); Xf = X + 0.1 * rng(41).standard_normal(X.shape)
+    H, R = O.build_hessian_linear(X, Xf, 0.25)
+    X2, Xf2 = X.reshape(-1, 12), Xf.reshape(-1, 12)
+    D = rng(42).standard_normal((5, 12)); W = rng(43).standard_normal((5, 12))
+    # ||D X + W dX||^2 - ||W dX||^2 = tr(D H D^T) + 2 tr(W (R / alpha) D^T)   (App. D, first display, G = I)
+    direct = np.linalg.norm(D @ X2.T + W @ (X2 - Xf2).T) ** 2 - np.linalg.norm(W @ (X2 - Xf2).T) ** 2
+    assert np.isclose(np.trace(D @ H @ D.T) + 2 * np.trace(W @ (R / 0.25) @ D.T), direct, rtol=1e-10)
+    # the same sums as the attention block's H_in, R for W_Q / W_K
+    Wz = np.zeros((8, 12))
+    Hs = O.build_hessians(X, Xf, Wz, Wz, Wz, np.zeros((12, 8)), 2, 2, 4, alpha=0.25)
+    assert np.allclose(H, Hs["Hin_qk"]) and np.allclose(R, Hs["R_qk"])
+    Wg = rng(44).standard_normal((7, 12)); Wu = rng(45).standard_normal((7, 12))
+    A = O.swiglu(X, Wg, Wu)
+    G, U = X @ Wg.T, X @ Wu.T
+    assert np.allclose(A, G * expit(G) * U, rtol=1e-12)                     # silu(g) = g sigmoid(g), library sigmoid
+    assert np.allclose(O.swiglu(X, 0 * Wg, Wu), 0.0)                          # silu(0) = 0
+    big = O.swiglu(np.array([[40.0]]), np.array([[1.0]]), np.array([[2.0]]))
+    assert np.isclose(big[0, 0], 40.0 * 80.0, rtol=1e-12)                     # silu(g) -> g for large g
+
+
 def test_pack_codes_bit_stream():
     """Hand-computed words, and an independent unpacking through Python integers."""
     assert O.pack_codes(np.array([[1, 2, 3, 0]]), 2).tolist() == [[1 | 2 << 2 | 3 << 4]]
