@@ -110,6 +110,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-R", action="store_true", help="first-block setting: no upstream deviation (R = 0)")
     ap.add_argument("--n-seqs", type=int, default=0, help="override the number of calibration sequences (profiling runs)")
+    ap.add_argument("--serial-layers", action="store_true", help="quantize W_Q, W_K, W_V one after the other on one stream")
     ap.add_argument("--with-mlp", action="store_true",
                     help="also time the gated MLP of the same transformer block (reported beside the metric, never inside `value`)")
     ap.add_argument("--roofline-probe", action="store_true",
@@ -141,8 +142,11 @@ def main():
     ctx = tb.Context()
     use_R = not args.no_R
 
+    from paper_2602_04929_amd.pipeline import make_side_contexts
+    side = None if args.serial_layers else make_side_contexts(2)
+
     def step(timings=None):
-        return quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=use_R, timings=timings)
+        return quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=use_R, timings=timings, side_contexts=side)
 
     for _ in range(args.warmup):
         out = step()
@@ -183,7 +187,7 @@ def main():
         "bf16_gemm_seconds_per_step": mfma_ms * 1e-3,
         "kernels": kernels,
         "losses": {k: out[k]["loss"] for k in ("q", "k", "v", "o")},
-        "workspace_gib": ctx.workspace_bytes() / 2 ** 30,
+        "workspace_gib": (ctx.workspace_bytes() + sum(c.workspace_bytes() for c in side or [])) / 2 ** 30,
         "grid_search": {"two_phase_passes": ctx.counter(0), "passes_fully_exact": ctx.counter(1), "rows_fully_exact": ctx.counter(2)},
         "roofline": roofline,
     }

@@ -87,6 +87,9 @@ typedef struct {
  *   Hin_v  [Hkv, d, d]   = sum over query heads of the group and sequences of (A_h X_s)^T (A_h X_s)
  *   R_v    [Hkv, d, d]   = alpha * sum (A_h X_s - A~_h X~_s)^T (A_h X_s), or NULL to skip
  *   Hout_v [Hkv, dh, dh] = sum over query heads of the group of W_out,h^T W_out,h
+ * The outputs come in independent parts, and a part whose pointers are NULL is not computed: {Hin_qk, Hout_q, Hout_k
+ * (+ R_qk)} (all three or none), {Hin_v (+ R_v)} (by far the most expensive part), {Hout_v}.  A caller may so obtain the
+ * factors of W_Q and W_K first and quantize them on other streams while the W_V part is still being built.
  */
 int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* desc,
                         const void* X, const void* X_fp,

@@ -181,7 +181,8 @@ class Context:
 
     # ---- the method
     def build_hessians(self, X, X_fp, Wq, Wk, Wv, Wo, n_q_heads, n_kv_heads, head_dim, alpha=0.0, causal=True,
-                       with_R_v=True, seq_chunk=0):
+                       with_R_v=True, seq_chunk=0, parts="all"):
+        """parts: "all", "qk" (H_in, R, H_out of W_Q and W_K, plus H_out of W_V) or "v" (H_in, R of W_V)."""
         S, L, d = X.shape
         dt = X.dtype
         for t in (X, Wq, Wk, Wv, Wo):
@@ -191,14 +192,19 @@ class Context:
         desc = AttnDesc(d, n_q_heads, n_kv_heads, head_dim, S, L, _dtype_code(X), int(causal), alpha, seq_chunk)
         f = dict(dtype=torch.float32, device=X.device)
         dh = head_dim
-        out = dict(Hin_qk=torch.empty(d, d, **f), Hout_q=torch.empty(n_q_heads, dh, dh, **f),
-                   Hout_k=torch.empty(n_kv_heads, dh, dh, **f), Hin_v=torch.empty(n_kv_heads, d, d, **f),
-                   Hout_v=torch.empty(n_kv_heads, dh, dh, **f), R_qk=None, R_v=None)
-        if X_fp is not None:
-            out["R_qk"] = torch.empty(d, d, **f)
-            if with_R_v:
+        qk, v = parts in ("all", "qk"), parts in ("all", "v")
+        out = dict(Hin_qk=None, Hout_q=None, Hout_k=None, Hin_v=None, Hout_v=None, R_qk=None, R_v=None)
+        if qk:
+            out.update(Hin_qk=torch.empty(d, d, **f), Hout_q=torch.empty(n_q_heads, dh, dh, **f),
+                       Hout_k=torch.empty(n_kv_heads, dh, dh, **f), Hout_v=torch.empty(n_kv_heads, dh, dh, **f))
+            if X_fp is not None:
+                out["R_qk"] = torch.empty(d, d, **f)
+        if v:
+            out["Hin_v"] = torch.empty(n_kv_heads, d, d, **f)
+            if X_fp is not None and with_R_v:
                 out["R_v"] = torch.empty(n_kv_heads, d, d, **f)
-        self._check(_lib.tboa_build_hessians(self._h, C.byref(desc), _ptr(X), _ptr(X_fp), _ptr(Wq), _ptr(Wk), _ptr(Wv),
+        self._check(_lib.tboa_build_hessians(self._h, C.byref(desc), _ptr(X), _ptr(X_fp if (qk or out["R_v"] is not None) else None),
+                                             _ptr(Wq), _ptr(Wk), _ptr(Wv),
                                              _ptr(Wo), _ptr(out["Hin_qk"]), _ptr(out["R_qk"]), _ptr(out["Hout_q"]),
                                              _ptr(out["Hout_k"]), _ptr(out["Hin_v"]), _ptr(out["R_v"]), _ptr(out["Hout_v"])))
         return out

@@ -319,6 +319,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     }
     hipStream_t st = ctx->stream;
     // ---- H_in and R for W_Q / W_K
+    if (Hin_qk) {
     TB_TRY(transpose(D, X, fp ? X_fp : nullptr, dm, T, dm, XT, fp ? dXh : nullptr, dXl, TP));
     TB_TRY(gram_splitk(ctx, splits, dm, XT, nullptr, XT, TP, T, 1.0, 1, part, Hin_qk));
     if (fp && R_qk) TB_TRY(gram_splitk(ctx, splits, dm, dXh, dXl, XT, TP, T, d->alpha, 0, part, R_qk));
@@ -326,7 +327,6 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     TB_TRY(launch_cvt_f32_to_f64(ctx, Hin_qk, Hin64, dd));
     TB_TRY(launch_cvt_to_f64(ctx, Wq, TBOA_BF16, Wq64, (int64_t)dq * dm));
     TB_TRY(launch_cvt_to_f64(ctx, Wk, TBOA_BF16, Wk64, (int64_t)dkv * dm));
-    TB_TRY(launch_cvt_to_f64(ctx, Wo, TBOA_BF16, Wo64, (int64_t)dm * dq));
     {
         GemmF64 a{};
         a.M = dq; a.N = dm; a.K = dm; a.alpha = 1.0; a.beta = 0.0; a.A = Wq64; a.sam = dm; a.sak = 1; a.B = Hin64; a.sbk = dm; a.sbn = 1;
@@ -345,6 +345,11 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
             TB_TRY(gemm_f64(ctx, b));
         }
         hipLaunchKernelGGL(bcast_heads_kernel, dim3(g1(Hkv * hh)), dim3(256), 0, st, Ho, Hout_k, 1, hh, Hkv * hh);
+        TB_KERNEL_CHECK(ctx);
+    }
+    }
+    if (Hout_v) {
+        TB_TRY(launch_cvt_to_f64(ctx, Wo, TBOA_BF16, Wo64, (int64_t)dm * dq));
         GemmF64 c{};   // W_out,h^T W_out,h, W_out,h = Wo[:, h dh : (h+1) dh]
         c.M = dh; c.N = dh; c.K = dm; c.alpha = 1.0; c.sam = 1; c.sak = dq; c.sbk = dq; c.sbn = 1; c.C = Ho; c.ldc = dh;
         c.batch = Hkv; c.strideA = (long long)rep * dh; c.strideB = c.strideA; c.strideC = hh;
@@ -356,6 +361,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         TB_KERNEL_CHECK(ctx);
     }
     // ---- H_in (and R) of W_V
+    if (!Hin_v) return 0;
     TB_TRY(launch_fill_f32(ctx, Hin_v, (int64_t)Hkv * dd, 0.f));
     if (rv) TB_TRY(launch_fill_f32(ctx, R_v, (int64_t)Hkv * dd, 0.f));
     const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
@@ -570,8 +576,13 @@ extern "C" int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* d, const
                                    float* Hout_k, float* Hin_v, float* R_v, float* Hout_v) {
     if (!ctx) return TBOA_EINVAL;
     TB_TRY(check_attn_desc(ctx, d));
-    if (!X || !Wq || !Wk || !Wo || !Hin_qk || !Hout_q || !Hout_k || !Hin_v || !Hout_v) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: null argument");
-    if (X_fp && !R_qk) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: X_fp given without R_qk");
+    if (!X || !Wq || !Wk || !Wo) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: null input");
+    if (!Hin_qk && !Hin_v && !Hout_v) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: no output requested");
+    if ((Hin_qk != nullptr) != (Hout_q != nullptr) || (Hin_qk != nullptr) != (Hout_k != nullptr))
+        return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: Hin_qk, Hout_q and Hout_k are computed together: give all three or none");
+    if ((R_qk && !Hin_qk) || (R_v && !Hin_v)) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: R_qk needs Hin_qk, R_v needs Hin_v");
+    if ((R_qk || R_v) && !X_fp) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: R_qk / R_v need X_fp");
+    if (X_fp && Hin_qk && !R_qk) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: X_fp given without R_qk");
     if (d->x_dtype == TBOA_F32) return build_hessians_f64(ctx, d, X, X_fp, Wq, Wk, Wv, Wo, Hin_qk, R_qk, Hout_q, Hout_k, Hin_v, R_v, Hout_v);
     return build_hessians_bf16(ctx, d, (const bf16*)X, (const bf16*)X_fp, (const bf16*)Wq, (const bf16*)Wk, (const bf16*)Wo, Hin_qk, R_qk,
                                Hout_q, Hout_k, Hin_v, R_v, Hout_v);

@@ -115,12 +115,12 @@ int build_hessians_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, co
                 TB_TRY(gemm_f64(ctx, mk(dm, dm, L, d->alpha, Yf, 1, dm, Y, dm, 1, 1.0, Rv + (long long)g * dm * dm, dm)));
             }
         }
-    TB_TRY(launch_cvt_f64_to_f32(ctx, Hin, Hin_qk, (int64_t)dm * dm));
+    if (Hin_qk) TB_TRY(launch_cvt_f64_to_f32(ctx, Hin, Hin_qk, (int64_t)dm * dm));
     if (fp && R_qk) TB_TRY(launch_cvt_f64_to_f32(ctx, Rq, R_qk, (int64_t)dm * dm));
-    TB_TRY(launch_cvt_f64_to_f32(ctx, Hoq, Hout_q, (int64_t)Hq * dh * dh));
-    TB_TRY(launch_cvt_f64_to_f32(ctx, Hok, Hout_k, (int64_t)Hkv * dh * dh));
-    TB_TRY(launch_cvt_f64_to_f32(ctx, Hov, Hout_v, (int64_t)Hkv * dh * dh));
-    TB_TRY(launch_cvt_f64_to_f32(ctx, Hiv, Hin_v, (int64_t)Hkv * dm * dm));
+    if (Hout_q) TB_TRY(launch_cvt_f64_to_f32(ctx, Hoq, Hout_q, (int64_t)Hq * dh * dh));
+    if (Hout_k) TB_TRY(launch_cvt_f64_to_f32(ctx, Hok, Hout_k, (int64_t)Hkv * dh * dh));
+    if (Hout_v) TB_TRY(launch_cvt_f64_to_f32(ctx, Hov, Hout_v, (int64_t)Hkv * dh * dh));
+    if (Hin_v) TB_TRY(launch_cvt_f64_to_f32(ctx, Hiv, Hin_v, (int64_t)Hkv * dm * dm));
     if (rv) TB_TRY(launch_cvt_f64_to_f32(ctx, Rv, R_v, (int64_t)Hkv * dm * dm));
     return 0;
 }

@@ -1,17 +1,25 @@
 """One attention block through the library: the sequence of C-ABI calls of the hot path, nothing else."""
 from __future__ import annotations
 
+import threading
 import time
 
 import torch
 
 
+def make_side_contexts(n=2):
+    """Contexts on fresh streams (default priority) for layers that may run beside the main context's work."""
+    import paper_2602_04929_amd as tb
+    return [tb.Context(stream=torch.cuda.Stream()) for _ in range(n)]
+
+
 def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=True, cd_iters=1, adaptive_grid=True,
-                             damp=0.01, seq_chunk=0, timings=None):
+                             damp=0.01, seq_chunk=0, timings=None, side_contexts=None):
     """(rotation, activation fake-quant ->) Hessians -> W_Q, W_K, W_V -> output-projection Hessian -> W_O.
 
     blk: dict from synth.make_block (device tensors); cfg: synth.BlockConfig.  Returns dict of per-layer results
-    and the Hessians.  `timings` (a dict) receives per-stage seconds measured with stream synchronisation."""
+    and the Hessians.  `timings` (a dict) receives per-stage seconds measured with stream synchronisation.
+    side_contexts: two more contexts on streams of their own (see make_side_contexts): W_Q, W_K, W_V then run side by side."""
     Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     X_fp = blk["X_fp"]
     X = blk["X"]
@@ -33,13 +41,43 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     if X is None:      # weight-activation setting: the quantized path sees per-token fake-quantized activations
         X = stage("act_fakequant", lambda: ctx.act_fakequant(X_fp, cfg.act_bits))
     Xf = X_fp if use_R else None
-    Hs = stage("build_hessians", lambda: ctx.build_hessians(X, Xf, blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], Hq, Hkv, dh,
-                                                            alpha=alpha, with_R_v=with_R_v, seq_chunk=seq_chunk))
+    hargs = (X, Xf, blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], Hq, Hkv, dh)
+    hkw = dict(alpha=alpha, with_R_v=with_R_v, seq_chunk=seq_chunk)
     kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp)
-    out = {"hessians": Hs, "X": X, "X_fp": X_fp}
-    out["q"] = stage("quantize_q", lambda: ctx.quantize_layer(blk["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq, **kw))
-    out["k"] = stage("quantize_k", lambda: ctx.quantize_layer(blk["Wk"], Hs["Hin_qk"], Hs["Hout_k"], Hs["R_qk"], Hkv, **kw))
-    out["v"] = stage("quantize_v", lambda: ctx.quantize_layer(blk["Wv"], Hs["Hin_v"], Hs["Hout_v"], Hs["R_v"], Hkv, **kw))
+    out = {"X": X, "X_fp": X_fp}
+    Hs = stage("build_hessians", lambda: ctx.build_hessians(*hargs, **hkw))
+    jobs = (("q", (blk["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq)), ("k", (blk["Wk"], Hs["Hin_qk"], Hs["Hout_k"], Hs["R_qk"], Hkv)),
+            ("v", (blk["Wv"], Hs["Hin_v"], Hs["Hout_v"], Hs["R_v"], Hkv)))
+    if side_contexts:
+        # W_Q, W_K, W_V are independent given the Hessians: one context (and stream) each, driven from three host threads, so
+        # that the latency-bound steps of one layer (factorisation panels, in-channel sweeps) run beside the GEMMs of another.
+        # (Starting W_Q and W_K already beside the H_in^V build, which tboa_build_hessians allows, was measured and gains
+        # nothing more: that build keeps the matrix cores busy by itself.)
+        def run(name, c, args):
+            with torch.cuda.stream(c._stream):
+                out[name] = c.quantize_layer(*args, **kw)
+
+        def all_three():
+            main = torch.cuda.current_stream()
+            ctxs = (ctx, side_contexts[0], side_contexts[1])
+            for c in ctxs[1:]:
+                c._stream.wait_stream(main)
+            threads = [threading.Thread(target=run, args=(name, c, args)) for (name, args), c in zip(jobs, ctxs)]
+            for t in threads:
+                t.start()
+            for t in threads:
+                t.join()
+            for c in ctxs[1:]:
+                main.wait_stream(c._stream)
+            for name in ("k", "v"):
+                for v in out[name].values():
+                    if torch.is_tensor(v):
+                        v.record_stream(main)
+        stage("quantize_qkv", all_three)
+    else:
+        for name, args in jobs:
+            out[name] = stage("quantize_" + name, lambda a=args: ctx.quantize_layer(*a, **kw))
+    out["hessians"] = Hs
     Ho = stage("build_hessian_out_proj", lambda: ctx.build_hessian_out_proj(
         X, Xf, out["q"]["W_deq"], out["k"]["W_deq"], out["v"]["W_deq"], blk["Wq"], blk["Wk"], blk["Wv"], Hq, Hkv, dh,
         alpha=alpha, seq_chunk=seq_chunk))

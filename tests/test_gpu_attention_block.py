@@ -30,15 +30,20 @@ def oracle_block(blk, cfg, alpha=0.25, use_R=True):
     return out
 
 
-@pytest.mark.parametrize("use_R", [True, False])
-def test_tiny_config_end_to_end(lib, use_R):
+@pytest.mark.parametrize("use_R,side", [(True, False), (False, False), (True, True)])
+def test_tiny_config_end_to_end(lib, use_R, side):
     """Config 1 (d_model 256, 4 heads x 64, 8 x 128 tokens, INT2, N = 4, seed 0): every layer against the oracle,
     each side building its own Hessians from the same X."""
     from paper_2602_04929_amd.pipeline import quantize_attention_block
     cfg = synth.CONFIGS["tiny"]
     blk = synth.make_block(cfg, seed=0, device="cuda")
     ctx = lib.Context()
-    got = quantize_attention_block(ctx, blk, cfg, use_R=use_R)
+    from paper_2602_04929_amd.pipeline import make_side_contexts
+    sc = make_side_contexts(2) if side else None        # W_Q, W_K, W_V on three streams from three host threads
+    got = quantize_attention_block(ctx, blk, cfg, use_R=use_R, side_contexts=sc)
+    torch.cuda.synchronize()
+    for c in sc or []:
+        c.close()
     want = oracle_block(blk, cfg, use_R=use_R)
     for layer in ("q", "k", "v", "o"):
         frac = compare_layer(got[layer], want[layer], label=layer)

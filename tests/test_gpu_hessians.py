@@ -77,6 +77,22 @@ def test_bf16_path_long_sequence(ctx):
     check_all(got, want, 1e-5, 2e-3, 2e-2)
 
 
+@pytest.mark.parametrize("name", ["tiny", "llama2-7b"])
+def test_hessian_parts_equal_the_whole(ctx, name):
+    """The {W_Q, W_K} part and the W_V part asked for separately are the same numbers as one call for everything."""
+    cfg = synth.scaled(synth.CONFIGS[name], d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=2, seq_len=64, n_outlier=2)
+    b = synth.make_block(cfg, seed=5, device="cuda")
+    args = (b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 4, 2, 32)
+    whole = ctx.build_hessians(*args, alpha=0.25)
+    qk = ctx.build_hessians(*args, alpha=0.25, parts="qk")
+    v = ctx.build_hessians(*args, alpha=0.25, parts="v")
+    assert qk["Hin_v"] is None and qk["R_v"] is None and v["Hin_qk"] is None and v["Hout_v"] is None
+    for k in ("Hin_qk", "R_qk", "Hout_q", "Hout_k", "Hout_v"):
+        assert torch.equal(qk[k], whole[k]), k
+    for k in ("Hin_v", "R_v"):
+        assert torch.equal(v[k], whole[k]), k
+
+
 def test_out_proj_fp32(ctx):
     cfg = synth.scaled(synth.CONFIGS["tiny"], d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, n_seqs=2, seq_len=40, n_outlier=2)
     b = synth.make_block(cfg, seed=3, device="cuda")
