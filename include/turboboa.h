@@ -54,8 +54,10 @@ const char* tboa_last_error(const tboa_ctx* ctx);
  * TBOA_CTR_GRID_PASSES: grid-search passes that used the two-phase search (approximate costs of all candidates on the
  * bf16 matrix cores, exact fp64 costs of the near-minimal ones); TBOA_CTR_GRID_FALLBACKS: those among them that met a
  * number of rows with more near-minimal candidates than the pass can handle one by one and therefore evaluated every
- * candidate of every row in fp64; TBOA_CTR_GRID_EXACT_ROWS: single rows that had every candidate evaluated in fp64. */
-enum tboa_counter_id { TBOA_CTR_GRID_PASSES = 0, TBOA_CTR_GRID_FALLBACKS = 1, TBOA_CTR_GRID_EXACT_ROWS = 2 };
+ * candidate of every row in fp64; TBOA_CTR_GRID_EXACT_ROWS: single rows that had every candidate evaluated in fp64;
+ * TBOA_CTR_GRID_SURVIVORS: near-minimal candidates that were evaluated exactly (rows with a single near-minimal
+ * candidate need none). */
+enum tboa_counter_id { TBOA_CTR_GRID_PASSES = 0, TBOA_CTR_GRID_FALLBACKS = 1, TBOA_CTR_GRID_EXACT_ROWS = 2, TBOA_CTR_GRID_SURVIVORS = 3 };
 int64_t tboa_counter(const tboa_ctx* ctx, int which);
 /* Bytes of context-owned workspace currently allocated (host value). */
 size_t tboa_workspace_bytes(const tboa_ctx* ctx);

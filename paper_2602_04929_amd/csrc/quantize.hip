@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256) void rowdot_split_kernel(const float* __restri
 constexpr int GRID_MAX_OVF = 96;    // rows per pass that may be re-evaluated exactly one by one
 
 __global__ void grid_select_kernel(const double* __restrict__ cost, int rows, int ncand, double tau, int* __restrict__ sel,
-                                   int* __restrict__ overflow) {
+                                   int* __restrict__ cnt_out, int* __restrict__ overflow) {
     const int row = blockIdx.x * blockDim.x + threadIdx.x;
     if (row >= rows) return;
     const double* c = cost + (long long)row * ncand;
@@ -185,34 +185,79 @@ __global__ void grid_select_kernel(const double* __restrict__ cost, int rows, in
             if (cnt < GRID_KS) o[cnt] = k;
             ++cnt;
         }
-    if (cnt > GRID_KS || !(m == m)) { const int i = atomicAdd(overflow, 1); if (i < GRID_MAX_OVF) overflow[1 + i] = row; }
+    const bool ovf = cnt > GRID_KS || !(m == m);
+    if (ovf) { const int i = atomicAdd(overflow, 1); if (i < GRID_MAX_OVF) overflow[1 + i] = row; }
     for (int j = cnt; j < GRID_KS; ++j) o[j] = first;
+    // a single candidate inside tau wins without an exact evaluation; a row with too many gets every candidate evaluated
+    // on its own afterwards: neither takes part in the exact pass
+    const int ev = (cnt > 1 && !ovf) ? cnt : 0;
+    cnt_out[row] = ev;
+    atomicAdd(overflow + 1 + GRID_MAX_OVF, ev);
 }
 
-// exact delta of the selected candidates: DeltaS[(row, j), c]
+// exclusive prefix sums of cnt over the rows of each group of `per` rows (one workgroup per group): off[row], total[group]
+__global__ __launch_bounds__(256) void grid_scan_kernel(const int* __restrict__ cnt, int per, int* __restrict__ off, int* __restrict__ total) {
+    __shared__ int part[256];
+    const int g = blockIdx.x, t = threadIdx.x;
+    const int* c = cnt + (long long)g * per; int* o = off + (long long)g * per;
+    const int chunk = (per + 255) / 256, lo = t * chunk, hi = min(per, lo + chunk);
+    int s = 0;
+    for (int i = lo; i < hi; ++i) s += c[i];
+    part[t] = s;
+    __syncthreads();
+    if (t == 0) { int run = 0; for (int i = 0; i < 256; ++i) { const int v = part[i]; part[i] = run; run += v; } total[g] = run; }
+    __syncthreads();
+    int run = part[t];
+    for (int i = lo; i < hi; ++i) { o[i] = run; run += c[i]; }
+}
+
+// exact delta of the candidates to evaluate, compacted per group of `per` rows: DeltaS[group][off[row] + j, c], j < cnt[row]
 __global__ __launch_bounds__(256) void grid_delta_sel_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
                                                              const double* __restrict__ cand_s, const double* __restrict__ cand_z,
-                                                             const int* __restrict__ sel, double* __restrict__ DeltaS) {
+                                                             const int* __restrict__ sel, const int* __restrict__ cnt, const int* __restrict__ off,
+                                                             int per, double* __restrict__ DeltaS) {
     const int row = blockIdx.y;
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= n) return;
+    const int nc = cnt[row];
+    if (c >= n || nc == 0) return;
     const double w = Wk[(long long)row * ldw + c];
-    for (int j = 0; j < GRID_KS; ++j) {
+    double* out = DeltaS + ((long long)(row / per) * per * GRID_KS + off[row]) * n + c;
+    for (int j = 0; j < nc; ++j) {
         const int k = sel[(long long)row * GRID_KS + j];
         const double s = cand_s[(long long)row * ncand + k], z = cand_z[(long long)row * ncand + k];
-        DeltaS[((long long)row * GRID_KS + j) * n + c] = s * (quant_code(w, s, z, maxq) - z) - w;
+        out[(long long)j * n] = s * (quant_code(w, s, z, maxq) - z) - w;
     }
 }
 
-// lowest exact cost among the selected (lowest k among equals: the slots are in increasing k)
-__global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const int* __restrict__ sel, const double* __restrict__ cand_s,
+// cost[i] = sum_c A[i, c] B[i, c] for the compacted rows: row i of group g (per * GRID_KS slots each) exists if i < total[g]
+__global__ __launch_bounds__(256) void rowdot_limited_kernel(const double* __restrict__ A, const double* __restrict__ B, int n, int slots,
+                                                             long long rows, const int* __restrict__ total, double* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    if ((int)(row % slots) >= total[row / slots]) return;
+    const double* a = A + row * n; const double* b = B + row * n;
+    double s = 0.0;
+    for (int c = lane; c < n; c += 64) s += a[c] * b[c];
+    s = wave_sum(s);
+    if (lane == 0) out[row] = s;
+}
+
+// lowest exact cost among the evaluated candidates of a row (lowest k among equals: they are in increasing k); a row
+// with a single candidate inside tau takes that one
+__global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const int* __restrict__ sel, const int* __restrict__ cnt,
+                                       const int* __restrict__ off, int per, const double* __restrict__ cand_s,
                                        const double* __restrict__ cand_z, int rows, int ncand, BlockMap m, int r_off,
                                        double* __restrict__ s_out, double* __restrict__ z_out, int ng, int gi) {
     const int row = blockIdx.x * blockDim.x + threadIdx.x;
     if (row >= rows) return;
-    const double* c = costS + (long long)row * GRID_KS;
-    int best = 0; double bc = c[0];
-    for (int j = 1; j < GRID_KS; ++j) if (c[j] < bc) { bc = c[j]; best = j; }
+    int best = 0;
+    const int nc = cnt[row];
+    if (nc > 1) {
+        const double* c = costS + (long long)(row / per) * per * GRID_KS + off[row];
+        double bc = c[0];
+        for (int j = 1; j < nc; ++j) if (c[j] < bc) { bc = c[j]; best = j; }
+    }
     const int k = sel[(long long)row * GRID_KS + best];
     const long long lr = layer_row(m, r_off + row);
     s_out[lr * ng + gi] = cand_s[(long long)row * ncand + k];
@@ -522,7 +567,8 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             __hip_bfloat16* Acat = (__hip_bfloat16*)L.Delta; float* G32 = (float*)L.G;
             int* ovf = ctx->d_status + 8;   // [0] count, [1..] rows
             TB_HIP(ctx, hipMemsetAsync(ovf, 0, sizeof(int), ctx->stream));
-            static_assert(9 + GRID_MAX_OVF <= 256, "status words");
+            TB_HIP(ctx, hipMemsetAsync(ovf + 1 + GRID_MAX_OVF, 0, sizeof(int), ctx->stream));
+            static_assert(10 + GRID_MAX_OVF <= 256, "status words");
             hipLaunchKernelGGL(grid_delta_split_kernel, dim3((n + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, n, ncand, L.maxq,
                                L.cand_s, L.cand_z, Acat);
             TB_KERNEL_CHECK(ctx);
@@ -535,25 +581,28 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             TB_TRY(gemm_bf16_nt(ctx, a));
             const long long crow = (long long)rows * ncand;
             hipLaunchKernelGGL(rowdot_split_kernel, dim3((unsigned)((crow + 3) / 4)), dim3(256), 0, ctx->stream, G32, Acat, crow, n, L.cost);
-            hipLaunchKernelGGL(grid_select_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.cost, rows, ncand, GRID_TAU, L.sel, ovf);
+            const int per = ph ? rows_per_head : rows, ngrp = rows / per;    // rows that share one H_in
+            int* cntv = L.sel + (long long)rows * GRID_KS; int* offv = cntv + rows; int* totv = offv + rows;
+            hipLaunchKernelGGL(grid_select_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.cost, rows, ncand, GRID_TAU, L.sel, cntv, ovf);
+            hipLaunchKernelGGL(grid_scan_kernel, dim3(ngrp), dim3(256), 0, ctx->stream, cntv, per, offv, totv);
             hipLaunchKernelGGL(grid_delta_sel_kernel, dim3((n + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, n, ncand, L.maxq,
-                               L.cand_s, L.cand_z, L.sel, L.DeltaS);
+                               L.cand_s, L.cand_z, L.sel, cntv, offv, per, L.DeltaS);
             TB_KERNEL_CHECK(ctx);
             GemmF64 g{};
-            g.N = n; g.K = n; g.alpha = 1.0; g.beta = 0.0; g.A = L.DeltaS; g.sam = n; g.sak = 1; g.sbk = n; g.sbn = 1; g.C = L.GS; g.ldc = n;
-            if (ph) { g.M = rows_per_head * GRID_KS; g.batch = nu; g.B = L.Hi + (long long)u0 * L.nn;
-                      g.strideA = (long long)g.M * n; g.strideB = L.nn; g.strideC = g.strideA; }
-            else { g.M = rows * GRID_KS; g.batch = 1; g.B = L.Hi; }
+            g.M = per * GRID_KS; g.N = n; g.K = n; g.alpha = 1.0; g.beta = 0.0; g.A = L.DeltaS; g.sam = n; g.sak = 1; g.sbk = n; g.sbn = 1;
+            g.C = L.GS; g.ldc = n; g.batch = ngrp; g.strideA = (long long)g.M * n; g.strideC = g.strideA; g.m_limit = totv;
+            g.B = L.Hi + (ph ? (long long)u0 * L.nn : 0); g.strideB = ph ? L.nn : 0;
             TB_TRY(gemm_f64(ctx, g));
             const long long srow = (long long)rows * GRID_KS;
-            hipLaunchKernelGGL(rowdot_kernel, dim3((unsigned)((srow + 3) / 4)), dim3(256), 0, ctx->stream, L.GS, (long long)n, L.DeltaS,
-                               (long long)n, srow, n, L.costS);
-            hipLaunchKernelGGL(grid_argmin_sel_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.costS, L.sel, L.cand_s, L.cand_z,
-                               rows, ncand, map, r0, L.s64, L.z64, L.ng, gi);
+            hipLaunchKernelGGL(rowdot_limited_kernel, dim3((unsigned)((srow + 3) / 4)), dim3(256), 0, ctx->stream, L.GS, L.DeltaS, n, per * GRID_KS,
+                               srow, totv, L.costS);
+            hipLaunchKernelGGL(grid_argmin_sel_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.costS, L.sel, cntv, offv, per,
+                               L.cand_s, L.cand_z, rows, ncand, map, r0, L.s64, L.z64, L.ng, gi);
             TB_KERNEL_CHECK(ctx);
-            TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 8, ovf, (1 + GRID_MAX_OVF) * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+            TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 8, ovf, (2 + GRID_MAX_OVF) * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
             TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
             ++ctx->counters[TBOA_CTR_GRID_PASSES];
+            ctx->counters[TBOA_CTR_GRID_SURVIVORS] += ctx->h_status[9 + GRID_MAX_OVF];
             const int novf = ctx->h_status[8];
             done = novf <= GRID_MAX_OVF;
             if (!done) ++ctx->counters[TBOA_CTR_GRID_FALLBACKS];
@@ -890,7 +939,7 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
         L.Delta = ar.get<double>(grows * L.ncand * L.gsz); L.G = ar.get<double>(grows * L.ncand * L.gsz);
         if (L.fast_grid) {
             L.DeltaS = ar.get<double>(grows * GRID_KS * n); L.GS = ar.get<double>(grows * GRID_KS * n);
-            L.costS = ar.get<double>(grows * GRID_KS); L.sel = ar.get<int>(grows * GRID_KS);
+            L.costS = ar.get<double>(grows * GRID_KS); L.sel = ar.get<int>(grows * (GRID_KS + 3));
             L.Hcat = ar.get<__hip_bfloat16>((size_t)L.nhin * n * (3 * (size_t)n + GRID_PAD));
         }
         L.Wbar = ar.get<double>(wn); L.Abar = ar.get<double>(wn); L.Z = ar.get<double>(wn);
