@@ -2,13 +2,16 @@
 //
 // Heads are independent and run side by side: the N rows of the current step of every head form one
 // "block" of n_heads*N rows (block row R = h*nbr + r  <->  layer row h*d_h + i0 + r).  Per step:
-//   grid search   (Alg. 1 line 9)  candidates -> delta matrix -> one fp64 GEMM with H_in -> row dots -> argmin
+//   grid search   (Alg. 1 line 9)  candidates -> approximate costs of all of them on the bf16 matrix cores (delta and H_in as
+//                                  (hi, lo) bf16 pairs) -> exact fp64 costs of the near-minimal ones -> argmin
+//                                  (narrow layers and group-wise grids: every candidate exactly, one fp64 GEMM)
 //   in-channel sweep (Algorithm 3) panels of 64 columns: a wavefront owns a row, lane k holds column k, the 64
 //                                  sequential column steps run inside the kernel with U/P panel rows in LDS;
 //                                  columns right of the panel get one rank-64 GEMM update per term
 //   compensation  (Prop. 3.1/3.2)  T = [U_out^T]_{i1:,B} [U_out^T]_{B,B}^-1 per head, then W~[i1:] -= T E as a
 //                                  batched GEMM, E = (W_B - Q_B) - ((W_B R) U_in^T) U_in
-// and after the last step the coordinate descent of Algorithm 2 on precomputed d_h x d_h Gram matrices.
+// and after the last step the coordinate descent of Algorithm 2 on precomputed Gram matrices (d_h x d_h per head; per
+// pair of groups when the grids are group-wise), then the outputs and the loss.
 #include "internal.h"
 #include <math.h>
 
