@@ -130,3 +130,18 @@ def test_llama2_7b_shape_mlp_sampled(lib):
         frac = compare_layer(sub, want, label=layer + " rows")
         print("  %s sampled rows: codes identical %.4f%%" % (layer, 100 * frac), flush=True)
     c.close()
+
+
+def test_mlp_entry_points_reject_bad_arguments(ctx, lib):
+    X = torch.zeros(4, 10, 72, device="cuda")
+    with pytest.raises(lib.TurboBoAError) as e:          # bf16 inputs need multiples of 8
+        ctx.build_hessian_linear(torch.zeros(3, 9, 20, device="cuda", dtype=torch.bfloat16))
+    assert e.value.code == -1
+    with pytest.raises(lib.TurboBoAError) as e:          # weights neither fp32 nor of the activations' type
+        ctx.swiglu_forward(X, torch.zeros(16, 72, device="cuda", dtype=torch.bfloat16), torch.zeros(16, 72, device="cuda", dtype=torch.bfloat16))
+    assert e.value.code == -1
+    H, R = ctx.build_hessian_linear(X)                     # all-zero activations: a zero Hessian, and quantize_layer reports it
+    assert R is None and float(H.abs().max()) == 0.0
+    with pytest.raises(lib.TurboBoAError) as e:
+        ctx.quantize_layer(torch.ones(8, 72, device="cuda"), H, None, None, 1, bits=2, block=8)
+    assert e.value.code == -2
