@@ -210,8 +210,12 @@ int tboa_gemm_f64(tboa_ctx* ctx, int M, int N, int K, double alpha,
  * pointers 16-byte aligned).  C [M, N] ldc, fp32 (c_dtype = TBOA_F32) or bf16 (TBOA_BF16, accumulate must be 0).
  * flags: TBOA_GEMM_LOWER computes only tiles on or below the diagonal (M == N; a symmetric product),
  *        TBOA_GEMM_CAUSAL_K limits the contraction of output column n to k <= n rounded up to the tile
- *        (B is lower triangular: causal attention probabilities). */
-enum { TBOA_GEMM_LOWER = 1, TBOA_GEMM_CAUSAL_K = 2 };
+ *        (B is lower triangular: causal attention probabilities),
+ *        TBOA_GEMM_PERSISTENT runs one resident workgroup per compute unit over a precomputed list of tiles instead of
+ *        one dispatched workgroup per tile (same arithmetic, same result; taken when the contraction length, or kseg, is
+ *        a multiple of 128, ignored otherwise).  Meant for launches that have the GPU to themselves: the lists are
+ *        balanced for compute units that all start together. */
+enum { TBOA_GEMM_LOWER = 1, TBOA_GEMM_CAUSAL_K = 2, TBOA_GEMM_PERSISTENT = 4 };
 int tboa_gemm_bf16_nt(tboa_ctx* ctx, int M, int N, int K, float alpha,
                       const void* A, int64_t lda, const void* B, int64_t ldb,
                       void* C, int64_t ldc, int c_dtype, int accumulate, int flags,

@@ -84,6 +84,7 @@ extern "C" void tboa_destroy(tboa_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (auto& t : ctx->tile_orders) (void)hipFree(t.dev);
+    for (auto& t : ctx->tile_schedules) (void)hipFree(t.dev);
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);

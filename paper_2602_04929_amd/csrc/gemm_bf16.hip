@@ -4,9 +4,11 @@
 // are kept in a transposed copy where the token axis is the contraction axis), so one kernel shape serves X^T X,
 // the projections, Q K^T, A X and the dominant Y^T Y.
 //
-// Two kernels share the 256 x 256 output tile per workgroup, the MFMA shape and the launch order of the tiles:
+// Three kernels share the 256 x 256 output tile per workgroup, the MFMA shape, the epilogue and the order of the tiles:
 //   gemm_bf16_nt_fast_kernel  (K a multiple of 32: every launch of the Hessian build and of the grid search) copies global
 //                             memory straight into a ring of LDS stages and runs 8 wavefronts; described at its definition;
+//   gemm_bf16_nt_stream_kernel (TBOA_GEMM_PERSISTENT, k ranges that are multiples of 128) is the same pipeline run by one
+//                             resident workgroup per CU over a list of tiles, the ring streaming across tile boundaries;
 //   gemm_bf16_nt_kernel       (any K that is a multiple of 8) stages through registers: 4 wavefronts (2 x 2), each owning
 //                             128 x 128 as 4 x 4 MFMA tiles of 32 x 32 (256 fp32 accumulators per lane), 64-deep k-steps,
 //                             two LDS stages, one barrier per k-step.
@@ -18,6 +20,7 @@
 // work on a compact block of ONE batch entry and share operand panels through that XCD's L2: see work_item / tile_order.
 #include "internal.h"
 #include <stdlib.h>
+#include <algorithm>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -33,11 +36,14 @@ struct Args {
     const __hip_bfloat16* B; long long ldb;
     void* C; long long ldc;
     int c_bf16, accumulate, flags;
+    int vec_c;                  // C rows and batch offsets allow 16-byte (fp32) / 8-byte (bf16) accesses at columns that are multiples of 4
     int batch_inner, kseg;
     long long sA1, sA2, sB1, sB2, sC1, sC2;
     const int* tile_order;      // (tm << 16 | tn) of the tiles of one batch entry, in launch order
     int ntiles;                 // tiles per batch entry
     long long nitems, per;      // batch * ntiles work items; per = items per XCD
+    const int2* sched;          // persistent kernel: [workgroups][rounds] of (batch entry or -1, tm << 16 | tn)
+    int rounds;
 };
 
 // Work item of this workgroup.  Workgroups are dealt to the eight XCDs round-robin by their linear number, so workgroup
@@ -53,6 +59,97 @@ __device__ __forceinline__ bool work_item(const Args& g, int& z, int& tm, int& t
     tm = __builtin_amdgcn_readfirstlane(packed >> 16); tn = __builtin_amdgcn_readfirstlane(packed & 0xffff);
     z = __builtin_amdgcn_readfirstlane(z);
     return true;
+}
+
+// Epilogue shared by the kernels.  The MFMA leaves lane l of a wavefront with column l % 32 of a 32 x 32 sub-tile and, in
+// accumulators 4 b .. 4 b + 3, the four consecutive rows 8 b + 4 (l / 32) + 0 .. 3: stored as they are, that is 128
+// wavefront stores of one scalar per lane for a 128 x 64 wavefront tile, twice the number a wavefront can have in flight,
+// and the epilogue then runs at the latency of its own stores (9 - 13 us per 256 x 256 tile measured, a third of a short
+// causal tile).  transpose_acc swaps rows and columns inside every 4 x 4 block held by four neighbouring lanes (two
+// butterfly steps of quad-permute moves), after which lane l holds, for row 8 b + 4 (l / 32) + l % 4, the four consecutive
+// columns 4 ((l % 32) / 4) + 0 .. 3: one 16-byte (fp32) or 8-byte (bf16) store per lane and group, eight full rows of
+// 128 bytes per wavefront store, 32 stores per wavefront tile.
+template <int CTRL>
+__device__ __forceinline__ float quad_perm(float v) {
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+template <int TJ>
+__device__ __forceinline__ void transpose_acc(f32x16 (&acc)[4][TJ]) {
+    const bool x0 = threadIdx.x & 1, x1 = threadIdx.x & 2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                float a0 = acc[i][j][4 * b], a1 = acc[i][j][4 * b + 1], a2 = acc[i][j][4 * b + 2], a3 = acc[i][j][4 * b + 3];
+                // with lane ^ 1 (quad_perm [1,0,3,2]): 2 x 2 blocks
+                const float r01 = quad_perm<0xB1>(x0 ? a0 : a1), r23 = quad_perm<0xB1>(x0 ? a2 : a3);
+                a0 = x0 ? r01 : a0; a1 = x0 ? a1 : r01; a2 = x0 ? r23 : a2; a3 = x0 ? a3 : r23;
+                // with lane ^ 2 (quad_perm [2,3,0,1])
+                const float r02 = quad_perm<0x4E>(x1 ? a0 : a2), r13 = quad_perm<0x4E>(x1 ? a1 : a3);
+                a0 = x1 ? r02 : a0; a2 = x1 ? a2 : r02; a1 = x1 ? r13 : a1; a3 = x1 ? a3 : r13;
+                acc[i][j][4 * b] = a0; acc[i][j][4 * b + 1] = a1; acc[i][j][4 * b + 2] = a2; acc[i][j][4 * b + 3] = a3;
+            }
+}
+
+// acc as left by transpose_acc; (row0, col0): first row and column of the wavefront's tile in C, uniform over the wavefront
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int TJ, bool SCALE>
+__device__ __forceinline__ void store_acc_interior(const Args& g, const f32x16 (&acc)[4][TJ], int row0, int col0, long long coff) {
+    // the whole wavefront tile lies inside C and C allows vector accesses: no predicates, addresses = uniform base of the
+    // group + one per-lane offset computed once
+    const int lane = threadIdx.x & 63, l32 = lane & 31, lh = lane >> 5;
+    const int es = g.c_bf16 ? 2 : 4;
+    const unsigned off = (unsigned)(((long long)(4 * lh + (l32 & 3)) * g.ldc + 4 * (l32 >> 2)) * es);
+    char* base = (char*)g.C + (coff + (long long)row0 * g.ldc + col0) * es;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) {
+                char* p = base + ((long long)(32 * i + 8 * b) * g.ldc + 32 * j) * es + off;
+                f32x4 r = {acc[i][j][4 * b], acc[i][j][4 * b + 1], acc[i][j][4 * b + 2], acc[i][j][4 * b + 3]};
+                if (SCALE) r *= g.alpha;
+                if (g.c_bf16) *(bf16x4*)p = __builtin_convertvector(r, bf16x4);
+                else {
+                    if (g.accumulate) r += *(const f32x4*)p;
+                    *(f32x4*)p = r;
+                }
+            }
+}
+
+template <int TJ>
+__device__ __forceinline__ void store_acc(const Args& g, const f32x16 (&acc)[4][TJ], int row0, int col0, long long coff) {
+    if (g.vec_c && row0 + 128 <= g.M && col0 + 32 * TJ <= g.N) {
+        if (g.alpha == 1.0f) store_acc_interior<TJ, false>(g, acc, row0, col0, coff);
+        else store_acc_interior<TJ, true>(g, acc, row0, col0, coff);
+        return;
+    }
+    const int lane = threadIdx.x & 63, l32 = lane & 31, lh = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int row = row0 + 32 * i + 8 * b + 4 * lh + (l32 & 3);
+            if (row >= g.M) continue;
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) {
+                const int col = col0 + 32 * j + 4 * (l32 >> 2);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (col + e >= g.N) continue;
+                    const long long idx = coff + (long long)row * g.ldc + col + e;
+                    const float r = g.alpha * acc[i][j][4 * b + e];
+                    if (g.c_bf16) ((__hip_bfloat16*)g.C)[idx] = __float2bfloat16(r);
+                    else { float* c = (float*)g.C + idx; *c = g.accumulate ? r + *c : r; }
+                }
+            }
+        }
 }
 
 __device__ __forceinline__ void load_tile(const __hip_bfloat16* __restrict__ base, long long ld, int r0, int k0, int r_lim, int k_lim,
@@ -151,24 +248,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
         __syncthreads();
     }
 
-    // accumulator v of tile (i, j): row 32 i + 8 (v / 4) + 4 (lane / 32) + v % 4, column 32 j + lane % 32
-    const long long coff = z1 * g.sC1 + z2 * g.sC2;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lh + (v & 3);
-            if (row >= g.M) continue;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int col = n0 + wn + 32 * j + l32;
-                if (col >= g.N) continue;
-                const long long idx = coff + (long long)row * g.ldc + col;
-                float r = g.alpha * acc[i][j][v];
-                if (g.c_bf16) ((__hip_bfloat16*)g.C)[idx] = __float2bfloat16(r);
-                else { float* c = (float*)g.C + idx; if (g.accumulate) r += *c; *c = r; }
-            }
-        }
+    transpose_acc<4>(acc);
+    store_acc<4>(g, acc, m0 + __builtin_amdgcn_readfirstlane(wm), n0 + __builtin_amdgcn_readfirstlane(wn), z1 * g.sC1 + z2 * g.sC2);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -353,23 +434,173 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
 #undef TB_LOAD_FRAGS
 #undef TB_INTERLEAVE_DS
 
-    const long long coff = z1 * g.sC1 + z2 * g.sC2;
+    transpose_acc<TJ>(acc);
+    store_acc<TJ>(g, acc, m0 + __builtin_amdgcn_readfirstlane(wm), n0 + __builtin_amdgcn_readfirstlane(wn), z1 * g.sC1 + z2 * g.sC2);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Persistent form of the fast path: one workgroup per CU walks a host-built list of tiles (tile_schedule below) and the
+// ring of LDS stages runs as ONE stream of stages across tile boundaries.  While the last three stages of a tile are
+// multiplied the first three of the next tile are already being fetched, every stage of every tile takes the steady
+// path, and no workgroup is dispatched per tile: a dispatched 512-thread workgroup with 128 KB of LDS costs about
+// 0.4 us of its XCD's dispatcher (4096 empty ones take 0.2 ms), which together with the exposed ring fill and drain was
+// 12 - 15 us per tile, a third of the time of the short causal A X tiles.
+// Needs every tile's stage count to be a multiple of NS (k ranges that are multiples of 32 NS), so that tile boundaries
+// fall on the boundaries of the unrolled ring.  After the last stage of the list the stream keeps re-reading its final
+// stage (in bounds, never multiplied), so the count of outstanding loads a wait refers to never changes.
+template <int NS>
+__global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
+    constexpr int TJ = 2, LPW = 2;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    __hip_bfloat16* ring = (__hip_bfloat16*)smem;     // [NS][STAGE_ELEMS]
+
+    const bool causal = g.flags & TBOA_GEMM_CAUSAL_K;
+    const int2* __restrict__ my = g.sched + (long long)blockIdx.x * g.rounds;
+    const int seg_len = g.kseg > 0 ? g.kseg : g.K;
+    const int nseg = g.kseg > 0 ? g.K / g.kseg : 1;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave / 4) * 128, wn = (wave % 4) * 64;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    // a tile of the list, decoded: everything here is uniform over the workgroup
+    struct Tile { int valid, m0, n0, kend, nk; const char *A, *B; long long coff; };
+    auto decode = [&](int2 e) {
+        Tile t;
+        t.valid = e.x >= 0;
+        const int z = t.valid ? e.x : 0;
+        t.m0 = (e.y >> 16) * BM; t.n0 = (e.y & 0xffff) * BN;
+        const int z1 = z / g.batch_inner, z2 = z % g.batch_inner;
+        t.A = (const char*)(g.A + z1 * g.sA1 + z2 * g.sA2 + (long long)t.m0 * g.lda);
+        t.B = (const char*)(g.B + z1 * g.sB1 + z2 * g.sB2 + (long long)t.n0 * g.ldb);
+        t.coff = z1 * g.sC1 + z2 * g.sC2;
+        t.kend = causal ? min(seg_len, t.n0 + BN) : seg_len;
+        t.nk = t.kend / FK * nseg;
+        return t;
+    };
+    const int2 none = make_int2(-1, 0);
+    Tile cur = decode(my[0]);
+    if (!cur.valid) return;
+    Tile nxt = decode(g.rounds > 1 ? my[1] : none);
+    int2 raw2 = g.rounds > 2 ? my[2] : none;
+    int t_idx = 0;
+
+    // the stream of stages being fetched: position inside the tile it is in
+    unsigned offA[LPW], offB[LPW];
+    auto set_offsets = [&](int m0, int n0) {
+        const int pr = lane >> 2, ph = lane & 3;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lh + (v & 3);
-            if (row >= g.M) continue;
-#pragma unroll
-            for (int j = 0; j < TJ; ++j) {
-                const int col = n0 + wn + 32 * j + l32;
-                if (col >= g.N) continue;
-                const long long idx = coff + (long long)row * g.ldc + col;
-                float r = g.alpha * acc[i][j][v];
-                if (g.c_bf16) ((__hip_bfloat16*)g.C)[idx] = __float2bfloat16(r);
-                else { float* c = (float*)g.C + idx; if (g.accumulate) r += *c; *c = r; }
-            }
+        for (int i = 0; i < LPW; ++i) {
+            const int row = 16 * (wave * LPW + i) + pr;
+            const int lc = ph ^ ((row >> 2) & 3);
+            offA[i] = (unsigned)(((long long)min(row, g.M - 1 - m0) * g.lda + lc * 8) * 2);
+            offB[i] = (unsigned)(((long long)min(row, g.N - 1 - n0) * g.ldb + lc * 8) * 2);
         }
+    };
+    const char* sA = cur.A; const char* sB = cur.B;
+    long long koff = 0; int kin = 0, skend = cur.kend, sleft = cur.nk;
+    bool nxt_taken = false;
+    set_offsets(cur.m0, cur.n0);
+    // called after the loads of the stage the stream points to have been issued
+    auto advance = [&]() {
+        if (sleft == 0) return;
+        if (--sleft > 0) {
+            kin += FK; koff += 2 * FK;
+            if (kin == skend) { kin = 0; koff += 2LL * (seg_len - skend); }
+        } else if (nxt.valid && !nxt_taken) {
+            sA = nxt.A; sB = nxt.B; skend = nxt.kend; sleft = nxt.nk; koff = 0; kin = 0;
+            set_offsets(nxt.m0, nxt.n0);
+            nxt_taken = true;
+        }
+    };
+    const unsigned ring_lds = (unsigned)(unsigned long long)((__attribute__((address_space(3))) void*)ring);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+
+    f32x16 acc[4][TJ];
+    bf16x8 fa[2][4], fb[2][TJ];
+#define TB_LOAD_FRAGS(SET, SLOT, KS)                                                                        \
+    {                                                                                                       \
+        const __hip_bfloat16* a_s = ring + (SLOT) * STAGE_ELEMS;                                            \
+        const __hip_bfloat16* b_s = a_s + BM * FK;                                                          \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) fa[SET][i] = read_frag32(a_s, wm + 32 * i + l32, 2 * (KS) + lh); \
+        _Pragma("unroll") for (int i = 0; i < TJ; ++i) fb[SET][i] = read_frag32(b_s, wn + 32 * i + l32, 2 * (KS) + lh); \
+    }
+    // one stage: as in gemm_bf16_nt_fast_kernel, except that the loads issued between the MFMAs of phase 2 belong to the
+    // stream's position, which may already be in the next tile
+#define TB_STAGE(SLOT, NEXTSLOT, WAIT, FIRST)                                                               \
+    {                                                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        const char* pa_ = sA + koff; const char* pb_ = sB + koff;                                           \
+        const unsigned st_ = ring_lds + (unsigned)((SLOT) * STAGE_ELEMS * 2);                               \
+        TB_LOAD_FRAGS(1, SLOT, 1)                                                                           \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                       \
+            _Pragma("unroll") for (int jj = 0; jj < TJ; ++jj)                                               \
+                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][jj], (FIRST) ? zero16 : acc[i][jj], 0, 0, 0); \
+        __builtin_amdgcn_sched_group_barrier(0x100, 4 + TJ, 0);                                             \
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * TJ, 0);                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        if (WAIT) wait_loads_but<(NS - 2) * 2 * LPW>();                                                     \
+        else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                             \
+        __syncthreads();                                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        TB_LOAD_FRAGS(0, NEXTSLOT, 0)                                                                       \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                     \
+            _Pragma("unroll") for (int jj = 0; jj < TJ; jj += 2) {                                          \
+                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][jj], acc[i][jj], 0, 0, 0); \
+                acc[i][jj + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][jj + 1], acc[i][jj + 1], 0, 0, 0); \
+                const int q_ = (i * TJ + jj) / 2;              /* 0 .. 2 LPW - 1 */                           \
+                const unsigned blk_ = (unsigned)(wave_s * LPW + q_ / 2) * 1024u;                            \
+                __builtin_amdgcn_sched_barrier(0);                                                          \
+                if (q_ % 2 == 0) lds_direct_16(offA[q_ / 2], pa_, st_ + blk_);                              \
+                else lds_direct_16(offB[q_ / 2], pb_, st_ + (unsigned)(BM * FK * 2) + blk_);                \
+                __builtin_amdgcn_sched_barrier(0);                                                          \
+            }                                                                                               \
+        }                                                                                                   \
+        advance();                                                                                          \
+    }
+
+    // fill the ring: the first NS stages of the stream
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const unsigned st = ring_lds + (unsigned)(s * STAGE_ELEMS * 2);
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const unsigned blk = (unsigned)(wave_s * LPW + i) * 1024u;
+            lds_direct_16(offA[i], sA + koff, st + blk);
+            lds_direct_16(offB[i], sB + koff, st + (unsigned)(BM * FK * 2) + blk);
+        }
+        advance();
+    }
+    wait_loads_but<0>();      // all NS stages: the first tile starts like every other one, with NS - 1 stages known to be there
+    __syncthreads();
+    TB_LOAD_FRAGS(0, 0, 0)
+
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    while (true) {
+        const int nk = cur.nk;     // the first MFMAs of the tile start from zero: no pass over the accumulators
+        // stages 1 .. NS - 1 of the tile landed before the previous epilogue (or the fill): only the last stage of the first
+        // round waits, for stage NS
+#pragma unroll
+        for (int u = 0; u < NS; ++u) TB_STAGE(u, (u + 1) % NS, u == NS - 1, u == 0)
+        for (int kt = NS; kt < nk; kt += NS) {
+#pragma unroll
+            for (int u = 0; u < NS; ++u) TB_STAGE(u, (u + 1) % NS, true, false)
+        }
+        transpose_acc<TJ>(acc);
+        // every load of the stream issued so far (up to stage NS - 1 of the next tile) has landed before the first store is
+        // issued: the first NS - 1 stages of the next tile then need no wait, and by the time stage NS is awaited the stores
+        // (which count among the outstanding operations) have had NS - 1 stage times to be acknowledged
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        store_acc<TJ>(g, acc, cur.m0 + __builtin_amdgcn_readfirstlane(wm), cur.n0 + __builtin_amdgcn_readfirstlane(wn), cur.coff);
+        if (!nxt.valid) break;
+        cur = nxt;                       // the stream entered this tile at least one stage ago
+        nxt = decode(raw2); nxt_taken = false;
+        ++t_idx;
+        raw2 = t_idx + 2 < g.rounds ? my[t_idx + 2] : none;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the re-read stages still in flight write LDS
+#undef TB_STAGE
+#undef TB_LOAD_FRAGS
 }
 
 // Launch order of the output tiles of one batch entry, built once per (tile counts, flags) and kept on the device.
@@ -400,6 +631,65 @@ int tile_order(tboa_ctx* ctx, int tiles_m, int tiles_n, int flags, const int** d
     return 0;
 }
 
+// Tile lists of the persistent kernel: workgroup w (on XCD w % 8) takes its tiles from XCD (w % 8)'s contiguous run of
+// the item list (batch-major, the order above inside a batch entry).  Inside a window of the run (one batch entry, or
+// 128 items when entries are small) the tiles go, longest contraction first, each to the workgroup of that XCD with the
+// least work so far: with equal tiles that is round-robin (32 consecutive tiles side by side, as with dispatched
+// workgroups), with a causal limit it pairs long and short tiles so that all lists end together.
+int tile_schedule(tboa_ctx* ctx, const GemmBf16& q, int tiles_m, int tiles_n, const int2** dev, int* rounds, int* wgs) {
+    const int flags = q.flags & (TBOA_GEMM_LOWER | TBOA_GEMM_CAUSAL_K);
+    const int seg_len = (flags & TBOA_GEMM_CAUSAL_K) ? (q.kseg > 0 ? q.kseg : q.K) : 0;
+    for (const TileSchedule& t : ctx->tile_schedules)
+        if (t.tiles_m == tiles_m && t.tiles_n == tiles_n && t.flags == flags && t.batch == q.batch && t.seg_len == seg_len) {
+            *dev = t.dev; *rounds = t.rounds; *wgs = t.wgs; return 0;
+        }
+    std::vector<int> order;
+    {
+        const bool lower = flags & TBOA_GEMM_LOWER, causal = flags & TBOA_GEMM_CAUSAL_K;
+        const int band = (causal && !lower) ? 16 : 8;
+        for (int m0 = 0; m0 < tiles_m; m0 += band) {
+            const int m1 = m0 + band < tiles_m ? m0 + band : tiles_m;
+            for (int c = 0; c < tiles_n; ++c) {
+                const int tn = (causal && !lower) ? tiles_n - 1 - c : c;
+                for (int tm = m0; tm < m1; ++tm)
+                    if (!lower || tn <= tm) order.push_back((tm << 16) | tn);
+            }
+        }
+    }
+    const long long ntiles = (long long)order.size(), nitems = ntiles * q.batch, per = (nitems + 7) / 8;
+    const int wpx = (int)(per < 32 ? per : 32);
+    const long long window = ntiles >= 64 ? ntiles : 128;
+    std::vector<std::vector<int2>> lists((size_t)8 * wpx);
+    auto length = [&](int packed) { return seg_len ? std::min<long long>(seg_len, ((packed & 0xffff) + 1LL) * BN) : 1LL; };
+    for (int x = 0; x < 8; ++x) {
+        std::vector<long long> load(wpx, 0);
+        const long long lo = x * per, hi = std::min(nitems, lo + per);
+        for (long long w0 = lo; w0 < hi; w0 += window) {
+            const long long w1 = std::min(hi, w0 + window);
+            std::vector<long long> idx;
+            for (long long it = w0; it < w1; ++it) idx.push_back(it);
+            std::stable_sort(idx.begin(), idx.end(), [&](long long a, long long b) { return length(order[a % ntiles]) > length(order[b % ntiles]); });
+            for (long long it : idx) {
+                int best = 0;
+                for (int c = 1; c < wpx; ++c) if (load[c] < load[best]) best = c;
+                load[best] += length(order[it % ntiles]);
+                lists[(size_t)best * 8 + x].push_back(make_int2((int)(it / ntiles), order[it % ntiles]));
+            }
+        }
+    }
+    size_t r = 1;
+    for (auto& l : lists) r = std::max(r, l.size());
+    std::vector<int2> h((size_t)8 * wpx * r, make_int2(-1, 0));
+    for (size_t w = 0; w < lists.size(); ++w) std::copy(lists[w].begin(), lists[w].end(), h.begin() + w * r);
+    TileSchedule t{tiles_m, tiles_n, flags, q.batch, seg_len, nullptr, (int)r, 8 * wpx};
+    TB_HIP(ctx, hipMalloc(&t.dev, h.size() * sizeof(int2)));
+    hipError_t e = hipMemcpy(t.dev, h.data(), h.size() * sizeof(int2), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(t.dev); return tboa_fail(ctx, TBOA_EHIP, "tile schedule upload: %s", hipGetErrorString(e)); }
+    ctx->tile_schedules.push_back(t);
+    *dev = t.dev; *rounds = t.rounds; *wgs = t.wgs;
+    return 0;
+}
+
 }  // namespace
 
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
@@ -419,13 +709,16 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
         TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<4, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
         TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
         TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8, 5>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast5));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_stream_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
         attr_set = true;
     }
     const bool fast = (q.kseg > 0 ? q.kseg : q.K) % FK == 0 && q.K > 0 && !getenv("TBOA_GEMM_GENERIC");
     Args a;
+    a.sched = nullptr; a.rounds = 0;
     a.M = q.M; a.N = q.N; a.K = q.K; a.alpha = q.alpha;
     a.A = q.A; a.lda = q.lda; a.B = q.B; a.ldb = q.ldb; a.C = q.C; a.ldc = q.ldc;
     a.c_bf16 = (q.c_dtype == TBOA_BF16); a.accumulate = q.accumulate; a.flags = q.flags;
+    a.vec_c = q.ldc % 4 == 0 && q.strideC % 4 == 0 && q.strideC2 % 4 == 0 && ((uintptr_t)q.C & 15) == 0;
     a.batch_inner = q.batch_inner > 0 ? q.batch_inner : 1;
     a.kseg = q.kseg;
     if (q.kseg < 0 || (q.kseg > 0 && (q.K % q.kseg || q.kseg % 8))) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: kseg must divide K and be a multiple of 8");
@@ -452,7 +745,13 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     }
     static const int waves = getenv("TBOA_GEMM_WAVES") ? atoi(getenv("TBOA_GEMM_WAVES")) : 8;
     static const int ring = getenv("TBOA_GEMM_RING") ? atoi(getenv("TBOA_GEMM_RING")) : 4;
-    if (fast && waves == 8 && ring == 5) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<8, 5>), dim3(nwg), dim3(512), smem_fast5, ctx->stream, a);
+    static const int stream_mode = getenv("TBOA_GEMM_PERSISTENT") ? atoi(getenv("TBOA_GEMM_PERSISTENT")) : -1;   // -1: as the caller asks
+    const bool persistent = fast && (q.kseg > 0 ? q.kseg : q.K) % (FK * 4) == 0 && (stream_mode < 0 ? (q.flags & TBOA_GEMM_PERSISTENT) != 0 : stream_mode != 0);
+    if (persistent) {
+        int wgs = 0;
+        TB_TRY(tile_schedule(ctx, q, tiles_m, tiles_n, &a.sched, &a.rounds, &wgs));
+        hipLaunchKernelGGL((gemm_bf16_nt_stream_kernel<4>), dim3(wgs), dim3(512), smem_fast, ctx->stream, a);
+    } else if (fast && waves == 8 && ring == 5) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<8, 5>), dim3(nwg), dim3(512), smem_fast5, ctx->stream, a);
     else if (fast && waves == 8) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<8, 4>), dim3(nwg), dim3(512), smem_fast, ctx->stream, a);
     else if (fast) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<4, 4>), dim3(nwg), dim3(256), smem_fast, ctx->stream, a);
     else hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(nwg), dim3(256), smem, ctx->stream, a);

@@ -228,7 +228,10 @@ GemmBf16 nt(int M, int N, int K, float alpha, const bf16* A, long long lda, cons
             int c_dtype, int accumulate, int flags) {
     GemmBf16 g{};
     g.M = M; g.N = N; g.K = K; g.alpha = alpha; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
-    g.c_dtype = c_dtype; g.accumulate = accumulate; g.flags = flags; g.batch = 1; g.tag = TBOA_PROF_PROJ;
+    // The Hessian builds have the GPU to themselves, and most of their products have short contractions (a sequence, a
+    // head): the persistent kernel, which hides the ring fill and the tile's write-out, is the default here; the callers
+    // with long contractions (gram_splitk, the sums over a chunk of sequences) clear the flag.
+    g.c_dtype = c_dtype; g.accumulate = accumulate; g.flags = flags | TBOA_GEMM_PERSISTENT; g.batch = 1; g.tag = TBOA_PROF_PROJ;
     return g;
 }
 
@@ -237,7 +240,7 @@ int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_l
                 float* part, float* out) {
     const int Kc = K / splits;
     GemmBf16 g = nt(n, n, Kc, 1.f, A, ld, B, ld, part, n, TBOA_F32, 0, lower ? TBOA_GEMM_LOWER : 0);
-    g.tag = TBOA_PROF_GRAM;
+    g.tag = TBOA_PROF_GRAM; g.flags &= ~TBOA_GEMM_PERSISTENT;
     g.batch = splits; g.strideA = Kc; g.strideB = Kc; g.strideC = (long long)n * n;
     if (lower) TB_TRY(launch_fill_f32(ctx, part, (int64_t)splits * n * n, 0.f));
     TB_TRY(gemm_bf16_nt(ctx, g));
@@ -395,6 +398,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         }
         GemmBf16 h = nt(dm, dm, (int)ky, 1.f, YT, ldy, YT, ldy, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER);
         h.batch = Hkv; h.strideA = (long long)dm * ldy; h.strideB = h.strideA; h.strideC = dd; h.tag = TBOA_PROF_HV_SYRK;
+        h.flags &= ~TBOA_GEMM_PERSISTENT;
         TB_TRY(gemm_bf16_nt(ctx, h));
         if (rv) { h.tag = TBOA_PROF_RV; h.A = dYT; h.C = R_v; h.flags = 0; h.alpha = (float)d->alpha; TB_TRY(gemm_bf16_nt(ctx, h)); }
     }

@@ -12,6 +12,8 @@
 struct ProfRec { hipEvent_t a, b; int tag; double flops; };
 
 struct TileOrder { int tiles_m, tiles_n, flags; int* dev; int count; };   // gemm_bf16: launch order of the output tiles
+// gemm_bf16, persistent kernel: per workgroup the list of (batch entry, tm << 16 | tn) it works through, `rounds` entries each
+struct TileSchedule { int tiles_m, tiles_n, flags, batch, seg_len; int2* dev; int rounds, wgs; };
 
 struct tboa_ctx {
     int device;
@@ -25,6 +27,7 @@ struct tboa_ctx {
     std::vector<ProfRec> prof;
     long long counters[4];   // tboa_counter_id
     std::vector<TileOrder> tile_orders;   // device tables owned by the context
+    std::vector<TileSchedule> tile_schedules;
 };
 
 int tboa_fail(tboa_ctx* ctx, int code, const char* fmt, ...);

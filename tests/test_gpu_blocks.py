@@ -90,3 +90,38 @@ def test_gemm_bf16_flags_and_batch(ctx, lib):
     want2 = Xt.double().cpu().numpy() @ P.double().cpu().numpy().T
     got2 = ctx.gemm_bf16_nt(Xt, P, flags=lib.GEMM_CAUSAL_K).cpu().numpy()
     assert np.allclose(got2, want2, atol=1e-3)
+
+
+@pytest.mark.parametrize("M,N,K,batch,flags", [
+    (256, 256, 128, 1, 0),            # one tile, one ring fill
+    (700, 900, 384, 3, 0),            # ragged edges, fewer tiles than compute units
+    (2304, 2048, 256, 5, 0),          # 360 tiles: several rounds per workgroup, short tiles back to back
+    (1280, 1280, 512, 9, 1),          # symmetric product, lower tiles only
+    (520, 1536, 1536, 7, 2),          # causal limit: tiles of 8 different lengths, balanced lists
+])
+def test_gemm_bf16_persistent_matches_dispatched(ctx, lib, M, N, K, batch, flags):
+    """The persistent kernel (one resident workgroup per compute unit, one stream of stages across tiles) accumulates every
+    tile in the same order as the dispatched one: identical bits; both against fp64 on sampled entries."""
+    print("gemm_bf16 persistent", M, N, K, batch, flags, flush=True)
+    g = torch.Generator(device="cuda"); g.manual_seed(M + N + K + batch)
+    A = torch.randn(batch, M, K, generator=g, device="cuda").to(torch.bfloat16)
+    B = torch.randn(batch, N, K, generator=g, device="cuda").to(torch.bfloat16)
+    if flags & lib.GEMM_LOWER:
+        B = A
+    if flags & lib.GEMM_CAUSAL_K:
+        B = torch.tril(B)
+    for accumulate in (False, True):
+        C0 = torch.full((batch, M, N), 0.25, device="cuda")
+        want = ctx.gemm_bf16_nt(A, B, C_out=C0.clone(), accumulate=accumulate, flags=flags)
+        got = ctx.gemm_bf16_nt(A, B, C_out=C0.clone(), accumulate=accumulate, flags=flags | lib.GEMM_PERSISTENT)
+        assert torch.equal(got, want)
+    got16 = ctx.gemm_bf16_nt(A, B, out_dtype=torch.bfloat16, flags=flags | lib.GEMM_PERSISTENT)
+    want16 = ctx.gemm_bf16_nt(A, B, out_dtype=torch.bfloat16, flags=flags)
+    assert torch.equal(got16, want16)
+    r = np.random.default_rng(0)
+    for _ in range(200):
+        b, i, j = r.integers(batch), r.integers(M), r.integers(N)
+        if (flags & lib.GEMM_LOWER) and j // 256 > i // 256:
+            continue
+        ref = float(A[b, i].double() @ B[b, j].double())
+        assert abs(float(got[b, i, j]) - 0.25 - ref) <= 1e-5 * np.sqrt(K) * 4 + 1e-6 * abs(ref)
