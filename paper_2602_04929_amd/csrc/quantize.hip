@@ -115,26 +115,31 @@ __global__ void grid_argmin_kernel(const double* __restrict__ cost, const double
 }
 
 // ---- two-phase search: approximate costs of all candidates on the bf16 matrix cores, exact fp64 costs of the few
-// candidates within GRID_TAU of the approximate minimum.  delta and H_in are each split into an exact-to-16-bits
-// (hi, lo) bf16 pair and  delta H  ~  hi.hi + lo.hi + hi.lo  is one GEMM over the concatenated axis.
+// candidates within GRID_TAU of the approximate minimum.  delta is split into an exact-to-16-bits (hi, lo) bf16 pair, H_in
+// is rounded to bf16, and  delta H  ~  hi.hi + lo.hi  is one GEMM over the concatenated axis.  The rounding of delta has
+// to be carried to 16 bits because it differs from candidate to candidate; the rounding of H_in, E = H_in - hi(H_in), is
+// the same for all of them: it moves every cost by delta E delta^T <= 2^-9 |delta|^T |H_in| |delta|, in practice (entries
+// of E of either sign) by some 1e-5 of the cost, far inside GRID_TAU, and moves neighbouring candidates alike.
 constexpr int GRID_PAD = 256;        // extra elements per row of the concatenated operands (memory-channel spread)
 constexpr int GRID_KS = 6;          // exact re-evaluations per row
 constexpr double GRID_TAU = 2e-3;   // survivors: approximate cost <= (1 + tau) * approximate minimum
 
 typedef __hip_bfloat16 bf16;
 
-// Hcat[b, r, :] = [hi(H[r,:]) | hi(H[r,:]) | lo(H[r,:])]
+constexpr int GRID_TERMS = 2;        // segments of the concatenated contraction axis
+
+// Hcat[b, r, :] = [hi(H[r,:]) | hi(H[r,:])]
 __global__ void hcat_kernel(const double* __restrict__ H, bf16* __restrict__ out, int n, long long total) {
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
         const long long row = i / n; const int c = (int)(i % n);
         const float v = (float)H[i];
         const bf16 hi = __float2bfloat16(v);
-        bf16* o = out + row * (3 * n + GRID_PAD) + c;
-        o[0] = hi; o[n] = hi; o[2 * n] = __float2bfloat16(v - __bfloat162float(hi));
+        bf16* o = out + row * (GRID_TERMS * n + GRID_PAD) + c;
+        o[0] = hi; o[n] = hi;
     }
 }
 
-// Acat[(row, k), :] = [hi(delta) | lo(delta) | hi(delta)], delta as in grid_delta_kernel
+// Acat[(row, k), :] = [hi(delta) | lo(delta)], delta as in grid_delta_kernel
 __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
                                                                const double* __restrict__ cand_s, const double* __restrict__ cand_z,
                                                                bf16* __restrict__ Acat) {
@@ -144,14 +149,14 @@ __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __r
     const double w = Wk[(long long)row * ldw + c];
     const double* cs = cand_s + (long long)row * ncand;
     const double* cz = cand_z + (long long)row * ncand;
-    const long long pitch = 3LL * n + GRID_PAD;
+    const long long pitch = (long long)GRID_TERMS * n + GRID_PAD;
     bf16* out = Acat + (long long)row * ncand * pitch + c;
     for (int k = 0; k < ncand; ++k) {
         const double s = cs[k], z = cz[k];
         const float dl = (float)(s * (quant_code(w, s, z, maxq) - z) - w);
         const bf16 hi = __float2bfloat16(dl);
         bf16* o = out + (long long)k * pitch;
-        o[0] = hi; o[n] = __float2bfloat16(dl - __bfloat162float(hi)); o[2 * n] = hi;
+        o[0] = hi; o[n] = __float2bfloat16(dl - __bfloat162float(hi));
     }
 }
 
@@ -161,7 +166,7 @@ __global__ __launch_bounds__(256) void rowdot_split_kernel(const float* __restri
     const int lane = threadIdx.x & 63;
     const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
-    const float* g = G + row * n; const bf16* a = Acat + row * (3LL * n + GRID_PAD);
+    const float* g = G + row * n; const bf16* a = Acat + row * ((long long)GRID_TERMS * n + GRID_PAD);
     double s = 0.0;
     for (int c = lane; c < n; c += 64) s += (double)g[c] * ((double)__bfloat162float(a[c]) + (double)__bfloat162float(a[n + c]));
     s = wave_sum(s);
@@ -576,7 +581,7 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
                                L.cand_s, L.cand_z, Acat);
             TB_KERNEL_CHECK(ctx);
             GemmBf16 a{};
-            a.N = n; a.K = 3 * n; a.alpha = 1.f; a.A = Acat; a.lda = 3LL * n + GRID_PAD; a.ldb = a.lda; a.C = G32; a.ldc = n;
+            a.N = n; a.K = GRID_TERMS * n; a.alpha = 1.f; a.A = Acat; a.lda = (long long)GRID_TERMS * n + GRID_PAD; a.ldb = a.lda; a.C = G32; a.ldc = n;
             a.c_dtype = TBOA_F32; a.accumulate = 0; a.flags = 0; a.tag = TBOA_PROF_GRID;
             if (ph) { a.M = rows_per_head * ncand; a.batch = nu; a.B = L.Hcat + (long long)u0 * n * a.lda;
                       a.strideA = (long long)a.M * a.lda; a.strideB = (long long)n * a.lda; a.strideC = (long long)a.M * n; }
@@ -943,7 +948,7 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
         if (L.fast_grid) {
             L.DeltaS = ar.get<double>(grows * GRID_KS * n); L.GS = ar.get<double>(grows * GRID_KS * n);
             L.costS = ar.get<double>(grows * GRID_KS); L.sel = ar.get<int>(grows * (GRID_KS + 3));
-            L.Hcat = ar.get<__hip_bfloat16>((size_t)L.nhin * n * (3 * (size_t)n + GRID_PAD));
+            L.Hcat = ar.get<__hip_bfloat16>((size_t)L.nhin * n * (GRID_TERMS * (size_t)n + GRID_PAD));
         }
         L.Wbar = ar.get<double>(wn); L.Abar = ar.get<double>(wn); L.Z = ar.get<double>(wn);
         L.WR = R ? ar.get<double>(wn) : nullptr;
