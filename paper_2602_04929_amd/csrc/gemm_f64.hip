@@ -25,7 +25,7 @@ struct Args {
     double* C; long long ldc;
     long long strideA, strideB, strideC, strideA2, strideB2, strideC2;
     int batch_inner;
-    int klo_m, klo_n, khi_m, khi_n, skip_lower, skip_upper, skip_col0;
+    int klo_m, klo_n, khi_m, khi_n, skip_lower, skip_upper, skip_col0, diag_order;
     const int* m_limit;
 };
 
@@ -85,7 +85,11 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(Args g, bool vecA, bool v
     __shared__ __attribute__((aligned(16))) double As[2][TILE];
     __shared__ __attribute__((aligned(16))) double Bs[2][TILE];
 
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    // Workgroups go to the eight XCDs round-robin by linear number, so with a column count that is a multiple of 8 an XCD
+    // always gets the same tile columns; where the contraction length grows with the column (diag_order), the columns of
+    // each tile row are rotated by the row number so that every XCD sees all lengths.
+    const int tx = g.diag_order ? (int)((blockIdx.x + blockIdx.y) % gridDim.x) : (int)blockIdx.x;
+    const int m0 = blockIdx.y * BM, n0 = tx * BN;
     if (g.m_limit && m0 >= g.m_limit[blockIdx.z]) return;
     if (g.skip_lower && g.skip_col0 + n0 + BN <= m0) return;
     if (g.skip_upper && m0 + BM <= g.skip_col0 + n0) return;
@@ -184,7 +188,7 @@ int gemm_f64(tboa_ctx* ctx, const GemmF64& q) {
     a.strideA2 = q.strideA2; a.strideB2 = q.strideB2; a.strideC2 = q.strideC2;
     a.batch_inner = q.batch_inner > 0 ? q.batch_inner : 1;
     a.klo_m = q.klo_m; a.klo_n = q.klo_n; a.khi_m = q.khi_m; a.khi_n = q.khi_n;
-    a.skip_lower = q.skip_lower; a.skip_upper = q.skip_upper; a.skip_col0 = q.skip_col0; a.m_limit = q.m_limit;
+    a.skip_lower = q.skip_lower; a.skip_upper = q.skip_upper; a.skip_col0 = q.skip_col0; a.m_limit = q.m_limit; a.diag_order = q.diag_order;
     // 16-byte vector loads need every row start and the tile offsets (even) to stay 16-byte aligned
     const bool vecA = ((uintptr_t)q.A % 16 == 0) && (q.strideA % 2 == 0) && (q.strideA2 % 2 == 0) && ((akc ? q.sam : q.sak) % 2 == 0);
     const bool vecB = ((uintptr_t)q.B % 16 == 0) && (q.strideB % 2 == 0) && (q.strideB2 % 2 == 0) && ((bkc ? q.sbn : q.sbk) % 2 == 0);

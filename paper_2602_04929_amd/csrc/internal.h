@@ -83,6 +83,7 @@ struct GemmF64 {
     int skip_lower = 0;  // skip tiles entirely below the diagonal (col end <= row start): left untouched
     int skip_upper = 0;  // skip tiles entirely above the diagonal (row end <= col start)
     int skip_col0 = 0;   // column of C's first column relative to its first row, for the two tests above
+    int diag_order = 0;  // rotate the tile columns of tile row r by r: spreads column-dependent contraction lengths over the XCDs
     const int* m_limit = nullptr;   // device array [batch]: rows m >= m_limit[b] of batch entry b are not computed
 };
 int gemm_f64(tboa_ctx* ctx, const GemmF64& g);

@@ -703,6 +703,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
         b.M = n; b.N = n; b.K = n; b.alpha = 1.0; b.beta = 0.0;
         b.A = L.Hfac; b.sam = n; b.sak = 1; b.klo_m = 1;       // (R U^T)_masked[j, m] = 0 for m <= j
         b.B = L.Uin; b.sbk = n; b.sbn = 1; b.khi_n = 1;        // U[m, k] = 0 for m > k
+        b.diag_order = 1;                                      // contraction range (row start, column end]: grows with the column
         b.C = L.P; b.ldc = n; b.batch = nhin; b.strideA = nn; b.strideB = nn; b.strideC = nn;
         TB_TRY(gemm_f64(ctx, b));
     }
