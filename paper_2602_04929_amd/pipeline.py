@@ -13,13 +13,27 @@ def make_side_contexts(n=2):
     return [tb.Context(stream=torch.cuda.Stream()) for _ in range(n)]
 
 
+def _split_stacked(res, rows_q, heads_q):
+    """Per-layer views of a result of W_Q and W_K quantized as one stacked layer (heads are independent)."""
+    def part(rs, hs):
+        lph = res["loss_per_head"][hs]
+        d = {k: res[k][rs] for k in ("codes", "scales", "zeros", "W_deq")}
+        d.update(loss_per_head=lph, loss=float(sum(lph)), loss_quad=None, loss_cross=None)
+        return d
+    return part(slice(0, rows_q), slice(0, heads_q)), part(slice(rows_q, None), slice(heads_q, None))
+
+
 def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=True, cd_iters=1, adaptive_grid=True,
-                             damp=0.01, seq_chunk=0, timings=None, side_contexts=None):
+                             damp=0.01, seq_chunk=0, timings=None, side_contexts=None, stack_qk=True):
     """(rotation, activation fake-quant ->) Hessians -> W_Q, W_K, W_V -> output-projection Hessian -> W_O.
 
     blk: dict from synth.make_block (device tensors); cfg: synth.BlockConfig.  Returns dict of per-layer results
     and the Hessians.  `timings` (a dict) receives per-stage seconds measured with stream synchronisation.
-    side_contexts: two more contexts on streams of their own (see make_side_contexts): W_Q, W_K, W_V then run side by side."""
+    side_contexts: more contexts on streams of their own (see make_side_contexts): the layers then run side by side.
+    stack_qk: W_Q and W_K share H_in and R (Table 1) and their heads are independent, so [W_Q; W_K] goes through
+    tboa_quantize_layer as ONE layer of Hq + Hkv heads with H_out = [H_out^Q; H_out^K]: one factorisation of H_in, one P,
+    steps over twice the rows.  out["qk"] is that call's result, out["q"] and out["k"] are views of it (their loss is the sum
+    of their heads' losses; the split into the two loss terms exists for the stacked layer only)."""
     Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     X_fp = blk["X_fp"]
     X = blk["X"]
@@ -46,8 +60,15 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp)
     out = {"X": X, "X_fp": X_fp}
     Hs = stage("build_hessians", lambda: ctx.build_hessians(*hargs, **hkw))
-    jobs = (("q", (blk["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq)), ("k", (blk["Wk"], Hs["Hin_qk"], Hs["Hout_k"], Hs["R_qk"], Hkv)),
-            ("v", (blk["Wv"], Hs["Hin_v"], Hs["Hout_v"], Hs["R_v"], Hkv)))
+    if stack_qk:
+        Wqk = blk.get("Wqk")
+        if Wqk is None:
+            Wqk = torch.cat([blk["Wq"], blk["Wk"]], dim=0)
+        jobs = (("qk", (Wqk, Hs["Hin_qk"], torch.cat([Hs["Hout_q"], Hs["Hout_k"]], dim=0), Hs["R_qk"], Hq + Hkv)),
+                ("v", (blk["Wv"], Hs["Hin_v"], Hs["Hout_v"], Hs["R_v"], Hkv)))
+    else:
+        jobs = (("q", (blk["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq)), ("k", (blk["Wk"], Hs["Hin_qk"], Hs["Hout_k"], Hs["R_qk"], Hkv)),
+                ("v", (blk["Wv"], Hs["Hin_v"], Hs["Hout_v"], Hs["R_v"], Hkv)))
     if side_contexts:
         # W_Q, W_K, W_V are independent given the Hessians: one context (and stream) each, driven from three host threads, so
         # that the latency-bound steps of one layer (factorisation panels, in-channel sweeps) run beside the GEMMs of another.
@@ -59,7 +80,7 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
 
         def all_three():
             main = torch.cuda.current_stream()
-            ctxs = (ctx, side_contexts[0], side_contexts[1])
+            ctxs = (ctx,) + tuple(side_contexts[:len(jobs) - 1])
             for c in ctxs[1:]:
                 c._stream.wait_stream(main)
             threads = [threading.Thread(target=run, args=(name, c, args)) for (name, args), c in zip(jobs, ctxs)]
@@ -69,7 +90,7 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
                 t.join()
             for c in ctxs[1:]:
                 main.wait_stream(c._stream)
-            for name in ("k", "v"):
+            for name, _ in jobs[1:]:
                 for v in out[name].values():
                     if torch.is_tensor(v):
                         v.record_stream(main)
@@ -77,6 +98,8 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     else:
         for name, args in jobs:
             out[name] = stage("quantize_" + name, lambda a=args: ctx.quantize_layer(*a, **kw))
+    if stack_qk:
+        out["q"], out["k"] = _split_stacked(out["qk"], Hq * dh, Hq)
     out["hessians"] = Hs
     Ho = stage("build_hessian_out_proj", lambda: ctx.build_hessian_out_proj(
         X, Xf, out["q"]["W_deq"], out["k"]["W_deq"], out["v"]["W_deq"], blk["Wq"], blk["Wk"], blk["Wv"], Hq, Hkv, dh,

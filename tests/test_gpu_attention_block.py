@@ -30,22 +30,36 @@ def oracle_block(blk, cfg, alpha=0.25, use_R=True):
     return out
 
 
-@pytest.mark.parametrize("use_R,side", [(True, False), (False, False), (True, True)])
-def test_tiny_config_end_to_end(lib, use_R, side):
+def stacked(a, b):
+    """Oracle results of W_Q and W_K as the result of the one stacked layer [W_Q; W_K] (heads are independent)."""
+    out = {k: np.concatenate([a[k], b[k]], axis=0) for k in ("codes", "scales", "zeros", "W_deq")}
+    out.update({k: a[k] + b[k] for k in ("loss_quad", "loss_cross", "loss")})
+    out["loss_per_head"] = np.concatenate([np.asarray(a["loss_per_head"]), np.asarray(b["loss_per_head"])])
+    return out
+
+
+@pytest.mark.parametrize("use_R,side,stack", [(True, False, True), (False, False, True), (True, True, True), (True, False, False), (True, True, False)])
+def test_tiny_config_end_to_end(lib, use_R, side, stack):
     """Config 1 (d_model 256, 4 heads x 64, 8 x 128 tokens, INT2, N = 4, seed 0): every layer against the oracle,
-    each side building its own Hessians from the same X."""
+    each side building its own Hessians from the same X.  stack: W_Q and W_K through tboa_quantize_layer as one layer of
+    Hq + Hkv heads (they share H_in and R), which must give what the two separate calls give."""
     from paper_2602_04929_amd.pipeline import quantize_attention_block
     cfg = synth.CONFIGS["tiny"]
     blk = synth.make_block(cfg, seed=0, device="cuda")
     ctx = lib.Context()
     from paper_2602_04929_amd.pipeline import make_side_contexts
     sc = make_side_contexts(2) if side else None        # W_Q, W_K, W_V on three streams from three host threads
-    got = quantize_attention_block(ctx, blk, cfg, use_R=use_R, side_contexts=sc)
+    got = quantize_attention_block(ctx, blk, cfg, use_R=use_R, side_contexts=sc, stack_qk=stack)
     torch.cuda.synchronize()
     for c in sc or []:
         c.close()
     want = oracle_block(blk, cfg, use_R=use_R)
-    for layer in ("q", "k", "v", "o"):
+    if stack:
+        want["qk"] = stacked(want["q"], want["k"])
+        for layer, rows in (("q", slice(0, cfg.n_q_heads * cfg.head_dim)), ("k", slice(cfg.n_q_heads * cfg.head_dim, None))):
+            assert torch.equal(got[layer]["codes"], got["qk"]["codes"][rows]) and torch.equal(got[layer]["W_deq"], got["qk"]["W_deq"][rows])
+            assert abs(got[layer]["loss"] - want[layer]["loss"]) <= 1e-4 * abs(want[layer]["loss_quad"])
+    for layer in ("qk", "v", "o") if stack else ("q", "k", "v", "o"):
         frac = compare_layer(got[layer], want[layer], label=layer)
         print("tiny R=%s layer %s: codes identical %.4f%%" % (use_R, layer, 100 * frac), flush=True)
     ctx.close()
