@@ -110,7 +110,8 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     return out
 
 
-def quantize_mlp(ctx, mlp, cfg, alpha=0.25, use_R=True, cd_iters=1, adaptive_grid=True, damp=0.01, timings=None):
+def quantize_mlp(ctx, mlp, cfg, alpha=0.25, use_R=True, cd_iters=1, adaptive_grid=True, damp=0.01, timings=None,
+                 stack_gate_up=True):
     """The gated MLP of the block: W_gate and W_up share their input (one Hessian), W_down sees silu(gate) * up computed
     from the dequantized W_gate, W_up on the quantized-path input (and from the full-precision weights on the
     full-precision input for its deviation correlation).  Every layer: tboa_quantize_layer with H_out = NULL."""
@@ -129,8 +130,15 @@ def quantize_mlp(ctx, mlp, cfg, alpha=0.25, use_R=True, cd_iters=1, adaptive_gri
     kw = dict(bits=cfg.bits, group=cfg.group, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp)
     out = {}
     H, R = stage("hessian_gate_up", lambda: ctx.build_hessian_linear(M, Mf, alpha))
-    out["gate"] = stage("quantize_gate", lambda: ctx.quantize_layer(mlp["Wg"], H, None, R, 1, block=cfg.d_ff, **kw))
-    out["up"] = stage("quantize_up", lambda: ctx.quantize_layer(mlp["Wu"], H, None, R, 1, block=cfg.d_ff, **kw))
+    if stack_gate_up:   # same H_in and R, rows decouple (H_out = I): one layer of 2 d_ff rows, one factorisation and one P
+        Wgu = torch.cat([mlp["Wg"], mlp["Wu"]], dim=0)
+        res = stage("quantize_gate_up", lambda: ctx.quantize_layer(Wgu, H, None, R, 1, block=2 * cfg.d_ff, **kw))
+        out["gate_up"] = res
+        for name, rs in (("gate", slice(0, cfg.d_ff)), ("up", slice(cfg.d_ff, None))):
+            out[name] = {k: res[k][rs] for k in ("codes", "scales", "zeros", "W_deq")}
+    else:
+        out["gate"] = stage("quantize_gate", lambda: ctx.quantize_layer(mlp["Wg"], H, None, R, 1, block=cfg.d_ff, **kw))
+        out["up"] = stage("quantize_up", lambda: ctx.quantize_layer(mlp["Wu"], H, None, R, 1, block=cfg.d_ff, **kw))
     act = stage("swiglu", lambda: ctx.swiglu_forward(M, out["gate"]["W_deq"], out["up"]["W_deq"]))
     act_fp = stage("swiglu", lambda: ctx.swiglu_forward(M_fp, mlp["Wg"], mlp["Wu"])) if use_R else None
     Hd, Rd = stage("hessian_down", lambda: ctx.build_hessian_linear(act, act_fp, alpha))

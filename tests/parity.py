@@ -25,3 +25,14 @@ def compare_layer(got, want, min_code_match=0.999, rtol=1e-4, label=""):
     lph = np.asarray(got["loss_per_head"])
     assert np.allclose(lph, want["loss_per_head"], rtol=10 * rtol, atol=rtol * abs(want["loss"])), label + " loss_per_head"
     return frac
+
+
+def stacked(a, b, concat_heads=True):
+    """Oracle results of two layers that share H_in and R as the result of the one stacked layer [W_a; W_b]: rows
+    concatenated, loss terms summed; loss_per_head concatenated (the layers' heads stay heads) or, for layers without
+    out-channel coupling that are quantized as ONE head, summed."""
+    out = {k: np.concatenate([a[k], b[k]], axis=0) for k in ("codes", "scales", "zeros", "W_deq")}
+    out.update({k: a[k] + b[k] for k in ("loss_quad", "loss_cross", "loss")})
+    la, lb = np.asarray(a["loss_per_head"]), np.asarray(b["loss_per_head"])
+    out["loss_per_head"] = np.concatenate([la, lb]) if concat_heads else la + lb
+    return out

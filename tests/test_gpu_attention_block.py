@@ -5,7 +5,7 @@ import torch
 
 from oracle import turboboa_ref as O
 from paper_2602_04929_amd import synth
-from tests.parity import compare_layer
+from tests.parity import compare_layer, stacked
 
 pytestmark = pytest.mark.gpu
 
@@ -27,14 +27,6 @@ def oracle_block(blk, cfg, alpha=0.25, use_R=True):
     Hin_o, R_o = O.build_hessian_out_proj(X, Xf, out["q"]["W_deq"], out["k"]["W_deq"], out["v"]["W_deq"], W["Wq"], W["Wk"], W["Wv"],
                                           Hq, Hkv, dh, alpha=alpha)
     out["o"] = O.quantize_layer(W["Wo"], Hin_o, None, R_o, 1, **dict(kw, block=cfg.d_model))
-    return out
-
-
-def stacked(a, b):
-    """Oracle results of W_Q and W_K as the result of the one stacked layer [W_Q; W_K] (heads are independent)."""
-    out = {k: np.concatenate([a[k], b[k]], axis=0) for k in ("codes", "scales", "zeros", "W_deq")}
-    out.update({k: a[k] + b[k] for k in ("loss_quad", "loss_cross", "loss")})
-    out["loss_per_head"] = np.concatenate([np.asarray(a["loss_per_head"]), np.asarray(b["loss_per_head"])])
     return out
 
 

@@ -6,7 +6,7 @@ import torch
 
 from oracle import turboboa_ref as O
 from paper_2602_04929_amd import synth
-from tests.parity import compare_layer
+from tests.parity import compare_layer, stacked
 
 pytestmark = pytest.mark.gpu
 
@@ -61,15 +61,16 @@ def test_linear_hessian_and_swiglu_bf16(ctx, dequantized):
     assert (err <= 2.0 ** -8 * np.abs(want) + 1e-6 * np.abs(want).max()).all()
 
 
-@pytest.mark.parametrize("use_R", [True, False])
-def test_tiny_mlp_end_to_end(lib, use_R):
+@pytest.mark.parametrize("use_R,stack", [(True, True), (False, True), (True, False)])
+def test_tiny_mlp_end_to_end(lib, use_R, stack):
     """Tiny configuration (d 256, d_ff 512, 8 x 128 tokens, INT2): gate, up and down projections against the oracle, each
-    side computing its own Hessians and activations from the same inputs."""
+    side computing its own Hessians and activations from the same inputs.  stack: gate and up (same H_in and R, rows
+    decouple) through tboa_quantize_layer as one layer of 2 d_ff rows."""
     from paper_2602_04929_amd.pipeline import quantize_mlp
     cfg = synth.CONFIGS["tiny"]
     m = synth.make_mlp(cfg, seed=0, device="cuda")
     c = lib.Context()
-    got = quantize_mlp(c, m, cfg, use_R=use_R)
+    got = quantize_mlp(c, m, cfg, use_R=use_R, stack_gate_up=stack)
     M, Mf = f64(m["M"]), f64(m["M_fp"]) if use_R else None
     W = {k: f64(m[k]) for k in ("Wg", "Wu", "Wd")}
     kw = dict(bits=cfg.bits, group=cfg.group)
@@ -80,7 +81,10 @@ def test_tiny_mlp_end_to_end(lib, use_R):
     act_fp = O.swiglu(Mf, W["Wg"], W["Wu"]) if use_R else None
     Hd, Rd = O.build_hessian_linear(act, act_fp, 0.25)
     want["down"] = O.quantize_layer(W["Wd"], Hd, None, Rd, 1, block=cfg.d_model, **kw)
-    for layer in ("gate", "up", "down"):
+    if stack:
+        want["gate_up"] = stacked(want["gate"], want["up"], concat_heads=False)
+        assert torch.equal(got["gate"]["codes"], got["gate_up"]["codes"][:cfg.d_ff]) and torch.equal(got["up"]["W_deq"], got["gate_up"]["W_deq"][cfg.d_ff:])
+    for layer in ("gate_up", "down") if stack else ("gate", "up", "down"):
         frac = compare_layer(got[layer], want[layer], label=layer)
         print("tiny MLP R=%s layer %s: codes identical %.4f%%" % (use_R, layer, 100 * frac), flush=True)
     c.close()
