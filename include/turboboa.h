@@ -56,8 +56,12 @@ const char* tboa_last_error(const tboa_ctx* ctx);
  * number of rows with more near-minimal candidates than the pass can handle one by one and therefore evaluated every
  * candidate of every row in fp64; TBOA_CTR_GRID_EXACT_ROWS: single rows that had every candidate evaluated in fp64;
  * TBOA_CTR_GRID_SURVIVORS: near-minimal candidates that were evaluated exactly (rows with a single near-minimal
- * candidate need none). */
-enum tboa_counter_id { TBOA_CTR_GRID_PASSES = 0, TBOA_CTR_GRID_FALLBACKS = 1, TBOA_CTR_GRID_EXACT_ROWS = 2, TBOA_CTR_GRID_SURVIVORS = 3 };
+ * candidate need none).
+ * TBOA_CTR_WEIGHTS_INT_FORM / TBOA_CTR_WEIGHTS_HILO: dequantized fp32 weight matrices handed to
+ * tboa_build_hessian_out_proj or tboa_swiglu_forward that were found to be integer multiples of one step per row (one
+ * bf16 GEMM with exact operands per product) / that were not and went through the general two-term split. */
+enum tboa_counter_id { TBOA_CTR_GRID_PASSES = 0, TBOA_CTR_GRID_FALLBACKS = 1, TBOA_CTR_GRID_EXACT_ROWS = 2, TBOA_CTR_GRID_SURVIVORS = 3,
+                       TBOA_CTR_WEIGHTS_INT_FORM = 4, TBOA_CTR_WEIGHTS_HILO = 5 };
 int64_t tboa_counter(const tboa_ctx* ctx, int which);
 /* Bytes of context-owned workspace currently allocated (host value). */
 size_t tboa_workspace_bytes(const tboa_ctx* ctx);
@@ -103,6 +107,9 @@ int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* desc,
  * attention output concat_h(A_h V_h) computed from the DEQUANTIZED W_Q, W_K, W_V (fp32 [.., d]) on X;
  * R_o = alpha (X_o - X~_o) X_o^T with X~_o from the full-precision weights (x_dtype) on X_fp.
  *   Hin_o [Hq*dh, Hq*dh] fp32;  R_o same shape or NULL (then X_fp, Wq, Wk, Wv may be NULL).
+ * On the bf16 path a dequantized weight whose rows are integer multiples (|k| <= 256) of one step per row, as the W_deq
+ * of tboa_quantize_layer with per-row grids is, enters its products as those integers (exact in bf16) with the steps
+ * applied to the result; any other fp32 weight as an exact-to-16-bit (hi, lo) bf16 pair.  Synchronises the stream.
  */
 int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* desc,
                                 const void* X, const void* X_fp,
@@ -119,8 +126,9 @@ int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* desc,
 int tboa_build_hessian_linear(tboa_ctx* ctx, int64_t n_tokens, int d_in, int x_dtype, double alpha,
                               const void* X, const void* X_fp, float* H_in, float* R);
 /* Input of the down projection: Act = silu(X W_gate^T) * (X W_up^T), silu(g) = g / (1 + exp(-g)).
- *   X [n_tokens, d] (x_dtype); W_gate, W_up [d_ff, d] in w_dtype: x_dtype, or TBOA_F32 for dequantized weights (then used
- *   as exact-to-16-bit (hi, lo) bf16 pairs on the bf16 path); Act [n_tokens, d_ff] (x_dtype). */
+ *   X [n_tokens, d] (x_dtype); W_gate, W_up [d_ff, d] in w_dtype: x_dtype, or TBOA_F32 for dequantized weights (on the
+ *   bf16 path used in integer form or as (hi, lo) bf16 pairs, as in tboa_build_hessian_out_proj);
+ *   Act [n_tokens, d_ff] (x_dtype). */
 int tboa_swiglu_forward(tboa_ctx* ctx, int64_t n_tokens, int d, int d_ff, int x_dtype, const void* X,
                         int w_dtype, const void* W_gate, const void* W_up, void* Act);
 

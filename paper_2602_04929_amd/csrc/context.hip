@@ -91,7 +91,7 @@ extern "C" void tboa_destroy(tboa_ctx* ctx) {
     delete ctx;
 }
 
-extern "C" int64_t tboa_counter(const tboa_ctx* ctx, int which) { return (ctx && which >= 0 && which < 4) ? ctx->counters[which] : -1; }
+extern "C" int64_t tboa_counter(const tboa_ctx* ctx, int which) { return (ctx && which >= 0 && which < 6) ? ctx->counters[which] : -1; }
 extern "C" const char* tboa_last_error(const tboa_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 extern "C" size_t tboa_workspace_bytes(const tboa_ctx* ctx) { return ctx ? ctx->ws_bytes : 0; }
 

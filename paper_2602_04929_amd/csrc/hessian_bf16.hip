@@ -15,6 +15,7 @@
 // (K_h^T K_h = W_K,h H_in W_K,h^T exactly, there being no positional rotation in the block).
 #include "internal.h"
 #include <math.h>
+#include <stdlib.h>
 
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
 
@@ -54,12 +55,14 @@ __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__
     }
 }
 
-// fp32 [rows, H*dh] -> bf16 [rows, H, 3*dh]: (hi, lo, hi) for the left operand, (hi, hi, lo) for the right one
-__global__ void split3_kernel(const float* __restrict__ in, bf16* __restrict__ out, long long rows, int hd, int dh, int right) {
+// fp32 [rows, H*dh] -> bf16 [rows, H, 3*dh]: (hi, lo, hi) for the left operand, (hi, hi, lo) for the right one;
+// scale (or NULL): one factor per column of `in`, applied first (projections through integer-form weights)
+__global__ void split3_kernel(const float* __restrict__ in, const float* __restrict__ scale, bf16* __restrict__ out, long long rows, int hd,
+                              int dh, int right) {
     const long long tot = rows * hd;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
         const long long row = i / hd; const int c = (int)(i % hd), h = c / dh, e = c % dh;
-        const float v = in[i];
+        const float v = scale ? in[i] * scale[c] : in[i];
         const bf16 hi = __float2bfloat16(v);
         const bf16 lo = __float2bfloat16(v - __bfloat162float(hi));
         bf16* o = out + (row * (hd / dh) + h) * 3 * dh;
@@ -76,14 +79,70 @@ __global__ void split_hilo_kernel(const float* __restrict__ in, bf16* __restrict
     }
 }
 
-// V^T fp32 [rows, G*L] -> per-sequence segments of length L: (hi, lo) of V^T in segments 0, 1 and, when the
-// full-precision V~^T is given, V^T - V~^T in segment 2 and V~^T in segment 3
-__global__ void vt_segments_kernel(const float* __restrict__ in, const float* __restrict__ in_fp, bf16* __restrict__ out, int rows,
-                                   int G, int L, int nseg, long long ld) {
+// Integer form of a dequantized weight.  A row of W_deq = s (codes - z) holds integer multiples of its scale, and small
+// integers are exact in bf16: X W_deq^T = (X K^T) diag(step) with K = W_deq / step needs ONE bf16 GEMM with exact operands,
+// where the general (hi, lo) split of an fp32 weight needs two.  One workgroup per row takes the greatest common divisor
+// (Euclid's algorithm on floats, remainders below 1e-3 of the divisor counting as zero) of the distances of the entries
+// from the row minimum, checks that every entry is a multiple k of it with |k| <= 256 (up to fp32 rounding of the
+// entries: with |k| <= 256 a true remainder is at least 1/256 of the divisor), and refines the step as the least-squares
+// fit sum(w k) / sum(k k).  A row that is not of this form (weights that are not a dequantized uniform grid, group-wise
+// scales, a row whose used levels all sit a common factor apart from zero) raises *fail, and the caller keeps the
+// (hi, lo) path for the whole matrix.
+__device__ __forceinline__ float float_gcd(float a, float b) {
+    if (a == 0.f) return b;
+    if (b == 0.f) return a;
+    if (a < b) { const float t = a; a = b; b = t; }
+    for (int it = 0; it < 32; ++it) {
+        const float r = fabsf(a - b * rintf(a / b));
+        if (r <= 1e-3f * b) return b;
+        a = b; b = r;
+    }
+    return b;
+}
+
+__global__ __launch_bounds__(256) void int_form_kernel(const float* __restrict__ W, int n, bf16* __restrict__ K, float* __restrict__ step,
+                                                       int* __restrict__ fail) {
+    __shared__ float red[4]; __shared__ double redd[8];
+    const float* w = W + (long long)blockIdx.x * n;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    float m = INFINITY;
+    for (int c = threadIdx.x; c < n; c += 256) m = fminf(m, w[c]);
+    for (int o = 32; o > 0; o >>= 1) m = fminf(m, __shfl_xor(m, o, 64));
+    if (lane == 0) red[wv] = m;
+    __syncthreads();
+    m = fminf(fminf(red[0], red[1]), fminf(red[2], red[3]));
+    __syncthreads();
+    float d = fabsf(m);          // the minimum itself is a multiple of the step too
+    for (int c = threadIdx.x; c < n; c += 256) d = float_gcd(d, w[c] - m);
+    for (int o = 32; o > 0; o >>= 1) d = float_gcd(d, __shfl_xor(d, o, 64));
+    if (lane == 0) red[wv] = d;
+    __syncthreads();
+    d = float_gcd(float_gcd(red[0], red[1]), float_gcd(red[2], red[3]));
+    if (!(d > 0.f)) d = 1.f;     // an all-zero row
+    bool ok = true;
+    double swk = 0.0, skk = 0.0;
+    for (int c = threadIdx.x; c < n; c += 256) {
+        const float k = w[c] / d, kr = rintf(k);
+        if (!(fabsf(k - kr) <= 1e-3f) || fabsf(kr) > 256.f) ok = false;
+        swk += (double)w[c] * kr; skk += (double)kr * kr;
+    }
+    for (int o = 32; o > 0; o >>= 1) { swk += __shfl_xor(swk, o, 64); skk += __shfl_xor(skk, o, 64); }
+    if (lane == 0) { redd[wv] = swk; redd[4 + wv] = skk; }
+    const int all_ok = __syncthreads_and(ok);
+    swk = redd[0] + redd[1] + redd[2] + redd[3]; skk = redd[4] + redd[5] + redd[6] + redd[7];
+    const float st = skk > 0.0 ? (float)(swk / skk) : d;
+    for (int c = threadIdx.x; c < n; c += 256) K[(long long)blockIdx.x * n + c] = __float2bfloat16(rintf(w[c] / d));
+    if (threadIdx.x == 0) { step[blockIdx.x] = st; if (!all_ok || !(st > 0.f)) atomicOr(fail, 1); }
+}
+
+// V^T fp32 [rows, G*L] (times row_scale, if given) -> per-sequence segments of length L: (hi, lo) of V^T in segments
+// 0, 1 and, when the full-precision V~^T is given, V^T - V~^T in segment 2 and V~^T in segment 3
+__global__ void vt_segments_kernel(const float* __restrict__ in, const float* __restrict__ row_scale, const float* __restrict__ in_fp,
+                                   bf16* __restrict__ out, int rows, int G, int L, int nseg, long long ld) {
     const long long tot = (long long)rows * G * L;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
         const long long row = i / ((long long)G * L); const int s = (int)((i / L) % G), t = (int)(i % L);
-        const float v = in[i];
+        const float v = row_scale ? in[i] * row_scale[row] : in[i];
         const bf16 h = __float2bfloat16(v);
         bf16* o = out + row * ld + ((long long)s * nseg) * L + t;
         o[0] = h; o[L] = __float2bfloat16(v - __bfloat162float(h));
@@ -252,13 +311,13 @@ int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_l
 
 // Q^ [rows, Hq, 3 dh] and K^ [rows, Hkv, 3 dh] of `rows` tokens Xr [rows, d]; weights as one or two (hi, lo) bf16 terms
 int project_qk(const Dims& D, const bf16* Xr, int rows, const bf16* Wq, const bf16* Wq_lo, const bf16* Wk, const bf16* Wk_lo,
-               float* Qf, float* Kf, bf16* Qh, bf16* Kh) {
+               float* Qf, float* Kf, bf16* Qh, bf16* Kh, const float* q_scale = nullptr, const float* k_scale = nullptr) {
     TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, Wq, D.dm, Qf, D.dq, TBOA_F32, 0, 0)));
     if (Wq_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, Wq_lo, D.dm, Qf, D.dq, TBOA_F32, 1, 0)));
     TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk, D.dm, Kf, D.dkv, TBOA_F32, 0, 0)));
     if (Wk_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk_lo, D.dm, Kf, D.dkv, TBOA_F32, 1, 0)));
-    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dq)), dim3(256), 0, D.ctx->stream, Qf, Qh, (long long)rows, D.dq, D.dh, 0);
-    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dkv)), dim3(256), 0, D.ctx->stream, Kf, Kh, (long long)rows, D.dkv, D.dh, 1);
+    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dq)), dim3(256), 0, D.ctx->stream, Qf, q_scale, Qh, (long long)rows, D.dq, D.dh, 0);
+    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dkv)), dim3(256), 0, D.ctx->stream, Kf, k_scale, Kh, (long long)rows, D.dkv, D.dh, 1);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
 }
@@ -406,6 +465,26 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     return 0;
 }
 
+// Operands for products with a dequantized weight W [rows, n] fp32: the integer form (hi = K, lo = NULL, *scale = step per
+// row) when every row has it, else the general exact-to-16-bits pair (hi, lo), *scale = NULL.  Synchronises once.
+int weight_operands(tboa_ctx* ctx, const float* W, int rows, int n, bf16* hi, bf16* lo, float* step, const bf16** lo_out, const float** scale) {
+    static const bool off = getenv("TBOA_NO_INT_FORM") != nullptr;
+    int* flag = ctx->d_status + 4;
+    *lo_out = lo; *scale = nullptr;
+    if (!off) {
+        TB_HIP(ctx, hipMemsetAsync(flag, 0, sizeof(int), ctx->stream));
+        hipLaunchKernelGGL(int_form_kernel, dim3(rows), dim3(256), 0, ctx->stream, W, n, hi, step, flag);
+        TB_KERNEL_CHECK(ctx);
+        TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 4, flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+        TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if (ctx->h_status[4] == 0) { *lo_out = nullptr; *scale = step; ++ctx->counters[TBOA_CTR_WEIGHTS_INT_FORM]; return 0; }
+    }
+    ++ctx->counters[TBOA_CTR_WEIGHTS_HILO];
+    hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)rows * n)), dim3(256), 0, ctx->stream, W, hi, lo, (long long)rows * n);
+    TB_KERNEL_CHECK(ctx);
+    return 0;
+}
+
 int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, const bf16* X_fp, const float* Wq_deq,
                                 const float* Wk_deq, const float* Wv_deq, const bf16* Wq, const bf16* Wk, const bf16* Wv, float* Hin_o,
                                 float* R_o) {
@@ -417,7 +496,7 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
     const int nsg = fp ? 4 : 2, nsp = fp ? 3 : 2, splits = pick_splits(D.S);   // segments of V^T / of P
     const long long TP = (long long)T + PADE, ldp = (long long)nsp * L + PADE;
     bf16 *Wqh, *Wql, *Wkh, *Wkl, *Wvh, *Wvl, *Qh, *Kh, *Qhf, *Khf, *P, *VTc, *OT, *dOT;
-    float *Qf, *Kf, *VT32, *VT32f, *Sc, *Scf, *part;
+    float *Qf, *Kf, *VT32, *VT32f, *Sc, *Scf, *part, *steps;
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
         Wqh = ar.get<bf16>((size_t)dq * dm); Wql = ar.get<bf16>((size_t)dq * dm);
@@ -431,28 +510,31 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         VTc = ar.get<bf16>((size_t)dkv * (G * nsg * L + PADE));
         OT = ar.get<bf16>((size_t)dq * TP); dOT = fp ? ar.get<bf16>((size_t)dq * TP) : nullptr;
         part = ar.get<float>((size_t)splits * dq * dq);
+        steps = ar.get<float>((size_t)dq + 2 * dkv);
         if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
     }
     hipStream_t st = ctx->stream;
-    // dequantized weights as exact-to-16-bits (hi, lo) bf16 pairs
-    hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dq * dm)), dim3(256), 0, st, Wq_deq, Wqh, Wql, (long long)dq * dm);
-    hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dkv * dm)), dim3(256), 0, st, Wk_deq, Wkh, Wkl, (long long)dkv * dm);
-    hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dkv * dm)), dim3(256), 0, st, Wv_deq, Wvh, Wvl, (long long)dkv * dm);
-    TB_KERNEL_CHECK(ctx);
+    // dequantized weights in integer form (one GEMM per product) or as exact-to-16-bits (hi, lo) bf16 pairs (two)
+    const bf16 *Wql_u, *Wkl_u, *Wvl_u; const float *sq, *sk, *sv;
+    TB_TRY(weight_operands(ctx, Wq_deq, dq, dm, Wqh, Wql, steps, &Wql_u, &sq));
+    TB_TRY(weight_operands(ctx, Wk_deq, dkv, dm, Wkh, Wkl, steps + dq, &Wkl_u, &sk));
+    TB_TRY(weight_operands(ctx, Wv_deq, dkv, dm, Wvh, Wvl, steps + dq + dkv, &Wvl_u, &sv));
     const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
     for (int s0 = 0; s0 < D.S; s0 += G) {
         const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
         const long long t0 = (long long)s0 * L, ldv = (long long)Gc * nsg * L + PADE;
         const bf16* Xc = X + t0 * dm;
-        // V'^T = Wv_deq Xc^T (fp32, from the (hi, lo) weight pair) and the full-precision V~^T = Wv X~c^T
+        // V'^T = Wv_deq Xc^T (fp32; the row steps of the integer form are applied by vt_segments_kernel) and the
+        // full-precision V~^T = Wv X~c^T
         TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvh, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 0, 0)));
-        TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvl, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 1, 0)));
-        TB_TRY(project_qk(D, Xc, Gc * L, Wqh, Wql, Wkh, Wkl, Qf, Kf, Qh, Kh));
+        if (Wvl_u) TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvl_u, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 1, 0)));
+        TB_TRY(project_qk(D, Xc, Gc * L, Wqh, Wql_u, Wkh, Wkl_u, Qf, Kf, Qh, Kh, sq, sk));
         if (fp) {
             TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wv, dm, X_fp + t0 * dm, dm, VT32f, (long long)Gc * L, TBOA_F32, 0, 0)));
             TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
         }
-        hipLaunchKernelGGL(vt_segments_kernel, dim3(g1((long long)dkv * Gc * L)), dim3(256), 0, st, VT32, fp ? VT32f : nullptr, VTc, dkv, Gc, L, nsg, ldv);
+        hipLaunchKernelGGL(vt_segments_kernel, dim3(g1((long long)dkv * Gc * L)), dim3(256), 0, st, VT32, sv, fp ? VT32f : nullptr, VTc, dkv, Gc, L,
+                           nsg, ldv);
         TB_KERNEL_CHECK(ctx);
         for (int sl = 0; sl < Gc; ++sl) {
             // V^T segments [V'hi | V'lo | V' - V~ | V~], P = [A' | A' | A' - A~]:
@@ -475,12 +557,15 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
     return 0;
 }
 
-// Act[t, c] = silu(G[t, c]) U[t, c], silu(g) = g / (1 + exp(-g))
+// Act[t, c] = silu(G[t, c]) U[t, c], silu(g) = g / (1 + exp(-g)); gs, us (or NULL): factors per column c of G and U,
+// applied first (projections through integer-form weights)
 template <typename TO>
-__global__ void swiglu_kernel(const float* __restrict__ G, const float* __restrict__ U, TO* __restrict__ out, long long n) {
+__global__ void swiglu_kernel(const float* __restrict__ G, const float* __restrict__ U, const float* __restrict__ gs, const float* __restrict__ us,
+                              int dff, TO* __restrict__ out, long long n) {
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
-        const float g = G[i];
-        out[i] = (TO)((g / (1.0f + __expf(-g))) * U[i]);
+        const int c = (int)(i % dff);
+        const float g = gs ? G[i] * gs[c] : G[i], u = us ? U[i] * us[c] : U[i];
+        out[i] = (TO)((g / (1.0f + __expf(-g))) * u);
     }
 }
 
@@ -511,19 +596,22 @@ int swiglu_forward_bf16(tboa_ctx* ctx, long long T, int d, int dff, const bf16* 
     if (d % 8 || dff % 8) return tboa_fail(ctx, TBOA_EINVAL, "swiglu_forward: d and d_ff must be multiples of 8 for bf16 inputs");
     const bool split = (w_dtype == TBOA_F32);
     const long long chunk = 16384;
-    bf16 *Wgh = nullptr, *Wgl = nullptr, *Wuh = nullptr, *Wul = nullptr; float *G, *U;
+    bf16 *Wgh = nullptr, *Wgl = nullptr, *Wuh = nullptr, *Wul = nullptr; float *G, *U, *steps = nullptr;
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
-        if (split) { Wgh = ar.get<bf16>((size_t)dff * d); Wgl = ar.get<bf16>((size_t)dff * d); Wuh = ar.get<bf16>((size_t)dff * d); Wul = ar.get<bf16>((size_t)dff * d); }
+        if (split) {
+            Wgh = ar.get<bf16>((size_t)dff * d); Wgl = ar.get<bf16>((size_t)dff * d); Wuh = ar.get<bf16>((size_t)dff * d); Wul = ar.get<bf16>((size_t)dff * d);
+            steps = ar.get<float>((size_t)2 * dff);
+        }
         G = ar.get<float>((size_t)chunk * dff); U = ar.get<float>((size_t)chunk * dff);
         if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
     }
     hipStream_t st = ctx->stream;
     const bf16* g_hi = (const bf16*)Wg; const bf16* u_hi = (const bf16*)Wu;
-    if (split) {
-        hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dff * d)), dim3(256), 0, st, (const float*)Wg, Wgh, Wgl, (long long)dff * d);
-        hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)dff * d)), dim3(256), 0, st, (const float*)Wu, Wuh, Wul, (long long)dff * d);
-        TB_KERNEL_CHECK(ctx);
+    const bf16 *g_lo = nullptr, *u_lo = nullptr; const float *gs = nullptr, *us = nullptr;
+    if (split) {   // fp32 (dequantized) weights: integer form, one GEMM each, or the (hi, lo) pair, two
+        TB_TRY(weight_operands(ctx, (const float*)Wg, dff, d, Wgh, Wgl, steps, &g_lo, &gs));
+        TB_TRY(weight_operands(ctx, (const float*)Wu, dff, d, Wuh, Wul, steps + dff, &u_lo, &us));
         g_hi = Wgh; u_hi = Wuh;
     }
     for (long long t0 = 0; t0 < T; t0 += chunk) {
@@ -531,11 +619,10 @@ int swiglu_forward_bf16(tboa_ctx* ctx, long long T, int d, int dff, const bf16* 
         const bf16* Xc = X + t0 * d;
         TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, g_hi, d, G, dff, TBOA_F32, 0, 0)));
         TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, u_hi, d, U, dff, TBOA_F32, 0, 0)));
-        if (split) {
-            TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, Wgl, d, G, dff, TBOA_F32, 1, 0)));
-            TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, Wul, d, U, dff, TBOA_F32, 1, 0)));
-        }
-        hipLaunchKernelGGL(swiglu_kernel<bf16>, dim3(g1((long long)rows * dff)), dim3(256), 0, st, G, U, Act + t0 * dff, (long long)rows * dff);
+        if (g_lo) TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, g_lo, d, G, dff, TBOA_F32, 1, 0)));
+        if (u_lo) TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, u_lo, d, U, dff, TBOA_F32, 1, 0)));
+        hipLaunchKernelGGL(swiglu_kernel<bf16>, dim3(g1((long long)rows * dff)), dim3(256), 0, st, G, U, gs, us, dff, Act + t0 * dff,
+                           (long long)rows * dff);
         TB_KERNEL_CHECK(ctx);
     }
     return 0;

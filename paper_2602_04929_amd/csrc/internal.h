@@ -25,7 +25,7 @@ struct tboa_ctx {
     int* h_status;       // pinned host mirror
     int prof_on;         // record HIP events around tagged GEMM launches
     std::vector<ProfRec> prof;
-    long long counters[4];   // tboa_counter_id
+    long long counters[8];   // tboa_counter_id
     std::vector<TileOrder> tile_orders;   // device tables owned by the context
     std::vector<TileSchedule> tile_schedules;
 };

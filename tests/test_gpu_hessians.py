@@ -119,6 +119,39 @@ def test_out_proj_bf16(ctx):
     assert R2 is None and rel_err(np64(H2), wH) <= 2e-3
 
 
+def uniform_grid_weights(w, bits, g):
+    """Rows of s_r * (codes - z_r): what a per-row uniform quantizer leaves (input construction, not the method)."""
+    lo, hi = w.min(dim=1, keepdim=True).values.clamp(max=0), w.max(dim=1, keepdim=True).values.clamp(min=0)
+    s = (hi - lo) / (2 ** bits - 1) * (0.7 + 0.3 * torch.rand(lo.shape, generator=g, device=w.device))
+    z = torch.round(-lo / s)
+    return (s * (torch.clamp(torch.round(w / s) + z, 0, 2 ** bits - 1) - z)).float()
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_out_proj_bf16_integer_form_weights(ctx, lib, bits):
+    """Dequantized weights that sit on a per-row uniform grid enter their products as exact small integers (one bf16 GEMM,
+    steps applied afterwards); a weight without that structure in the same call keeps the two-term split."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=264, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=3, seq_len=320, n_outlier=3)
+    b = synth.make_block(cfg, seed=6, device="cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(2)
+    deq = [uniform_grid_weights(w.float(), bits, g) for w in (b["Wq"], b["Wk"], b["Wv"])]
+    n_int, n_split = ctx.counter(4), ctx.counter(5)
+    Hin_o, R_o = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, b["Wq"], b["Wk"], b["Wv"], 4, 2, 32, alpha=0.25, seq_chunk=2)
+    assert ctx.counter(4) == n_int + 3 and ctx.counter(5) == n_split
+    wH, wR = O.build_hessian_out_proj(np64(b["X"]), np64(b["X_fp"]), *[np64(w) for w in deq], np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]),
+                                      4, 2, 32, alpha=0.25)
+    eH, eR = rel_err(np64(Hin_o), wH), rel_err(np64(R_o), wR)
+    print("integer-form weights, %d bits: Hin_o %.2e R_o %.2e" % (bits, eH, eR), flush=True)
+    # at 960 tokens the bf16 rounding of the probabilities and of the attention output dominates: 1 - 2e-3 here on either
+    # path (the two-term split gives the same figures to three digits on these inputs)
+    assert eH <= 3e-3 and eR <= 2e-2
+    deq[1] = deq[1] * (1 + 0.01 * torch.randn(deq[1].shape, generator=g, device="cuda"))     # W_K off the grid
+    H2, _ = ctx.build_hessian_out_proj(b["X"], None, *deq, None, None, None, 4, 2, 32, seq_chunk=3)
+    assert ctx.counter(4) == n_int + 5 and ctx.counter(5) == n_split + 1
+    wH2, _ = O.build_hessian_out_proj(np64(b["X"]), None, *[np64(w) for w in deq], None, None, None, 4, 2, 32)
+    assert rel_err(np64(H2), wH2) <= 3e-3
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_act_fakequant(ctx, dtype):
     g = torch.Generator(device="cuda"); g.manual_seed(5)

@@ -39,7 +39,7 @@ def test_linear_hessian_and_swiglu_fp32(ctx):
     assert act.shape == (3, 50, 100) and rel(f64(act), want) <= 1e-6
 
 
-@pytest.mark.parametrize("dequantized", [False, True])
+@pytest.mark.parametrize("dequantized", [False, True, "grid"])
 def test_linear_hessian_and_swiglu_bf16(ctx, dequantized):
     """bf16 path at sizes that span several 256-tiles with ragged edges (T = 960, d = 264, d_ff = 392)."""
     cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=264, n_seqs=3, seq_len=320, n_outlier=3, d_ff=392)
@@ -50,11 +50,21 @@ def test_linear_hessian_and_swiglu_bf16(ctx, dequantized):
     assert rel(f64(H), wH) <= 1e-5 and rel(f64(R), wR) <= 1e-4
     assert torch.equal(H, H.T)
     Wg, Wu = m["Wg"], m["Wu"]
-    if dequantized:      # fp32 weights that are not representable in bf16: the (hi, lo) split must carry them
+    n_int, n_split = ctx.counter(4), ctx.counter(5)
+    if dequantized == "grid":     # fp32 weights on a per-row uniform INT3 grid: taken as exact small integers times a step per row
+        g = torch.Generator(device="cuda"); g.manual_seed(3)
+        def on_grid(w):
+            lo, hi = w.min(dim=1, keepdim=True).values.clamp(max=0), w.max(dim=1, keepdim=True).values.clamp(min=0)
+            s = (hi - lo) / 7 * (0.7 + 0.3 * torch.rand(lo.shape, generator=g, device="cuda"))
+            z = torch.round(-lo / s)
+            return (s * (torch.clamp(torch.round(w / s) + z, 0, 7) - z)).float()
+        Wg, Wu = on_grid(Wg.float()), on_grid(Wu.float())
+    elif dequantized:      # fp32 weights that are not representable in bf16: the (hi, lo) split must carry them
         g = torch.Generator(device="cuda"); g.manual_seed(3)
         Wg = Wg.float() * (1 + 0.01 * torch.randn(Wg.shape, generator=g, device="cuda"))
         Wu = Wu.float() * (1 + 0.01 * torch.randn(Wu.shape, generator=g, device="cuda"))
     act = ctx.swiglu_forward(m["M"], Wg, Wu)
+    assert (ctx.counter(4) - n_int, ctx.counter(5) - n_split) == {False: (0, 0), True: (0, 2), "grid": (2, 0)}[dequantized]
     want = O.swiglu(f64(m["M"]), f64(Wg), f64(Wu))
     err = np.abs(f64(act) - want)
     # the result is stored in bf16: half an ulp of the value, plus the fp32 arithmetic before it
