@@ -96,12 +96,18 @@ typedef struct {
  * The outputs come in independent parts, and a part whose pointers are NULL is not computed: {Hin_qk, Hout_q, Hout_k
  * (+ R_qk)} (all three or none), {Hin_v (+ R_v)} (by far the most expensive part), {Hout_v}.  A caller may so obtain the
  * factors of W_Q and W_K first and quantize them on other streams while the W_V part is still being built.
+ *   fp_cache  NULL, or caller-allocated device memory of tboa_fp_cache_bytes(desc) bytes (16-byte aligned; needs R_v):
+ *             receives the projections of X_fp by the full-precision W_Q and W_K (an opaque layout), which both this call
+ *             and tboa_build_hessian_out_proj need for their deviation terms; handing the buffer to the latter saves it two
+ *             projections per token.  Valid for the (desc, X_fp, Wq, Wk) of this call.  Used on the bf16 path only
+ *             (tboa_fp_cache_bytes is 0 for fp32 inputs: pass NULL).
  */
+size_t tboa_fp_cache_bytes(const tboa_attn_desc* desc);
 int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* desc,
                         const void* X, const void* X_fp,
                         const void* Wq, const void* Wk, const void* Wv, const void* Wo,
                         float* Hin_qk, float* R_qk, float* Hout_q, float* Hout_k,
-                        float* Hin_v, float* R_v, float* Hout_v);
+                        float* Hin_v, float* R_v, float* Hout_v, void* fp_cache);
 
 /* Hessian of the output projection: the layer-wise row of Table 1, X_o X_o^T (x) I, with X_o the
  * attention output concat_h(A_h V_h) computed from the DEQUANTIZED W_Q, W_K, W_V (fp32 [.., d]) on X;
@@ -110,12 +116,14 @@ int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* desc,
  * On the bf16 path a dequantized weight whose rows are integer multiples (|k| <= 256) of one step per row, as the W_deq
  * of tboa_quantize_layer with per-row grids is, enters its products as those integers (exact in bf16) with the steps
  * applied to the result; any other fp32 weight as an exact-to-16-bit (hi, lo) bf16 pair.  Synchronises the stream.
+ *   fp_cache  NULL, or the buffer a tboa_build_hessians call with the same desc, X_fp, Wq, Wk filled (bf16 path, R_o
+ *             requested): the projections of X_fp are then read from it and Wq, Wk may be NULL.
  */
 int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* desc,
                                 const void* X, const void* X_fp,
                                 const float* Wq_deq, const float* Wk_deq, const float* Wv_deq,
                                 const void* Wq, const void* Wk, const void* Wv,
-                                float* Hin_o, float* R_o);
+                                float* Hin_o, float* R_o, const void* fp_cache);
 
 /* Gated MLP of the same transformer block (W_gate, W_up: [d_ff, d]; W_down: [d, d_ff]).  Its three projections are plain
  * linear layers: the layer-wise row of Table 1 (H = X X^T (x) I, no out-channel coupling), quantized by

@@ -53,8 +53,9 @@ def _load():
         "tboa_gemm_f64": ([vp, i32, i32, i32, f64, vp, i64, i64, vp, i64, i64, f64, vp, i64, i32, i64, i64, i64], i32),
         "tboa_gemm_bf16_nt": ([vp, i32, i32, i32, f32, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i64, i64, i64], i32),
         "tboa_chol_inv_upper": ([vp, i32, i32, vp, f64, vp], i32),
-        "tboa_build_hessians": ([vp, C.POINTER(AttnDesc)] + [vp] * 13, i32),
-        "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 10, i32),
+        "tboa_build_hessians": ([vp, C.POINTER(AttnDesc)] + [vp] * 14, i32),
+        "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 11, i32),
+        "tboa_fp_cache_bytes": ([C.POINTER(AttnDesc)], C.c_size_t),
         "tboa_act_fakequant": ([vp, i64, i32, i32, i32, vp, vp], i32),
         "tboa_hadamard_rotate": ([vp, i64, i32, i32, vp, vp, vp], i32),
         "tboa_build_hessian_linear": ([vp, i64, i32, i32, f64, vp, vp, vp, vp], i32),
@@ -123,7 +124,8 @@ class Context:
             raise TurboBoAError(rc, _lib.tboa_last_error(self._h).decode())
 
     def counter(self, which):
-        """0: two-phase grid-search passes, 1: passes that fell back to exact evaluation of every candidate."""
+        """tboa_counter_id: 0 two-phase grid-search passes, 1 passes that evaluated every candidate exactly, 2 rows that did,
+        3 near-minimal candidates evaluated exactly, 4 / 5 dequantized weight matrices taken in integer form / split."""
         return int(_lib.tboa_counter(self._h, which))
 
     def workspace_bytes(self):
@@ -181,8 +183,10 @@ class Context:
 
     # ---- the method
     def build_hessians(self, X, X_fp, Wq, Wk, Wv, Wo, n_q_heads, n_kv_heads, head_dim, alpha=0.0, causal=True,
-                       with_R_v=True, seq_chunk=0, parts="all"):
-        """parts: "all", "qk" (H_in, R, H_out of W_Q and W_K, plus H_out of W_V) or "v" (H_in, R of W_V)."""
+                       with_R_v=True, seq_chunk=0, parts="all", keep_fp_projections=False):
+        """parts: "all", "qk" (H_in, R, H_out of W_Q and W_K, plus H_out of W_V) or "v" (H_in, R of W_V).
+        keep_fp_projections: also returns "fp_cache", the buffer tboa_build_hessian_out_proj can reuse (None when the
+        library has no use for one: fp32 inputs, or no R_v)."""
         S, L, d = X.shape
         dt = X.dtype
         for t in (X, Wq, Wk, Wv, Wo):
@@ -203,14 +207,20 @@ class Context:
             out["Hin_v"] = torch.empty(n_kv_heads, d, d, **f)
             if X_fp is not None and with_R_v:
                 out["R_v"] = torch.empty(n_kv_heads, d, d, **f)
+        cache = None
+        if keep_fp_projections and out["R_v"] is not None:
+            nbytes = int(_lib.tboa_fp_cache_bytes(C.byref(desc)))
+            cache = torch.empty(nbytes, dtype=torch.uint8, device=X.device) if nbytes else None
         self._check(_lib.tboa_build_hessians(self._h, C.byref(desc), _ptr(X), _ptr(X_fp if (qk or out["R_v"] is not None) else None),
                                              _ptr(Wq), _ptr(Wk), _ptr(Wv),
                                              _ptr(Wo), _ptr(out["Hin_qk"]), _ptr(out["R_qk"]), _ptr(out["Hout_q"]),
-                                             _ptr(out["Hout_k"]), _ptr(out["Hin_v"]), _ptr(out["R_v"]), _ptr(out["Hout_v"])))
+                                             _ptr(out["Hout_k"]), _ptr(out["Hin_v"]), _ptr(out["R_v"]), _ptr(out["Hout_v"]), _ptr(cache)))
+        if keep_fp_projections:
+            out["fp_cache"] = cache
         return out
 
     def build_hessian_out_proj(self, X, X_fp, Wq_deq, Wk_deq, Wv_deq, Wq, Wk, Wv, n_q_heads, n_kv_heads, head_dim,
-                               alpha=0.0, causal=True, seq_chunk=0):
+                               alpha=0.0, causal=True, seq_chunk=0, fp_cache=None):
         S, L, d = X.shape
         for t in (Wq_deq, Wk_deq, Wv_deq):
             _dev(t, torch.float32)
@@ -220,7 +230,7 @@ class Context:
         R_o = torch.empty_like(Hin_o) if X_fp is not None else None
         self._check(_lib.tboa_build_hessian_out_proj(self._h, C.byref(desc), _ptr(_dev(X)), _ptr(X_fp), _ptr(Wq_deq),
                                                      _ptr(Wk_deq), _ptr(Wv_deq), _ptr(Wq), _ptr(Wk), _ptr(Wv),
-                                                     _ptr(Hin_o), _ptr(R_o)))
+                                                     _ptr(Hin_o), _ptr(R_o), _ptr(fp_cache)))
         return Hin_o, R_o
 
     def act_fakequant(self, X, bits, out=None):

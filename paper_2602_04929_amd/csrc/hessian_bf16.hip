@@ -351,7 +351,8 @@ int check_bf16_dims(const Dims& D) {
 }
 
 int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, const bf16* X_fp, const bf16* Wq, const bf16* Wk,
-                        const bf16* Wo, float* Hin_qk, float* R_qk, float* Hout_q, float* Hout_k, float* Hin_v, float* R_v, float* Hout_v) {
+                        const bf16* Wo, float* Hin_qk, float* R_qk, float* Hout_q, float* Hout_k, float* Hin_v, float* R_v, float* Hout_v,
+                        bf16* fp_cache) {
     const Dims D = dims_of(ctx, d);
     TB_TRY(check_bf16_dims(D));
     const int T = D.T, dm = D.dm, Hq = D.Hq, Hkv = D.Hkv, dh = D.dh, L = D.L, dq = D.dq, dkv = D.dkv, rep = D.rep;
@@ -432,6 +433,9 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         const long long t0 = (long long)s0 * L;
         const long long ldx = (long long)Gc * nsx * L + PADE, ky = (long long)rep * Gc * L, ldy = ky + PADE, ldp = (long long)nsg * L + PADE;
         TB_TRY(project_qk(D, X + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qh, Kh));
+        if (rv && fp_cache) {   // the caller keeps the full-precision projections of all tokens: written in place
+            Qhf = fp_cache + t0 * dq * 3; Khf = fp_cache + (long long)T * dq * 3 + t0 * dkv * 3;
+        }
         if (rv) TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
         for (int sl = 0; sl < Gc; ++sl) {   // XcT[:, sl, :, :] = X_s^T | (X_s - X~_s)^T | X~_s^T
             const bf16* xs = X + (t0 + (long long)sl * L) * dm;
@@ -487,7 +491,7 @@ int weight_operands(tboa_ctx* ctx, const float* W, int rows, int n, bf16* hi, bf
 
 int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, const bf16* X_fp, const float* Wq_deq,
                                 const float* Wk_deq, const float* Wv_deq, const bf16* Wq, const bf16* Wk, const bf16* Wv, float* Hin_o,
-                                float* R_o) {
+                                float* R_o, const bf16* fp_cache) {
     const Dims D = dims_of(ctx, d);
     TB_TRY(check_bf16_dims(D));
     const int T = D.T, dm = D.dm, Hq = D.Hq, dh = D.dh, L = D.L, dq = D.dq, dkv = D.dkv, rep = D.rep;
@@ -531,7 +535,9 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         TB_TRY(project_qk(D, Xc, Gc * L, Wqh, Wql_u, Wkh, Wkl_u, Qf, Kf, Qh, Kh, sq, sk));
         if (fp) {
             TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wv, dm, X_fp + t0 * dm, dm, VT32f, (long long)Gc * L, TBOA_F32, 0, 0)));
-            TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
+            if (fp_cache) {     // projections of X_fp by W_Q, W_K as tboa_build_hessians left them
+                Qhf = (bf16*)fp_cache + t0 * dq * 3; Khf = (bf16*)fp_cache + (long long)T * dq * 3 + t0 * dkv * 3;
+            } else TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
         }
         hipLaunchKernelGGL(vt_segments_kernel, dim3(g1((long long)dkv * Gc * L)), dim3(256), 0, st, VT32, sv, fp ? VT32f : nullptr, VTc, dkv, Gc, L,
                            nsg, ldv);
@@ -664,7 +670,7 @@ static int check_attn_desc(tboa_ctx* ctx, const tboa_attn_desc* d) {
 
 extern "C" int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, const void* X_fp, const void* Wq,
                                    const void* Wk, const void* Wv, const void* Wo, float* Hin_qk, float* R_qk, float* Hout_q,
-                                   float* Hout_k, float* Hin_v, float* R_v, float* Hout_v) {
+                                   float* Hout_k, float* Hin_v, float* R_v, float* Hout_v, void* fp_cache) {
     if (!ctx) return TBOA_EINVAL;
     TB_TRY(check_attn_desc(ctx, d));
     if (!X || !Wq || !Wk || !Wo) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: null input");
@@ -674,21 +680,30 @@ extern "C" int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* d, const
     if ((R_qk && !Hin_qk) || (R_v && !Hin_v)) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: R_qk needs Hin_qk, R_v needs Hin_v");
     if ((R_qk || R_v) && !X_fp) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: R_qk / R_v need X_fp");
     if (X_fp && Hin_qk && !R_qk) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: X_fp given without R_qk");
+    if (fp_cache && !R_v) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: fp_cache is filled while R_v is built: R_v missing");
+    if (fp_cache && ((uintptr_t)fp_cache & 15)) return tboa_fail(ctx, TBOA_EINVAL, "build_hessians: fp_cache must be 16-byte aligned");
     if (d->x_dtype == TBOA_F32) return build_hessians_f64(ctx, d, X, X_fp, Wq, Wk, Wv, Wo, Hin_qk, R_qk, Hout_q, Hout_k, Hin_v, R_v, Hout_v);
     return build_hessians_bf16(ctx, d, (const bf16*)X, (const bf16*)X_fp, (const bf16*)Wq, (const bf16*)Wk, (const bf16*)Wo, Hin_qk, R_qk,
-                               Hout_q, Hout_k, Hin_v, R_v, Hout_v);
+                               Hout_q, Hout_k, Hin_v, R_v, Hout_v, (bf16*)fp_cache);
 }
 
 extern "C" int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, const void* X_fp, const float* Wq_deq,
                                            const float* Wk_deq, const float* Wv_deq, const void* Wq, const void* Wk, const void* Wv,
-                                           float* Hin_o, float* R_o) {
+                                           float* Hin_o, float* R_o, const void* fp_cache) {
     if (!ctx) return TBOA_EINVAL;
     TB_TRY(check_attn_desc(ctx, d));
     if (!X || !Wq_deq || !Wk_deq || !Wv_deq || !Hin_o) return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_out_proj: null argument");
-    if (R_o && (!X_fp || !Wq || !Wk || !Wv)) return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_out_proj: R_o needs X_fp and the full-precision weights");
+    if (R_o && (!X_fp || !Wv || (!fp_cache && (!Wq || !Wk))))
+        return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_out_proj: R_o needs X_fp and the full-precision weights");
+    if (fp_cache && ((uintptr_t)fp_cache & 15)) return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_out_proj: fp_cache must be 16-byte aligned");
     if (d->x_dtype == TBOA_F32) return build_hessian_out_proj_f64(ctx, d, X, X_fp, Wq_deq, Wk_deq, Wv_deq, Wq, Wk, Wv, Hin_o, R_o);
     return build_hessian_out_proj_bf16(ctx, d, (const bf16*)X, (const bf16*)X_fp, Wq_deq, Wk_deq, Wv_deq, (const bf16*)Wq, (const bf16*)Wk,
-                                       (const bf16*)Wv, Hin_o, R_o);
+                                       (const bf16*)Wv, Hin_o, R_o, (const bf16*)fp_cache);
+}
+
+extern "C" size_t tboa_fp_cache_bytes(const tboa_attn_desc* d) {
+    if (!d || d->x_dtype != TBOA_BF16 || d->n_seqs <= 0 || d->seq_len <= 0 || d->head_dim <= 0) return 0;
+    return (size_t)d->n_seqs * d->seq_len * (size_t)(d->n_q_heads + d->n_kv_heads) * d->head_dim * 3 * sizeof(bf16);
 }
 
 extern "C" int tboa_act_fakequant(tboa_ctx* ctx, int64_t n_tokens, int d, int bits, int dtype, const void* X_in, void* X_out) {

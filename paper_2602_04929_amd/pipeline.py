@@ -56,7 +56,7 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
         X = stage("act_fakequant", lambda: ctx.act_fakequant(X_fp, cfg.act_bits))
     Xf = X_fp if use_R else None
     hargs = (X, Xf, blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], Hq, Hkv, dh)
-    hkw = dict(alpha=alpha, with_R_v=with_R_v, seq_chunk=seq_chunk)
+    hkw = dict(alpha=alpha, with_R_v=with_R_v, seq_chunk=seq_chunk, keep_fp_projections=True)
     kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp)
     out = {"X": X, "X_fp": X_fp}
     Hs = stage("build_hessians", lambda: ctx.build_hessians(*hargs, **hkw))
@@ -103,7 +103,7 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     out["hessians"] = Hs
     Ho = stage("build_hessian_out_proj", lambda: ctx.build_hessian_out_proj(
         X, Xf, out["q"]["W_deq"], out["k"]["W_deq"], out["v"]["W_deq"], blk["Wq"], blk["Wk"], blk["Wv"], Hq, Hkv, dh,
-        alpha=alpha, seq_chunk=seq_chunk))
+        alpha=alpha, seq_chunk=seq_chunk, fp_cache=Hs.get("fp_cache")))
     out["Hin_o"], out["R_o"] = Ho
     kwo = dict(kw, block=cfg.d_model)      # H_out = I: all rows form one step
     out["o"] = stage("quantize_o", lambda: ctx.quantize_layer(blk["Wo"], Ho[0], None, Ho[1], 1, **kwo))

@@ -119,6 +119,31 @@ def test_out_proj_bf16(ctx):
     assert R2 is None and rel_err(np64(H2), wH) <= 2e-3
 
 
+def test_out_proj_reuses_fp_projections(ctx, lib):
+    """The projections of X_fp by the full-precision W_Q, W_K kept by tboa_build_hessians (fp_cache) give the output-projection
+    Hessian the same bits as recomputing them; W_Q, W_K may then be omitted."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=264, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=5, seq_len=320, n_outlier=3)
+    b = synth.make_block(cfg, seed=8, device="cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    deq = [w.float() * (1 + 0.05 * torch.randn(w.shape, generator=g, device="cuda")) for w in (b["Wq"], b["Wk"], b["Wv"])]
+    Hs = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 4, 2, 32, alpha=0.25, seq_chunk=2, keep_fp_projections=True)
+    cache = Hs["fp_cache"]
+    assert cache is not None and cache.numel() == 5 * 320 * (4 + 2) * 32 * 3 * 2
+    plain = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 4, 2, 32, alpha=0.25, seq_chunk=2)
+    for k in ("Hin_qk", "R_qk", "Hin_v", "R_v", "Hout_q", "Hout_k", "Hout_v"):
+        assert torch.equal(Hs[k], plain[k]), k
+    H0, R0 = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, b["Wq"], b["Wk"], b["Wv"], 4, 2, 32, alpha=0.25, seq_chunk=3)
+    H1, R1 = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, None, None, b["Wv"], 4, 2, 32, alpha=0.25, seq_chunk=3, fp_cache=cache)
+    assert torch.equal(H0, H1) and torch.equal(R0, R1)
+    with pytest.raises(lib.TurboBoAError):       # neither the cache nor the weights to recompute it
+        ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, None, None, b["Wv"], 4, 2, 32, alpha=0.25)
+    # fp32 inputs: the library has no use for a cache
+    cfg32 = synth.scaled(synth.CONFIGS["tiny"], d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, n_seqs=2, seq_len=40, n_outlier=2)
+    b32 = synth.make_block(cfg32, seed=3, device="cuda")
+    assert ctx.build_hessians(b32["X"], b32["X_fp"], b32["Wq"], b32["Wk"], b32["Wv"], b32["Wo"], 4, 2, 16, alpha=0.25,
+                              keep_fp_projections=True)["fp_cache"] is None
+
+
 def uniform_grid_weights(w, bits, g):
     """Rows of s_r * (codes - z_r): what a per-row uniform quantizer leaves (input construction, not the method)."""
     lo, hi = w.min(dim=1, keepdim=True).values.clamp(max=0), w.max(dim=1, keepdim=True).values.clamp(min=0)

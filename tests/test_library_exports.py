@@ -25,7 +25,7 @@ def lib():
 
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
-    for must in ("tboa_create", "tboa_destroy", "tboa_last_error", "tboa_build_hessians", "tboa_build_hessian_out_proj",
+    for must in ("tboa_create", "tboa_destroy", "tboa_last_error", "tboa_build_hessians", "tboa_build_hessian_out_proj", "tboa_fp_cache_bytes",
                  "tboa_quantize_layer", "tboa_act_fakequant", "tboa_hadamard_rotate", "tboa_build_hessian_linear", "tboa_swiglu_forward", "tboa_pack_codes", "tboa_dequant_gemv", "tboa_packed_words_per_row", "tboa_chol_inv_upper", "tboa_gemm_f64", "tboa_gemm_bf16_nt"):
         assert must in names
 
