@@ -116,6 +116,7 @@ class Context:
         if getattr(self, "_h", None) and _lib is not None:
             _lib.tboa_destroy(self._h)
         self._h = None
+        self._fp_cache = None
 
     __del__ = close
 
@@ -186,7 +187,8 @@ class Context:
                        with_R_v=True, seq_chunk=0, parts="all", keep_fp_projections=False):
         """parts: "all", "qk" (H_in, R, H_out of W_Q and W_K, plus H_out of W_V) or "v" (H_in, R of W_V).
         keep_fp_projections: also returns "fp_cache", the buffer tboa_build_hessian_out_proj can reuse (None when the
-        library has no use for one: fp32 inputs, or no R_v)."""
+        library has no use for one: fp32 inputs, or no R_v).  The buffer belongs to this context and is overwritten by its
+        next call with keep_fp_projections."""
         S, L, d = X.shape
         dt = X.dtype
         for t in (X, Wq, Wk, Wv, Wo):
@@ -210,7 +212,11 @@ class Context:
         cache = None
         if keep_fp_projections and out["R_v"] is not None:
             nbytes = int(_lib.tboa_fp_cache_bytes(C.byref(desc)))
-            cache = torch.empty(nbytes, dtype=torch.uint8, device=X.device) if nbytes else None
+            cache = getattr(self, "_fp_cache", None)      # one buffer per context, reused from block to block
+            if nbytes == 0:
+                cache = None
+            elif cache is None or cache.numel() != nbytes or cache.device != X.device:
+                cache = self._fp_cache = torch.empty(nbytes, dtype=torch.uint8, device=X.device)
         self._check(_lib.tboa_build_hessians(self._h, C.byref(desc), _ptr(X), _ptr(X_fp if (qk or out["R_v"] is not None) else None),
                                              _ptr(Wq), _ptr(Wk), _ptr(Wv),
                                              _ptr(Wo), _ptr(out["Hin_qk"]), _ptr(out["R_qk"]), _ptr(out["Hout_q"]),
