@@ -23,7 +23,9 @@ __global__ __launch_bounds__(256) void diag_factor_kernel(double* __restrict__ H
         V[r][c] = (c >= r) ? Hb[(long long)(j0 + r) * n + j0 + c] : 0.0;
     }
     __syncthreads();
-    // H_jj = V V^T, V upper: columns from the last to the first
+    // H_jj = V V^T, V upper: columns from the last to the first.  Thread (tx, ty) = (t % 64, t / 64) owns column tx of the
+    // rows ty, ty + 4, ... in both phases.
+    const int tx = t & 63, ty = t >> 6;
     for (int c = bs - 1; c >= 0; --c) {
         const double piv = V[c][c];
         __syncthreads();
@@ -35,24 +37,25 @@ __global__ __launch_bounds__(256) void diag_factor_kernel(double* __restrict__ H
         if (t == c) V[c][c] = dv;
         __syncthreads();
         // trailing (upper part): V[r][r2] -= V[r][c] * V[r2][c] for r <= r2 < c
-        for (int i = t; i < c * c; i += 256) {
-            const int r = i / c, r2 = i % c;
-            if (r2 >= r) V[r][r2] -= V[r][c] * V[r2][c];
+        if (tx < c) {
+            const double vc = V[tx][c];
+            for (int r = ty; r <= tx; r += 4) V[r][tx] -= V[r][c] * vc;
         }
         __syncthreads();
     }
-    // W = V^-1 (upper): one column per thread, back substitution
-    if (t < bs) {
-        const int c = t;
-        for (int r = bs - 1; r > c; --r) W[r][c] = 0.0;
-        W[c][c] = 1.0 / V[c][c];
-        for (int r = c - 1; r >= 0; --r) {
-            double s = 0.0;
-            for (int k = r + 1; k <= c; ++k) s += V[r][k] * W[k][c];
-            W[r][c] = -s / V[r][r];
-        }
-    }
+    // W = V^-1 (upper), V W = I solved for all columns at once from the last row up: row r of W is final once the
+    // contributions of the rows below it have been taken from the right-hand side, and is then taken from the rows above
+    for (int r = ty; r < NB; r += 4) W[r][tx] = (r == tx && r < bs) ? 1.0 : 0.0;     // right-hand side, becomes W
     __syncthreads();
+    for (int r = bs - 1; r >= 0; --r) {
+        if (ty == 0 && tx >= r && tx < bs) W[r][tx] = W[r][tx] / V[r][r];
+        __syncthreads();
+        if (tx >= r && tx < bs) {
+            const double wr = W[r][tx];
+            for (int i = ty; i < r; i += 4) W[i][tx] -= V[i][r] * wr;
+        }
+        __syncthreads();
+    }
     double* D = dinv + ((long long)b * nblk + blk) * NB * NB;
     for (int i = t; i < NB * NB; i += 256) {
         const int r = i / NB, c = i % NB;
