@@ -230,8 +230,18 @@ int tboa_gemm_f64(tboa_ctx* ctx, int M, int N, int K, double alpha,
  *        TBOA_GEMM_PERSISTENT runs one resident workgroup per compute unit over a precomputed list of tiles instead of
  *        one dispatched workgroup per tile (same arithmetic, same result; taken when the contraction length, or kseg, is
  *        a multiple of 128, ignored otherwise).  Meant for launches that have the GPU to themselves: the lists are
- *        balanced for compute units that all start together. */
-enum { TBOA_GEMM_LOWER = 1, TBOA_GEMM_CAUSAL_K = 2, TBOA_GEMM_PERSISTENT = 4 };
+ *        balanced for compute units that all start together.
+ *        TBOA_GEMM_A_TILED / _B_TILED / _C_TILED: that matrix is not row-major but stored in blocks of 16 rows x 32 columns
+ *        (1 KB, the unit the kernel copies into LDS with one wavefront load): element (r, c) of a matrix with leading
+ *        dimension ld (a multiple of 32) sits at element offset
+ *            ((r / 16) * (ld / 32) + c / 32) * 512 + (r % 16) * 32 + (((c % 32) / 8) ^ (((r % 16) / 4) % 4)) * 8 + c % 8,
+ *        i.e. the blocks of a block row follow each other along the columns and the four 16-byte pieces of a row of a
+ *        block are XOR-permuted the way the kernel keeps them in LDS.  A column offset c0 (a multiple of 32) into such a
+ *        matrix is the pointer offset 16 * c0.  Operands: rows a multiple of 16, K a multiple of 32, batch strides
+ *        multiples of 512; C: bf16, no accumulation, M and N multiples of 256.  Meant for chains of products where one
+ *        product's bf16 result is the next one's operand (its loads are then whole contiguous blocks). */
+enum { TBOA_GEMM_LOWER = 1, TBOA_GEMM_CAUSAL_K = 2, TBOA_GEMM_PERSISTENT = 4, TBOA_GEMM_A_TILED = 8, TBOA_GEMM_B_TILED = 16,
+       TBOA_GEMM_C_TILED = 32 };
 int tboa_gemm_bf16_nt(tboa_ctx* ctx, int M, int N, int K, float alpha,
                       const void* A, int64_t lda, const void* B, int64_t ldb,
                       void* C, int64_t ldc, int c_dtype, int accumulate, int flags,

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libturboboa.so")
 
 F32, BF16, F64 = 0, 1, 2
-GEMM_LOWER, GEMM_CAUSAL_K, GEMM_PERSISTENT = 1, 2, 4
+GEMM_LOWER, GEMM_CAUSAL_K, GEMM_PERSISTENT, GEMM_A_TILED, GEMM_B_TILED, GEMM_C_TILED = 1, 2, 4, 8, 16, 32
 
 STATUS = {0: "OK", -1: "EINVAL", -2: "ENOTSPD", -3: "ENOMEM", -4: "EHIP", -5: "ENAN"}
 

@@ -123,8 +123,35 @@ __device__ __forceinline__ void store_acc_interior(const Args& g, const f32x16 (
             }
 }
 
+// C in 16 x 32 blocks (TBOA_GEMM_C_TILED; bf16, whole tiles): the 8 bytes of a lane go to row (8 b + 4 (l / 32) + l % 4) % 16
+// of block (row / 16, column / 32), piece ((l % 32) / 8) ^ ((row % 16) / 4) of that row, first or second half of the piece
+template <int TJ, bool SCALE>
+__device__ __forceinline__ void store_acc_tiled(const Args& g, const f32x16 (&acc)[4][TJ], int row0, int col0, long long coff) {
+    const int lane = threadIdx.x & 63, l32 = lane & 31, lh = lane >> 5, q = l32 & 3, c = l32 >> 2;
+    const long long kb = g.ldc >> 5;
+    __hip_bfloat16* base = (__hip_bfloat16*)g.C + coff + ((long long)(row0 >> 4) * kb + (col0 >> 5)) * 512;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int ri = 8 * (b & 1) + 4 * lh + q, cs = (c >> 1) ^ ((2 * (b & 1) + lh) & 3);
+            const unsigned off = (unsigned)(ri * 32 + cs * 8 + (c & 1) * 4);
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) {
+                f32x4 r = {acc[i][j][4 * b], acc[i][j][4 * b + 1], acc[i][j][4 * b + 2], acc[i][j][4 * b + 3]};
+                if (SCALE) r *= g.alpha;
+                *(bf16x4*)(base + ((long long)(2 * i + (b >> 1)) * kb + j) * 512 + off) = __builtin_convertvector(r, bf16x4);
+            }
+        }
+}
+
 template <int TJ>
 __device__ __forceinline__ void store_acc(const Args& g, const f32x16 (&acc)[4][TJ], int row0, int col0, long long coff) {
+    if (g.flags & TBOA_GEMM_C_TILED) {
+        if (g.alpha == 1.0f) store_acc_tiled<TJ, false>(g, acc, row0, col0, coff);
+        else store_acc_tiled<TJ, true>(g, acc, row0, col0, coff);
+        return;
+    }
     if (g.vec_c && row0 + 128 <= g.M && col0 + 32 * TJ <= g.N) {
         if (g.alpha == 1.0f) store_acc_interior<TJ, false>(g, acc, row0, col0, coff);
         else store_acc_interior<TJ, true>(g, acc, row0, col0, coff);
@@ -319,6 +346,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     // loop-invariant per-lane byte offsets of this wavefront's loads of a stage, relative to the tile's first row
+    const bool tiledA = g.flags & TBOA_GEMM_A_TILED, tiledB = g.flags & TBOA_GEMM_B_TILED;
+    const int shA = tiledA ? 4 : 0, shB = tiledB ? 4 : 0;
     unsigned offA[LPW], offB[LPW];
     {
         const int pr = lane >> 2, ph = lane & 3;
@@ -328,11 +357,16 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
             const int lc = ph ^ ((row >> 2) & 3);
             offA[i] = (unsigned)(((long long)min(row, g.M - 1 - m0) * g.lda + lc * 8) * 2);
             offB[i] = (unsigned)(((long long)min(row, g.N - 1 - n0) * g.ldb + lc * 8) * 2);
+            // an operand stored in 16 x 32 blocks: block row of the 1 KB block, the lane's 16 bytes inside it
+            if (tiledA) offA[i] = (unsigned)((long long)min(wave * LPW + i, (g.M - 1 - m0) >> 4) * (g.lda >> 5) * 1024 + lane * 16);
+            if (tiledB) offB[i] = (unsigned)((long long)min(wave * LPW + i, (g.N - 1 - n0) >> 4) * (g.ldb >> 5) * 1024 + lane * 16);
         }
     }
+    // (for a blocked operand m0 * lda is also the element offset of its block row m0 / 16)
     const char* Arow = (const char*)(A + (long long)m0 * g.lda);
     const char* Brow = (const char*)(B + (long long)n0 * g.ldb);
-    // byte offset along k of the next stage to be issued (stages are issued strictly in order), kept incrementally
+    // byte offset along k of the next stage to be issued (stages are issued strictly in order), kept incrementally;
+    // in a blocked operand 32 k are one block of 1 KB, not 64 bytes of a row
     long long koff_next = 0; int kin_next = 0;
     auto advance = [&]() { kin_next += FK; koff_next += 2 * FK; if (kin_next == kend) { kin_next = 0; koff_next += 2LL * (seg_len - kend); } };
     const unsigned ring_lds = (unsigned)(unsigned long long)((__attribute__((address_space(3))) void*)ring);
@@ -344,8 +378,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const unsigned blk = (unsigned)(wave_s * LPW + i) * 1024u;
-            lds_direct_16(offA[i], Arow + kb, st + blk);
-            lds_direct_16(offB[i], Brow + kb, st + (unsigned)(BM * FK * 2) + blk);
+            lds_direct_16(offA[i], Arow + (kb << shA), st + blk);
+            lds_direct_16(offB[i], Brow + (kb << shB), st + (unsigned)(BM * FK * 2) + blk);
         }
     };
     // Fragments are double-buffered in registers at k-step granularity: while the MFMAs of one k-step run, the
@@ -372,7 +406,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
 #define TB_STAGE_STEADY(KT, SLOT, NEXTSLOT)                                                                 \
     {                                                                                                       \
         __builtin_amdgcn_sched_barrier(0);                                                                  \
-        const char* pa_ = Arow + koff_next; const char* pb_ = Brow + koff_next;                             \
+        const char* pa_ = Arow + (koff_next << shA); const char* pb_ = Brow + (koff_next << shB);           \
         const unsigned st_ = ring_lds + (unsigned)((SLOT) * STAGE_ELEMS * 2);                               \
         advance();                                                                                          \
         TB_LOAD_FRAGS(1, SLOT, 1)                                                                           \
@@ -701,6 +735,16 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     if (q.c_dtype == TBOA_BF16 && q.accumulate) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: accumulate needs an fp32 C");
     if (q.c_dtype != TBOA_BF16 && q.c_dtype != TBOA_F32) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: C must be fp32 or bf16");
     if ((q.flags & TBOA_GEMM_LOWER) && q.M != q.N) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: LOWER needs M == N");
+    if (q.flags & (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED)) {
+        const bool ta = q.flags & TBOA_GEMM_A_TILED, tb = q.flags & TBOA_GEMM_B_TILED;
+        if ((q.kseg > 0 ? q.kseg : q.K) % 32 || q.K <= 0) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: blocked operands need K (and kseg) to be multiples of 32");
+        if ((ta && (q.lda % 32 || q.M % 16 || q.strideA % 512 || q.strideA2 % 512)) || (tb && (q.ldb % 32 || q.N % 16 || q.strideB % 512 || q.strideB2 % 512)))
+            return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: a blocked operand needs rows % 16 == 0, ld % 32 == 0 and batch strides % 512 == 0");
+    }
+    if (q.flags & TBOA_GEMM_C_TILED) {
+        if (q.c_dtype != TBOA_BF16 || q.accumulate || q.M % 256 || q.N % 256 || q.ldc % 32 || q.strideC % 4 || q.strideC2 % 4 || ((uintptr_t)q.C & 7))
+            return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: a blocked C must be bf16 without accumulation, M and N multiples of 256, ldc a multiple of 32");
+    }
     static bool attr_set = false;
     const int smem = 2 * (BM + BN) * BK * (int)sizeof(__hip_bfloat16);
     const int smem_fast = 4 * STAGE_ELEMS * (int)sizeof(__hip_bfloat16), smem_fast5 = 5 * STAGE_ELEMS * (int)sizeof(__hip_bfloat16);
@@ -713,6 +757,7 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
         attr_set = true;
     }
     const bool fast = (q.kseg > 0 ? q.kseg : q.K) % FK == 0 && q.K > 0 && !getenv("TBOA_GEMM_GENERIC");
+    if ((q.flags & (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED)) && !fast) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: blocked operands are read by the LDS-direct kernel only");
     Args a;
     a.sched = nullptr; a.rounds = 0;
     a.M = q.M; a.N = q.N; a.K = q.K; a.alpha = q.alpha;
@@ -746,7 +791,7 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     static const int waves = getenv("TBOA_GEMM_WAVES") ? atoi(getenv("TBOA_GEMM_WAVES")) : 8;
     static const int ring = getenv("TBOA_GEMM_RING") ? atoi(getenv("TBOA_GEMM_RING")) : 4;
     static const int stream_mode = getenv("TBOA_GEMM_PERSISTENT") ? atoi(getenv("TBOA_GEMM_PERSISTENT")) : -1;   // -1: as the caller asks
-    const bool persistent = fast && (q.kseg > 0 ? q.kseg : q.K) % (FK * 4) == 0 && (stream_mode < 0 ? (q.flags & TBOA_GEMM_PERSISTENT) != 0 : stream_mode != 0);
+    const bool persistent = fast && !(q.flags & (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED)) && (q.kseg > 0 ? q.kseg : q.K) % (FK * 4) == 0 && (stream_mode < 0 ? (q.flags & TBOA_GEMM_PERSISTENT) != 0 : stream_mode != 0);
     if (persistent) {
         int wgs = 0;
         TB_TRY(tile_schedule(ctx, q, tiles_m, tiles_n, &a.sched, &a.rounds, &wgs));

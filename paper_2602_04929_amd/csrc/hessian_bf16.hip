@@ -428,6 +428,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     TB_TRY(launch_fill_f32(ctx, Hin_v, (int64_t)Hkv * dd, 0.f));
     if (rv) TB_TRY(launch_fill_f32(ctx, R_v, (int64_t)Hkv * dd, 0.f));
     const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
+    const bool blocked = dm % 256 == 0 && L % 256 == 0 && !getenv("TBOA_NO_BLOCKED_Y");
     for (int s0 = 0; s0 < D.S; s0 += G) {
         const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
         const long long t0 = (long long)s0 * L;
@@ -452,18 +453,23 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
             TB_TRY(scores(D, Qh, Kh, sl, Sc));
             if (rv) TB_TRY(scores(D, Qhf, Khf, sl, Scf));
             TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, ldp, 1, L));
-            GemmBf16 y = nt(dm, L, L, 1.f, XcT + (long long)sl * nsx * L, ldx, P, ldp, YT + (long long)sl * L, ldy, TBOA_BF16, 0, cflag);
+            // Y^T and (Y - Y~)^T are read only by the two products below: with whole 256 x 256 tiles they are written in the
+            // blocked layout of the GEMM (column offset c -> pointer offset 16 c), whose blocks those products load whole
+            const long long cs = blocked ? 16 : 1;
+            GemmBf16 y = nt(dm, L, L, 1.f, XcT + (long long)sl * nsx * L, ldx, P, ldp, YT + cs * sl * L, ldy, TBOA_BF16, 0,
+                            cflag | (blocked ? TBOA_GEMM_C_TILED : 0));
             y.batch = Hq; y.batch_inner = rep; y.tag = TBOA_PROF_AX;
             y.strideB = (long long)rep * L * ldp; y.strideB2 = (long long)L * ldp;
-            y.strideC = (long long)dm * ldy; y.strideC2 = (long long)Gc * L;
+            y.strideC = (long long)dm * ldy; y.strideC2 = cs * Gc * L;
             TB_TRY(gemm_bf16_nt(ctx, y));
-            if (rv) { y.A = XcT + ((long long)sl * nsx + 1) * L; y.K = 2 * L; y.kseg = L; y.C = dYT + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, y)); }
+            if (rv) { y.A = XcT + ((long long)sl * nsx + 1) * L; y.K = 2 * L; y.kseg = L; y.C = dYT + cs * sl * L; TB_TRY(gemm_bf16_nt(ctx, y)); }
         }
-        GemmBf16 h = nt(dm, dm, (int)ky, 1.f, YT, ldy, YT, ldy, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER);
+        const int oflag = blocked ? (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED) : 0;
+        GemmBf16 h = nt(dm, dm, (int)ky, 1.f, YT, ldy, YT, ldy, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER | oflag);
         h.batch = Hkv; h.strideA = (long long)dm * ldy; h.strideB = h.strideA; h.strideC = dd; h.tag = TBOA_PROF_HV_SYRK;
         h.flags &= ~TBOA_GEMM_PERSISTENT;
         TB_TRY(gemm_bf16_nt(ctx, h));
-        if (rv) { h.tag = TBOA_PROF_RV; h.A = dYT; h.C = R_v; h.flags = 0; h.alpha = (float)d->alpha; TB_TRY(gemm_bf16_nt(ctx, h)); }
+        if (rv) { h.tag = TBOA_PROF_RV; h.A = dYT; h.C = R_v; h.flags = oflag; h.alpha = (float)d->alpha; TB_TRY(gemm_bf16_nt(ctx, h)); }
     }
     TB_TRY(launch_mirror_lower_f32(ctx, Hin_v, dm, Hkv));
     return 0;

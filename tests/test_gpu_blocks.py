@@ -125,3 +125,49 @@ def test_gemm_bf16_persistent_matches_dispatched(ctx, lib, M, N, K, batch, flags
             continue
         ref = float(A[b, i].double() @ B[b, j].double())
         assert abs(float(got[b, i, j]) - 0.25 - ref) <= 1e-5 * np.sqrt(K) * 4 + 1e-6 * abs(ref)
+
+
+def to_blocks(M):
+    """Row-major [R, K] -> the 16 x 32 block layout of TBOA_GEMM_*_TILED (an index permutation, written from the header)."""
+    R, K = M.shape
+    r = torch.arange(R, device=M.device)[:, None]; c = torch.arange(K, device=M.device)[None, :]
+    off = ((r // 16) * (K // 32) + c // 32) * 512 + (r % 16) * 32 + (((c % 32) // 8) ^ (((r % 16) // 4) % 4)) * 8 + c % 8
+    out = torch.empty(R * K, dtype=M.dtype, device=M.device)
+    out[off.reshape(-1)] = M.reshape(-1)
+    return out.reshape(R, K)
+
+
+def from_blocks(T):
+    R, K = T.shape
+    r = torch.arange(R, device=T.device)[:, None]; c = torch.arange(K, device=T.device)[None, :]
+    off = ((r // 16) * (K // 32) + c // 32) * 512 + (r % 16) * 32 + (((c % 32) // 8) ^ (((r % 16) // 4) % 4)) * 8 + c % 8
+    return T.reshape(-1)[off.reshape(-1)].reshape(R, K)
+
+
+@pytest.mark.parametrize("persistent", [False, True])
+def test_gemm_bf16_blocked_layouts(ctx, lib, persistent):
+    """Operands and result in 16 x 32 blocks: same bits as the row-major call, for ragged operand tiles, a batch, a
+    symmetric product and a chain (the blocked bf16 result of one product read as the operand of the next)."""
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    pf = lib.GEMM_PERSISTENT if persistent else 0
+    M, N, K = 528, 784, 448          # 16 | M, N; 32 | K; neither a multiple of 256
+    A = torch.randn(2, M, K, generator=g, device="cuda").to(torch.bfloat16)
+    B = torch.randn(2, N, K, generator=g, device="cuda").to(torch.bfloat16)
+    At = torch.stack([to_blocks(a) for a in A]); Bt = torch.stack([to_blocks(b) for b in B])
+    want = ctx.gemm_bf16_nt(A, B)
+    assert torch.equal(ctx.gemm_bf16_nt(At, B, flags=lib.GEMM_A_TILED | pf), want)
+    assert torch.equal(ctx.gemm_bf16_nt(A, Bt, flags=lib.GEMM_B_TILED | pf), want)
+    assert torch.equal(ctx.gemm_bf16_nt(At, Bt, flags=lib.GEMM_A_TILED | lib.GEMM_B_TILED | pf), want)
+    low = ctx.gemm_bf16_nt(A[:, :512], A[:, :512], flags=lib.GEMM_LOWER)
+    assert torch.equal(ctx.gemm_bf16_nt(At[:, :512], At[:, :512], flags=lib.GEMM_LOWER | lib.GEMM_A_TILED | lib.GEMM_B_TILED), low)
+    # blocked result: M, N multiples of 256
+    X = torch.randn(512, 320, generator=g, device="cuda").to(torch.bfloat16)
+    Y = torch.randn(768, 320, generator=g, device="cuda").to(torch.bfloat16)
+    C = ctx.gemm_bf16_nt(X, Y, out_dtype=torch.bfloat16, alpha=0.5, flags=pf)
+    Ct = ctx.gemm_bf16_nt(X, Y, out_dtype=torch.bfloat16, alpha=0.5, flags=lib.GEMM_C_TILED | pf)
+    assert torch.equal(from_blocks(Ct), C)
+    # chain: (X Y^T) as the blocked left operand of the next product, K = 768
+    Z = torch.randn(256, 768, generator=g, device="cuda").to(torch.bfloat16)
+    assert torch.equal(ctx.gemm_bf16_nt(Ct, Z, flags=lib.GEMM_A_TILED), ctx.gemm_bf16_nt(C, Z))
+    with pytest.raises(lib.TurboBoAError):
+        ctx.gemm_bf16_nt(X[:500], Y, out_dtype=torch.bfloat16, flags=lib.GEMM_C_TILED)      # M not a multiple of 256
