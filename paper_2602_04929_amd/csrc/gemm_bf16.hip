@@ -520,6 +520,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
     int t_idx = 0;
 
     // the stream of stages being fetched: position inside the tile it is in
+    const bool tiledA = g.flags & TBOA_GEMM_A_TILED, tiledB = g.flags & TBOA_GEMM_B_TILED;     // operands in 16 x 32 blocks
+    const int shA = tiledA ? 4 : 0, shB = tiledB ? 4 : 0;
     unsigned offA[LPW], offB[LPW];
     auto set_offsets = [&](int m0, int n0) {
         const int pr = lane >> 2, ph = lane & 3;
@@ -529,6 +531,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
             const int lc = ph ^ ((row >> 2) & 3);
             offA[i] = (unsigned)(((long long)min(row, g.M - 1 - m0) * g.lda + lc * 8) * 2);
             offB[i] = (unsigned)(((long long)min(row, g.N - 1 - n0) * g.ldb + lc * 8) * 2);
+            if (tiledA) offA[i] = (unsigned)((long long)min(wave * LPW + i, (g.M - 1 - m0) >> 4) * (g.lda >> 5) * 1024 + lane * 16);
+            if (tiledB) offB[i] = (unsigned)((long long)min(wave * LPW + i, (g.N - 1 - n0) >> 4) * (g.ldb >> 5) * 1024 + lane * 16);
         }
     };
     const char* sA = cur.A; const char* sB = cur.B;
@@ -564,7 +568,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
 #define TB_STAGE(SLOT, NEXTSLOT, WAIT, FIRST)                                                               \
     {                                                                                                       \
         __builtin_amdgcn_sched_barrier(0);                                                                  \
-        const char* pa_ = sA + koff; const char* pb_ = sB + koff;                                           \
+        const char* pa_ = sA + (koff << shA); const char* pb_ = sB + (koff << shB);                         \
         const unsigned st_ = ring_lds + (unsigned)((SLOT) * STAGE_ELEMS * 2);                               \
         TB_LOAD_FRAGS(1, SLOT, 1)                                                                           \
         _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                       \
@@ -600,8 +604,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const unsigned blk = (unsigned)(wave_s * LPW + i) * 1024u;
-            lds_direct_16(offA[i], sA + koff, st + blk);
-            lds_direct_16(offB[i], sB + koff, st + (unsigned)(BM * FK * 2) + blk);
+            lds_direct_16(offA[i], sA + (koff << shA), st + blk);
+            lds_direct_16(offB[i], sB + (koff << shB), st + (unsigned)(BM * FK * 2) + blk);
         }
         advance();
     }
@@ -791,7 +795,7 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     static const int waves = getenv("TBOA_GEMM_WAVES") ? atoi(getenv("TBOA_GEMM_WAVES")) : 8;
     static const int ring = getenv("TBOA_GEMM_RING") ? atoi(getenv("TBOA_GEMM_RING")) : 4;
     static const int stream_mode = getenv("TBOA_GEMM_PERSISTENT") ? atoi(getenv("TBOA_GEMM_PERSISTENT")) : -1;   // -1: as the caller asks
-    const bool persistent = fast && !(q.flags & (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED)) && (q.kseg > 0 ? q.kseg : q.K) % (FK * 4) == 0 && (stream_mode < 0 ? (q.flags & TBOA_GEMM_PERSISTENT) != 0 : stream_mode != 0);
+    const bool persistent = fast && (q.kseg > 0 ? q.kseg : q.K) % (FK * 4) == 0 && (stream_mode < 0 ? (q.flags & TBOA_GEMM_PERSISTENT) != 0 : stream_mode != 0);
     if (persistent) {
         int wgs = 0;
         TB_TRY(tile_schedule(ctx, q, tiles_m, tiles_n, &a.sched, &a.rounds, &wgs));

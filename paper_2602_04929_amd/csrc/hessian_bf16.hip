@@ -23,10 +23,18 @@ namespace {
 
 typedef __hip_bfloat16 bf16;
 
-// out[c, r] = in[r, c] (optionally also the exact hi/lo split of in - in2), 64 x 64 tiles through LDS
+// element offset of (r, c) in a matrix kept in the 16 x 32 blocks the bf16 GEMM can read and write (TBOA_GEMM_*_TILED);
+// kb = leading dimension / 32
+__device__ __forceinline__ long long blocked_offset(long long r, long long c, long long kb) {
+    const int ri = (int)(r & 15), ci = (int)(c & 31);
+    return ((r >> 4) * kb + (c >> 5)) * 512 + ri * 32 + (((ci >> 3) ^ (ri >> 2)) << 3) + (ci & 7);
+}
+
+// out[c, r] = in[r, c] (optionally also the exact hi/lo split of in - in2), 64 x 64 tiles through LDS; blocked: the
+// outputs are kept in 16 x 32 blocks
 __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__ in, const bf16* __restrict__ in2, long long ld_in,
                                                         int rows, int cols, bf16* __restrict__ out, bf16* __restrict__ out_hi,
-                                                        bf16* __restrict__ out_lo, long long ld_out) {
+                                                        bf16* __restrict__ out_lo, long long ld_out, int blocked) {
     __shared__ float t0[64][65];
     __shared__ float t1[64][65];
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
@@ -43,7 +51,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__
     for (int i = threadIdx.x; i < 64 * 64; i += 256) {
         const int c = i >> 6, r = i & 63;
         if (r0 + r < rows && c0 + c < cols) {
-            const long long o = (long long)(c0 + c) * ld_out + r0 + r;
+            const long long o = blocked ? blocked_offset(c0 + c, r0 + r, ld_out >> 5) : (long long)(c0 + c) * ld_out + r0 + r;
             if (out) out[o] = __float2bfloat16(t0[r][c]);
             if (out_hi) {
                 const float dlt = t1[r][c];
@@ -184,12 +192,13 @@ __global__ __launch_bounds__(256) void softmax_bf16_kernel(const float* __restri
 // is taken once, and the probabilities leave as 8-byte stores.
 template <int NCH>
 __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __restrict__ S, const float* __restrict__ S2, int L, int causal,
-                                                                bf16* __restrict__ P, long long ldp, long long head_stride, int copies, int dcol) {
+                                                                bf16* __restrict__ P, long long ldp, long long head_stride, int copies, int dcol,
+                                                                int blocked) {
     const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= L) return;
     const long long so = ((long long)blockIdx.y * L + t) * L;
     const float* s = S + so; const float* s2 = S2 ? S2 + so : nullptr;
-    bf16* p = P + blockIdx.y * head_stride + (long long)t * ldp;
+    bf16* p = P + blockIdx.y * head_stride + (blocked ? 0 : (long long)t * ldp);
     const int kend = causal ? t + 1 : L;
     int kz = ((kend + 255) / 256) * 256; if (kz > L) kz = L;
     float v[NCH][4], w[NCH][4];
@@ -231,8 +240,13 @@ __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __r
             pa.h[i] = __float2bfloat16(a);
             pd.h[i] = __float2bfloat16(s2 ? a - w[c][i] * inv2 : 0.f);
         }
-        for (int cp = 0; cp < copies; ++cp) *(uint2*)(p + (long long)cp * L + k) = pa.u;
-        if (s2) *(uint2*)(p + dcol + k) = pd.u;
+        if (blocked) {     // the head's [L, ldp] matrix in 16 x 32 blocks: 4 consecutive columns stay together
+            for (int cp = 0; cp < copies; ++cp) *(uint2*)(p + blocked_offset(t, (long long)cp * L + k, ldp >> 5)) = pa.u;
+            if (s2) *(uint2*)(p + blocked_offset(t, dcol + k, ldp >> 5)) = pd.u;
+        } else {
+            for (int cp = 0; cp < copies; ++cp) *(uint2*)(p + (long long)cp * L + k) = pa.u;
+            if (s2) *(uint2*)(p + dcol + k) = pd.u;
+        }
     }
 }
 
@@ -276,9 +290,10 @@ int pick_splits(int n_seqs) {
     return 1;
 }
 
-int transpose(const Dims& D, const bf16* in, const bf16* in2, long long ld_in, int rows, int cols, bf16* out, bf16* hi, bf16* lo, long long ld_out) {
+int transpose(const Dims& D, const bf16* in, const bf16* in2, long long ld_in, int rows, int cols, bf16* out, bf16* hi, bf16* lo, long long ld_out,
+              int blocked = 0) {
     hipLaunchKernelGGL(transpose_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, D.ctx->stream, in, in2, ld_in, rows, cols,
-                       out, hi, lo, ld_out);
+                       out, hi, lo, ld_out, blocked);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
 }
@@ -333,15 +348,23 @@ int scores(const Dims& D, const bf16* Qh, const bf16* Kh, int sl, float* Sc) {
     return gemm_bf16_nt(D.ctx, g);
 }
 
-int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long ldp, int copies, int dcol) {
+// probabilities in 16 x 32 blocks (per head) when `blocked`: see blocked_inputs
+int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long ldp, int copies, int dcol, int blocked = 0) {
     if (D.L % 4 == 0 && D.L <= 2048 && ldp % 4 == 0 && dcol % 4 == 0)
         hipLaunchKernelGGL(softmax_bf16_regs_kernel<8>, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P,
-                           ldp, (long long)D.L * ldp, copies, dcol);
+                           ldp, (long long)D.L * ldp, copies, dcol, blocked);
+    else if (blocked) return tboa_fail(D.ctx, TBOA_EINVAL, "softmax: blocked probabilities need the in-register kernel");
     else
         hipLaunchKernelGGL(softmax_bf16_kernel, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P, ldp,
                            (long long)D.L * ldp, copies, dcol);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
+}
+
+// The transposed activations and the probabilities are operands of the A X products only: they are kept in the GEMM's
+// 16 x 32 blocks when the shapes allow (whole blocks, the in-register softmax)
+bool blocked_inputs(const Dims& D) {
+    return D.L % 32 == 0 && D.L <= 2048 && D.dm % 16 == 0 && !getenv("TBOA_NO_BLOCKED_AX");
 }
 
 int check_bf16_dims(const Dims& D) {
@@ -429,6 +452,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     if (rv) TB_TRY(launch_fill_f32(ctx, R_v, (int64_t)Hkv * dd, 0.f));
     const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
     const bool blocked = dm % 256 == 0 && L % 256 == 0 && !getenv("TBOA_NO_BLOCKED_Y");
+    const int bin = blocked_inputs(D);
     for (int s0 = 0; s0 < D.S; s0 += G) {
         const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
         const long long t0 = (long long)s0 * L;
@@ -438,31 +462,32 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
             Qhf = fp_cache + t0 * dq * 3; Khf = fp_cache + (long long)T * dq * 3 + t0 * dkv * 3;
         }
         if (rv) TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
+        const long long is = bin ? 16 : 1;      // a column offset c into a blocked matrix is the pointer offset 16 c
         for (int sl = 0; sl < Gc; ++sl) {   // XcT[:, sl, :, :] = X_s^T | (X_s - X~_s)^T | X~_s^T
             const bf16* xs = X + (t0 + (long long)sl * L) * dm;
-            bf16* o = XcT + (long long)sl * nsx * L;
-            if (!rv) TB_TRY(transpose(D, xs, nullptr, dm, L, dm, o, nullptr, nullptr, ldx));
+            bf16* o = XcT + is * sl * nsx * L;
+            if (!rv) TB_TRY(transpose(D, xs, nullptr, dm, L, dm, o, nullptr, nullptr, ldx, bin));
             else {
                 const bf16* xf = X_fp + (t0 + (long long)sl * L) * dm;
-                TB_TRY(transpose(D, xs, xf, dm, L, dm, o, o + L, nullptr, ldx));
-                TB_TRY(transpose(D, xf, nullptr, dm, L, dm, o + 2 * L, nullptr, nullptr, ldx));
+                TB_TRY(transpose(D, xs, xf, dm, L, dm, o, o + is * L, nullptr, ldx, bin));
+                TB_TRY(transpose(D, xf, nullptr, dm, L, dm, o + is * 2 * L, nullptr, nullptr, ldx, bin));
             }
         }
         for (int sl = 0; sl < Gc; ++sl) {
             // P = [A | A - A~];  Y^T = X_s^T A^T;  (Y - Y~)^T = [dX_s^T | X~_s^T] [A | A - A~]^T  since  A X - A~ X~ = A dX + (A - A~) X~
             TB_TRY(scores(D, Qh, Kh, sl, Sc));
             if (rv) TB_TRY(scores(D, Qhf, Khf, sl, Scf));
-            TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, ldp, 1, L));
+            TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, ldp, 1, L, bin));
             // Y^T and (Y - Y~)^T are read only by the two products below: with whole 256 x 256 tiles they are written in the
             // blocked layout of the GEMM (column offset c -> pointer offset 16 c), whose blocks those products load whole
             const long long cs = blocked ? 16 : 1;
-            GemmBf16 y = nt(dm, L, L, 1.f, XcT + (long long)sl * nsx * L, ldx, P, ldp, YT + cs * sl * L, ldy, TBOA_BF16, 0,
-                            cflag | (blocked ? TBOA_GEMM_C_TILED : 0));
+            GemmBf16 y = nt(dm, L, L, 1.f, XcT + is * sl * nsx * L, ldx, P, ldp, YT + cs * sl * L, ldy, TBOA_BF16, 0,
+                            cflag | (blocked ? TBOA_GEMM_C_TILED : 0) | (bin ? TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED : 0));
             y.batch = Hq; y.batch_inner = rep; y.tag = TBOA_PROF_AX;
             y.strideB = (long long)rep * L * ldp; y.strideB2 = (long long)L * ldp;
             y.strideC = (long long)dm * ldy; y.strideC2 = cs * Gc * L;
             TB_TRY(gemm_bf16_nt(ctx, y));
-            if (rv) { y.A = XcT + ((long long)sl * nsx + 1) * L; y.K = 2 * L; y.kseg = L; y.C = dYT + cs * sl * L; TB_TRY(gemm_bf16_nt(ctx, y)); }
+            if (rv) { y.A = XcT + is * ((long long)sl * nsx + 1) * L; y.K = 2 * L; y.kseg = L; y.C = dYT + cs * sl * L; TB_TRY(gemm_bf16_nt(ctx, y)); }
         }
         const int oflag = blocked ? (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED) : 0;
         GemmBf16 h = nt(dm, dm, (int)ky, 1.f, YT, ldy, YT, ldy, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER | oflag);
