@@ -23,13 +23,6 @@ namespace {
 
 typedef __hip_bfloat16 bf16;
 
-// element offset of (r, c) in a matrix kept in the 16 x 32 blocks the bf16 GEMM can read and write (TBOA_GEMM_*_TILED);
-// kb = leading dimension / 32
-__device__ __forceinline__ long long blocked_offset(long long r, long long c, long long kb) {
-    const int ri = (int)(r & 15), ci = (int)(c & 31);
-    return ((r >> 4) * kb + (c >> 5)) * 512 + ri * 32 + (((ci >> 3) ^ (ri >> 2)) << 3) + (ci & 7);
-}
-
 // out[c, r] = in[r, c] (optionally also the exact hi/lo split of in - in2), 64 x 64 tiles through LDS; blocked: the
 // outputs are kept in 16 x 32 blocks
 __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__ in, const bf16* __restrict__ in2, long long ld_in,
@@ -51,7 +44,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__
     for (int i = threadIdx.x; i < 64 * 64; i += 256) {
         const int c = i >> 6, r = i & 63;
         if (r0 + r < rows && c0 + c < cols) {
-            const long long o = blocked ? blocked_offset(c0 + c, r0 + r, ld_out >> 5) : (long long)(c0 + c) * ld_out + r0 + r;
+            const long long o = blocked ? tboa_blocked_offset(c0 + c, r0 + r, ld_out >> 5) : (long long)(c0 + c) * ld_out + r0 + r;
             if (out) out[o] = __float2bfloat16(t0[r][c]);
             if (out_hi) {
                 const float dlt = t1[r][c];
@@ -241,8 +234,8 @@ __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __r
             pd.h[i] = __float2bfloat16(s2 ? a - w[c][i] * inv2 : 0.f);
         }
         if (blocked) {     // the head's [L, ldp] matrix in 16 x 32 blocks: 4 consecutive columns stay together
-            for (int cp = 0; cp < copies; ++cp) *(uint2*)(p + blocked_offset(t, (long long)cp * L + k, ldp >> 5)) = pa.u;
-            if (s2) *(uint2*)(p + blocked_offset(t, dcol + k, ldp >> 5)) = pd.u;
+            for (int cp = 0; cp < copies; ++cp) *(uint2*)(p + tboa_blocked_offset(t, (long long)cp * L + k, ldp >> 5)) = pa.u;
+            if (s2) *(uint2*)(p + tboa_blocked_offset(t, dcol + k, ldp >> 5)) = pd.u;
         } else {
             for (int cp = 0; cp < copies; ++cp) *(uint2*)(p + (long long)cp * L + k) = pa.u;
             if (s2) *(uint2*)(p + dcol + k) = pd.u;

@@ -103,6 +103,13 @@ struct GemmBf16 {
 };
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
 
+// element offset of (r, c) in a matrix kept in the 16 x 32 blocks the bf16 GEMM can read and write (TBOA_GEMM_*_TILED);
+// kb = leading dimension / 32
+__device__ __forceinline__ long long tboa_blocked_offset(long long r, long long c, long long kb) {
+    const int ri = (int)(r & 15), ci = (int)(c & 31);
+    return ((r >> 4) * kb + (c >> 5)) * 512 + ri * 32 + (((ci >> 3) ^ (ri >> 2)) << 3) + (ci & 7);
+}
+
 // ---------------------------------------------------------------- factor.hip
 // H64 [batch, n, n] fp64, overwritten; U [batch, n, n] fp64 out.  Checks the device status and
 // returns TBOA_ENOTSPD on breakdown (synchronises).  tmp: workspace of batch*n*TB_FACT_OB doubles,

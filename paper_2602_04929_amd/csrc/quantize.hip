@@ -13,6 +13,7 @@
 // and after the last step the coordinate descent of Algorithm 2 on precomputed Gram matrices (d_h x d_h per head; per
 // pair of groups when the grids are group-wise), then the outputs and the loss.
 #include "internal.h"
+#include <stdlib.h>
 #include <math.h>
 
 namespace {
@@ -128,21 +129,28 @@ typedef __hip_bfloat16 bf16;
 
 constexpr int GRID_TERMS = 2;        // segments of the concatenated contraction axis
 
-// Hcat[b, r, :] = [hi(H[r,:]) | hi(H[r,:])]
-__global__ void hcat_kernel(const double* __restrict__ H, bf16* __restrict__ out, int n, long long total) {
+// Hcat[b, r, :] = [hi(H[r,:]) | hi(H[r,:])]; blocked: every [n, 2n + pad] matrix in the 16 x 32 blocks of the bf16 GEMM
+__global__ void hcat_kernel(const double* __restrict__ H, bf16* __restrict__ out, int n, long long total, int blocked) {
+    const long long pitch = GRID_TERMS * n + GRID_PAD;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
         const long long row = i / n; const int c = (int)(i % n);
         const float v = (float)H[i];
         const bf16 hi = __float2bfloat16(v);
-        bf16* o = out + row * (GRID_TERMS * n + GRID_PAD) + c;
-        o[0] = hi; o[n] = hi;
+        if (blocked) {
+            bf16* o = out + (row / n) * n * pitch; const long long r = row % n;
+            o[tboa_blocked_offset(r, c, pitch >> 5)] = hi; o[tboa_blocked_offset(r, n + c, pitch >> 5)] = hi;
+        } else {
+            bf16* o = out + row * pitch + c;
+            o[0] = hi; o[n] = hi;
+        }
     }
 }
 
-// Acat[(row, k), :] = [hi(delta) | lo(delta)], delta as in grid_delta_kernel
+// Acat[(row, k), :] = [hi(delta) | lo(delta)], delta as in grid_delta_kernel; mat_rows > 0: Acat is a sequence of matrices
+// of mat_rows rows each (the rows that share one H_in), every one kept in the 16 x 32 blocks of the bf16 GEMM
 __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
                                                                const double* __restrict__ cand_s, const double* __restrict__ cand_z,
-                                                               bf16* __restrict__ Acat) {
+                                                               bf16* __restrict__ Acat, long long mat_rows) {
     const int row = blockIdx.y;
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= n) return;
@@ -154,20 +162,33 @@ __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __r
     for (int k = 0; k < ncand; ++k) {
         const double s = cs[k], z = cz[k];
         const float dl = (float)(s * (quant_code(w, s, z, maxq) - z) - w);
-        const bf16 hi = __float2bfloat16(dl);
-        bf16* o = out + (long long)k * pitch;
-        o[0] = hi; o[n] = __float2bfloat16(dl - __bfloat162float(hi));
+        const bf16 hi = __float2bfloat16(dl), lo = __float2bfloat16(dl - __bfloat162float(hi));
+        if (mat_rows > 0) {
+            const long long R = (long long)row * ncand + k;
+            bf16* o = Acat + (R / mat_rows) * mat_rows * pitch; const long long r = R % mat_rows;
+            o[tboa_blocked_offset(r, c, pitch >> 5)] = hi; o[tboa_blocked_offset(r, n + c, pitch >> 5)] = lo;
+        } else {
+            bf16* o = out + (long long)k * pitch;
+            o[0] = hi; o[n] = lo;
+        }
     }
 }
 
 // cost[i] = sum_c G[i, c] (hi + lo)[i, c], one wavefront per row
 __global__ __launch_bounds__(256) void rowdot_split_kernel(const float* __restrict__ G, const bf16* __restrict__ Acat, long long rows, int n,
-                                                           double* __restrict__ out) {
+                                                           double* __restrict__ out, long long mat_rows) {
     const int lane = threadIdx.x & 63;
     const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
-    const float* g = G + row * n; const bf16* a = Acat + row * ((long long)GRID_TERMS * n + GRID_PAD);
+    const long long pitch = (long long)GRID_TERMS * n + GRID_PAD;
+    const float* g = G + row * n; const bf16* a = Acat + row * pitch;
     double s = 0.0;
+    if (mat_rows > 0) {
+        a = Acat + (row / mat_rows) * mat_rows * pitch; const long long r = row % mat_rows;
+        for (int c = lane; c < n; c += 64)
+            s += (double)g[c] * ((double)__bfloat162float(a[tboa_blocked_offset(r, c, pitch >> 5)]) +
+                                 (double)__bfloat162float(a[tboa_blocked_offset(r, n + c, pitch >> 5)]));
+    } else
     for (int c = lane; c < n; c += 64) s += (double)g[c] * ((double)__bfloat162float(a[c]) + (double)__bfloat162float(a[n + c]));
     s = wave_sum(s);
     if (lane == 0) out[row] = s;
@@ -548,7 +569,7 @@ struct Layer {
     double *Q64, *s64, *z64;
     double *Wb, *Wk, *Epan, *Wsnap, *E, *S1, *S2, *T;
     double *cand_s, *cand_z, *Delta, *G, *cost, *DeltaS, *GS, *costS;
-    __hip_bfloat16* Hcat; int* sel; int fast_grid;
+    __hip_bfloat16* Hcat; int* sel; int fast_grid, grid_blocked;
     double *Wbar, *Abar, *Z, *WR, *Cm, *Fm, *dvec, *lossbuf;
     double *Cg, *Fg;    // group-wise refinement: Gram blocks per (group, group) pair
     int grid_chunk;     // block rows (shared H_in) or heads (per-head H_in) per grid-search pass
@@ -577,18 +598,21 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             TB_HIP(ctx, hipMemsetAsync(ovf, 0, sizeof(int), ctx->stream));
             TB_HIP(ctx, hipMemsetAsync(ovf + 1 + GRID_MAX_OVF, 0, sizeof(int), ctx->stream));
             static_assert(10 + GRID_MAX_OVF <= 256, "status words");
+            // both operands in the GEMM's 16 x 32 blocks when the shapes allow it (L.grid_blocked, decided with Hcat)
+            long long mat_rows = L.grid_blocked ? (long long)(ph ? rows_per_head : rows) * ncand : 0;
+            if (mat_rows % 16) mat_rows = 0;
             hipLaunchKernelGGL(grid_delta_split_kernel, dim3((n + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, n, ncand, L.maxq,
-                               L.cand_s, L.cand_z, Acat);
+                               L.cand_s, L.cand_z, Acat, mat_rows);
             TB_KERNEL_CHECK(ctx);
             GemmBf16 a{};
             a.N = n; a.K = GRID_TERMS * n; a.alpha = 1.f; a.A = Acat; a.lda = (long long)GRID_TERMS * n + GRID_PAD; a.ldb = a.lda; a.C = G32; a.ldc = n;
-            a.c_dtype = TBOA_F32; a.accumulate = 0; a.flags = 0; a.tag = TBOA_PROF_GRID;
+            a.c_dtype = TBOA_F32; a.accumulate = 0; a.flags = (mat_rows > 0 ? TBOA_GEMM_A_TILED : 0) | (L.grid_blocked ? TBOA_GEMM_B_TILED : 0); a.tag = TBOA_PROF_GRID;
             if (ph) { a.M = rows_per_head * ncand; a.batch = nu; a.B = L.Hcat + (long long)u0 * n * a.lda;
                       a.strideA = (long long)a.M * a.lda; a.strideB = (long long)n * a.lda; a.strideC = (long long)a.M * n; }
             else { a.M = rows * ncand; a.batch = 1; a.B = L.Hcat; }
             TB_TRY(gemm_bf16_nt(ctx, a));
             const long long crow = (long long)rows * ncand;
-            hipLaunchKernelGGL(rowdot_split_kernel, dim3((unsigned)((crow + 3) / 4)), dim3(256), 0, ctx->stream, G32, Acat, crow, n, L.cost);
+            hipLaunchKernelGGL(rowdot_split_kernel, dim3((unsigned)((crow + 3) / 4)), dim3(256), 0, ctx->stream, G32, Acat, crow, n, L.cost, mat_rows);
             const int per = ph ? rows_per_head : rows, ngrp = rows / per;    // rows that share one H_in
             int* cntv = L.sel + (long long)rows * GRID_KS; int* offv = cntv + rows; int* totv = offv + rows;
             hipLaunchKernelGGL(grid_select_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.cost, rows, ncand, GRID_TAU, L.sel, cntv, ovf);
@@ -686,7 +710,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     TB_HIP(ctx, hipMemcpyAsync(L.Hfac, L.Hi, nhin * nn * sizeof(double), hipMemcpyDeviceToDevice, st));
     if (L.fast_grid) {
         long long tot = nhin * nn, gb = (tot + 255) / 256; if (gb > 32768) gb = 32768;
-        hipLaunchKernelGGL(hcat_kernel, dim3((unsigned)gb), dim3(256), 0, st, L.Hi, L.Hcat, n, tot);
+        hipLaunchKernelGGL(hcat_kernel, dim3((unsigned)gb), dim3(256), 0, st, L.Hi, L.Hcat, n, tot, L.grid_blocked);
         TB_KERNEL_CHECK(ctx);
     }
     TB_TRY(chol_inv_upper_f64(ctx, n, nhin, L.Hfac, L.Uin, L.ftmp, L.fdinv));
@@ -925,6 +949,7 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
         else { int c = (int)(cap / per_row); const int tot = nh * max_rows_block; L.grid_chunk = c < 1 ? 1 : (c > tot ? tot : c); }
     }
     L.fast_grid = (!d->group && n % 8 == 0 && n >= 256) ? 1 : 0;   // per-row grids of wide layers: two-phase search
+    L.grid_blocked = (L.fast_grid && n % 32 == 0 && !getenv("TBOA_NO_BLOCKED_GRID")) ? 1 : 0;   // its GEMM operands in 16 x 32 blocks
     const size_t grows = (size_t)L.grid_chunk * (L.nhin > 1 ? (d->adaptive_grid ? blk : dh) : 1);
     const int fmax = n > dh ? n : dh;
     const int fb = (L.nhin > nh) ? L.nhin : nh;
