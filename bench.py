@@ -77,7 +77,8 @@ def cpu_baseline(blk, cfg, hessians, budget_note):
 def roofline_probe(ctx, cfg, torch):
     """The command the HBM-traffic counter runs are made with: one plain copy of 1 GiB (a kernel of known traffic, to scale
     the counters), then ONE launch of the dominant kernel in the launch shape the benchmark times: H_in^V += Y^T (Y^T)^T for
-    all KV heads over a chunk of 8 sequences (lower tiles, accumulating into fp32), operands at the benchmark's row pitch."""
+    all KV heads over a chunk of 8 sequences (lower tiles, accumulating into fp32), operands at the benchmark's row pitch and,
+    as in the benchmark, read as 16 x 32 blocks (the values are random either way)."""
     import paper_2602_04929_amd as tb
     rep, G = cfg.n_q_heads // cfg.n_kv_heads, 8
     ky = rep * G * cfg.seq_len
@@ -92,11 +93,11 @@ def roofline_probe(ctx, cfg, torch):
     torch.mul(src, 1.0, out=dst)                                              # reads 1 GiB, writes 1 GiB
     torch.cuda.synchronize()
     Y = YT[:, :, :ky]
-    ctx.gemm_bf16_nt(Y, Y, C_out=Hv, accumulate=True, flags=tb.GEMM_LOWER)
+    ctx.gemm_bf16_nt(Y, Y, C_out=Hv, accumulate=True, flags=tb.GEMM_LOWER | tb.GEMM_A_TILED | tb.GEMM_B_TILED)
     torch.cuda.synchronize()
     n = cfg.d_model
     alg = cfg.n_kv_heads * (n * ky * 2 + 2 * 4 * n * (n + 1) // 2)            # Y^T read once, lower half of H read + written
-    print(json.dumps({"probe": "copy 1 GiB, then gemm_bf16_nt LOWER accumulate", "copy_bytes_read": src.numel() * 4,
+    print(json.dumps({"probe": "copy 1 GiB, then gemm_bf16_nt LOWER accumulate, blocked operands", "copy_bytes_read": src.numel() * 4,
                       "copy_bytes_written": src.numel() * 4, "gemm_batch": cfg.n_kv_heads, "gemm_M": n, "gemm_K": ky,
                       "gemm_algorithmic_bytes": alg}))
 
