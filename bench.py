@@ -111,6 +111,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-R", action="store_true", help="first-block setting: no upstream deviation (R = 0)")
     ap.add_argument("--n-seqs", type=int, default=0, help="override the number of calibration sequences (profiling runs)")
+    ap.add_argument("--seq-chunk", type=int, default=0, help="sequences per pass of the W_V Hessian build (0 = library default)")
     ap.add_argument("--serial-layers", action="store_true", help="quantize W_Q, W_K, W_V one after the other on one stream")
     ap.add_argument("--with-mlp", action="store_true",
                     help="also time the gated MLP of the same transformer block (reported beside the metric, never inside `value`)")
@@ -147,7 +148,7 @@ def main():
     side = None if args.serial_layers else make_side_contexts(2)
 
     def step(timings=None):
-        return quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=use_R, timings=timings, side_contexts=side)
+        return quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=use_R, timings=timings, side_contexts=side, seq_chunk=args.seq_chunk)
 
     for _ in range(args.warmup):
         out = step()

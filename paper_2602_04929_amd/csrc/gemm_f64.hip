@@ -6,6 +6,9 @@
 // conflict-free.  Workgroup: 256 threads = 4 wavefronts (2 x 2), tile 128 x 128 x 16, each wavefront owns a
 // 64 x 64 sub-tile as 4 x 4 MFMA tiles (64 fp64 accumulators per lane).  Global -> register -> LDS software
 // pipeline with two LDS buffers, one barrier per k-step.
+// Products with at most 32 rows per batch entry (the compensation terms of a block of out-channels against a d x d
+// factor per head) run a 32 x 128 tile instead (wavefronts 1 x 4, each 32 x 32): with the 128-row tile three quarters
+// of the MFMAs would multiply padding, and those products are bound by reading B once from HBM.
 #include "internal.h"
 
 typedef double v4d __attribute__((ext_vector_type(4)));
@@ -31,15 +34,15 @@ struct Args {
 
 // Loads the BMxBK tile of an operand whose element (r, k) lives at base[r*s_r + k*s_k].
 // KC: s_k == 1 (k-contiguous), else s_r == 1.  Out-of-range elements read as zero.
-template <bool KC>
+template <bool KC, int ROWS>
 __device__ __forceinline__ void load_tile(const double* __restrict__ base, long long s_r, long long s_k,
-                                          int r0, int k0, int r_lim, int k_lim, bool vec, double (&reg)[8]) {
+                                          int r0, int k0, int r_lim, int k_lim, bool vec, double (&reg)[ROWS / 16]) {
     const int t = threadIdx.x;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < ROWS / 32; ++p) {
         const int idx = t + 256 * p;
         int r, k;
-        if (KC) { r = idx >> 3; k = (idx & 7) * 2; } else { k = idx >> 6; r = (idx & 63) * 2; }
+        if (KC) { r = idx >> 3; k = (idx & 7) * 2; } else { k = idx / (ROWS / 2); r = (idx % (ROWS / 2)) * 2; }
         const int gr = r0 + r, gk = k0 + k;
         double v0 = 0.0, v1 = 0.0;
         if (KC) {
@@ -59,40 +62,44 @@ __device__ __forceinline__ void load_tile(const double* __restrict__ base, long 
     }
 }
 
-template <bool KC>
-__device__ __forceinline__ void store_tile(double* __restrict__ lds, const double (&reg)[8]) {
+template <bool KC, int ROWS>
+__device__ __forceinline__ void store_tile(double* __restrict__ lds, const double (&reg)[ROWS / 16]) {
     const int t = threadIdx.x;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < ROWS / 32; ++p) {
         const int idx = t + 256 * p;
         if (KC) {
             const int r = idx >> 3, k = (idx & 7) * 2;
             lds[r * PKC + k] = reg[2 * p]; lds[r * PKC + k + 1] = reg[2 * p + 1];
         } else {
-            const int k = idx >> 6, r = (idx & 63) * 2;
-            *(double2*)(lds + k * PMC + r) = make_double2(reg[2 * p], reg[2 * p + 1]);
+            const int k = idx / (ROWS / 2), r = (idx % (ROWS / 2)) * 2;
+            *(double2*)(lds + k * (ROWS + 16) + r) = make_double2(reg[2 * p], reg[2 * p + 1]);
         }
     }
 }
 
-template <bool KC>
+// pitch of a [k][row] tile: ROWS + 16 doubles, so that k and k + 1 land 32 of the 64 LDS banks apart (ROWS = 128 or 32)
+template <bool KC, int ROWS>
 __device__ __forceinline__ double lds_at(const double* __restrict__ lds, int r, int k) {
-    return KC ? lds[r * PKC + k] : lds[k * PMC + r];
+    return KC ? lds[r * PKC + k] : lds[k * (ROWS + 16) + r];
 }
 
-template <bool AKC, bool BKC>
+// TM: rows of the output tile, 128 (wavefronts 2 x 2, 64 x 64 each) or 32 (wavefronts 1 x 4, 32 x 32 each)
+template <bool AKC, bool BKC, int TM>
 __global__ __launch_bounds__(256) void gemm_f64_kernel(Args g, bool vecA, bool vecB) {
-    __shared__ __attribute__((aligned(16))) double As[2][TILE];
+    constexpr int TI = TM == 128 ? 4 : 2, TJ = TM == 128 ? 4 : 2;     // 16 x 16 MFMA tiles per wavefront
+    constexpr int ATILE = TM == 128 ? TILE : 32 * (BK + 16);          // covers [32][PKC] and [BK][32 + 16]
+    __shared__ __attribute__((aligned(16))) double As[2][ATILE];
     __shared__ __attribute__((aligned(16))) double Bs[2][TILE];
 
     // Workgroups go to the eight XCDs round-robin by linear number, so with a column count that is a multiple of 8 an XCD
     // always gets the same tile columns; where the contraction length grows with the column (diag_order), the columns of
     // each tile row are rotated by the row number so that every XCD sees all lengths.
     const int tx = g.diag_order ? (int)((blockIdx.x + blockIdx.y) % gridDim.x) : (int)blockIdx.x;
-    const int m0 = blockIdx.y * BM, n0 = tx * BN;
+    const int m0 = blockIdx.y * TM, n0 = tx * BN;
     if (g.m_limit && m0 >= g.m_limit[blockIdx.z]) return;
     if (g.skip_lower && g.skip_col0 + n0 + BN <= m0) return;
-    if (g.skip_upper && m0 + BM <= g.skip_col0 + n0) return;
+    if (g.skip_upper && m0 + TM <= g.skip_col0 + n0) return;
     const long long b = blockIdx.z / g.batch_inner, b2 = blockIdx.z % g.batch_inner;
     const double* A = g.A + b * g.strideA + b2 * g.strideA2;
     const double* B = g.B + b * g.strideB + b2 * g.strideB2;
@@ -101,27 +108,27 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(Args g, bool vecA, bool v
     int klo = 0, khi = g.K;
     if (g.klo_m) klo = max(klo, m0);
     if (g.klo_n) klo = max(klo, n0);
-    if (g.khi_m) khi = min(khi, m0 + BM);
+    if (g.khi_m) khi = min(khi, m0 + TM);
     if (g.khi_n) khi = min(khi, n0 + BN);
     klo = (klo / BK) * BK;
     const int nk = khi > klo ? (khi - klo + BK - 1) / BK : 0;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int wm = TM == 128 ? (wave >> 1) * 64 : 0, wn = TM == 128 ? (wave & 1) * 64 : wave * 32;
     const int l16 = lane & 15, lk = lane >> 4;
 
-    v4d acc[4][4];
+    v4d acc[TI][TJ];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (v4d){0.0, 0.0, 0.0, 0.0};
+        for (int j = 0; j < TJ; ++j) acc[i][j] = (v4d){0.0, 0.0, 0.0, 0.0};
 
-    double ra[8], rb[8];
+    double ra[TM / 16], rb[8];
     if (nk > 0) {
-        load_tile<AKC>(A, g.sa_r, g.sa_k, m0, klo, g.M, khi, vecA, ra);
-        load_tile<BKC>(B, g.sb_r, g.sb_k, n0, klo, g.N, khi, vecB, rb);
-        store_tile<AKC>(As[0], ra);
-        store_tile<BKC>(Bs[0], rb);
+        load_tile<AKC, TM>(A, g.sa_r, g.sa_k, m0, klo, g.M, khi, vecA, ra);
+        load_tile<BKC, BN>(B, g.sb_r, g.sb_k, n0, klo, g.N, khi, vecB, rb);
+        store_tile<AKC, TM>(As[0], ra);
+        store_tile<BKC, BN>(Bs[0], rb);
     }
     __syncthreads();
 
@@ -129,38 +136,38 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(Args g, bool vecA, bool v
         const int cur = kt & 1;
         if (kt + 1 < nk) {
             const int k0 = klo + (kt + 1) * BK;
-            load_tile<AKC>(A, g.sa_r, g.sa_k, m0, k0, g.M, khi, vecA, ra);
-            load_tile<BKC>(B, g.sb_r, g.sb_k, n0, k0, g.N, khi, vecB, rb);
+            load_tile<AKC, TM>(A, g.sa_r, g.sa_k, m0, k0, g.M, khi, vecA, ra);
+            load_tile<BKC, BN>(B, g.sb_r, g.sb_k, n0, k0, g.N, khi, vecB, rb);
         }
 #pragma unroll
         for (int k4 = 0; k4 < BK / 4; ++k4) {
-            double a[4], bb[4];
+            double a[TI], bb[TJ];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = lds_at<AKC>(As[cur], wm + 16 * i + l16, 4 * k4 + lk);
+            for (int i = 0; i < TI; ++i) a[i] = lds_at<AKC, TM>(As[cur], wm + 16 * i + l16, 4 * k4 + lk);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bb[j] = lds_at<BKC>(Bs[cur], wn + 16 * j + l16, 4 * k4 + lk);
+            for (int j = 0; j < TJ; ++j) bb[j] = lds_at<BKC, BN>(Bs[cur], wn + 16 * j + l16, 4 * k4 + lk);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < TI; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < TJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], bb[j], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < nk) {
-            store_tile<AKC>(As[cur ^ 1], ra);
-            store_tile<BKC>(Bs[cur ^ 1], rb);
+            store_tile<AKC, TM>(As[cur ^ 1], ra);
+            store_tile<BKC, BN>(Bs[cur ^ 1], rb);
         }
         __syncthreads();
     }
 
     // accumulator element v of tile (i, j): row 16 i + lane / 16 + 4 v, column 16 j + lane % 16
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int row = m0 + wm + 16 * i + lk + 4 * v;
             if (row >= g.M) continue;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < TJ; ++j) {
                 const int col = n0 + wn + 16 * j + l16;
                 if (col >= g.N) continue;
                 double* c = C + (long long)row * g.ldc + col;
@@ -192,12 +199,15 @@ int gemm_f64(tboa_ctx* ctx, const GemmF64& q) {
     // 16-byte vector loads need every row start and the tile offsets (even) to stay 16-byte aligned
     const bool vecA = ((uintptr_t)q.A % 16 == 0) && (q.strideA % 2 == 0) && (q.strideA2 % 2 == 0) && ((akc ? q.sam : q.sak) % 2 == 0);
     const bool vecB = ((uintptr_t)q.B % 16 == 0) && (q.strideB % 2 == 0) && (q.strideB2 % 2 == 0) && ((bkc ? q.sbn : q.sbk) % 2 == 0);
-    dim3 grid((unsigned)cdiv64(q.N, BN), (unsigned)cdiv64(q.M, BM), (unsigned)q.batch);
+    const bool skinny = q.M <= 32 && akc;
+    dim3 grid((unsigned)cdiv64(q.N, BN), (unsigned)cdiv64(q.M, skinny ? 32 : BM), (unsigned)q.batch);
     if (grid.y > 65535 || grid.z > 65535) return tboa_fail(ctx, TBOA_EINVAL, "gemm_f64: grid too large");
-    if (akc && bkc) hipLaunchKernelGGL((gemm_f64_kernel<true, true>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
-    else if (akc && !bkc) hipLaunchKernelGGL((gemm_f64_kernel<true, false>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
-    else if (!akc && bkc) hipLaunchKernelGGL((gemm_f64_kernel<false, true>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
-    else hipLaunchKernelGGL((gemm_f64_kernel<false, false>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
+    if (skinny && bkc) hipLaunchKernelGGL((gemm_f64_kernel<true, true, 32>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
+    else if (skinny) hipLaunchKernelGGL((gemm_f64_kernel<true, false, 32>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
+    else if (akc && bkc) hipLaunchKernelGGL((gemm_f64_kernel<true, true, BM>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
+    else if (akc && !bkc) hipLaunchKernelGGL((gemm_f64_kernel<true, false, BM>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
+    else if (!akc && bkc) hipLaunchKernelGGL((gemm_f64_kernel<false, true, BM>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
+    else hipLaunchKernelGGL((gemm_f64_kernel<false, false, BM>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
     TB_KERNEL_CHECK(ctx);
     return 0;
 }

@@ -15,7 +15,8 @@ def ctx(lib):
     c.close()
 
 
-@pytest.mark.parametrize("M,N,K", [(128, 128, 16), (256, 384, 64), (77, 131, 45), (1, 5, 3), (300, 64, 1000)])
+# M <= 32 with a k-contiguous A takes the 32-row tile
+@pytest.mark.parametrize("M,N,K", [(128, 128, 16), (256, 384, 64), (77, 131, 45), (1, 5, 3), (300, 64, 1000), (32, 640, 333), (20, 257, 77)])
 @pytest.mark.parametrize("tA,tB", [(False, False), (False, True), (True, False), (True, True)])
 def test_gemm_f64(ctx, M, N, K, tA, tB):
     print("gemm_f64", M, N, K, tA, tB, flush=True)
