@@ -30,6 +30,7 @@ struct Args {
     int batch_inner;
     int klo_m, klo_n, khi_m, khi_n, skip_lower, skip_upper, skip_col0, diag_order;
     const int* m_limit;
+    const double* A2; const double* B2;
 };
 
 // Loads the BMxBK tile of an operand whose element (r, k) lives at base[r*s_r + k*s_k].
@@ -103,6 +104,8 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(Args g, bool vecA, bool v
     const long long b = blockIdx.z / g.batch_inner, b2 = blockIdx.z % g.batch_inner;
     const double* A = g.A + b * g.strideA + b2 * g.strideA2;
     const double* B = g.B + b * g.strideB + b2 * g.strideB2;
+    const double* A2 = g.A2 ? g.A2 + b * g.strideA + b2 * g.strideA2 : nullptr;
+    const double* B2 = g.A2 ? g.B2 + b * g.strideB + b2 * g.strideB2 : nullptr;
     double* C = g.C + b * g.strideC + b2 * g.strideC2;
 
     int klo = 0, khi = g.K;
@@ -111,7 +114,8 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(Args g, bool vecA, bool v
     if (g.khi_m) khi = min(khi, m0 + TM);
     if (g.khi_n) khi = min(khi, n0 + BN);
     klo = (klo / BK) * BK;
-    const int nk = khi > klo ? (khi - klo + BK - 1) / BK : 0;
+    const int nk1 = khi > klo ? (khi - klo + BK - 1) / BK : 0;      // k-steps of one pair of operands
+    const int nk = A2 ? 2 * nk1 : nk1;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = TM == 128 ? (wave >> 1) * 64 : 0, wn = TM == 128 ? (wave & 1) * 64 : wave * 32;
@@ -135,9 +139,10 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(Args g, bool vecA, bool v
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
         if (kt + 1 < nk) {
-            const int k0 = klo + (kt + 1) * BK;
-            load_tile<AKC, TM>(A, g.sa_r, g.sa_k, m0, k0, g.M, khi, vecA, ra);
-            load_tile<BKC, BN>(B, g.sb_r, g.sb_k, n0, k0, g.N, khi, vecB, rb);
+            const bool second = kt + 1 >= nk1;
+            const int k0 = klo + (kt + 1 - (second ? nk1 : 0)) * BK;
+            load_tile<AKC, TM>(second ? A2 : A, g.sa_r, g.sa_k, m0, k0, g.M, khi, vecA, ra);
+            load_tile<BKC, BN>(second ? B2 : B, g.sb_r, g.sb_k, n0, k0, g.N, khi, vecB, rb);
         }
 #pragma unroll
         for (int k4 = 0; k4 < BK / 4; ++k4) {
@@ -195,10 +200,12 @@ int gemm_f64(tboa_ctx* ctx, const GemmF64& q) {
     a.strideA2 = q.strideA2; a.strideB2 = q.strideB2; a.strideC2 = q.strideC2;
     a.batch_inner = q.batch_inner > 0 ? q.batch_inner : 1;
     a.klo_m = q.klo_m; a.klo_n = q.klo_n; a.khi_m = q.khi_m; a.khi_n = q.khi_n;
+    a.A2 = q.A2; a.B2 = q.A2 ? q.B2 : nullptr;
+    if (q.A2 && (!q.B2 || q.klo_m || q.klo_n || q.khi_m || q.khi_n)) return tboa_fail(ctx, TBOA_EINVAL, "gemm_f64: a second operand pair needs both operands and an unrestricted contraction");
     a.skip_lower = q.skip_lower; a.skip_upper = q.skip_upper; a.skip_col0 = q.skip_col0; a.m_limit = q.m_limit; a.diag_order = q.diag_order;
     // 16-byte vector loads need every row start and the tile offsets (even) to stay 16-byte aligned
-    const bool vecA = ((uintptr_t)q.A % 16 == 0) && (q.strideA % 2 == 0) && (q.strideA2 % 2 == 0) && ((akc ? q.sam : q.sak) % 2 == 0);
-    const bool vecB = ((uintptr_t)q.B % 16 == 0) && (q.strideB % 2 == 0) && (q.strideB2 % 2 == 0) && ((bkc ? q.sbn : q.sbk) % 2 == 0);
+    const bool vecA = ((uintptr_t)q.A % 16 == 0) && ((uintptr_t)q.A2 % 16 == 0) && (q.strideA % 2 == 0) && (q.strideA2 % 2 == 0) && ((akc ? q.sam : q.sak) % 2 == 0);
+    const bool vecB = ((uintptr_t)q.B % 16 == 0) && ((uintptr_t)q.B2 % 16 == 0) && (q.strideB % 2 == 0) && (q.strideB2 % 2 == 0) && ((bkc ? q.sbn : q.sbk) % 2 == 0);
     const bool skinny = q.M <= 32 && akc;
     dim3 grid((unsigned)cdiv64(q.N, BN), (unsigned)cdiv64(q.M, skinny ? 32 : BM), (unsigned)q.batch);
     if (grid.y > 65535 || grid.z > 65535) return tboa_fail(ctx, TBOA_EINVAL, "gemm_f64: grid too large");

@@ -85,6 +85,9 @@ struct GemmF64 {
     int skip_col0 = 0;   // column of C's first column relative to its first row, for the two tests above
     int diag_order = 0;  // rotate the tile columns of tile row r by r: spreads column-dependent contraction lengths over the XCDs
     const int* m_limit = nullptr;   // device array [batch]: rows m >= m_limit[b] of batch entry b are not computed
+    // optional second pair of operands with the shapes, strides and batch strides of the first:
+    // C = alpha (A B + A2 B2) + beta C in one pass (not combined with the contraction-range restrictions)
+    const double* A2 = nullptr; const double* B2 = nullptr;
 };
 int gemm_f64(tboa_ctx* ctx, const GemmF64& g);
 

@@ -762,8 +762,9 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
             hipLaunchKernelGGL((sweep_panel_kernel<2>), dim3((nbr + 7) / 8, nh), dim3(256), 0, st, a);
             TB_KERNEL_CHECK(ctx);
             if (c1 < n) {   // columns right of the panel: W[:, c1:] -= E U[c0:c1, c1:] + Wsnap P[c0:c1, c1:]
-                TB_TRY(block_gemm(L, nbr, n - c1, pw, -1.0, L.Epan, 64, L.Uin, (long long)c0 * n + c1, n, 1, 1.0, L.Wk + c1, n));
-                if (Pp) TB_TRY(block_gemm(L, nbr, n - c1, pw, -1.0, L.Wsnap, 64, L.P, (long long)c0 * n + c1, n, 1, 1.0, L.Wk + c1, n));
+                GemmF64 two{};   // both terms in one pass over the output
+                if (Pp) { two.A2 = L.Wsnap; two.B2 = L.P + (long long)c0 * n + c1; }
+                TB_TRY(block_gemm(L, nbr, n - c1, pw, -1.0, L.Epan, 64, L.Uin, (long long)c0 * n + c1, n, 1, 1.0, L.Wk + c1, n, &two));
             }
         }
         if (H_out && i1 < dh) {
