@@ -532,6 +532,19 @@ __global__ void finalize_kernel(const double* __restrict__ Wbar, const double* _
         }
 }
 
+// (Q - W) H_in from products that the scale refinement already formed, for one scale per row (Q = diag(s) Wbar):
+// DH = diag(s) (Wbar H_in) - W H_in, with W H_in = Z + W R where Z = W (H_in - R).  Overwrites AH = Wbar H_in.
+__global__ void dh_from_products_kernel(double* __restrict__ AH, const double* __restrict__ s, const double* __restrict__ Z,
+                                        const double* __restrict__ WR, int n) {
+    const int r = blockIdx.y;
+    const double sr = s[r];
+    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < n; c += gridDim.x * blockDim.x) {
+        const long long i = (long long)r * n + c;
+        const double wh = WR ? Z[i] + WR[i] : Z[i];
+        AH[i] = sr * AH[i] - wh;
+    }
+}
+
 // out[h] = scale * sum_{j,k} Ho[h][j,k] M[h][k,j]
 __global__ __launch_bounds__(256) void head_trace_kernel(const double* __restrict__ Ho, const double* __restrict__ M, int dh,
                                                          double scale, double* __restrict__ out) {
@@ -871,7 +884,10 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     if (loss || loss_per_head) {
         // D = Q - W (into Wbar), D H_in (into Abar)
         TB_TRY(launch_sub_f64(ctx, L.Q64, L.W64, L.Wbar, wn));
-        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.Wbar, n, L.Hi, 0, n, 1, 0.0, L.Abar, n));
+        if (d->cd_iters > 0 && !d->group) {   // Abar = Wbar H_in and Z are still those of the scale refinement
+            hipLaunchKernelGGL(dh_from_products_kernel, dim3(gx(n), rows_all), dim3(256), 0, st, L.Abar, L.s64, L.Z, R ? L.WR : nullptr, n);
+            TB_KERNEL_CHECK(ctx);
+        } else TB_TRY(block_gemm(L, dh, n, n, 1.0, L.Wbar, n, L.Hi, 0, n, 1, 0.0, L.Abar, n));
         double* lq = L.lossbuf; double* lc = L.lossbuf + nh;
         TB_TRY(launch_fill_f64(ctx, L.lossbuf, 2 * nh, 0.0));
         if (H_out) {
