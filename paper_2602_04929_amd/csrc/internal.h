@@ -118,7 +118,7 @@ __device__ __forceinline__ long long tboa_blocked_offset(long long r, long long 
 // returns TBOA_ENOTSPD on breakdown (synchronises).  tmp: workspace of batch*n*TB_FACT_OB doubles,
 // dinv: batch * ceil(n / TB_FACT_NB) * TB_FACT_NB^2 doubles.
 #define TB_FACT_NB 64     // diagonal blocks factored inside LDS
-#define TB_FACT_OB 256    // outer blocks: width of the large trailing updates
+#define TB_FACT_OB 512    // outer blocks: width of the large trailing updates
 int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H64, double* U, double* tmp, double* dinv);
 int launch_f32_to_f64_damp(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* out);
 
