@@ -129,12 +129,15 @@ typedef __hip_bfloat16 bf16;
 
 constexpr int GRID_TERMS = 2;        // segments of the concatenated contraction axis
 
-// Hcat[b, r, :] = [hi(H[r,:]) | hi(H[r,:])]; blocked: every [n, 2n + pad] matrix in the 16 x 32 blocks of the bf16 GEMM
+// H_in is symmetric, so delta H delta^T = 2 delta T delta^T with T = the lower triangle of H and half its diagonal: the GEMM
+// then needs, for output column r, only the contraction indices c <= r (its causal limit), half the products.
+// Hcat[b, r, :] = [hi(T[r,:]) | hi(T[r,:])]; blocked: every [n, 2n + pad] matrix in the 16 x 32 blocks of the bf16 GEMM
 __global__ void hcat_kernel(const double* __restrict__ H, bf16* __restrict__ out, int n, long long total, int blocked) {
     const long long pitch = GRID_TERMS * n + GRID_PAD;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
         const long long row = i / n; const int c = (int)(i % n);
-        const float v = (float)H[i];
+        const int rr = (int)(row % n);
+        const float v = c < rr ? (float)H[i] : c == rr ? (float)(0.5 * H[i]) : 0.f;
         const bf16 hi = __float2bfloat16(v);
         if (blocked) {
             bf16* o = out + (row / n) * n * pitch; const long long r = row % n;
@@ -174,7 +177,7 @@ __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __r
     }
 }
 
-// cost[i] = sum_c G[i, c] (hi + lo)[i, c], one wavefront per row
+// cost[i] = 2 sum_c G[i, c] (hi + lo)[i, c], one wavefront per row (G = delta T^T, see hcat_kernel)
 __global__ __launch_bounds__(256) void rowdot_split_kernel(const float* __restrict__ G, const bf16* __restrict__ Acat, long long rows, int n,
                                                            double* __restrict__ out, long long mat_rows) {
     const int lane = threadIdx.x & 63;
@@ -191,7 +194,7 @@ __global__ __launch_bounds__(256) void rowdot_split_kernel(const float* __restri
     } else
     for (int c = lane; c < n; c += 64) s += (double)g[c] * ((double)__bfloat162float(a[c]) + (double)__bfloat162float(a[n + c]));
     s = wave_sum(s);
-    if (lane == 0) out[row] = s;
+    if (lane == 0) out[row] = 2.0 * s;
 }
 
 // per row: the candidates within tau of the approximate minimum, in increasing k (unused slots repeat the first);
@@ -620,6 +623,7 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             GemmBf16 a{};
             a.N = n; a.K = GRID_TERMS * n; a.alpha = 1.f; a.A = Acat; a.lda = (long long)GRID_TERMS * n + GRID_PAD; a.ldb = a.lda; a.C = G32; a.ldc = n;
             a.c_dtype = TBOA_F32; a.accumulate = 0; a.flags = (mat_rows > 0 ? TBOA_GEMM_A_TILED : 0) | (L.grid_blocked ? TBOA_GEMM_B_TILED : 0); a.tag = TBOA_PROF_GRID;
+            a.flags |= TBOA_GEMM_CAUSAL_K; a.kseg = n;   // Hcat holds the lower triangle: contraction index <= output column, in both segments
             if (ph) { a.M = rows_per_head * ncand; a.batch = nu; a.B = L.Hcat + (long long)u0 * n * a.lda;
                       a.strideA = (long long)a.M * a.lda; a.strideB = (long long)n * a.lda; a.strideC = (long long)a.M * n; }
             else { a.M = rows * ncand; a.batch = 1; a.B = L.Hcat; }
