@@ -341,6 +341,24 @@ int scores(const Dims& D, const bf16* Qh, const bf16* Kh, int sl, float* Sc) {
     return gemm_bf16_nt(D.ctx, g);
 }
 
+// Both score matrices of a sequence (the quantized-input path and the full-precision path).  With one query head per KV
+// head the two products are one launch whose outer batch index is the path: 2 x 36 x H tiles fill the 256 CUs evenly
+// where 36 x H leave the last round half empty.  (The path stride is the distance between the two buffers.)
+int scores_pair(const Dims& D, const bf16* Qh, const bf16* Kh, const bf16* Qhf, const bf16* Khf, int sl, float* Sc, float* Scf) {
+    const long long dq = Qhf - Qh, dk = Khf - Kh, dc = Scf - Sc;
+    if (D.rep != 1 || dq % 8 || dk % 8 || dc % 4 || getenv("TBOA_NO_SCORES_PAIR")) {
+        TB_TRY(scores(D, Qh, Kh, sl, Sc));
+        return scores(D, Qhf, Khf, sl, Scf);
+    }
+    const int L = D.L, dh3 = 3 * D.dh;
+    GemmBf16 g = nt(L, L, dh3, (float)(1.0 / sqrt((double)D.dh)), Qh + (long long)sl * L * D.Hq * dh3, (long long)D.Hq * dh3,
+                    Kh + (long long)sl * L * D.Hkv * dh3, (long long)D.Hkv * dh3, Sc, L, TBOA_F32, 0, D.d->causal ? TBOA_GEMM_LOWER : 0);
+    g.batch = 2 * D.Hq; g.batch_inner = D.Hq;
+    g.strideA = dq; g.strideA2 = dh3; g.strideB = dk; g.strideB2 = dh3;
+    g.strideC = dc; g.strideC2 = (long long)L * L;
+    return gemm_bf16_nt(D.ctx, g);
+}
+
 // probabilities in 16 x 32 blocks (per head) when `blocked`: see blocked_inputs
 int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long ldp, int copies, int dcol, int blocked = 0) {
     if (D.L % 4 == 0 && D.L <= 2048 && ldp % 4 == 0 && dcol % 4 == 0)
@@ -468,8 +486,8 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         }
         for (int sl = 0; sl < Gc; ++sl) {
             // P = [A | A - A~];  Y^T = X_s^T A^T;  (Y - Y~)^T = [dX_s^T | X~_s^T] [A | A - A~]^T  since  A X - A~ X~ = A dX + (A - A~) X~
-            TB_TRY(scores(D, Qh, Kh, sl, Sc));
-            if (rv) TB_TRY(scores(D, Qhf, Khf, sl, Scf));
+            if (rv) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
+            else TB_TRY(scores(D, Qh, Kh, sl, Sc));
             TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, ldp, 1, L, bin));
             // Y^T and (Y - Y~)^T are read only by the two products below: with whole 256 x 256 tiles they are written in the
             // blocked layout of the GEMM (column offset c -> pointer offset 16 c), whose blocks those products load whole
@@ -569,8 +587,8 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         for (int sl = 0; sl < Gc; ++sl) {
             // V^T segments [V'hi | V'lo | V' - V~ | V~], P = [A' | A' | A' - A~]:
             // O^T_h = [V'hi | V'lo] [A' | A']^T ;  (O - O~)^T_h = [V' - V~ | V~] [A' | A' - A~]^T
-            TB_TRY(scores(D, Qh, Kh, sl, Sc));
-            if (fp) TB_TRY(scores(D, Qhf, Khf, sl, Scf));
+            if (fp) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
+            else TB_TRY(scores(D, Qh, Kh, sl, Sc));
             TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, ldp, 2, 2 * L));
             GemmBf16 o = nt(dh, L, 2 * L, 1.f, VTc + (long long)sl * nsg * L, ldv, P, ldp, OT + t0 + (long long)sl * L, TP,
                             TBOA_BF16, 0, cflag);
