@@ -596,8 +596,18 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             o.strideA = (long long)dh * ldv; o.strideA2 = 0;
             o.strideB = (long long)rep * L * ldp; o.strideB2 = (long long)L * ldp;
             o.strideC = (long long)rep * dh * TP; o.strideC2 = (long long)dh * TP;
-            TB_TRY(gemm_bf16_nt(ctx, o));
-            if (fp) { o.A = VTc + ((long long)sl * nsg + 2) * L; o.B = P + L; o.C = dOT + t0 + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, o)); }
+            if (fp && rep == 1 && (dOT - OT) % 8 == 0 && !getenv("TBOA_NO_PV_PAIR")) {
+                // both products in one launch, the outer batch index choosing the pair of segments and the output: with one
+                // 256-wide tile per CU the launch lasts as long as its deepest causal tile, with two they pair up long and short
+                o.batch = 2 * Hq; o.batch_inner = Hq;
+                o.strideA = 2 * L; o.strideA2 = (long long)dh * ldv;
+                o.strideB = L; o.strideB2 = (long long)L * ldp;
+                o.strideC = dOT - OT; o.strideC2 = (long long)dh * TP;
+                TB_TRY(gemm_bf16_nt(ctx, o));
+            } else {
+                TB_TRY(gemm_bf16_nt(ctx, o));
+                if (fp) { o.A = VTc + ((long long)sl * nsg + 2) * L; o.B = P + L; o.C = dOT + t0 + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, o)); }
+            }
         }
     }
     TB_TRY(gram_splitk(ctx, splits, dq, OT, nullptr, OT, TP, T, 1.0, 1, part, Hin_o));
