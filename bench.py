@@ -111,6 +111,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-R", action="store_true", help="first-block setting: no upstream deviation (R = 0)")
     ap.add_argument("--n-seqs", type=int, default=0, help="override the number of calibration sequences (profiling runs)")
+    ap.add_argument("--correlated", action="store_true", help="correlated channels: X <- X (I + 0.3 low-rank); reported separately")
     ap.add_argument("--seq-chunk", type=int, default=0, help="sequences per pass of the W_V Hessian build (0 = library default)")
     ap.add_argument("--serial-layers", action="store_true", help="quantize W_Q, W_K, W_V one after the other on one stream")
     ap.add_argument("--with-mlp", action="store_true",
@@ -141,6 +142,8 @@ def main():
         ctx.close()
         return
     blk = synth.make_block(cfg, seed=0, device="cuda:0")
+    if args.correlated:
+        synth.apply_mix(blk, synth.correlated_mix(cfg.d_model, seed=0, device="cuda:0"))
     ctx = tb.Context()
     use_R = not args.no_R
 
@@ -183,7 +186,7 @@ def main():
         "config": {"workload": "%s attention block: d_model=%d, %d q-heads / %d kv-heads x %d, %d seqs x %d tokens, INT%d, N=%d, "
                                "group=%d, alpha=0.25, R %s, adaptive grid, 1 CD sweep"
                                % (cfg.name, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_seqs, cfg.seq_len, cfg.bits,
-                                  cfg.block, cfg.group, "on" if use_R else "off")},
+                                  cfg.block, cfg.group, "on" if use_R else "off") + (", correlated channels" if args.correlated else "")},
         "mfma_util_pct": 100.0 * achieved / PEAK_BF16_TFLOPS,
         "stage_seconds": {k: v / args.steps for k, v in stages.items()},
         "bf16_gemm_seconds_per_step": mfma_ms * 1e-3,

@@ -13,6 +13,7 @@
 // and after the last step the coordinate descent of Algorithm 2 on precomputed Gram matrices (d_h x d_h per head; per
 // pair of groups when the grids are group-wise), then the outputs and the loss.
 #include "internal.h"
+#include <string.h>
 #include <stdlib.h>
 #include <math.h>
 
@@ -116,40 +117,43 @@ __global__ void grid_argmin_kernel(const double* __restrict__ cost, const double
 }
 
 // ---- two-phase search: approximate costs of all candidates on the bf16 matrix cores, exact fp64 costs of the few
-// candidates within GRID_TAU of the approximate minimum.  delta is split into an exact-to-16-bits (hi, lo) bf16 pair, H_in
-// is rounded to bf16, and  delta H  ~  hi.hi + lo.hi  is one GEMM over the concatenated axis.  The rounding of delta has
-// to be carried to 16 bits because it differs from candidate to candidate; the rounding of H_in, E = H_in - hi(H_in), is
-// the same for all of them: it moves every cost by delta E delta^T <= 2^-9 |delta|^T |H_in| |delta|, in practice (entries
-// of E of either sign) by some 1e-5 of the cost, far inside GRID_TAU, and moves neighbouring candidates alike.
+// candidates within GRID_TAU of the approximate minimum.  delta and H_in are each split into an exact-to-16-bits (hi, lo)
+// bf16 pair and  delta H  ~  hi.hi + lo.hi + hi.lo  is one GEMM over three concatenated segments.  Both need their second
+// term: the cost is a difference of large terms when the input channels are correlated (cost / (|delta| |H| |delta|^T)
+// of 2e-3 is ordinary), so an operand carried to 8 bits leaves errors of 1e-2 of the cost, five times GRID_TAU, and the
+// true minimum can fall outside the survivors; with 16 bits on both sides the error is some 1e-5 of the cost.  As a guard,
+// every exact re-evaluation is compared with its approximation, and a pass whose largest deviation exceeds a quarter of
+// GRID_TAU is repeated with exact costs for every candidate (counted by tboa_counter).
 constexpr int GRID_PAD = 256;        // extra elements per row of the concatenated operands (memory-channel spread)
 constexpr int GRID_KS = 6;          // exact re-evaluations per row
 constexpr double GRID_TAU = 2e-3;   // survivors: approximate cost <= (1 + tau) * approximate minimum
 
 typedef __hip_bfloat16 bf16;
 
-constexpr int GRID_TERMS = 2;        // segments of the concatenated contraction axis
+constexpr int GRID_TERMS = 3;        // segments of the concatenated contraction axis: [hi | lo | hi] of delta against [hi | hi | lo] of T
 
 // H_in is symmetric, so delta H delta^T = 2 delta T delta^T with T = the lower triangle of H and half its diagonal: the GEMM
 // then needs, for output column r, only the contraction indices c <= r (its causal limit), half the products.
-// Hcat[b, r, :] = [hi(T[r,:]) | hi(T[r,:])]; blocked: every [n, 2n + pad] matrix in the 16 x 32 blocks of the bf16 GEMM
+// Hcat[b, r, :] = [hi(T[r,:]) | hi(T[r,:]) | lo(T[r,:])]; blocked: every [n, 3n + pad] matrix in the 16 x 32 blocks of the bf16 GEMM
 __global__ void hcat_kernel(const double* __restrict__ H, bf16* __restrict__ out, int n, long long total, int blocked) {
     const long long pitch = GRID_TERMS * n + GRID_PAD;
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
         const long long row = i / n; const int c = (int)(i % n);
         const int rr = (int)(row % n);
         const float v = c < rr ? (float)H[i] : c == rr ? (float)(0.5 * H[i]) : 0.f;
-        const bf16 hi = __float2bfloat16(v);
+        const bf16 hi = __float2bfloat16(v), lo = __float2bfloat16(v - __bfloat162float(hi));
         if (blocked) {
             bf16* o = out + (row / n) * n * pitch; const long long r = row % n;
             o[tboa_blocked_offset(r, c, pitch >> 5)] = hi; o[tboa_blocked_offset(r, n + c, pitch >> 5)] = hi;
+            o[tboa_blocked_offset(r, 2 * n + c, pitch >> 5)] = lo;
         } else {
             bf16* o = out + row * pitch + c;
-            o[0] = hi; o[n] = hi;
+            o[0] = hi; o[n] = hi; o[2 * n] = lo;
         }
     }
 }
 
-// Acat[(row, k), :] = [hi(delta) | lo(delta)], delta as in grid_delta_kernel; mat_rows > 0: Acat is a sequence of matrices
+// Acat[(row, k), :] = [hi(delta) | lo(delta) | hi(delta)], delta as in grid_delta_kernel; mat_rows > 0: Acat is a sequence of matrices
 // of mat_rows rows each (the rows that share one H_in), every one kept in the 16 x 32 blocks of the bf16 GEMM
 __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
                                                                const double* __restrict__ cand_s, const double* __restrict__ cand_z,
@@ -170,9 +174,10 @@ __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __r
             const long long R = (long long)row * ncand + k;
             bf16* o = Acat + (R / mat_rows) * mat_rows * pitch; const long long r = R % mat_rows;
             o[tboa_blocked_offset(r, c, pitch >> 5)] = hi; o[tboa_blocked_offset(r, n + c, pitch >> 5)] = lo;
+            o[tboa_blocked_offset(r, 2 * n + c, pitch >> 5)] = hi;
         } else {
             bf16* o = out + (long long)k * pitch;
-            o[0] = hi; o[n] = lo;
+            o[0] = hi; o[n] = lo; o[2 * n] = hi;
         }
     }
 }
@@ -277,18 +282,26 @@ __global__ __launch_bounds__(256) void rowdot_limited_kernel(const double* __res
 
 // lowest exact cost among the evaluated candidates of a row (lowest k among equals: they are in increasing k); a row
 // with a single candidate inside tau takes that one
-__global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const int* __restrict__ sel, const int* __restrict__ cnt,
+// max_dev: the largest |approximate - exact| / exact seen over all re-evaluated candidates, as the bits of a non-negative float
+__global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const double* __restrict__ cost, const int* __restrict__ sel,
+                                       const int* __restrict__ cnt,
                                        const int* __restrict__ off, int per, const double* __restrict__ cand_s,
                                        const double* __restrict__ cand_z, int rows, int ncand, BlockMap m, int r_off,
-                                       double* __restrict__ s_out, double* __restrict__ z_out, int ng, int gi) {
+                                       double* __restrict__ s_out, double* __restrict__ z_out, int ng, int gi, int* __restrict__ max_dev) {
     const int row = blockIdx.x * blockDim.x + threadIdx.x;
     if (row >= rows) return;
     int best = 0;
     const int nc = cnt[row];
     if (nc > 1) {
         const double* c = costS + (long long)(row / per) * per * GRID_KS + off[row];
-        double bc = c[0];
-        for (int j = 1; j < nc; ++j) if (c[j] < bc) { bc = c[j]; best = j; }
+        double bc = c[0], dev = 0.0;
+        for (int j = 0; j < nc; ++j) {
+            if (c[j] < bc) { bc = c[j]; best = j; }
+            const double a = cost[(long long)row * ncand + sel[(long long)row * GRID_KS + j]];
+            const double d = fabs(a - c[j]) / fabs(c[j]);
+            dev = (d == d) ? fmax(dev, d) : 1.0;
+        }
+        atomicMax(max_dev, __float_as_int((float)fmin(dev, 1.0)));
     }
     const int k = sel[(long long)row * GRID_KS + best];
     const long long lr = layer_row(m, r_off + row);
@@ -612,8 +625,8 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             __hip_bfloat16* Acat = (__hip_bfloat16*)L.Delta; float* G32 = (float*)L.G;
             int* ovf = ctx->d_status + 8;   // [0] count, [1..] rows
             TB_HIP(ctx, hipMemsetAsync(ovf, 0, sizeof(int), ctx->stream));
-            TB_HIP(ctx, hipMemsetAsync(ovf + 1 + GRID_MAX_OVF, 0, sizeof(int), ctx->stream));
-            static_assert(10 + GRID_MAX_OVF <= 256, "status words");
+            TB_HIP(ctx, hipMemsetAsync(ovf + 1 + GRID_MAX_OVF, 0, 2 * sizeof(int), ctx->stream));   // survivors, largest deviation
+            static_assert(11 + GRID_MAX_OVF <= 256, "status words");
             // both operands in the GEMM's 16 x 32 blocks when the shapes allow it (L.grid_blocked, decided with Hcat)
             long long mat_rows = L.grid_blocked ? (long long)(ph ? rows_per_head : rows) * ncand : 0;
             if (mat_rows % 16) mat_rows = 0;
@@ -623,7 +636,7 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             GemmBf16 a{};
             a.N = n; a.K = GRID_TERMS * n; a.alpha = 1.f; a.A = Acat; a.lda = (long long)GRID_TERMS * n + GRID_PAD; a.ldb = a.lda; a.C = G32; a.ldc = n;
             a.c_dtype = TBOA_F32; a.accumulate = 0; a.flags = (mat_rows > 0 ? TBOA_GEMM_A_TILED : 0) | (L.grid_blocked ? TBOA_GEMM_B_TILED : 0); a.tag = TBOA_PROF_GRID;
-            a.flags |= TBOA_GEMM_CAUSAL_K; a.kseg = n;   // Hcat holds the lower triangle: contraction index <= output column, in both segments
+            a.flags |= TBOA_GEMM_CAUSAL_K; a.kseg = n;   // Hcat holds the lower triangle: contraction index <= output column, in every segment
             if (ph) { a.M = rows_per_head * ncand; a.batch = nu; a.B = L.Hcat + (long long)u0 * n * a.lda;
                       a.strideA = (long long)a.M * a.lda; a.strideB = (long long)n * a.lda; a.strideC = (long long)a.M * n; }
             else { a.M = rows * ncand; a.batch = 1; a.B = L.Hcat; }
@@ -645,15 +658,17 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             const long long srow = (long long)rows * GRID_KS;
             hipLaunchKernelGGL(rowdot_limited_kernel, dim3((unsigned)((srow + 3) / 4)), dim3(256), 0, ctx->stream, L.GS, L.DeltaS, n, per * GRID_KS,
                                srow, totv, L.costS);
-            hipLaunchKernelGGL(grid_argmin_sel_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.costS, L.sel, cntv, offv, per,
-                               L.cand_s, L.cand_z, rows, ncand, map, r0, L.s64, L.z64, L.ng, gi);
+            hipLaunchKernelGGL(grid_argmin_sel_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.costS, L.cost, L.sel, cntv, offv, per,
+                               L.cand_s, L.cand_z, rows, ncand, map, r0, L.s64, L.z64, L.ng, gi, ovf + 2 + GRID_MAX_OVF);
             TB_KERNEL_CHECK(ctx);
-            TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 8, ovf, (2 + GRID_MAX_OVF) * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+            TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 8, ovf, (3 + GRID_MAX_OVF) * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
             TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
             ++ctx->counters[TBOA_CTR_GRID_PASSES];
             ctx->counters[TBOA_CTR_GRID_SURVIVORS] += ctx->h_status[9 + GRID_MAX_OVF];
             const int novf = ctx->h_status[8];
-            done = novf <= GRID_MAX_OVF;
+            float dev; memcpy(&dev, &ctx->h_status[10 + GRID_MAX_OVF], sizeof(float));
+            // approximate costs that stray from the exact ones by a quarter of the survivors' margin are not trusted: exact pass
+            done = novf <= GRID_MAX_OVF && dev <= 0.25 * GRID_TAU;
             if (!done) ++ctx->counters[TBOA_CTR_GRID_FALLBACKS];
             for (int i = 0; done && i < novf; ++i) {
                 // a row with many near-minimal candidates: every candidate exactly, for this row alone
@@ -969,7 +984,7 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
         if (L.nhin > 1) { int c = (int)(cap / (per_row * max_rows_block)); L.grid_chunk = c < 1 ? 1 : (c > nh ? nh : c); }
         else { int c = (int)(cap / per_row); const int tot = nh * max_rows_block; L.grid_chunk = c < 1 ? 1 : (c > tot ? tot : c); }
     }
-    L.fast_grid = (!d->group && n % 8 == 0 && n >= 256) ? 1 : 0;   // per-row grids of wide layers: two-phase search
+    L.fast_grid = (!d->group && n % 8 == 0 && n >= 256 && !getenv("TBOA_NO_FAST_GRID")) ? 1 : 0;   // per-row grids of wide layers: two-phase search
     L.grid_blocked = (L.fast_grid && n % 32 == 0 && !getenv("TBOA_NO_BLOCKED_GRID")) ? 1 : 0;   // its GEMM operands in 16 x 32 blocks
     const size_t grows = (size_t)L.grid_chunk * (L.nhin > 1 ? (d->adaptive_grid ? blk : dh) : 1);
     const int fmax = n > dh ? n : dh;

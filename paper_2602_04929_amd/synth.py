@@ -135,3 +135,14 @@ def correlated_mix(d, rank=8, strength=0.3, seed=0, device="cpu"):
     a = torch.randn(d, rank, generator=g, device=device)
     b = torch.randn(rank, d, generator=g, device=device)
     return torch.eye(d, device=device) + strength * (a @ b) / math.sqrt(rank)
+
+
+def apply_mix(blk, M):
+    """X_fp <- X_fp M and X <- X M in place, one sequence at a time (fp32 product, rounded back to the block's dtype)."""
+    for key in ("X_fp", "X"):
+        t = blk.get(key)
+        if t is None:
+            continue
+        for s in range(t.shape[0]):
+            t[s] = (t[s].float() @ M).to(t.dtype)
+    return blk

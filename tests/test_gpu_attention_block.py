@@ -55,3 +55,25 @@ def test_tiny_config_end_to_end(lib, use_R, side, stack):
         frac = compare_layer(got[layer], want[layer], label=layer)
         print("tiny R=%s layer %s: codes identical %.4f%%" % (use_R, layer, 100 * frac), flush=True)
     ctx.close()
+
+
+def test_tiny_config_correlated_channels(lib):
+    """The tiny configuration with correlated channels (X <- X (I + 0.3 low-rank)): iid channels give a nearly diagonal
+    H_in, under which the compensation and the P term of the sweep do little; here they carry weight."""
+    from paper_2602_04929_amd.pipeline import quantize_attention_block
+    cfg = synth.CONFIGS["tiny"]
+    blk = synth.make_block(cfg, seed=0, device="cuda")
+    synth.apply_mix(blk, synth.correlated_mix(cfg.d_model, seed=0, device="cuda"))
+    ctx = lib.Context()
+    got = quantize_attention_block(ctx, blk, cfg, use_R=True)
+    torch.cuda.synchronize()
+    want = oracle_block(blk, cfg, use_R=True)
+    Hin = want["hessians"]["Hin_qk"]
+    dg = np.sqrt(np.diag(Hin))
+    off = np.abs(Hin / dg[:, None] / dg[None, :] - np.eye(cfg.d_model)).max()
+    assert off > 0.3, "the mix should couple the channels"
+    want["qk"] = stacked(want["q"], want["k"])
+    for layer in ("qk", "v", "o"):
+        frac = compare_layer(got[layer], want[layer], label=layer)
+        print("tiny correlated layer %s: codes identical %.4f%%, largest off-diagonal correlation %.2f" % (layer, 100 * frac, off), flush=True)
+    ctx.close()
