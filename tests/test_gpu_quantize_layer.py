@@ -1,4 +1,6 @@
 """tboa_quantize_layer against the fp64 oracle on the same seeded inputs (GPU)."""
+import zlib
+
 import numpy as np
 import pytest
 import torch
@@ -16,12 +18,13 @@ def ctx(lib):
     c.close()
 
 
-def make_case(seed, n_heads, dh, n, T, per_head_in=False, corr=0.5):
+def make_case(seed, n_heads, dh, n, T, per_head_in=False, corr=0.5, mix=0.0):
     r = np.random.default_rng(seed)
+    M = np.eye(n) + mix * (r.standard_normal((n, 8)) @ r.standard_normal((8, n))) / np.sqrt(8.0) if mix else None
     def acts():
         X = r.standard_normal((T, n)) + corr * r.standard_normal((T, 1))
         X[:, r.integers(0, n, 3)] *= 10
-        return X
+        return X @ M if mix else X
     W = (r.standard_normal((n_heads * dh, n)) * 0.02).astype(np.float32)
     if per_head_in:
         Xs = [acts() for _ in range(n_heads)]
@@ -62,6 +65,11 @@ CASES = [
     ("group-o", 1, 48, 256, False, False, True, dict(bits=3, block=48, group=128, cd_iters=2)),
     ("group-32", 2, 16, 96, False, True, True, dict(bits=4, block=4, group=32)),
     ("group-fixed-grid", 2, 16, 128, False, True, False, dict(bits=3, block=4, group=64, adaptive_grid=False)),
+    # the two-phase grid search (d_in >= 256) over two tile columns, with strongly coupled input channels (X <- X (I + 0.3
+    # low-rank)): the cost delta H delta^T is then a small difference of large terms
+    ("coupled-q-512", 2, 32, 512, False, True, True, dict(bits=2, block=16)),
+    ("coupled-v-512", 2, 16, 512, True, True, True, dict(bits=2, block=8)),
+    ("coupled-o-384-int4", 1, 64, 384, False, False, True, dict(bits=4, block=64)),
 ]
 
 
@@ -69,7 +77,8 @@ CASES = [
 def test_quantize_layer_matches_oracle(ctx, case):
     name, nh, dh, n, ph, use_ho, use_r, kw = case
     print("quantize_layer case", name, flush=True)
-    W, Hin, Hout, R = make_case(hash(name) % 1000, nh, dh, n, T=4 * n, per_head_in=ph)
+    W, Hin, Hout, R = make_case(zlib.crc32(name.encode()) % 1000, nh, dh, n, T=4 * n, per_head_in=ph,
+                                mix=0.3 if name.startswith("coupled") else 0.0)
     got, want = run_both(ctx, W, Hin, Hout if use_ho else None, R if use_r else None, nh, **kw)
     frac = compare_layer(got, want, label=name)
     print("codes identical: %.4f%%" % (100 * frac), flush=True)
