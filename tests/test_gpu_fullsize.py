@@ -134,3 +134,25 @@ def test_quantize_out_proj_sampled_rows(full):
     frac = compare_layer(sub, want, label="o rows")
     print("  W_O sampled rows: codes identical %.4f%%" % (100 * frac), flush=True)
     assert np.isfinite(got["loss"])
+
+
+def test_quantize_layer_coupled_channels_full_width(lib):
+    """d_in = 4096 with strongly coupled channels (X <- X (I + 0.3 low-rank), built here rather than through the attention
+    block): the two-phase grid search over 16 tile columns where the cost is a small difference of large terms."""
+    d, dh, nh, T = CFG.d_model, CFG.head_dim, 2, 16384
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    M = synth.correlated_mix(d, seed=3, device="cuda")
+    X = torch.randn(T, d, generator=g, device="cuda") @ M
+    dX = 0.05 * torch.randn(T, d, generator=g, device="cuda")
+    Hin = (X.double().T @ X.double()).float()
+    R = (0.25 * (dX.double().T @ X.double())).float()
+    Gq = torch.randn(nh, T, dh, generator=g, device="cuda").double()
+    Hout = (Gq.transpose(1, 2) @ Gq).float()
+    W = (0.02 * torch.randn(nh * dh, d, generator=g, device="cuda")).to(torch.bfloat16)
+    ctx = lib.Context()
+    got = ctx.quantize_layer(W, Hin, Hout, R, nh, bits=CFG.bits, block=CFG.block)
+    print("  passes %d, fully exact passes %d, fully exact rows %d" % (ctx.counter(0), ctx.counter(1), ctx.counter(2)), flush=True)
+    want = O.quantize_layer(f64(W), f64(Hin), f64(Hout), f64(R), nh, bits=CFG.bits, block=CFG.block)
+    frac = compare_layer(got, want, label="coupled full width")
+    print("  coupled channels, d_in 4096: codes identical %.4f%%" % (100 * frac), flush=True)
+    ctx.close()
