@@ -227,7 +227,8 @@ __global__ void grid_select_kernel(const double* __restrict__ cost, int rows, in
     for (int j = cnt; j < GRID_KS; ++j) o[j] = first;
     // a single candidate inside tau wins without an exact evaluation; a row with too many gets every candidate evaluated
     // on its own afterwards: neither takes part in the exact pass
-    const int ev = (cnt > 1 && !ovf) ? cnt : 0;
+    // (every eighth row is re-evaluated even then: its exact cost is what the deviation guard of the pass measures)
+    const int ev = ((cnt > 1 || row % 8 == 0) && !ovf) ? cnt : 0;
     cnt_out[row] = ev;
     atomicAdd(overflow + 1 + GRID_MAX_OVF, ev);
 }
@@ -292,7 +293,7 @@ __global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const d
     if (row >= rows) return;
     int best = 0;
     const int nc = cnt[row];
-    if (nc > 1) {
+    if (nc > 0) {
         const double* c = costS + (long long)(row / per) * per * GRID_KS + off[row];
         double bc = c[0], dev = 0.0;
         for (int j = 0; j < nc; ++j) {
@@ -668,7 +669,10 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             const int novf = ctx->h_status[8];
             float dev; memcpy(&dev, &ctx->h_status[10 + GRID_MAX_OVF], sizeof(float));
             // approximate costs that stray from the exact ones by a quarter of the survivors' margin are not trusted: exact pass
-            done = novf <= GRID_MAX_OVF && dev <= 0.25 * GRID_TAU;
+            // (TBOA_GRID_GUARD: the fraction of tau, default 0.25; 0 sends every pass with re-evaluations to the exact path, which
+            // is how the tests reach it)
+            const char* gs = getenv("TBOA_GRID_GUARD");
+            done = novf <= GRID_MAX_OVF && dev <= (gs ? atof(gs) : 0.25) * GRID_TAU;
             if (!done) ++ctx->counters[TBOA_CTR_GRID_FALLBACKS];
             for (int i = 0; done && i < novf; ++i) {
                 // a row with many near-minimal candidates: every candidate exactly, for this row alone

@@ -148,3 +148,17 @@ def test_packed_layer_carries_the_quantized_weights(ctx):
     y = ctx.dequant_gemv(packed, got["scales"], got["zeros"], x, 256, 3, 64)
     ref = got["W_deq"].double() @ x.double()
     assert torch.allclose(y.double(), ref, rtol=1e-5, atol=1e-6 * ref.abs().max().item())
+
+
+def test_grid_search_guard_takes_the_exact_path(ctx, monkeypatch):
+    """The two-phase search repeats a pass with exact costs for every candidate when its approximate costs stray from the
+    exact re-evaluations by more than a fraction of tau.  With the fraction set to 0 every pass that re-evaluated anything
+    takes that path; the result must be the oracle's all the same."""
+    W, Hin, Hout, R = make_case(77, 2, 32, 256, T=1024, mix=0.3)
+    before = ctx.counter(1)
+    monkeypatch.setenv("TBOA_GRID_GUARD", "0")
+    got, want = run_both(ctx, W, Hin, Hout, R, 2, bits=2, block=16)
+    monkeypatch.delenv("TBOA_GRID_GUARD")
+    assert ctx.counter(1) > before, "no pass fell back to exact costs"
+    frac = compare_layer(got, want, label="guard")
+    print("guarded passes: %d, codes identical %.4f%%" % (ctx.counter(1) - before, 100 * frac), flush=True)
