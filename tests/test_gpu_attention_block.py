@@ -77,3 +77,20 @@ def test_tiny_config_correlated_channels(lib):
         frac = compare_layer(got[layer], want[layer], label=layer)
         print("tiny correlated layer %s: codes identical %.4f%%, largest off-diagonal correlation %.2f" % (layer, 100 * frac, off), flush=True)
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_tiny_config_other_seeds(lib, seed):
+    """The tiny configuration end to end on two more seeds (the parity cases above all use seed 0)."""
+    from paper_2602_04929_amd.pipeline import quantize_attention_block
+    cfg = synth.CONFIGS["tiny"]
+    blk = synth.make_block(cfg, seed=seed, device="cuda")
+    ctx = lib.Context()
+    got = quantize_attention_block(ctx, blk, cfg, use_R=True)
+    torch.cuda.synchronize()
+    want = oracle_block(blk, cfg, use_R=True)
+    want["qk"] = stacked(want["q"], want["k"])
+    for layer in ("qk", "v", "o"):
+        frac = compare_layer(got[layer], want[layer], label=layer)
+        print("tiny seed %d layer %s: codes identical %.4f%%" % (seed, layer, 100 * frac), flush=True)
+    ctx.close()
