@@ -200,7 +200,11 @@ __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __r
     for (int c = 0; c < NCH; ++c) {
         const int k = c * 256 + lane * 4;
         float4 a = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY), b = a;
-        if (k < kz) { a = *(const float4*)(s + k); if (s2) b = *(const float4*)(s2 + k); }
+        if (k < kz) {     // the scores are read this once: streaming loads leave the L2 to the probabilities being written
+            typedef float f4 __attribute__((ext_vector_type(4)));
+            const f4 ta = __builtin_nontemporal_load((const f4*)(s + k)); a = make_float4(ta.x, ta.y, ta.z, ta.w);
+            if (s2) { const f4 tb = __builtin_nontemporal_load((const f4*)(s2 + k)); b = make_float4(tb.x, tb.y, tb.z, tb.w); }
+        }
         v[c][0] = a.x; v[c][1] = a.y; v[c][2] = a.z; v[c][3] = a.w;
         w[c][0] = b.x; w[c][1] = b.y; w[c][2] = b.z; w[c][3] = b.w;
 #pragma unroll
