@@ -191,7 +191,21 @@ __global__ __launch_bounds__(256) void rowdot_split_kernel(const float* __restri
     const long long pitch = (long long)GRID_TERMS * n + GRID_PAD;
     const float* g = G + row * n; const bf16* a = Acat + row * pitch;
     double s = 0.0;
-    if (mat_rows > 0) {
+    if (n % 4 == 0) {     // four consecutive columns per lane (they share a 16-byte chunk of a block): 16- and 8-byte streaming loads
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const bf16* base = mat_rows > 0 ? Acat + (row / mat_rows) * mat_rows * pitch : a;
+        const long long r = mat_rows > 0 ? row % mat_rows : 0;
+        for (int c = 4 * lane; c < n; c += 256) {
+            const f4 gv = __builtin_nontemporal_load((const f4*)(g + c));
+            union { uint2 u; bf16 b[4]; } hi, lo;
+            if (mat_rows > 0) {
+                hi.u = *(const uint2*)(base + tboa_blocked_offset(r, c, pitch >> 5));
+                lo.u = *(const uint2*)(base + tboa_blocked_offset(r, n + c, pitch >> 5));
+            } else { hi.u = *(const uint2*)(a + c); lo.u = *(const uint2*)(a + n + c); }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s += (double)gv[j] * ((double)__bfloat162float(hi.b[j]) + (double)__bfloat162float(lo.b[j]));
+        }
+    } else if (mat_rows > 0) {
         a = Acat + (row / mat_rows) * mat_rows * pitch; const long long r = row % mat_rows;
         for (int c = lane; c < n; c += 64)
             s += (double)g[c] * ((double)__bfloat162float(a[tboa_blocked_offset(r, c, pitch >> 5)]) +
