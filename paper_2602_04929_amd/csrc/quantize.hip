@@ -158,27 +158,37 @@ __global__ void hcat_kernel(const double* __restrict__ H, bf16* __restrict__ out
 __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
                                                                const double* __restrict__ cand_s, const double* __restrict__ cand_z,
                                                                bf16* __restrict__ Acat, long long mat_rows) {
+    // four consecutive columns per thread (they share a 16-byte chunk of a block): 8-byte stores
     const int row = blockIdx.y;
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    const int c = 4 * (blockIdx.x * blockDim.x + threadIdx.x);
     if (c >= n) return;
-    const double w = Wk[(long long)row * ldw + c];
+    const int nv = n - c < 4 ? n - c : 4;
+    const bool vec = nv == 4 && n % 4 == 0;
+    double w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = j < nv ? Wk[(long long)row * ldw + c + j] : 0.0;
     const double* cs = cand_s + (long long)row * ncand;
     const double* cz = cand_z + (long long)row * ncand;
     const long long pitch = (long long)GRID_TERMS * n + GRID_PAD;
-    bf16* out = Acat + (long long)row * ncand * pitch + c;
     for (int k = 0; k < ncand; ++k) {
         const double s = cs[k], z = cz[k];
-        const float dl = (float)(s * (quant_code(w, s, z, maxq) - z) - w);
-        const bf16 hi = __float2bfloat16(dl), lo = __float2bfloat16(dl - __bfloat162float(hi));
-        if (mat_rows > 0) {
-            const long long R = (long long)row * ncand + k;
-            bf16* o = Acat + (R / mat_rows) * mat_rows * pitch; const long long r = R % mat_rows;
-            o[tboa_blocked_offset(r, c, pitch >> 5)] = hi; o[tboa_blocked_offset(r, n + c, pitch >> 5)] = lo;
-            o[tboa_blocked_offset(r, 2 * n + c, pitch >> 5)] = hi;
-        } else {
-            bf16* o = out + (long long)k * pitch;
-            o[0] = hi; o[n] = lo; o[2 * n] = hi;
+        union { bf16 b[4]; uint2 u; } hi, lo;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float dl = (float)(s * (quant_code(w[j], s, z, maxq) - z) - w[j]);
+            hi.b[j] = __float2bfloat16(dl); lo.b[j] = __float2bfloat16(dl - __bfloat162float(hi.b[j]));
         }
+        const long long R = (long long)row * ncand + k;
+        bf16* o; long long o0, o1, o2;
+        if (mat_rows > 0) {
+            o = Acat + (R / mat_rows) * mat_rows * pitch; const long long r = R % mat_rows;
+            o0 = tboa_blocked_offset(r, c, pitch >> 5); o1 = tboa_blocked_offset(r, n + c, pitch >> 5); o2 = tboa_blocked_offset(r, 2 * n + c, pitch >> 5);
+        } else { o = Acat + R * pitch; o0 = c; o1 = n + c; o2 = 2 * n + c; }
+        if (vec) { *(uint2*)(o + o0) = hi.u; *(uint2*)(o + o1) = lo.u; *(uint2*)(o + o2) = hi.u; }
+        else
+            for (int j = 0; j < nv; ++j) {     // (a blocked Acat has n % 32 == 0 and never comes here)
+                o[o0 + j] = hi.b[j]; o[o1 + j] = lo.b[j]; o[o2 + j] = hi.b[j];
+            }
     }
 }
 
@@ -645,7 +655,7 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             // both operands in the GEMM's 16 x 32 blocks when the shapes allow it (L.grid_blocked, decided with Hcat)
             long long mat_rows = L.grid_blocked ? (long long)(ph ? rows_per_head : rows) * ncand : 0;
             if (mat_rows % 16) mat_rows = 0;
-            hipLaunchKernelGGL(grid_delta_split_kernel, dim3((n + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, n, ncand, L.maxq,
+            hipLaunchKernelGGL(grid_delta_split_kernel, dim3((n + 1023) / 1024, rows), dim3(256), 0, ctx->stream, Wc, ldw, n, ncand, L.maxq,
                                L.cand_s, L.cand_z, Acat, mat_rows);
             TB_KERNEL_CHECK(ctx);
             GemmBf16 a{};
