@@ -27,10 +27,41 @@ typedef __hip_bfloat16 bf16;
 // outputs are kept in 16 x 32 blocks
 __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__ in, const bf16* __restrict__ in2, long long ld_in,
                                                         int rows, int cols, bf16* __restrict__ out, bf16* __restrict__ out_hi,
-                                                        bf16* __restrict__ out_lo, long long ld_out, int blocked) {
+                                                        bf16* __restrict__ out_lo, long long ld_out, int blocked, int vec) {
     __shared__ float t0[64][65];
     __shared__ float t1[64][65];
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    if (vec && r0 + 64 <= rows && c0 + 64 <= cols) {
+        // whole tile: 16-byte loads of 8 consecutive input columns, 16-byte stores of 8 consecutive input rows (one chunk of a
+        // 16 x 32 block, or of an output row)
+        for (int i = threadIdx.x; i < 512; i += 256) {
+            const int r = i >> 3, c = (i & 7) * 8;
+            union { uint4 u; bf16 b[8]; } a, b2;
+            a.u = *(const uint4*)(in + (long long)(r0 + r) * ld_in + c0 + c);
+            if (in2) b2.u = *(const uint4*)(in2 + (long long)(r0 + r) * ld_in + c0 + c);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float v = __bfloat162float(a.b[j]);
+                t0[r][c + j] = v; t1[r][c + j] = in2 ? v - __bfloat162float(b2.b[j]) : v;
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < 512; i += 256) {
+            const int c = i >> 3, r = (i & 7) * 8;
+            const long long o = blocked ? tboa_blocked_offset(c0 + c, r0 + r, ld_out >> 5) : (long long)(c0 + c) * ld_out + r0 + r;
+            union { uint4 u; bf16 b[8]; } x, hi, lo;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                x.b[j] = __float2bfloat16(t0[r + j][c]);
+                const float dlt = t1[r + j][c];
+                hi.b[j] = __float2bfloat16(dlt);
+                lo.b[j] = __float2bfloat16(dlt - __bfloat162float(hi.b[j]));
+            }
+            if (out) *(uint4*)(out + o) = x.u;
+            if (out_hi) { *(uint4*)(out_hi + o) = hi.u; if (out_lo) *(uint4*)(out_lo + o) = lo.u; }
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < 64 * 64; i += 256) {
         const int r = i >> 6, c = i & 63;
         float v = 0.f, w = 0.f;
@@ -308,8 +339,10 @@ int pick_splits(int n_seqs) {
 
 int transpose(const Dims& D, const bf16* in, const bf16* in2, long long ld_in, int rows, int cols, bf16* out, bf16* hi, bf16* lo, long long ld_out,
               int blocked = 0) {
+    auto al = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+    const int vec = ld_in % 8 == 0 && ld_out % 8 == 0 && al(in) && al(in2) && al(out) && al(hi) && al(lo);
     hipLaunchKernelGGL(transpose_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, D.ctx->stream, in, in2, ld_in, rows, cols,
-                       out, hi, lo, ld_out, blocked);
+                       out, hi, lo, ld_out, blocked, vec);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
 }
