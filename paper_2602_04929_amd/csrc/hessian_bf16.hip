@@ -191,6 +191,26 @@ __global__ __launch_bounds__(256) void int_form_kernel(const float* __restrict__
 __global__ void vt_segments_kernel(const float* __restrict__ in, const float* __restrict__ row_scale, const float* __restrict__ in_fp,
                                    bf16* __restrict__ out, int rows, int G, int L, int nseg, long long ld) {
     const long long tot = (long long)rows * G * L;
+    if (L % 4 == 0 && ld % 4 == 0 && ((uintptr_t)out & 7) == 0) {     // four consecutive tokens per thread: 16-byte streaming loads, 8-byte stores
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        for (long long i4 = blockIdx.x * (long long)blockDim.x + threadIdx.x; i4 < tot / 4; i4 += (long long)gridDim.x * blockDim.x) {
+            const long long i = 4 * i4, row = i / ((long long)G * L); const int s = (int)((i / L) % G), t = (int)(i % L);
+            f4 v = __builtin_nontemporal_load((const f4*)(in + i));
+            if (row_scale) v = v * row_scale[row];
+            f4 w = {0.f, 0.f, 0.f, 0.f};
+            if (in_fp) w = __builtin_nontemporal_load((const f4*)(in_fp + i));
+            union { bf16 b[4]; uint2 u; } h, l, dv, wf;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                h.b[j] = __float2bfloat16(v[j]); l.b[j] = __float2bfloat16(v[j] - __bfloat162float(h.b[j]));
+                dv.b[j] = __float2bfloat16(v[j] - w[j]); wf.b[j] = __float2bfloat16(w[j]);
+            }
+            bf16* o = out + row * ld + ((long long)s * nseg) * L + t;
+            *(uint2*)o = h.u; *(uint2*)(o + L) = l.u;
+            if (in_fp) { *(uint2*)(o + 2 * L) = dv.u; *(uint2*)(o + 3 * L) = wf.u; }
+        }
+        return;
+    }
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
         const long long row = i / ((long long)G * L); const int s = (int)((i / L) % G), t = (int)(i % L);
         const float v = row_scale ? in[i] * row_scale[row] : in[i];
