@@ -129,12 +129,25 @@ __global__ void strict_upper_kernel(double* a, int n) {
     }
 }
 
-__global__ void mirror_lower_kernel(float* a, int n) {
+// upper triangle <- transpose of the lower one, 64 x 64 tiles through LDS (coalesced reads of the lower tile (tr, tc),
+// coalesced writes of its mirror image (tc, tr)); grid.x runs over the tile pairs tr >= tc, grid.z over the matrices
+__global__ __launch_bounds__(256) void mirror_lower_kernel(float* a, int n) {
+    __shared__ float t[64][65];
     float* m = a + (long long)blockIdx.z * n * n;
-    const long long tot = (long long)n * n;
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
-        const int r = (int)(i / n), c = (int)(i % n);
-        if (c > r) m[i] = m[(long long)c * n + r];
+    // tile pair number -> (tr, tc), tr >= tc
+    int tr = (int)((sqrtf(8.f * (float)blockIdx.x + 1.f) - 1.f) * 0.5f);
+    while ((long long)(tr + 1) * (tr + 2) / 2 <= (long long)blockIdx.x) ++tr;
+    while ((long long)tr * (tr + 1) / 2 > (long long)blockIdx.x) --tr;
+    const int tc = (int)(blockIdx.x - (long long)tr * (tr + 1) / 2);
+    const int r0 = tr * 64, c0 = tc * 64;
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int r = i >> 6, c = i & 63;
+        t[r][c] = (r0 + r < n && c0 + c < n) ? m[(long long)(r0 + r) * n + c0 + c] : 0.f;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int c = i >> 6, r = i & 63;      // writes element (c0 + c, r0 + r) = transpose of (r0 + r, c0 + c)
+        if (r0 + r < n && c0 + c < n && r0 + r > c0 + c) m[(long long)(c0 + c) * n + r0 + r] = t[r][c];
     }
 }
 
@@ -181,7 +194,8 @@ int launch_strict_upper_f64(tboa_ctx* ctx, double* a, int n, int batch) {
     TB_KERNEL_CHECK(ctx); return 0;
 }
 int launch_mirror_lower_f32(tboa_ctx* ctx, float* a, int n, int batch) {
-    hipLaunchKernelGGL(mirror_lower_kernel, dim3(grid_for((long long)n * n), 1, batch), dim3(256), 0, ctx->stream, a, n);
+    const long long nt = (n + 63) / 64;
+    hipLaunchKernelGGL(mirror_lower_kernel, dim3((unsigned)(nt * (nt + 1) / 2), 1, batch), dim3(256), 0, ctx->stream, a, n);
     TB_KERNEL_CHECK(ctx); return 0;
 }
 int launch_sub_f64(tboa_ctx* ctx, const double* a, const double* b, double* out, int64_t n) {

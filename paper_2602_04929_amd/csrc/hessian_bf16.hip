@@ -329,6 +329,38 @@ __global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits,
     }
 }
 
+// The same for a symmetric result whose partial sums hold the lower tiles only: tile pair (tr >= tc) per workgroup, the
+// lower tile summed from coalesced reads and written with its mirror image through LDS
+__global__ __launch_bounds__(256) void splitk_reduce_lower_kernel(const float* __restrict__ part, int splits, int n, double scale,
+                                                                  float* __restrict__ out) {
+    __shared__ float t[64][65];
+    const long long nn = (long long)n * n;
+    int tr = (int)((sqrtf(8.f * (float)blockIdx.x + 1.f) - 1.f) * 0.5f);
+    while ((long long)(tr + 1) * (tr + 2) / 2 <= (long long)blockIdx.x) ++tr;
+    while ((long long)tr * (tr + 1) / 2 > (long long)blockIdx.x) --tr;
+    const int tc = (int)(blockIdx.x - (long long)tr * (tr + 1) / 2);
+    const int r0 = tr * 64, c0 = tc * 64;
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int r = i >> 6, c = i & 63;
+        float v = 0.f;
+        if (r0 + r < n && c0 + c < n) {
+            // on the diagonal tile the entries above the diagonal take their mirror image
+            const long long src = (c0 + c > r0 + r) ? (long long)(c0 + c) * n + r0 + r : (long long)(r0 + r) * n + c0 + c;
+            double acc = 0.0;
+            for (int s = 0; s < splits; ++s) acc += (double)part[s * nn + src];
+            v = (float)(scale * acc);
+            out[(long long)(r0 + r) * n + c0 + c] = v;
+        }
+        t[r][c] = v;
+    }
+    if (tr == tc) return;
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int c = i >> 6, r = i & 63;
+        if (r0 + r < n && c0 + c < n) out[(long long)(c0 + c) * n + r0 + r] = t[r][c];
+    }
+}
+
 __global__ void bcast_heads_kernel(const double* __restrict__ src, float* __restrict__ dst, int rep, long long per, long long total) {
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
         const long long h = i / per, e = i % per;
@@ -388,7 +420,11 @@ int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_l
     if (lower) TB_TRY(launch_fill_f32(ctx, part, (int64_t)splits * n * n, 0.f));
     TB_TRY(gemm_bf16_nt(ctx, g));
     if (A_lo) { g.A = A_lo; g.accumulate = 1; TB_TRY(gemm_bf16_nt(ctx, g)); }
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(g1((long long)n * n)), dim3(256), 0, ctx->stream, part, splits, n, scale, lower, out);
+    if (lower) {
+        const long long nt = (n + 63) / 64;
+        hipLaunchKernelGGL(splitk_reduce_lower_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(256), 0, ctx->stream, part, splits, n, scale, out);
+    } else
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(g1((long long)n * n)), dim3(256), 0, ctx->stream, part, splits, n, scale, lower, out);
     TB_HIP(ctx, hipGetLastError());
     return 0;
 }
