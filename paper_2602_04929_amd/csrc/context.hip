@@ -37,12 +37,19 @@ extern "C" int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream) {
     c->err[0] = 0;
     c->ws = nullptr; c->ws_bytes = 0;
     c->d_status = nullptr; c->h_status = nullptr; c->prof_on = 0;
+    c->aux = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
     for (auto& v : c->counters) v = 0;
     if (hipMalloc(&c->d_status, 256 * sizeof(int)) != hipSuccess ||
         hipHostMalloc(&c->h_status, 256 * sizeof(int)) != hipSuccess) {
         if (c->d_status) (void)hipFree(c->d_status);
         delete c;
         return TBOA_ENOMEM;
+    }
+    if (hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+        tboa_destroy(c);
+        return TBOA_EHIP;
     }
     *out = c;
     return 0;
@@ -82,6 +89,9 @@ extern "C" void tboa_destroy(tboa_ctx* ctx) {
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->aux) { (void)hipStreamSynchronize(ctx->aux); (void)hipStreamDestroy(ctx->aux); }
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
     for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (auto& t : ctx->tile_orders) (void)hipFree(t.dev);
     for (auto& t : ctx->tile_schedules) (void)hipFree(t.dev);

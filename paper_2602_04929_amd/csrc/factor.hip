@@ -116,18 +116,28 @@ int launch_f32_to_f64_damp(tboa_ctx* ctx, int n, int batch, const float* H, doub
 // is finished block by block with updates confined to its own columns, after which ONE update with an OB-deep
 // contraction carries it into the rest of the matrix: the large updates are bound by the matrix cores, not by reading
 // and writing the trailing matrix once per NB columns.  The inverse is assembled the same way, OB columns at a time.
-int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H, double* U, double* tmp, double* dinv) {
+int chol_status_f64(tboa_ctx* ctx, int status_slot) {
+    TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + status_slot, ctx->d_status + status_slot, 2 * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->h_status[status_slot] != 0)
+        return tboa_fail(ctx, TBOA_ENOTSPD, "Hessian %d of the batch is not positive definite: pivot %d is not positive",
+                         ctx->h_status[status_slot + 1], ctx->h_status[status_slot] - 1);
+    return 0;
+}
+
+int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H, double* U, double* tmp, double* dinv, int status_slot, bool defer_status) {
+    int* status = ctx->d_status + status_slot;
     constexpr int OB = TB_FACT_OB, IPB = OB / NB;
     const int nblk = (n + NB - 1) / NB, nob = (n + OB - 1) / OB;
     const long long nn = (long long)n * n, dstride = (long long)nblk * NB * NB;
-    TB_HIP(ctx, hipMemsetAsync(ctx->d_status, 0, 2 * sizeof(int), ctx->stream));
+    TB_HIP(ctx, hipMemsetAsync(status, 0, 2 * sizeof(int), ctx->stream));
     // ---- H = V V^T from the last column to the first
     for (int ob = nob - 1; ob >= 0; --ob) {
         const int J0 = ob * OB, J1 = (J0 + OB < n) ? J0 + OB : n;
         const int blk_hi = (J1 + NB - 1) / NB - 1, blk_lo = ob * IPB;
         for (int blk = blk_hi; blk >= blk_lo; --blk) {
             const int j0 = blk * NB, bs = (n - j0 < NB) ? n - j0 : NB;
-            hipLaunchKernelGGL(diag_factor_kernel, dim3(batch), dim3(256), 0, ctx->stream, H, n, j0, bs, dinv, blk, nblk, ctx->d_status);
+            hipLaunchKernelGGL(diag_factor_kernel, dim3(batch), dim3(256), 0, ctx->stream, H, n, j0, bs, dinv, blk, nblk, status);
             TB_KERNEL_CHECK(ctx);
             if (j0 == 0) break;
             // panel: V[0:j0, blk] = H[0:j0, blk] Vinv_jj^T   (in place: one column tile, each workgroup owns its rows)
@@ -200,12 +210,7 @@ int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H, double* U, do
             TB_TRY(gemm_f64(ctx, c));
         }
     }
-    TB_HIP(ctx, hipMemcpyAsync(ctx->h_status, ctx->d_status, 2 * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
-    TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    if (ctx->h_status[0] != 0)
-        return tboa_fail(ctx, TBOA_ENOTSPD, "Hessian %d of the batch is not positive definite: pivot %d is not positive",
-                         ctx->h_status[1], ctx->h_status[0] - 1);
-    return 0;
+    return defer_status ? 0 : chol_status_f64(ctx, status_slot);
 }
 
 extern "C" int tboa_chol_inv_upper(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* U) {

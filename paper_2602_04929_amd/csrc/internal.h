@@ -23,6 +23,8 @@ struct tboa_ctx {
     size_t ws_bytes;
     int* d_status;       // device status words (factorisation breakdown etc.)
     int* h_status;       // pinned host mirror
+    hipStream_t aux;     // second stream (default priority) for work of one call that is independent of what `stream` does
+    hipEvent_t ev_fork, ev_join;
     int prof_on;         // record HIP events around tagged GEMM launches
     std::vector<ProfRec> prof;
     long long counters[8];   // tboa_counter_id
@@ -119,7 +121,11 @@ __device__ __forceinline__ long long tboa_blocked_offset(long long r, long long 
 // dinv: batch * ceil(n / TB_FACT_NB) * TB_FACT_NB^2 doubles.
 #define TB_FACT_NB 64     // diagonal blocks factored inside LDS
 #define TB_FACT_OB 512    // outer blocks: width of the large trailing updates
-int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H64, double* U, double* tmp, double* dinv);
+// status_slot: which pair of device status words records a breakdown (0 or 2); defer_status: do not wait for them here,
+// the caller checks with chol_status_f64 once the work has been joined.
+int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H64, double* U, double* tmp, double* dinv, int status_slot = 0,
+                       bool defer_status = false);
+int chol_status_f64(tboa_ctx* ctx, int status_slot);
 int launch_f32_to_f64_damp(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* out);
 
 // ---------------------------------------------------------------- misc elementwise (elementwise.hip)

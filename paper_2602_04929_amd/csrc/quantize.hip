@@ -773,7 +773,22 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
         hipLaunchKernelGGL(hcat_kernel, dim3((unsigned)gb), dim3(256), 0, st, L.Hi, L.Hcat, n, tot, L.grid_blocked);
         TB_KERNEL_CHECK(ctx);
     }
-    TB_TRY(chol_inv_upper_f64(ctx, n, nhin, L.Hfac, L.Uin, L.ftmp, L.fdinv));
+    // U_in, P and U_out are first needed by the first in-channel sweep; the grid search before it needs only W and H_in.
+    // The factorisations and the two P products (for one matrix: chains of small kernels that leave most of the GPU idle)
+    // therefore run on the context's second stream, beside that grid search; setup_join() below is where they meet.
+    struct StreamSwap {      // everything enqueued while this lives goes to the second stream
+        tboa_ctx* c; hipStream_t keep;
+        explicit StreamSwap(tboa_ctx* c_) : c(c_), keep(c_->stream) { c->stream = c->aux; }
+        ~StreamSwap() { c->stream = keep; }
+    };
+    static const bool no_overlap = getenv("TBOA_NO_SETUP_OVERLAP") != nullptr;
+    const bool forked = !no_overlap;
+    TB_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+    {
+    StreamSwap swap(ctx);
+    if (forked) TB_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->ev_fork, 0));
+    else ctx->stream = st;
+    TB_TRY(chol_inv_upper_f64(ctx, n, nhin, L.Hfac, L.Uin, L.ftmp, L.fdinv, 0, true));
     if (R) {   // Algorithm 3 line 2: P = ((R U^T) * M_U) U
         TB_TRY(launch_cvt_f32_to_f64(ctx, R, L.Rd, nhin * nn));
         GemmF64 a{};
@@ -793,9 +808,24 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     }
     if (H_out) {
         TB_TRY(launch_f32_to_f64_damp(ctx, dh, nh, H_out, d->damp, L.Ho));
-        TB_HIP(ctx, hipMemcpyAsync(L.Hofac, L.Ho, (size_t)nh * dh * dh * sizeof(double), hipMemcpyDeviceToDevice, st));
-        TB_TRY(chol_inv_upper_f64(ctx, dh, nh, L.Hofac, L.Uout, L.ftmp, L.fdinv));
+        TB_HIP(ctx, hipMemcpyAsync(L.Hofac, L.Ho, (size_t)nh * dh * dh * sizeof(double), hipMemcpyDeviceToDevice, ctx->stream));
+        TB_TRY(chol_inv_upper_f64(ctx, dh, nh, L.Hofac, L.Uout, L.ftmp, L.fdinv, 2, true));
     }
+    if (forked) TB_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux));
+    }
+    bool joined = false;
+    struct DrainAux {      // an error return before the join must not leave work running on the workspace
+        tboa_ctx* c; const bool* joined; bool forked;
+        ~DrainAux() { if (forked && !*joined) (void)hipStreamSynchronize(c->aux); }
+    } drain{ctx, &joined, forked};
+    auto setup_join = [&]() -> int {
+        if (joined) return 0;
+        joined = true;
+        if (forked) TB_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
+        TB_TRY(chol_status_f64(ctx, 0));
+        if (H_out) TB_TRY(chol_status_f64(ctx, 2));
+        return 0;
+    };
     const double* Pp = R ? L.P : nullptr;
     const int pw_max = L.gsz < 64 ? L.gsz : 64;
 
@@ -819,6 +849,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
             a.Wk = L.Wk; a.n = n; a.nbr = nbr; a.map = map; a.U = L.Uin; a.P = Pp; a.per_head = nhin > 1;
             a.c0 = c0; a.pw = pw; a.s = L.s64; a.z = L.z64; a.ng = ng; a.gi = gi; a.maxq = L.maxq;
             a.codes = codes; a.Q = L.Q64; a.Epan = L.Epan; a.Wsnap = L.Wsnap;
+            TB_TRY(setup_join());
             hipLaunchKernelGGL((sweep_panel_kernel<2>), dim3((nbr + 7) / 8, nh), dim3(256), 0, st, a);
             TB_KERNEL_CHECK(ctx);
             if (c1 < n) {   // columns right of the panel: W[:, c1:] -= E U[c0:c1, c1:] + Wsnap P[c0:c1, c1:]
