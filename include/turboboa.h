@@ -45,7 +45,10 @@ enum tboa_status {
 enum tboa_dtype { TBOA_F32 = 0, TBOA_BF16 = 1, TBOA_F64 = 2 };
 
 /* Creates a context bound to HIP device `hip_device`; all kernels run on `hip_stream`
- * (a hipStream_t, e.g. torch.cuda.current_stream().cuda_stream; NULL = the default stream). */
+ * (a hipStream_t, e.g. torch.cuda.current_stream().cuda_stream; NULL = the default stream).
+ * The context also owns one more stream of default priority on which tboa_quantize_layer runs work that is independent of
+ * what `hip_stream` is doing; it is forked from and joined back into `hip_stream` inside the call, so that for the caller
+ * everything still happens on `hip_stream` in call order. */
 int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream);
 void tboa_destroy(tboa_ctx* ctx);
 /* Text of the last error on this context; owned by the context, valid until the next call on it. */
