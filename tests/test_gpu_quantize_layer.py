@@ -123,6 +123,12 @@ def test_error_paths(ctx, lib):
     assert e.value.code == -2
     ok = ctx.quantize_layer(t(W), t(Hbad), t(Hout), None, 2, bits=2, block=4, damp=0.01)   # damping repairs it
     assert np.isfinite(ok["loss"])
+    Hobad = Hout.copy(); Hobad[1, 3, :] = 0; Hobad[1, :, 3] = 0     # the same for H_out of head 1 (its own status words)
+    with pytest.raises(lib.TurboBoAError) as e:
+        ctx.quantize_layer(t(W), t(Hin), t(Hobad), None, 2, bits=2, block=4, damp=0.0)
+    assert e.value.code == -2 and "Hessian 1" in str(e.value)
+    ok = ctx.quantize_layer(t(W), t(Hin), t(Hout), None, 2, bits=2, block=4)                # the context is usable afterwards
+    assert np.isfinite(ok["loss"])
 
 
 @pytest.mark.parametrize("bits,group", [(2, 0), (3, 0), (3, 64), (4, 32), (8, 0)])
