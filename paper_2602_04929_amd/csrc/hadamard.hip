@@ -64,7 +64,7 @@ __global__ void hadamard_rotate_kernel(const T* __restrict__ X, const float* __r
     const T* x = X + (long long)blockIdx.x * d;
     T* y = Y + (long long)blockIdx.x * d;
     float v[16];
-    // round 1: bits [0, 4) from 16 consecutive values (16-byte loads)
+    // first butterfly round: bits [0, 4) from 16 consecutive values (16-byte loads)
     load16<T>(x + 16 * t, v);
     if (signs) {
         float sg[16];
