@@ -74,11 +74,13 @@ def cpu_baseline(blk, cfg, hessians, budget_note):
                          budget_note)}
 
 
-def roofline_probe(ctx, cfg, torch):
+def roofline_probe(ctx, cfg, torch, zero=False, reps=0):
     """The command the HBM-traffic counter runs are made with: one plain copy of 1 GiB (a kernel of known traffic, to scale
     the counters), then ONE launch of the dominant kernel in the launch shape the benchmark times: H_in^V += Y^T (Y^T)^T for
     all KV heads over a chunk of 8 sequences (lower tiles, accumulating into fp32), operands at the benchmark's row pitch and,
-    as in the benchmark, read as 16 x 32 blocks (the values are random either way)."""
+    as in the benchmark, read as 16 x 32 blocks (the values are random either way).
+    zero: all-zero operands instead of random ones (same launch, same addresses: what the operand values alone do to the
+    rate).  reps > 0: that many further launches, timed with events on the context's stream, their mean printed."""
     import paper_2602_04929_amd as tb
     rep, G = cfg.n_q_heads // cfg.n_kv_heads, 8
     ky = rep * G * cfg.seq_len
@@ -88,6 +90,8 @@ def roofline_probe(ctx, cfg, torch):
     YT = torch.empty(cfg.n_kv_heads, cfg.d_model, ky + 256, dtype=torch.bfloat16, device="cuda")
     for h in range(cfg.n_kv_heads):
         YT[h] = torch.randn(cfg.d_model, ky + 256, generator=g, device="cuda").to(torch.bfloat16)
+    if zero:
+        YT.zero_()
     Hv = torch.zeros(cfg.n_kv_heads, cfg.d_model, cfg.d_model, device="cuda")
     torch.cuda.synchronize()
     torch.mul(src, 1.0, out=dst)                                              # reads 1 GiB, writes 1 GiB
@@ -97,9 +101,21 @@ def roofline_probe(ctx, cfg, torch):
     torch.cuda.synchronize()
     n = cfg.d_model
     alg = cfg.n_kv_heads * (n * ky * 2 + 2 * 4 * n * (n + 1) // 2)            # Y^T read once, lower half of H read + written
-    print(json.dumps({"probe": "copy 1 GiB, then gemm_bf16_nt LOWER accumulate, blocked operands", "copy_bytes_read": src.numel() * 4,
-                      "copy_bytes_written": src.numel() * 4, "gemm_batch": cfg.n_kv_heads, "gemm_M": n, "gemm_K": ky,
-                      "gemm_algorithmic_bytes": alg}))
+    rec = {"probe": "copy 1 GiB, then gemm_bf16_nt LOWER accumulate, blocked operands", "copy_bytes_read": src.numel() * 4,
+           "copy_bytes_written": src.numel() * 4, "gemm_batch": cfg.n_kv_heads, "gemm_M": n, "gemm_K": ky,
+           "gemm_algorithmic_bytes": alg, "operands": "zero" if zero else "random"}
+    if reps > 0:
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]    # the context runs on torch's current stream
+        ev[0].record()
+        for i in range(reps):
+            ctx.gemm_bf16_nt(Y, Y, C_out=Hv, accumulate=True, flags=tb.GEMM_LOWER | tb.GEMM_A_TILED | tb.GEMM_B_TILED)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+        flops = 2.0 * cfg.n_kv_heads * (n * (n + 1) // 2) * ky                  # the lower triangle, as the library counts this launch
+        rec.update({"reps": reps, "median_launch_ms": ms[reps // 2], "min_launch_ms": ms[0],
+                    "median_tflops": flops / (ms[reps // 2] * 1e-3) / 1e12})
+    print(json.dumps(rec))
 
 
 def main():
@@ -119,6 +135,8 @@ def main():
     ap.add_argument("--roofline-probe", action="store_true",
                     help="run one plain 1 GiB copy and one launch of the dominant kernel in the benchmark's launch shape, nothing else "
                          "(the command for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--probe-zero", action="store_true", help="with --roofline-probe: all-zero operands (same launch otherwise)")
+    ap.add_argument("--probe-reps", type=int, default=0, help="with --roofline-probe: time this many further launches of the kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (heads would shard across GPUs, see DESIGN.md); use --gpus 1", file=sys.stderr)
@@ -138,7 +156,7 @@ def main():
     torch.cuda.set_device(0)
     if args.roofline_probe:
         ctx = tb.Context()
-        roofline_probe(ctx, cfg, torch)
+        roofline_probe(ctx, cfg, torch, zero=args.probe_zero, reps=args.probe_reps)
         ctx.close()
         return
     blk = synth.make_block(cfg, seed=0, device="cuda:0")
