@@ -798,25 +798,85 @@ int swiglu_forward_bf16(tboa_ctx* ctx, long long T, int d, int dff, const bf16* 
     return 0;
 }
 
-// Min-Max per-token fake quantization: one wavefront per token
-template <typename T>
-__global__ __launch_bounds__(256) void act_fakequant_kernel(const T* __restrict__ in, T* __restrict__ out, long long ntok, int d, float maxq) {
+// Min-Max per-token fake quantization (weight-activation setting, Sec. 4.2): one wavefront per token.
+// The level of an element is rint(v / s) + z with the quotient in fp64.  fl32(v * fl32(1/s)) is within 2^-23 (relative) of that
+// quotient, so wherever it lies further than 2^-20 |t| from a half-integer both round to the same integer; only the
+// elements inside that margin (and non-finite products) take the fp64 division.
+__device__ __forceinline__ float act_level(float v, double s, float inv_s, float z, float maxq) {
+    const float t = v * inv_s;
+    float r = rintf(t);
+    const bool safe = fabsf(t - r) < 0.5f - (fabsf(t) * 9.5367431640625e-7f + 9.5367431640625e-7f);
+    if (!safe) r = (float)rint((double)v / s);
+    return fminf(fmaxf(r + z, 0.f), maxq);
+}
+
+// VEC = 16 / sizeof(T) elements per lane and load; vec == 0: element-wise (any d, any alignment).  The first NCH chunks of
+// 64 * VEC elements of a row stay in registers between the two passes, further ones are read again (L2 hits).
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void act_fakequant_kernel(const T* __restrict__ in, T* __restrict__ out, long long ntok, int d, float maxq,
+                                                            int vec) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    union Pack { f4 raw; T e[VEC]; };
     const int lane = threadIdx.x & 63;
     const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= ntok) return;
     const T* x = in + t * d; T* y = out + t * d;
     float lo = 0.f, hi = 0.f;
-    for (int c = lane; c < d; c += 64) { const float v = (float)x[c]; lo = fminf(lo, v); hi = fmaxf(hi, v); }
+    Pack buf[NCH];
+    if (vec) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int k = (c * 64 + lane) * VEC;
+            if (k < d) {
+                buf[c].raw = __builtin_nontemporal_load((const f4*)(x + k));
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) { const float v = (float)buf[c].e[i]; lo = fminf(lo, v); hi = fmaxf(hi, v); }
+            }
+        }
+        for (int k = (NCH * 64 + lane) * VEC; k < d; k += 64 * VEC) {
+            Pack pk; pk.raw = *(const f4*)(x + k);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { const float v = (float)pk.e[i]; lo = fminf(lo, v); hi = fmaxf(hi, v); }
+        }
+    } else {
+        for (int c = lane; c < d; c += 64) { const float v = (float)x[c]; lo = fminf(lo, v); hi = fmaxf(hi, v); }
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) { lo = fminf(lo, __shfl_xor(lo, o, 64)); hi = fmaxf(hi, __shfl_xor(hi, o, 64)); }
     if (lo == hi) { lo = -1.f; hi = 1.f; }
-    // the decision (which level) is taken in fp64 from the exact input values
+    // the decision (which level) is that of fp64 arithmetic on the exact input values
     const double s = ((double)hi - (double)lo) / (double)maxq;
-    const double z = rint(-(double)lo / s);
-    for (int c = lane; c < d; c += 64) {
-        const double v = (double)(float)x[c];
-        const double q = fmin(fmax(rint(v / s) + z, 0.0), (double)maxq);
-        y[c] = (T)(float)(s * (q - z));
+    const double zd = rint(-(double)lo / s);
+    const float inv_s = (float)(1.0 / s), z = (float)zd;
+    if (vec) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int k = (c * 64 + lane) * VEC;
+            if (k < d) {
+                Pack o;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    const float q = act_level((float)buf[c].e[i], s, inv_s, z, maxq);
+                    o.e[i] = (T)(float)(s * ((double)q - zd));
+                }
+                __builtin_nontemporal_store(o.raw, (f4*)(y + k));
+            }
+        }
+        for (int k = (NCH * 64 + lane) * VEC; k < d; k += 64 * VEC) {
+            Pack pk, o; pk.raw = *(const f4*)(x + k);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                const float q = act_level((float)pk.e[i], s, inv_s, z, maxq);
+                o.e[i] = (T)(float)(s * ((double)q - zd));
+            }
+            __builtin_nontemporal_store(o.raw, (f4*)(y + k));
+        }
+    } else {
+        for (int c = lane; c < d; c += 64) {
+            const float q = act_level((float)x[c], s, inv_s, z, maxq);
+            y[c] = (T)(float)(s * ((double)q - zd));
+        }
     }
 }
 
@@ -876,10 +936,15 @@ extern "C" int tboa_act_fakequant(tboa_ctx* ctx, int64_t n_tokens, int d, int bi
     if (n_tokens == 0) return 0;
     const float maxq = (float)((1 << bits) - 1);
     const unsigned grid = (unsigned)((n_tokens + 3) / 4);
+    const int esz = dtype == TBOA_F32 ? 4 : 2;
+    // whole 16-byte pieces per lane when every row starts on a 16-byte boundary (in place is fine: a wavefront reads a piece before it writes it)
+    const int vec = (((uintptr_t)X_in | (uintptr_t)X_out) & 15) == 0 && ((long long)d * esz) % 16 == 0;
     if (dtype == TBOA_F32)
-        hipLaunchKernelGGL(act_fakequant_kernel<float>, dim3(grid), dim3(256), 0, ctx->stream, (const float*)X_in, (float*)X_out, (long long)n_tokens, d, maxq);
+        hipLaunchKernelGGL((act_fakequant_kernel<float, 8>), dim3(grid), dim3(256), 0, ctx->stream, (const float*)X_in, (float*)X_out, (long long)n_tokens, d,
+                           maxq, vec);
     else if (dtype == TBOA_BF16)
-        hipLaunchKernelGGL(act_fakequant_kernel<bf16>, dim3(grid), dim3(256), 0, ctx->stream, (const bf16*)X_in, (bf16*)X_out, (long long)n_tokens, d, maxq);
+        hipLaunchKernelGGL((act_fakequant_kernel<bf16, 8>), dim3(grid), dim3(256), 0, ctx->stream, (const bf16*)X_in, (bf16*)X_out, (long long)n_tokens, d,
+                           maxq, vec);
     else return tboa_fail(ctx, TBOA_EINVAL, "act_fakequant: dtype must be fp32 or bf16");
     TB_KERNEL_CHECK(ctx);
     return 0;

@@ -178,14 +178,30 @@ def test_out_proj_bf16_integer_form_weights(ctx, lib, bits):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-def test_act_fakequant(ctx, dtype):
-    g = torch.Generator(device="cuda"); g.manual_seed(5)
-    X = (torch.randn(37, 200, generator=g, device="cuda") * torch.rand(37, 1, generator=g, device="cuda") * 4).to(dtype)
+@pytest.mark.parametrize("d", [200, 203, 4096, 8200])
+def test_act_fakequant(ctx, dtype, d):
+    """Rows of whole 16-byte pieces (200), element-wise rows (203), rows that fill the kernel's registers (4096) and longer
+    ones (8200); a zero row; rows whose elements sit exactly on and next to the half-way points between two levels
+    (min 0, max 15, scale 1: k + 1/2 rounds to even in fp64, its neighbours do not tie); in place."""
+    g = torch.Generator(device="cuda"); g.manual_seed(5 + d)
+    X = (torch.randn(37, d, generator=g, device="cuda") * torch.rand(37, 1, generator=g, device="cuda") * 4).to(dtype)
     X[5] = 0
+    k = torch.arange(d, device="cuda") % 15
+    X[7] = (k + 0.5).to(dtype); X[7, 0] = 0; X[7, 1] = 15
+    X[8] = (k + 0.5 + 2.0 ** -7).to(dtype); X[8, 0] = 0; X[8, 1] = 15
+    X[9] = (k + 0.5 - 2.0 ** -7).to(dtype); X[9, 0] = 0; X[9, 1] = 15
+    X[10] = -X[7]
     got = ctx.act_fakequant(X, 4)
     want = O.act_fakequant_per_token(np64(X), 4)
     want_t = torch.tensor(want).to(dtype).float().numpy()          # the output is stored in the input's type
     assert np.array_equal(got.float().cpu().numpy(), want_t)
+    assert np.array_equal(want[7, 2:17], np.array([2, 4, 4, 6, 6, 8, 8, 10, 10, 12, 12, 14, 14, 0, 2], dtype=np.float64))   # ties to even
+    Y = X.clone()
+    ctx.act_fakequant(Y, 4, out=Y)
+    assert torch.equal(Y, got)
+    got8 = ctx.act_fakequant(X, 8)
+    want8 = torch.tensor(O.act_fakequant_per_token(np64(X), 8)).to(dtype).float().numpy()
+    assert np.array_equal(got8.float().cpu().numpy(), want8)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
