@@ -802,10 +802,11 @@ int swiglu_forward_bf16(tboa_ctx* ctx, long long T, int d, int dff, const bf16* 
 // The level of an element is rint(v / s) + z with the quotient in fp64.  fl32(v * fl32(1/s)) is within 2^-23 (relative) of that
 // quotient, so wherever it lies further than 2^-20 |t| from a half-integer both round to the same integer; only the
 // elements inside that margin (and non-finite products) take the fp64 division.
+// (inv_s == 0 marks a reciprocal that fp32 cannot hold as a normal number: every element then takes the division.)
 __device__ __forceinline__ float act_level(float v, double s, float inv_s, float z, float maxq) {
     const float t = v * inv_s;
     float r = rintf(t);
-    const bool safe = fabsf(t - r) < 0.5f - (fabsf(t) * 9.5367431640625e-7f + 9.5367431640625e-7f);
+    const bool safe = inv_s != 0.f && fabsf(t - r) < 0.5f - (fabsf(t) * 9.5367431640625e-7f + 9.5367431640625e-7f);
     if (!safe) r = (float)rint((double)v / s);
     return fminf(fmaxf(r + z, 0.f), maxq);
 }
@@ -848,7 +849,8 @@ __global__ __launch_bounds__(256) void act_fakequant_kernel(const T* __restrict_
     // the decision (which level) is that of fp64 arithmetic on the exact input values
     const double s = ((double)hi - (double)lo) / (double)maxq;
     const double zd = rint(-(double)lo / s);
-    const float inv_s = (float)(1.0 / s), z = (float)zd;
+    const double rs = 1.0 / s;
+    const float inv_s = (rs >= 1.17549435e-38 && rs <= 3.4e38) ? (float)rs : 0.f, z = (float)zd;
     if (vec) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {

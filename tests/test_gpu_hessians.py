@@ -199,6 +199,10 @@ def test_act_fakequant(ctx, dtype, d):
     Y = X.clone()
     ctx.act_fakequant(Y, 4, out=Y)
     assert torch.equal(Y, got)
+    big = ((torch.rand(3, d, generator=g, device="cuda") - 0.5) * 3e38).to(dtype)    # scale above 8.5e37: its reciprocal is subnormal in fp32
+    big[:, 0] = -1.5e38; big[:, 1] = 1.5e38
+    want2 = torch.tensor(O.act_fakequant_per_token(np64(big), 2)).to(dtype).float().numpy()
+    assert np.array_equal(ctx.act_fakequant(big, 2).float().cpu().numpy(), want2)
     got8 = ctx.act_fakequant(X, 8)
     want8 = torch.tensor(O.act_fakequant_per_token(np64(X), 8)).to(dtype).float().numpy()
     assert np.array_equal(got8.float().cpu().numpy(), want8)
