@@ -317,9 +317,24 @@ __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __r
     }
 }
 
-// out = scale * sum_s partial[s] (fp64 accumulation); lower: only r >= c is read, the result is mirrored
-__global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits, int n, double scale, int lower, float* __restrict__ out) {
+// out = scale * sum_s partial[s] (fp64 accumulation); lower: only r >= c is read, the result is mirrored.
+// vec (not with lower; n * n a multiple of 4, 16-byte aligned buffers): four consecutive elements per thread, the partial
+// sums read once with 16-byte streaming loads.
+__global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits, int n, double scale, int lower, float* __restrict__ out, int vec) {
     const long long nn = (long long)n * n;
+    if (vec) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < nn / 4; i += (long long)gridDim.x * blockDim.x) {
+            double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+            for (int s = 0; s < splits; ++s) {
+                const f4 v = __builtin_nontemporal_load((const f4*)(part + s * nn) + i);
+                a0 += (double)v.x; a1 += (double)v.y; a2 += (double)v.z; a3 += (double)v.w;
+            }
+            const f4 o = {(float)(scale * a0), (float)(scale * a1), (float)(scale * a2), (float)(scale * a3)};
+            ((f4*)out)[i] = o;
+        }
+        return;
+    }
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < nn; i += (long long)gridDim.x * blockDim.x) {
         const int r = (int)(i / n), c = (int)(i % n);
         const long long src = (lower && c > r) ? (long long)c * n + r : i;
@@ -330,9 +345,11 @@ __global__ void splitk_reduce_kernel(const float* __restrict__ part, int splits,
 }
 
 // The same for a symmetric result whose partial sums hold the lower tiles only: tile pair (tr >= tc) per workgroup, the
-// lower tile summed from coalesced reads and written with its mirror image through LDS
+// lower tile summed from coalesced reads and written with its mirror image through LDS.  vec (n a multiple of 64, 16-byte
+// aligned buffers): off the diagonal a thread sums four consecutive columns from 16-byte streaming loads and writes four
+// consecutive elements of a mirrored row.
 __global__ __launch_bounds__(256) void splitk_reduce_lower_kernel(const float* __restrict__ part, int splits, int n, double scale,
-                                                                  float* __restrict__ out) {
+                                                                  float* __restrict__ out, int vec) {
     __shared__ float t[64][65];
     const long long nn = (long long)n * n;
     int tr = (int)((sqrtf(8.f * (float)blockIdx.x + 1.f) - 1.f) * 0.5f);
@@ -340,6 +357,28 @@ __global__ __launch_bounds__(256) void splitk_reduce_lower_kernel(const float* _
     while ((long long)tr * (tr + 1) / 2 > (long long)blockIdx.x) --tr;
     const int tc = (int)(blockIdx.x - (long long)tr * (tr + 1) / 2);
     const int r0 = tr * 64, c0 = tc * 64;
+    if (vec && tr != tc) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        for (int i = threadIdx.x; i < 64 * 16; i += 256) {
+            const int r = i >> 4, c = (i & 15) * 4;
+            const long long src = (long long)(r0 + r) * n + c0 + c;
+            double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+            for (int s = 0; s < splits; ++s) {
+                const f4 v = __builtin_nontemporal_load((const f4*)(part + s * nn + src));
+                a0 += (double)v.x; a1 += (double)v.y; a2 += (double)v.z; a3 += (double)v.w;
+            }
+            const f4 o = {(float)(scale * a0), (float)(scale * a1), (float)(scale * a2), (float)(scale * a3)};
+            *(f4*)(out + src) = o;
+            t[r][c] = o.x; t[r][c + 1] = o.y; t[r][c + 2] = o.z; t[r][c + 3] = o.w;
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < 64 * 16; i += 256) {
+            const int c = i >> 4, r = (i & 15) * 4;
+            const f4 o = {t[r][c], t[r + 1][c], t[r + 2][c], t[r + 3][c]};
+            *(f4*)(out + (long long)(c0 + c) * n + r0 + r) = o;
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < 64 * 64; i += 256) {
         const int r = i >> 6, c = i & 63;
         float v = 0.f;
@@ -420,11 +459,14 @@ int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_l
     if (lower) TB_TRY(launch_fill_f32(ctx, part, (int64_t)splits * n * n, 0.f));
     TB_TRY(gemm_bf16_nt(ctx, g));
     if (A_lo) { g.A = A_lo; g.accumulate = 1; TB_TRY(gemm_bf16_nt(ctx, g)); }
+    const bool aligned16 = (((uintptr_t)part | (uintptr_t)out) & 15) == 0;
+    const int vec = (!lower && aligned16 && ((long long)n * n) % 4 == 0) ? 1 : 0;
     if (lower) {
         const long long nt = (n + 63) / 64;
-        hipLaunchKernelGGL(splitk_reduce_lower_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(256), 0, ctx->stream, part, splits, n, scale, out);
+        hipLaunchKernelGGL(splitk_reduce_lower_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(256), 0, ctx->stream, part, splits, n, scale, out,
+                           (n % 64 == 0 && aligned16) ? 1 : 0);
     } else
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(g1((long long)n * n)), dim3(256), 0, ctx->stream, part, splits, n, scale, lower, out);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(g1((long long)n * n / (vec ? 4 : 1))), dim3(256), 0, ctx->stream, part, splits, n, scale, lower, out, vec);
     TB_HIP(ctx, hipGetLastError());
     return 0;
 }
