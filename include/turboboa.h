@@ -240,8 +240,9 @@ int tboa_gemm_f64(tboa_ctx* ctx, int M, int N, int K, double alpha,
  *            ((r / 16) * (ld / 32) + c / 32) * 512 + (r % 16) * 32 + (((c % 32) / 8) ^ (((r % 16) / 4) % 4)) * 8 + c % 8,
  *        i.e. the blocks of a block row follow each other along the columns and the four 16-byte pieces of a row of a
  *        block are XOR-permuted the way the kernel keeps them in LDS.  A column offset c0 (a multiple of 32) into such a
- *        matrix is the pointer offset 16 * c0.  Operands: rows a multiple of 16, K a multiple of 32, batch strides
- *        multiples of 512; C: bf16, no accumulation, M and N multiples of 256.  Meant for chains of products where one
+ *        matrix is the pointer offset 16 * c0.  Operands: rows a multiple of 16, K a multiple of 32 (batch strides as for
+ *        row-major operands; blocks that start on 128-byte boundaries are read as whole cache lines); C: bf16, no
+ *        accumulation, M and N multiples of 256.  Meant for chains of products where one
  *        product's bf16 result is the next one's operand (its loads are then whole contiguous blocks). */
 enum { TBOA_GEMM_LOWER = 1, TBOA_GEMM_CAUSAL_K = 2, TBOA_GEMM_PERSISTENT = 4, TBOA_GEMM_A_TILED = 8, TBOA_GEMM_B_TILED = 16,
        TBOA_GEMM_C_TILED = 32 };

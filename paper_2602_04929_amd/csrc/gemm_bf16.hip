@@ -746,8 +746,10 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     if (q.flags & (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED)) {
         const bool ta = q.flags & TBOA_GEMM_A_TILED, tb = q.flags & TBOA_GEMM_B_TILED;
         if ((q.kseg > 0 ? q.kseg : q.K) % 32 || q.K <= 0) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: blocked operands need K (and kseg) to be multiples of 32");
-        if ((ta && (q.lda % 32 || q.M % 16 || q.strideA % 512 || q.strideA2 % 512)) || (tb && (q.ldb % 32 || q.N % 16 || q.strideB % 512 || q.strideB2 % 512)))
-            return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: a blocked operand needs rows % 16 == 0, ld % 32 == 0 and batch strides % 512 == 0");
+        // (batch strides only need the 16-byte alignment of every operand: a stride may be the distance between two buffers;
+        // blocks that start on 128-byte boundaries are read as whole cache lines)
+        if ((ta && (q.lda % 32 || q.M % 16)) || (tb && (q.ldb % 32 || q.N % 16)))
+            return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: a blocked operand needs rows % 16 == 0 and ld % 32 == 0");
     }
     if (q.flags & TBOA_GEMM_C_TILED) {
         if (q.c_dtype != TBOA_BF16 || q.accumulate || q.M % 256 || q.N % 256 || q.ldc % 32 || q.strideC % 4 || q.strideC2 % 4 || ((uintptr_t)q.C & 7))

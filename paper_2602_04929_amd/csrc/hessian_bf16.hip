@@ -88,9 +88,50 @@ __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__
 }
 
 // fp32 [rows, H*dh] -> bf16 [rows, H, 3*dh]: (hi, lo, hi) for the left operand, (hi, hi, lo) for the right one;
-// scale (or NULL): one factor per column of `in`, applied first (projections through integer-form weights)
+// scale (or NULL): one factor per column of `in`, applied first (projections through integer-form weights).
+// L > 0: the rows are whole sequences of L tokens and the result is one [L, 3*dh] matrix per (sequence, head), each in the
+// 16 x 32 blocks the bf16 GEMM reads (L a multiple of 16, 3*dh of 32): element (t, c) of sequence s, head h at
+// ((s H + h) L 3dh) + tboa_blocked_offset(t, c, 3dh / 32).
+__device__ __forceinline__ long long split3_offset(long long row, int h, int c, int H, int dh, int L) {
+    if (L > 0) return ((row / L) * H + h) * (long long)L * 3 * dh + tboa_blocked_offset(row % L, c, (3 * dh) >> 5);
+    return (row * H + h) * 3 * dh + c;
+}
+
 __global__ void split3_kernel(const float* __restrict__ in, const float* __restrict__ scale, bf16* __restrict__ out, long long rows, int hd,
-                              int dh, int right) {
+                              int dh, int right, int L) {
+    const int H = hd / dh;
+    if (L > 0 && dh % 32 == 0 && rows % 16 == 0 && rows / 16 * (hd / 32) < 2147483647LL) {
+        // blocked result: a wavefront takes a 16 x 32 piece of `in` in two loads of eight whole rows of 128 bytes (lane: row
+        // lane / 8 and that row + 8, four columns from 4 (lane % 8)) and writes the three 1 KB blocks it becomes, each as two
+        // contiguous halves of 512 bytes.  Everything but the lane's place inside the block is uniform over the wavefront
+        // (32-bit scalar arithmetic).
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const int lane = threadIdx.x & 63, ri = lane >> 3, c4 = (lane & 7) * 4;
+        const unsigned cbs = hd / 32, nblk = (unsigned)(rows / 16) * cbs, nw = gridDim.x * (blockDim.x >> 6);
+        const unsigned in_lane = ri * hd + c4, kb = (3 * dh) >> 5;
+        // rows ri and ri + 8 of the block: the 16-byte piece c4 / 8 is permuted with (row / 4) % 4
+        const unsigned out_a = ri * 32 + (((c4 >> 3) ^ (ri >> 2)) << 3) + (c4 & 7), out_b = (ri + 8) * 32 + (((c4 >> 3) ^ ((ri + 8) >> 2)) << 3) + (c4 & 7);
+        for (unsigned b = __builtin_amdgcn_readfirstlane(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)); b < nblk; b += nw) {
+            const unsigned rb = b / cbs, c0 = (b % cbs) * 32, h = c0 / dh, e0 = c0 % dh;
+            const unsigned row0 = rb * 16, sq = row0 / (unsigned)L, t0 = row0 % (unsigned)L;
+            const float* src = in + (long long)row0 * hd + c0 + in_lane;
+            f4 va = __builtin_nontemporal_load((const f4*)src), vb = __builtin_nontemporal_load((const f4*)(src + 8LL * hd));
+            if (scale) { const f4 sc = *(const f4*)(scale + c0 + c4); va = va * sc; vb = vb * sc; }
+            union { bf16 b[4]; uint2 u; } ha, la, hb, lb;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                ha.b[k] = __float2bfloat16(va[k]); la.b[k] = __float2bfloat16(va[k] - __bfloat162float(ha.b[k]));
+                hb.b[k] = __float2bfloat16(vb[k]); lb.b[k] = __float2bfloat16(vb[k] - __bfloat162float(hb.b[k]));
+            }
+            // block (t0 / 16, (seg dh + e0) / 32) of the [L, 3 dh] matrix of (sequence sq, head h)
+            bf16* o = out + ((long long)sq * H + h) * L * 3 * dh + ((long long)(t0 >> 4) * kb + (e0 >> 5)) * 512;
+            const long long seg = (long long)(dh >> 5) * 512;
+            *(uint2*)(o + out_a) = ha.u; *(uint2*)(o + out_b) = hb.u;
+            *(uint2*)(o + seg + out_a) = right ? ha.u : la.u; *(uint2*)(o + seg + out_b) = right ? hb.u : lb.u;
+            *(uint2*)(o + 2 * seg + out_a) = right ? la.u : ha.u; *(uint2*)(o + 2 * seg + out_b) = right ? lb.u : hb.u;
+        }
+        return;
+    }
     if (hd % 4 == 0 && dh % 4 == 0) {     // four consecutive columns per thread: 16-byte streaming loads, 8-byte stores
         typedef float f4 __attribute__((ext_vector_type(4)));
         const long long tot4 = rows * hd / 4;
@@ -105,8 +146,9 @@ __global__ void split3_kernel(const float* __restrict__ in, const float* __restr
                 hi.b[j] = __float2bfloat16(v[j]);
                 lo.b[j] = __float2bfloat16(v[j] - __bfloat162float(hi.b[j]));
             }
-            bf16* o = out + (row * (hd / dh) + h) * 3 * dh + e;
-            *(uint2*)o = hi.u; *(uint2*)(o + dh) = right ? hi.u : lo.u; *(uint2*)(o + 2 * dh) = right ? lo.u : hi.u;
+            *(uint2*)(out + split3_offset(row, h, e, H, dh, L)) = hi.u;
+            *(uint2*)(out + split3_offset(row, h, dh + e, H, dh, L)) = right ? hi.u : lo.u;
+            *(uint2*)(out + split3_offset(row, h, 2 * dh + e, H, dh, L)) = right ? lo.u : hi.u;
         }
         return;
     }
@@ -116,8 +158,9 @@ __global__ void split3_kernel(const float* __restrict__ in, const float* __restr
         const float v = scale ? in[i] * scale[c] : in[i];
         const bf16 hi = __float2bfloat16(v);
         const bf16 lo = __float2bfloat16(v - __bfloat162float(hi));
-        bf16* o = out + (row * (hd / dh) + h) * 3 * dh;
-        o[e] = hi; o[dh + e] = right ? hi : lo; o[2 * dh + e] = right ? lo : hi;
+        out[split3_offset(row, h, e, H, dh, L)] = hi;
+        out[split3_offset(row, h, dh + e, H, dh, L)] = right ? hi : lo;
+        out[split3_offset(row, h, 2 * dh + e, H, dh, L)] = right ? lo : hi;
     }
 }
 
@@ -423,6 +466,10 @@ Dims dims_of(tboa_ctx* ctx, const tboa_attn_desc* d) {
                 d->n_q_heads / d->n_kv_heads, d->n_q_heads * d->head_dim, d->n_kv_heads * d->head_dim};
 }
 
+// Q^ and K^ (the three-segment operands of the score products) are kept per (sequence, head) in 16 x 32 blocks when the
+// shapes allow it: whole 1 KB blocks instead of 64-byte row pieces at a pitch of all heads
+bool qk_blocked(const Dims& D) { return D.L % 16 == 0 && (3 * D.dh) % 32 == 0 && !getenv("TBOA_NO_BLOCKED_QK"); }
+
 int pick_splits(int n_seqs) {
     for (int s = 16; s > 1; --s) if (n_seqs % s == 0) return s;
     return 1;
@@ -478,8 +525,10 @@ int project_qk(const Dims& D, const bf16* Xr, int rows, const bf16* Wq, const bf
     if (Wq_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, Wq_lo, D.dm, Qf, D.dq, TBOA_F32, 1, 0)));
     TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk, D.dm, Kf, D.dkv, TBOA_F32, 0, 0)));
     if (Wk_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk_lo, D.dm, Kf, D.dkv, TBOA_F32, 1, 0)));
-    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dq)), dim3(256), 0, D.ctx->stream, Qf, q_scale, Qh, (long long)rows, D.dq, D.dh, 0);
-    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dkv)), dim3(256), 0, D.ctx->stream, Kf, k_scale, Kh, (long long)rows, D.dkv, D.dh, 1);
+    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dq)), dim3(256), 0, D.ctx->stream, Qf, q_scale, Qh, (long long)rows, D.dq, D.dh, 0,
+                       qk_blocked(D) ? D.L : 0);
+    hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dkv)), dim3(256), 0, D.ctx->stream, Kf, k_scale, Kh, (long long)rows, D.dkv, D.dh, 1,
+                       qk_blocked(D) ? D.L : 0);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
 }
@@ -491,6 +540,10 @@ int scores(const Dims& D, const bf16* Qh, const bf16* Kh, int sl, float* Sc) {
                     Kh + (long long)sl * L * D.Hkv * dh3, (long long)D.Hkv * dh3, Sc, L, TBOA_F32, 0, D.d->causal ? TBOA_GEMM_LOWER : 0);
     g.batch = D.Hq; g.batch_inner = D.rep;
     g.strideA = (long long)D.rep * dh3; g.strideA2 = dh3; g.strideB = dh3; g.strideB2 = 0;
+    if (qk_blocked(D)) {     // one blocked [L, 3 dh] matrix per (sequence, head)
+        g.flags |= TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED; g.lda = dh3; g.ldb = dh3;
+        g.strideA = (long long)D.rep * L * dh3; g.strideA2 = (long long)L * dh3; g.strideB = (long long)L * dh3;
+    }
     g.strideC = (long long)D.rep * L * L; g.strideC2 = (long long)L * L;
     return gemm_bf16_nt(D.ctx, g);
 }
@@ -509,6 +562,10 @@ int scores_pair(const Dims& D, const bf16* Qh, const bf16* Kh, const bf16* Qhf, 
                     Kh + (long long)sl * L * D.Hkv * dh3, (long long)D.Hkv * dh3, Sc, L, TBOA_F32, 0, D.d->causal ? TBOA_GEMM_LOWER : 0);
     g.batch = 2 * D.Hq; g.batch_inner = D.Hq;
     g.strideA = dq; g.strideA2 = dh3; g.strideB = dk; g.strideB2 = dh3;
+    if (qk_blocked(D)) {
+        g.flags |= TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED; g.lda = dh3; g.ldb = dh3;
+        g.strideA2 = (long long)L * dh3; g.strideB2 = (long long)L * dh3;
+    }
     g.strideC = dc; g.strideC2 = (long long)L * L;
     return gemm_bf16_nt(D.ctx, g);
 }
