@@ -302,9 +302,12 @@ __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __r
                                                                 int blocked) {
     const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= L) return;
-    const long long so = ((long long)blockIdx.y * L + t) * L;
+    // heads from the last to the first: the score product wrote them in ascending order, so the last ones are the part of the
+    // scores the memory-side cache still holds (measured: 175 -> 169 us on 32 heads x 2048^2)
+    const int hy = gridDim.y - 1 - blockIdx.y;
+    const long long so = ((long long)hy * L + t) * L;
     const float* s = S + so; const float* s2 = S2 ? S2 + so : nullptr;
-    bf16* p = P + blockIdx.y * head_stride + (blocked ? 0 : (long long)t * ldp);
+    bf16* p = P + hy * head_stride + (blocked ? 0 : (long long)t * ldp);
     const int kend = causal ? t + 1 : L;
     int kz = ((kend + 255) / 256) * 256; if (kz > L) kz = L;
     float v[NCH][4], w[NCH][4];
