@@ -9,17 +9,19 @@ Notation follows the paper.  Activations are stored token-major, ``Xr[t, :]`` is
 one token (the paper's ``X`` is ``Xr.T``), so ``H_in = X X^T = Xr^T Xr``.
 The paper's N (out-channels quantized jointly) is ``block`` here.
 
-Pins (see tests/test_oracle_*.py): trace/Kronecker identities for the Hessians,
+Pins (see tests/test_oracle_pins.py): trace/Kronecker identities for the Hessians,
 textbook properties of U = Chol(H^-1)^T, brute-force constrained least squares
 for Prop. 3.1 and Prop. 3.2, an independently written row-at-a-time BoA for
-block=1, textbook OBS elimination for the in-channel sweep with R = 0, the
-explicit quadratic in s for Prop. 3.3, exhaustive evaluation for the grid search.
+block=1, textbook OBS elimination for the in-channel sweep with R = 0, every step
+of the sweep with R != 0 as the least-squares problem it solves (explicit X and
+X - X~, no factor of H), Algorithm 1 with R != 0 and per-head Hessians rebuilt from
+those pieces, the explicit quadratic in s for Prop. 3.3, exhaustive evaluation for
+the grid search, hand-computed rows for the activation quantizer.
 
 parity unpinned:
-  * the in-channel sweep with R != 0 (Algorithm 3's P-term) is the literal
-    algorithm; only structural properties are checked, no independent closed form;
   * the candidate list of the grid search and the group-wise (row, group)
-    extension are readings of ours, the paper gives only the objective.
+    extension are readings of ours, the paper gives only the objective; they are
+    checked against exhaustive loops over the same list only.
 """
 from __future__ import annotations
 
@@ -397,7 +399,8 @@ def quantize_layer(W, H_in, H_out, R, n_heads, bits, block, group=0, cd_iters=1,
     W [d_out, d_in], d_out = n_heads * d_h; H_in [d_in, d_in] or [n_heads, d_in, d_in];
     H_out [n_heads, d_h, d_h] or None (identity: no out-channel coupling, the output-projection /
     GPTQ case); R like H_in (already alpha-scaled) or None.
-    Returns dict(codes, scales, zeros, W_deq, loss, loss_quad, loss_cross, loss_per_head).
+    Returns dict(codes, scales, zeros, W_deq, loss, loss_quad, loss_cross, loss_per_head [n_heads],
+    loss_per_head_terms [n_heads, 2] = (quad, cross) of every head).
     Every Hessian is damped once at entry and the damped matrices are used throughout."""
     W = np.asarray(W, F64)
     d_out, n = W.shape
@@ -453,4 +456,4 @@ def quantize_layer(W, H_in, H_out, R, n_heads, bits, block, group=0, cd_iters=1,
     quad = loss_per_head[:, 0].sum(); cross = loss_per_head[:, 1].sum()
     return dict(codes=codes.astype(np.uint8), scales=scales, zeros=zeros, W_deq=Qfull,
                 loss=quad + cross, loss_quad=quad, loss_cross=cross,
-                loss_per_head=loss_per_head.sum(axis=1))
+                loss_per_head=loss_per_head.sum(axis=1), loss_per_head_terms=loss_per_head)

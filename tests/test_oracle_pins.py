@@ -691,3 +691,133 @@ def test_per_head_hin_and_groupwise(layer_case):
     # group = d_in is the per-row path
     gfull = O.quantize_layer(c["W"], c["Hin"], c["Hout"], c["R"], c["n_heads"], bits=3, block=4, group=24)
     assert np.array_equal(gfull["codes"], a["codes"]) and np.allclose(gfull["scales"], a["scales"], rtol=1e-12)
+
+
+# ---------------------------------------------------------------- Algorithm 3 with R != 0, and Algorithm 1 around it,
+# re-derived from explicit activations by least squares (no Cholesky factor, no P, no S anywhere on this route)
+
+def lstsq_sweep_row(w, X, dX, s, z, maxq):
+    """One row through the in-channel sweep, every step solved as the least-squares problem it stands for.
+
+    X, dX [n, L] are the paper's X and X - X~ (channels x tokens).  Entering step j the row holds w; channel j is
+    rounded to Q_j, and the channels after j move by the delta_F that minimises
+        || (Q_j - w_j) x_j + delta_F X_F + w_j dx_j ||^2
+    (x_j, dx_j: rows j of X and dX; F = the channels after j): the rounding error of channel j and the deviation that
+    channel j carries (its value on entry to the step times dx_j) are absorbed by the channels not yet fixed.  Solving
+    the normal equations with H_FF^-1 = U_FF^T U_FF gives the update line of Algorithm 3, e_j U[j, F] + w_j P[j, F]."""
+    w = np.array(w, float); n = len(w)
+    codes = np.zeros(n); Q = np.zeros(n)
+    for j in range(n):
+        wj = w[j]
+        q = min(max(np.rint(wj / s) + z, 0.0), maxq)
+        codes[j] = q; Q[j] = s * (q - z)
+        if j + 1 < n:
+            target = -((Q[j] - wj) * X[j] + wj * dX[j])
+            w[j + 1:] += np.linalg.lstsq(X[j + 1:].T, target, rcond=None)[0]
+    return codes, Q
+
+
+def test_sweep_with_R_is_stepwise_least_squares():
+    n, r_, L = 9, 5, 40
+    r = rng(61)
+    X = r.standard_normal((n, L)); X[2] *= 4.0
+    dX = 0.3 * r.standard_normal((n, L)) + 0.2 * X          # deviations correlated with the input: a sizeable R
+    H, R = X @ X.T, dX @ X.T
+    U = O.chol_inv_upper(H)
+    P = O.sweep_P(R, U)
+    Wr = r.standard_normal((r_, n))
+    for bits in (2, 4):
+        maxq = 2 ** bits - 1
+        s, z = O.grid_search(Wr, H, bits)
+        Q, codes = O.gptaq_sweep(Wr, U, P, s[:, None].copy(), z[:, None].copy(), bits)
+        flips_without_P = 0
+        for i in range(r_):
+            c_ls, Q_ls = lstsq_sweep_row(Wr[i], X, dX, s[i], z[i], maxq)
+            assert np.array_equal(codes[i], c_ls), (bits, i)
+            assert np.allclose(Q[i], Q_ls, rtol=1e-12)
+            flips_without_P += int(np.sum(lstsq_sweep_row(Wr[i], X, 0 * dX, s[i], z[i], maxq)[0] != c_ls))
+        assert flips_without_P > 0          # the deviation term matters on this case: the comparison above can see it
+
+
+def independent_turboboa(W, Xs, dXs, Gs, n_heads, bits, block):
+    """Algorithm 1 (no damping, no scale refinement) from explicit G_h, X_h, dX_h: the grid of a step by an exhaustive
+    loop, the in-channel sweep as step-wise least squares, the compensation of the remaining out-channels as the dense
+    constrained minimiser of || G dW X + G[:, B] W_B dX ||_F^2 (eq. 7) over the rows that are still free."""
+    d_out, n = W.shape
+    dh = d_out // n_heads
+    maxq = 2 ** bits - 1
+    codes = np.zeros((d_out, n)); scales = np.zeros(d_out)
+    for h in range(n_heads):
+        X, dX, G = Xs[h], dXs[h], Gs[h]
+        Hin, Hout, R = X @ X.T, G.T @ G, dX @ X.T
+        Wt = W[h * dh:(h + 1) * dh].copy()
+        for i0 in range(0, dh, block):
+            i1 = min(i0 + block, dh)
+            Wb = Wt[i0:i1].copy(); Qb = np.zeros_like(Wb)
+            for a in range(i1 - i0):
+                _, s, z = exhaustive_grid(Wb[a], Hin, bits)
+                codes[h * dh + i0 + a], Qb[a] = lstsq_sweep_row(Wb[a], X, dX, s, z, maxq)
+                scales[h * dh + i0 + a] = s
+            if i1 < dh:
+                Ht = Hout[i0:, i0:]                         # rows before i0 are fixed and already accounted for
+                Wt[i1:] += brute_force_remaining_rows(Hin, Ht, Qb - Wb, lin=Ht[:, :i1 - i0] @ Wb @ R)
+    return codes, scales
+
+
+@pytest.fixture(scope="module")
+def explicit_case():
+    r = rng(90)
+    n_heads, dh, n, L, m = 2, 6, 5, 30, 9
+    Xs = [r.standard_normal((n, L)) * np.array([[1.0], [3.0], [1.0], [0.5], [1.0]]) for _ in range(n_heads)]
+    dXs = [0.25 * r.standard_normal((n, L)) + 0.15 * X for X in Xs]
+    Gs = [r.standard_normal((m, dh)) + 0.8 * r.standard_normal((m, 1)) for _ in range(n_heads)]
+    W = r.standard_normal((n_heads * dh, n))
+    return dict(W=W, Xs=Xs, dXs=dXs, Gs=Gs, n_heads=n_heads, dh=dh, n=n)
+
+
+@pytest.mark.parametrize("block", [1, 2, 4])
+def test_algorithm1_with_R_equals_least_squares_reconstruction(explicit_case, block):
+    """The deviation term of Prop. 3.2 inside the loop of Algorithm 1 (and the per-head H_in, R of the W_V row of
+    Table 1): every head has activations of its own here."""
+    c = explicit_case
+    Hin = np.stack([X @ X.T for X in c["Xs"]]); R = np.stack([dX @ X.T for dX, X in zip(c["dXs"], c["Xs"])])
+    Hout = np.stack([G.T @ G for G in c["Gs"]])
+    for bits in (3, 4):
+        out = O.quantize_layer(c["W"], Hin, Hout, R, c["n_heads"], bits=bits, block=block, cd_iters=0, damp=0.0)
+        codes, scales = independent_turboboa(c["W"], c["Xs"], c["dXs"], c["Gs"], c["n_heads"], bits, block)
+        assert np.array_equal(out["codes"], codes.astype(np.uint8)), (bits, block)
+        assert np.allclose(out["scales"][:, 0], scales, rtol=1e-12)
+    # the case can tell the terms apart: without the deviation the codes of the later steps differ
+    zero = [0 * dX for dX in c["dXs"]]
+    other, _ = independent_turboboa(c["W"], c["Xs"], zero, c["Gs"], c["n_heads"], 4, block)
+    assert np.any(other != codes)
+
+
+def test_per_head_hessians_are_taken_per_head(explicit_case):
+    c = explicit_case
+    Hin = np.stack([X @ X.T for X in c["Xs"]]); R = np.stack([dX @ X.T for dX, X in zip(c["dXs"], c["Xs"])])
+    Hout = np.stack([G.T @ G for G in c["Gs"]])
+    dh = c["dh"]
+    both = O.quantize_layer(c["W"], Hin, Hout, R, 2, bits=3, block=2)
+    for h in range(2):
+        one = O.quantize_layer(c["W"][h * dh:(h + 1) * dh], Hin[h], Hout[h:h + 1], R[h], 1, bits=3, block=2)
+        rows = slice(h * dh, (h + 1) * dh)
+        assert np.array_equal(both["codes"][rows], one["codes"])
+        assert np.array_equal(both["scales"][rows], one["scales"]) and np.array_equal(both["W_deq"][rows], one["W_deq"])
+        assert np.isclose(both["loss_per_head"][h], one["loss"], rtol=1e-12)
+        assert np.allclose(both["loss_per_head_terms"][h], [one["loss_quad"], one["loss_cross"]], rtol=1e-12)
+    # the two heads' Hessians differ enough to matter: swapping them changes the result
+    swapped = O.quantize_layer(c["W"], Hin[::-1], Hout, R[::-1], 2, bits=3, block=2)
+    assert np.any(swapped["codes"] != both["codes"])
+
+
+def test_act_fakequant_hand_computed_rows():
+    """The per-token range always contains zero.  Rows worked out by hand, 2 bits (levels 0..3):
+    [1, 2, 3, 4]: range [0, 4], s = 4/3, z = 0, levels rint(0.75, 1.5, 2.25, 3) = 1, 2, 2, 3 (1.5 rounds to even);
+    [-4, -3, -2, -1]: range [-4, 0], s = 4/3, z = 3, levels rint(-3, -2.25, -1.5, -0.75) + 3 = 0, 1, 1, 2;
+    [-1, 0, 1, 2]: range [-1, 2], s = 1, z = 1, exact."""
+    Y = O.act_fakequant_per_token(np.array([[1.0, 2.0, 3.0, 4.0], [-4.0, -3.0, -2.0, -1.0], [-1.0, 0.0, 1.0, 2.0]]), 2)
+    t = 4.0 / 3.0
+    assert np.allclose(Y[0], [t, 2 * t, 2 * t, 3 * t], rtol=1e-15)
+    assert np.allclose(Y[1], [-3 * t, -2 * t, -2 * t, -t], rtol=1e-15)
+    assert np.array_equal(Y[2], [-1.0, 0.0, 1.0, 2.0])
