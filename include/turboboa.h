@@ -217,6 +217,17 @@ int tboa_dequant_gemv(tboa_ctx* ctx, int d_out, int d_in, int bits, int group, c
  * H fp32 [batch, n, n] (only read); damp as in tboa_layer_desc; U fp64 [batch, n, n] (strict lower part zero). */
 int tboa_chol_inv_upper(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* U);
 
+/* tboa_chol_inv_upper for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): same arguments, same kernels, same result, but the temporaries live in a static device
+ * array of 24 MiB that every GPU the library runs on holds until the process ends (its address is looked up by
+ * tboa_create), not in the context's workspace.  The call allocates and frees nothing.
+ * Limits: n <= 512 and batch * roundup64(n)^2 <= tboa_chol_inv_upper_static_max_elems() (= 2^20; e.g. 64 matrices of order
+ * 128, 4 of order 512); larger requests return TBOA_EINVAL with a message and touch nothing.
+ * All calls on one GPU share the array, which keeps the last call's contents (nothing in it needs to start at zero: every
+ * part is written before it is read): calls that overlap in time on the same GPU race, on whatever streams or contexts. */
+size_t tboa_chol_inv_upper_static_max_elems(void);
+int tboa_chol_inv_upper_static(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* U);
+
 /* C[b] = alpha * A[b] B[b] + beta * C[b] in fp64 on the fp64 matrix cores.
  * A(m,k) = A[m*sam + k*sak], B(k,n) = B[k*sbk + n*sbn]; in each pair one stride must be 1. C row-major, ldc. */
 int tboa_gemm_f64(tboa_ctx* ctx, int M, int N, int K, double alpha,

@@ -53,6 +53,8 @@ def _load():
         "tboa_gemm_f64": ([vp, i32, i32, i32, f64, vp, i64, i64, vp, i64, i64, f64, vp, i64, i32, i64, i64, i64], i32),
         "tboa_gemm_bf16_nt": ([vp, i32, i32, i32, f32, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i64, i64, i64], i32),
         "tboa_chol_inv_upper": ([vp, i32, i32, vp, f64, vp], i32),
+        "tboa_chol_inv_upper_static": ([vp, i32, i32, vp, f64, vp], i32),
+        "tboa_chol_inv_upper_static_max_elems": ([], C.c_size_t),
         "tboa_build_hessians": ([vp, C.POINTER(AttnDesc)] + [vp] * 14, i32),
         "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 11, i32),
         "tboa_fp_cache_bytes": ([C.POINTER(AttnDesc)], C.c_size_t),
@@ -175,12 +177,14 @@ class Context:
                                            _dtype_code(C_out), int(accumulate), flags, bs, A3.stride(0), B3.stride(0), M * N))
         return C_out
 
-    def chol_inv_upper(self, H, damp=0.0):
-        """U = Chol(H^-1)^T for fp32 H [n, n] or [batch, n, n]; returns fp64."""
+    def chol_inv_upper(self, H, damp=0.0, out=None, static=False):
+        """U = Chol(H^-1)^T for fp32 H [n, n] or [batch, n, n]; returns fp64 (written into `out` when given).
+        static: the entry point that allocates nothing (temporaries in the library's static device array; small sizes only)."""
         H3 = _dev(H if H.dim() == 3 else H[None], torch.float32)
-        U = torch.empty(H3.shape, dtype=torch.float64, device=H.device)
-        self._check(_lib.tboa_chol_inv_upper(self._h, H3.shape[1], H3.shape[0], _ptr(H3), damp, _ptr(U)))
-        return U if H.dim() == 3 else U[0]
+        U = torch.empty(H3.shape, dtype=torch.float64, device=H.device) if out is None else _dev(out, torch.float64)
+        fn = _lib.tboa_chol_inv_upper_static if static else _lib.tboa_chol_inv_upper
+        self._check(fn(self._h, H3.shape[1], H3.shape[0], _ptr(H3), damp, _ptr(U)))
+        return U if (H.dim() == 3 or out is not None) else U[0]
 
     # ---- the method
     def build_hessians(self, X, X_fp, Wq, Wk, Wv, Wo, n_q_heads, n_kv_heads, head_dim, alpha=0.0, causal=True,

@@ -31,6 +31,7 @@ extern "C" int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream) {
     int n = 0;
     if (hipGetDeviceCount(&n) != hipSuccess || hip_device < 0 || hip_device >= n) return TBOA_EINVAL;
     if (hipSetDevice(hip_device) != hipSuccess) return TBOA_EHIP;
+    if (chol_static_init(hip_device) != 0) return TBOA_EHIP;
     tboa_ctx* c = new tboa_ctx();
     c->device = hip_device;
     c->stream = (hipStream_t)hip_stream;

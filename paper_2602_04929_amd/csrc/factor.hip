@@ -67,6 +67,8 @@ __global__ __launch_bounds__(256) void diag_factor_kernel(double* __restrict__ H
     }
 }
 
+__global__ void clear_status_kernel(int* status) { if (threadIdx.x < 2) status[threadIdx.x] = 0; }
+
 __global__ void place_diag_inverse_kernel(double* __restrict__ U, int n, const double* __restrict__ dinv, int nblk) {
     const int b = blockIdx.y, blk = blockIdx.x;
     const int j0 = blk * NB, bs = min(NB, n - j0);
@@ -129,8 +131,10 @@ int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H, double* U, do
     int* status = ctx->d_status + status_slot;
     constexpr int OB = TB_FACT_OB, IPB = OB / NB;
     const int nblk = (n + NB - 1) / NB, nob = (n + OB - 1) / OB;
+    const int TL = chol_tmp_pitch(n);     // row pitch of tmp: a matrix of one outer block only ever holds NB columns there
     const long long nn = (long long)n * n, dstride = (long long)nblk * NB * NB;
-    TB_HIP(ctx, hipMemsetAsync(status, 0, 2 * sizeof(int), ctx->stream));
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, ctx->stream, status);
+    TB_KERNEL_CHECK(ctx);
     // ---- H = V V^T from the last column to the first
     for (int ob = nob - 1; ob >= 0; --ob) {
         const int J0 = ob * OB, J1 = (J0 + OB < n) ? J0 + OB : n;
@@ -181,15 +185,15 @@ int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H, double* U, do
             a.M = m; a.N = bs; a.K = m; a.alpha = 1.0; a.beta = 0.0;
             a.A = U + (long long)J0 * n + J0; a.sam = n; a.sak = 1; a.klo_m = 1;
             a.B = H + (long long)J0 * n + j0; a.sbk = n; a.sbn = 1;
-            a.C = tmp; a.ldc = OB;
-            a.batch = batch; a.strideA = nn; a.strideB = nn; a.strideC = (long long)n * OB;
+            a.C = tmp; a.ldc = TL;
+            a.batch = batch; a.strideA = nn; a.strideB = nn; a.strideC = (long long)n * TL;
             TB_TRY(gemm_f64(ctx, a));
             GemmF64 c{};   // U[J0:j0, blk] = -tmp Vinv_jj
             c.M = m; c.N = bs; c.K = bs; c.alpha = -1.0; c.beta = 0.0;
-            c.A = tmp; c.sam = OB; c.sak = 1;
+            c.A = tmp; c.sam = TL; c.sak = 1;
             c.B = dinv + (long long)blk * NB * NB; c.sbk = NB; c.sbn = 1;
             c.C = U + (long long)J0 * n + j0; c.ldc = n;
-            c.batch = batch; c.strideA = (long long)n * OB; c.strideB = dstride; c.strideC = nn;
+            c.batch = batch; c.strideA = (long long)n * TL; c.strideB = dstride; c.strideC = nn;
             TB_TRY(gemm_f64(ctx, c));
         }
         if (J0 > 0) {
@@ -198,15 +202,15 @@ int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H, double* U, do
             a.M = J0; a.N = w; a.K = J0; a.alpha = 1.0; a.beta = 0.0;
             a.A = U; a.sam = n; a.sak = 1; a.klo_m = 1;
             a.B = H + J0; a.sbk = n; a.sbn = 1;
-            a.C = tmp; a.ldc = OB;
-            a.batch = batch; a.strideA = nn; a.strideB = nn; a.strideC = (long long)n * OB;
+            a.C = tmp; a.ldc = TL;
+            a.batch = batch; a.strideA = nn; a.strideB = nn; a.strideC = (long long)n * TL;
             TB_TRY(gemm_f64(ctx, a));
             GemmF64 c{};   // U[0:J0, ob] = -tmp U[ob, ob]   (U[ob, ob] upper: k <= column)
             c.M = J0; c.N = w; c.K = w; c.alpha = -1.0; c.beta = 0.0;
-            c.A = tmp; c.sam = OB; c.sak = 1;
+            c.A = tmp; c.sam = TL; c.sak = 1;
             c.B = U + (long long)J0 * n + J0; c.sbk = n; c.sbn = 1; c.khi_n = 1;
             c.C = U + J0; c.ldc = n;
-            c.batch = batch; c.strideA = (long long)n * OB; c.strideB = nn; c.strideC = nn;
+            c.batch = batch; c.strideA = (long long)n * TL; c.strideB = nn; c.strideC = nn;
             TB_TRY(gemm_f64(ctx, c));
         }
     }
@@ -221,11 +225,50 @@ extern "C" int tboa_chol_inv_upper(tboa_ctx* ctx, int n, int batch, const float*
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
         double* H64 = ar.get<double>((size_t)batch * n * n);
-        double* tmp = ar.get<double>((size_t)batch * n * TB_FACT_OB);
+        double* tmp = ar.get<double>((size_t)batch * n * chol_tmp_pitch(n));
         double* dinv = ar.get<double>((size_t)batch * nblk * NB * NB);
         if (!pass) { TB_TRY(tboa_ws_reserve(ctx, ar.off)); continue; }
         TB_TRY(launch_f32_to_f64_damp(ctx, n, batch, H, damp, H64));
         TB_TRY(chol_inv_upper_f64(ctx, n, batch, H64, U, tmp, dinv));
     }
     return 0;
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same factorisation for callers that cannot allocate: its three temporaries (the fp64 copy of H that becomes V,
+// the panel buffer of the triangular inverse, the inverted diagonal blocks) live in a file-scope device array instead
+// of the context's workspace.  Every GPU the library runs on holds its own copy of the array until the process ends;
+// its address on a device is looked up once, by tboa_create with that device current.  All calls on one GPU share the
+// array: two calls that overlap in time on the same GPU (different streams, different host threads) race.
+namespace {
+constexpr size_t STATIC_REGION = (size_t)1 << 20;                    // doubles per temporary: 8 MiB
+__device__ __align__(256) double scratch[3 * STATIC_REGION];         // 24 MiB
+constexpr int MAX_DEVICES = 64;
+double* scratch_on_device[MAX_DEVICES];                              // device address of `scratch`, per device (0 = not looked up)
+}  // namespace
+
+int chol_static_init(int device) {
+    if (device < 0 || device >= MAX_DEVICES) return TBOA_EINVAL;
+    if (scratch_on_device[device]) return 0;
+    double* p = nullptr;
+    if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return TBOA_EHIP; }
+    scratch_on_device[device] = p;
+    return 0;
+}
+
+extern "C" size_t tboa_chol_inv_upper_static_max_elems(void) { return STATIC_REGION; }
+
+extern "C" int tboa_chol_inv_upper_static(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* U) {
+    if (!ctx) return TBOA_EINVAL;
+    if (n <= 0 || batch <= 0 || !H || !U) return tboa_fail(ctx, TBOA_EINVAL, "chol_inv_upper_static: bad arguments");
+    const size_t n64 = (size_t)((n + NB - 1) / NB) * NB;
+    if (n > TB_FACT_OB || (size_t)batch * n64 * n64 > STATIC_REGION)
+        return tboa_fail(ctx, TBOA_EINVAL, "chol_inv_upper_static: n = %d, batch = %d exceed the static scratch (n <= %d and "
+                         "batch * roundup64(n)^2 <= %zu); use tboa_chol_inv_upper", n, batch, TB_FACT_OB, STATIC_REGION);
+    double* base = (ctx->device >= 0 && ctx->device < MAX_DEVICES) ? scratch_on_device[ctx->device] : nullptr;
+    if (!base) return tboa_fail(ctx, TBOA_EHIP, "chol_inv_upper_static: the static scratch of device %d was not found at tboa_create", ctx->device);
+    // H64: batch n^2; tmp: batch n 64 (one outer block: chol_tmp_pitch(n) = 64); dinv: batch ceil(n / 64) 64^2 -- each within a region
+    double* H64 = base; double* tmp = base + STATIC_REGION; double* dinv = base + 2 * STATIC_REGION;
+    TB_TRY(launch_f32_to_f64_damp(ctx, n, batch, H, damp, H64));
+    return chol_inv_upper_f64(ctx, n, batch, H64, U, tmp, dinv);
 }

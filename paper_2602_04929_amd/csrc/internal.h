@@ -117,15 +117,17 @@ __device__ __forceinline__ long long tboa_blocked_offset(long long r, long long 
 
 // ---------------------------------------------------------------- factor.hip
 // H64 [batch, n, n] fp64, overwritten; U [batch, n, n] fp64 out.  Checks the device status and
-// returns TBOA_ENOTSPD on breakdown (synchronises).  tmp: workspace of batch*n*TB_FACT_OB doubles,
+// returns TBOA_ENOTSPD on breakdown (synchronises).  tmp: workspace of batch * n * chol_tmp_pitch(n) doubles,
 // dinv: batch * ceil(n / TB_FACT_NB) * TB_FACT_NB^2 doubles.
 #define TB_FACT_NB 64     // diagonal blocks factored inside LDS
 #define TB_FACT_OB 512    // outer blocks: width of the large trailing updates
+static inline int chol_tmp_pitch(int n) { return n <= TB_FACT_OB ? TB_FACT_NB : TB_FACT_OB; }
 // status_slot: which pair of device status words records a breakdown (0 or 2); defer_status: do not wait for them here,
 // the caller checks with chol_status_f64 once the work has been joined.
 int chol_inv_upper_f64(tboa_ctx* ctx, int n, int batch, double* H64, double* U, double* tmp, double* dinv, int status_slot = 0,
                        bool defer_status = false);
 int chol_status_f64(tboa_ctx* ctx, int status_slot);
+int chol_static_init(int device);   // looks up the device address of the static scratch of tboa_chol_inv_upper_static (device current)
 int launch_f32_to_f64_damp(tboa_ctx* ctx, int n, int batch, const float* H, double damp, double* out);
 
 // ---------------------------------------------------------------- misc elementwise (elementwise.hip)
