@@ -12,12 +12,14 @@
  * Conventions
  *   - Every tensor pointer is DEVICE memory owned by the caller unless marked "host".  Inputs are never
  *     modified; the library keeps no pointer after a call returns.  Temporary storage belongs to the
- *     context (grown on demand, released by tboa_destroy).
+ *     context: one workspace, grown on demand (a growth frees and reallocates it after synchronising the stream) and
+ *     released by tboa_destroy.  tboa_hessian_workspace_bytes / tboa_quantize_workspace_bytes tell what a call will need
+ *     and tboa_reserve_workspace obtains it ahead, so that no call allocates afterwards.
  *   - Matrices are dense row-major.  Activations are token-major: X[t, c] is channel c of token t, so the
  *     paper's X (channels x tokens) is the transpose and H_in = X X^T = sum_t x_t x_t^T.
  *     Weights are [out-channels, in-channels]; head h of a projection owns rows h*d_h .. (h+1)*d_h-1.
- *   - All work is enqueued on the stream given to tboa_create; a call that returns a status read from the
- *     device (factorisation breakdown) synchronises that stream once before returning.
+ *   - All work is enqueued on the stream given to tboa_create; a call that returns values or a status read from the
+ *     device (tboa_quantize_layer: factorisation breakdown, losses) synchronises that stream once, at its end.
  *   - Every function returns 0 on success or a negative tboa_status; tboa_last_error() then describes it.
  *     No exceptions, no abort, nothing printed.  One context per host thread.
  */
@@ -55,9 +57,9 @@ void tboa_destroy(tboa_ctx* ctx);
 const char* tboa_last_error(const tboa_ctx* ctx);
 /* Event counters of this context since its creation (host values).
  * TBOA_CTR_GRID_PASSES: grid-search passes that used the two-phase search (approximate costs of all candidates on the
- * bf16 matrix cores, exact fp64 costs of the near-minimal ones); TBOA_CTR_GRID_FALLBACKS: those among them that met a
- * number of rows with more near-minimal candidates than the pass can handle one by one and therefore evaluated every
- * candidate of every row in fp64; TBOA_CTR_GRID_EXACT_ROWS: single rows that had every candidate evaluated in fp64;
+ * bf16 matrix cores, exact fp64 costs of the near-minimal ones); TBOA_CTR_GRID_FALLBACKS: tboa_quantize_layer calls whose
+ * two-phase search did not trust itself (see tboa_layer_desc.grid_guard) and that were therefore run again with every
+ * candidate of every row evaluated in fp64; TBOA_CTR_GRID_EXACT_ROWS: unused, always 0;
  * TBOA_CTR_GRID_SURVIVORS: near-minimal candidates that were evaluated exactly (rows with a single near-minimal
  * candidate need none).
  * TBOA_CTR_WEIGHTS_INT_FORM / TBOA_CTR_WEIGHTS_HILO: dequantized fp32 weight matrices handed to
@@ -68,6 +70,9 @@ enum tboa_counter_id { TBOA_CTR_GRID_PASSES = 0, TBOA_CTR_GRID_FALLBACKS = 1, TB
 int64_t tboa_counter(const tboa_ctx* ctx, int which);
 /* Bytes of context-owned workspace currently allocated (host value). */
 size_t tboa_workspace_bytes(const tboa_ctx* ctx);
+/* Makes the context's workspace at least `bytes` large (no-op when it already is).  Synchronises the stream when it has to
+ * reallocate.  TBOA_ENOMEM when the device cannot provide it (the context then has no workspace at all). */
+int tboa_reserve_workspace(tboa_ctx* ctx, size_t bytes);
 
 /* ------------------------------------------------------------------------------------------------
  * Attention block description (Algorithm 1 inputs).  T = n_seqs * seq_len tokens.
@@ -106,6 +111,9 @@ typedef struct {
  *             (tboa_fp_cache_bytes is 0 for fp32 inputs: pass NULL).
  */
 size_t tboa_fp_cache_bytes(const tboa_attn_desc* desc);
+/* Workspace that tboa_build_hessians and tboa_build_hessian_out_proj need for this block (the larger of the two, with X_fp
+ * and every output requested); 0 for an invalid descriptor. */
+size_t tboa_hessian_workspace_bytes(const tboa_attn_desc* desc);
 int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* desc,
                         const void* X, const void* X_fp,
                         const void* Wq, const void* Wk, const void* Wv, const void* Wo,
@@ -173,7 +181,16 @@ typedef struct {
     int grid_points;    /* candidates per unit shrink (100)                                           */
     double max_shrink;  /* candidates k = 0 .. ceil(max_shrink*grid_points)-1, range scaled by 1-k/grid_points */
     double damp;        /* every Hessian gets damp * mean(diag) added to its diagonal at entry        */
+    double grid_guard;  /* the grid search of wide per-row layers (d_in >= 256, group = 0) finds its candidates' costs
+                           approximately on the bf16 matrix cores and re-evaluates the near-minimal ones (within tau = 2e-3
+                           of the minimum) in fp64; every re-evaluation is compared with its approximation, and a call in
+                           which one differs by more than grid_guard * tau (relative) is run again with fp64 costs for every
+                           candidate.  0: the default, 0.25.  Negative: fp64 costs for every candidate from the start. */
 } tboa_layer_desc;
+
+/* Workspace that tboa_quantize_layer needs for this descriptor (an upper bound: the size with H_out and R given);
+ * 0 for an invalid descriptor. */
+size_t tboa_quantize_workspace_bytes(const tboa_layer_desc* desc);
 
 /*   W      [d_out, d_in]            (w_dtype)
  *   H_in   fp32, shape per hin_per_head
@@ -186,7 +203,8 @@ typedef struct {
  *   W_deq  [d_out, d_in] fp32 = scales * (codes - zeros)
  *   loss   host double[2] or NULL: {tr(H_out D H_in D^T), 2 tr(H_out W R D^T)} summed over heads, D = W_deq - W,
  *          on the damped Hessians (the D-dependent part of the attention reconstruction error)
- *   loss_per_head  host double[n_heads] or NULL: the sum of the two terms per head
+ *   loss_per_head  host double[n_heads][2] or NULL: the two terms of every head
+ * Synchronises the stream once, at the end (breakdown status of the factorisations, the losses, the guard of the grid search).
  */
 int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* desc,
                         const void* W, const float* H_in, const float* H_out, const float* R,
@@ -254,17 +272,22 @@ int tboa_gemm_f64(tboa_ctx* ctx, int M, int N, int K, double alpha,
  *        matrix is the pointer offset 16 * c0.  Operands: rows a multiple of 16, K a multiple of 32 (batch strides as for
  *        row-major operands; blocks that start on 128-byte boundaries are read as whole cache lines); C: bf16, no
  *        accumulation, M and N multiples of 256.  Meant for chains of products where one
- *        product's bf16 result is the next one's operand (its loads are then whole contiguous blocks). */
+ *        product's bf16 result is the next one's operand (its loads are then whole contiguous blocks).
+ *        TBOA_GEMM_KLO: the contraction of the output tile at (m0, n0) starts at k = max(m0, n0) (tile starts, multiples of
+ *        256) in every segment: for operands with A[m, k] = 0 for k < m and B[n, k] = 0 for k < n, such as transposed causal
+ *        attention probabilities (contraction or segment length a multiple of 256, M and N not larger).
+ *        TBOA_GEMM_F16: A and B (and a C of c_dtype TBOA_BF16, i.e. 16 bits wide) hold IEEE half values instead of bf16:
+ *        same layouts, same rate, 11 instead of 8 significant bits, range up to 65504. */
 enum { TBOA_GEMM_LOWER = 1, TBOA_GEMM_CAUSAL_K = 2, TBOA_GEMM_PERSISTENT = 4, TBOA_GEMM_A_TILED = 8, TBOA_GEMM_B_TILED = 16,
-       TBOA_GEMM_C_TILED = 32 };
+       TBOA_GEMM_C_TILED = 32, TBOA_GEMM_F16 = 64, TBOA_GEMM_KLO = 128 };
 int tboa_gemm_bf16_nt(tboa_ctx* ctx, int M, int N, int K, float alpha,
                       const void* A, int64_t lda, const void* B, int64_t ldb,
                       void* C, int64_t ldc, int c_dtype, int accumulate, int flags,
                       int batch, int64_t strideA, int64_t strideB, int64_t strideC);
 
 /* ------------------------------------------------------------------------------------------------
- * Live kernel timing.  With profiling on, every bf16 GEMM launch that carries one of the tags
- * below is bracketed by HIP events on the context's stream.  tboa_profile_read synchronises the stream and returns,
+ * Live kernel timing.  With profiling on, every GEMM launch that carries one of the tags
+ * below is bracketed by HIP events on the stream it is launched on.  tboa_profile_read synchronises the stream and returns,
  * for one tag, the summed kernel time, the number of launches and the summed algorithmic flops of those launches
  * (2 M N K per batch entry; a symmetric product counts its M(M+1)/2 unique outputs, a product with a lower
  * triangular factor the k <= n part).  tboa_profile_reset drops the records.
@@ -276,7 +299,14 @@ enum tboa_prof_tag {
     TBOA_PROF_GRAM = 3,      /* X X^T, dX X^T, O O^T over all tokens  */
     TBOA_PROF_PROJ = 4,      /* projections and scores                */
     TBOA_PROF_GRID = 5,      /* approximate grid-search costs (quantize_layer) */
-    TBOA_PROF_NTAGS = 6
+    /* fp64 matrix-core GEMMs of tboa_quantize_layer (flops: 2 M N K over the contraction range every tile really has) */
+    TBOA_PROF_F64_GRID = 6,    /* exact grid-search costs (near-minimal candidates: timed, flops not counted; or all candidates) */
+    TBOA_PROF_F64_FACTOR = 7,  /* P = ((R U^T) * M_U) U of Algorithm 3                                    */
+    TBOA_PROF_F64_SWEEP = 8,   /* rank-64 updates of the columns right of a panel of the in-channel sweep */
+    TBOA_PROF_F64_COMP = 9,    /* compensation of the remaining out-channels (Prop. 3.1 / 3.2)            */
+    TBOA_PROF_F64_CD = 10,     /* products of the scale refinement (Algorithm 2) and of the loss          */
+    TBOA_PROF_ATA = 11,        /* sum over a KV group's heads of A_h^T A_h and A_h^T (A_h - A~_h) (grouped-query form of the W_V Hessian) */
+    TBOA_PROF_NTAGS = 12
 };
 int tboa_profile_enable(tboa_ctx* ctx, int on);
 int tboa_profile_reset(tboa_ctx* ctx);

@@ -6,7 +6,7 @@ libturboboa.so and raises ImportError when it is missing: there is no fallback p
 from . import synth  # noqa: F401
 
 _BINDING_NAMES = ("Context", "TurboBoAError", "AttnDesc", "LayerDesc", "F32", "BF16", "F64",
-                  "GEMM_LOWER", "GEMM_CAUSAL_K", "GEMM_PERSISTENT", "GEMM_A_TILED", "GEMM_B_TILED", "GEMM_C_TILED", "LIB_PATH")
+                  "GEMM_LOWER", "GEMM_CAUSAL_K", "GEMM_PERSISTENT", "GEMM_A_TILED", "GEMM_B_TILED", "GEMM_C_TILED", "GEMM_F16", "GEMM_KLO", "LIB_PATH")
 
 
 def __getattr__(name):

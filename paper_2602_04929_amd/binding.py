@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libturboboa.so")
 
 F32, BF16, F64 = 0, 1, 2
-GEMM_LOWER, GEMM_CAUSAL_K, GEMM_PERSISTENT, GEMM_A_TILED, GEMM_B_TILED, GEMM_C_TILED = 1, 2, 4, 8, 16, 32
+GEMM_LOWER, GEMM_CAUSAL_K, GEMM_PERSISTENT, GEMM_A_TILED, GEMM_B_TILED, GEMM_C_TILED, GEMM_F16, GEMM_KLO = 1, 2, 4, 8, 16, 32, 64, 128
 
 STATUS = {0: "OK", -1: "EINVAL", -2: "ENOTSPD", -3: "ENOMEM", -4: "EHIP", -5: "ENAN"}
 
@@ -36,7 +36,7 @@ class LayerDesc(C.Structure):
     _fields_ = [("d_out", C.c_int), ("d_in", C.c_int), ("n_heads", C.c_int), ("hin_per_head", C.c_int),
                 ("bits", C.c_int), ("block", C.c_int), ("group", C.c_int), ("w_dtype", C.c_int),
                 ("cd_iters", C.c_int), ("adaptive_grid", C.c_int), ("grid_points", C.c_int),
-                ("max_shrink", C.c_double), ("damp", C.c_double)]
+                ("max_shrink", C.c_double), ("damp", C.c_double), ("grid_guard", C.c_double)]
 
 
 def _load():
@@ -50,6 +50,8 @@ def _load():
         "tboa_destroy": ([vp], None),
         "tboa_last_error": ([vp], C.c_char_p),
         "tboa_workspace_bytes": ([vp], C.c_size_t),
+        "tboa_reserve_workspace": ([vp, C.c_size_t], i32),
+        "tboa_quantize_workspace_bytes": ([C.POINTER(LayerDesc)], C.c_size_t),
         "tboa_gemm_f64": ([vp, i32, i32, i32, f64, vp, i64, i64, vp, i64, i64, f64, vp, i64, i32, i64, i64, i64], i32),
         "tboa_gemm_bf16_nt": ([vp, i32, i32, i32, f32, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i64, i64, i64], i32),
         "tboa_chol_inv_upper": ([vp, i32, i32, vp, f64, vp], i32),
@@ -58,6 +60,7 @@ def _load():
         "tboa_build_hessians": ([vp, C.POINTER(AttnDesc)] + [vp] * 14, i32),
         "tboa_build_hessian_out_proj": ([vp, C.POINTER(AttnDesc)] + [vp] * 11, i32),
         "tboa_fp_cache_bytes": ([C.POINTER(AttnDesc)], C.c_size_t),
+        "tboa_hessian_workspace_bytes": ([C.POINTER(AttnDesc)], C.c_size_t),
         "tboa_act_fakequant": ([vp, i64, i32, i32, i32, vp, vp], i32),
         "tboa_hadamard_rotate": ([vp, i64, i32, i32, vp, vp, vp], i32),
         "tboa_build_hessian_linear": ([vp, i64, i32, i32, f64, vp, vp, vp, vp], i32),
@@ -127,15 +130,36 @@ class Context:
             raise TurboBoAError(rc, _lib.tboa_last_error(self._h).decode())
 
     def counter(self, which):
-        """tboa_counter_id: 0 two-phase grid-search passes, 1 passes that evaluated every candidate exactly, 2 rows that did,
-        3 near-minimal candidates evaluated exactly, 4 / 5 dequantized weight matrices taken in integer form / split."""
+        """tboa_counter_id: 0 two-phase grid-search passes, 1 quantize_layer calls run again with exact grid-search costs,
+        2 unused, 3 near-minimal candidates evaluated exactly, 4 / 5 dequantized weight matrices taken in integer form / split."""
         return int(_lib.tboa_counter(self._h, which))
 
     def workspace_bytes(self):
         return int(_lib.tboa_workspace_bytes(self._h))
 
+    def reserve_workspace(self, nbytes):
+        self._check(_lib.tboa_reserve_workspace(self._h, int(nbytes)))
+
+    @staticmethod
+    def layer_desc(W, H_in, n_heads, bits, block, group=0, cd_iters=1, adaptive_grid=True, grid_points=100, max_shrink=0.8,
+                   damp=0.01, grid_guard=0.0):
+        d_out, d_in = W.shape
+        return LayerDesc(d_out, d_in, n_heads, int(H_in.dim() == 3), bits, block, group, _dtype_code(W), cd_iters,
+                         int(adaptive_grid), grid_points, max_shrink, damp, grid_guard)
+
+    @staticmethod
+    def hessian_workspace_bytes(d_model, n_q_heads, n_kv_heads, head_dim, n_seqs, seq_len, dtype, causal=True, seq_chunk=0):
+        desc = AttnDesc(d_model, n_q_heads, n_kv_heads, head_dim, n_seqs, seq_len, {torch.float32: F32, torch.bfloat16: BF16}[dtype],
+                        int(causal), 0.0, seq_chunk)
+        return int(_lib.tboa_hessian_workspace_bytes(C.byref(desc)))
+
+    @staticmethod
+    def quantize_workspace_bytes(desc):
+        return int(_lib.tboa_quantize_workspace_bytes(C.byref(desc)))
+
     # ---- live kernel timing
-    PROF_TAGS = {"hv_syrk": 0, "ax": 1, "rv": 2, "gram": 3, "proj": 4, "grid": 5}
+    PROF_TAGS = {"hv_syrk": 0, "ax": 1, "rv": 2, "gram": 3, "proj": 4, "grid": 5,
+                 "f64_grid": 6, "f64_factor": 7, "f64_sweep": 8, "f64_comp": 9, "f64_cd": 10, "ata": 11}
 
     def profile(self, on=True):
         self._check(_lib.tboa_profile_enable(self._h, int(on)))
@@ -165,16 +189,21 @@ class Context:
         return C_out
 
     def gemm_bf16_nt(self, A, B, out_dtype=torch.float32, alpha=1.0, C_out=None, accumulate=False, flags=0):
-        """C = alpha A B^T (+ C) for bf16 A [.., M, K], B [.., N, K]; rows may be pitched (views of a wider tensor)."""
+        """C = alpha A B^T (+ C) for bf16 (or, both, float16: TBOA_GEMM_F16 is then set) A [.., M, K], B [.., N, K]; rows may be
+        pitched (views of a wider tensor).  A 16-bit C has the operands' type."""
         batched = A.dim() == 3
         A3 = A if batched else A[None]; B3 = B if batched else B[None]
         for t in (A3, B3):
-            assert t.is_cuda and t.dtype == torch.bfloat16 and t.stride(2) == 1, "expected K-contiguous bf16 CUDA tensors"
+            assert t.is_cuda and t.dtype == A.dtype and t.dtype in (torch.bfloat16, torch.float16) and t.stride(2) == 1, \
+                "expected K-contiguous bf16 or float16 CUDA tensors"
+        if A.dtype == torch.float16:
+            flags |= GEMM_F16
         bs, M, K = A3.shape; N = B3.shape[1]
         if C_out is None:
             C_out = torch.zeros((bs, M, N) if batched else (M, N), dtype=out_dtype, device=A.device)
+        assert C_out.dtype in (torch.float32, A.dtype)
         self._check(_lib.tboa_gemm_bf16_nt(self._h, M, N, K, alpha, _ptr(A3), A3.stride(1), _ptr(B3), B3.stride(1), _ptr(C_out), N,
-                                           _dtype_code(C_out), int(accumulate), flags, bs, A3.stride(0), B3.stride(0), M * N))
+                                           F32 if C_out.dtype == torch.float32 else BF16, int(accumulate), flags, bs, A3.stride(0), B3.stride(0), M * N))
         return C_out
 
     def chol_inv_upper(self, H, damp=0.0, out=None, static=False):
@@ -296,24 +325,25 @@ class Context:
         return y
 
     def quantize_layer(self, W, H_in, H_out, R, n_heads, bits, block, group=0, cd_iters=1, adaptive_grid=True,
-                       grid_points=100, max_shrink=0.8, damp=0.01):
+                       grid_points=100, max_shrink=0.8, damp=0.01, grid_guard=0.0):
+        """grid_guard: see tboa_layer_desc (0: default; negative: fp64 costs for every grid candidate)."""
         _dev(W); _dev(H_in, torch.float32)
         d_out, d_in = W.shape
         ng = d_in // group if group else 1
-        desc = LayerDesc(d_out, d_in, n_heads, int(H_in.dim() == 3), bits, block, group, _dtype_code(W), cd_iters,
-                         int(adaptive_grid), grid_points, max_shrink, damp)
+        desc = self.layer_desc(W, H_in, n_heads, bits, block, group, cd_iters, adaptive_grid, grid_points, max_shrink, damp, grid_guard)
         dev = W.device
         codes = torch.empty(d_out, d_in, dtype=torch.uint8, device=dev)
         scales = torch.empty(d_out, ng, dtype=torch.float32, device=dev)
         zeros = torch.empty(d_out, ng, dtype=torch.float32, device=dev)
         W_deq = torch.empty(d_out, d_in, dtype=torch.float32, device=dev)
         loss = (C.c_double * 2)()
-        lph = (C.c_double * n_heads)()
+        lph = (C.c_double * (2 * n_heads))()
         if H_out is not None:
             _dev(H_out, torch.float32)
         if R is not None:
             _dev(R, torch.float32)
         self._check(_lib.tboa_quantize_layer(self._h, C.byref(desc), _ptr(W), _ptr(H_in), _ptr(H_out), _ptr(R),
                                              _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(W_deq), loss, lph))
+        terms = [(lph[2 * h], lph[2 * h + 1]) for h in range(n_heads)]
         return dict(codes=codes, scales=scales, zeros=zeros, W_deq=W_deq, loss_quad=loss[0], loss_cross=loss[1],
-                    loss=loss[0] + loss[1], loss_per_head=list(lph))
+                    loss=loss[0] + loss[1], loss_per_head=[q + c for q, c in terms], loss_per_head_terms=terms)

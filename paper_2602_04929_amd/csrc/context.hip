@@ -12,6 +12,7 @@ int tboa_fail(tboa_ctx* ctx, int code, const char* fmt, ...) {
 }
 
 int tboa_ws_reserve(tboa_ctx* ctx, size_t bytes) {
+    if (ctx->plan_only) { if (bytes > ctx->plan_bytes) ctx->plan_bytes = bytes; return TB_PLAN_STOP; }
     if (bytes <= ctx->ws_bytes) return 0;
     TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (ctx->ws) { TB_HIP(ctx, hipFree(ctx->ws)); ctx->ws = nullptr; ctx->ws_bytes = 0; }
@@ -56,6 +57,27 @@ extern "C" int tboa_create(tboa_ctx** out, int hip_device, void* hip_stream) {
     return 0;
 }
 
+extern "C" int tboa_reserve_workspace(tboa_ctx* ctx, size_t bytes) {
+    if (!ctx) return TBOA_EINVAL;
+    return tboa_ws_reserve(ctx, bytes);
+}
+
+int prof_begin(tboa_ctx* ctx, int tag, double flops, ProfRec& rec, bool& timed) {
+    timed = ctx->prof_on && tag >= 0;
+    if (!timed) return 0;
+    TB_HIP(ctx, hipEventCreate(&rec.a)); TB_HIP(ctx, hipEventCreate(&rec.b));
+    rec.tag = tag; rec.flops = flops;
+    TB_HIP(ctx, hipEventRecord(rec.a, ctx->stream));
+    return 0;
+}
+
+int prof_end(tboa_ctx* ctx, const ProfRec& rec, bool timed) {
+    if (!timed) return 0;
+    TB_HIP(ctx, hipEventRecord(rec.b, ctx->stream));
+    ctx->prof.push_back(rec);
+    return 0;
+}
+
 extern "C" int tboa_profile_enable(tboa_ctx* ctx, int on) {
     if (!ctx) return TBOA_EINVAL;
     ctx->prof_on = on ? 1 : 0;
@@ -65,6 +87,7 @@ extern "C" int tboa_profile_enable(tboa_ctx* ctx, int on) {
 extern "C" int tboa_profile_reset(tboa_ctx* ctx) {
     if (!ctx) return TBOA_EINVAL;
     TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    TB_HIP(ctx, hipStreamSynchronize(ctx->aux));
     for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     ctx->prof.clear();
     return 0;
@@ -72,7 +95,9 @@ extern "C" int tboa_profile_reset(tboa_ctx* ctx) {
 
 extern "C" int tboa_profile_read(tboa_ctx* ctx, int tag, double* ms_total, int64_t* launches, double* flops_total) {
     if (!ctx) return TBOA_EINVAL;
+    if (tag < 0 || tag >= TBOA_PROF_NTAGS) return tboa_fail(ctx, TBOA_EINVAL, "profile_read: unknown tag %d", tag);
     TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    TB_HIP(ctx, hipStreamSynchronize(ctx->aux));
     double ms = 0.0, fl = 0.0; int64_t n = 0;
     for (auto& r : ctx->prof) {
         if (r.tag != tag) continue;

@@ -1,4 +1,5 @@
-// bf16 x bf16 -> fp32 GEMM, C = alpha A B^T, on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16).
+// bf16 x bf16 -> fp32 GEMM, C = alpha A B^T, on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16); with TBOA_GEMM_F16 the
+// same kernels take IEEE half operands (v_mfma_f32_32x32x16_f16: same layouts, same rate, three more mantissa bits).
 //
 // Both operands are K-contiguous ("NT"): every contraction of the Hessian build is arranged that way (activations
 // are kept in a transposed copy where the token axis is the contraction axis), so one kernel shape serves X^T X,
@@ -23,7 +24,15 @@
 #include <algorithm>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// one 32 x 32 x 16 matrix-core step on 16-bit operands held as 8 x 16 bits per lane; F16: the bits are IEEE half, else bf16
+template <bool F16>
+__device__ __forceinline__ f32x16 mma16(bf16x8 a, bf16x8 b, f32x16 c) {
+    if constexpr (F16) return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
 
 namespace {
 
@@ -35,7 +44,8 @@ struct Args {
     const __hip_bfloat16* A; long long lda;
     const __hip_bfloat16* B; long long ldb;
     void* C; long long ldc;
-    int c_bf16, accumulate, flags;
+    void* C2;                   // TBOA_GEMM_C_HILO: receives the low parts, same layout as C
+    int c_bf16, accumulate, flags;   // c_bf16: C holds 16-bit values (bf16, or IEEE half with TBOA_GEMM_F16)
     int vec_c;                  // C rows and batch offsets allow 16-byte (fp32) / 8-byte (bf16) accesses at columns that are multiples of 4
     int batch_inner, kseg;
     long long sA1, sA2, sB1, sB2, sC1, sC2;
@@ -100,7 +110,19 @@ __device__ __forceinline__ void transpose_acc(f32x16 (&acc)[4][TJ]) {
 
 // acc as left by transpose_acc; (row0, col0): first row and column of the wavefront's tile in C, uniform over the wavefront
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// four results as 16-bit values (8 bytes): bf16, or IEEE half when the launch carries TBOA_GEMM_F16
+__device__ __forceinline__ uint2 pack16x4(const Args& g, f32x4 r) {
+    if ((g.flags & TBOA_GEMM_F16) && !(g.flags & TBOA_GEMM_C_HILO)) return __builtin_bit_cast(uint2, __builtin_convertvector(r, f16x4));
+    return __builtin_bit_cast(uint2, __builtin_convertvector(r, bf16x4));
+}
+// TBOA_GEMM_C_HILO: the result leaves as an exact-to-16-bit pair of bf16 values, hi into C and lo = bf16(r - hi) into C2
+__device__ __forceinline__ uint2 pack_lo4(f32x4 r) {
+    const bf16x4 hi = __builtin_convertvector(r, bf16x4);
+    return __builtin_bit_cast(uint2, __builtin_convertvector(r - __builtin_convertvector(hi, f32x4), bf16x4));
+}
 
 template <int TJ, bool SCALE>
 __device__ __forceinline__ void store_acc_interior(const Args& g, const f32x16 (&acc)[4][TJ], int row0, int col0, long long coff) {
@@ -119,7 +141,10 @@ __device__ __forceinline__ void store_acc_interior(const Args& g, const f32x16 (
                 char* p = base + ((long long)(32 * i + 8 * b) * g.ldc + 32 * j) * es + off;
                 f32x4 r = {acc[i][j][4 * b], acc[i][j][4 * b + 1], acc[i][j][4 * b + 2], acc[i][j][4 * b + 3]};
                 if (SCALE) r *= g.alpha;
-                if (g.c_bf16) *(bf16x4*)p = __builtin_convertvector(r, bf16x4);
+                if (g.c_bf16) {
+                    *(uint2*)p = pack16x4(g, r);
+                    if (g.flags & TBOA_GEMM_C_HILO) *(uint2*)((char*)g.C2 + (p - (char*)g.C)) = pack_lo4(r);
+                }
                 else {
                     if (g.accumulate) r += *(const f32x4*)p;
                     *(f32x4*)p = r;
@@ -144,7 +169,9 @@ __device__ __forceinline__ void store_acc_tiled(const Args& g, const f32x16 (&ac
             for (int j = 0; j < TJ; ++j) {
                 f32x4 r = {acc[i][j][4 * b], acc[i][j][4 * b + 1], acc[i][j][4 * b + 2], acc[i][j][4 * b + 3]};
                 if (SCALE) r *= g.alpha;
-                *(bf16x4*)(base + ((long long)(2 * i + (b >> 1)) * kb + j) * 512 + off) = __builtin_convertvector(r, bf16x4);
+                __hip_bfloat16* p = base + ((long long)(2 * i + (b >> 1)) * kb + j) * 512 + off;
+                *(uint2*)p = pack16x4(g, r);
+                if (g.flags & TBOA_GEMM_C_HILO) *(uint2*)((__hip_bfloat16*)g.C2 + (p - (__hip_bfloat16*)g.C)) = pack_lo4(r);
             }
         }
 }
@@ -176,7 +203,13 @@ __device__ __forceinline__ void store_acc(const Args& g, const f32x16 (&acc)[4][
                     if (col + e >= g.N) continue;
                     const long long idx = coff + (long long)row * g.ldc + col + e;
                     const float r = g.alpha * acc[i][j][4 * b + e];
-                    if (g.c_bf16) ((__hip_bfloat16*)g.C)[idx] = __float2bfloat16(r);
+                    if (g.c_bf16) {
+                        if (g.flags & TBOA_GEMM_C_HILO) {
+                            const __hip_bfloat16 hi = __float2bfloat16(r);
+                            ((__hip_bfloat16*)g.C)[idx] = hi; ((__hip_bfloat16*)g.C2)[idx] = __float2bfloat16(r - __bfloat162float(hi));
+                        } else if (g.flags & TBOA_GEMM_F16) ((_Float16*)g.C)[idx] = (_Float16)r;
+                        else ((__hip_bfloat16*)g.C)[idx] = __float2bfloat16(r);
+                    }
                     else { float* c = (float*)g.C + idx; *c = g.accumulate ? r + *c : r; }
                 }
             }
@@ -208,6 +241,7 @@ __device__ __forceinline__ bf16x8 read_frag(const __hip_bfloat16* __restrict__ l
     return *(const bf16x8*)(lds + row * BK + ((chunk ^ ((row >> 1) & 7)) * 8));
 }
 
+template <bool F16>
 __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __hip_bfloat16* As = (__hip_bfloat16*)smem;                 // [2][BM*BK]
@@ -226,7 +260,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
     const int nseg = g.kseg > 0 ? g.K / g.kseg : 1;
     int kend = seg_len;
     if (g.flags & TBOA_GEMM_CAUSAL_K) kend = min(kend, n0 + BN);
-    const int nk_seg = (kend + BK - 1) / BK;
+    const int kbeg = (g.flags & TBOA_GEMM_KLO) ? min(kend, max(m0, n0)) : 0;      // a multiple of the tile size
+    const int nk_seg = (kend - kbeg + BK - 1) / BK;
     const int nk = nk_seg * nseg;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -243,8 +278,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
 
     uint4 ra[8], rb[8];
     if (nk > 0) {
-        load_tile(A, g.lda, m0, 0, g.M, kend, ra);
-        load_tile(B, g.ldb, n0, 0, g.N, kend, rb);   // first tile of segment 0
+        load_tile(A, g.lda, m0, kbeg, g.M, kend, ra);
+        load_tile(B, g.ldb, n0, kbeg, g.N, kend, rb);   // first tile of segment 0
         store_tile(As, ra);
         store_tile(Bs, rb);
     }
@@ -255,7 +290,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
         const __hip_bfloat16* b_s = Bs + cur * BN * BK;
         if (kt + 1 < nk) {
             const int sg = (kt + 1) / nk_seg, kb = sg * seg_len;
-            const int k0 = kb + ((kt + 1) - sg * nk_seg) * BK;
+            const int k0 = kb + kbeg + ((kt + 1) - sg * nk_seg) * BK;
             load_tile(A, g.lda, m0, k0, g.M, kb + kend, ra);
             load_tile(B, g.ldb, n0, k0, g.N, kb + kend, rb);
         }
@@ -270,7 +305,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_kernel(Args g) {
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = mma16<F16>(af[i], bfr[j], acc[i][j]);
         }
         if (kt + 1 < nk) {
             store_tile(As + (cur ^ 1) * BM * BK, ra);
@@ -314,7 +349,7 @@ template <int N>
 __device__ __forceinline__ void wait_loads_but() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(N) : "memory"); }
 
 // NS: stages in the LDS ring (NS - 1 of them in flight while one is multiplied)
-template <int WAVES, int NS>
+template <int WAVES, int NS, bool F16>
 __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
     constexpr int TJ = (WAVES == 8) ? 2 : 4;         // 32-wide MFMA tile columns per wavefront
     constexpr int LPW = 16 / WAVES;                  // 1 KB blocks of the A tile (and of the B tile) per wavefront and stage
@@ -334,7 +369,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
     const int nseg = g.kseg > 0 ? g.K / g.kseg : 1;
     int kend = seg_len;
     if (causal) kend = min(kend, n0 + BN);
-    const int nk_seg = kend / FK;                  // kend is a multiple of 32 on this path
+    const int kbeg = (g.flags & TBOA_GEMM_KLO) ? min(kend, max(m0, n0)) : 0;      // a multiple of the tile size
+    const int nk_seg = (kend - kbeg) / FK;         // kend is a multiple of 32 on this path
     const int nk = nk_seg * nseg;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -371,8 +407,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
     const char* Brow = (const char*)(B + (long long)n0 * g.ldb);
     // byte offset along k of the next stage to be issued (stages are issued strictly in order), kept incrementally;
     // in a blocked operand 32 k are one block of 1 KB, not 64 bytes of a row
-    long long koff_next = 0; int kin_next = 0;
-    auto advance = [&]() { kin_next += FK; koff_next += 2 * FK; if (kin_next == kend) { kin_next = 0; koff_next += 2LL * (seg_len - kend); } };
+    long long koff_next = 2LL * kbeg; int kin_next = kbeg;
+    auto advance = [&]() { kin_next += FK; koff_next += 2 * FK; if (kin_next == kend) { kin_next = kbeg; koff_next += 2LL * (seg_len - kend + kbeg); } };
     const unsigned ring_lds = (unsigned)(unsigned long long)((__attribute__((address_space(3))) void*)ring);
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     auto issue = [&](int slot) {
@@ -399,7 +435,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
 #define TB_MMA(SET)                                                                                         \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                           \
         _Pragma("unroll") for (int jj = 0; jj < TJ; ++jj)                                                   \
-            acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[SET][i], fb[SET][jj], acc[i][jj], 0, 0, 0);
+            acc[i][jj] = mma16<F16>(fa[SET][i], fb[SET][jj], acc[i][jj]);
 #define TB_INTERLEAVE_DS                                                                                    \
     __builtin_amdgcn_sched_group_barrier(0x100, 4 + TJ, 0);                                                 \
     __builtin_amdgcn_sched_group_barrier(0x008, 4 * TJ, 0);
@@ -424,8 +460,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
         {                                                                                                   \
             _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
                 _Pragma("unroll") for (int jj = 0; jj < TJ; jj += 2) {                                      \
-                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][jj], acc[i][jj], 0, 0, 0); \
-                    acc[i][jj + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][jj + 1], acc[i][jj + 1], 0, 0, 0); \
+                    acc[i][jj] = mma16<F16>(fa[1][i], fb[1][jj], acc[i][jj]); \
+                    acc[i][jj + 1] = mma16<F16>(fa[1][i], fb[1][jj + 1], acc[i][jj + 1]); \
                     const int q_ = (i * TJ + jj) / 2;              /* 0 .. 2 LPW - 1 */                       \
                     const unsigned blk_ = (unsigned)(wave_s * LPW + q_ / 2) * 1024u;                        \
                     __builtin_amdgcn_sched_barrier(0);                                                      \
@@ -486,7 +522,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_nt_fast_kernel(Args g) {
 // Needs every tile's stage count to be a multiple of NS (k ranges that are multiples of 32 NS), so that tile boundaries
 // fall on the boundaries of the unrolled ring.  After the last stage of the list the stream keeps re-reading its final
 // stage (in bounds, never multiplied), so the count of outstanding loads a wait refers to never changes.
-template <int NS>
+template <int NS, bool F16>
 __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
     constexpr int TJ = 2, LPW = 2;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -502,7 +538,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
     const int l32 = lane & 31, lh = lane >> 5;
 
     // a tile of the list, decoded: everything here is uniform over the workgroup
-    struct Tile { int valid, m0, n0, kend, nk; const char *A, *B; long long coff; };
+    struct Tile { int valid, m0, n0, kbeg, kend, nk; const char *A, *B; long long coff; };
     auto decode = [&](int2 e) {
         Tile t;
         t.valid = e.x >= 0;
@@ -513,7 +549,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
         t.B = (const char*)(g.B + z1 * g.sB1 + z2 * g.sB2 + (long long)t.n0 * g.ldb);
         t.coff = z1 * g.sC1 + z2 * g.sC2;
         t.kend = causal ? min(seg_len, t.n0 + BN) : seg_len;
-        t.nk = t.kend / FK * nseg;
+        t.kbeg = (g.flags & TBOA_GEMM_KLO) ? min(t.kend, max(t.m0, t.n0)) : 0;
+        t.nk = (t.kend - t.kbeg) / FK * nseg;
         return t;
     };
     const int2 none = make_int2(-1, 0);
@@ -540,7 +577,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
         }
     };
     const char* sA = cur.A; const char* sB = cur.B;
-    long long koff = 0; int kin = 0, skend = cur.kend, sleft = cur.nk;
+    long long koff = 2LL * cur.kbeg; int kin = cur.kbeg, skbeg = cur.kbeg, skend = cur.kend, sleft = cur.nk;
     bool nxt_taken = false;
     set_offsets(cur.m0, cur.n0);
     // called after the loads of the stage the stream points to have been issued
@@ -548,9 +585,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
         if (sleft == 0) return;
         if (--sleft > 0) {
             kin += FK; koff += 2 * FK;
-            if (kin == skend) { kin = 0; koff += 2LL * (seg_len - skend); }
+            if (kin == skend) { kin = skbeg; koff += 2LL * (seg_len - skend + skbeg); }
         } else if (nxt.valid && !nxt_taken) {
-            sA = nxt.A; sB = nxt.B; skend = nxt.kend; sleft = nxt.nk; koff = 0; kin = 0;
+            sA = nxt.A; sB = nxt.B; skbeg = nxt.kbeg; skend = nxt.kend; sleft = nxt.nk; koff = 2LL * nxt.kbeg; kin = nxt.kbeg;
             set_offsets(nxt.m0, nxt.n0);
             nxt_taken = true;
         }
@@ -577,7 +614,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
         TB_LOAD_FRAGS(1, SLOT, 1)                                                                           \
         _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                       \
             _Pragma("unroll") for (int jj = 0; jj < TJ; ++jj)                                               \
-                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][jj], (FIRST) ? zero16 : acc[i][jj], 0, 0, 0); \
+                acc[i][jj] = mma16<F16>(fa[0][i], fb[0][jj], (FIRST) ? zero16 : acc[i][jj]); \
         __builtin_amdgcn_sched_group_barrier(0x100, 4 + TJ, 0);                                             \
         __builtin_amdgcn_sched_group_barrier(0x008, 4 * TJ, 0);                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                  \
@@ -588,8 +625,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
         TB_LOAD_FRAGS(0, NEXTSLOT, 0)                                                                       \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                     \
             _Pragma("unroll") for (int jj = 0; jj < TJ; jj += 2) {                                          \
-                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][jj], acc[i][jj], 0, 0, 0); \
-                acc[i][jj + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][jj + 1], acc[i][jj + 1], 0, 0, 0); \
+                acc[i][jj] = mma16<F16>(fa[1][i], fb[1][jj], acc[i][jj]); \
+                acc[i][jj + 1] = mma16<F16>(fa[1][i], fb[1][jj + 1], acc[i][jj + 1]); \
                 const int q_ = (i * TJ + jj) / 2;              /* 0 .. 2 LPW - 1 */                           \
                 const unsigned blk_ = (unsigned)(wave_s * LPW + q_ / 2) * 1024u;                            \
                 __builtin_amdgcn_sched_barrier(0);                                                          \
@@ -679,8 +716,8 @@ int tile_order(tboa_ctx* ctx, int tiles_m, int tiles_n, int flags, const int** d
 // least work so far: with equal tiles that is round-robin (32 consecutive tiles side by side, as with dispatched
 // workgroups), with a causal limit it pairs long and short tiles so that all lists end together.
 int tile_schedule(tboa_ctx* ctx, const GemmBf16& q, int tiles_m, int tiles_n, const int2** dev, int* rounds, int* wgs) {
-    const int flags = q.flags & (TBOA_GEMM_LOWER | TBOA_GEMM_CAUSAL_K);
-    const int seg_len = (flags & TBOA_GEMM_CAUSAL_K) ? (q.kseg > 0 ? q.kseg : q.K) : 0;
+    const int flags = q.flags & (TBOA_GEMM_LOWER | TBOA_GEMM_CAUSAL_K | TBOA_GEMM_KLO);
+    const int seg_len = (flags & (TBOA_GEMM_CAUSAL_K | TBOA_GEMM_KLO)) ? (q.kseg > 0 ? q.kseg : q.K) : 0;
     for (const TileSchedule& t : ctx->tile_schedules)
         if (t.tiles_m == tiles_m && t.tiles_n == tiles_n && t.flags == flags && t.batch == q.batch && t.seg_len == seg_len) {
             *dev = t.dev; *rounds = t.rounds; *wgs = t.wgs; return 0;
@@ -702,7 +739,12 @@ int tile_schedule(tboa_ctx* ctx, const GemmBf16& q, int tiles_m, int tiles_n, co
     const int wpx = (int)(per < 32 ? per : 32);
     const long long window = ntiles >= 64 ? ntiles : 128;
     std::vector<std::vector<int2>> lists((size_t)8 * wpx);
-    auto length = [&](int packed) { return seg_len ? std::min<long long>(seg_len, ((packed & 0xffff) + 1LL) * BN) : 1LL; };
+    auto length = [&](int packed) {      // relative cost of a tile: its contraction range
+        if (!seg_len) return 1LL;
+        const long long hi = (flags & TBOA_GEMM_CAUSAL_K) ? std::min<long long>(seg_len, ((packed & 0xffff) + 1LL) * BN) : seg_len;
+        const long long lo = (flags & TBOA_GEMM_KLO) ? std::min<long long>(hi, (long long)std::max(packed >> 16, packed & 0xffff) * BM) : 0;
+        return std::max(1LL, hi - lo);
+    };
     for (int x = 0; x < 8; ++x) {
         std::vector<long long> load(wpx, 0);
         const long long lo = x * per, hi = std::min(nitems, lo + per);
@@ -751,27 +793,35 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
         if ((ta && (q.lda % 32 || q.M % 16)) || (tb && (q.ldb % 32 || q.N % 16)))
             return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: a blocked operand needs rows % 16 == 0 and ld % 32 == 0");
     }
+    if (q.flags & TBOA_GEMM_KLO) {
+        const int sl = q.kseg > 0 ? q.kseg : q.K;
+        if (sl % 256 || q.M > sl || q.N > sl) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: KLO needs a contraction (segment) length that is a multiple of 256 and at least M and N");
+    }
+    if (q.flags & TBOA_GEMM_C_HILO) {
+        if (q.c_dtype != TBOA_BF16 || !q.C2 || ((uintptr_t)q.C2 & 7)) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: a (hi, lo) result needs a 16-bit C and a second buffer");
+    }
     if (q.flags & TBOA_GEMM_C_TILED) {
         if (q.c_dtype != TBOA_BF16 || q.accumulate || q.M % 256 || q.N % 256 || q.ldc % 32 || q.strideC % 4 || q.strideC2 % 4 || ((uintptr_t)q.C & 7))
             return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: a blocked C must be bf16 without accumulation, M and N multiples of 256, ldc a multiple of 32");
     }
     static bool attr_set = false;
     const int smem = 2 * (BM + BN) * BK * (int)sizeof(__hip_bfloat16);
-    const int smem_fast = 4 * STAGE_ELEMS * (int)sizeof(__hip_bfloat16), smem_fast5 = 5 * STAGE_ELEMS * (int)sizeof(__hip_bfloat16);
+    const int smem_fast = 4 * STAGE_ELEMS * (int)sizeof(__hip_bfloat16);
     if (!attr_set) {
-        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<4, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
-        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
-        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8, 5>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast5));
-        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_stream_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8, 4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_fast_kernel<8, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_stream_kernel<4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)gemm_bf16_nt_stream_kernel<4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_fast));
         attr_set = true;
     }
-    const bool fast = (q.kseg > 0 ? q.kseg : q.K) % FK == 0 && q.K > 0 && !getenv("TBOA_GEMM_GENERIC");
+    const bool fast = (q.kseg > 0 ? q.kseg : q.K) % FK == 0 && q.K > 0;
     if ((q.flags & (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED)) && !fast) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: blocked operands are read by the LDS-direct kernel only");
     Args a;
     a.sched = nullptr; a.rounds = 0;
     a.M = q.M; a.N = q.N; a.K = q.K; a.alpha = q.alpha;
-    a.A = q.A; a.lda = q.lda; a.B = q.B; a.ldb = q.ldb; a.C = q.C; a.ldc = q.ldc;
+    a.A = q.A; a.lda = q.lda; a.B = q.B; a.ldb = q.ldb; a.C = q.C; a.ldc = q.ldc; a.C2 = q.C2;
     a.c_bf16 = (q.c_dtype == TBOA_BF16); a.accumulate = q.accumulate; a.flags = q.flags;
     a.vec_c = q.ldc % 4 == 0 && q.strideC % 4 == 0 && q.strideC2 % 4 == 0 && ((uintptr_t)q.C & 15) == 0;
     a.batch_inner = q.batch_inner > 0 ? q.batch_inner : 1;
@@ -787,33 +837,34 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     if (q.batch >= 8) { a.chunk = 32; a.per = ((a.nitems + a.chunk - 1) / a.chunk + 7) / 8 * a.chunk; }
     if (a.per > 200000000LL) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: grid too large");
     const unsigned nwg = (unsigned)(8 * a.per);
-    const bool timed = ctx->prof_on && q.tag >= 0;
-    ProfRec rec{};
-    if (timed) {
-        TB_HIP(ctx, hipEventCreate(&rec.a)); TB_HIP(ctx, hipEventCreate(&rec.b));
-        rec.tag = q.tag;
+    ProfRec rec{}; bool timed = false;
+    if (ctx->prof_on && q.tag >= 0) {
         const int nseg = q.kseg > 0 ? q.K / q.kseg : 1;
         const double ks = q.kseg > 0 ? q.kseg : q.K;
         double mnk = (double)q.M * q.N * ks;
-        if (q.flags & TBOA_GEMM_LOWER) mnk = 0.5 * (double)q.M * (q.M + 1.0) * ks;
+        if ((q.flags & TBOA_GEMM_KLO) && q.M == q.N) {      // sum over (i, j) of (ks - max(i, j)); the symmetric product: i >= j only
+            const double n = q.M;
+            mnk = (q.flags & TBOA_GEMM_LOWER) ? n * ks * (n + 1.0) / 2.0 - (n - 1.0) * n * (n + 1.0) / 3.0
+                                              : n * n * ks - (n - 1.0) * n * (4.0 * n + 1.0) / 6.0;
+        }
+        else if (q.flags & TBOA_GEMM_LOWER) mnk = 0.5 * (double)q.M * (q.M + 1.0) * ks;
         else if ((q.flags & TBOA_GEMM_CAUSAL_K) && ks >= q.N) mnk = 0.5 * (double)q.M * q.N * (q.N + 1.0);
-        rec.flops = 2.0 * mnk * nseg * q.batch;
-        TB_HIP(ctx, hipEventRecord(rec.a, ctx->stream));
+        TB_TRY(prof_begin(ctx, q.tag, 2.0 * mnk * nseg * q.batch, rec, timed));
     }
-    static const int waves = getenv("TBOA_GEMM_WAVES") ? atoi(getenv("TBOA_GEMM_WAVES")) : 8;
-    static const int ring = getenv("TBOA_GEMM_RING") ? atoi(getenv("TBOA_GEMM_RING")) : 4;
-    static const int stream_mode = getenv("TBOA_GEMM_PERSISTENT") ? atoi(getenv("TBOA_GEMM_PERSISTENT")) : -1;   // -1: as the caller asks
-    const bool persistent = fast && (q.kseg > 0 ? q.kseg : q.K) % (FK * 4) == 0 && (stream_mode < 0 ? (q.flags & TBOA_GEMM_PERSISTENT) != 0 : stream_mode != 0);
+    const bool f16 = (q.flags & TBOA_GEMM_F16) != 0;
+    const bool persistent = fast && (q.kseg > 0 ? q.kseg : q.K) % (FK * 4) == 0 && (q.flags & TBOA_GEMM_PERSISTENT) != 0;
     if (persistent) {
         int wgs = 0;
         TB_TRY(tile_schedule(ctx, q, tiles_m, tiles_n, &a.sched, &a.rounds, &wgs));
-        hipLaunchKernelGGL((gemm_bf16_nt_stream_kernel<4>), dim3(wgs), dim3(512), smem_fast, ctx->stream, a);
-    } else if (fast && waves == 8 && ring == 5) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<8, 5>), dim3(nwg), dim3(512), smem_fast5, ctx->stream, a);
-    else if (fast && waves == 8) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<8, 4>), dim3(nwg), dim3(512), smem_fast, ctx->stream, a);
-    else if (fast) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<4, 4>), dim3(nwg), dim3(256), smem_fast, ctx->stream, a);
-    else hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3(nwg), dim3(256), smem, ctx->stream, a);
+        if (f16) hipLaunchKernelGGL((gemm_bf16_nt_stream_kernel<4, true>), dim3(wgs), dim3(512), smem_fast, ctx->stream, a);
+        else hipLaunchKernelGGL((gemm_bf16_nt_stream_kernel<4, false>), dim3(wgs), dim3(512), smem_fast, ctx->stream, a);
+    } else if (fast) {
+        if (f16) hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<8, 4, true>), dim3(nwg), dim3(512), smem_fast, ctx->stream, a);
+        else hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<8, 4, false>), dim3(nwg), dim3(512), smem_fast, ctx->stream, a);
+    } else if (f16) hipLaunchKernelGGL(gemm_bf16_nt_kernel<true>, dim3(nwg), dim3(256), smem, ctx->stream, a);
+    else hipLaunchKernelGGL(gemm_bf16_nt_kernel<false>, dim3(nwg), dim3(256), smem, ctx->stream, a);
     TB_KERNEL_CHECK(ctx);
-    if (timed) { TB_HIP(ctx, hipEventRecord(rec.b, ctx->stream)); ctx->prof.push_back(rec); }
+    TB_TRY(prof_end(ctx, rec, timed));
     return 0;
 }
 

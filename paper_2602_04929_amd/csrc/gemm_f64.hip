@@ -10,6 +10,7 @@
 // factor per head) run a 32 x 128 tile instead (wavefronts 1 x 4, each 32 x 32): with the 128-row tile three quarters
 // of the MFMAs would multiply padding, and those products are bound by reading B once from HBM.
 #include "internal.h"
+#include <algorithm>
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
@@ -206,6 +207,25 @@ int gemm_f64(tboa_ctx* ctx, const GemmF64& q) {
     // 16-byte vector loads need every row start and the tile offsets (even) to stay 16-byte aligned
     const bool vecA = ((uintptr_t)q.A % 16 == 0) && ((uintptr_t)q.A2 % 16 == 0) && (q.strideA % 2 == 0) && (q.strideA2 % 2 == 0) && ((akc ? q.sam : q.sak) % 2 == 0);
     const bool vecB = ((uintptr_t)q.B % 16 == 0) && ((uintptr_t)q.B2 % 16 == 0) && (q.strideB % 2 == 0) && (q.strideB2 % 2 == 0) && ((bkc ? q.sbn : q.sbk) % 2 == 0);
+    // algorithmic flops of a tagged launch: 2 M N K per batch entry over the contraction range each output tile really has;
+    // a launch whose row count comes from device memory (m_limit) is timed but not counted
+    ProfRec rec{}; bool timed = false;
+    if (ctx->prof_on && q.tag >= 0) {
+        double macs = 0.0;
+        if (!q.m_limit)
+            for (int m0 = 0; m0 < q.M; m0 += BM)
+                for (int n0 = 0; n0 < q.N; n0 += BN) {
+                    if (q.skip_lower && q.skip_col0 + n0 + BN <= m0) continue;
+                    if (q.skip_upper && m0 + BM <= q.skip_col0 + n0) continue;
+                    int klo = 0, khi = q.K;
+                    if (q.klo_m) klo = std::max(klo, m0);
+                    if (q.klo_n) klo = std::max(klo, n0);
+                    if (q.khi_m) khi = std::min(khi, m0 + BM);
+                    if (q.khi_n) khi = std::min(khi, n0 + BN);
+                    if (khi > klo) macs += (double)std::min(BM, q.M - m0) * std::min(BN, q.N - n0) * (khi - klo) * (q.A2 ? 2.0 : 1.0);
+                }
+        TB_TRY(prof_begin(ctx, q.tag, 2.0 * macs * q.batch, rec, timed));
+    }
     const bool skinny = q.M <= 32 && akc;
     dim3 grid((unsigned)cdiv64(q.N, BN), (unsigned)cdiv64(q.M, skinny ? 32 : BM), (unsigned)q.batch);
     if (grid.y > 65535 || grid.z > 65535) return tboa_fail(ctx, TBOA_EINVAL, "gemm_f64: grid too large");
@@ -216,6 +236,7 @@ int gemm_f64(tboa_ctx* ctx, const GemmF64& q) {
     else if (!akc && bkc) hipLaunchKernelGGL((gemm_f64_kernel<false, true, BM>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
     else hipLaunchKernelGGL((gemm_f64_kernel<false, false, BM>), grid, dim3(256), 0, ctx->stream, a, vecA, vecB);
     TB_KERNEL_CHECK(ctx);
+    TB_TRY(prof_end(ctx, rec, timed));
     return 0;
 }
 

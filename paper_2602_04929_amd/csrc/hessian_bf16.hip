@@ -23,11 +23,23 @@ namespace {
 
 typedef __hip_bfloat16 bf16;
 
-// out[c, r] = in[r, c] (optionally also the exact hi/lo split of in - in2), 64 x 64 tiles through LDS; blocked: the
-// outputs are kept in 16 x 32 blocks
+// Operands of the W_V and W_O Hessian chains (probabilities, transposed activations, A X) are 16-bit values of one of two
+// kinds, chosen per call: IEEE half (11 significant bits; the default) or bf16 (8 bits; taken when an activation exceeds the
+// range of half).  Buffers are typed bf16 either way; these helpers produce and read the bits.
+__device__ __forceinline__ bf16 enc16(float v, int f16) {
+    if (f16) { const _Float16 h = (_Float16)v; return __builtin_bit_cast(bf16, h); }
+    return __float2bfloat16(v);
+}
+__device__ __forceinline__ float dec16(bf16 b, int f16) {
+    if (f16) return (float)__builtin_bit_cast(_Float16, b);
+    return __bfloat162float(b);
+}
+
+// out[c, r] = in[r, c] (optionally also the hi/lo split of in - in2), 64 x 64 tiles through LDS; blocked: the
+// outputs are kept in 16 x 32 blocks; f16: the outputs are IEEE half (the inputs are always bf16)
 __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__ in, const bf16* __restrict__ in2, long long ld_in,
                                                         int rows, int cols, bf16* __restrict__ out, bf16* __restrict__ out_hi,
-                                                        bf16* __restrict__ out_lo, long long ld_out, int blocked, int vec) {
+                                                        bf16* __restrict__ out_lo, long long ld_out, int blocked, int vec, int f16) {
     __shared__ float t0[64][65];
     __shared__ float t1[64][65];
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
@@ -52,10 +64,10 @@ __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__
             union { uint4 u; bf16 b[8]; } x, hi, lo;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                x.b[j] = __float2bfloat16(t0[r + j][c]);
+                x.b[j] = enc16(t0[r + j][c], f16);
                 const float dlt = t1[r + j][c];
-                hi.b[j] = __float2bfloat16(dlt);
-                lo.b[j] = __float2bfloat16(dlt - __bfloat162float(hi.b[j]));
+                hi.b[j] = enc16(dlt, f16);
+                lo.b[j] = enc16(dlt - dec16(hi.b[j], f16), f16);
             }
             if (out) *(uint4*)(out + o) = x.u;
             if (out_hi) { *(uint4*)(out_hi + o) = hi.u; if (out_lo) *(uint4*)(out_lo + o) = lo.u; }
@@ -76,12 +88,12 @@ __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__
         const int c = i >> 6, r = i & 63;
         if (r0 + r < rows && c0 + c < cols) {
             const long long o = blocked ? tboa_blocked_offset(c0 + c, r0 + r, ld_out >> 5) : (long long)(c0 + c) * ld_out + r0 + r;
-            if (out) out[o] = __float2bfloat16(t0[r][c]);
+            if (out) out[o] = enc16(t0[r][c], f16);
             if (out_hi) {
                 const float dlt = t1[r][c];
-                const bf16 hi = __float2bfloat16(dlt);
+                const bf16 hi = enc16(dlt, f16);
                 out_hi[o] = hi;
-                if (out_lo) out_lo[o] = __float2bfloat16(dlt - __bfloat162float(hi));
+                if (out_lo) out_lo[o] = enc16(dlt - dec16(hi, f16), f16);
             }
         }
     }
@@ -229,10 +241,10 @@ __global__ __launch_bounds__(256) void int_form_kernel(const float* __restrict__
     if (threadIdx.x == 0) { step[blockIdx.x] = st; if (!all_ok || !(st > 0.f)) atomicOr(fail, 1); }
 }
 
-// V^T fp32 [rows, G*L] (times row_scale, if given) -> per-sequence segments of length L: (hi, lo) of V^T in segments
-// 0, 1 and, when the full-precision V~^T is given, V^T - V~^T in segment 2 and V~^T in segment 3
+// V^T fp32 [rows, G*L] (times row_scale, if given) -> per-sequence segments of length L: (hi, hi, lo) of V^T in segments
+// 0, 1, 2 and, when the full-precision V~^T is given, V^T - V~^T in segment 3 and V~^T in segment 4
 __global__ void vt_segments_kernel(const float* __restrict__ in, const float* __restrict__ row_scale, const float* __restrict__ in_fp,
-                                   bf16* __restrict__ out, int rows, int G, int L, int nseg, long long ld) {
+                                   bf16* __restrict__ out, int rows, int G, int L, int nseg, long long ld, int f16) {
     const long long tot = (long long)rows * G * L;
     if (L % 4 == 0 && ld % 4 == 0 && ((uintptr_t)out & 7) == 0) {     // four consecutive tokens per thread: 16-byte streaming loads, 8-byte stores
         typedef float f4 __attribute__((ext_vector_type(4)));
@@ -245,30 +257,31 @@ __global__ void vt_segments_kernel(const float* __restrict__ in, const float* __
             union { bf16 b[4]; uint2 u; } h, l, dv, wf;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                h.b[j] = __float2bfloat16(v[j]); l.b[j] = __float2bfloat16(v[j] - __bfloat162float(h.b[j]));
-                dv.b[j] = __float2bfloat16(v[j] - w[j]); wf.b[j] = __float2bfloat16(w[j]);
+                h.b[j] = enc16(v[j], f16); l.b[j] = enc16(v[j] - dec16(h.b[j], f16), f16);
+                dv.b[j] = enc16(v[j] - w[j], f16); wf.b[j] = enc16(w[j], f16);
             }
             bf16* o = out + row * ld + ((long long)s * nseg) * L + t;
-            *(uint2*)o = h.u; *(uint2*)(o + L) = l.u;
-            if (in_fp) { *(uint2*)(o + 2 * L) = dv.u; *(uint2*)(o + 3 * L) = wf.u; }
+            *(uint2*)o = h.u; *(uint2*)(o + L) = h.u; *(uint2*)(o + 2 * L) = l.u;
+            if (in_fp) { *(uint2*)(o + 3 * L) = dv.u; *(uint2*)(o + 4 * L) = wf.u; }
         }
         return;
     }
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < tot; i += (long long)gridDim.x * blockDim.x) {
         const long long row = i / ((long long)G * L); const int s = (int)((i / L) % G), t = (int)(i % L);
         const float v = row_scale ? in[i] * row_scale[row] : in[i];
-        const bf16 h = __float2bfloat16(v);
+        const bf16 h = enc16(v, f16);
         bf16* o = out + row * ld + ((long long)s * nseg) * L + t;
-        o[0] = h; o[L] = __float2bfloat16(v - __bfloat162float(h));
-        if (in_fp) { const float w = in_fp[i]; o[2 * L] = __float2bfloat16(v - w); o[3 * L] = __float2bfloat16(w); }
+        o[0] = h; o[L] = h; o[2 * L] = enc16(v - dec16(h, f16), f16);
+        if (in_fp) { const float w = in_fp[i]; o[3 * L] = enc16(v - w, f16); o[4 * L] = enc16(w, f16); }
     }
 }
 
-// P[t, c*L + k] = A[t, k] for c < copies, A = softmax over the first t+1 (causal) or L entries of the score row; with a
+// P[t, k] = A[t, k] (and once more at column hi2col + k, and its low part A - P[t, k] at locol + k, when those are not
+// negative), A = softmax over the first t+1 (causal) or L entries of the score row; with a
 // second score matrix S2 also P[t, dcol + k] = A[t, k] - A2[t, k], the difference taken in fp32 before rounding.
 // Zero up to the next multiple of 256 (the k-loop of the consumer stops there).  One wavefront per row, y = head.
 __global__ __launch_bounds__(256) void softmax_bf16_kernel(const float* __restrict__ S, const float* __restrict__ S2, int L, int causal,
-                                                           bf16* __restrict__ P, long long ldp, long long head_stride, int copies, int dcol) {
+                                                           bf16* __restrict__ P, long long ldp, long long head_stride, int hi2col, int locol, int dcol, int f16) {
     const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= L) return;
     const long long so = ((long long)blockIdx.y * L + t) * L;
@@ -287,9 +300,11 @@ __global__ __launch_bounds__(256) void softmax_bf16_kernel(const float* __restri
     const float inv = 1.f / sum, inv2 = s2 ? 1.f / sum2 : 0.f;
     for (int k = lane; k < kz; k += 64) {
         const float a = k < kend ? __expf(s[k] - m) * inv : 0.f;
-        const bf16 v = __float2bfloat16(a);
-        for (int c = 0; c < copies; ++c) p[(long long)c * L + k] = v;
-        if (s2) p[dcol + k] = __float2bfloat16(k < kend ? a - __expf(s2[k] - m2) * inv2 : 0.f);
+        const bf16 v = enc16(a, f16);
+        p[k] = v;
+        if (hi2col >= 0) p[hi2col + k] = v;
+        if (locol >= 0) p[locol + k] = enc16(a - dec16(v, f16), f16);
+        if (s2) p[dcol + k] = enc16(k < kend ? a - __expf(s2[k] - m2) * inv2 : 0.f, f16);
     }
 }
 
@@ -298,8 +313,8 @@ __global__ __launch_bounds__(256) void softmax_bf16_kernel(const float* __restri
 // is taken once, and the probabilities leave as 8-byte stores.
 template <int NCH>
 __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __restrict__ S, const float* __restrict__ S2, int L, int causal,
-                                                                bf16* __restrict__ P, long long ldp, long long head_stride, int copies, int dcol,
-                                                                int blocked) {
+                                                                bf16* __restrict__ P, long long ldp, long long head_stride, int hi2col, int locol, int dcol,
+                                                                int blocked, int f16) {
     const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= L) return;
     // heads from the last to the first: the score product wrote them in ascending order, so the last ones are the part of the
@@ -346,21 +361,147 @@ __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __r
     for (int c = 0; c < NCH; ++c) {
         const int k = c * 256 + lane * 4;
         if (k >= kz) continue;
-        union { bf16 h[4]; uint2 u; } pa, pd;
+        union { bf16 h[4]; uint2 u; } pa, pl, pd;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float a = v[c][i] * inv;
-            pa.h[i] = __float2bfloat16(a);
-            pd.h[i] = __float2bfloat16(s2 ? a - w[c][i] * inv2 : 0.f);
+            pa.h[i] = enc16(a, f16);
+            pl.h[i] = enc16(a - dec16(pa.h[i], f16), f16);
+            pd.h[i] = enc16(s2 ? a - w[c][i] * inv2 : 0.f, f16);
         }
         if (blocked) {     // the head's [L, ldp] matrix in 16 x 32 blocks: 4 consecutive columns stay together
-            for (int cp = 0; cp < copies; ++cp) *(uint2*)(p + tboa_blocked_offset(t, (long long)cp * L + k, ldp >> 5)) = pa.u;
+            *(uint2*)(p + tboa_blocked_offset(t, k, ldp >> 5)) = pa.u;
+            if (hi2col >= 0) *(uint2*)(p + tboa_blocked_offset(t, (long long)hi2col + k, ldp >> 5)) = pa.u;
+            if (locol >= 0) *(uint2*)(p + tboa_blocked_offset(t, (long long)locol + k, ldp >> 5)) = pl.u;
             if (s2) *(uint2*)(p + tboa_blocked_offset(t, dcol + k, ldp >> 5)) = pd.u;
         } else {
-            for (int cp = 0; cp < copies; ++cp) *(uint2*)(p + (long long)cp * L + k) = pa.u;
+            *(uint2*)(p + k) = pa.u;
+            if (hi2col >= 0) *(uint2*)(p + hi2col + k) = pa.u;
+            if (locol >= 0) *(uint2*)(p + locol + k) = pl.u;
             if (s2) *(uint2*)(p + dcol + k) = pd.u;
         }
     }
+}
+
+// Transposed probabilities, for the form of the W_V Hessian that sums over the query heads of a KV group before the wide
+// products:  Pt[g][i][r L + t] = A_h[t, i] and dPt[g][i][r L + t] = A_h[t, i] - A~_h[t, i] with h = g rep + r, each as an
+// exact-to-twice-the-mantissa (hi, lo) pair of 16-bit values; every [L, rep L (+ pad)] matrix of a group is kept in
+// 16 x 32 blocks.  One workgroup per (64 rows t, head): the statistics of its rows first (one pass, running maximum and
+// rescaled sum; a wavefront takes 16 rows), then the 64 x 64 pieces of the scores are read again, turned into
+// probabilities and written transposed through LDS.  The rows i up to the end of the 256-tile that holds t are written,
+// zeros beyond the diagonal: a product that starts its contraction at the 256-tile of its rows and columns
+// (TBOA_GEMM_KLO) reads nothing else.  Causal scores with valid lower 256-tiles, L a multiple of 256.
+struct PtOut { bf16 *hi, *lo, *dhi, *dlo; };     // dhi, dlo: nullptr without a second score matrix
+
+__global__ __launch_bounds__(256) void softmax_t_kernel(const float* __restrict__ S, const float* __restrict__ S2, int L, int rep,
+                                                        PtOut out, long long ldp, long long group_stride, int f16) {
+    __shared__ float st[4][64];                                      // max, 1 / sum of the two score matrices, per row
+    __shared__ __attribute__((aligned(16))) bf16 tp[4][64][72];      // [part][i][t]: hi, lo of A, hi, lo of A - A~; rows of 144 bytes
+    const int h = gridDim.y - 1 - blockIdx.y, t0 = blockIdx.x * 64;      // heads from the last: their scores were written last
+    const int g = h / rep, r = h % rep;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float* s = S + (long long)h * L * L;
+    const float* s2 = S2 ? S2 + (long long)h * L * L : nullptr;
+    for (int rr = 0; rr < 16; ++rr) {
+        const int tl = wave * 16 + rr, t = t0 + tl;
+        const float* row = s + (long long)t * L; const float* row2 = s2 ? s2 + (long long)t * L : nullptr;
+        float m = -INFINITY, sum = 0.f, m2 = -INFINITY, sum2 = 0.f;
+        for (int k = lane; k <= t; k += 64) {
+            const float v = row[k];
+            if (v > m) { sum = sum * __expf(m - v) + 1.f; m = v; } else sum += __expf(v - m);
+            if (row2) { const float w = row2[k]; if (w > m2) { sum2 = sum2 * __expf(m2 - w) + 1.f; m2 = w; } else sum2 += __expf(w - m2); }
+        }
+        float M = m, M2 = m2;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) { M = fmaxf(M, __shfl_xor(M, o, 64)); M2 = fmaxf(M2, __shfl_xor(M2, o, 64)); }
+        sum = (m == -INFINITY) ? 0.f : sum * __expf(m - M);
+        sum2 = (m2 == -INFINITY) ? 0.f : sum2 * __expf(m2 - M2);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) { sum += __shfl_xor(sum, o, 64); sum2 += __shfl_xor(sum2, o, 64); }
+        if (lane == 0) { st[0][tl] = M; st[1][tl] = 1.f / sum; st[2][tl] = M2; st[3][tl] = row2 ? 1.f / sum2 : 0.f; }
+    }
+    __syncthreads();
+    bf16* dst[4] = {out.hi + g * group_stride, out.lo + g * group_stride, out.dhi ? out.dhi + g * group_stride : nullptr,
+                    out.dlo ? out.dlo + g * group_stride : nullptr};
+    const int nparts = s2 ? 4 : 2;
+    const int iend = min(L, (t0 / 256 + 1) * 256);
+    const int tr = threadIdx.x >> 2, kc = (threadIdx.x & 3) * 16, t = t0 + tr;
+    const float m = st[0][tr], inv = st[1][tr], m2 = st[2][tr], inv2 = st[3][tr];
+    for (int i0 = 0; i0 < iend; i0 += 64) {
+        if (i0 <= t0) {     // the piece holds entries on or left of the diagonal
+            typedef float f4 __attribute__((ext_vector_type(4)));
+            const float* src = s + (long long)t * L + i0 + kc;
+            const float* src2 = s2 ? s2 + (long long)t * L + i0 + kc : nullptr;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4 v = *(const f4*)(src + 4 * q);
+                f4 w = {0.f, 0.f, 0.f, 0.f};
+                if (src2) w = *(const f4*)(src2 + 4 * q);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = i0 + kc + 4 * q + e;
+                    const float a = i <= t ? __expf(v[e] - m) * inv : 0.f;
+                    const bf16 ah = enc16(a, f16);
+                    tp[0][kc + 4 * q + e][tr] = ah;
+                    tp[1][kc + 4 * q + e][tr] = enc16(a - dec16(ah, f16), f16);
+                    if (src2) {
+                        const float da = a - (i <= t ? __expf(w[e] - m2) * inv2 : 0.f);
+                        const bf16 dh = enc16(da, f16);
+                        tp[2][kc + 4 * q + e][tr] = dh;
+                        tp[3][kc + 4 * q + e][tr] = enc16(da - dec16(dh, f16), f16);
+                    }
+                }
+            }
+        } else {
+            const bf16 zero = enc16(0.f, f16);
+            for (int pt = 0; pt < nparts; ++pt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) tp[pt][kc + e][tr] = zero;
+        }
+        __syncthreads();
+        {   // thread: row i0 + tr of the piece, 16 consecutive t from kc: two 16-byte chunks of a block row
+            const long long col = (long long)r * L + t0 + kc;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const long long o = tboa_blocked_offset(i0 + tr, col + 8 * q, ldp >> 5);
+                for (int pt = 0; pt < nparts; ++pt) *(uint4*)(dst[pt] + o) = *(const uint4*)&tp[pt][tr][kc + 8 * q];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// [B1 | B2^T] of a group, fp32 row-major [L, L] each, -> the blocked 16-bit operand [B1_hi | B1_lo | B2^T_hi | B2^T_lo]
+// (or [B1_hi | B1_lo] without B2): element (i, seg L + j); four consecutive columns per thread
+__global__ void bcat_kernel(const float* __restrict__ B1, const float* __restrict__ B2, int L, bf16* __restrict__ out, long long ldb,
+                            long long group_stride, int f16) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const long long nn = (long long)L * L, tot4 = nn / 4;
+    const int g = blockIdx.y;
+    bf16* o = out + g * group_stride;
+    for (long long i4 = blockIdx.x * (long long)blockDim.x + threadIdx.x; i4 < tot4; i4 += (long long)gridDim.x * blockDim.x) {
+        const long long e = 4 * i4; const int i = (int)(e / L), j = (int)(e % L);
+        for (int which = 0; which < (B2 ? 2 : 1); ++which) {
+            const f4 v = __builtin_nontemporal_load((const f4*)((which ? B2 : B1) + g * nn + e));
+            union { bf16 b[4]; uint2 u; } hi, lo;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { hi.b[k] = enc16(v[k], f16); lo.b[k] = enc16(v[k] - dec16(hi.b[k], f16), f16); }
+            *(uint2*)(o + tboa_blocked_offset(i, (2LL * which) * L + j, ldb >> 5)) = hi.u;
+            *(uint2*)(o + tboa_blocked_offset(i, (2LL * which + 1) * L + j, ldb >> 5)) = lo.u;
+        }
+    }
+}
+
+// largest |x| of a bf16 array, as the bits of a non-negative float (atomicMax on the integer)
+__global__ void absmax_bf16_kernel(const bf16* __restrict__ x, long long n, int* __restrict__ out) {
+    float m = 0.f;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+        const float v = fabsf(__bfloat162float(x[i]));
+        m = (v > m || !(v == v)) ? (v == v ? v : INFINITY) : m;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    if ((threadIdx.x & 63) == 0) atomicMax(out, __float_as_int(m));
 }
 
 // out = scale * sum_s partial[s] (fp64 accumulation); lower: only r >= c is read, the result is mirrored.
@@ -462,28 +603,43 @@ inline unsigned g1(long long n) { long long g = (n + 255) / 256; return (unsigne
 struct Dims {
     tboa_ctx* ctx; const tboa_attn_desc* d;
     int T, dm, Hq, Hkv, dh, L, S, rep, dq, dkv;
+    int f16;      // the 16-bit operands of the W_V / W_O chains are IEEE half (else bf16)
 };
 
 Dims dims_of(tboa_ctx* ctx, const tboa_attn_desc* d) {
     return Dims{ctx, d, d->n_seqs * d->seq_len, d->d_model, d->n_q_heads, d->n_kv_heads, d->head_dim, d->seq_len, d->n_seqs,
-                d->n_q_heads / d->n_kv_heads, d->n_q_heads * d->head_dim, d->n_kv_heads * d->head_dim};
+                d->n_q_heads / d->n_kv_heads, d->n_q_heads * d->head_dim, d->n_kv_heads * d->head_dim, 0};
 }
 
 // Q^ and K^ (the three-segment operands of the score products) are kept per (sequence, head) in 16 x 32 blocks when the
 // shapes allow it: whole 1 KB blocks instead of 64-byte row pieces at a pitch of all heads
-bool qk_blocked(const Dims& D) { return D.L % 16 == 0 && (3 * D.dh) % 32 == 0 && !getenv("TBOA_NO_BLOCKED_QK"); }
+bool qk_blocked(const Dims& D) { return D.L % 16 == 0 && (3 * D.dh) % 32 == 0; }
 
 int pick_splits(int n_seqs) {
     for (int s = 16; s > 1; --s) if (n_seqs % s == 0) return s;
     return 1;
 }
 
+// Whether the activations fit IEEE half (|x| < 2^15, finite): one reduction over each array, one read-back.
+int fits_half(tboa_ctx* ctx, const bf16* X, const bf16* X_fp, long long n, int* fits) {
+    int* w = ctx->d_status + 5;
+    TB_HIP(ctx, hipMemsetAsync(w, 0, sizeof(int), ctx->stream));
+    hipLaunchKernelGGL(absmax_bf16_kernel, dim3(2048), dim3(256), 0, ctx->stream, X, n, w);
+    if (X_fp) hipLaunchKernelGGL(absmax_bf16_kernel, dim3(2048), dim3(256), 0, ctx->stream, X_fp, n, w);
+    TB_KERNEL_CHECK(ctx);
+    TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 5, w, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    float m; memcpy(&m, ctx->h_status + 5, sizeof(float));
+    *fits = (m < 32768.f) ? 1 : 0;
+    return 0;
+}
+
 int transpose(const Dims& D, const bf16* in, const bf16* in2, long long ld_in, int rows, int cols, bf16* out, bf16* hi, bf16* lo, long long ld_out,
-              int blocked = 0) {
+              int blocked = 0, int f16 = 0) {
     auto al = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
     const int vec = ld_in % 8 == 0 && ld_out % 8 == 0 && al(in) && al(in2) && al(out) && al(hi) && al(lo);
     hipLaunchKernelGGL(transpose_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, D.ctx->stream, in, in2, ld_in, rows, cols,
-                       out, hi, lo, ld_out, blocked, vec);
+                       out, hi, lo, ld_out, blocked, vec, f16);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
 }
@@ -499,16 +655,20 @@ GemmBf16 nt(int M, int N, int K, float alpha, const bf16* A, long long lda, cons
     return g;
 }
 
-// out[n, n] = scale * A B^T with the contraction over all T tokens split into `splits` chunks
-int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_lo, const bf16* B, long long ld, int K, double scale, int lower,
-                float* part, float* out) {
+// out[n, n] = scale * sum over the operand pairs p of A_p B_p^T, with the contraction over all T tokens split into `splits`
+// chunks (an exact-to-16-bit (hi, lo) operand takes part as several pairs: hi.hi + lo.hi + hi.lo)
+struct GramPair { const bf16* A; const bf16* B; };
+int gram_splitk(tboa_ctx* ctx, int splits, int n, int npairs, const GramPair* pairs, long long ld, int K, double scale, int lower,
+                float* part, float* out, int f16 = 0) {
     const int Kc = K / splits;
-    GemmBf16 g = nt(n, n, Kc, 1.f, A, ld, B, ld, part, n, TBOA_F32, 0, lower ? TBOA_GEMM_LOWER : 0);
+    GemmBf16 g = nt(n, n, Kc, 1.f, pairs[0].A, ld, pairs[0].B, ld, part, n, TBOA_F32, 0, (lower ? TBOA_GEMM_LOWER : 0) | (f16 ? TBOA_GEMM_F16 : 0));
     g.tag = TBOA_PROF_GRAM; g.flags &= ~TBOA_GEMM_PERSISTENT;
     g.batch = splits; g.strideA = Kc; g.strideB = Kc; g.strideC = (long long)n * n;
     if (lower) TB_TRY(launch_fill_f32(ctx, part, (int64_t)splits * n * n, 0.f));
-    TB_TRY(gemm_bf16_nt(ctx, g));
-    if (A_lo) { g.A = A_lo; g.accumulate = 1; TB_TRY(gemm_bf16_nt(ctx, g)); }
+    for (int p = 0; p < npairs; ++p) {
+        g.A = pairs[p].A; g.B = pairs[p].B; g.accumulate = p ? 1 : 0;
+        TB_TRY(gemm_bf16_nt(ctx, g));
+    }
     const bool aligned16 = (((uintptr_t)part | (uintptr_t)out) & 15) == 0;
     const int vec = (!lower && aligned16 && ((long long)n * n) % 4 == 0) ? 1 : 0;
     if (lower) {
@@ -519,6 +679,11 @@ int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_l
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3(g1((long long)n * n / (vec ? 4 : 1))), dim3(256), 0, ctx->stream, part, splits, n, scale, lower, out, vec);
     TB_HIP(ctx, hipGetLastError());
     return 0;
+}
+int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_lo, const bf16* B, long long ld, int K, double scale, int lower,
+                float* part, float* out) {
+    const GramPair pairs[2] = {{A, B}, {A_lo, B}};
+    return gram_splitk(ctx, splits, n, A_lo ? 2 : 1, pairs, ld, K, scale, lower, part, out);
 }
 
 // Q^ [rows, Hq, 3 dh] and K^ [rows, Hkv, 3 dh] of `rows` tokens Xr [rows, d]; weights as one or two (hi, lo) bf16 terms
@@ -556,7 +721,7 @@ int scores(const Dims& D, const bf16* Qh, const bf16* Kh, int sl, float* Sc) {
 // where 36 x H leave the last round half empty.  (The path stride is the distance between the two buffers.)
 int scores_pair(const Dims& D, const bf16* Qh, const bf16* Kh, const bf16* Qhf, const bf16* Khf, int sl, float* Sc, float* Scf) {
     const long long dq = Qhf - Qh, dk = Khf - Kh, dc = Scf - Sc;
-    if (D.rep != 1 || dq % 8 || dk % 8 || dc % 4 || getenv("TBOA_NO_SCORES_PAIR")) {
+    if (D.rep != 1 || dq % 8 || dk % 8 || dc % 4) {
         TB_TRY(scores(D, Qh, Kh, sl, Sc));
         return scores(D, Qhf, Khf, sl, Scf);
     }
@@ -574,14 +739,14 @@ int scores_pair(const Dims& D, const bf16* Qh, const bf16* Kh, const bf16* Qhf, 
 }
 
 // probabilities in 16 x 32 blocks (per head) when `blocked`: see blocked_inputs
-int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long ldp, int copies, int dcol, int blocked = 0) {
+int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long ldp, int hi2col, int locol, int dcol, int blocked = 0) {
     if (D.L % 4 == 0 && D.L <= 2048 && ldp % 4 == 0 && dcol % 4 == 0)
         hipLaunchKernelGGL(softmax_bf16_regs_kernel<8>, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P,
-                           ldp, (long long)D.L * ldp, copies, dcol, blocked);
+                           ldp, (long long)D.L * ldp, hi2col, locol, dcol, blocked, D.f16);
     else if (blocked) return tboa_fail(D.ctx, TBOA_EINVAL, "softmax: blocked probabilities need the in-register kernel");
     else
         hipLaunchKernelGGL(softmax_bf16_kernel, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P, ldp,
-                           (long long)D.L * ldp, copies, dcol);
+                           (long long)D.L * ldp, hi2col, locol, dcol, D.f16);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
 }
@@ -589,7 +754,13 @@ int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long
 // The transposed activations and the probabilities are operands of the A X products only: they are kept in the GEMM's
 // 16 x 32 blocks when the shapes allow (whole blocks, the in-register softmax)
 bool blocked_inputs(const Dims& D) {
-    return D.L % 32 == 0 && D.L <= 2048 && D.dm % 16 == 0 && !getenv("TBOA_NO_BLOCKED_AX");
+    return D.L % 32 == 0 && D.L <= 2048 && D.dm % 16 == 0;
+}
+
+// The form of the W_V Hessian that works on L x L Gram matrices of the probabilities (see build_hessians_bf16): needs
+// whole 256-tiles and causal probabilities.  Other shapes take the per-head products.
+bool summed_form(const Dims& D) {
+    return D.d->causal && D.L % 256 == 0 && D.dm % 256 == 0;
 }
 
 int check_bf16_dims(const Dims& D) {
@@ -598,18 +769,39 @@ int check_bf16_dims(const Dims& D) {
     return 0;
 }
 
+// H_in and R of W_V for bf16 inputs (Table 1: X A_h^T A_h X^T, summed over the sequences and the query heads of the KV group).
+//
+// Summed form (summed_form: every named configuration):  sum_{h in g} (A_h X_s)^T (A_h X_s) = X_s^T (sum_h A_h^T A_h) X_s, so
+// the sum over the heads of a group is taken on L x L matrices and the products that are d wide run once per (sequence,
+// group), with the exact input X_s as one operand:
+//     B1 = sum_h A_h^T A_h,   B2^T = sum_h A_h^T (A_h - A~_h)         [L, L] per group, from transposed probabilities
+//     T1 = B1 X_s,   Z = B1 dX_s + B2^T X~_s                            [L, d]
+//     H_in^V[g] += T1^T X_s,   R_v[g] += alpha Z^T X_s                 summed over a chunk of sequences per launch
+// since sum_h (A_h X - A~_h X~)^T (A_h X) = sum_h (A_h dX + (A_h - A~_h) X~)^T A_h X.  Every intermediate (A, A - A~, B1, B2,
+// T1, Z) is carried as an exact-to-twice-the-mantissa (hi, lo) pair of 16-bit values and every product accumulates
+// hi.hi + lo.hi + hi.lo in fp32, so the result is fp32-grade (measured against fp64: 1e-6 of the diagonal).  A_h^T has
+// zeros above its diagonal, so the contractions over the tokens t start at the tile of max(i, j) (TBOA_GEMM_KLO).
+//
+// Per-head form (shapes without whole 256-tiles, or no causal mask):  Y_h = A_h X_s per (sequence, head), H_in^V += Y^T Y,
+// R_v += alpha dY^T Y with dY = A dX + (A - A~) X~; probabilities and Y are single 16-bit values there (1e-4-grade).
 int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, const bf16* X_fp, const bf16* Wq, const bf16* Wk,
                         const bf16* Wo, float* Hin_qk, float* R_qk, float* Hout_q, float* Hout_k, float* Hin_v, float* R_v, float* Hout_v,
                         bf16* fp_cache) {
-    const Dims D = dims_of(ctx, d);
+    Dims D = dims_of(ctx, d);
     TB_TRY(check_bf16_dims(D));
     const int T = D.T, dm = D.dm, Hq = D.Hq, Hkv = D.Hkv, dh = D.dh, L = D.L, dq = D.dq, dkv = D.dkv, rep = D.rep;
     const bool fp = X_fp != nullptr, rv = fp && R_v;
+    const bool grouped = summed_form(D);
     int G = d->seq_chunk > 0 ? d->seq_chunk : 8; if (G > D.S) G = D.S;
-    const int nsg = rv ? 2 : 1, nsx = rv ? 3 : 1, splits = pick_splits(D.S);   // segments of P / of the transposed chunk
+    // segments of P / of the transposed chunk ([X | dX | X~]; summed form: every one twice, for the (hi, lo) operands it meets)
+    const int nsg = rv ? 2 : 1, nsx = (grouped ? 2 : 1) * (rv ? 3 : 1), splits = pick_splits(D.S);
     const long long dd = (long long)dm * dm, hh = (long long)dh * dh, TP = (long long)T + PADE;
+    // summed form: pitches of the transposed probabilities, of [B1_hi | B1_lo | B2^T_hi | B2^T_lo], of the chunk buffers
+    const long long ldpt = (long long)rep * L + PADE, ldbc = (rv ? 4LL : 2LL) * L + PADE, ldg = (long long)G * L + PADE;
     bf16 *XT, *dXh, *dXl, *Qh, *Kh, *Qhf, *Khf, *P, *XcT, *YT, *dYT;
-    float *part, *Qf, *Kf, *Sc, *Scf;
+    bf16 *Bcat = nullptr, *XgT = nullptr, *YTl = nullptr, *dYTl = nullptr;
+    PtOut pt{nullptr, nullptr, nullptr, nullptr};
+    float *part, *Qf, *Kf, *Sc, *Scf, *B1f = nullptr, *B2f = nullptr;
     double *Hin64, *Wq64, *Wk64, *Wo64, *Tq, *Tk, *Ho;
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
@@ -620,9 +812,20 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         Qh = ar.get<bf16>((size_t)G * L * dq * 3); Kh = ar.get<bf16>((size_t)G * L * dkv * 3);
         Qhf = rv ? ar.get<bf16>((size_t)G * L * dq * 3) : nullptr; Khf = rv ? ar.get<bf16>((size_t)G * L * dkv * 3) : nullptr;
         Sc = ar.get<float>((size_t)Hq * L * L); Scf = rv ? ar.get<float>((size_t)Hq * L * L) : nullptr;
-        P = ar.get<bf16>((size_t)Hq * L * (nsg * L + PADE));
         XcT = ar.get<bf16>((size_t)dm * (G * nsx * L + PADE));
-        YT = ar.get<bf16>((size_t)Hkv * dm * (rep * G * L + PADE)); dYT = rv ? ar.get<bf16>((size_t)Hkv * dm * (rep * G * L + PADE)) : nullptr;
+        if (grouped) {
+            P = nullptr;
+            pt.hi = ar.get<bf16>((size_t)Hkv * L * ldpt); pt.lo = ar.get<bf16>((size_t)Hkv * L * ldpt);
+            pt.dhi = rv ? ar.get<bf16>((size_t)Hkv * L * ldpt) : nullptr; pt.dlo = rv ? ar.get<bf16>((size_t)Hkv * L * ldpt) : nullptr;
+            B1f = ar.get<float>((size_t)Hkv * L * L); B2f = rv ? ar.get<float>((size_t)Hkv * L * L) : nullptr;
+            Bcat = ar.get<bf16>((size_t)Hkv * L * ldbc);
+            XgT = ar.get<bf16>((size_t)dm * ldg);
+            YT = ar.get<bf16>((size_t)Hkv * dm * ldg); YTl = ar.get<bf16>((size_t)Hkv * dm * ldg);
+            dYT = rv ? ar.get<bf16>((size_t)Hkv * dm * ldg) : nullptr; dYTl = rv ? ar.get<bf16>((size_t)Hkv * dm * ldg) : nullptr;
+        } else {
+            P = ar.get<bf16>((size_t)Hq * L * (nsg * L + PADE));
+            YT = ar.get<bf16>((size_t)Hkv * dm * (rep * G * L + PADE)); dYT = rv ? ar.get<bf16>((size_t)Hkv * dm * (rep * G * L + PADE)) : nullptr;
+        }
         Hin64 = ar.get<double>((size_t)dd); Wq64 = ar.get<double>((size_t)dq * dm); Wk64 = ar.get<double>((size_t)dkv * dm);
         Wo64 = ar.get<double>((size_t)dm * dq); Tq = ar.get<double>((size_t)dq * dm); Tk = ar.get<double>((size_t)dkv * dm);
         Ho = ar.get<double>((size_t)Hkv * hh);
@@ -673,11 +876,13 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     }
     // ---- H_in (and R) of W_V
     if (!Hin_v) return 0;
+    TB_TRY(fits_half(ctx, X, rv ? X_fp : nullptr, (long long)T * dm, &D.f16));
+    const int hf = D.f16 ? TBOA_GEMM_F16 : 0;
     TB_TRY(launch_fill_f32(ctx, Hin_v, (int64_t)Hkv * dd, 0.f));
     if (rv) TB_TRY(launch_fill_f32(ctx, R_v, (int64_t)Hkv * dd, 0.f));
     const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
-    const bool blocked = dm % 256 == 0 && L % 256 == 0 && !getenv("TBOA_NO_BLOCKED_Y");
-    const int bin = blocked_inputs(D);
+    const bool blocked = dm % 256 == 0 && L % 256 == 0;
+    const int bin = grouped ? 1 : blocked_inputs(D);      // (the grouped form has whole blocks by its own conditions)
     for (int s0 = 0; s0 < D.S; s0 += G) {
         const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
         const long long t0 = (long long)s0 * L;
@@ -691,30 +896,84 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         for (int sl = 0; sl < Gc; ++sl) {   // XcT[:, sl, :, :] = X_s^T | (X_s - X~_s)^T | X~_s^T
             const bf16* xs = X + (t0 + (long long)sl * L) * dm;
             bf16* o = XcT + is * sl * nsx * L;
-            if (!rv) TB_TRY(transpose(D, xs, nullptr, dm, L, dm, o, nullptr, nullptr, ldx, bin));
+            if (grouped) {      // [X | X | dX | dX | X~ | X~], and X_s^T once more as bf16 (the exact input), the chunk's sequences side by side
+                const bf16* xf = rv ? X_fp + (t0 + (long long)sl * L) * dm : nullptr;
+                for (int c = 0; c < 2; ++c) {
+                    TB_TRY(transpose(D, xs, xf, dm, L, dm, o + 16LL * c * L, rv ? o + 16LL * (2 + c) * L : nullptr, nullptr, ldx, 1, D.f16));
+                    if (rv) TB_TRY(transpose(D, xf, nullptr, dm, L, dm, o + 16LL * (4 + c) * L, nullptr, nullptr, ldx, 1, D.f16));
+                }
+                TB_TRY(transpose(D, xs, nullptr, dm, L, dm, XgT + 16LL * sl * L, nullptr, nullptr, ldg, 1, 0));
+            } else if (!rv) TB_TRY(transpose(D, xs, nullptr, dm, L, dm, o, nullptr, nullptr, ldx, bin, D.f16));
             else {
                 const bf16* xf = X_fp + (t0 + (long long)sl * L) * dm;
-                TB_TRY(transpose(D, xs, xf, dm, L, dm, o, o + is * L, nullptr, ldx, bin));
-                TB_TRY(transpose(D, xf, nullptr, dm, L, dm, o + is * 2 * L, nullptr, nullptr, ldx, bin));
+                TB_TRY(transpose(D, xs, xf, dm, L, dm, o, o + is * L, nullptr, ldx, bin, D.f16));
+                TB_TRY(transpose(D, xf, nullptr, dm, L, dm, o + is * 2 * L, nullptr, nullptr, ldx, bin, D.f16));
             }
+        }
+        if (grouped) {
+            const int tiled = TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED;
+            for (int sl = 0; sl < Gc; ++sl) {
+                if (rv) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
+                else TB_TRY(scores(D, Qh, Kh, sl, Sc));
+                hipLaunchKernelGGL(softmax_t_kernel, dim3(L / 64, Hq), dim3(256), 0, st, Sc, rv ? Scf : nullptr, L, rep, pt, ldpt,
+                                   (long long)L * ldpt, D.f16);
+                TB_KERNEL_CHECK(ctx);
+                // B1 = sum_h A_h^T A_h and B2^T = sum_h A_h^T (A_h - A~_h): contraction over (head of the group, t >= max(i, j)),
+                // three products of (hi, lo) parts each, accumulated in fp32
+                GemmBf16 b = nt(L, L, rep * L, 1.f, pt.hi, ldpt, pt.hi, ldpt, B1f, L, TBOA_F32, 0, tiled | TBOA_GEMM_KLO | hf);
+                b.kseg = L; b.batch = Hkv; b.strideA = (long long)L * ldpt; b.strideB = b.strideA; b.strideC = (long long)L * L; b.tag = TBOA_PROF_ATA;
+                const bf16* lefts[3] = {pt.hi, pt.lo, pt.hi};
+                const bf16* rights1[3] = {pt.hi, pt.hi, pt.lo};
+                const bf16* rights2[3] = {pt.dhi, pt.dhi, pt.dlo};
+                for (int term = 0; term < 3; ++term) {
+                    b.A = lefts[term]; b.B = rights1[term]; b.C = B1f; b.accumulate = term ? 1 : 0;
+                    TB_TRY(gemm_bf16_nt(ctx, b));
+                    if (rv) { b.B = rights2[term]; b.C = B2f; TB_TRY(gemm_bf16_nt(ctx, b)); }
+                }
+                hipLaunchKernelGGL(bcat_kernel, dim3(1024, Hkv), dim3(256), 0, st, B1f, B2f, L, Bcat, ldbc, (long long)L * ldbc, D.f16);
+                TB_KERNEL_CHECK(ctx);
+                // T1^T = [X_s^T | X_s^T] [B1_hi | B1_lo]^T and Z^T = [dX_s^T | dX_s^T | X~_s^T | X~_s^T] [B1_hi | B1_lo | B2^T_hi | B2^T_lo]^T,
+                // each left as a (hi, lo) pair of bf16
+                GemmBf16 y = nt(dm, L, 2 * L, 1.f, XcT + 16LL * sl * nsx * L, ldx, Bcat, ldbc, YT + 16LL * sl * L, ldg, TBOA_BF16, 0,
+                                tiled | TBOA_GEMM_C_TILED | TBOA_GEMM_C_HILO | hf);
+                y.C2 = YTl + 16LL * sl * L;
+                y.batch = Hkv; y.strideA = 0; y.strideB = (long long)L * ldbc; y.strideC = (long long)dm * ldg; y.tag = TBOA_PROF_AX;
+                TB_TRY(gemm_bf16_nt(ctx, y));
+                if (rv) {
+                    y.A = XcT + 16LL * ((long long)sl * nsx + 2) * L; y.K = 4 * L; y.C = dYT + 16LL * sl * L; y.C2 = dYTl + 16LL * sl * L;
+                    TB_TRY(gemm_bf16_nt(ctx, y));
+                }
+            }
+            // over the chunk: H_in^V[g] += (T1_hi + T1_lo)^T X,  R_v[g] += alpha (Z_hi + Z_lo)^T X   (bf16 operands: X is exact)
+            GemmBf16 h = nt(dm, dm, Gc * L, 1.f, YT, ldg, XgT, ldg, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER | tiled);
+            h.batch = Hkv; h.strideA = (long long)dm * ldg; h.strideB = 0; h.strideC = dd; h.tag = TBOA_PROF_HV_SYRK;
+            h.flags &= ~TBOA_GEMM_PERSISTENT;
+            TB_TRY(gemm_bf16_nt(ctx, h));
+            h.A = YTl; TB_TRY(gemm_bf16_nt(ctx, h));
+            if (rv) {
+                h.tag = TBOA_PROF_RV; h.C = R_v; h.flags = tiled; h.alpha = (float)d->alpha;
+                h.A = dYT; TB_TRY(gemm_bf16_nt(ctx, h));
+                h.A = dYTl; TB_TRY(gemm_bf16_nt(ctx, h));
+            }
+            continue;
         }
         for (int sl = 0; sl < Gc; ++sl) {
             // P = [A | A - A~];  Y^T = X_s^T A^T;  (Y - Y~)^T = [dX_s^T | X~_s^T] [A | A - A~]^T  since  A X - A~ X~ = A dX + (A - A~) X~
             if (rv) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
             else TB_TRY(scores(D, Qh, Kh, sl, Sc));
-            TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, ldp, 1, L, bin));
+            TB_TRY(softmax(D, Sc, rv ? Scf : nullptr, P, ldp, -1, -1, L, bin));
             // Y^T and (Y - Y~)^T are read only by the two products below: with whole 256 x 256 tiles they are written in the
             // blocked layout of the GEMM (column offset c -> pointer offset 16 c), whose blocks those products load whole
             const long long cs = blocked ? 16 : 1;
             GemmBf16 y = nt(dm, L, L, 1.f, XcT + is * sl * nsx * L, ldx, P, ldp, YT + cs * sl * L, ldy, TBOA_BF16, 0,
-                            cflag | (blocked ? TBOA_GEMM_C_TILED : 0) | (bin ? TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED : 0));
+                            cflag | hf | (blocked ? TBOA_GEMM_C_TILED : 0) | (bin ? TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED : 0));
             y.batch = Hq; y.batch_inner = rep; y.tag = TBOA_PROF_AX;
             y.strideB = (long long)rep * L * ldp; y.strideB2 = (long long)L * ldp;
             y.strideC = (long long)dm * ldy; y.strideC2 = cs * Gc * L;
             TB_TRY(gemm_bf16_nt(ctx, y));
             if (rv) { y.A = XcT + is * ((long long)sl * nsx + 1) * L; y.K = 2 * L; y.kseg = L; y.C = dYT + cs * sl * L; TB_TRY(gemm_bf16_nt(ctx, y)); }
         }
-        const int oflag = blocked ? (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED) : 0;
+        const int oflag = (blocked ? (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED) : 0) | hf;
         GemmBf16 h = nt(dm, dm, (int)ky, 1.f, YT, ldy, YT, ldy, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER | oflag);
         h.batch = Hkv; h.strideA = (long long)dm * ldy; h.strideB = h.strideA; h.strideC = dd; h.tag = TBOA_PROF_HV_SYRK;
         h.flags &= ~TBOA_GEMM_PERSISTENT;
@@ -728,17 +987,14 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
 // Operands for products with a dequantized weight W [rows, n] fp32: the integer form (hi = K, lo = NULL, *scale = step per
 // row) when every row has it, else the general exact-to-16-bits pair (hi, lo), *scale = NULL.  Synchronises once.
 int weight_operands(tboa_ctx* ctx, const float* W, int rows, int n, bf16* hi, bf16* lo, float* step, const bf16** lo_out, const float** scale) {
-    static const bool off = getenv("TBOA_NO_INT_FORM") != nullptr;
     int* flag = ctx->d_status + 4;
     *lo_out = lo; *scale = nullptr;
-    if (!off) {
-        TB_HIP(ctx, hipMemsetAsync(flag, 0, sizeof(int), ctx->stream));
-        hipLaunchKernelGGL(int_form_kernel, dim3(rows), dim3(256), 0, ctx->stream, W, n, hi, step, flag);
-        TB_KERNEL_CHECK(ctx);
-        TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 4, flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
-        TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        if (ctx->h_status[4] == 0) { *lo_out = nullptr; *scale = step; ++ctx->counters[TBOA_CTR_WEIGHTS_INT_FORM]; return 0; }
-    }
+    TB_HIP(ctx, hipMemsetAsync(flag, 0, sizeof(int), ctx->stream));
+    hipLaunchKernelGGL(int_form_kernel, dim3(rows), dim3(256), 0, ctx->stream, W, n, hi, step, flag);
+    TB_KERNEL_CHECK(ctx);
+    TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 4, flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->h_status[4] == 0) { *lo_out = nullptr; *scale = step; ++ctx->counters[TBOA_CTR_WEIGHTS_INT_FORM]; return 0; }
     ++ctx->counters[TBOA_CTR_WEIGHTS_HILO];
     hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)rows * n)), dim3(256), 0, ctx->stream, W, hi, lo, (long long)rows * n);
     TB_KERNEL_CHECK(ctx);
@@ -748,14 +1004,14 @@ int weight_operands(tboa_ctx* ctx, const float* W, int rows, int n, bf16* hi, bf
 int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, const bf16* X_fp, const float* Wq_deq,
                                 const float* Wk_deq, const float* Wv_deq, const bf16* Wq, const bf16* Wk, const bf16* Wv, float* Hin_o,
                                 float* R_o, const bf16* fp_cache) {
-    const Dims D = dims_of(ctx, d);
+    Dims D = dims_of(ctx, d);
     TB_TRY(check_bf16_dims(D));
     const int T = D.T, dm = D.dm, Hq = D.Hq, dh = D.dh, L = D.L, dq = D.dq, dkv = D.dkv, rep = D.rep;
     const bool fp = X_fp && R_o;
     int G = d->seq_chunk > 0 ? d->seq_chunk : 8; if (G > D.S) G = D.S;
-    const int nsg = fp ? 4 : 2, nsp = fp ? 3 : 2, splits = pick_splits(D.S);   // segments of V^T / of P
+    const int nsg = fp ? 5 : 3, nsp = fp ? 4 : 3, splits = pick_splits(D.S);   // segments of V^T / of P
     const long long TP = (long long)T + PADE, ldp = (long long)nsp * L + PADE;
-    bf16 *Wqh, *Wql, *Wkh, *Wkl, *Wvh, *Wvl, *Qh, *Kh, *Qhf, *Khf, *P, *VTc, *OT, *dOT;
+    bf16 *Wqh, *Wql, *Wkh, *Wkl, *Wvh, *Wvl, *Qh, *Kh, *Qhf, *Khf, *P, *VTc, *OT, *OTl, *dOT, *dOTl;
     float *Qf, *Kf, *VT32, *VT32f, *Sc, *Scf, *part, *steps;
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
@@ -768,7 +1024,8 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         Qhf = fp ? ar.get<bf16>((size_t)G * L * dq * 3) : nullptr; Khf = fp ? ar.get<bf16>((size_t)G * L * dkv * 3) : nullptr;
         Sc = ar.get<float>((size_t)Hq * L * L); P = ar.get<bf16>((size_t)Hq * L * ldp);
         VTc = ar.get<bf16>((size_t)dkv * (G * nsg * L + PADE));
-        OT = ar.get<bf16>((size_t)dq * TP); dOT = fp ? ar.get<bf16>((size_t)dq * TP) : nullptr;
+        OT = ar.get<bf16>((size_t)dq * TP); OTl = ar.get<bf16>((size_t)dq * TP);
+        dOT = fp ? ar.get<bf16>((size_t)dq * TP) : nullptr; dOTl = fp ? ar.get<bf16>((size_t)dq * TP) : nullptr;
         part = ar.get<float>((size_t)splits * dq * dq);
         steps = ar.get<float>((size_t)dq + 2 * dkv);
         if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
@@ -779,7 +1036,11 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
     TB_TRY(weight_operands(ctx, Wq_deq, dq, dm, Wqh, Wql, steps, &Wql_u, &sq));
     TB_TRY(weight_operands(ctx, Wk_deq, dkv, dm, Wkh, Wkl, steps + dq, &Wkl_u, &sk));
     TB_TRY(weight_operands(ctx, Wv_deq, dkv, dm, Wvh, Wvl, steps + dq + dkv, &Wvl_u, &sv));
-    const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
+    // half operands when the activations fit half; a value V = W_v x beyond the range of half (|x|_max ||w||_1 > 65504) would
+    // turn infinite there and surface as a non-finite Hessian, which tboa_quantize_layer rejects
+    TB_TRY(fits_half(ctx, X, fp ? X_fp : nullptr, (long long)T * dm, &D.f16));
+    const int hf = D.f16 ? TBOA_GEMM_F16 : 0;
+    const int cflag = (d->causal ? TBOA_GEMM_CAUSAL_K : 0) | hf;
     for (int s0 = 0; s0 < D.S; s0 += G) {
         const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
         const long long t0 = (long long)s0 * L, ldv = (long long)Gc * nsg * L + PADE;
@@ -796,36 +1057,36 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             } else TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
         }
         hipLaunchKernelGGL(vt_segments_kernel, dim3(g1((long long)dkv * Gc * L)), dim3(256), 0, st, VT32, sv, fp ? VT32f : nullptr, VTc, dkv, Gc, L,
-                           nsg, ldv);
+                           nsg, ldv, D.f16);
         TB_KERNEL_CHECK(ctx);
         for (int sl = 0; sl < Gc; ++sl) {
-            // V^T segments [V'hi | V'lo | V' - V~ | V~], P = [A' | A' | A' - A~]:
-            // O^T_h = [V'hi | V'lo] [A' | A']^T ;  (O - O~)^T_h = [V' - V~ | V~] [A' | A' - A~]^T
+            // V^T segments [V'hi | V'hi | V'lo | V' - V~ | V~], P = [A'hi | A'lo | A'hi | A' - A~]:
+            // O^T_h = [V'hi | V'hi | V'lo] [A'hi | A'lo | A'hi]^T ;  (O - O~)^T_h = [V' - V~ | V~] [A'hi | A' - A~]^T,
+            // both left as exact-to-16-bit (hi, lo) pairs of bf16
             if (fp) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
             else TB_TRY(scores(D, Qh, Kh, sl, Sc));
-            TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, ldp, 2, 2 * L));
-            GemmBf16 o = nt(dh, L, 2 * L, 1.f, VTc + (long long)sl * nsg * L, ldv, P, ldp, OT + t0 + (long long)sl * L, TP,
-                            TBOA_BF16, 0, cflag);
+            TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, ldp, 2 * L, L, 3 * L));
+            const long long co = t0 + (long long)sl * L;
+            GemmBf16 o = nt(dh, L, 3 * L, 1.f, VTc + (long long)sl * nsg * L, ldv, P, ldp, OT + co, TP, TBOA_BF16, 0, cflag | TBOA_GEMM_C_HILO);
+            o.C2 = OTl + co;
             o.kseg = L; o.batch = Hq; o.batch_inner = rep;
             o.strideA = (long long)dh * ldv; o.strideA2 = 0;
             o.strideB = (long long)rep * L * ldp; o.strideB2 = (long long)L * ldp;
             o.strideC = (long long)rep * dh * TP; o.strideC2 = (long long)dh * TP;
-            if (fp && rep == 1 && (dOT - OT) % 8 == 0 && !getenv("TBOA_NO_PV_PAIR")) {
-                // both products in one launch, the outer batch index choosing the pair of segments and the output: with one
-                // 256-wide tile per CU the launch lasts as long as its deepest causal tile, with two they pair up long and short
-                o.batch = 2 * Hq; o.batch_inner = Hq;
-                o.strideA = 2 * L; o.strideA2 = (long long)dh * ldv;
-                o.strideB = L; o.strideB2 = (long long)L * ldp;
-                o.strideC = dOT - OT; o.strideC2 = (long long)dh * TP;
+            TB_TRY(gemm_bf16_nt(ctx, o));
+            if (fp) {
+                o.A = VTc + ((long long)sl * nsg + 3) * L; o.B = P + 2 * L; o.K = 2 * L; o.C = dOT + co; o.C2 = dOTl + co;
                 TB_TRY(gemm_bf16_nt(ctx, o));
-            } else {
-                TB_TRY(gemm_bf16_nt(ctx, o));
-                if (fp) { o.A = VTc + ((long long)sl * nsg + 2) * L; o.B = P + L; o.C = dOT + t0 + (long long)sl * L; TB_TRY(gemm_bf16_nt(ctx, o)); }
             }
         }
     }
-    TB_TRY(gram_splitk(ctx, splits, dq, OT, nullptr, OT, TP, T, 1.0, 1, part, Hin_o));
-    if (fp) TB_TRY(gram_splitk(ctx, splits, dq, dOT, nullptr, OT, TP, T, d->alpha, 0, part, R_o));
+    // H_in^O = (O_hi + O_lo)^T (O_hi + O_lo), R_o = alpha (dO_hi + dO_lo)^T (O_hi + O_lo), without the lo.lo terms
+    const GramPair ho[3] = {{OT, OT}, {OTl, OT}, {OT, OTl}};
+    TB_TRY(gram_splitk(ctx, splits, dq, 3, ho, TP, T, 1.0, 1, part, Hin_o));
+    if (fp) {
+        const GramPair ro[3] = {{dOT, OT}, {dOTl, OT}, {dOT, OTl}};
+        TB_TRY(gram_splitk(ctx, splits, dq, 3, ro, TP, T, d->alpha, 0, part, R_o));
+    }
     return 0;
 }
 
@@ -1027,6 +1288,20 @@ extern "C" int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* 
     if (d->x_dtype == TBOA_F32) return build_hessian_out_proj_f64(ctx, d, X, X_fp, Wq_deq, Wk_deq, Wv_deq, Wq, Wk, Wv, Hin_o, R_o);
     return build_hessian_out_proj_bf16(ctx, d, (const bf16*)X, (const bf16*)X_fp, Wq_deq, Wk_deq, Wv_deq, (const bf16*)Wq, (const bf16*)Wk,
                                        (const bf16*)Wv, Hin_o, R_o, (const bf16*)fp_cache);
+}
+
+// The workspace the two Hessian builds of an attention block need: their own planning code, run on a host-only context that
+// stops at the point where a real call would reserve the workspace (no pointer is read before that).
+extern "C" size_t tboa_hessian_workspace_bytes(const tboa_attn_desc* d) {
+    tboa_ctx plan{};
+    plan.plan_only = 1;
+    if (check_attn_desc(&plan, d) != 0) return 0;
+    const void* in = (const void*)256; float* out = (float*)256;      // never dereferenced
+    int rc = tboa_build_hessians(&plan, d, in, in, in, in, in, in, out, out, out, out, out, out, out, nullptr);
+    if (rc != TB_PLAN_STOP) return 0;
+    rc = tboa_build_hessian_out_proj(&plan, d, in, in, out, out, out, in, in, in, out, out, nullptr);
+    if (rc != TB_PLAN_STOP) return 0;
+    return plan.plan_bytes;
 }
 
 extern "C" size_t tboa_fp_cache_bytes(const tboa_attn_desc* d) {

@@ -21,17 +21,21 @@ struct tboa_ctx {
     char err[768];
     void* ws;            // context-owned workspace
     size_t ws_bytes;
-    int* d_status;       // device status words (factorisation breakdown etc.)
+    int* d_status;       // device status words: [0..3] factorisation breakdown (two slots), [4] integer-form check,
+                         // [TB_GSTAT_WORD ..] bookkeeping of the two-phase grid search
     int* h_status;       // pinned host mirror
     hipStream_t aux;     // second stream (default priority) for work of one call that is independent of what `stream` does
     hipEvent_t ev_fork, ev_join;
     int prof_on;         // record HIP events around tagged GEMM launches
     std::vector<ProfRec> prof;
     long long counters[8];   // tboa_counter_id
+    int plan_only = 0;       // a host-only context of the workspace queries: tboa_ws_reserve records the request and stops the call
+    size_t plan_bytes = 0;
     std::vector<TileOrder> tile_orders;   // device tables owned by the context
     std::vector<TileSchedule> tile_schedules;
 };
 
+#define TB_GSTAT_WORD 8
 int tboa_fail(tboa_ctx* ctx, int code, const char* fmt, ...);
 
 #define TB_HIP(ctx, call)                                                                          \
@@ -64,6 +68,8 @@ struct Arena {
         return p;
     }
 };
+// returns TB_PLAN_STOP (not an error) on a plan-only context, after recording `bytes`
+#define TB_PLAN_STOP 1000
 int tboa_ws_reserve(tboa_ctx* ctx, size_t bytes);
 
 static inline int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -90,8 +96,12 @@ struct GemmF64 {
     // optional second pair of operands with the shapes, strides and batch strides of the first:
     // C = alpha (A B + A2 B2) + beta C in one pass (not combined with the contraction-range restrictions)
     const double* A2 = nullptr; const double* B2 = nullptr;
+    int tag = -1;   // tboa_prof_tag of this launch (timed with HIP events when profiling is on)
 };
 int gemm_f64(tboa_ctx* ctx, const GemmF64& g);
+// brackets a tagged launch with HIP events on the context's current stream when profiling is on
+int prof_begin(tboa_ctx* ctx, int tag, double flops, ProfRec& rec, bool& timed);
+int prof_end(tboa_ctx* ctx, const ProfRec& rec, bool timed);
 
 // ---------------------------------------------------------------- gemm_bf16.hip
 struct GemmBf16 {
@@ -100,12 +110,15 @@ struct GemmBf16 {
     const __hip_bfloat16* A; int64_t lda;
     const __hip_bfloat16* B; int64_t ldb;
     void* C; int64_t ldc; int c_dtype; int accumulate; int flags;
+    void* C2 = nullptr;   // with TBOA_GEMM_C_HILO: second 16-bit result buffer (the low parts), laid out as C
     int batch; int64_t strideA, strideB, strideC;
     // two-level batch: z -> (z / batch_inner, z % batch_inner); the *2 strides apply to the inner index
     int batch_inner = 1; int64_t strideA2 = 0, strideB2 = 0, strideC2 = 0;
     int tag = -1;   // tboa_prof_tag of this launch (timed with HIP events when profiling is on)
     int kseg = 0;   // > 0: K is a concatenation of K/kseg segments; TBOA_GEMM_CAUSAL_K then limits each segment
 };
+// internal flag: a 16-bit result leaves as an exact-to-16-bit pair of bf16 values (hi into C, lo into C2), whatever the operands
+#define TBOA_GEMM_C_HILO 0x10000
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
 
 // element offset of (r, c) in a matrix kept in the 16 x 32 blocks the bf16 GEMM can read and write (TBOA_GEMM_*_TILED);

@@ -226,39 +226,37 @@ __global__ __launch_bounds__(256) void rowdot_split_kernel(const float* __restri
     if (lane == 0) out[row] = 2.0 * s;
 }
 
-// per row: the candidates within tau of the approximate minimum, in increasing k (unused slots repeat the first);
-// a row with more than GRID_KS of them is appended to the overflow list (overflow[0] = count, then row numbers)
-constexpr int GRID_MAX_OVF = 96;    // rows per pass that may be re-evaluated exactly one by one
+// Device-side bookkeeping of the two-phase search, accumulated over every pass of a quantize_layer call and read once at
+// its end: [0] set when a pass could not be trusted as it stands (non-finite approximate cost, more near-minimal
+// candidates in a group of rows than the exact re-evaluation has room for), [1] near-minimal candidates evaluated exactly,
+// [2] the largest |approximate - exact| / |exact| seen, as the bits of a non-negative float.
+enum { GS_TRIPPED = 0, GS_SURVIVORS = 1, GS_MAXDEV = 2, GS_WORDS = 3 };
 
-__global__ void grid_select_kernel(const double* __restrict__ cost, int rows, int ncand, double tau, int* __restrict__ sel,
-                                   int* __restrict__ cnt_out, int* __restrict__ overflow) {
+// per row: the limit below which a candidate's approximate cost makes it a survivor, and the number of survivors that the
+// exact pass evaluates.  A row with a single survivor needs none (that candidate wins), except every eighth row, whose
+// exact cost is what the deviation guard of the pass measures.
+__global__ void grid_count_kernel(const double* __restrict__ cost, int rows, int ncand, double tau, double* __restrict__ lim_out,
+                                  int* __restrict__ cnt_out, int* __restrict__ gstat) {
     const int row = blockIdx.x * blockDim.x + threadIdx.x;
     if (row >= rows) return;
     const double* c = cost + (long long)row * ncand;
     double m = c[0];
-    for (int k = 1; k < ncand; ++k) m = fmin(m, c[k]);
+    bool bad = !(c[0] == c[0]);
+    for (int k = 1; k < ncand; ++k) { m = fmin(m, c[k]); bad |= !(c[k] == c[k]); }
     const double lim = m + tau * fabs(m);
-    int cnt = 0, first = 0;
-    int* o = sel + (long long)row * GRID_KS;
-    for (int k = 0; k < ncand; ++k)
-        if (c[k] <= lim || !(c[k] == c[k])) {
-            if (cnt == 0) first = k;
-            if (cnt < GRID_KS) o[cnt] = k;
-            ++cnt;
-        }
-    const bool ovf = cnt > GRID_KS || !(m == m);
-    if (ovf) { const int i = atomicAdd(overflow, 1); if (i < GRID_MAX_OVF) overflow[1 + i] = row; }
-    for (int j = cnt; j < GRID_KS; ++j) o[j] = first;
-    // a single candidate inside tau wins without an exact evaluation; a row with too many gets every candidate evaluated
-    // on its own afterwards: neither takes part in the exact pass
-    // (every eighth row is re-evaluated even then: its exact cost is what the deviation guard of the pass measures)
-    const int ev = ((cnt > 1 || row % 8 == 0) && !ovf) ? cnt : 0;
+    int cnt = 0;
+    for (int k = 0; k < ncand; ++k) cnt += (c[k] <= lim) ? 1 : 0;
+    if (bad || !(m == m) || cnt == 0) { atomicOr(gstat + GS_TRIPPED, 1); cnt = 0; }
+    lim_out[row] = lim;
+    const int ev = (cnt > 1 || row % 8 == 0) ? cnt : 0;
     cnt_out[row] = ev;
-    atomicAdd(overflow + 1 + GRID_MAX_OVF, ev);
+    if (ev) atomicAdd(gstat + GS_SURVIVORS, ev);
 }
 
-// exclusive prefix sums of cnt over the rows of each group of `per` rows (one workgroup per group): off[row], total[group]
-__global__ __launch_bounds__(256) void grid_scan_kernel(const int* __restrict__ cnt, int per, int* __restrict__ off, int* __restrict__ total) {
+// exclusive prefix sums of cnt over the rows of each group of `per` rows (one workgroup per group): off[row], total[group];
+// a group with more survivors than `cap` slots trips the guard, and its total is cut to cap (rows beyond are not evaluated)
+__global__ __launch_bounds__(256) void grid_scan_kernel(const int* __restrict__ cnt, int per, int cap, int* __restrict__ off,
+                                                        int* __restrict__ total, int* __restrict__ gstat) {
     __shared__ int part[256];
     const int g = blockIdx.x, t = threadIdx.x;
     const int* c = cnt + (long long)g * per; int* o = off + (long long)g * per;
@@ -267,31 +265,41 @@ __global__ __launch_bounds__(256) void grid_scan_kernel(const int* __restrict__ 
     for (int i = lo; i < hi; ++i) s += c[i];
     part[t] = s;
     __syncthreads();
-    if (t == 0) { int run = 0; for (int i = 0; i < 256; ++i) { const int v = part[i]; part[i] = run; run += v; } total[g] = run; }
+    if (t == 0) {
+        int run = 0;
+        for (int i = 0; i < 256; ++i) { const int v = part[i]; part[i] = run; run += v; }
+        if (run > cap) { atomicOr(gstat + GS_TRIPPED, 1); run = cap; }
+        total[g] = run;
+    }
     __syncthreads();
     int run = part[t];
     for (int i = lo; i < hi; ++i) { o[i] = run; run += c[i]; }
 }
 
-// exact delta of the candidates to evaluate, compacted per group of `per` rows: DeltaS[group][off[row] + j, c], j < cnt[row]
+// exact delta of the survivors, compacted per group of `per` rows: DeltaS[group][off[row] + j, c] for the j-th survivor of
+// the row (increasing k); slots at or beyond cap do not exist
 __global__ __launch_bounds__(256) void grid_delta_sel_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
                                                              const double* __restrict__ cand_s, const double* __restrict__ cand_z,
-                                                             const int* __restrict__ sel, const int* __restrict__ cnt, const int* __restrict__ off,
-                                                             int per, double* __restrict__ DeltaS) {
+                                                             const double* __restrict__ cost, const double* __restrict__ lim,
+                                                             const int* __restrict__ cnt, const int* __restrict__ off,
+                                                             int per, int cap, double* __restrict__ DeltaS) {
     const int row = blockIdx.y;
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    const int nc = cnt[row];
-    if (c >= n || nc == 0) return;
+    if (c >= n || cnt[row] == 0) return;
     const double w = Wk[(long long)row * ldw + c];
-    double* out = DeltaS + ((long long)(row / per) * per * GRID_KS + off[row]) * n + c;
-    for (int j = 0; j < nc; ++j) {
-        const int k = sel[(long long)row * GRID_KS + j];
+    const double l = lim[row];
+    const double* cr = cost + (long long)row * ncand;
+    double* out = DeltaS + ((long long)(row / per) * cap) * n + c;
+    int slot = off[row];
+    for (int k = 0; k < ncand && slot < cap; ++k) {
+        if (!(cr[k] <= l)) continue;
         const double s = cand_s[(long long)row * ncand + k], z = cand_z[(long long)row * ncand + k];
-        out[(long long)j * n] = s * (quant_code(w, s, z, maxq) - z) - w;
+        out[(long long)slot * n] = s * (quant_code(w, s, z, maxq) - z) - w;
+        ++slot;
     }
 }
 
-// cost[i] = sum_c A[i, c] B[i, c] for the compacted rows: row i of group g (per * GRID_KS slots each) exists if i < total[g]
+// cost[i] = sum_c A[i, c] B[i, c] for the compacted rows: row i of group g (`slots` each) exists if i < total[g]
 __global__ __launch_bounds__(256) void rowdot_limited_kernel(const double* __restrict__ A, const double* __restrict__ B, int n, int slots,
                                                              long long rows, const int* __restrict__ total, double* __restrict__ out) {
     const int lane = threadIdx.x & 63;
@@ -305,34 +313,44 @@ __global__ __launch_bounds__(256) void rowdot_limited_kernel(const double* __res
     if (lane == 0) out[row] = s;
 }
 
-// lowest exact cost among the evaluated candidates of a row (lowest k among equals: they are in increasing k); a row
-// with a single candidate inside tau takes that one
-// max_dev: the largest |approximate - exact| / exact seen over all re-evaluated candidates, as the bits of a non-negative float
-__global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const double* __restrict__ cost, const int* __restrict__ sel,
-                                       const int* __restrict__ cnt,
-                                       const int* __restrict__ off, int per, const double* __restrict__ cand_s,
-                                       const double* __restrict__ cand_z, int rows, int ncand, BlockMap m, int r_off,
-                                       double* __restrict__ s_out, double* __restrict__ z_out, int ng, int gi, int* __restrict__ max_dev) {
+// lowest exact cost among the survivors of a row (lowest k among equals: they are visited in increasing k); a row whose
+// survivors were not evaluated takes its first one (it has a single one, or the pass is void anyway).  Every exact
+// re-evaluation is compared with its approximation for the guard.
+__global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const double* __restrict__ cost, const double* __restrict__ lim,
+                                       const int* __restrict__ cnt, const int* __restrict__ off, int per, int cap,
+                                       const double* __restrict__ cand_s, const double* __restrict__ cand_z, int rows, int ncand,
+                                       BlockMap m, int r_off, double* __restrict__ s_out, double* __restrict__ z_out, int ng, int gi,
+                                       int* __restrict__ gstat) {
     const int row = blockIdx.x * blockDim.x + threadIdx.x;
     if (row >= rows) return;
-    int best = 0;
+    const double* cr = cost + (long long)row * ncand;
+    const double l = lim[row];
     const int nc = cnt[row];
+    int best = -1;
     if (nc > 0) {
-        const double* c = costS + (long long)(row / per) * per * GRID_KS + off[row];
-        double bc = c[0], dev = 0.0;
-        for (int j = 0; j < nc; ++j) {
-            if (c[j] < bc) { bc = c[j]; best = j; }
-            const double a = cost[(long long)row * ncand + sel[(long long)row * GRID_KS + j]];
-            const double d = fabs(a - c[j]) / fabs(c[j]);
+        const double* ce = costS + (long long)(row / per) * cap;
+        int slot = off[row];
+        double bc = 0.0, dev = 0.0;
+        for (int k = 0; k < ncand && slot < cap; ++k) {
+            if (!(cr[k] <= l)) continue;
+            const double e = ce[slot];
+            if (best < 0 || e < bc) { bc = e; best = k; }
+            const double d = fabs(cr[k] - e) / fabs(e);
             dev = (d == d) ? fmax(dev, d) : 1.0;
+            ++slot;
         }
-        atomicMax(max_dev, __float_as_int((float)fmin(dev, 1.0)));
+        atomicMax(gstat + GS_MAXDEV, __float_as_int((float)fmin(dev, 1.0)));
     }
-    const int k = sel[(long long)row * GRID_KS + best];
+    if (best < 0) {
+        best = 0;
+        for (int k = 0; k < ncand; ++k) if (cr[k] <= l) { best = k; break; }
+    }
     const long long lr = layer_row(m, r_off + row);
-    s_out[lr * ng + gi] = cand_s[(long long)row * ncand + k];
-    z_out[lr * ng + gi] = cand_z[(long long)row * ncand + k];
+    s_out[lr * ng + gi] = cand_s[(long long)row * ncand + best];
+    z_out[lr * ng + gi] = cand_z[(long long)row * ncand + best];
 }
+
+__global__ void clear_words_kernel(int* p, int n) { if ((int)threadIdx.x < n) p[threadIdx.x] = 0; }
 
 // ------------------------------------------------------------------------------------------------ Algorithm 3
 struct SweepArgs {
@@ -622,14 +640,17 @@ struct Layer {
     double *W64, *Wt, *Hi, *Hfac, *Uin, *Rd, *P, *Ho, *Hofac, *Uout, *ftmp, *fdinv;
     double *Q64, *s64, *z64;
     double *Wb, *Wk, *Epan, *Wsnap, *E, *S1, *S2, *T;
-    double *cand_s, *cand_z, *Delta, *G, *cost, *DeltaS, *GS, *costS;
+    double *cand_s, *cand_z, *Delta, *G, *cost, *DeltaS, *GS, *costS, *lim;
     __hip_bfloat16* Hcat; int* sel; int fast_grid, grid_blocked;
     double *Wbar, *Abar, *Z, *WR, *Cm, *Fm, *dvec, *lossbuf;
     double *Cg, *Fg;    // group-wise refinement: Gram blocks per (group, group) pair
     int grid_chunk;     // block rows (shared H_in) or heads (per-head H_in) per grid-search pass
+    int* gstat;         // device words of the two-phase search (GS_*), cleared at the start of a run
     long long nn;
 };
 
+// Algorithm 1 line 9 for the rows Wrows (block rows of every head, or whole heads for the fixed grid), columns [c0, c0 + ncols).
+// Everything is enqueued; nothing is read back here.
 int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head, BlockMap map, int c0, int ncols, int gi) {
     tboa_ctx* ctx = L.ctx;
     const int nh = L.nh, ncand = L.ncand;
@@ -644,14 +665,9 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
         hipLaunchKernelGGL(grid_candidates_kernel, dim3((rows + 3) / 4), dim3(256), 0, ctx->stream, Wc, ldw, c0, ncols, rows,
                            ncand, L.d->grid_points, L.maxq, L.cand_s, L.cand_z);
         TB_KERNEL_CHECK(ctx);
-        bool done = false;
         if (L.fast_grid && c0 == 0 && ncols == L.n) {
             const int n = L.n;
             __hip_bfloat16* Acat = (__hip_bfloat16*)L.Delta; float* G32 = (float*)L.G;
-            int* ovf = ctx->d_status + 8;   // [0] count, [1..] rows
-            TB_HIP(ctx, hipMemsetAsync(ovf, 0, sizeof(int), ctx->stream));
-            TB_HIP(ctx, hipMemsetAsync(ovf + 1 + GRID_MAX_OVF, 0, 2 * sizeof(int), ctx->stream));   // survivors, largest deviation
-            static_assert(11 + GRID_MAX_OVF <= 256, "status words");
             // both operands in the GEMM's 16 x 32 blocks when the shapes allow it (L.grid_blocked, decided with Hcat)
             long long mat_rows = L.grid_blocked ? (long long)(ph ? rows_per_head : rows) * ncand : 0;
             if (mat_rows % 16) mat_rows = 0;
@@ -669,54 +685,28 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
             const long long crow = (long long)rows * ncand;
             hipLaunchKernelGGL(rowdot_split_kernel, dim3((unsigned)((crow + 3) / 4)), dim3(256), 0, ctx->stream, G32, Acat, crow, n, L.cost, mat_rows);
             const int per = ph ? rows_per_head : rows, ngrp = rows / per;    // rows that share one H_in
-            int* cntv = L.sel + (long long)rows * GRID_KS; int* offv = cntv + rows; int* totv = offv + rows;
-            hipLaunchKernelGGL(grid_select_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.cost, rows, ncand, GRID_TAU, L.sel, cntv, ovf);
-            hipLaunchKernelGGL(grid_scan_kernel, dim3(ngrp), dim3(256), 0, ctx->stream, cntv, per, offv, totv);
+            const int cap = per * GRID_KS;                                    // exact re-evaluations a group has room for
+            int* cntv = L.sel; int* offv = cntv + rows; int* totv = offv + rows;
+            hipLaunchKernelGGL(grid_count_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.cost, rows, ncand, GRID_TAU, L.lim, cntv, L.gstat);
+            hipLaunchKernelGGL(grid_scan_kernel, dim3(ngrp), dim3(256), 0, ctx->stream, cntv, per, cap, offv, totv, L.gstat);
             hipLaunchKernelGGL(grid_delta_sel_kernel, dim3((n + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, n, ncand, L.maxq,
-                               L.cand_s, L.cand_z, L.sel, cntv, offv, per, L.DeltaS);
+                               L.cand_s, L.cand_z, L.cost, L.lim, cntv, offv, per, cap, L.DeltaS);
             TB_KERNEL_CHECK(ctx);
             GemmF64 g{};
-            g.M = per * GRID_KS; g.N = n; g.K = n; g.alpha = 1.0; g.beta = 0.0; g.A = L.DeltaS; g.sam = n; g.sak = 1; g.sbk = n; g.sbn = 1;
+            g.M = cap; g.N = n; g.K = n; g.alpha = 1.0; g.beta = 0.0; g.A = L.DeltaS; g.sam = n; g.sak = 1; g.sbk = n; g.sbn = 1;
             g.C = L.GS; g.ldc = n; g.batch = ngrp; g.strideA = (long long)g.M * n; g.strideC = g.strideA; g.m_limit = totv;
             g.B = L.Hi + (ph ? (long long)u0 * L.nn : 0); g.strideB = ph ? L.nn : 0;
+            g.tag = TBOA_PROF_F64_GRID;
             TB_TRY(gemm_f64(ctx, g));
-            const long long srow = (long long)rows * GRID_KS;
-            hipLaunchKernelGGL(rowdot_limited_kernel, dim3((unsigned)((srow + 3) / 4)), dim3(256), 0, ctx->stream, L.GS, L.DeltaS, n, per * GRID_KS,
+            const long long srow = (long long)ngrp * cap;
+            hipLaunchKernelGGL(rowdot_limited_kernel, dim3((unsigned)((srow + 3) / 4)), dim3(256), 0, ctx->stream, L.GS, L.DeltaS, n, cap,
                                srow, totv, L.costS);
-            hipLaunchKernelGGL(grid_argmin_sel_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.costS, L.cost, L.sel, cntv, offv, per,
-                               L.cand_s, L.cand_z, rows, ncand, map, r0, L.s64, L.z64, L.ng, gi, ovf + 2 + GRID_MAX_OVF);
+            hipLaunchKernelGGL(grid_argmin_sel_kernel, dim3((rows + 255) / 256), dim3(256), 0, ctx->stream, L.costS, L.cost, L.lim, cntv, offv, per, cap,
+                               L.cand_s, L.cand_z, rows, ncand, map, r0, L.s64, L.z64, L.ng, gi, L.gstat);
             TB_KERNEL_CHECK(ctx);
-            TB_HIP(ctx, hipMemcpyAsync(ctx->h_status + 8, ovf, (3 + GRID_MAX_OVF) * sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
-            TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
             ++ctx->counters[TBOA_CTR_GRID_PASSES];
-            ctx->counters[TBOA_CTR_GRID_SURVIVORS] += ctx->h_status[9 + GRID_MAX_OVF];
-            const int novf = ctx->h_status[8];
-            float dev; memcpy(&dev, &ctx->h_status[10 + GRID_MAX_OVF], sizeof(float));
-            // approximate costs that stray from the exact ones by a quarter of the survivors' margin are not trusted: exact pass
-            // (TBOA_GRID_GUARD: the fraction of tau, default 0.25; 0 sends every pass with re-evaluations to the exact path, which
-            // is how the tests reach it)
-            const char* gs = getenv("TBOA_GRID_GUARD");
-            done = novf <= GRID_MAX_OVF && dev <= (gs ? atof(gs) : 0.25) * GRID_TAU;
-            if (!done) ++ctx->counters[TBOA_CTR_GRID_FALLBACKS];
-            for (int i = 0; done && i < novf; ++i) {
-                // a row with many near-minimal candidates: every candidate exactly, for this row alone
-                const int r = ctx->h_status[9 + i];
-                ++ctx->counters[TBOA_CTR_GRID_EXACT_ROWS];
-                hipLaunchKernelGGL(grid_delta_kernel, dim3((n + 255) / 256, 1), dim3(256), 0, ctx->stream, Wc + (long long)r * ldw, ldw, 0, n,
-                                   ncand, L.maxq, L.cand_s + (long long)r * ncand, L.cand_z + (long long)r * ncand, L.Delta);
-                TB_KERNEL_CHECK(ctx);
-                GemmF64 e{};
-                e.M = ncand; e.N = n; e.K = n; e.alpha = 1.0; e.beta = 0.0; e.A = L.Delta; e.sam = n; e.sak = 1;
-                e.B = L.Hi + (ph ? (long long)(u0 + r / rows_per_head) * L.nn : 0); e.sbk = n; e.sbn = 1; e.C = L.G; e.ldc = n; e.batch = 1;
-                TB_TRY(gemm_f64(ctx, e));
-                hipLaunchKernelGGL(rowdot_kernel, dim3((ncand + 3) / 4), dim3(256), 0, ctx->stream, L.G, (long long)n, L.Delta, (long long)n,
-                                   (long long)ncand, n, L.cost);
-                hipLaunchKernelGGL(grid_argmin_kernel, dim3(1), dim3(64), 0, ctx->stream, L.cost, L.cand_s + (long long)r * ncand,
-                                   L.cand_z + (long long)r * ncand, 1, ncand, map, r0 + r, L.s64, L.z64, L.ng, gi);
-                TB_KERNEL_CHECK(ctx);
-            }
+            continue;
         }
-        if (done) continue;
         hipLaunchKernelGGL(grid_delta_kernel, dim3((ncols + 255) / 256, rows), dim3(256), 0, ctx->stream, Wc, ldw, c0, ncols, ncand,
                            L.maxq, L.cand_s, L.cand_z, L.Delta);
         TB_KERNEL_CHECK(ctx);
@@ -724,6 +714,7 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
         g.N = ncols; g.K = ncols; g.alpha = 1.0; g.beta = 0.0;
         g.A = L.Delta; g.sam = ncols; g.sak = 1;
         g.sbk = L.n; g.sbn = 1; g.C = L.G; g.ldc = ncols;
+        g.tag = TBOA_PROF_F64_GRID;
         if (ph) {
             g.M = rows_per_head * ncand; g.batch = nu;
             g.B = L.Hi + (long long)u0 * L.nn + (long long)c0 * L.n + c0;
@@ -746,9 +737,10 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
 // one GEMM over all block rows (shared H_in) or batched per head (per-head H_in): C = alpha A op(B) + beta C,
 // A, C block arrays [nh*nbr, *]; B a d_in x d_in matrix (or one per head) addressed by (sbk, sbn) at offset boff.
 int block_gemm(Layer& L, int nbr, int N, int K, double alpha, const double* A, long long lda, const double* B, long long boff,
-               long long sbk, long long sbn, double beta, double* C, long long ldc, const GemmF64* flags = nullptr) {
+               long long sbk, long long sbn, double beta, double* C, long long ldc, int tag, const GemmF64* flags = nullptr) {
     GemmF64 g{};
     if (flags) g = *flags;
+    g.tag = tag;
     g.N = N; g.K = K; g.alpha = alpha; g.beta = beta;
     g.A = A; g.sam = lda; g.sak = 1; g.B = B + boff; g.sbk = sbk; g.sbn = sbn; g.C = C; g.ldc = ldc;
     if (L.nhin > 1) { g.M = nbr; g.batch = L.nh; g.strideA = (long long)nbr * lda; g.strideB = L.nn; g.strideC = (long long)nbr * ldc; }
@@ -756,12 +748,19 @@ int block_gemm(Layer& L, int nbr, int N, int K, double alpha, const double* A, l
     return gemm_f64(L.ctx, g);
 }
 
+// return value of run_layer: the approximate costs of the two-phase grid search could not be trusted somewhere in this
+// run (see grid_search): the caller runs the layer again with exact costs for every candidate
+constexpr int RUN_AGAIN_EXACT = 1;
+
 int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, const float* R, uint8_t* codes, float* scales,
               float* zeros, float* W_deq, double* loss, double* loss_per_head) {
     tboa_ctx* ctx = L.ctx; const tboa_layer_desc* d = L.d;
     const int n = L.n, nh = L.nh, dh = L.dh, ng = L.ng, nhin = L.nhin;
     const long long nn = L.nn, wn = (long long)d->d_out * n;
     hipStream_t st = ctx->stream;
+
+    hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, st, L.gstat, (int)GS_WORDS);
+    TB_KERNEL_CHECK(ctx);
 
     TB_TRY(launch_cvt_to_f64(ctx, W, d->w_dtype, L.W64, wn));
     TB_HIP(ctx, hipMemcpyAsync(L.Wt, L.W64, wn * sizeof(double), hipMemcpyDeviceToDevice, st));
@@ -776,18 +775,21 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     // U_in, P and U_out are first needed by the first in-channel sweep; the grid search before it needs only W and H_in.
     // The factorisations and the two P products (for one matrix: chains of small kernels that leave most of the GPU idle)
     // therefore run on the context's second stream, beside that grid search; setup_join() below is where they meet.
+    // The breakdown status of the factorisations is read at the end of the call, with everything else that comes back.
     struct StreamSwap {      // everything enqueued while this lives goes to the second stream
         tboa_ctx* c; hipStream_t keep;
         explicit StreamSwap(tboa_ctx* c_) : c(c_), keep(c_->stream) { c->stream = c->aux; }
         ~StreamSwap() { c->stream = keep; }
     };
-    static const bool no_overlap = getenv("TBOA_NO_SETUP_OVERLAP") != nullptr;
-    const bool forked = !no_overlap;
+    bool joined = false;
+    struct DrainAux {      // an error return before the join must not leave work running on the workspace
+        tboa_ctx* c; const bool* joined;
+        ~DrainAux() { if (!*joined) (void)hipStreamSynchronize(c->aux); }
+    } drain{ctx, &joined};
     TB_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
     {
     StreamSwap swap(ctx);
-    if (forked) TB_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->ev_fork, 0));
-    else ctx->stream = st;
+    TB_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->ev_fork, 0));
     TB_TRY(chol_inv_upper_f64(ctx, n, nhin, L.Hfac, L.Uin, L.ftmp, L.fdinv, 0, true));
     if (R) {   // Algorithm 3 line 2: P = ((R U^T) * M_U) U
         TB_TRY(launch_cvt_f32_to_f64(ctx, R, L.Rd, nhin * nn));
@@ -796,6 +798,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
         a.A = L.Rd; a.sam = n; a.sak = 1; a.B = L.Uin; a.sbk = 1; a.sbn = n; a.klo_n = 1;   // U[c, k] = 0 for k < c
         a.skip_lower = 1;   // only the part above the diagonal survives the mask below
         a.C = L.Hfac; a.ldc = n; a.batch = nhin; a.strideA = nn; a.strideB = nn; a.strideC = nn;
+        a.tag = TBOA_PROF_F64_FACTOR;
         TB_TRY(gemm_f64(ctx, a));
         TB_TRY(launch_strict_upper_f64(ctx, L.Hfac, n, nhin));
         GemmF64 b{};
@@ -804,6 +807,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
         b.B = L.Uin; b.sbk = n; b.sbn = 1; b.khi_n = 1;        // U[m, k] = 0 for m > k
         b.diag_order = 1;                                      // contraction range (row start, column end]: grows with the column
         b.C = L.P; b.ldc = n; b.batch = nhin; b.strideA = nn; b.strideB = nn; b.strideC = nn;
+        b.tag = TBOA_PROF_F64_FACTOR;
         TB_TRY(gemm_f64(ctx, b));
     }
     if (H_out) {
@@ -811,19 +815,12 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
         TB_HIP(ctx, hipMemcpyAsync(L.Hofac, L.Ho, (size_t)nh * dh * dh * sizeof(double), hipMemcpyDeviceToDevice, ctx->stream));
         TB_TRY(chol_inv_upper_f64(ctx, dh, nh, L.Hofac, L.Uout, L.ftmp, L.fdinv, 2, true));
     }
-    if (forked) TB_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux));
+    TB_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux));
     }
-    bool joined = false;
-    struct DrainAux {      // an error return before the join must not leave work running on the workspace
-        tboa_ctx* c; const bool* joined; bool forked;
-        ~DrainAux() { if (forked && !*joined) (void)hipStreamSynchronize(c->aux); }
-    } drain{ctx, &joined, forked};
     auto setup_join = [&]() -> int {
         if (joined) return 0;
+        TB_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
         joined = true;
-        if (forked) TB_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
-        TB_TRY(chol_status_f64(ctx, 0));
-        if (H_out) TB_TRY(chol_status_f64(ctx, 2));
         return 0;
     };
     const double* Pp = R ? L.P : nullptr;
@@ -855,7 +852,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
             if (c1 < n) {   // columns right of the panel: W[:, c1:] -= E U[c0:c1, c1:] + Wsnap P[c0:c1, c1:]
                 GemmF64 two{};   // both terms in one pass over the output
                 if (Pp) { two.A2 = L.Wsnap; two.B2 = L.P + (long long)c0 * n + c1; }
-                TB_TRY(block_gemm(L, nbr, n - c1, pw, -1.0, L.Epan, 64, L.Uin, (long long)c0 * n + c1, n, 1, 1.0, L.Wk + c1, n, &two));
+                TB_TRY(block_gemm(L, nbr, n - c1, pw, -1.0, L.Epan, 64, L.Uin, (long long)c0 * n + c1, n, 1, 1.0, L.Wk + c1, n, TBOA_PROF_F64_SWEEP, &two));
             }
         }
         if (H_out && i1 < dh) {
@@ -863,9 +860,9 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
             if (R) {   // W_B R H_in^-1 = ((W_B R) U^T) U
                 GemmF64 f1{}; f1.klo_n = 1;
                 GemmF64 f2{}; f2.khi_n = 1;
-                TB_TRY(block_gemm(L, nbr, n, n, 1.0, L.Wb, n, L.Rd, 0, n, 1, 0.0, L.S1, n));
-                TB_TRY(block_gemm(L, nbr, n, n, 1.0, L.S1, n, L.Uin, 0, 1, n, 0.0, L.S2, n, &f1));
-                TB_TRY(block_gemm(L, nbr, n, n, 1.0, L.S2, n, L.Uin, 0, n, 1, 0.0, L.S1, n, &f2));
+                TB_TRY(block_gemm(L, nbr, n, n, 1.0, L.Wb, n, L.Rd, 0, n, 1, 0.0, L.S1, n, TBOA_PROF_F64_COMP));
+                TB_TRY(block_gemm(L, nbr, n, n, 1.0, L.S1, n, L.Uin, 0, 1, n, 0.0, L.S2, n, TBOA_PROF_F64_COMP, &f1));
+                TB_TRY(block_gemm(L, nbr, n, n, 1.0, L.S2, n, L.Uin, 0, n, 1, 0.0, L.S1, n, TBOA_PROF_F64_COMP, &f2));
                 S3 = L.S1;
             }
             hipLaunchKernelGGL(comp_error_kernel, dim3(gx(n), rows), dim3(256), 0, st, L.Wb, L.Q64, S3, L.E, map, n);
@@ -878,6 +875,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
             u.B = L.E; u.sbk = n; u.sbn = 1;
             u.C = L.Wt + (long long)i1 * n; u.ldc = n;
             u.batch = nh; u.strideA = (long long)dh * d->block; u.strideB = (long long)nbr * n; u.strideC = (long long)dh * n;
+            u.tag = TBOA_PROF_F64_COMP;
             TB_TRY(gemm_f64(ctx, u));
         }
     }
@@ -886,12 +884,12 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     const int rows_all = d->d_out;
     hipLaunchKernelGGL(wbar_kernel, dim3(gx(n), rows_all), dim3(256), 0, st, codes, L.z64, ng, L.gsz, n, L.Wbar);
     TB_KERNEL_CHECK(ctx);
-    if (R) TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Rd, 0, n, 1, 0.0, L.WR, n));
+    if (R) TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Rd, 0, n, 1, 0.0, L.WR, n, TBOA_PROF_F64_CD));
     if (d->cd_iters > 0 && d->group) {
         // Z = W (H_in - R); per group g: AH = Wbar[:, G] H_in[G, :] (into Abar), then the Gram blocks against every group
         const int gsz = L.gsz;
         const long long rr = (long long)dh * dh;
-        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Hi, 0, n, 1, 0.0, L.Z, n));
+        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Hi, 0, n, 1, 0.0, L.Z, n, TBOA_PROF_F64_CD));
         if (R) TB_TRY(launch_sub_f64(ctx, L.Z, L.WR, L.Z, wn));
         if (H_out) {
             GemmF64 f{};   // Fg[h][g] = Wbar_h[:, G] Z_h[:, G]^T
@@ -907,7 +905,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
             TB_KERNEL_CHECK(ctx);
         }
         for (int g = 0; g < ng; ++g) {
-            TB_TRY(block_gemm(L, dh, n, gsz, 1.0, L.Wbar + (long long)g * gsz, n, L.Hi, (long long)g * gsz * n, n, 1, 0.0, L.Abar, n));
+            TB_TRY(block_gemm(L, dh, n, gsz, 1.0, L.Wbar + (long long)g * gsz, n, L.Hi, (long long)g * gsz * n, n, 1, 0.0, L.Abar, n, TBOA_PROF_F64_CD));
             if (H_out) {
                 GemmF64 c{};   // Cg[h][g][g'] = AH_h[:, G'] Wbar_h[:, G']^T
                 c.M = dh; c.N = dh; c.K = gsz; c.alpha = 1.0; c.beta = 0.0;
@@ -934,8 +932,8 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
         }
         TB_KERNEL_CHECK(ctx);
     } else if (d->cd_iters > 0) {
-        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.Wbar, n, L.Hi, 0, n, 1, 0.0, L.Abar, n));
-        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Hi, 0, n, 1, 0.0, L.Z, n));
+        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.Wbar, n, L.Hi, 0, n, 1, 0.0, L.Abar, n, TBOA_PROF_F64_CD));
+        TB_TRY(block_gemm(L, dh, n, n, 1.0, L.W64, n, L.Hi, 0, n, 1, 0.0, L.Z, n, TBOA_PROF_F64_CD));
         if (R) TB_TRY(launch_sub_f64(ctx, L.Z, L.WR, L.Z, wn));
         if (H_out) {
             GemmF64 c{};
@@ -959,13 +957,14 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     hipLaunchKernelGGL(finalize_kernel, dim3(gx(n), rows_all), dim3(256), 0, st, L.Wbar, L.s64, L.z64, ng, L.gsz, n, L.Q64, W_deq,
                        scales, zeros);
     TB_KERNEL_CHECK(ctx);
-    if (loss || loss_per_head) {
+    const bool want_loss = loss || loss_per_head;
+    if (want_loss) {
         // D = Q - W (into Wbar), D H_in (into Abar)
         TB_TRY(launch_sub_f64(ctx, L.Q64, L.W64, L.Wbar, wn));
         if (d->cd_iters > 0 && !d->group) {   // Abar = Wbar H_in and Z are still those of the scale refinement
             hipLaunchKernelGGL(dh_from_products_kernel, dim3(gx(n), rows_all), dim3(256), 0, st, L.Abar, L.s64, L.Z, R ? L.WR : nullptr, n);
             TB_KERNEL_CHECK(ctx);
-        } else TB_TRY(block_gemm(L, dh, n, n, 1.0, L.Wbar, n, L.Hi, 0, n, 1, 0.0, L.Abar, n));
+        } else TB_TRY(block_gemm(L, dh, n, n, 1.0, L.Wbar, n, L.Hi, 0, n, 1, 0.0, L.Abar, n, TBOA_PROF_F64_CD));
         double* lq = L.lossbuf; double* lc = L.lossbuf + nh;
         TB_TRY(launch_fill_f64(ctx, L.lossbuf, 2 * nh, 0.0));
         if (H_out) {
@@ -973,6 +972,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
             c.M = dh; c.N = dh; c.K = n; c.alpha = 1.0; c.beta = 0.0;
             c.A = L.Abar; c.sam = n; c.sak = 1; c.B = L.Wbar; c.sbk = 1; c.sbn = n; c.C = L.Cm; c.ldc = dh;
             c.batch = nh; c.strideA = (long long)dh * n; c.strideB = c.strideA; c.strideC = (long long)dh * dh;
+            c.tag = TBOA_PROF_F64_CD;
             TB_TRY(gemm_f64(ctx, c));
             hipLaunchKernelGGL(head_trace_kernel, dim3(nh), dim3(256), 0, st, L.Ho, L.Cm, dh, 1.0, lq);
             if (R) {
@@ -991,13 +991,37 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
             }
         }
         TB_KERNEL_CHECK(ctx);
-        double* host = (double*)malloc(2 * nh * sizeof(double));
+    }
+    // ---- the one place where the call waits for the device: factorisation status, the bookkeeping of the grid search, losses
+    TB_TRY(setup_join());      // (a layer with no in-channel sweep at all never joined)
+    double* host = nullptr;
+    if (want_loss) {
+        host = (double*)malloc(2 * (size_t)nh * sizeof(double));
         if (!host) return tboa_fail(ctx, TBOA_ENOMEM, "host buffer");
-        hipError_t e = hipMemcpyAsync(host, L.lossbuf, 2 * nh * sizeof(double), hipMemcpyDeviceToHost, st);
-        if (e == hipSuccess) e = hipStreamSynchronize(st);
-        if (e != hipSuccess) { free(host); return tboa_fail(ctx, TBOA_EHIP, "loss copy: %s", hipGetErrorString(e)); }
+    }
+    hipError_t e = hipMemcpyAsync(ctx->h_status, ctx->d_status, (TB_GSTAT_WORD + GS_WORDS) * sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess && want_loss) e = hipMemcpyAsync(host, L.lossbuf, 2 * (size_t)nh * sizeof(double), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { free(host); return tboa_fail(ctx, TBOA_EHIP, "status and loss copy: %s", hipGetErrorString(e)); }
+    for (int slot = 0; slot <= (H_out ? 2 : 0); slot += 2)
+        if (ctx->h_status[slot] != 0) {
+            free(host);
+            return tboa_fail(ctx, TBOA_ENOTSPD, "%s Hessian %d of the batch is not positive definite: pivot %d is not positive",
+                             slot ? "out-channel" : "in-channel", ctx->h_status[slot + 1], ctx->h_status[slot] - 1);
+        }
+    if (L.fast_grid) {
+        const int* gs = ctx->h_status + TB_GSTAT_WORD;
+        float dev; memcpy(&dev, &gs[GS_MAXDEV], sizeof(float));
+        ctx->counters[TBOA_CTR_GRID_SURVIVORS] += gs[GS_SURVIVORS];
+        const double guard = d->grid_guard > 0.0 ? d->grid_guard : 0.25;
+        if (gs[GS_TRIPPED] || dev > guard * GRID_TAU) { free(host); return RUN_AGAIN_EXACT; }
+    }
+    if (want_loss) {
         double q = 0.0, c = 0.0;
-        for (int h = 0; h < nh; ++h) { q += host[h]; c += host[nh + h]; if (loss_per_head) loss_per_head[h] = host[h] + host[nh + h]; }
+        for (int h = 0; h < nh; ++h) {
+            q += host[h]; c += host[nh + h];
+            if (loss_per_head) { loss_per_head[2 * h] = host[h]; loss_per_head[2 * h + 1] = host[nh + h]; }
+        }
         if (loss) { loss[0] = q; loss[1] = c; }
         free(host);
         if (!(q == q) || !(c == c)) return tboa_fail(ctx, TBOA_ENAN, "quantize_layer: loss is not finite (non-finite input?)");
@@ -1005,13 +1029,52 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     return 0;
 }
 
-}  // namespace
+// The workspace of a quantize_layer call, carved from `ar` (base == nullptr: only counted).
+void plan_layer(Layer& L, bool H_out, bool R, Arena& ar) {
+    const tboa_layer_desc* d = L.d;
+    const int n = L.n, nh = L.nh, dh = L.dh;
+    const int blk = d->block < dh ? d->block : dh;
+    const size_t wn = (size_t)d->d_out * n, brows = (size_t)nh * blk;
+    const size_t grows = (size_t)L.grid_chunk * (L.nhin > 1 ? (d->adaptive_grid ? blk : dh) : 1);
+    const int fmax = n > dh ? n : dh;
+    const int fb = (L.nhin > nh) ? L.nhin : nh;
+    const int nblk_f = (fmax + TB_FACT_NB - 1) / TB_FACT_NB;
+    L.W64 = ar.get<double>(wn); L.Wt = ar.get<double>(wn); L.Q64 = ar.get<double>(wn);
+    L.s64 = ar.get<double>((size_t)d->d_out * L.ng); L.z64 = ar.get<double>((size_t)d->d_out * L.ng);
+    L.Hi = ar.get<double>((size_t)L.nhin * L.nn); L.Hfac = ar.get<double>((size_t)L.nhin * L.nn); L.Uin = ar.get<double>((size_t)L.nhin * L.nn);
+    L.Rd = R ? ar.get<double>((size_t)L.nhin * L.nn) : nullptr; L.P = R ? ar.get<double>((size_t)L.nhin * L.nn) : nullptr;
+    L.Ho = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr; L.Hofac = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
+    L.Uout = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
+    // the two factorisations (H_in: nhin matrices of order n; H_out: nh of order dh) share their temporaries
+    const size_t t_in = (size_t)L.nhin * n * chol_tmp_pitch(n), t_out = H_out ? (size_t)nh * dh * chol_tmp_pitch(dh) : 0;
+    L.ftmp = ar.get<double>(t_in > t_out ? t_in : t_out); L.fdinv = ar.get<double>((size_t)fb * nblk_f * TB_FACT_NB * TB_FACT_NB);
+    L.Wb = ar.get<double>(brows * n); L.Wk = ar.get<double>(brows * n);
+    L.Epan = ar.get<double>(brows * 64); L.Wsnap = ar.get<double>(brows * 64);
+    L.E = H_out ? ar.get<double>(brows * n) : nullptr;
+    L.S1 = (H_out && R) ? ar.get<double>(brows * n) : nullptr; L.S2 = (H_out && R) ? ar.get<double>(brows * n) : nullptr;
+    L.T = H_out ? ar.get<double>((size_t)nh * dh * d->block) : nullptr;
+    L.cand_s = ar.get<double>(grows * L.ncand); L.cand_z = ar.get<double>(grows * L.ncand); L.cost = ar.get<double>(grows * L.ncand);
+    L.Delta = ar.get<double>(grows * L.ncand * L.gsz); L.G = ar.get<double>(grows * L.ncand * L.gsz);
+    L.DeltaS = L.GS = L.costS = L.lim = nullptr; L.sel = nullptr; L.Hcat = nullptr;
+    if (L.fast_grid) {
+        L.DeltaS = ar.get<double>(grows * GRID_KS * n); L.GS = ar.get<double>(grows * GRID_KS * n);
+        L.costS = ar.get<double>(grows * GRID_KS); L.lim = ar.get<double>(grows); L.sel = ar.get<int>(grows * 3);
+        L.Hcat = ar.get<__hip_bfloat16>((size_t)L.nhin * n * (GRID_TERMS * (size_t)n + GRID_PAD));
+    }
+    L.Wbar = ar.get<double>(wn); L.Abar = ar.get<double>(wn); L.Z = ar.get<double>(wn);
+    L.WR = R ? ar.get<double>(wn) : nullptr;
+    L.Cm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr; L.Fm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
+    L.dvec = ar.get<double>(2 * (size_t)d->d_out); L.lossbuf = ar.get<double>(2 * (size_t)nh);
+    L.Cg = L.Fg = nullptr;
+    if (d->group && d->cd_iters > 0) {
+        const size_t ng = (size_t)L.ng;
+        L.Cg = ar.get<double>(H_out ? (size_t)nh * ng * ng * dh * dh : (size_t)d->d_out * ng * ng);
+        L.Fg = ar.get<double>(H_out ? (size_t)nh * ng * dh * dh : (size_t)d->d_out * ng);
+    }
+}
 
-extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, const void* W, const float* H_in, const float* H_out,
-                                   const float* R, uint8_t* codes, float* scales, float* zeros, float* W_deq, double* loss,
-                                   double* loss_per_head) {
-    if (!ctx) return TBOA_EINVAL;
-    if (!d || !W || !H_in || !codes || !scales || !zeros || !W_deq) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: null argument");
+int check_layer_desc(tboa_ctx* ctx, const tboa_layer_desc* d) {
+    if (!d) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: null descriptor");
     if (d->d_out <= 0 || d->d_in <= 0 || d->n_heads <= 0 || d->d_out % d->n_heads != 0)
         return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: d_out=%d must be a positive multiple of n_heads=%d", d->d_out, d->n_heads);
     if (!(d->bits == 2 || d->bits == 3 || d->bits == 4 || d->bits == 8)) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: bits=%d not in {2,3,4,8}", d->bits);
@@ -1019,11 +1082,13 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
     if (d->group < 0 || (d->group > 0 && d->d_in % d->group != 0)) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: group=%d must divide d_in=%d", d->group, d->d_in);
     if (d->group > 0 && !(d->group % 64 == 0 || 64 % d->group == 0)) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: group=%d must divide or be a multiple of 64", d->group);
     if (d->w_dtype != TBOA_F32 && d->w_dtype != TBOA_BF16) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: w_dtype");
-    if (d->grid_points <= 0 || !(d->max_shrink > 0.0) || d->max_shrink > 1.0 || d->damp < 0.0 || d->cd_iters < 0)
-        return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: grid_points/max_shrink/damp/cd_iters out of range");
-    if (d->hin_per_head && d->n_heads > 1 && !H_out) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: per-head H_in needs H_out");
+    if (d->grid_points <= 0 || !(d->max_shrink > 0.0) || d->max_shrink > 1.0 || d->damp < 0.0 || d->cd_iters < 0 || !(d->grid_guard == d->grid_guard))
+        return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: grid_points/max_shrink/damp/cd_iters/grid_guard out of range");
+    return 0;
+}
 
-    Layer L{};
+// the quantities of a layer that follow from its descriptor alone
+void init_layer(Layer& L, tboa_ctx* ctx, const tboa_layer_desc* d) {
     L.ctx = ctx; L.d = d;
     L.n = d->d_in; L.nh = d->n_heads; L.dh = d->d_out / d->n_heads;
     L.ng = d->group ? d->d_in / d->group : 1; L.gsz = d->group ? d->group : d->d_in;
@@ -1032,56 +1097,52 @@ extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, cons
     if (L.ncand < 1) L.ncand = 1;
     L.maxq = (double)((1 << d->bits) - 1);
     L.nn = (long long)L.n * L.n;
-    const int n = L.n, nh = L.nh, dh = L.dh;
-    const int blk = d->block < dh ? d->block : dh;
-    const size_t wn = (size_t)d->d_out * n, brows = (size_t)nh * blk;
+    const int blk = d->block < L.dh ? d->block : L.dh;
     // grid-search pass size: keep Delta and G near 2 GiB each
-    {
-        const double cap = 2147483648.0;
-        const double per_row = (double)L.ncand * L.gsz * 8.0;
-        const int max_rows_block = d->adaptive_grid ? blk : dh;
-        if (L.nhin > 1) { int c = (int)(cap / (per_row * max_rows_block)); L.grid_chunk = c < 1 ? 1 : (c > nh ? nh : c); }
-        else { int c = (int)(cap / per_row); const int tot = nh * max_rows_block; L.grid_chunk = c < 1 ? 1 : (c > tot ? tot : c); }
-    }
-    L.fast_grid = (!d->group && n % 8 == 0 && n >= 256 && !getenv("TBOA_NO_FAST_GRID")) ? 1 : 0;   // per-row grids of wide layers: two-phase search
-    L.grid_blocked = (L.fast_grid && n % 32 == 0 && !getenv("TBOA_NO_BLOCKED_GRID")) ? 1 : 0;   // its GEMM operands in 16 x 32 blocks
-    const size_t grows = (size_t)L.grid_chunk * (L.nhin > 1 ? (d->adaptive_grid ? blk : dh) : 1);
-    const int fmax = n > dh ? n : dh;
-    const int fb = (L.nhin > nh) ? L.nhin : nh;
-    const int nblk_f = (fmax + TB_FACT_NB - 1) / TB_FACT_NB;
+    const double cap = 2147483648.0;
+    const double per_row = (double)L.ncand * L.gsz * 8.0;
+    const int max_rows_block = d->adaptive_grid ? blk : L.dh;
+    if (L.nhin > 1) { int c = (int)(cap / (per_row * max_rows_block)); L.grid_chunk = c < 1 ? 1 : (c > L.nh ? L.nh : c); }
+    else { int c = (int)(cap / per_row); const int tot = L.nh * max_rows_block; L.grid_chunk = c < 1 ? 1 : (c > tot ? tot : c); }
+    // per-row grids of wide layers: two-phase search (a negative grid_guard asks for exact costs throughout); its GEMM
+    // operands in 16 x 32 blocks when the width allows
+    L.fast_grid = (!d->group && L.n % 8 == 0 && L.n >= 256 && !(d->grid_guard < 0.0)) ? 1 : 0;
+    L.grid_blocked = (L.fast_grid && L.n % 32 == 0) ? 1 : 0;
+    L.gstat = ctx ? ctx->d_status + TB_GSTAT_WORD : nullptr;
+}
 
+}  // namespace
+
+extern "C" size_t tboa_quantize_workspace_bytes(const tboa_layer_desc* d) {
+    if (check_layer_desc(nullptr, d) != 0) return 0;
+    Layer L{};
+    init_layer(L, nullptr, d);
+    Arena ar(nullptr);
+    plan_layer(L, true, true, ar);      // with H_out and R: an upper bound for the calls without them
+    return ar.off;
+}
+
+extern "C" int tboa_quantize_layer(tboa_ctx* ctx, const tboa_layer_desc* d, const void* W, const float* H_in, const float* H_out,
+                                   const float* R, uint8_t* codes, float* scales, float* zeros, float* W_deq, double* loss,
+                                   double* loss_per_head) {
+    if (!ctx) return TBOA_EINVAL;
+    if (!d || !W || !H_in || !codes || !scales || !zeros || !W_deq) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: null argument");
+    TB_TRY(check_layer_desc(ctx, d));
+    if (d->hin_per_head && d->n_heads > 1 && !H_out) return tboa_fail(ctx, TBOA_EINVAL, "quantize_layer: per-head H_in needs H_out");
+
+    Layer L{};
+    init_layer(L, ctx, d);
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
-        L.W64 = ar.get<double>(wn); L.Wt = ar.get<double>(wn); L.Q64 = ar.get<double>(wn);
-        L.s64 = ar.get<double>((size_t)d->d_out * L.ng); L.z64 = ar.get<double>((size_t)d->d_out * L.ng);
-        L.Hi = ar.get<double>((size_t)L.nhin * L.nn); L.Hfac = ar.get<double>((size_t)L.nhin * L.nn); L.Uin = ar.get<double>((size_t)L.nhin * L.nn);
-        L.Rd = R ? ar.get<double>((size_t)L.nhin * L.nn) : nullptr; L.P = R ? ar.get<double>((size_t)L.nhin * L.nn) : nullptr;
-        L.Ho = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr; L.Hofac = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
-        L.Uout = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
-        L.ftmp = ar.get<double>((size_t)fb * fmax * TB_FACT_OB); L.fdinv = ar.get<double>((size_t)fb * nblk_f * TB_FACT_NB * TB_FACT_NB);
-        L.Wb = ar.get<double>(brows * n); L.Wk = ar.get<double>(brows * n);
-        L.Epan = ar.get<double>(brows * 64); L.Wsnap = ar.get<double>(brows * 64);
-        L.E = H_out ? ar.get<double>(brows * n) : nullptr;
-        L.S1 = (H_out && R) ? ar.get<double>(brows * n) : nullptr; L.S2 = (H_out && R) ? ar.get<double>(brows * n) : nullptr;
-        L.T = H_out ? ar.get<double>((size_t)nh * dh * d->block) : nullptr;
-        L.cand_s = ar.get<double>(grows * L.ncand); L.cand_z = ar.get<double>(grows * L.ncand); L.cost = ar.get<double>(grows * L.ncand);
-        L.Delta = ar.get<double>(grows * L.ncand * L.gsz); L.G = ar.get<double>(grows * L.ncand * L.gsz);
-        if (L.fast_grid) {
-            L.DeltaS = ar.get<double>(grows * GRID_KS * n); L.GS = ar.get<double>(grows * GRID_KS * n);
-            L.costS = ar.get<double>(grows * GRID_KS); L.sel = ar.get<int>(grows * (GRID_KS + 3));
-            L.Hcat = ar.get<__hip_bfloat16>((size_t)L.nhin * n * (GRID_TERMS * (size_t)n + GRID_PAD));
-        }
-        L.Wbar = ar.get<double>(wn); L.Abar = ar.get<double>(wn); L.Z = ar.get<double>(wn);
-        L.WR = R ? ar.get<double>(wn) : nullptr;
-        L.Cm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr; L.Fm = H_out ? ar.get<double>((size_t)nh * dh * dh) : nullptr;
-        L.dvec = ar.get<double>(2 * (size_t)d->d_out); L.lossbuf = ar.get<double>(2 * (size_t)nh);
-        L.Cg = L.Fg = nullptr;
-        if (d->group && d->cd_iters > 0) {
-            const size_t ng = (size_t)L.ng;
-            L.Cg = ar.get<double>(H_out ? (size_t)nh * ng * ng * dh * dh : (size_t)d->d_out * ng * ng);
-            L.Fg = ar.get<double>(H_out ? (size_t)nh * ng * dh * dh : (size_t)d->d_out * ng);
-        }
+        plan_layer(L, H_out != nullptr, R != nullptr, ar);
         if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
     }
-    return run_layer(L, W, H_in, H_out, R, codes, scales, zeros, W_deq, loss, loss_per_head);
+    int rc = run_layer(L, W, H_in, H_out, R, codes, scales, zeros, W_deq, loss, loss_per_head);
+    if (rc == RUN_AGAIN_EXACT) {
+        // the guard of the two-phase grid search: exact costs for every candidate, same workspace
+        ++ctx->counters[TBOA_CTR_GRID_FALLBACKS];
+        L.fast_grid = 0;
+        rc = run_layer(L, W, H_in, H_out, R, codes, scales, zeros, W_deq, loss, loss_per_head);
+    }
+    return rc;
 }

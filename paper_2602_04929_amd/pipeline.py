@@ -13,12 +13,40 @@ def make_side_contexts(n=2):
     return [tb.Context(stream=torch.cuda.Stream()) for _ in range(n)]
 
 
+def reserve_workspaces(ctx, cfg, side_contexts=None, stack_qk=True, cd_iters=1, adaptive_grid=True, seq_chunk=0):
+    """Sizes every context's workspace for one attention block of `cfg` ahead of the calls (tboa_hessian_workspace_bytes,
+    tboa_quantize_workspace_bytes, tboa_reserve_workspace), so that no call of quantize_attention_block allocates.  Returns
+    the bytes reserved per context."""
+    import paper_2602_04929_amd as tb
+    dt = {"fp32": torch.float32, "bf16": torch.bfloat16}[cfg.dtype]
+    wd = tb.F32 if cfg.dtype == "fp32" else tb.BF16
+    Hq, Hkv, dh, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_model
+
+    def layer(d_out, d_in, n_heads, per_head, block):
+        return ctx.quantize_workspace_bytes(tb.LayerDesc(d_out, d_in, n_heads, int(per_head), cfg.bits, block, cfg.group, wd, cd_iters,
+                                                         int(adaptive_grid), 100, 0.8, 0.01, 0.0))
+    hess = ctx.hessian_workspace_bytes(d, Hq, Hkv, dh, cfg.n_seqs, cfg.seq_len, dt, seq_chunk=seq_chunk)
+    o = layer(d, Hq * dh, 1, False, d)
+    v = layer(Hkv * dh, d, Hkv, True, cfg.block)
+    first = [layer((Hq + Hkv) * dh, d, Hq + Hkv, False, cfg.block)] if stack_qk else [layer(Hq * dh, d, Hq, False, cfg.block), layer(Hkv * dh, d, Hkv, False, cfg.block)]
+    jobs = first + [v]
+    ctxs = [ctx] + list(side_contexts or [])[:len(jobs) - 1]
+    need = [0] * len(ctxs)
+    for i, b in enumerate(jobs):          # job i runs on context i when there are side contexts, else all on the main one
+        need[i if i < len(ctxs) else 0] = max(need[i if i < len(ctxs) else 0], b)
+    need[0] = max(need[0], hess, o, *(jobs if len(ctxs) == 1 else []))
+    for c, n in zip(ctxs, need):
+        c.reserve_workspace(n)
+    return need
+
+
 def _split_stacked(res, rows_q, heads_q):
     """Per-layer views of a result of W_Q and W_K quantized as one stacked layer (heads are independent)."""
     def part(rs, hs):
-        lph = res["loss_per_head"][hs]
+        lph, terms = res["loss_per_head"][hs], res["loss_per_head_terms"][hs]
         d = {k: res[k][rs] for k in ("codes", "scales", "zeros", "W_deq")}
-        d.update(loss_per_head=lph, loss=float(sum(lph)), loss_quad=None, loss_cross=None)
+        d.update(loss_per_head=lph, loss_per_head_terms=terms, loss=float(sum(lph)),
+                 loss_quad=float(sum(t[0] for t in terms)), loss_cross=float(sum(t[1] for t in terms)))
         return d
     return part(slice(0, rows_q), slice(0, heads_q)), part(slice(rows_q, None), slice(heads_q, None))
 
@@ -32,8 +60,8 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     side_contexts: more contexts on streams of their own (see make_side_contexts): the layers then run side by side.
     stack_qk: W_Q and W_K share H_in and R (Table 1) and their heads are independent, so [W_Q; W_K] goes through
     tboa_quantize_layer as ONE layer of Hq + Hkv heads with H_out = [H_out^Q; H_out^K]: one factorisation of H_in, one P,
-    steps over twice the rows.  out["qk"] is that call's result, out["q"] and out["k"] are views of it (their loss is the sum
-    of their heads' losses; the split into the two loss terms exists for the stacked layer only)."""
+    steps over twice the rows.  out["qk"] is that call's result, out["q"] and out["k"] are views of it (their losses are the sums
+    over their heads)."""
     Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     X_fp = blk["X_fp"]
     X = blk["X"]

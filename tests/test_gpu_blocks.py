@@ -76,6 +76,30 @@ def test_gemm_bf16_nt(ctx, M, N, K):
     assert np.allclose(acc, want + 1.0, rtol=0, atol=1e-5 * np.sqrt(K) * 4)
 
 
+@pytest.mark.parametrize("M,N,K,persistent", [(512, 768, 256, False), (300, 200, 72, False), (1024, 1280, 512, True)])
+def test_gemm_f16_operands(ctx, lib, M, N, K, persistent):
+    """The same kernels on IEEE half operands (TBOA_GEMM_F16): three kernels (register-staged for K = 72, LDS-direct,
+    persistent), fp32 and 16-bit results, the blocked result layout."""
+    print("gemm f16", M, N, K, persistent, flush=True)
+    g = torch.Generator(device="cuda"); g.manual_seed(M + N + K)
+    A = torch.randn(M, K, generator=g, device="cuda").to(torch.float16)
+    B = torch.randn(N, K, generator=g, device="cuda").to(torch.float16)
+    pf = lib.GEMM_PERSISTENT if persistent else 0
+    want = A.double().cpu().numpy() @ B.double().cpu().numpy().T
+    got = ctx.gemm_bf16_nt(A, B, alpha=0.5, flags=pf).cpu().numpy()
+    assert np.allclose(got, 0.5 * want, rtol=0, atol=1e-5 * np.sqrt(K) * 4)
+    got16 = ctx.gemm_bf16_nt(A, B, out_dtype=torch.float16, flags=pf)
+    assert got16.dtype == torch.float16
+    assert np.allclose(got16.float().cpu().numpy(), want, rtol=2 ** -11, atol=1e-3)
+    # the products of half operands are exact in fp32 just as those of bf16 operands: same result as bf16 inputs that hold
+    # the same values (small integers are exact in both)
+    Ai = torch.randint(-8, 9, (M, K), generator=g, device="cuda").float(); Bi = torch.randint(-8, 9, (N, K), generator=g, device="cuda").float()
+    assert torch.equal(ctx.gemm_bf16_nt(Ai.half(), Bi.half(), flags=pf), ctx.gemm_bf16_nt(Ai.bfloat16(), Bi.bfloat16(), flags=pf))
+    if M % 256 == 0 and N % 256 == 0:
+        Ct = ctx.gemm_bf16_nt(A, B, out_dtype=torch.float16, flags=lib.GEMM_C_TILED | pf)
+        assert torch.equal(to_blocks(got16), Ct)
+
+
 def test_gemm_bf16_flags_and_batch(ctx, lib):
     g = torch.Generator(device="cuda"); g.manual_seed(3)
     n, K = 768, 512

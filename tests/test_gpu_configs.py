@@ -11,7 +11,7 @@ import torch
 
 from oracle import turboboa_ref as O
 from paper_2602_04929_amd import synth
-from tests.parity import compare_layer
+from tests.parity import check_returned_loss, compare_layer, head_of, rows_of
 
 pytestmark = pytest.mark.gpu
 
@@ -97,42 +97,86 @@ def check_group_entries(c, g, seed):
     assert e_hv <= 5e-4 and e_rv <= 5e-3          # probabilities and A X are rounded to bf16 before the last contraction
 
 
-def check_layer_head(c, wkey, hin, hout, rkey, n_heads, h, per_head=False):
-    cfg, blk, Hs, ctx = c["cfg"], c["blk"], c["Hs"], c["ctx"]
+def quantize_block(c):
+    """The whole block through the driver the benchmark uses (W_Q and W_K stacked, the layers on contexts of their own),
+    from the Hessians already built and checked."""
+    from paper_2602_04929_amd.pipeline import make_side_contexts, quantize_attention_block
+    cfg, blk, ctx = c["cfg"], c["blk"], c["ctx"]
+    print("  quantizing W_Q, W_K, W_V, W_O on the GPU", flush=True)
+    side = make_side_contexts(2)
+    b2 = dict(blk, signs=None)       # rotation and activation fake-quant were applied by build()
+    out = quantize_attention_block(ctx, b2, cfg, alpha=ALPHA, side_contexts=side)
+    torch.cuda.synchronize()
+    for s_ in side:
+        s_.close()
+    # the driver builds its Hessians again: they are the same bits as the ones checked entry by entry
+    for k in ("Hin_qk", "R_qk", "Hin_v", "R_v", "Hout_q", "Hout_k", "Hout_v"):
+        assert torch.equal(out["hessians"][k], c["Hs"][k]), k
+    c["out"] = out
+    return out
+
+
+def check_head(c, layer, h):
+    """Head h of W_Q / W_K / W_V (heads are independent) against the oracle, which consumes the GPU-built Hessians."""
+    cfg, blk, Hs, out = c["cfg"], c["blk"], c["Hs"], c["out"]
     dh = cfg.head_dim
     kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group)
-    print("  quantize_layer %s (%d heads) on the GPU" % (wkey, n_heads), flush=True)
-    got = ctx.quantize_layer(blk[wkey], Hs[hin], Hs[hout], Hs[rkey], n_heads, **kw)
+    wkey, hin, hout, rkey, per_head, got, gh = {
+        "q": ("Wq", "Hin_qk", "Hout_q", "R_qk", False, out["qk"], h),
+        "k": ("Wk", "Hin_qk", "Hout_k", "R_qk", False, out["qk"], cfg.n_q_heads + h),
+        "v": ("Wv", "Hin_v", "Hout_v", "R_v", True, out["v"], h)}[layer]
     rows = slice(h * dh, (h + 1) * dh)
     Hi = f64(Hs[hin][h:h + 1]) if per_head else f64(Hs[hin])
     Rr = f64(Hs[rkey][h:h + 1]) if per_head else f64(Hs[rkey])
-    print("  oracle quantize_layer on head", h, flush=True)
+    print("  oracle quantize_layer on head %d of W_%s" % (h, layer.upper()), flush=True)
     want = O.quantize_layer(f64(blk[wkey][rows]), Hi, f64(Hs[hout][h:h + 1]), Rr, 1, **kw)
-    sub = dict(codes=got["codes"][rows], scales=got["scales"][rows], zeros=got["zeros"][rows], W_deq=got["W_deq"][rows],
-               loss_per_head=[got["loss_per_head"][h]], loss=got["loss_per_head"][h], loss_quad=want["loss_quad"],
-               loss_cross=want["loss_cross"])
+    sub = head_of(got, gh, dh)
     frac = compare_layer(sub, want, label="%s head %d" % (wkey, h))
     print("  %s head %d: codes identical %.4f%%, loss %.6g vs %.6g" % (wkey, h, 100 * frac, sub["loss"], want["loss"]), flush=True)
-    assert np.isfinite(got["loss"])
-    return got
+
+
+def check_out_proj_rows(c, n_rows, seed):
+    """Sampled rows of W_O (H_out = I: rows decouple) against the oracle on the GPU-built H_in^O, R^O; the losses the library
+    returned for the whole layer against their evaluation from the W_deq it returned."""
+    cfg, blk, out = c["cfg"], c["blk"], c["out"]
+    rows = np.sort(np.random.default_rng(seed).choice(cfg.d_model, n_rows, replace=False))
+    ridx = torch.tensor(rows, device="cuda")
+    Hin_o, R_o = f64(out["Hin_o"]), f64(out["R_o"])
+    print("  oracle quantize_layer on %d sampled rows of W_O" % n_rows, flush=True)
+    want = O.quantize_layer(f64(blk["Wo"][ridx]), Hin_o, None, R_o, 1, bits=cfg.bits, block=n_rows, group=cfg.group)
+    sub = rows_of(out["o"], ridx, f64(blk["Wo"][ridx]), O.damp_hessian(Hin_o, 0.01), R_o, O.layer_loss)
+    frac = compare_layer(sub, want, label="o rows")
+    print("  W_O sampled rows: codes identical %.4f%%" % (100 * frac), flush=True)
+    check_returned_loss(out["o"], blk["Wo"], out["Hin_o"], None, out["R_o"], 1, label="o")
 
 
 def test_llama2_13b_shape_groupwise_int3(lib):
+    """INT3 with groups of 128 in-channels at d = 5120: a head of W_Q, a head of W_V (per-head H_in: its group grids use that
+    head's own Hessian blocks), rows of W_O (group-wise grids without out-channel coupling); sampled Hessian entries."""
     c = build(lib, "llama2-13b")
     try:
         check_qk_entries(c, 11)
-        check_layer_head(c, "Wq", "Hin_qk", "Hout_q", "R_qk", c["cfg"].n_q_heads, 21)
+        check_group_entries(c, 17, 21)
+        quantize_block(c)
+        check_head(c, "q", 21)
+        check_head(c, "v", 17)
+        check_out_proj_rows(c, 24, 22)
     finally:
         release(c)
 
 
 def test_llama2_70b_shape_grouped_query(lib):
+    """64 query heads on 8 KV heads, N = 64, d = 8192: a head of W_Q (H_out of its KV group), a head of W_K (H_out summed over
+    the 8 query heads of its group), a head of W_V (H_in, R and H_out summed over the group), rows of W_O."""
     c = build(lib, "llama2-70b")
     try:
         check_qk_entries(c, 12)
         check_group_entries(c, 5, 13)
-        # W_K: 8 KV heads, H_out summed over the 8 query heads of each group
-        check_layer_head(c, "Wk", "Hin_qk", "Hout_k", "R_qk", c["cfg"].n_kv_heads, 5)
+        quantize_block(c)
+        check_head(c, "q", 43)
+        check_head(c, "k", 5)
+        check_head(c, "v", 5)
+        check_out_proj_rows(c, 24, 23)
     finally:
         release(c)
 
@@ -148,6 +192,9 @@ def test_llama2_7b_w4a4_shape(lib):
         got = blk["X"].reshape(-1, cfg.d_model)[torch.tensor(tok, device="cuda")].float().cpu().numpy()
         assert np.array_equal(got, want)
         check_qk_entries(c, 15)
-        check_layer_head(c, "Wv", "Hin_v", "Hout_v", "R_v", cfg.n_kv_heads, 9, per_head=True)
+        quantize_block(c)
+        check_head(c, "q", 3)
+        check_head(c, "v", 9)
+        check_out_proj_rows(c, 24, 24)
     finally:
         release(c)

@@ -9,7 +9,7 @@ import torch
 
 from oracle import turboboa_ref as O
 from paper_2602_04929_amd import synth
-from tests.parity import compare_layer
+from tests.parity import check_returned_loss, compare_layer, head_of, rows_of
 
 pytestmark = pytest.mark.gpu
 
@@ -104,16 +104,14 @@ def test_quantize_layer_sampled_heads(full, layer):
     dh, nh = CFG.head_dim, CFG.n_q_heads
     print("full-size quantize_layer", name, flush=True)
     got = ctx.quantize_layer(blk[wkey], Hs[hin], Hs[hout], Hs[rkey], nh, bits=CFG.bits, block=CFG.block)
+    check_returned_loss(got, blk[wkey], Hs[hin], Hs[hout], Hs[rkey], nh, label=name)
     for h in (7, 30):
         rows = slice(h * dh, (h + 1) * dh)
         Hi = f64(Hs[hin][h:h + 1]) if per_head else f64(Hs[hin])
         Rr = f64(Hs[rkey][h:h + 1]) if per_head else f64(Hs[rkey])
         want = O.quantize_layer(f64(blk[wkey][rows]), Hi, f64(Hs[hout][h:h + 1]), Rr, 1, bits=CFG.bits, block=CFG.block)
-        sub = dict(codes=got["codes"][rows], scales=got["scales"][rows], zeros=got["zeros"][rows], W_deq=got["W_deq"][rows],
-                   loss_per_head=[got["loss_per_head"][h]])
-        # the per-layer totals are checked through the per-head value
-        sub["loss"] = got["loss_per_head"][h]; sub["loss_quad"] = want["loss_quad"]; sub["loss_cross"] = want["loss_cross"]
-        frac = compare_layer(sub, dict(want, loss=want["loss"]), label="%s head %d" % (name, h))
+        sub = head_of(got, h, dh)
+        frac = compare_layer(sub, want, label="%s head %d" % (name, h))
         print("  %s head %d: codes identical %.4f%%, loss %.6g vs %.6g" % (name, h, 100 * frac, sub["loss"], want["loss"]), flush=True)
     full[name] = got
     print("  grid-search passes %d, fully exact passes %d, fully exact rows %d" % (ctx.counter(0), ctx.counter(1), ctx.counter(2)), flush=True)
@@ -129,8 +127,8 @@ def test_quantize_out_proj_sampled_rows(full):
     rows = np.sort(np.random.default_rng(3).choice(CFG.d_model, 48, replace=False))
     ridx = torch.tensor(rows, device="cuda")
     want = O.quantize_layer(f64(blk["Wo"][ridx]), f64(Hin_o), None, f64(R_o), 1, bits=CFG.bits, block=len(rows))
-    sub = dict(codes=got["codes"][ridx], scales=got["scales"][ridx], zeros=got["zeros"][ridx], W_deq=got["W_deq"][ridx],
-               loss=want["loss"], loss_quad=want["loss_quad"], loss_cross=want["loss_cross"], loss_per_head=[want["loss"]])
+    sub = rows_of(got, ridx, f64(blk["Wo"][ridx]), O.damp_hessian(f64(Hin_o), 0.01), f64(R_o), O.layer_loss)
+    check_returned_loss(got, blk["Wo"], Hin_o, None, R_o, 1, label="o")
     frac = compare_layer(sub, want, label="o rows")
     print("  W_O sampled rows: codes identical %.4f%%" % (100 * frac), flush=True)
     assert np.isfinite(got["loss"])

@@ -6,7 +6,7 @@ import torch
 
 from oracle import turboboa_ref as O
 from paper_2602_04929_amd import synth
-from tests.parity import compare_layer, stacked
+from tests.parity import compare_layer, rows_of, stacked
 
 pytestmark = pytest.mark.gpu
 
@@ -139,8 +139,7 @@ def test_llama2_7b_shape_mlp_sampled(lib):
         print("  oracle quantize_layer on %d sampled rows of %s" % (nrows, layer), flush=True)
         want = O.quantize_layer(f64(m[wkey][ridx]), f64(got["hessians"][hk]), None, f64(got["hessians"][rk]), 1, bits=cfg.bits, block=nrows)
         g = got[layer]
-        sub = dict(codes=g["codes"][ridx], scales=g["scales"][ridx], zeros=g["zeros"][ridx], W_deq=g["W_deq"][ridx],
-                   loss=want["loss"], loss_quad=want["loss_quad"], loss_cross=want["loss_cross"], loss_per_head=[want["loss"]])
+        sub = rows_of(g, ridx, f64(m[wkey][ridx]), O.damp_hessian(f64(got["hessians"][hk]), 0.01), f64(got["hessians"][rk]), O.layer_loss)
         frac = compare_layer(sub, want, label=layer + " rows")
         print("  %s sampled rows: codes identical %.4f%%" % (layer, 100 * frac), flush=True)
     c.close()

@@ -163,15 +163,44 @@ def test_packed_layer_carries_the_quantized_weights(ctx):
     assert torch.allclose(y.double(), ref, rtol=1e-5, atol=1e-6 * ref.abs().max().item())
 
 
-def test_grid_search_guard_takes_the_exact_path(ctx, monkeypatch):
-    """The two-phase search repeats a pass with exact costs for every candidate when its approximate costs stray from the
-    exact re-evaluations by more than a fraction of tau.  With the fraction set to 0 every pass that re-evaluated anything
-    takes that path; the result must be the oracle's all the same."""
+def test_grid_search_guard_takes_the_exact_path(ctx):
+    """The two-phase search compares every exact re-evaluation with its approximation, and a call in which one strays by
+    more than grid_guard * tau is run again with exact costs for every candidate.  With a vanishing grid_guard every call
+    that re-evaluated anything takes that path; the result must be the oracle's all the same, and equal to what asking for
+    exact costs from the start (negative grid_guard) gives."""
     W, Hin, Hout, R = make_case(77, 2, 32, 256, T=1024, mix=0.3)
-    before = ctx.counter(1)
-    monkeypatch.setenv("TBOA_GRID_GUARD", "0")
-    got, want = run_both(ctx, W, Hin, Hout, R, 2, bits=2, block=16)
-    monkeypatch.delenv("TBOA_GRID_GUARD")
-    assert ctx.counter(1) > before, "no pass fell back to exact costs"
+    dev = lambda a: torch.tensor(a, device="cuda")
+    before, passes = ctx.counter(1), ctx.counter(0)
+    got = ctx.quantize_layer(dev(W), dev(Hin), dev(Hout), dev(R), 2, bits=2, block=16, grid_guard=1e-300)
+    assert ctx.counter(1) == before + 1, "the call was not run again with exact costs"
+    assert ctx.counter(0) > passes
+    want = O.quantize_layer(W.astype(np.float64), Hin.astype(np.float64), Hout.astype(np.float64), R.astype(np.float64), 2, bits=2, block=16)
     frac = compare_layer(got, want, label="guard")
-    print("guarded passes: %d, codes identical %.4f%%" % (ctx.counter(1) - before, 100 * frac), flush=True)
+    print("guarded call: codes identical %.4f%%" % (100 * frac), flush=True)
+    passes = ctx.counter(0)
+    exact = ctx.quantize_layer(dev(W), dev(Hin), dev(Hout), dev(R), 2, bits=2, block=16, grid_guard=-1.0)
+    assert ctx.counter(0) == passes and ctx.counter(1) == before + 1          # no two-phase pass at all
+    assert torch.equal(exact["codes"], got["codes"]) and torch.equal(exact["scales"], got["scales"])
+
+
+def test_workspace_queries(ctx, lib):
+    """tboa_quantize_workspace_bytes bounds what a call takes; a context that reserved it does not grow."""
+    W, Hin, Hout, R = make_case(5, 2, 32, 256, T=1024)
+    t = lambda a: torch.tensor(a, device="cuda")
+    c2 = lib.Context()
+    try:
+        desc = c2.layer_desc(t(W), t(Hin), 2, bits=2, block=8)
+        need = c2.quantize_workspace_bytes(desc)
+        assert need > 0 and c2.workspace_bytes() == 0
+        c2.reserve_workspace(need)
+        assert c2.workspace_bytes() == need
+        a = c2.quantize_layer(t(W), t(Hin), t(Hout), t(R), 2, bits=2, block=8)
+        assert c2.workspace_bytes() == need                      # with H_out and R: exactly the bound
+        c2.quantize_layer(t(W), t(Hin), None, None, 2, bits=2, block=8)
+        assert c2.workspace_bytes() == need                      # without them: less
+        b = ctx.quantize_layer(t(W), t(Hin), t(Hout), t(R), 2, bits=2, block=8)
+        assert torch.equal(a["codes"], b["codes"]) and a["loss"] == b["loss"]
+        bad = c2.layer_desc(t(W), t(Hin), 2, bits=5, block=8)
+        assert c2.quantize_workspace_bytes(bad) == 0
+    finally:
+        c2.close()

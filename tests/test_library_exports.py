@@ -67,3 +67,22 @@ def test_descriptor_structs_match_the_header():
                 fields += [(n.strip(), ctype) for n in names.split(",")]
         got = [(n, {"c_int": "int", "c_double": "double", "c_float": "float"}[t.__name__]) for n, t in cls._fields_]
         assert got == fields
+
+
+def test_workspace_queries_are_host_arithmetic():
+    """tboa_hessian_workspace_bytes / tboa_quantize_workspace_bytes run the library's own planning code on the host: no device
+    is touched, sizes grow with the problem, an invalid descriptor gives 0."""
+    import paper_2602_04929_amd as tb
+    import torch
+    C = tb.Context
+    small = C.hessian_workspace_bytes(256, 4, 4, 64, 8, 128, torch.float32)
+    big = C.hessian_workspace_bytes(4096, 32, 32, 128, 128, 2048, torch.bfloat16)
+    gqa = C.hessian_workspace_bytes(8192, 64, 8, 128, 128, 2048, torch.bfloat16)
+    assert 0 < small < big < gqa < 288 * 2 ** 30
+    assert C.hessian_workspace_bytes(256, 4, 3, 64, 8, 128, torch.float32) == 0        # heads not divisible
+    d = tb.LayerDesc(4096, 4096, 32, 0, 2, 32, 0, tb.BF16, 1, 1, 100, 0.8, 0.01, 0.0)
+    per_head = tb.LayerDesc(4096, 4096, 32, 1, 2, 32, 0, tb.BF16, 1, 1, 100, 0.8, 0.01, 0.0)
+    a, b = C.quantize_workspace_bytes(d), C.quantize_workspace_bytes(per_head)
+    assert 0 < a < b < 288 * 2 ** 30
+    assert C.quantize_workspace_bytes(tb.LayerDesc(4096, 4096, 32, 0, 5, 32, 0, tb.BF16, 1, 1, 100, 0.8, 0.01, 0.0)) == 0
+    print("workspace: 7B Hessians %.1f GiB, 70B Hessians %.1f GiB, 7B W_Q %.1f GiB, 7B W_V %.1f GiB" % (big / 2 ** 30, gqa / 2 ** 30, a / 2 ** 30, b / 2 ** 30))
