@@ -112,7 +112,7 @@ def cpu_baseline(blk, cfg, hessians, out):
                                                                         t_opair, pairs, t_oseq, cfg.n_seqs)}
 
 
-def roofline_probe(ctx, cfg, torch, tag, zero=False, reps=0):
+def roofline_probe(ctx, cfg, torch, tag, zero=False, reps=0, persistent=False):
     """The command the HBM-traffic counter runs are made with: one plain copy of 1 GiB (a kernel of known traffic, to scale
     the counters), then ONE launch of the benchmark's dominant kernel in its launch shape, for all KV heads over a chunk of 8
     sequences, accumulating into fp32, operands in 16 x 32 blocks at the benchmark's row pitch (random values):
@@ -138,7 +138,7 @@ def roofline_probe(ctx, cfg, torch, tag, zero=False, reps=0):
     torch.mul(src, 1.0, out=dst)                                              # reads 1 GiB, writes 1 GiB
     torch.cuda.synchronize()
     A = ZT[:, :, :K]; B = XT[None, :, :K].expand(Hkv, n, K)
-    flags = tb.GEMM_A_TILED | tb.GEMM_B_TILED | (tb.GEMM_LOWER if tag == "hv_syrk" else 0)
+    flags = tb.GEMM_A_TILED | tb.GEMM_B_TILED | (tb.GEMM_LOWER if tag == "hv_syrk" else 0) | (tb.GEMM_PERSISTENT if persistent else 0)
     ctx.gemm_bf16_nt(A, B, C_out=C, accumulate=True, flags=flags)
     torch.cuda.synchronize()
     cells = n * (n + 1) // 2 if tag == "hv_syrk" else n * n
@@ -180,6 +180,7 @@ def main():
     ap.add_argument("--probe-tag", default="rv", choices=("rv", "hv_syrk"), help="with --roofline-probe: which launch")
     ap.add_argument("--probe-zero", action="store_true", help="with --roofline-probe: all-zero operands (same launch otherwise)")
     ap.add_argument("--probe-reps", type=int, default=0, help="with --roofline-probe: time this many further launches of the kernel")
+    ap.add_argument("--probe-persistent", action="store_true", help="with --roofline-probe: the persistent form of the kernel (one resident workgroup per CU)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (heads would shard across GPUs, see DESIGN.md); use --gpus 1", file=sys.stderr)
@@ -199,7 +200,7 @@ def main():
     torch.cuda.set_device(0)
     if args.roofline_probe:
         ctx = tb.Context()
-        roofline_probe(ctx, cfg, torch, args.probe_tag, zero=args.probe_zero, reps=args.probe_reps)
+        roofline_probe(ctx, cfg, torch, args.probe_tag, zero=args.probe_zero, reps=args.probe_reps, persistent=args.probe_persistent)
         ctx.close()
         return
     blk = synth.make_block(cfg, seed=0, device="cuda:0")

@@ -151,6 +151,27 @@ int tboa_build_hessian_linear(tboa_ctx* ctx, int64_t n_tokens, int d_in, int x_d
 int tboa_swiglu_forward(tboa_ctx* ctx, int64_t n_tokens, int d, int d_ff, int x_dtype, const void* X,
                         int w_dtype, const void* W_gate, const void* W_up, void* Act);
 
+/* Out-channel Hessian factor of a projection whose partner is given as a weight matrix (Table 1 without positional rotation:
+ * K_g^T K_g = W_K,g H_in W_K,g^T and likewise for Q):  H_out[g] = sum over the `rep` consecutive heads h of group g of W_h H_in W_h^T,
+ * W_h = rows h*head_dim .. of W.  With W = the DEQUANTIZED W_Q (w_dtype TBOA_F32) and rep = Hq / Hkv this is the H_out of W_K as
+ * Algorithm 1 computes it when its Hessians are formed inside the loop over the layers (line 4), after W_Q has been quantized;
+ * with W = W_K and rep = 1 it is the H_out of W_Q (per KV head).  H_in [d_in, d_in] fp32 (undamped), W [n_heads*rep*head_dim, d_in]
+ * in w_dtype (TBOA_F32 or TBOA_BF16), H_out [n_heads, head_dim, head_dim] fp32.  fp64 arithmetic. */
+int tboa_build_hout(tboa_ctx* ctx, int d_in, int n_heads, int rep, int head_dim, const float* H_in, int w_dtype, const void* W,
+                    float* H_out);
+
+/* Forward pass of the block, for the driver that carries the two activation streams from one transformer block to the next
+ * (Sec. 3.2: the deviation that Prop. 3.2 corrects is the one accumulated through the preceding quantized layers):
+ * tboa_attention_forward: O[t, h dh + c] = sum_k A_h[t, k] V_g(h)[k, c], A_h = softmax(Q_h K_g^T / sqrt(d_h)) per sequence (the input of
+ *   the output projection).  X [T, d_model] (x_dtype); Wq [Hq dh, d], Wk, Wv [Hkv dh, d] in w_dtype: x_dtype, or TBOA_F32 for
+ *   dequantized weights; O [T, Hq dh] (x_dtype).  bf16 path: same products as tboa_build_hessian_out_proj (synchronises).
+ * tboa_linear_forward: Y = X W^T (+ Res).  X [n_tokens, d_in], Res (or NULL) and Y [n_tokens, d_out] in x_dtype; W [d_out, d_in] in
+ *   w_dtype (x_dtype or TBOA_F32). */
+int tboa_attention_forward(tboa_ctx* ctx, const tboa_attn_desc* desc, const void* X, int w_dtype, const void* Wq, const void* Wk,
+                           const void* Wv, void* O);
+int tboa_linear_forward(tboa_ctx* ctx, int64_t n_tokens, int d_in, int d_out, int x_dtype, const void* X, int w_dtype, const void* W,
+                        const void* Res, void* Y);
+
 /* Min-Max dynamic per-token activation quantizer (weight-activation experiments): one asymmetric
  * (scale, zero) per token from that token's min and max, `bits` levels; writes the dequantized
  * activations.  X_in, X_out [T, d] in `dtype` (TBOA_F32 or TBOA_BF16); may alias. */

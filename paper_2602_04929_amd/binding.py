@@ -65,6 +65,9 @@ def _load():
         "tboa_hadamard_rotate": ([vp, i64, i32, i32, vp, vp, vp], i32),
         "tboa_build_hessian_linear": ([vp, i64, i32, i32, f64, vp, vp, vp, vp], i32),
         "tboa_swiglu_forward": ([vp, i64, i32, i32, i32, vp, i32, vp, vp, vp], i32),
+        "tboa_build_hout": ([vp, i32, i32, i32, i32, vp, i32, vp, vp], i32),
+        "tboa_attention_forward": ([vp, C.POINTER(AttnDesc), vp, i32, vp, vp, vp, vp], i32),
+        "tboa_linear_forward": ([vp, i64, i32, i32, i32, vp, i32, vp, vp, vp], i32),
         "tboa_packed_words_per_row": ([i32, i32], i64),
         "tboa_pack_codes": ([vp, i32, i32, i32, vp, vp], i32),
         "tboa_dequant_gemv": ([vp, i32, i32, i32, i32, vp, vp, vp, vp, vp], i32),
@@ -306,6 +309,33 @@ class Context:
         d = X.shape[-1]; dff = Wg.shape[0]
         out = torch.empty(*X.shape[:-1], dff, dtype=X.dtype, device=X.device)
         self._check(_lib.tboa_swiglu_forward(self._h, X.numel() // d, d, dff, _dtype_code(X), _ptr(X), _dtype_code(Wg), _ptr(Wg), _ptr(Wu), _ptr(out)))
+        return out
+
+    def build_hout(self, H_in, W, n_heads, rep, head_dim):
+        """H_out[g] = sum over the rep heads of group g of W_h H_in W_h^T (fp32 [n_heads, dh, dh]); W in fp32 or bf16."""
+        _dev(H_in, torch.float32); _dev(W)
+        out = torch.empty(n_heads, head_dim, head_dim, dtype=torch.float32, device=W.device)
+        self._check(_lib.tboa_build_hout(self._h, H_in.shape[0], n_heads, rep, head_dim, _ptr(H_in), _dtype_code(W), _ptr(W), _ptr(out)))
+        return out
+
+    def attention_forward(self, X, Wq, Wk, Wv, n_q_heads, n_kv_heads, head_dim, causal=True):
+        """concat_h(A_h V_h) [S, L, Hq dh] of X [S, L, d]; weights in X's type or fp32 (dequantized)."""
+        _dev(X); _dev(Wq); _dev(Wk, Wq.dtype); _dev(Wv, Wq.dtype)
+        S, L, d = X.shape
+        desc = AttnDesc(d, n_q_heads, n_kv_heads, head_dim, S, L, _dtype_code(X), int(causal), 0.0, 0)
+        out = torch.empty(S, L, n_q_heads * head_dim, dtype=X.dtype, device=X.device)
+        self._check(_lib.tboa_attention_forward(self._h, C.byref(desc), _ptr(X), _dtype_code(Wq), _ptr(Wq), _ptr(Wk), _ptr(Wv), _ptr(out)))
+        return out
+
+    def linear_forward(self, X, W, residual=None):
+        """X W^T (+ residual); W [d_out, d_in] in X's type or fp32 (dequantized)."""
+        _dev(X); _dev(W)
+        if residual is not None:
+            _dev(residual, X.dtype)
+        d_in = X.shape[-1]; d_out = W.shape[0]
+        out = torch.empty(*X.shape[:-1], d_out, dtype=X.dtype, device=X.device)
+        self._check(_lib.tboa_linear_forward(self._h, X.numel() // d_in, d_in, d_out, _dtype_code(X), _ptr(X), _dtype_code(W), _ptr(W),
+                                             _ptr(residual), _ptr(out)))
         return out
 
     def pack_codes(self, codes, bits):

@@ -1001,9 +1001,32 @@ int weight_operands(tboa_ctx* ctx, const float* W, int rows, int n, bf16* hi, bf
     return 0;
 }
 
-int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, const bf16* X_fp, const float* Wq_deq,
-                                const float* Wk_deq, const float* Wv_deq, const bf16* Wq, const bf16* Wk, const bf16* Wv, float* Hin_o,
-                                float* R_o, const bf16* fp_cache) {
+// sums the (hi, lo) halves of a transposed attention output OT [dq, T (+ pad)] into token-major rows O [T, dq] (bf16)
+__global__ __launch_bounds__(256) void ot_rows_kernel(const bf16* __restrict__ OTh, const bf16* __restrict__ OTl, long long ld, int dq,
+                                                      long long T, bf16* __restrict__ O) {
+    __shared__ float t[64][65];
+    const long long t0 = (long long)blockIdx.x * 64; const int c0 = blockIdx.y * 64;
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int c = i >> 6, tt = i & 63;
+        float v = 0.f;
+        if (c0 + c < dq && t0 + tt < T) {
+            const long long o = (long long)(c0 + c) * ld + t0 + tt;
+            v = __bfloat162float(OTh[o]) + __bfloat162float(OTl[o]);
+        }
+        t[c][tt] = v;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+        const int tt = i >> 6, c = i & 63;
+        if (c0 + c < dq && t0 + tt < T) O[(t0 + tt) * dq + c0 + c] = __float2bfloat16(t[c][tt]);
+    }
+}
+
+// Hessian of the output projection, or (O_rows given) the attention output itself as token-major rows.
+// wq_dtype: type of the weights the quantized path uses, TBOA_F32 (dequantized) or TBOA_BF16.
+int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, const bf16* X_fp, int wq_dtype, const void* Wq_deq,
+                                const void* Wk_deq, const void* Wv_deq, const bf16* Wq, const bf16* Wk, const bf16* Wv, float* Hin_o,
+                                float* R_o, const bf16* fp_cache, bf16* O_rows) {
     Dims D = dims_of(ctx, d);
     TB_TRY(check_bf16_dims(D));
     const int T = D.T, dm = D.dm, Hq = D.Hq, dh = D.dh, L = D.L, dq = D.dq, dkv = D.dkv, rep = D.rep;
@@ -1032,10 +1055,12 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
     }
     hipStream_t st = ctx->stream;
     // dequantized weights in integer form (one GEMM per product) or as exact-to-16-bits (hi, lo) bf16 pairs (two)
-    const bf16 *Wql_u, *Wkl_u, *Wvl_u; const float *sq, *sk, *sv;
-    TB_TRY(weight_operands(ctx, Wq_deq, dq, dm, Wqh, Wql, steps, &Wql_u, &sq));
-    TB_TRY(weight_operands(ctx, Wk_deq, dkv, dm, Wkh, Wkl, steps + dq, &Wkl_u, &sk));
-    TB_TRY(weight_operands(ctx, Wv_deq, dkv, dm, Wvh, Wvl, steps + dq + dkv, &Wvl_u, &sv));
+    const bf16 *Wql_u = nullptr, *Wkl_u = nullptr, *Wvl_u = nullptr; const float *sq = nullptr, *sk = nullptr, *sv = nullptr;
+    if (wq_dtype == TBOA_F32) {
+        TB_TRY(weight_operands(ctx, (const float*)Wq_deq, dq, dm, Wqh, Wql, steps, &Wql_u, &sq));
+        TB_TRY(weight_operands(ctx, (const float*)Wk_deq, dkv, dm, Wkh, Wkl, steps + dq, &Wkl_u, &sk));
+        TB_TRY(weight_operands(ctx, (const float*)Wv_deq, dkv, dm, Wvh, Wvl, steps + dq + dkv, &Wvl_u, &sv));
+    } else { Wqh = (bf16*)Wq_deq; Wkh = (bf16*)Wk_deq; Wvh = (bf16*)Wv_deq; }      // bf16 weights are exact operands as they are
     // half operands when the activations fit half; a value V = W_v x beyond the range of half (|x|_max ||w||_1 > 65504) would
     // turn infinite there and surface as a non-finite Hessian, which tboa_quantize_layer rejects
     TB_TRY(fits_half(ctx, X, fp ? X_fp : nullptr, (long long)T * dm, &D.f16));
@@ -1079,6 +1104,11 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
                 TB_TRY(gemm_bf16_nt(ctx, o));
             }
         }
+    }
+    if (O_rows) {
+        hipLaunchKernelGGL(ot_rows_kernel, dim3((unsigned)((T + 63) / 64), (dq + 63) / 64), dim3(256), 0, st, OT, OTl, TP, dq, (long long)T, O_rows);
+        TB_KERNEL_CHECK(ctx);
+        if (!Hin_o) return 0;
     }
     // H_in^O = (O_hi + O_lo)^T (O_hi + O_lo), R_o = alpha (dO_hi + dO_lo)^T (O_hi + O_lo), without the lo.lo terms
     const GramPair ho[3] = {{OT, OT}, {OTl, OT}, {OT, OTl}};
@@ -1156,6 +1186,41 @@ int swiglu_forward_bf16(tboa_ctx* ctx, long long T, int d, int dff, const bf16* 
         if (u_lo) TB_TRY(gemm_bf16_nt(ctx, nt(rows, dff, d, 1.f, Xc, d, u_lo, d, U, dff, TBOA_F32, 1, 0)));
         hipLaunchKernelGGL(swiglu_kernel<bf16>, dim3(g1((long long)rows * dff)), dim3(256), 0, st, G, U, gs, us, dff, Act + t0 * dff,
                            (long long)rows * dff);
+        TB_KERNEL_CHECK(ctx);
+    }
+    return 0;
+}
+
+// Y[t, c] = G[t, c] * scale[c] + Res[t, c]  (scale, Res optional)
+__global__ void linear_out_kernel(const float* __restrict__ G, const float* __restrict__ scale, const bf16* __restrict__ Res, int dout,
+                                  bf16* __restrict__ Y, long long n) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+        float v = scale ? G[i] * scale[(int)(i % dout)] : G[i];
+        if (Res) v += __bfloat162float(Res[i]);
+        Y[i] = __float2bfloat16(v);
+    }
+}
+
+// Y = X W^T (+ Res) for bf16 activations; W bf16, or fp32 (dequantized: integer form or (hi, lo) pair)
+int linear_forward_bf16(tboa_ctx* ctx, long long T, int din, int dout, const bf16* X, int w_dtype, const void* W, const bf16* Res, bf16* Y) {
+    if (din % 8 || dout % 8) return tboa_fail(ctx, TBOA_EINVAL, "linear_forward: d_in and d_out must be multiples of 8 for bf16 inputs");
+    const bool split = (w_dtype == TBOA_F32);
+    const long long chunk = 16384;
+    bf16 *Wh = nullptr, *Wl = nullptr; float *G, *steps = nullptr;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        if (split) { Wh = ar.get<bf16>((size_t)dout * din); Wl = ar.get<bf16>((size_t)dout * din); steps = ar.get<float>((size_t)dout); }
+        G = ar.get<float>((size_t)chunk * dout);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    const bf16* w_hi = (const bf16*)W; const bf16* w_lo = nullptr; const float* sc = nullptr;
+    if (split) { TB_TRY(weight_operands(ctx, (const float*)W, dout, din, Wh, Wl, steps, &w_lo, &sc)); w_hi = Wh; }
+    for (long long t0 = 0; t0 < T; t0 += chunk) {
+        const int rows = (int)((T - t0 < chunk) ? T - t0 : chunk);
+        TB_TRY(gemm_bf16_nt(ctx, nt(rows, dout, din, 1.f, X + t0 * din, din, w_hi, din, G, dout, TBOA_F32, 0, 0)));
+        if (w_lo) TB_TRY(gemm_bf16_nt(ctx, nt(rows, dout, din, 1.f, X + t0 * din, din, w_lo, din, G, dout, TBOA_F32, 1, 0)));
+        hipLaunchKernelGGL(linear_out_kernel, dim3(g1((long long)rows * dout)), dim3(256), 0, ctx->stream, G, sc, Res ? Res + t0 * dout : nullptr, dout,
+                           Y + t0 * dout, (long long)rows * dout);
         TB_KERNEL_CHECK(ctx);
     }
     return 0;
@@ -1286,8 +1351,8 @@ extern "C" int tboa_build_hessian_out_proj(tboa_ctx* ctx, const tboa_attn_desc* 
         return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_out_proj: R_o needs X_fp and the full-precision weights");
     if (fp_cache && ((uintptr_t)fp_cache & 15)) return tboa_fail(ctx, TBOA_EINVAL, "build_hessian_out_proj: fp_cache must be 16-byte aligned");
     if (d->x_dtype == TBOA_F32) return build_hessian_out_proj_f64(ctx, d, X, X_fp, Wq_deq, Wk_deq, Wv_deq, Wq, Wk, Wv, Hin_o, R_o);
-    return build_hessian_out_proj_bf16(ctx, d, (const bf16*)X, (const bf16*)X_fp, Wq_deq, Wk_deq, Wv_deq, (const bf16*)Wq, (const bf16*)Wk,
-                                       (const bf16*)Wv, Hin_o, R_o, (const bf16*)fp_cache);
+    return build_hessian_out_proj_bf16(ctx, d, (const bf16*)X, (const bf16*)X_fp, TBOA_F32, Wq_deq, Wk_deq, Wv_deq, (const bf16*)Wq, (const bf16*)Wk,
+                                       (const bf16*)Wv, Hin_o, R_o, (const bf16*)fp_cache, nullptr);
 }
 
 // The workspace the two Hessian builds of an attention block need: their own planning code, run on a host-only context that
@@ -1302,6 +1367,55 @@ extern "C" size_t tboa_hessian_workspace_bytes(const tboa_attn_desc* d) {
     rc = tboa_build_hessian_out_proj(&plan, d, in, in, out, out, out, in, in, in, out, out, nullptr);
     if (rc != TB_PLAN_STOP) return 0;
     return plan.plan_bytes;
+}
+
+extern "C" int tboa_build_hout(tboa_ctx* ctx, int d_in, int n_heads, int rep, int head_dim, const float* H_in, int w_dtype, const void* W,
+                               float* H_out) {
+    if (!ctx) return TBOA_EINVAL;
+    if (d_in <= 0 || n_heads <= 0 || rep <= 0 || head_dim <= 0 || !H_in || !W || !H_out) return tboa_fail(ctx, TBOA_EINVAL, "build_hout: bad arguments");
+    if (w_dtype != TBOA_F32 && w_dtype != TBOA_BF16) return tboa_fail(ctx, TBOA_EINVAL, "build_hout: w_dtype must be fp32 or bf16");
+    const long long rows = (long long)n_heads * rep * head_dim, dd = (long long)d_in * d_in, hh = (long long)head_dim * head_dim;
+    double *H64, *W64, *TW, *Ho;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        H64 = ar.get<double>((size_t)dd); W64 = ar.get<double>((size_t)rows * d_in); TW = ar.get<double>((size_t)rows * d_in);
+        Ho = ar.get<double>((size_t)n_heads * hh);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    TB_TRY(launch_cvt_f32_to_f64(ctx, H_in, H64, dd));
+    TB_TRY(launch_cvt_to_f64(ctx, W, w_dtype, W64, rows * d_in));
+    GemmF64 a{};      // TW = W H_in
+    a.M = (int)rows; a.N = d_in; a.K = d_in; a.alpha = 1.0; a.beta = 0.0; a.A = W64; a.sam = d_in; a.sak = 1; a.B = H64; a.sbk = d_in; a.sbn = 1;
+    a.C = TW; a.ldc = d_in; a.batch = 1;
+    TB_TRY(gemm_f64(ctx, a));
+    GemmF64 b{};      // per head of the result: sum over its rep row blocks of TW_h W_h^T
+    b.M = head_dim; b.N = head_dim; b.K = d_in; b.alpha = 1.0; b.sam = d_in; b.sak = 1; b.sbk = 1; b.sbn = d_in;
+    b.C = Ho; b.ldc = head_dim; b.batch = n_heads; b.strideA = (long long)rep * head_dim * d_in; b.strideB = b.strideA; b.strideC = hh;
+    for (int r = 0; r < rep; ++r) {
+        b.A = TW + (long long)r * head_dim * d_in; b.B = W64 + (long long)r * head_dim * d_in; b.beta = r ? 1.0 : 0.0;
+        TB_TRY(gemm_f64(ctx, b));
+    }
+    return launch_cvt_f64_to_f32(ctx, Ho, H_out, (int64_t)n_heads * hh);
+}
+
+extern "C" int tboa_attention_forward(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, int w_dtype, const void* Wq, const void* Wk,
+                                      const void* Wv, void* O) {
+    if (!ctx) return TBOA_EINVAL;
+    TB_TRY(check_attn_desc(ctx, d));
+    if (!X || !Wq || !Wk || !Wv || !O) return tboa_fail(ctx, TBOA_EINVAL, "attention_forward: null argument");
+    if (w_dtype != TBOA_F32 && w_dtype != d->x_dtype) return tboa_fail(ctx, TBOA_EINVAL, "attention_forward: weights must be fp32 or of the activations' type");
+    if (d->x_dtype == TBOA_F32) return attention_forward_f64(ctx, d, (const float*)X, (const float*)Wq, (const float*)Wk, (const float*)Wv, (float*)O);
+    return build_hessian_out_proj_bf16(ctx, d, (const bf16*)X, nullptr, w_dtype, Wq, Wk, Wv, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, (bf16*)O);
+}
+
+extern "C" int tboa_linear_forward(tboa_ctx* ctx, int64_t n_tokens, int d_in, int d_out, int x_dtype, const void* X, int w_dtype, const void* W,
+                                   const void* Res, void* Y) {
+    if (!ctx) return TBOA_EINVAL;
+    if (n_tokens <= 0 || n_tokens > 2147483647LL || d_in <= 0 || d_out <= 0 || !X || !W || !Y) return tboa_fail(ctx, TBOA_EINVAL, "linear_forward: bad arguments");
+    if (w_dtype != TBOA_F32 && w_dtype != x_dtype) return tboa_fail(ctx, TBOA_EINVAL, "linear_forward: weights must be fp32 or of the activations' type");
+    if (x_dtype == TBOA_F32) return linear_forward_f64(ctx, n_tokens, d_in, d_out, (const float*)X, (const float*)W, (const float*)Res, (float*)Y);
+    if (x_dtype == TBOA_BF16) return linear_forward_bf16(ctx, n_tokens, d_in, d_out, (const bf16*)X, w_dtype, W, (const bf16*)Res, (bf16*)Y);
+    return tboa_fail(ctx, TBOA_EINVAL, "linear_forward: x_dtype must be fp32 or bf16");
 }
 
 extern "C" size_t tboa_fp_cache_bytes(const tboa_attn_desc* d) {

@@ -181,6 +181,53 @@ int build_hessian_out_proj_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const voi
     return 0;
 }
 
+// attention output concat_h(A_h V_g(h)) [T, Hq dh] (fp32) of fp32 activations and weights, on the fp64 matrix cores
+int attention_forward_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const float* X, const float* Wq, const float* Wk, const float* Wv, float* O) {
+    F64Attn a{ctx, d, d->n_seqs * d->seq_len, d->d_model, d->n_q_heads, d->n_kv_heads, d->head_dim, d->seq_len, d->n_seqs,
+              d->n_q_heads / d->n_kv_heads, d->n_q_heads * d->head_dim, d->n_kv_heads * d->head_dim};
+    const int T = a.T, dm = a.dm, L = a.L, dq = a.dq, dkv = a.dkv;
+    double *X64, *Wq64, *Wk64, *Wv64, *Qa, *Ka, *Va, *Sb, *Pb, *O64;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        X64 = ar.get<double>((size_t)T * dm);
+        Wq64 = ar.get<double>((size_t)dq * dm); Wk64 = ar.get<double>((size_t)dkv * dm); Wv64 = ar.get<double>((size_t)dkv * dm);
+        Qa = ar.get<double>((size_t)T * dq); Ka = ar.get<double>((size_t)T * dkv); Va = ar.get<double>((size_t)T * dkv);
+        Sb = ar.get<double>((size_t)L * L); Pb = ar.get<double>((size_t)L * L);
+        O64 = ar.get<double>((size_t)T * dq);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    TB_TRY(launch_cvt_to_f64(ctx, X, TBOA_F32, X64, (int64_t)T * dm));
+    TB_TRY(launch_cvt_to_f64(ctx, Wq, TBOA_F32, Wq64, (int64_t)dq * dm));
+    TB_TRY(launch_cvt_to_f64(ctx, Wk, TBOA_F32, Wk64, (int64_t)dkv * dm));
+    TB_TRY(launch_cvt_to_f64(ctx, Wv, TBOA_F32, Wv64, (int64_t)dkv * dm));
+    TB_TRY(attn_output_f64(a, X64, Wq64, Wk64, Wv64, Qa, Ka, Va, Sb, Pb, O64));
+    return launch_cvt_f64_to_f32(ctx, O64, O, (int64_t)T * dq);
+}
+
+namespace {
+__global__ void add_cvt_kernel(const double* __restrict__ Y, const float* __restrict__ Res, float* __restrict__ out, long long n) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+        out[i] = (float)(Res ? Y[i] + (double)Res[i] : Y[i]);
+}
+}  // namespace
+
+// Y = X W^T (+ Res), fp32 in and out, on the fp64 matrix cores
+int linear_forward_f64(tboa_ctx* ctx, long long T, int din, int dout, const float* X, const float* W, const float* Res, float* Y) {
+    double *X64, *W64, *Y64;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        X64 = ar.get<double>((size_t)T * din); W64 = ar.get<double>((size_t)dout * din); Y64 = ar.get<double>((size_t)T * dout);
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    TB_TRY(launch_cvt_to_f64(ctx, X, TBOA_F32, X64, (int64_t)T * din));
+    TB_TRY(launch_cvt_to_f64(ctx, W, TBOA_F32, W64, (int64_t)dout * din));
+    TB_TRY(gemm_f64(ctx, mk((int)T, dout, din, 1.0, X64, din, 1, W64, 1, din, 0.0, Y64, dout)));
+    long long n = T * dout, gb = (n + 255) / 256; if (gb > 16384) gb = 16384;
+    hipLaunchKernelGGL(add_cvt_kernel, dim3((unsigned)gb), dim3(256), 0, ctx->stream, Y64, Res, Y, n);
+    TB_HIP(ctx, hipGetLastError());
+    return 0;
+}
+
 namespace {
 __global__ void swiglu_f64_kernel(const double* __restrict__ G, const double* __restrict__ U, float* __restrict__ out, long long n) {
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {

@@ -163,4 +163,6 @@ int build_hessian_out_proj_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const voi
                                const float* Wk_deq, const float* Wv_deq, const void* Wq, const void* Wk, const void* Wv,
                                float* Hin_o, float* R_o);
 int build_hessian_linear_f64(tboa_ctx* ctx, long long T, int n, double alpha, const float* X, const float* X_fp, float* H_in, float* R);
+int attention_forward_f64(tboa_ctx* ctx, const tboa_attn_desc* d, const float* X, const float* Wq, const float* Wk, const float* Wv, float* O);
+int linear_forward_f64(tboa_ctx* ctx, long long T, int din, int dout, const float* X, const float* W, const float* Res, float* Y);
 int swiglu_forward_f64(tboa_ctx* ctx, long long T, int d, int dff, const float* X, const float* Wg, const float* Wu, float* Act);

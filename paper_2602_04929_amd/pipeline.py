@@ -52,7 +52,7 @@ def _split_stacked(res, rows_q, heads_q):
 
 
 def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=True, cd_iters=1, adaptive_grid=True,
-                             damp=0.01, seq_chunk=0, timings=None, side_contexts=None, stack_qk=True):
+                             damp=0.01, seq_chunk=0, timings=None, side_contexts=None, stack_qk=True, hout_k_from_quantized_q=False):
     """(rotation, activation fake-quant ->) Hessians -> W_Q, W_K, W_V -> output-projection Hessian -> W_O.
 
     blk: dict from synth.make_block (device tensors); cfg: synth.BlockConfig.  Returns dict of per-layer results
@@ -61,7 +61,10 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     stack_qk: W_Q and W_K share H_in and R (Table 1) and their heads are independent, so [W_Q; W_K] goes through
     tboa_quantize_layer as ONE layer of Hq + Hkv heads with H_out = [H_out^Q; H_out^K]: one factorisation of H_in, one P,
     steps over twice the rows.  out["qk"] is that call's result, out["q"] and out["k"] are views of it (their losses are the sums
-    over their heads)."""
+    over their heads).
+    hout_k_from_quantized_q: the other reading of Algorithm 1 line 4 (Hessians formed inside the loop over the layers): W_Q is
+    quantized first and H_out of W_K is sum_h Q_h^T Q_h with Q_h from the DEQUANTIZED W_Q (tboa_build_hout); W_Q and W_K then go
+    through tboa_quantize_layer one after the other (no stacking, no side contexts for them)."""
     Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     X_fp = blk["X_fp"]
     X = blk["X"]
@@ -88,7 +91,12 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp)
     out = {"X": X, "X_fp": X_fp}
     Hs = stage("build_hessians", lambda: ctx.build_hessians(*hargs, **hkw))
-    if stack_qk:
+    if hout_k_from_quantized_q:
+        stack_qk = False
+        out["q"] = stage("quantize_q", lambda: ctx.quantize_layer(blk["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq, **kw))
+        Hs["Hout_k"] = stage("build_hout_k", lambda: ctx.build_hout(Hs["Hin_qk"], out["q"]["W_deq"], Hkv, Hq // Hkv, dh))
+        jobs = (("k", (blk["Wk"], Hs["Hin_qk"], Hs["Hout_k"], Hs["R_qk"], Hkv)), ("v", (blk["Wv"], Hs["Hin_v"], Hs["Hout_v"], Hs["R_v"], Hkv)))
+    elif stack_qk:
         Wqk = blk.get("Wqk")
         if Wqk is None:
             Wqk = torch.cat([blk["Wq"], blk["Wk"]], dim=0)
@@ -136,6 +144,33 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     kwo = dict(kw, block=cfg.d_model)      # H_out = I: all rows form one step
     out["o"] = stage("quantize_o", lambda: ctx.quantize_layer(blk["Wo"], Ho[0], None, Ho[1], 1, **kwo))
     return out
+
+
+def quantize_blocks(ctx, blocks, X, X_fp, cfg, alpha=0.25, cd_iters=1, adaptive_grid=True, damp=0.01, side_contexts=None, **attn_kw):
+    """Several transformer blocks in a row (attention + gated MLP, residual connections, no normalisation layers), carrying both
+    activation streams from block to block: X through the quantized weights, X_fp through the full-precision ones, so that the
+    deviation X - X_fp every block sees is the one accumulated through the blocks before it (what Prop. 3.2 corrects).
+
+    blocks: list of dicts with Wq, Wk, Wv, Wo, Wg, Wu, Wd; X, X_fp [S, L, d] (X_fp is X for the first block of a model).
+    Per block: quantize_attention_block; Xa = X + attention(X; dequantized) W_O,deq^T (and the same with the full-precision
+    weights on X_fp); quantize_mlp on (Xa, Xa_fp); X <- Xa + act W_down,deq^T.  Returns the per-block results and the final
+    activations.  Every product runs in the library (tboa_attention_forward, tboa_linear_forward, tboa_swiglu_forward)."""
+    Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    results = []
+    for b in blocks:
+        blk = dict(Wq=b["Wq"], Wk=b["Wk"], Wv=b["Wv"], Wo=b["Wo"], X=X, X_fp=X_fp, signs=None)
+        att = quantize_attention_block(ctx, blk, cfg, alpha=alpha, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp,
+                                       side_contexts=side_contexts, **attn_kw)
+        O_q = ctx.attention_forward(X, att["q"]["W_deq"], att["k"]["W_deq"], att["v"]["W_deq"], Hq, Hkv, dh)
+        O_f = ctx.attention_forward(X_fp, b["Wq"], b["Wk"], b["Wv"], Hq, Hkv, dh)
+        Xa = ctx.linear_forward(O_q, att["o"]["W_deq"], residual=X)
+        Xa_fp = ctx.linear_forward(O_f, b["Wo"], residual=X_fp)
+        mlp = quantize_mlp(ctx, dict(Wg=b["Wg"], Wu=b["Wu"], Wd=b["Wd"], M=Xa, M_fp=Xa_fp), cfg, alpha=alpha, cd_iters=cd_iters,
+                           adaptive_grid=adaptive_grid, damp=damp)
+        X = ctx.linear_forward(mlp["act"], mlp["down"]["W_deq"], residual=Xa)
+        X_fp = ctx.linear_forward(mlp["act_fp"], b["Wd"], residual=Xa_fp)
+        results.append(dict(attention=att, mlp=mlp, X_out=X, X_fp_out=X_fp, X_mid=Xa, X_fp_mid=Xa_fp))
+    return results, X, X_fp
 
 
 def quantize_mlp(ctx, mlp, cfg, alpha=0.25, use_R=True, cd_iters=1, adaptive_grid=True, damp=0.01, timings=None,

@@ -122,7 +122,9 @@ def test_bf16_block_end_to_end(lib, case):
     Hs, Hw = got["hessians"], want["hessians"]
     for k in ("Hin_qk", "R_qk", "Hout_q", "Hout_k", "Hin_v", "R_v", "Hout_v"):
         g, w = f64(Hs[k]), Hw[k]
-        print("  %s %s: max |err| / max |entry| = %.2e" % (name, k, np.abs(g - w).max() / np.abs(w).max()), flush=True)
+        e = np.abs(g - w).max() / np.abs(w).max()
+        print("  %s %s: max |err| / max |entry| = %.2e" % (name, k, e), flush=True)
+        assert e <= (5e-4 if k.startswith("R_v") else 1e-5), (k, e)
     Xn, Xfn = f64(blk["X"]), f64(blk["X_fp"])
     wq, wk, wv = (f64(got[k]["W_deq"]) for k in ("q", "k", "v"))       # the oracle's Table 1 sums from the library's own W_deq
     Ho_w, Ro_w = O.build_hessian_out_proj(Xn, Xfn, wq, wk, wv, f64(blk["Wq"]), f64(blk["Wk"]), f64(blk["Wv"]), hq, hkv, dh, alpha=0.25)

@@ -63,9 +63,39 @@ def test_bf16_path_small(ctx, causal, hq, hkv):
     got = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], hq, hkv, 32, alpha=0.25, causal=causal, seq_chunk=2)
     want = O.build_hessians(np64(b["X"]), np64(b["X_fp"]), np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), hq, hkv, 32,
                             alpha=0.25, causal=causal)
-    # X, W exact in bf16 and fp32 accumulation: 1e-5; probabilities and Y rounded to bf16 (2^-9, unbiased): 2e-3
-    check_all(got, want, 1e-5, 2e-3, 2e-2)
+    # X, W exact in bf16 and fp32 accumulation: 1e-5; no whole 256-tiles here, so the W_V part takes the per-head form with
+    # probabilities and A X as single half-precision values (2^-12, unbiased)
+    check_all(got, want, 1e-5, 5e-4, 5e-3)
     assert torch.equal(got["Hin_v"], got["Hin_v"].transpose(1, 2))
+
+
+@pytest.mark.parametrize("hq,hkv,d,L,S,with_fp", [(2, 2, 256, 256, 4, True), (8, 2, 256, 512, 3, True), (4, 1, 512, 256, 5, False)])
+def test_bf16_summed_form(ctx, hq, hkv, d, L, S, with_fp):
+    """Whole 256-tiles: the W_V Hessian takes the form that sums the heads of a KV group on L x L Gram matrices of the
+    transposed probabilities, every intermediate an exact-to-twice-the-mantissa (hi, lo) pair: fp32-grade results (1, 2 and 4
+    query heads per KV head; several sequence chunks with a ragged last one; with and without the deviation term)."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=d, n_q_heads=hq, n_kv_heads=hkv, head_dim=32, n_seqs=S, seq_len=L, n_outlier=3)
+    b = synth.make_block(cfg, seed=7, device="cuda")
+    Xf = b["X_fp"] if with_fp else None
+    got = ctx.build_hessians(b["X"], Xf, b["Wq"], b["Wk"], b["Wv"], b["Wo"], hq, hkv, 32, alpha=0.25, seq_chunk=2)
+    want = O.build_hessians(np64(b["X"]), np64(Xf) if with_fp else None, np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), hq, hkv, 32,
+                            alpha=0.25)
+    # R_v is measured against its own largest entry and is noise-like on these inputs (X - X~ is independent of X), so the
+    # 11 significant bits of the half-precision X - X~ show in it undiminished
+    check_all(got, want, 1e-5, 1e-5, 5e-4)
+    assert torch.equal(got["Hin_v"], got["Hin_v"].transpose(1, 2))
+
+
+def test_activations_beyond_half_precision_range_take_bf16_operands(ctx):
+    """An activation of 1e5 does not fit IEEE half: the build then keeps bf16 operands (8 significant bits in the per-head
+    form, (hi, lo) pairs of bf16 in the summed form) and stays finite and close."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=256, n_q_heads=2, n_kv_heads=2, head_dim=32, n_seqs=2, seq_len=256, n_outlier=3)
+    b = synth.make_block(cfg, seed=8, device="cuda")
+    b["X"][0, 5, 7] = 1.0e5; b["X_fp"][0, 5, 7] = 1.0e5
+    got = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 2, 2, 32, alpha=0.25)
+    want = O.build_hessians(np64(b["X"]), np64(b["X_fp"]), np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), 2, 2, 32, alpha=0.25)
+    assert all(torch.isfinite(v).all() for v in got.values() if v is not None)
+    check_all(got, want, 1e-5, 1e-4, 1e-2)
 
 
 def test_bf16_path_long_sequence(ctx):
@@ -74,7 +104,7 @@ def test_bf16_path_long_sequence(ctx):
     b = synth.make_block(cfg, seed=4, device="cuda")
     got = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 1, 1, 32, alpha=0.25)
     want = O.build_hessians(np64(b["X"]), np64(b["X_fp"]), np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), 1, 1, 32, alpha=0.25)
-    check_all(got, want, 1e-5, 2e-3, 2e-2)
+    check_all(got, want, 1e-5, 5e-4, 5e-3)
 
 
 @pytest.mark.parametrize("name", ["tiny", "llama2-7b"])
@@ -114,9 +144,11 @@ def test_out_proj_bf16(ctx):
                                       4, 2, 32, alpha=0.25)
     eH, eR = rel_err(np64(Hin_o), wH), rel_err(np64(R_o), wR)
     print("Hin_o %.2e R_o %.2e" % (eH, eR), flush=True)
-    assert eH <= 2e-3 and eR <= 2e-2
+    # probabilities, values and attention outputs are (hi, lo) pairs; the deviations are single half-precision values, and R_o
+    # (noise-like here: measured against its own largest entry) shows their 11 bits
+    assert eH <= 3e-5 and eR <= 1e-3
     H2, R2 = ctx.build_hessian_out_proj(b["X"], None, *deq, None, None, None, 4, 2, 32, seq_chunk=3)
-    assert R2 is None and rel_err(np64(H2), wH) <= 2e-3
+    assert R2 is None and rel_err(np64(H2), wH) <= 3e-5
 
 
 def test_out_proj_reuses_fp_projections(ctx, lib):
@@ -167,14 +199,12 @@ def test_out_proj_bf16_integer_form_weights(ctx, lib, bits):
                                       4, 2, 32, alpha=0.25)
     eH, eR = rel_err(np64(Hin_o), wH), rel_err(np64(R_o), wR)
     print("integer-form weights, %d bits: Hin_o %.2e R_o %.2e" % (bits, eH, eR), flush=True)
-    # at 960 tokens the bf16 rounding of the probabilities and of the attention output dominates: 1 - 2e-3 here on either
-    # path (the two-term split gives the same figures to three digits on these inputs)
-    assert eH <= 3e-3 and eR <= 2e-2
+    assert eH <= 2e-5 and eR <= 1e-3
     deq[1] = deq[1] * (1 + 0.01 * torch.randn(deq[1].shape, generator=g, device="cuda"))     # W_K off the grid
     H2, _ = ctx.build_hessian_out_proj(b["X"], None, *deq, None, None, None, 4, 2, 32, seq_chunk=3)
     assert ctx.counter(4) == n_int + 5 and ctx.counter(5) == n_split + 1
     wH2, _ = O.build_hessian_out_proj(np64(b["X"]), None, *[np64(w) for w in deq], None, None, None, 4, 2, 32)
-    assert rel_err(np64(H2), wH2) <= 3e-3
+    assert rel_err(np64(H2), wH2) <= 2e-5
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])

@@ -821,3 +821,19 @@ def test_act_fakequant_hand_computed_rows():
     assert np.allclose(Y[0], [t, 2 * t, 2 * t, 3 * t], rtol=1e-15)
     assert np.allclose(Y[1], [-3 * t, -2 * t, -2 * t, -t], rtol=1e-15)
     assert np.array_equal(Y[2], [-1.0, 0.0, 1.0, 2.0])
+
+
+def test_hout_k_closed_form_and_from_other_query_weights(small_block):
+    """H_out of W_K,g = sum over the query heads of the group of W_Q,h H_in W_Q,h^T (no positional rotation), whatever query
+    weights are put in: the reading of Algorithm 1 that forms the Hessians inside the loop over the layers takes the
+    dequantized W_Q there."""
+    b = small_block
+    d, dh, rep = b["d"], b["dh"], b["Hq"] // b["Hkv"]
+    Wq2 = np.rint(b["Wq"] * 4) / 4                               # stands in for a dequantized W_Q
+    Hs2 = O.build_hessians(b["X"], b["Xf"], Wq2, b["Wk"], b["Wv"], b["Wo"], b["Hq"], b["Hkv"], dh, alpha=1.0)
+    for Wq, Hs in ((b["Wq"], b["Hs"]), (Wq2, Hs2)):
+        for g in range(b["Hkv"]):
+            want = sum(Wq[h * dh:(h + 1) * dh] @ Hs["Hin_qk"] @ Wq[h * dh:(h + 1) * dh].T for h in range(g * rep, (g + 1) * rep))
+            assert np.allclose(Hs["Hout_k"][g], want, rtol=1e-10)
+    assert np.array_equal(Hs2["Hin_qk"], b["Hs"]["Hin_qk"]) and np.array_equal(Hs2["Hout_q"], b["Hs"]["Hout_q"])
+    assert not np.allclose(Hs2["Hout_k"], b["Hs"]["Hout_k"], rtol=1e-3)
