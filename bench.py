@@ -17,11 +17,12 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA, published
 PEAK_F64_TFLOPS = 78.6         # MI355X fp64 MFMA, published
-BF16_TAGS = ("hv_syrk", "rv", "ax", "ata", "gram", "proj", "grid")
+BF16_TAGS = ("hv_syrk", "rv", "ax", "ata", "gram", "proj", "scores", "pv", "grid")
 F64_TAGS = ("f64_factor", "f64_sweep", "f64_comp", "f64_cd", "f64_grid")
 KERNEL_OF = {"hv_syrk": "gemm_bf16_nt_fast_kernel (H_in^V += T1^T X, lower tiles)", "rv": "gemm_bf16_nt_fast_kernel (R_v += alpha Z^T X)",
              "ax": "gemm_bf16_nt_stream_kernel (T1 = B1 X, Z = B1 dX + B2^T X~; per-head form: A X)", "ata": "gemm_bf16_nt_stream_kernel (sum_h A_h^T A_h)",
-             "gram": "gemm_bf16_nt_fast_kernel (X^T X, dX^T X, O^T O)", "proj": "gemm_bf16_nt_stream_kernel (projections, scores, P V)",
+             "gram": "gemm_bf16_nt_fast_kernel (X^T X, dX^T X, O^T O)", "proj": "gemm_bf16_nt_stream_kernel (projections X W^T)", "scores": "gemm_bf16_nt_stream_kernel (Q K^T, fp32 out)",
+             "pv": "gemm_bf16_nt_stream_kernel (O^T = V^T A^T)",
              "grid": "gemm_bf16_nt_fast_kernel (approximate grid-search costs)"}
 
 

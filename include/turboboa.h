@@ -327,7 +327,9 @@ enum tboa_prof_tag {
     TBOA_PROF_F64_COMP = 9,    /* compensation of the remaining out-channels (Prop. 3.1 / 3.2)            */
     TBOA_PROF_F64_CD = 10,     /* products of the scale refinement (Algorithm 2) and of the loss          */
     TBOA_PROF_ATA = 11,        /* sum over a KV group's heads of A_h^T A_h and A_h^T (A_h - A~_h) (grouped-query form of the W_V Hessian) */
-    TBOA_PROF_NTAGS = 12
+    TBOA_PROF_SCORES = 12,     /* scores Q_h K_g^T of a sequence (short contraction: 3 d_h with the (hi, lo) parts), fp32 out */
+    TBOA_PROF_PV = 13,         /* attention outputs O_h^T = V^T A_h^T and their differences, for the W_O Hessian */
+    TBOA_PROF_NTAGS = 14
 };
 int tboa_profile_enable(tboa_ctx* ctx, int on);
 int tboa_profile_reset(tboa_ctx* ctx);

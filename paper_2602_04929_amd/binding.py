@@ -162,7 +162,7 @@ class Context:
 
     # ---- live kernel timing
     PROF_TAGS = {"hv_syrk": 0, "ax": 1, "rv": 2, "gram": 3, "proj": 4, "grid": 5,
-                 "f64_grid": 6, "f64_factor": 7, "f64_sweep": 8, "f64_comp": 9, "f64_cd": 10, "ata": 11}
+                 "f64_grid": 6, "f64_factor": 7, "f64_sweep": 8, "f64_comp": 9, "f64_cd": 10, "ata": 11, "scores": 12, "pv": 13}
 
     def profile(self, on=True):
         self._check(_lib.tboa_profile_enable(self._h, int(on)))

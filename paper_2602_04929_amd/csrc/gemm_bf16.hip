@@ -55,6 +55,10 @@ struct Args {
     int chunk;                  // 0: XCD x takes the contiguous run [x per, (x + 1) per); else runs of `chunk` items are dealt to the XCDs in turn
     const int2* sched;          // persistent kernel: [workgroups][rounds] of (batch entry or -1, tm << 16 | tn)
     int rounds;
+    // persistent kernel, several operand pairs: after every term_segs segments the operand pointers move on by term_dA /
+    // term_dB bytes (the distance to the next pair's buffer less the columns just read); term_segs = 0: one pair
+    int term_segs;
+    long long term_dA[3], term_dB[3];
 };
 
 // Work item of this workgroup.  Workgroups are dealt to the eight XCDs round-robin by their linear number, so workgroup
@@ -578,6 +582,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
     };
     const char* sA = cur.A; const char* sB = cur.B;
     long long koff = 2LL * cur.kbeg; int kin = cur.kbeg, skbeg = cur.kbeg, skend = cur.kend, sleft = cur.nk;
+    int sseg = 0, sterm = 0;      // segments read of the current operand pair, and its number
     bool nxt_taken = false;
     set_offsets(cur.m0, cur.n0);
     // called after the loads of the stage the stream points to have been issued
@@ -585,9 +590,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_stream_kernel(Args g) {
         if (sleft == 0) return;
         if (--sleft > 0) {
             kin += FK; koff += 2 * FK;
-            if (kin == skend) { kin = skbeg; koff += 2LL * (seg_len - skend + skbeg); }
+            if (kin == skend) {
+                kin = skbeg; koff += 2LL * (seg_len - skend + skbeg);
+                if (g.term_segs && ++sseg == g.term_segs) { sA += g.term_dA[sterm]; sB += g.term_dB[sterm]; ++sterm; sseg = 0; }
+            }
         } else if (nxt.valid && !nxt_taken) {
             sA = nxt.A; sB = nxt.B; skbeg = nxt.kbeg; skend = nxt.kend; sleft = nxt.nk; koff = 2LL * nxt.kbeg; kin = nxt.kbeg;
+            sseg = 0; sterm = 0;
             set_offsets(nxt.m0, nxt.n0);
             nxt_taken = true;
         }
@@ -818,7 +827,7 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     }
     const bool fast = (q.kseg > 0 ? q.kseg : q.K) % FK == 0 && q.K > 0;
     if ((q.flags & (TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED)) && !fast) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: blocked operands are read by the LDS-direct kernel only");
-    Args a;
+    Args a{};
     a.sched = nullptr; a.rounds = 0;
     a.M = q.M; a.N = q.N; a.K = q.K; a.alpha = q.alpha;
     a.A = q.A; a.lda = q.lda; a.B = q.B; a.ldb = q.ldb; a.C = q.C; a.ldc = q.ldc; a.C2 = q.C2;
@@ -852,6 +861,24 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
         TB_TRY(prof_begin(ctx, q.tag, 2.0 * mnk * nseg * q.batch, rec, timed));
     }
     const bool f16 = (q.flags & TBOA_GEMM_F16) != 0;
+    a.term_segs = 0;
+    if (q.nterms > 1) {
+        const bool pers = fast && (q.kseg > 0 ? q.kseg : q.K) % (FK * 4) == 0 && (q.flags & TBOA_GEMM_PERSISTENT) != 0;
+        const int seg = q.kseg > 0 ? q.kseg : q.K;
+        if (!pers || q.nterms > 4 || q.K % q.nterms || (q.K / q.nterms) % seg)
+            return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: several operand pairs need the persistent kernel, at most 4 pairs, whole segments per pair");
+        const long long term_cols = q.K / q.nterms;
+        const long long bytesA = (term_cols * 2) << ((q.flags & TBOA_GEMM_A_TILED) ? 4 : 0), bytesB = (term_cols * 2) << ((q.flags & TBOA_GEMM_B_TILED) ? 4 : 0);
+        for (int t = 0; t < q.nterms; ++t)
+            if (!q.termA[t] || !q.termB[t] || ((uintptr_t)q.termA[t] & 15) || ((uintptr_t)q.termB[t] & 15))
+                return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: operand pair %d missing or not 16-byte aligned", t);
+        if (q.termA[0] != q.A || q.termB[0] != q.B) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: the first operand pair must be (A, B)");
+        a.term_segs = (int)(term_cols / seg);
+        for (int t = 0; t + 1 < q.nterms; ++t) {
+            a.term_dA[t] = ((const char*)q.termA[t + 1] - (const char*)q.termA[t]) - bytesA;
+            a.term_dB[t] = ((const char*)q.termB[t + 1] - (const char*)q.termB[t]) - bytesB;
+        }
+    }
     const bool persistent = fast && (q.kseg > 0 ? q.kseg : q.K) % (FK * 4) == 0 && (q.flags & TBOA_GEMM_PERSISTENT) != 0;
     if (persistent) {
         int wgs = 0;

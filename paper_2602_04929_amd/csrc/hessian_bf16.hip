@@ -402,14 +402,23 @@ __global__ __launch_bounds__(256) void softmax_t_kernel(const float* __restrict_
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float* s = S + (long long)h * L * L;
     const float* s2 = S2 ? S2 + (long long)h * L * L : nullptr;
+    typedef float f4 __attribute__((ext_vector_type(4)));
     for (int rr = 0; rr < 16; ++rr) {
         const int tl = wave * 16 + rr, t = t0 + tl;
         const float* row = s + (long long)t * L; const float* row2 = s2 ? s2 + (long long)t * L : nullptr;
+        // one pass, four consecutive scores per lane and step: running maximum and rescaled sum per lane, merged at the end
         float m = -INFINITY, sum = 0.f, m2 = -INFINITY, sum2 = 0.f;
-        for (int k = lane; k <= t; k += 64) {
-            const float v = row[k];
-            if (v > m) { sum = sum * __expf(m - v) + 1.f; m = v; } else sum += __expf(v - m);
-            if (row2) { const float w = row2[k]; if (w > m2) { sum2 = sum2 * __expf(m2 - w) + 1.f; m2 = w; } else sum2 += __expf(w - m2); }
+        for (int k = 4 * lane; k <= t; k += 256) {
+            const f4 v = *(const f4*)(row + k);
+            f4 w = {0.f, 0.f, 0.f, 0.f};
+            if (row2) w = *(const f4*)(row2 + k);
+            float vm = -INFINITY, wm = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (k + e <= t) { vm = fmaxf(vm, v[e]); wm = fmaxf(wm, w[e]); }
+            if (vm > m) { sum *= __expf(m - vm); m = vm; }
+            if (row2 && wm > m2) { sum2 *= __expf(m2 - wm); m2 = wm; }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (k + e <= t) { sum += __expf(v[e] - m); if (row2) sum2 += __expf(w[e] - m2); }
         }
         float M = m, M2 = m2;
 #pragma unroll
@@ -425,30 +434,32 @@ __global__ __launch_bounds__(256) void softmax_t_kernel(const float* __restrict_
                     out.dlo ? out.dlo + g * group_stride : nullptr};
     const int nparts = s2 ? 4 : 2;
     const int iend = min(L, (t0 / 256 + 1) * 256);
-    const int tr = threadIdx.x >> 2, kc = (threadIdx.x & 3) * 16, t = t0 + tr;
+    // reading a 64 x 64 piece: thread (row tr of the piece, quarter sq) takes the columns 16 q + 4 sq + 0..3, q = 0..3, so that a row
+    // is read as whole 64-byte runs and the transposed LDS writes of the four threads of a row fall into different banks;
+    // writing it: thread (row tr of the transposed piece, 16 consecutive t from kc)
+    const int tr = threadIdx.x >> 2, sq = threadIdx.x & 3, kc = sq * 16, t = t0 + tr;
     const float m = st[0][tr], inv = st[1][tr], m2 = st[2][tr], inv2 = st[3][tr];
     for (int i0 = 0; i0 < iend; i0 += 64) {
         if (i0 <= t0) {     // the piece holds entries on or left of the diagonal
-            typedef float f4 __attribute__((ext_vector_type(4)));
-            const float* src = s + (long long)t * L + i0 + kc;
-            const float* src2 = s2 ? s2 + (long long)t * L + i0 + kc : nullptr;
+            const float* src = s + (long long)t * L + i0 + 4 * sq;
+            const float* src2 = s2 ? s2 + (long long)t * L + i0 + 4 * sq : nullptr;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const f4 v = *(const f4*)(src + 4 * q);
+                const f4 v = *(const f4*)(src + 16 * q);
                 f4 w = {0.f, 0.f, 0.f, 0.f};
-                if (src2) w = *(const f4*)(src2 + 4 * q);
+                if (src2) w = *(const f4*)(src2 + 16 * q);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int i = i0 + kc + 4 * q + e;
+                    const int il = 16 * q + 4 * sq + e, i = i0 + il;
                     const float a = i <= t ? __expf(v[e] - m) * inv : 0.f;
                     const bf16 ah = enc16(a, f16);
-                    tp[0][kc + 4 * q + e][tr] = ah;
-                    tp[1][kc + 4 * q + e][tr] = enc16(a - dec16(ah, f16), f16);
+                    tp[0][il][tr] = ah;
+                    tp[1][il][tr] = enc16(a - dec16(ah, f16), f16);
                     if (src2) {
                         const float da = a - (i <= t ? __expf(w[e] - m2) * inv2 : 0.f);
                         const bf16 dh = enc16(da, f16);
-                        tp[2][kc + 4 * q + e][tr] = dh;
-                        tp[3][kc + 4 * q + e][tr] = enc16(da - dec16(dh, f16), f16);
+                        tp[2][il][tr] = dh;
+                        tp[3][il][tr] = enc16(da - dec16(dh, f16), f16);
                     }
                 }
             }
@@ -471,23 +482,51 @@ __global__ __launch_bounds__(256) void softmax_t_kernel(const float* __restrict_
     }
 }
 
-// [B1 | B2^T] of a group, fp32 row-major [L, L] each, -> the blocked 16-bit operand [B1_hi | B1_lo | B2^T_hi | B2^T_lo]
-// (or [B1_hi | B1_lo] without B2): element (i, seg L + j); four consecutive columns per thread
-__global__ void bcat_kernel(const float* __restrict__ B1, const float* __restrict__ B2, int L, bf16* __restrict__ out, long long ldb,
-                            long long group_stride, int f16) {
+// [B1 | B2^T] of a group -> the blocked 16-bit operand [B1_hi | B1_lo | B2^T_hi | B2^T_lo] (or [B1_hi | B1_lo] without B2):
+// element (i, seg L + j).  B1 and B2^T arrive as `parts` partial sums (over subsets of the group's heads), fp32 row-major
+// [parts][groups][L, L]; of the symmetric B1 only the 256-tiles on or below the diagonal are valid, the rest is taken from
+// the mirrored tile through LDS.  One workgroup per 64 x 64 piece: thread (row, 16 consecutive columns).
+__global__ __launch_bounds__(256) void bcat_kernel(const float* __restrict__ B1, const float* __restrict__ B2, int L, int parts, long long part_stride,
+                                                   bf16* __restrict__ out, long long ldb, long long group_stride, int f16) {
     typedef float f4 __attribute__((ext_vector_type(4)));
-    const long long nn = (long long)L * L, tot4 = nn / 4;
-    const int g = blockIdx.y;
+    __shared__ float tt[64][65];
+    const long long nn = (long long)L * L;
+    const int g = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+    const int tr = threadIdx.x >> 2, c0 = (threadIdx.x & 3) * 16;
     bf16* o = out + g * group_stride;
-    for (long long i4 = blockIdx.x * (long long)blockDim.x + threadIdx.x; i4 < tot4; i4 += (long long)gridDim.x * blockDim.x) {
-        const long long e = 4 * i4; const int i = (int)(e / L), j = (int)(e % L);
-        for (int which = 0; which < (B2 ? 2 : 1); ++which) {
-            const f4 v = __builtin_nontemporal_load((const f4*)((which ? B2 : B1) + g * nn + e));
-            union { bf16 b[4]; uint2 u; } hi, lo;
+    for (int which = 0; which < (B2 ? 2 : 1); ++which) {
+        const float* src = (which ? B2 : B1) + g * nn;
+        float v[16];
+        if (which == 0 && (j0 >> 8) > (i0 >> 8)) {      // B1 above the diagonal tiles: the piece (j0, i0), transposed
+            f4 acc[4] = {};
+            for (int p = 0; p < parts; ++p)
 #pragma unroll
-            for (int k = 0; k < 4; ++k) { hi.b[k] = enc16(v[k], f16); lo.b[k] = enc16(v[k] - dec16(hi.b[k], f16), f16); }
-            *(uint2*)(o + tboa_blocked_offset(i, (2LL * which) * L + j, ldb >> 5)) = hi.u;
-            *(uint2*)(o + tboa_blocked_offset(i, (2LL * which + 1) * L + j, ldb >> 5)) = lo.u;
+                for (int q = 0; q < 4; ++q) acc[q] += *(const f4*)(src + p * part_stride + (long long)(j0 + tr) * L + i0 + c0 + 4 * q);
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) tt[tr][c0 + 4 * q + e] = acc[q][e];
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 16; ++e) v[e] = tt[c0 + e][tr];
+        } else {
+            f4 acc[4] = {};
+            for (int p = 0; p < parts; ++p)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] += *(const f4*)(src + p * part_stride + (long long)(i0 + tr) * L + j0 + c0 + 4 * q);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[4 * q + e] = acc[q][e];
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            union { bf16 b[8]; uint4 u; } hi, lo;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { hi.b[k] = enc16(v[8 * q + k], f16); lo.b[k] = enc16(v[8 * q + k] - dec16(hi.b[k], f16), f16); }
+            *(uint4*)(o + tboa_blocked_offset(i0 + tr, (2LL * which) * L + j0 + c0 + 8 * q, ldb >> 5)) = hi.u;
+            *(uint4*)(o + tboa_blocked_offset(i0 + tr, (2LL * which + 1) * L + j0 + c0 + 8 * q, ldb >> 5)) = lo.u;
         }
     }
 }
@@ -706,7 +745,7 @@ int scores(const Dims& D, const bf16* Qh, const bf16* Kh, int sl, float* Sc) {
     const int L = D.L, dh3 = 3 * D.dh;
     GemmBf16 g = nt(L, L, dh3, (float)(1.0 / sqrt((double)D.dh)), Qh + (long long)sl * L * D.Hq * dh3, (long long)D.Hq * dh3,
                     Kh + (long long)sl * L * D.Hkv * dh3, (long long)D.Hkv * dh3, Sc, L, TBOA_F32, 0, D.d->causal ? TBOA_GEMM_LOWER : 0);
-    g.batch = D.Hq; g.batch_inner = D.rep;
+    g.batch = D.Hq; g.batch_inner = D.rep; g.tag = TBOA_PROF_SCORES;
     g.strideA = (long long)D.rep * dh3; g.strideA2 = dh3; g.strideB = dh3; g.strideB2 = 0;
     if (qk_blocked(D)) {     // one blocked [L, 3 dh] matrix per (sequence, head)
         g.flags |= TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED; g.lda = dh3; g.ldb = dh3;
@@ -728,7 +767,7 @@ int scores_pair(const Dims& D, const bf16* Qh, const bf16* Kh, const bf16* Qhf, 
     const int L = D.L, dh3 = 3 * D.dh;
     GemmBf16 g = nt(L, L, dh3, (float)(1.0 / sqrt((double)D.dh)), Qh + (long long)sl * L * D.Hq * dh3, (long long)D.Hq * dh3,
                     Kh + (long long)sl * L * D.Hkv * dh3, (long long)D.Hkv * dh3, Sc, L, TBOA_F32, 0, D.d->causal ? TBOA_GEMM_LOWER : 0);
-    g.batch = 2 * D.Hq; g.batch_inner = D.Hq;
+    g.batch = 2 * D.Hq; g.batch_inner = D.Hq; g.tag = TBOA_PROF_SCORES;
     g.strideA = dq; g.strideA2 = dh3; g.strideB = dk; g.strideB2 = dh3;
     if (qk_blocked(D)) {
         g.flags |= TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED; g.lda = dh3; g.ldb = dh3;
@@ -798,6 +837,10 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     const long long dd = (long long)dm * dm, hh = (long long)dh * dh, TP = (long long)T + PADE;
     // summed form: pitches of the transposed probabilities, of [B1_hi | B1_lo | B2^T_hi | B2^T_lo], of the chunk buffers
     const long long ldpt = (long long)rep * L + PADE, ldbc = (rv ? 4LL : 2LL) * L + PADE, ldg = (long long)G * L + PADE;
+    // summed form: the L x L Gram matrices of a group are built as `parts` partial sums over subsets of its heads (added up
+    // where they are split into 16-bit operands): the tile at the origin contracts over all L tokens of every head, the tile at
+    // the far corner over 256, so with few batch entries the longest tile alone would set the time of the launch
+    const int parts = (Hkv < 32 && rep % 2 == 0) ? 2 : 1;
     bf16 *XT, *dXh, *dXl, *Qh, *Kh, *Qhf, *Khf, *P, *XcT, *YT, *dYT;
     bf16 *Bcat = nullptr, *XgT = nullptr, *YTl = nullptr, *dYTl = nullptr;
     PtOut pt{nullptr, nullptr, nullptr, nullptr};
@@ -817,7 +860,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
             P = nullptr;
             pt.hi = ar.get<bf16>((size_t)Hkv * L * ldpt); pt.lo = ar.get<bf16>((size_t)Hkv * L * ldpt);
             pt.dhi = rv ? ar.get<bf16>((size_t)Hkv * L * ldpt) : nullptr; pt.dlo = rv ? ar.get<bf16>((size_t)Hkv * L * ldpt) : nullptr;
-            B1f = ar.get<float>((size_t)Hkv * L * L); B2f = rv ? ar.get<float>((size_t)Hkv * L * L) : nullptr;
+            B1f = ar.get<float>((size_t)parts * Hkv * L * L); B2f = rv ? ar.get<float>((size_t)parts * Hkv * L * L) : nullptr;
             Bcat = ar.get<bf16>((size_t)Hkv * L * ldbc);
             XgT = ar.get<bf16>((size_t)dm * ldg);
             YT = ar.get<bf16>((size_t)Hkv * dm * ldg); YTl = ar.get<bf16>((size_t)Hkv * dm * ldg);
@@ -918,19 +961,23 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
                 hipLaunchKernelGGL(softmax_t_kernel, dim3(L / 64, Hq), dim3(256), 0, st, Sc, rv ? Scf : nullptr, L, rep, pt, ldpt,
                                    (long long)L * ldpt, D.f16);
                 TB_KERNEL_CHECK(ctx);
-                // B1 = sum_h A_h^T A_h and B2^T = sum_h A_h^T (A_h - A~_h): contraction over (head of the group, t >= max(i, j)),
-                // three products of (hi, lo) parts each, accumulated in fp32
-                GemmBf16 b = nt(L, L, rep * L, 1.f, pt.hi, ldpt, pt.hi, ldpt, B1f, L, TBOA_F32, 0, tiled | TBOA_GEMM_KLO | hf);
-                b.kseg = L; b.batch = Hkv; b.strideA = (long long)L * ldpt; b.strideB = b.strideA; b.strideC = (long long)L * L; b.tag = TBOA_PROF_ATA;
-                const bf16* lefts[3] = {pt.hi, pt.lo, pt.hi};
-                const bf16* rights1[3] = {pt.hi, pt.hi, pt.lo};
-                const bf16* rights2[3] = {pt.dhi, pt.dhi, pt.dlo};
-                for (int term = 0; term < 3; ++term) {
-                    b.A = lefts[term]; b.B = rights1[term]; b.C = B1f; b.accumulate = term ? 1 : 0;
+                // B1 = sum_h A_h^T A_h and B2^T = sum_h A_h^T (A_h - A~_h): contraction over (head of the group, t >= max(i, j)) and
+                // over the three products of (hi, lo) parts, in one pass.  B1 is symmetric: only its tiles on or below the diagonal
+                GemmBf16 b = nt(L, L, 3 * (rep / parts) * L, 1.f, pt.hi, ldpt, pt.hi, ldpt, B1f, L, TBOA_F32, 0, tiled | TBOA_GEMM_KLO | TBOA_GEMM_LOWER | hf);
+                b.kseg = L; b.batch = Hkv * parts; b.batch_inner = parts; b.tag = TBOA_PROF_ATA;
+                b.strideA = (long long)L * ldpt; b.strideA2 = 16LL * (rep / parts) * L; b.strideB = b.strideA; b.strideB2 = b.strideA2;
+                b.strideC = (long long)L * L; b.strideC2 = (long long)Hkv * L * L;
+                b.nterms = 3;
+                b.termA[0] = pt.hi; b.termA[1] = pt.lo; b.termA[2] = pt.hi;
+                b.termB[0] = pt.hi; b.termB[1] = pt.hi; b.termB[2] = pt.lo;
+                TB_TRY(gemm_bf16_nt(ctx, b));
+                if (rv) {
+                    b.flags &= ~TBOA_GEMM_LOWER; b.C = B2f; b.B = pt.dhi;
+                    b.termB[0] = pt.dhi; b.termB[1] = pt.dhi; b.termB[2] = pt.dlo;
                     TB_TRY(gemm_bf16_nt(ctx, b));
-                    if (rv) { b.B = rights2[term]; b.C = B2f; TB_TRY(gemm_bf16_nt(ctx, b)); }
                 }
-                hipLaunchKernelGGL(bcat_kernel, dim3(1024, Hkv), dim3(256), 0, st, B1f, B2f, L, Bcat, ldbc, (long long)L * ldbc, D.f16);
+                hipLaunchKernelGGL(bcat_kernel, dim3(L / 64, L / 64, Hkv), dim3(256), 0, st, B1f, B2f, L, parts, (long long)Hkv * L * L, Bcat, ldbc,
+                                   (long long)L * ldbc, D.f16);
                 TB_KERNEL_CHECK(ctx);
                 // T1^T = [X_s^T | X_s^T] [B1_hi | B1_lo]^T and Z^T = [dX_s^T | dX_s^T | X~_s^T | X~_s^T] [B1_hi | B1_lo | B2^T_hi | B2^T_lo]^T,
                 // each left as a (hi, lo) pair of bf16
@@ -1094,7 +1141,7 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             const long long co = t0 + (long long)sl * L;
             GemmBf16 o = nt(dh, L, 3 * L, 1.f, VTc + (long long)sl * nsg * L, ldv, P, ldp, OT + co, TP, TBOA_BF16, 0, cflag | TBOA_GEMM_C_HILO);
             o.C2 = OTl + co;
-            o.kseg = L; o.batch = Hq; o.batch_inner = rep;
+            o.kseg = L; o.batch = Hq; o.batch_inner = rep; o.tag = TBOA_PROF_PV;
             o.strideA = (long long)dh * ldv; o.strideA2 = 0;
             o.strideB = (long long)rep * L * ldp; o.strideB2 = (long long)L * ldp;
             o.strideC = (long long)rep * dh * TP; o.strideC2 = (long long)dh * TP;

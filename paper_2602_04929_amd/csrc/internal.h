@@ -116,6 +116,10 @@ struct GemmBf16 {
     int batch_inner = 1; int64_t strideA2 = 0, strideB2 = 0, strideC2 = 0;
     int tag = -1;   // tboa_prof_tag of this launch (timed with HIP events when profiling is on)
     int kseg = 0;   // > 0: K is a concatenation of K/kseg segments; TBOA_GEMM_CAUSAL_K then limits each segment
+    // nterms > 1 (persistent kernel only): the contraction runs over nterms operand pairs, K / nterms columns each, the
+    // t-th pair read from termA[t], termB[t] (laid out and strided as A and B; A = termA[0], B = termB[0]):
+    // C = sum_t termA[t] termB[t]^T in one pass over the accumulators
+    int nterms = 1; const __hip_bfloat16* termA[4] = {}; const __hip_bfloat16* termB[4] = {};
 };
 // internal flag: a 16-bit result leaves as an exact-to-16-bit pair of bf16 values (hi into C, lo into C2), whatever the operands
 #define TBOA_GEMM_C_HILO 0x10000
