@@ -237,7 +237,9 @@ def main():
     for c in ctxs:
         c.profile(False)
     rate = lambda v: (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["ms"] > 0 else 0.0
-    dom = max(BF16_TAGS, key=lambda k: prof[k]["ms"])
+    # the dominant kernel is taken among the launches of the Hessian builds, which have the GPU to themselves; the grid search's
+    # product runs beside other layers' kernels on other streams, so its event times overstate it
+    dom = max((k for k in BF16_TAGS if k != "grid"), key=lambda k: prof[k]["ms"])
     achieved = rate(prof[dom])
     roofline = {"bound": "mfma", "kernel": KERNEL_OF[dom], "tag": dom, "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,

@@ -1,0 +1,278 @@
+// Causal attention probabilities of one sequence, written transposed and as (hi, lo) pairs of 16-bit values, straight from
+// the operands of the score product: the scores Q_h K_g^T / sqrt(d_h) (Table 1: A_h = softmax of the scaled scores) are
+// formed on the matrix cores tile by tile and never stored.  This is what the summed form of the W_V Hessian reads
+// (Pt[g][i][r L + t] = A_h[t, i], h = g rep + r; see build_hessians_bf16), for both score matrices at once: the one of the
+// quantized-input path and the one of the full-precision path, whose difference A - A~ is the second output.
+//
+// Operands: Q^ = [q_hi | q_lo | q_hi] and K^ = [k_hi | k_hi | k_lo], one [L, 3 d_h] bf16 matrix per head in 16 x 32 blocks
+// (as split3_kernel writes them), so that Q^ K^T = q_hi k_hi + q_lo k_hi + q_hi k_lo carries the fp32 projections to 16 bits.
+//
+// One workgroup per (64 query rows t, head), four wavefronts = (path, half of the 64 keys of a tile).  A wavefront keeps
+// the Q^ fragments of its path for all 64 queries in registers (two 32-wide blocks, the distinct segments q_hi and q_lo)
+// and computes S^T = K^ Q^T for its 32 keys: with the keys as the rows of the MFMA result, a lane holds ONE query column
+// and 16 key rows, so the running maximum and sum of a query need no traffic between lanes until the end.  The K^ tile of
+// both paths (segments k_hi, k_lo: 64 x d_h each) is copied global -> LDS block by block (a 16 x 32 block is 1 KB contiguous
+// in memory and lands as it is: its XOR-swizzled 16-byte pieces are what conflict-free fragment reads need), the copy of
+// the next tile running under the element-wise work on the current one.
+// Pass 1 walks the key tiles up to the diagonal and leaves, per query, maximum and 1 / sum; pass 2 walks them again,
+// turns scores into probabilities, exchanges them through LDS (so that A - A~ can be formed and every thread ends up with
+// 16 consecutive queries of one key row), and writes whole 16-byte pieces of the blocked result; the key tiles between the
+// diagonal and the end of its 256-tile get zeros (a product that starts its contraction at the 256-tile of its rows and
+// columns reads nothing else).  Recomputing the scores costs 2 x 3 d_h flops per entry and pass; storing them would cost
+// 8 bytes written and 16 read per entry.
+#include "internal.h"
+
+typedef __hip_bfloat16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+__device__ __forceinline__ bf16 enc16(float v, int f16) {
+    if (f16) { const _Float16 h = (_Float16)v; return __builtin_bit_cast(bf16, h); }
+    return __float2bfloat16(v);
+}
+__device__ __forceinline__ float dec16(bf16 b, int f16) {
+    if (f16) return (float)__builtin_bit_cast(_Float16, b);
+    return __bfloat162float(b);
+}
+
+constexpr int EXP = 72;        // floats per row of the exchange buffer: the two lane halves of a wavefront write rows 4 apart
+
+template <int DH>
+constexpr int attn_lds_bytes() { return 4 * 64 * 2 * DH + 2 * 64 * EXP * 4 + 2 * 2 * 2 * 64 * 4 + 2 * 2 * 64 * 4; }
+
+// one 1 KB block global -> LDS: lane l moves the 16 bytes at base + voff (voff = 16 l) to lds_addr + 16 l
+__device__ __forceinline__ void lds_direct_16(unsigned voff, const char* base, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" ::"v"(voff), "s"(lds_addr), "s"(base) : "memory", "m0");
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_probs_t_kernel(const bf16* __restrict__ Qa, const bf16* __restrict__ Ka, const bf16* __restrict__ Qb,
+                                                           const bf16* __restrict__ Kb, int L, int nheads, int rep, int xcd_runs, float scale,
+                                                           PtOut out, long long ldp, long long group_stride, int f16) {
+    constexpr int NKS = DH / 16;                 // 16-deep MFMA steps per segment
+    constexpr int NCB = DH / 32;                 // 32-column blocks per segment
+    constexpr int SEGB = 64 * 2 * DH;            // bytes of one (path, segment) image: [NCB][64 keys][32 elements], pieces swizzled
+    constexpr int KB = 3 * DH / 32;              // 16 x 32 blocks per block row of Q^ / K^
+    constexpr int NBLK = 2 * 2 * NCB * 4;        // 1 KB blocks of a tile, both paths
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    unsigned char* kt = smem;                                // [path][k_hi, k_lo][NCB][64 keys][64 bytes]
+    float* ex = (float*)(smem + 4 * SEGB);                   // [path][64 keys][EXP]: probabilities of the tile
+    float* stat = ex + 2 * 64 * EXP;                         // [path][key half][max, sum][64 queries]
+    float* fin = stat + 2 * 2 * 2 * 64;                      // [path][max, 1 / sum][64 queries]
+
+    // Work items in the order (KV group, 64-row block from the last, i.e. longest, to the first, head of the group).  When the
+    // groups divide evenly over the 8 XCDs (workgroup w runs on XCD w % 8), XCD x takes the contiguous run of items of its
+    // groups: the K^ of a group (both paths: 12 L d_h bytes, 3 MB for L = 2048, d_h = 128) then stays in that XCD's L2 and the
+    // heads of a group walk the same key tiles side by side.  Otherwise the items are taken in order.
+    const int ntb = L / 64, total = nheads * ntb;
+    int item = blockIdx.x;
+    if (xcd_runs) item = (blockIdx.x & 7) * (total / 8) + (blockIdx.x >> 3);
+    const int g = item / (rep * ntb), rem = item % (rep * ntb), r = rem % rep, h = g * rep + r;
+    const int t0 = (ntb - 1 - rem / rep) * 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, p = wave >> 1, wi = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const bool two = Qb != nullptr, active = (p == 0) || two;
+    const long long mat = (long long)L * 3 * DH;
+    const bf16* K0 = Ka + g * mat; const bf16* K1 = two ? Kb + g * mat : K0;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned kt_lds = (unsigned)(unsigned long long)((__attribute__((address_space(3))) void*)kt);
+
+    // Q^ fragments of this wavefront's path: B operand of the MFMA (lane: query l32 of block tb, 8 contraction elements from 8 lh)
+    bf16x8 qh[2][NKS], ql[2][NKS];
+    if (active) {
+        const bf16* Qp = (p ? Qb : Qa) + h * mat;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                const int t = t0 + 32 * tb + l32, c = 16 * ks + 8 * lh;
+                qh[tb][ks] = *(const bf16x8*)(Qp + tboa_blocked_offset(t, c, KB));
+                ql[tb][ks] = *(const bf16x8*)(Qp + tboa_blocked_offset(t, DH + c, KB));
+            }
+    }
+
+    // the K^ tile at keys i0: block b = ((path 2 + segment) NCB + cb) 4 + rb of the LDS image comes from block
+    // (i0 / 16 + rb, segment's first block + cb) of that path's K^; wavefront w copies the blocks w, w + 4, ...
+    auto issue = [&](int i0) {
+        const int nblk = two ? NBLK : NBLK / 2;
+#pragma unroll
+        for (int j = 0; j < NBLK / 4; ++j) {
+            const int b = wave_s + 4 * j;
+            if (b < nblk) {
+                const int rb = b & 3, cb = (b >> 2) % NCB, ps = (b >> 2) / NCB;     // ps = path 2 + segment (k_hi, k_lo)
+                const bf16* src = ((ps >> 1) ? K1 : K0) + ((long long)((i0 >> 4) + rb) * KB + ((ps & 1) ? 2 * NCB : 0) + cb) * 512;
+                lds_direct_16((unsigned)lane * 16u, (const char*)src, kt_lds + (unsigned)b * 1024u);
+            }
+        }
+    };
+    // S^T of the tile for this wavefront: acc[tb][4 b + j] = score(key i0 + 32 wi + 8 b + 4 lh + j, query t0 + 32 tb + l32)
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 acc[2];
+    auto multiply = [&]() {
+        acc[0] = zero16; acc[1] = zero16;
+        const int row = 32 * wi + l32;
+        const unsigned char* kh_img = kt + (p * 2 + 0) * SEGB + row * 64;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const int c8 = 2 * ks + lh;                                   // 8-element piece of the segment
+            const int off = (c8 >> 2) * 4096 + (((c8 & 3) ^ ((row >> 2) & 3)) << 4);
+            const bf16x8 kh = *(const bf16x8*)(kh_img + off), kl = *(const bf16x8*)(kh_img + SEGB + off);
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, qh[tb][ks], acc[tb], 0, 0, 0);
+                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, ql[tb][ks], acc[tb], 0, 0, 0);
+                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, qh[tb][ks], acc[tb], 0, 0, 0);
+            }
+        }
+    };
+    auto landed = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); };
+
+    const int live = t0 / 64 + 1;                              // key tiles up to and including the diagonal
+    const int tiles = min(L, (t0 / 256 + 1) * 256) / 64;       // ... up to the end of the diagonal's 256-tile
+    // ---- pass 1: maximum and sum per query, over this wavefront's keys
+    float m[2] = {-INFINITY, -INFINITY}, s[2] = {0.f, 0.f};
+    issue(0);
+    landed();
+    for (int it = 0; it < live; ++it) {
+        if (active) multiply();
+        __syncthreads();                                   // every wavefront has read the tile
+        if (it + 1 < live) issue(64 * (it + 1));           // the next one lands under the element-wise work below
+        if (active) {
+            const int ib = 64 * it + 32 * wi + 4 * lh;
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const int t = t0 + 32 * tb + l32;
+                float vm = -INFINITY;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int i = ib + 8 * (e >> 2) + (e & 3);
+                    acc[tb][e] *= scale;
+                    if (i <= t) vm = fmaxf(vm, acc[tb][e]);
+                }
+                if (vm > m[tb]) { s[tb] *= __expf(m[tb] - vm); m[tb] = vm; }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int i = ib + 8 * (e >> 2) + (e & 3);
+                    if (i <= t) s[tb] += __expf(acc[tb][e] - m[tb]);
+                }
+            }
+        }
+        landed();
+    }
+    if (active) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {       // the two lane halves hold different keys of the same query
+            const float m2 = __shfl_xor(m[tb], 32, 64), s2 = __shfl_xor(s[tb], 32, 64);
+            const float M = fmaxf(m[tb], m2);
+            const float sum = (m[tb] == -INFINITY ? 0.f : s[tb] * __expf(m[tb] - M)) + (m2 == -INFINITY ? 0.f : s2 * __expf(m2 - M));
+            if (lh == 0) { stat[((p * 2 + wi) * 2 + 0) * 64 + 32 * tb + l32] = M; stat[((p * 2 + wi) * 2 + 1) * 64 + 32 * tb + l32] = sum; }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 128 && (threadIdx.x < 64 || two)) {
+        const int pp = threadIdx.x >> 6, tl = threadIdx.x & 63;
+        const float ma = stat[((pp * 2 + 0) * 2 + 0) * 64 + tl], sa = stat[((pp * 2 + 0) * 2 + 1) * 64 + tl];
+        const float mb = stat[((pp * 2 + 1) * 2 + 0) * 64 + tl], sb = stat[((pp * 2 + 1) * 2 + 1) * 64 + tl];
+        const float M = fmaxf(ma, mb);
+        const float sum = (ma == -INFINITY ? 0.f : sa * __expf(ma - M)) + (mb == -INFINITY ? 0.f : sb * __expf(mb - M));
+        fin[(pp * 2 + 0) * 64 + tl] = M; fin[(pp * 2 + 1) * 64 + tl] = 1.f / sum;
+    }
+    __syncthreads();
+    float M[2] = {0.f, 0.f}, inv[2] = {0.f, 0.f};
+    if (active) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) { M[tb] = fin[(p * 2 + 0) * 64 + 32 * tb + l32]; inv[tb] = fin[(p * 2 + 1) * 64 + 32 * tb + l32]; }
+    }
+    // ---- pass 2: probabilities, exchanged through LDS, written transposed
+    bf16* dst[4] = {out.hi + g * group_stride, out.lo + g * group_stride, out.dhi ? out.dhi + g * group_stride : nullptr,
+                    out.dlo ? out.dlo + g * group_stride : nullptr};
+    const int ri = threadIdx.x >> 2, tc = (threadIdx.x & 3) * 16;      // store phase: key row of the tile, 16 consecutive queries
+    issue(0);
+    landed();
+    for (int it = 0; it < tiles; ++it) {
+        const int i0 = 64 * it;
+        if (it < live) {
+            if (active) {
+                multiply();
+                const int il = 32 * wi + 4 * lh;
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+                    const int t = t0 + 32 * tb + l32;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int row = il + 8 * (e >> 2) + (e & 3);
+                        const float a = (i0 + row <= t) ? __expf(acc[tb][e] * scale - M[tb]) * inv[tb] : 0.f;
+                        ex[(p * 64 + row) * EXP + 32 * tb + l32] = a;
+                    }
+                }
+            }
+            __syncthreads();                               // the tile has been read, its probabilities are in LDS
+            if (it + 1 < live) issue(64 * (it + 1));
+        }
+        float a[16], d[16];
+        if (it < live) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f4 v = *(const f4*)(ex + ri * EXP + tc + 4 * q);
+                f4 w = {0.f, 0.f, 0.f, 0.f};
+                if (two) w = *(const f4*)(ex + (64 + ri) * EXP + tc + 4 * q);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { a[4 * q + e] = v[e]; d[4 * q + e] = v[e] - w[e]; }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { a[e] = 0.f; d[e] = 0.f; }
+        }
+        const long long col = (long long)r * L + t0 + tc;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            union { bf16 b[8]; uint4 u; } hi, lo, dh, dl;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                hi.b[k] = enc16(a[8 * q + k], f16); lo.b[k] = enc16(a[8 * q + k] - dec16(hi.b[k], f16), f16);
+                dh.b[k] = enc16(d[8 * q + k], f16); dl.b[k] = enc16(d[8 * q + k] - dec16(dh.b[k], f16), f16);
+            }
+            const long long o = tboa_blocked_offset(i0 + ri, col + 8 * q, ldp >> 5);
+            *(uint4*)(dst[0] + o) = hi.u; *(uint4*)(dst[1] + o) = lo.u;
+            if (two) { *(uint4*)(dst[2] + o) = dh.u; *(uint4*)(dst[3] + o) = dl.u; }
+        }
+        if (it < live) landed();                           // next tile in LDS; the exchange buffer is free again
+    }
+}
+
+template <int DH>
+int launch(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, PtOut out, long long ldp,
+           long long group_stride, int f16) {
+    static bool attr_set = false;
+    constexpr int smem = attn_lds_bytes<DH>();
+    if (!attr_set) {
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)attn_probs_t_kernel<DH>, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        attr_set = true;
+    }
+    const int total = Hq * (L / 64), xcd_runs = ((Hq / rep) % 8 == 0 && total % 8 == 0) ? 1 : 0;
+    hipLaunchKernelGGL(attn_probs_t_kernel<DH>, dim3(total), dim3(256), smem, ctx->stream, Qa, Ka, Qb, Kb, L, Hq, rep, xcd_runs,
+                       (float)(1.0 / sqrt((double)DH)), out, ldp, group_stride, f16);
+    TB_KERNEL_CHECK(ctx);
+    return 0;
+}
+
+}  // namespace
+
+bool attn_probs_t_supported(int L, int dh) {
+    return L % 256 == 0 && (dh == 32 || dh == 64 || dh == 96 || dh == 128);
+}
+
+int attn_probs_t(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, int dh, PtOut out,
+                 long long ldp, long long group_stride, int f16) {
+    if (!attn_probs_t_supported(L, dh) || Hq % rep || !Qa || !Ka || (Qb && !Kb) || !out.hi || !out.lo || (Qb && (!out.dhi || !out.dlo)) || ldp % 32)
+        return tboa_fail(ctx, TBOA_EINVAL, "attn_probs_t: unsupported shape or missing buffer");
+    switch (dh) {
+        case 32: return launch<32>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
+        case 64: return launch<64>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
+        case 96: return launch<96>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
+        default: return launch<128>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
+    }
+}

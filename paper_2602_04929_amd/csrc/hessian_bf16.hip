@@ -391,7 +391,6 @@ __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __r
 // probabilities and written transposed through LDS.  The rows i up to the end of the 256-tile that holds t are written,
 // zeros beyond the diagonal: a product that starts its contraction at the 256-tile of its rows and columns
 // (TBOA_GEMM_KLO) reads nothing else.  Causal scores with valid lower 256-tiles, L a multiple of 256.
-struct PtOut { bf16 *hi, *lo, *dhi, *dlo; };     // dhi, dlo: nullptr without a second score matrix
 
 __global__ __launch_bounds__(256) void softmax_t_kernel(const float* __restrict__ S, const float* __restrict__ S2, int L, int rep,
                                                         PtOut out, long long ldp, long long group_stride, int f16) {
@@ -531,13 +530,21 @@ __global__ __launch_bounds__(256) void bcat_kernel(const float* __restrict__ B1,
     }
 }
 
-// largest |x| of a bf16 array, as the bits of a non-negative float (atomicMax on the integer)
+// largest |x| of a bf16 array, as the bits of a non-negative float (atomicMax on the integer); a NaN counts as infinity.
+// Eight values per 16-byte load where the pointer allows it.
 __global__ void absmax_bf16_kernel(const bf16* __restrict__ x, long long n, int* __restrict__ out) {
     float m = 0.f;
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
-        const float v = fabsf(__bfloat162float(x[i]));
-        m = (v > m || !(v == v)) ? (v == v ? v : INFINITY) : m;
+    auto take = [&](float v) { v = fabsf(v); m = (v > m || !(v == v)) ? (v == v ? v : INFINITY) : m; };
+    const long long tid = blockIdx.x * (long long)blockDim.x + threadIdx.x, nth = (long long)gridDim.x * blockDim.x;
+    const long long n8 = (((uintptr_t)x & 15) == 0) ? n / 8 : 0;
+    for (long long i = tid; i < n8; i += nth) {
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        union { u4 u; bf16 b[8]; } v;
+        v.u = __builtin_nontemporal_load((const u4*)x + i);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) take(__bfloat162float(v.b[k]));
     }
+    for (long long i = 8 * n8 + tid; i < n; i += nth) take(__bfloat162float(x[i]));
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
     if ((threadIdx.x & 63) == 0) atomicMax(out, __float_as_int(m));
@@ -831,6 +838,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     const int T = D.T, dm = D.dm, Hq = D.Hq, Hkv = D.Hkv, dh = D.dh, L = D.L, dq = D.dq, dkv = D.dkv, rep = D.rep;
     const bool fp = X_fp != nullptr, rv = fp && R_v;
     const bool grouped = summed_form(D);
+    const bool fused = grouped && qk_blocked(D) && attn_probs_t_supported(D.L, D.dh);     // no score matrices in memory
     int G = d->seq_chunk > 0 ? d->seq_chunk : 8; if (G > D.S) G = D.S;
     // segments of P / of the transposed chunk ([X | dX | X~]; summed form: every one twice, for the (hi, lo) operands it meets)
     const int nsg = rv ? 2 : 1, nsx = (grouped ? 2 : 1) * (rv ? 3 : 1), splits = pick_splits(D.S);
@@ -854,7 +862,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         Qf = ar.get<float>((size_t)G * L * dq); Kf = ar.get<float>((size_t)G * L * dkv);
         Qh = ar.get<bf16>((size_t)G * L * dq * 3); Kh = ar.get<bf16>((size_t)G * L * dkv * 3);
         Qhf = rv ? ar.get<bf16>((size_t)G * L * dq * 3) : nullptr; Khf = rv ? ar.get<bf16>((size_t)G * L * dkv * 3) : nullptr;
-        Sc = ar.get<float>((size_t)Hq * L * L); Scf = rv ? ar.get<float>((size_t)Hq * L * L) : nullptr;
+        Sc = fused ? nullptr : ar.get<float>((size_t)Hq * L * L); Scf = (rv && !fused) ? ar.get<float>((size_t)Hq * L * L) : nullptr;
         XcT = ar.get<bf16>((size_t)dm * (G * nsx * L + PADE));
         if (grouped) {
             P = nullptr;
@@ -956,11 +964,17 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         if (grouped) {
             const int tiled = TBOA_GEMM_A_TILED | TBOA_GEMM_B_TILED;
             for (int sl = 0; sl < Gc; ++sl) {
-                if (rv) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
-                else TB_TRY(scores(D, Qh, Kh, sl, Sc));
-                hipLaunchKernelGGL(softmax_t_kernel, dim3(L / 64, Hq), dim3(256), 0, st, Sc, rv ? Scf : nullptr, L, rep, pt, ldpt,
-                                   (long long)L * ldpt, D.f16);
-                TB_KERNEL_CHECK(ctx);
+                if (fused) {       // scores and softmax in one kernel, nothing of the scores stored
+                    const long long qo = (long long)sl * Hq * L * 3 * dh, ko = (long long)sl * Hkv * L * 3 * dh;
+                    TB_TRY(attn_probs_t(ctx, Qh + qo, Kh + ko, rv ? Qhf + qo : nullptr, rv ? Khf + ko : nullptr, L, Hq, rep, dh, pt, ldpt,
+                                        (long long)L * ldpt, D.f16));
+                } else {
+                    if (rv) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
+                    else TB_TRY(scores(D, Qh, Kh, sl, Sc));
+                    hipLaunchKernelGGL(softmax_t_kernel, dim3(L / 64, Hq), dim3(256), 0, st, Sc, rv ? Scf : nullptr, L, rep, pt, ldpt,
+                                       (long long)L * ldpt, D.f16);
+                    TB_KERNEL_CHECK(ctx);
+                }
                 // B1 = sum_h A_h^T A_h and B2^T = sum_h A_h^T (A_h - A~_h): contraction over (head of the group, t >= max(i, j)) and
                 // over the three products of (hi, lo) parts, in one pass.  B1 is symmetric: only its tiles on or below the diagonal
                 GemmBf16 b = nt(L, L, 3 * (rep / parts) * L, 1.f, pt.hi, ldpt, pt.hi, ldpt, B1f, L, TBOA_F32, 0, tiled | TBOA_GEMM_KLO | TBOA_GEMM_LOWER | hf);

@@ -125,6 +125,17 @@ struct GemmBf16 {
 #define TBOA_GEMM_C_HILO 0x10000
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
 
+// Transposed causal attention probabilities of all heads of one sequence as (hi, lo) pairs of 16-bit values (IEEE half
+// when f16, else bf16): Pt[g][i][r L + t] = A_h[t, i], h = g rep + r, every [L, ldp] matrix of a KV group in 16 x 32 blocks,
+// rows i up to the end of the 256-tile that holds t written (zeros beyond the diagonal).  dhi, dlo: A - A~ of a second
+// score matrix (nullptr without one).
+struct PtOut { __hip_bfloat16 *hi, *lo, *dhi, *dlo; };
+// straight from the blocked 3-term operands Q^ [Hq][L, 3 dh], K^ [Hkv][L, 3 dh] of the score product (second pair Qb, Kb or
+// nullptr); attn_probs_t_supported tells which shapes the kernel takes
+bool attn_probs_t_supported(int L, int dh);
+int attn_probs_t(tboa_ctx* ctx, const __hip_bfloat16* Qa, const __hip_bfloat16* Ka, const __hip_bfloat16* Qb, const __hip_bfloat16* Kb, int L,
+                 int Hq, int rep, int dh, PtOut out, long long ldp, long long group_stride, int f16);
+
 // element offset of (r, c) in a matrix kept in the 16 x 32 blocks the bf16 GEMM can read and write (TBOA_GEMM_*_TILED);
 // kb = leading dimension / 32
 __device__ __forceinline__ long long tboa_blocked_offset(long long r, long long c, long long kb) {
