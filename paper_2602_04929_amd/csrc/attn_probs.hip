@@ -7,8 +7,8 @@
 // Operands: Q^ = [q_hi | q_lo | q_hi] and K^ = [k_hi | k_hi | k_lo], one [L, 3 d_h] bf16 matrix per head in 16 x 32 blocks
 // (as split3_kernel writes them), so that Q^ K^T = q_hi k_hi + q_lo k_hi + q_hi k_lo carries the fp32 projections to 16 bits.
 //
-// One workgroup per (64 query rows t, head), four wavefronts = (path, half of the 64 keys of a tile).  A wavefront keeps
-// the Q^ fragments of its path for all 64 queries in registers (two 32-wide blocks, the distinct segments q_hi and q_lo)
+// One workgroup per (128 query rows t, head), eight wavefronts = (path, half of the 64 keys of a tile, half of the queries).
+// A wavefront keeps the Q^ fragments of its path for its 64 queries in registers (two 32-wide blocks, the distinct segments q_hi and q_lo)
 // and computes S^T = K^ Q^T for its 32 keys: with the keys as the rows of the MFMA result, a lane holds ONE query column
 // and 16 key rows, so the running maximum and sum of a query need no traffic between lanes until the end.  The K^ tile of
 // both paths (segments k_hi, k_lo: 64 x d_h each) is copied global -> LDS block by block (a 16 x 32 block is 1 KB contiguous
@@ -38,19 +38,23 @@ __device__ __forceinline__ float dec16(bf16 b, int f16) {
     return __bfloat162float(b);
 }
 
-constexpr int EXP = 72;        // floats per row of the exchange buffer: the two lane halves of a wavefront write rows 4 apart
+constexpr int BT = 128;        // queries per workgroup
+constexpr int EXP = BT + 8;    // floats per row of the exchange buffer: the two lane halves of a wavefront write rows 4 apart
 
 template <int DH>
-constexpr int attn_lds_bytes() { return 4 * 64 * 2 * DH + 2 * 64 * EXP * 4 + 2 * 2 * 2 * 64 * 4 + 2 * 2 * 64 * 4; }
+constexpr int attn_lds_bytes() { return 4 * 64 * 2 * DH + 2 * 64 * EXP * 4 + 2 * 2 * 2 * BT * 4 + 2 * 2 * BT * 4; }
 
 // one 1 KB block global -> LDS: lane l moves the 16 bytes at base + voff (voff = 16 l) to lds_addr + 16 l
 __device__ __forceinline__ void lds_direct_16(unsigned voff, const char* base, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" ::"v"(voff), "s"(lds_addr), "s"(base) : "memory", "m0");
 }
 
+// 2^x on the transcendental unit
+__device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 template <int DH>
-__global__ __launch_bounds__(256) void attn_probs_t_kernel(const bf16* __restrict__ Qa, const bf16* __restrict__ Ka, const bf16* __restrict__ Qb,
-                                                           const bf16* __restrict__ Kb, int L, int nheads, int rep, int xcd_runs, float scale,
+__global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restrict__ Qa, const bf16* __restrict__ Ka, const bf16* __restrict__ Qb,
+                                                           const bf16* __restrict__ Kb, int L, int nheads, int rep, int xcd_runs, float scale2,
                                                            PtOut out, long long ldp, long long group_stride, int f16) {
     constexpr int NKS = DH / 16;                 // 16-deep MFMA steps per segment
     constexpr int NCB = DH / 32;                 // 32-column blocks per segment
@@ -60,25 +64,28 @@ __global__ __launch_bounds__(256) void attn_probs_t_kernel(const bf16* __restric
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     unsigned char* kt = smem;                                // [path][k_hi, k_lo][NCB][64 keys][64 bytes]
     float* ex = (float*)(smem + 4 * SEGB);                   // [path][64 keys][EXP]: probabilities of the tile
-    float* stat = ex + 2 * 64 * EXP;                         // [path][key half][max, sum][64 queries]
-    float* fin = stat + 2 * 2 * 2 * 64;                      // [path][max, 1 / sum][64 queries]
+    float* stat = ex + 2 * 64 * EXP;                         // [path][key half][max, sum][BT queries]
+    float* fin = stat + 2 * 2 * 2 * BT;                      // [path][max, 1 / sum][BT queries]
 
-    // Work items in the order (KV group, 64-row block from the last, i.e. longest, to the first, head of the group).  When the
+    // Work items in the order (KV group, 128-row block from the last, i.e. longest, to the first, head of the group).  When the
     // groups divide evenly over the 8 XCDs (workgroup w runs on XCD w % 8), XCD x takes the contiguous run of items of its
     // groups: the K^ of a group (both paths: 12 L d_h bytes, 3 MB for L = 2048, d_h = 128) then stays in that XCD's L2 and the
     // heads of a group walk the same key tiles side by side.  Otherwise the items are taken in order.
-    const int ntb = L / 64, total = nheads * ntb;
+    const int ntb = L / BT, total = nheads * ntb;
     int item = blockIdx.x;
     if (xcd_runs) item = (blockIdx.x & 7) * (total / 8) + (blockIdx.x >> 3);
     const int g = item / (rep * ntb), rem = item % (rep * ntb), r = rem % rep, h = g * rep + r;
-    const int t0 = (ntb - 1 - rem / rep) * 64;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, p = wave >> 1, wi = wave & 1;
+    const int t0 = (ntb - 1 - rem / rep) * BT;
+    // eight wavefronts = (path, half of the tile's 64 keys, half of the 128 queries); two per SIMD, so that the element-wise
+    // work of one runs under the MFMAs of the other
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, p = wave >> 2, wi = (wave >> 1) & 1, th = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
     const bool two = Qb != nullptr, active = (p == 0) || two;
     const long long mat = (long long)L * 3 * DH;
     const bf16* K0 = Ka + g * mat; const bf16* K1 = two ? Kb + g * mat : K0;
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const unsigned kt_lds = (unsigned)(unsigned long long)((__attribute__((address_space(3))) void*)kt);
+    const int tq = t0 + 64 * th;                 // first query of this wavefront
 
     // Q^ fragments of this wavefront's path: B operand of the MFMA (lane: query l32 of block tb, 8 contraction elements from 8 lh)
     bf16x8 qh[2][NKS], ql[2][NKS];
@@ -88,19 +95,19 @@ __global__ __launch_bounds__(256) void attn_probs_t_kernel(const bf16* __restric
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                const int t = t0 + 32 * tb + l32, c = 16 * ks + 8 * lh;
+                const int t = tq + 32 * tb + l32, c = 16 * ks + 8 * lh;
                 qh[tb][ks] = *(const bf16x8*)(Qp + tboa_blocked_offset(t, c, KB));
                 ql[tb][ks] = *(const bf16x8*)(Qp + tboa_blocked_offset(t, DH + c, KB));
             }
     }
 
     // the K^ tile at keys i0: block b = ((path 2 + segment) NCB + cb) 4 + rb of the LDS image comes from block
-    // (i0 / 16 + rb, segment's first block + cb) of that path's K^; wavefront w copies the blocks w, w + 4, ...
+    // (i0 / 16 + rb, segment's first block + cb) of that path's K^; wavefront w copies the blocks w, w + 8, ...
     auto issue = [&](int i0) {
         const int nblk = two ? NBLK : NBLK / 2;
 #pragma unroll
-        for (int j = 0; j < NBLK / 4; ++j) {
-            const int b = wave_s + 4 * j;
+        for (int j = 0; j < NBLK / 8; ++j) {
+            const int b = wave_s + 8 * j;
             if (b < nblk) {
                 const int rb = b & 3, cb = (b >> 2) % NCB, ps = (b >> 2) / NCB;     // ps = path 2 + segment (k_hi, k_lo)
                 const bf16* src = ((ps >> 1) ? K1 : K0) + ((long long)((i0 >> 4) + rb) * KB + ((ps & 1) ? 2 * NCB : 0) + cb) * 512;
@@ -108,7 +115,7 @@ __global__ __launch_bounds__(256) void attn_probs_t_kernel(const bf16* __restric
             }
         }
     };
-    // S^T of the tile for this wavefront: acc[tb][4 b + j] = score(key i0 + 32 wi + 8 b + 4 lh + j, query t0 + 32 tb + l32)
+    // S^T of the tile for this wavefront: acc[tb][4 b + j] = q . k of (key i0 + 32 wi + 8 b + 4 lh + j, query tq + 32 tb + l32)
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     f32x16 acc[2];
     auto multiply = [&]() {
@@ -130,8 +137,9 @@ __global__ __launch_bounds__(256) void attn_probs_t_kernel(const bf16* __restric
     };
     auto landed = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); };
 
-    const int live = t0 / 64 + 1;                              // key tiles up to and including the diagonal
+    const int live = t0 / 64 + 2;                              // key tiles up to and including the two on the diagonal
     const int tiles = min(L, (t0 / 256 + 1) * 256) / 64;       // ... up to the end of the diagonal's 256-tile
+    // Scores are kept in units of log 2: v = (q . k) scale2 with scale2 = log2(e) / sqrt(d_h), probabilities 2^(v - max) / sum.
     // ---- pass 1: maximum and sum per query, over this wavefront's keys
     float m[2] = {-INFINITY, -INFINITY}, s[2] = {0.f, 0.f};
     issue(0);
@@ -142,21 +150,21 @@ __global__ __launch_bounds__(256) void attn_probs_t_kernel(const bf16* __restric
         if (it + 1 < live) issue(64 * (it + 1));           // the next one lands under the element-wise work below
         if (active) {
             const int ib = 64 * it + 32 * wi + 4 * lh;
+            const bool masked = 64 * it + 63 > tq;         // a tile that reaches beyond the first query of this wavefront
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) {
-                const int t = t0 + 32 * tb + l32;
+                const int t = tq + 32 * tb + l32;
                 float vm = -INFINITY;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int i = ib + 8 * (e >> 2) + (e & 3);
-                    acc[tb][e] *= scale;
-                    if (i <= t) vm = fmaxf(vm, acc[tb][e]);
+                    acc[tb][e] *= scale2;
+                    if (masked && ib + 8 * (e >> 2) + (e & 3) > t) acc[tb][e] = -INFINITY;
+                    vm = fmaxf(vm, acc[tb][e]);
                 }
-                if (vm > m[tb]) { s[tb] *= __expf(m[tb] - vm); m[tb] = vm; }
+                if (vm > m[tb]) { s[tb] *= ex2(m[tb] - vm); m[tb] = vm; }
+                if (m[tb] != -INFINITY) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int i = ib + 8 * (e >> 2) + (e & 3);
-                    if (i <= t) s[tb] += __expf(acc[tb][e] - m[tb]);
+                    for (int e = 0; e < 16; ++e) s[tb] += ex2(acc[tb][e] - m[tb]);
                 }
             }
         }
@@ -167,29 +175,33 @@ __global__ __launch_bounds__(256) void attn_probs_t_kernel(const bf16* __restric
         for (int tb = 0; tb < 2; ++tb) {       // the two lane halves hold different keys of the same query
             const float m2 = __shfl_xor(m[tb], 32, 64), s2 = __shfl_xor(s[tb], 32, 64);
             const float M = fmaxf(m[tb], m2);
-            const float sum = (m[tb] == -INFINITY ? 0.f : s[tb] * __expf(m[tb] - M)) + (m2 == -INFINITY ? 0.f : s2 * __expf(m2 - M));
-            if (lh == 0) { stat[((p * 2 + wi) * 2 + 0) * 64 + 32 * tb + l32] = M; stat[((p * 2 + wi) * 2 + 1) * 64 + 32 * tb + l32] = sum; }
+            const float sum = (m[tb] == -INFINITY ? 0.f : s[tb] * ex2(m[tb] - M)) + (m2 == -INFINITY ? 0.f : s2 * ex2(m2 - M));
+            const int tl = 64 * th + 32 * tb + l32;
+            if (lh == 0) { stat[((p * 2 + wi) * 2 + 0) * BT + tl] = M; stat[((p * 2 + wi) * 2 + 1) * BT + tl] = sum; }
         }
     }
     __syncthreads();
-    if (threadIdx.x < 128 && (threadIdx.x < 64 || two)) {
-        const int pp = threadIdx.x >> 6, tl = threadIdx.x & 63;
-        const float ma = stat[((pp * 2 + 0) * 2 + 0) * 64 + tl], sa = stat[((pp * 2 + 0) * 2 + 1) * 64 + tl];
-        const float mb = stat[((pp * 2 + 1) * 2 + 0) * 64 + tl], sb = stat[((pp * 2 + 1) * 2 + 1) * 64 + tl];
+    if (threadIdx.x < 2 * BT && (threadIdx.x < BT || two)) {
+        const int pp = threadIdx.x / BT, tl = threadIdx.x % BT;
+        const float ma = stat[((pp * 2 + 0) * 2 + 0) * BT + tl], sa = stat[((pp * 2 + 0) * 2 + 1) * BT + tl];
+        const float mb = stat[((pp * 2 + 1) * 2 + 0) * BT + tl], sb = stat[((pp * 2 + 1) * 2 + 1) * BT + tl];
         const float M = fmaxf(ma, mb);
-        const float sum = (ma == -INFINITY ? 0.f : sa * __expf(ma - M)) + (mb == -INFINITY ? 0.f : sb * __expf(mb - M));
-        fin[(pp * 2 + 0) * 64 + tl] = M; fin[(pp * 2 + 1) * 64 + tl] = 1.f / sum;
+        const float sum = (ma == -INFINITY ? 0.f : sa * ex2(ma - M)) + (mb == -INFINITY ? 0.f : sb * ex2(mb - M));
+        fin[(pp * 2 + 0) * BT + tl] = M; fin[(pp * 2 + 1) * BT + tl] = 1.f / sum;
     }
     __syncthreads();
     float M[2] = {0.f, 0.f}, inv[2] = {0.f, 0.f};
     if (active) {
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) { M[tb] = fin[(p * 2 + 0) * 64 + 32 * tb + l32]; inv[tb] = fin[(p * 2 + 1) * 64 + 32 * tb + l32]; }
+        for (int tb = 0; tb < 2; ++tb) {
+            const int tl = 64 * th + 32 * tb + l32;
+            M[tb] = fin[(p * 2 + 0) * BT + tl]; inv[tb] = fin[(p * 2 + 1) * BT + tl];
+        }
     }
     // ---- pass 2: probabilities, exchanged through LDS, written transposed
     bf16* dst[4] = {out.hi + g * group_stride, out.lo + g * group_stride, out.dhi ? out.dhi + g * group_stride : nullptr,
                     out.dlo ? out.dlo + g * group_stride : nullptr};
-    const int ri = threadIdx.x >> 2, tc = (threadIdx.x & 3) * 16;      // store phase: key row of the tile, 16 consecutive queries
+    const int ri = threadIdx.x >> 3, tc = (threadIdx.x & 7) * 16;      // store phase: key row of the tile, 16 consecutive queries
     issue(0);
     landed();
     for (int it = 0; it < tiles; ++it) {
@@ -198,14 +210,16 @@ __global__ __launch_bounds__(256) void attn_probs_t_kernel(const bf16* __restric
             if (active) {
                 multiply();
                 const int il = 32 * wi + 4 * lh;
+                const bool masked = i0 + 63 > tq;
 #pragma unroll
                 for (int tb = 0; tb < 2; ++tb) {
-                    const int t = t0 + 32 * tb + l32;
+                    const int t = tq + 32 * tb + l32;
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         const int row = il + 8 * (e >> 2) + (e & 3);
-                        const float a = (i0 + row <= t) ? __expf(acc[tb][e] * scale - M[tb]) * inv[tb] : 0.f;
-                        ex[(p * 64 + row) * EXP + 32 * tb + l32] = a;
+                        float a = ex2(acc[tb][e] * scale2 - M[tb]) * inv[tb];
+                        if (masked && i0 + row > t) a = 0.f;
+                        ex[(p * 64 + row) * EXP + 64 * th + 32 * tb + l32] = a;
                     }
                 }
             }
@@ -252,9 +266,9 @@ int launch(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const 
         TB_HIP(ctx, hipFuncSetAttribute((const void*)attn_probs_t_kernel<DH>, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
         attr_set = true;
     }
-    const int total = Hq * (L / 64), xcd_runs = ((Hq / rep) % 8 == 0 && total % 8 == 0) ? 1 : 0;
-    hipLaunchKernelGGL(attn_probs_t_kernel<DH>, dim3(total), dim3(256), smem, ctx->stream, Qa, Ka, Qb, Kb, L, Hq, rep, xcd_runs,
-                       (float)(1.0 / sqrt((double)DH)), out, ldp, group_stride, f16);
+    const int total = Hq * (L / BT), xcd_runs = ((Hq / rep) % 8 == 0 && total % 8 == 0) ? 1 : 0;
+    hipLaunchKernelGGL(attn_probs_t_kernel<DH>, dim3(total), dim3(512), smem, ctx->stream, Qa, Ka, Qb, Kb, L, Hq, rep, xcd_runs,
+                       (float)(1.4426950408889634 / sqrt((double)DH)), out, ldp, group_stride, f16);
     TB_KERNEL_CHECK(ctx);
     return 0;
 }
