@@ -209,9 +209,10 @@ typedef struct {
                            candidate.  0: the default, 0.25.  Negative: fp64 costs for every candidate from the start. */
 } tboa_layer_desc;
 
-/* Workspace that tboa_quantize_layer needs for this descriptor (an upper bound: the size with H_out and R given);
- * 0 for an invalid descriptor. */
-size_t tboa_quantize_workspace_bytes(const tboa_layer_desc* desc);
+/* Workspace that tboa_quantize_layer needs for this descriptor, called with (with_H_out != 0) or without H_out and with
+ * (with_R != 0) or without R; 0 for an invalid descriptor.  (Without H_out the rows are independent, and the group-wise
+ * scale refinement then keeps one Gram entry per row and pair of groups instead of one d_h x d_h block per head.) */
+size_t tboa_quantize_workspace_bytes(const tboa_layer_desc* desc, int with_H_out, int with_R);
 
 /*   W      [d_out, d_in]            (w_dtype)
  *   H_in   fp32, shape per hin_per_head

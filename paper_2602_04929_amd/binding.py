@@ -51,7 +51,7 @@ def _load():
         "tboa_last_error": ([vp], C.c_char_p),
         "tboa_workspace_bytes": ([vp], C.c_size_t),
         "tboa_reserve_workspace": ([vp, C.c_size_t], i32),
-        "tboa_quantize_workspace_bytes": ([C.POINTER(LayerDesc)], C.c_size_t),
+        "tboa_quantize_workspace_bytes": ([C.POINTER(LayerDesc), C.c_int, C.c_int], C.c_size_t),
         "tboa_gemm_f64": ([vp, i32, i32, i32, f64, vp, i64, i64, vp, i64, i64, f64, vp, i64, i32, i64, i64, i64], i32),
         "tboa_gemm_bf16_nt": ([vp, i32, i32, i32, f32, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i64, i64, i64], i32),
         "tboa_chol_inv_upper": ([vp, i32, i32, vp, f64, vp], i32),
@@ -157,8 +157,8 @@ class Context:
         return int(_lib.tboa_hessian_workspace_bytes(C.byref(desc)))
 
     @staticmethod
-    def quantize_workspace_bytes(desc):
-        return int(_lib.tboa_quantize_workspace_bytes(C.byref(desc)))
+    def quantize_workspace_bytes(desc, with_H_out=True, with_R=True):
+        return int(_lib.tboa_quantize_workspace_bytes(C.byref(desc), int(with_H_out), int(with_R)))
 
     # ---- live kernel timing
     PROF_TAGS = {"hv_syrk": 0, "ax": 1, "rv": 2, "gram": 3, "proj": 4, "grid": 5,

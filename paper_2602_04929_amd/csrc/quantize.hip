@@ -153,6 +153,15 @@ __global__ void hcat_kernel(const double* __restrict__ H, bf16* __restrict__ out
     }
 }
 
+// T[b][k][c] = H[b][k][c] for k < c, half of it for k == c, 0 for k > c (fp64): delta H delta^T = 2 delta T delta^T for the
+// symmetric H, and a product with T needs, for output column c, only the contraction indices k <= c
+__global__ void tri_half_kernel(const double* __restrict__ H, double* __restrict__ T, int n, long long total) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const int k = (int)((i / n) % n), c = (int)(i % n);
+        T[i] = k < c ? H[i] : k == c ? 0.5 * H[i] : 0.0;
+    }
+}
+
 // Acat[(row, k), :] = [hi(delta) | lo(delta) | hi(delta)], delta as in grid_delta_kernel; mat_rows > 0: Acat is a sequence of matrices
 // of mat_rows rows each (the rows that share one H_in), every one kept in the 16 x 32 blocks of the bf16 GEMM
 __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
@@ -353,13 +362,15 @@ __global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const d
 __global__ void clear_words_kernel(int* p, int n) { if ((int)threadIdx.x < n) p[threadIdx.x] = 0; }
 
 // ------------------------------------------------------------------------------------------------ Algorithm 3
+constexpr int SWEEP_SP = 256;      // columns whose updates of the columns further right are applied in one product
 struct SweepArgs {
     double* Wk; int n; int nbr; BlockMap map;
     const double* U; const double* P; int per_head;   // U, P: [n, n] or [n_heads, n, n]
     int c0, pw;
     const double* s; const double* z; int ng, gi; double maxq;
     uint8_t* codes; double* Q;       // layer arrays [d_out, n]
-    double* Epan; double* Wsnap;     // block arrays [rows, 64]
+    double* Epan; double* Wsnap;     // block arrays [rows, epitch], already offset to this panel's first column
+    int epitch;
 };
 
 template <int RPW>
@@ -406,9 +417,9 @@ __global__ __launch_bounds__(256) void sweep_panel_kernel(SweepArgs a) {
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
         if (!valid[i]) continue;
-        a.Epan[(long long)R[i] * 64 + lane] = ev[i];
-        a.Wsnap[(long long)R[i] * 64 + lane] = wsv[i];
         if (lane < pw) {
+            a.Epan[(long long)R[i] * a.epitch + lane] = ev[i];
+            a.Wsnap[(long long)R[i] * a.epitch + lane] = wsv[i];
             const long long lr = layer_row(a.map, R[i]);
             a.codes[lr * n + c0 + lane] = (uint8_t)qv[i];
             a.Q[lr * n + c0 + lane] = Qv[i];
@@ -642,6 +653,7 @@ struct Layer {
     double *Wb, *Wk, *Epan, *Wsnap, *E, *S1, *S2, *T;
     double *cand_s, *cand_z, *Delta, *G, *cost, *DeltaS, *GS, *costS, *lim;
     __hip_bfloat16* Hcat; int* sel; int fast_grid, grid_blocked;
+    double* Ht;         // two-phase search: upper triangle of H_in with half its diagonal (see tri_half_kernel)
     double *Wbar, *Abar, *Z, *WR, *Cm, *Fm, *dvec, *lossbuf;
     double *Cg, *Fg;    // group-wise refinement: Gram blocks per (group, group) pair
     int grid_chunk;     // block rows (shared H_in) or heads (per-head H_in) per grid-search pass
@@ -693,9 +705,10 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
                                L.cand_s, L.cand_z, L.cost, L.lim, cntv, offv, per, cap, L.DeltaS);
             TB_KERNEL_CHECK(ctx);
             GemmF64 g{};
-            g.M = cap; g.N = n; g.K = n; g.alpha = 1.0; g.beta = 0.0; g.A = L.DeltaS; g.sam = n; g.sak = 1; g.sbk = n; g.sbn = 1;
+            // exact costs of the survivors: delta H delta^T = 2 delta T delta^T, the contraction of column c ending at c
+            g.M = cap; g.N = n; g.K = n; g.alpha = 2.0; g.beta = 0.0; g.A = L.DeltaS; g.sam = n; g.sak = 1; g.sbk = n; g.sbn = 1;
             g.C = L.GS; g.ldc = n; g.batch = ngrp; g.strideA = (long long)g.M * n; g.strideC = g.strideA; g.m_limit = totv;
-            g.B = L.Hi + (ph ? (long long)u0 * L.nn : 0); g.strideB = ph ? L.nn : 0;
+            g.B = L.Ht + (ph ? (long long)u0 * L.nn : 0); g.strideB = ph ? L.nn : 0; g.khi_n = 1;
             g.tag = TBOA_PROF_F64_GRID;
             TB_TRY(gemm_f64(ctx, g));
             const long long srow = (long long)ngrp * cap;
@@ -770,6 +783,7 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     if (L.fast_grid) {
         long long tot = nhin * nn, gb = (tot + 255) / 256; if (gb > 32768) gb = 32768;
         hipLaunchKernelGGL(hcat_kernel, dim3((unsigned)gb), dim3(256), 0, st, L.Hi, L.Hcat, n, tot, L.grid_blocked);
+        hipLaunchKernelGGL(tri_half_kernel, dim3((unsigned)gb), dim3(256), 0, st, L.Hi, L.Ht, n, tot);
         TB_KERNEL_CHECK(ctx);
     }
     // U_in, P and U_out are first needed by the first in-channel sweep; the grid search before it needs only W and H_in.
@@ -825,6 +839,9 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     };
     const double* Pp = R ? L.P : nullptr;
     const int pw_max = L.gsz < 64 ? L.gsz : 64;
+    // columns per group of panels: a group-wise grid is searched on the current columns of its group when the sweep enters
+    // it, so a group of panels must not straddle a grid group that starts inside it unaligned
+    const int sp = (!d->group || SWEEP_SP % L.gsz == 0 || L.gsz % SWEEP_SP == 0) ? SWEEP_SP : pw_max;
 
     if (!d->adaptive_grid) {   // BoA: one grid from the original weights
         BlockMap id{dh, dh, 0};
@@ -838,21 +855,34 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
         TB_KERNEL_CHECK(ctx);
         TB_HIP(ctx, hipMemcpyAsync(L.Wk, L.Wb, (size_t)rows * n * sizeof(double), hipMemcpyDeviceToDevice, st));
         if (d->adaptive_grid && !d->group) TB_TRY(grid_search(L, L.Wk, n, nbr, map, 0, n, 0));
-        for (int c0 = 0; c0 < n; c0 += pw_max) {
-            const int pw = (n - c0 < pw_max) ? n - c0 : pw_max, c1 = c0 + pw;
-            const int gi = c0 / L.gsz;
-            if (d->group && d->adaptive_grid && c0 % L.gsz == 0) TB_TRY(grid_search(L, L.Wk, n, nbr, map, c0, L.gsz, gi));
-            SweepArgs a;
-            a.Wk = L.Wk; a.n = n; a.nbr = nbr; a.map = map; a.U = L.Uin; a.P = Pp; a.per_head = nhin > 1;
-            a.c0 = c0; a.pw = pw; a.s = L.s64; a.z = L.z64; a.ng = ng; a.gi = gi; a.maxq = L.maxq;
-            a.codes = codes; a.Q = L.Q64; a.Epan = L.Epan; a.Wsnap = L.Wsnap;
-            TB_TRY(setup_join());
-            hipLaunchKernelGGL((sweep_panel_kernel<2>), dim3((nbr + 7) / 8, nh), dim3(256), 0, st, a);
-            TB_KERNEL_CHECK(ctx);
-            if (c1 < n) {   // columns right of the panel: W[:, c1:] -= E U[c0:c1, c1:] + Wsnap P[c0:c1, c1:]
-                GemmF64 two{};   // both terms in one pass over the output
-                if (Pp) { two.A2 = L.Wsnap; two.B2 = L.P + (long long)c0 * n + c1; }
-                TB_TRY(block_gemm(L, nbr, n - c1, pw, -1.0, L.Epan, 64, L.Uin, (long long)c0 * n + c1, n, 1, 1.0, L.Wk + c1, n, TBOA_PROF_F64_SWEEP, &two));
+        // Algorithm 3 in panels on two levels: inside a group of up to SWEEP_SP columns every 64-column panel updates the rest of
+        // the group at once; the columns right of the group get the group's whole update in one product (a contraction SWEEP_SP
+        // deep instead of 64: a quarter of the passes over the remaining columns)
+        for (int s0 = 0; s0 < n; s0 += sp) {
+            const int s1 = (n - s0 < sp) ? n : s0 + sp;
+            for (int c0 = s0; c0 < s1; c0 += pw_max) {
+                const int pw = (s1 - c0 < pw_max) ? s1 - c0 : pw_max, c1 = c0 + pw;
+                const int gi = c0 / L.gsz;
+                if (d->group && d->adaptive_grid && c0 % L.gsz == 0) TB_TRY(grid_search(L, L.Wk, n, nbr, map, c0, L.gsz, gi));
+                SweepArgs a;
+                a.Wk = L.Wk; a.n = n; a.nbr = nbr; a.map = map; a.U = L.Uin; a.P = Pp; a.per_head = nhin > 1;
+                a.c0 = c0; a.pw = pw; a.s = L.s64; a.z = L.z64; a.ng = ng; a.gi = gi; a.maxq = L.maxq;
+                a.codes = codes; a.Q = L.Q64; a.Epan = L.Epan + (c0 - s0); a.Wsnap = L.Wsnap + (c0 - s0); a.epitch = SWEEP_SP;
+                TB_TRY(setup_join());
+                hipLaunchKernelGGL((sweep_panel_kernel<2>), dim3((nbr + 7) / 8, nh), dim3(256), 0, st, a);
+                TB_KERNEL_CHECK(ctx);
+                if (c1 < s1) {   // rest of the group: W[:, c1:s1] -= E U[c0:c1, c1:s1] + Wsnap P[c0:c1, c1:s1]
+                    GemmF64 two{};   // both terms in one pass over the output
+                    if (Pp) { two.A2 = L.Wsnap + (c0 - s0); two.B2 = L.P + (long long)c0 * n + c1; }
+                    TB_TRY(block_gemm(L, nbr, s1 - c1, pw, -1.0, L.Epan + (c0 - s0), SWEEP_SP, L.Uin, (long long)c0 * n + c1, n, 1, 1.0, L.Wk + c1, n,
+                                      TBOA_PROF_F64_SWEEP, &two));
+                }
+            }
+            if (s1 < n) {   // columns right of the group: W[:, s1:] -= E U[s0:s1, s1:] + Wsnap P[s0:s1, s1:]
+                GemmF64 two{};
+                if (Pp) { two.A2 = L.Wsnap; two.B2 = L.P + (long long)s0 * n + s1; }
+                TB_TRY(block_gemm(L, nbr, n - s1, s1 - s0, -1.0, L.Epan, SWEEP_SP, L.Uin, (long long)s0 * n + s1, n, 1, 1.0, L.Wk + s1, n,
+                                  TBOA_PROF_F64_SWEEP, &two));
             }
         }
         if (H_out && i1 < dh) {
@@ -1049,17 +1079,18 @@ void plan_layer(Layer& L, bool H_out, bool R, Arena& ar) {
     const size_t t_in = (size_t)L.nhin * n * chol_tmp_pitch(n), t_out = H_out ? (size_t)nh * dh * chol_tmp_pitch(dh) : 0;
     L.ftmp = ar.get<double>(t_in > t_out ? t_in : t_out); L.fdinv = ar.get<double>((size_t)fb * nblk_f * TB_FACT_NB * TB_FACT_NB);
     L.Wb = ar.get<double>(brows * n); L.Wk = ar.get<double>(brows * n);
-    L.Epan = ar.get<double>(brows * 64); L.Wsnap = ar.get<double>(brows * 64);
+    L.Epan = ar.get<double>(brows * SWEEP_SP); L.Wsnap = ar.get<double>(brows * SWEEP_SP);
     L.E = H_out ? ar.get<double>(brows * n) : nullptr;
     L.S1 = (H_out && R) ? ar.get<double>(brows * n) : nullptr; L.S2 = (H_out && R) ? ar.get<double>(brows * n) : nullptr;
     L.T = H_out ? ar.get<double>((size_t)nh * dh * d->block) : nullptr;
     L.cand_s = ar.get<double>(grows * L.ncand); L.cand_z = ar.get<double>(grows * L.ncand); L.cost = ar.get<double>(grows * L.ncand);
     L.Delta = ar.get<double>(grows * L.ncand * L.gsz); L.G = ar.get<double>(grows * L.ncand * L.gsz);
-    L.DeltaS = L.GS = L.costS = L.lim = nullptr; L.sel = nullptr; L.Hcat = nullptr;
+    L.DeltaS = L.GS = L.costS = L.lim = nullptr; L.sel = nullptr; L.Hcat = nullptr; L.Ht = nullptr;
     if (L.fast_grid) {
         L.DeltaS = ar.get<double>(grows * GRID_KS * n); L.GS = ar.get<double>(grows * GRID_KS * n);
         L.costS = ar.get<double>(grows * GRID_KS); L.lim = ar.get<double>(grows); L.sel = ar.get<int>(grows * 3);
         L.Hcat = ar.get<__hip_bfloat16>((size_t)L.nhin * n * (GRID_TERMS * (size_t)n + GRID_PAD));
+        L.Ht = ar.get<double>((size_t)L.nhin * L.nn);
     }
     L.Wbar = ar.get<double>(wn); L.Abar = ar.get<double>(wn); L.Z = ar.get<double>(wn);
     L.WR = R ? ar.get<double>(wn) : nullptr;
@@ -1113,12 +1144,12 @@ void init_layer(Layer& L, tboa_ctx* ctx, const tboa_layer_desc* d) {
 
 }  // namespace
 
-extern "C" size_t tboa_quantize_workspace_bytes(const tboa_layer_desc* d) {
+extern "C" size_t tboa_quantize_workspace_bytes(const tboa_layer_desc* d, int with_H_out, int with_R) {
     if (check_layer_desc(nullptr, d) != 0) return 0;
     Layer L{};
     init_layer(L, nullptr, d);
     Arena ar(nullptr);
-    plan_layer(L, true, true, ar);      // with H_out and R: an upper bound for the calls without them
+    plan_layer(L, with_H_out != 0, with_R != 0, ar);
     return ar.off;
 }
 

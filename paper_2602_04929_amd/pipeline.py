@@ -22,11 +22,11 @@ def reserve_workspaces(ctx, cfg, side_contexts=None, stack_qk=True, cd_iters=1, 
     wd = tb.F32 if cfg.dtype == "fp32" else tb.BF16
     Hq, Hkv, dh, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_model
 
-    def layer(d_out, d_in, n_heads, per_head, block):
+    def layer(d_out, d_in, n_heads, per_head, block, with_H_out=True):
         return ctx.quantize_workspace_bytes(tb.LayerDesc(d_out, d_in, n_heads, int(per_head), cfg.bits, block, cfg.group, wd, cd_iters,
-                                                         int(adaptive_grid), 100, 0.8, 0.01, 0.0))
+                                                         int(adaptive_grid), 100, 0.8, 0.01, 0.0), with_H_out, True)
     hess = ctx.hessian_workspace_bytes(d, Hq, Hkv, dh, cfg.n_seqs, cfg.seq_len, dt, seq_chunk=seq_chunk)
-    o = layer(d, Hq * dh, 1, False, d)
+    o = layer(d, Hq * dh, 1, False, d, with_H_out=False)
     v = layer(Hkv * dh, d, Hkv, True, cfg.block)
     first = [layer((Hq + Hkv) * dh, d, Hq + Hkv, False, cfg.block)] if stack_qk else [layer(Hq * dh, d, Hq, False, cfg.block), layer(Hkv * dh, d, Hkv, False, cfg.block)]
     jobs = first + [v]

@@ -198,6 +198,7 @@ def test_workspace_queries(ctx, lib):
         assert c2.workspace_bytes() == need                      # with H_out and R: exactly the bound
         c2.quantize_layer(t(W), t(Hin), None, None, 2, bits=2, block=8)
         assert c2.workspace_bytes() == need                      # without them: less
+        assert 0 < c2.quantize_workspace_bytes(desc, with_H_out=False, with_R=False) <= need
         b = ctx.quantize_layer(t(W), t(Hin), t(Hout), t(R), 2, bits=2, block=8)
         assert torch.equal(a["codes"], b["codes"]) and a["loss"] == b["loss"]
         bad = c2.layer_desc(t(W), t(Hin), 2, bits=5, block=8)

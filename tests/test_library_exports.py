@@ -85,4 +85,14 @@ def test_workspace_queries_are_host_arithmetic():
     a, b = C.quantize_workspace_bytes(d), C.quantize_workspace_bytes(per_head)
     assert 0 < a < b < 288 * 2 ** 30
     assert C.quantize_workspace_bytes(tb.LayerDesc(4096, 4096, 32, 0, 5, 32, 0, tb.BF16, 1, 1, 100, 0.8, 0.01, 0.0)) == 0
+    # every layer of every named configuration fits one GPU: W_O goes without H_out (its rows are independent), which is what
+    # keeps the group-wise refinement of the 13B-shaped layer small (one Gram entry per row instead of a block per head)
+    from paper_2602_04929_amd import synth
+    for name in ("llama2-7b", "llama2-13b", "llama2-70b", "llama2-7b-w4a4"):
+        cfg = synth.CONFIGS[name]
+        desc = lambda d_out, d_in, nh, per, block: tb.LayerDesc(d_out, d_in, nh, per, cfg.bits, block, cfg.group, tb.BF16, 1, 1, 100, 0.8, 0.01, 0.0)
+        o = C.quantize_workspace_bytes(desc(cfg.d_model, cfg.d_q, 1, 0, cfg.d_model), with_H_out=False)
+        v = C.quantize_workspace_bytes(desc(cfg.d_kv, cfg.d_model, cfg.n_kv_heads, 1, cfg.block))
+        qk = C.quantize_workspace_bytes(desc(cfg.d_q + cfg.d_kv, cfg.d_model, cfg.n_q_heads + cfg.n_kv_heads, 0, cfg.block))
+        assert 0 < o < 64 * 2 ** 30 and 0 < v < 64 * 2 ** 30 and 0 < qk < 64 * 2 ** 30, (name, o, v, qk)
     print("workspace: 7B Hessians %.1f GiB, 70B Hessians %.1f GiB, 7B W_Q %.1f GiB, 7B W_V %.1f GiB" % (big / 2 ** 30, gqa / 2 ** 30, a / 2 ** 30, b / 2 ** 30))
