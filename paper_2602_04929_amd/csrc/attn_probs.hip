@@ -52,7 +52,7 @@ __device__ __forceinline__ void lds_direct_16(unsigned voff, const char* base, u
 // 2^x on the transcendental unit
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <int DH>
+template <int DH, bool ROWS>
 __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restrict__ Qa, const bf16* __restrict__ Ka, const bf16* __restrict__ Qb,
                                                            const bf16* __restrict__ Kb, int L, int nheads, int rep, int xcd_runs, float scale2,
                                                            PtOut out, long long ldp, long long group_stride, int f16) {
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
         }
     }
     // ---- pass 2: probabilities, exchanged through LDS, written transposed
-    bf16* dst[4] = {out.hi + g * group_stride, out.lo + g * group_stride, out.dhi ? out.dhi + g * group_stride : nullptr,
+    bf16* dst[4] = {out.hi + g * group_stride, out.lo ? out.lo + g * group_stride : nullptr, out.dhi ? out.dhi + g * group_stride : nullptr,
                     out.dlo ? out.dlo + g * group_stride : nullptr};
     const int ri = threadIdx.x >> 3, tc = (threadIdx.x & 7) * 16;      // store phase: key row of the tile, 16 consecutive queries
     issue(0);
@@ -226,6 +226,28 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
             __syncthreads();                               // the tile has been read, its probabilities are in LDS
             if (it + 1 < live) issue(64 * (it + 1));
         }
+        if constexpr (ROWS) {
+            // row-major result P[h][t][.] = [A_hi | A_lo | A_hi | A - A~] (segments of L columns): thread = (query, 16 consecutive keys)
+            const int tq2 = threadIdx.x & (BT - 1), ic = threadIdx.x >> 7;
+            float a[16], d[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                a[e] = (it < live) ? ex[(16 * ic + e) * EXP + tq2] : 0.f;
+                d[e] = (it < live && two) ? a[e] - ex[(64 + 16 * ic + e) * EXP + tq2] : 0.f;
+            }
+            bf16* prow = out.hi + h * group_stride + (long long)(t0 + tq2) * ldp + i0 + 16 * ic;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                union { bf16 b[8]; uint4 u; } hi, lo, dd;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    hi.b[k] = enc16(a[8 * q + k], f16); lo.b[k] = enc16(a[8 * q + k] - dec16(hi.b[k], f16), f16);
+                    dd.b[k] = enc16(d[8 * q + k], f16);
+                }
+                *(uint4*)(prow + 8 * q) = hi.u; *(uint4*)(prow + L + 8 * q) = lo.u; *(uint4*)(prow + 2LL * L + 8 * q) = hi.u;
+                if (two) *(uint4*)(prow + 3LL * L + 8 * q) = dd.u;
+            }
+        } else {
         float a[16], d[16];
         if (it < live) {
 #pragma unroll
@@ -253,24 +275,36 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
             *(uint4*)(dst[0] + o) = hi.u; *(uint4*)(dst[1] + o) = lo.u;
             if (two) { *(uint4*)(dst[2] + o) = dh.u; *(uint4*)(dst[3] + o) = dl.u; }
         }
+        }
         if (it < live) landed();                           // next tile in LDS; the exchange buffer is free again
     }
 }
 
-template <int DH>
+template <int DH, bool ROWS>
 int launch(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, PtOut out, long long ldp,
            long long group_stride, int f16) {
     static bool attr_set = false;
     constexpr int smem = attn_lds_bytes<DH>();
     if (!attr_set) {
-        TB_HIP(ctx, hipFuncSetAttribute((const void*)attn_probs_t_kernel<DH>, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        TB_HIP(ctx, hipFuncSetAttribute((const void*)attn_probs_t_kernel<DH, ROWS>, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
         attr_set = true;
     }
     const int total = Hq * (L / BT), xcd_runs = ((Hq / rep) % 8 == 0 && total % 8 == 0) ? 1 : 0;
-    hipLaunchKernelGGL(attn_probs_t_kernel<DH>, dim3(total), dim3(512), smem, ctx->stream, Qa, Ka, Qb, Kb, L, Hq, rep, xcd_runs,
+    hipLaunchKernelGGL((attn_probs_t_kernel<DH, ROWS>), dim3(total), dim3(512), smem, ctx->stream, Qa, Ka, Qb, Kb, L, Hq, rep, xcd_runs,
                        (float)(1.4426950408889634 / sqrt((double)DH)), out, ldp, group_stride, f16);
     TB_KERNEL_CHECK(ctx);
     return 0;
+}
+
+template <bool ROWS>
+int dispatch(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, int dh, PtOut out,
+             long long ldp, long long group_stride, int f16) {
+    switch (dh) {
+        case 32: return launch<32, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
+        case 64: return launch<64, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
+        case 96: return launch<96, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
+        default: return launch<128, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
+    }
 }
 
 }  // namespace
@@ -283,10 +317,13 @@ int attn_probs_t(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, 
                  long long ldp, long long group_stride, int f16) {
     if (!attn_probs_t_supported(L, dh) || Hq % rep || !Qa || !Ka || (Qb && !Kb) || !out.hi || !out.lo || (Qb && (!out.dhi || !out.dlo)) || ldp % 32)
         return tboa_fail(ctx, TBOA_EINVAL, "attn_probs_t: unsupported shape or missing buffer");
-    switch (dh) {
-        case 32: return launch<32>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
-        case 64: return launch<64>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
-        case 96: return launch<96>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
-        default: return launch<128>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
-    }
+    return dispatch<false>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, dh, out, ldp, group_stride, f16);
+}
+
+int attn_probs_rows(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, int dh, bf16* P,
+                    long long ldp, int f16) {
+    if (!attn_probs_t_supported(L, dh) || Hq % rep || !Qa || !Ka || (Qb && !Kb) || !P || ldp % 8 || ldp < (Qb ? 4LL : 3LL) * L || ((uintptr_t)P & 15))
+        return tboa_fail(ctx, TBOA_EINVAL, "attn_probs_rows: unsupported shape or missing buffer");
+    PtOut out{P, nullptr, nullptr, nullptr};
+    return dispatch<true>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, dh, out, ldp, (long long)L * ldp, f16);
 }

@@ -1094,6 +1094,7 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
     const bool fp = X_fp && R_o;
     int G = d->seq_chunk > 0 ? d->seq_chunk : 8; if (G > D.S) G = D.S;
     const int nsg = fp ? 5 : 3, nsp = fp ? 4 : 3, splits = pick_splits(D.S);   // segments of V^T / of P
+    const bool fused = d->causal && qk_blocked(D) && attn_probs_t_supported(D.L, D.dh);     // no score matrices in memory
     const long long TP = (long long)T + PADE, ldp = (long long)nsp * L + PADE;
     bf16 *Wqh, *Wql, *Wkh, *Wkl, *Wvh, *Wvl, *Qh, *Kh, *Qhf, *Khf, *P, *VTc, *OT, *OTl, *dOT, *dOTl;
     float *Qf, *Kf, *VT32, *VT32f, *Sc, *Scf, *part, *steps;
@@ -1103,10 +1104,10 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         Wkh = ar.get<bf16>((size_t)dkv * dm); Wkl = ar.get<bf16>((size_t)dkv * dm);
         Wvh = ar.get<bf16>((size_t)dkv * dm); Wvl = ar.get<bf16>((size_t)dkv * dm);
         Qf = ar.get<float>((size_t)G * L * dq); Kf = ar.get<float>((size_t)G * L * dkv); VT32 = ar.get<float>((size_t)dkv * G * L);
-        VT32f = fp ? ar.get<float>((size_t)dkv * G * L) : nullptr; Scf = fp ? ar.get<float>((size_t)Hq * L * L) : nullptr;
+        VT32f = fp ? ar.get<float>((size_t)dkv * G * L) : nullptr; Scf = (fp && !fused) ? ar.get<float>((size_t)Hq * L * L) : nullptr;
         Qh = ar.get<bf16>((size_t)G * L * dq * 3); Kh = ar.get<bf16>((size_t)G * L * dkv * 3);
         Qhf = fp ? ar.get<bf16>((size_t)G * L * dq * 3) : nullptr; Khf = fp ? ar.get<bf16>((size_t)G * L * dkv * 3) : nullptr;
-        Sc = ar.get<float>((size_t)Hq * L * L); P = ar.get<bf16>((size_t)Hq * L * ldp);
+        Sc = fused ? nullptr : ar.get<float>((size_t)Hq * L * L); P = ar.get<bf16>((size_t)Hq * L * ldp);
         VTc = ar.get<bf16>((size_t)dkv * (G * nsg * L + PADE));
         OT = ar.get<bf16>((size_t)dq * TP); OTl = ar.get<bf16>((size_t)dq * TP);
         dOT = fp ? ar.get<bf16>((size_t)dq * TP) : nullptr; dOTl = fp ? ar.get<bf16>((size_t)dq * TP) : nullptr;
@@ -1149,9 +1150,14 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             // V^T segments [V'hi | V'hi | V'lo | V' - V~ | V~], P = [A'hi | A'lo | A'hi | A' - A~]:
             // O^T_h = [V'hi | V'hi | V'lo] [A'hi | A'lo | A'hi]^T ;  (O - O~)^T_h = [V' - V~ | V~] [A'hi | A' - A~]^T,
             // both left as exact-to-16-bit (hi, lo) pairs of bf16
-            if (fp) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
-            else TB_TRY(scores(D, Qh, Kh, sl, Sc));
-            TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, ldp, 2 * L, L, 3 * L));
+            if (fused) {      // scores and softmax in one kernel, nothing of the scores stored
+                const long long qo = (long long)sl * Hq * L * 3 * dh, ko = (long long)sl * D.Hkv * L * 3 * dh;
+                TB_TRY(attn_probs_rows(ctx, Qh + qo, Kh + ko, fp ? Qhf + qo : nullptr, fp ? Khf + ko : nullptr, L, Hq, rep, dh, P, ldp, D.f16));
+            } else {
+                if (fp) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
+                else TB_TRY(scores(D, Qh, Kh, sl, Sc));
+                TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, ldp, 2 * L, L, 3 * L));
+            }
             const long long co = t0 + (long long)sl * L;
             GemmBf16 o = nt(dh, L, 3 * L, 1.f, VTc + (long long)sl * nsg * L, ldv, P, ldp, OT + co, TP, TBOA_BF16, 0, cflag | TBOA_GEMM_C_HILO);
             o.C2 = OTl + co;

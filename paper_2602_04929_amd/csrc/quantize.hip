@@ -153,15 +153,6 @@ __global__ void hcat_kernel(const double* __restrict__ H, bf16* __restrict__ out
     }
 }
 
-// T[b][k][c] = H[b][k][c] for k < c, half of it for k == c, 0 for k > c (fp64): delta H delta^T = 2 delta T delta^T for the
-// symmetric H, and a product with T needs, for output column c, only the contraction indices k <= c
-__global__ void tri_half_kernel(const double* __restrict__ H, double* __restrict__ T, int n, long long total) {
-    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-        const int k = (int)((i / n) % n), c = (int)(i % n);
-        T[i] = k < c ? H[i] : k == c ? 0.5 * H[i] : 0.0;
-    }
-}
-
 // Acat[(row, k), :] = [hi(delta) | lo(delta) | hi(delta)], delta as in grid_delta_kernel; mat_rows > 0: Acat is a sequence of matrices
 // of mat_rows rows each (the rows that share one H_in), every one kept in the 16 x 32 blocks of the bf16 GEMM
 __global__ __launch_bounds__(256) void grid_delta_split_kernel(const double* __restrict__ Wk, long long ldw, int n, int ncand, double maxq,
@@ -653,7 +644,6 @@ struct Layer {
     double *Wb, *Wk, *Epan, *Wsnap, *E, *S1, *S2, *T;
     double *cand_s, *cand_z, *Delta, *G, *cost, *DeltaS, *GS, *costS, *lim;
     __hip_bfloat16* Hcat; int* sel; int fast_grid, grid_blocked;
-    double* Ht;         // two-phase search: upper triangle of H_in with half its diagonal (see tri_half_kernel)
     double *Wbar, *Abar, *Z, *WR, *Cm, *Fm, *dvec, *lossbuf;
     double *Cg, *Fg;    // group-wise refinement: Gram blocks per (group, group) pair
     int grid_chunk;     // block rows (shared H_in) or heads (per-head H_in) per grid-search pass
@@ -705,10 +695,9 @@ int grid_search(Layer& L, const double* Wrows, long long ldw, int rows_per_head,
                                L.cand_s, L.cand_z, L.cost, L.lim, cntv, offv, per, cap, L.DeltaS);
             TB_KERNEL_CHECK(ctx);
             GemmF64 g{};
-            // exact costs of the survivors: delta H delta^T = 2 delta T delta^T, the contraction of column c ending at c
-            g.M = cap; g.N = n; g.K = n; g.alpha = 2.0; g.beta = 0.0; g.A = L.DeltaS; g.sam = n; g.sak = 1; g.sbk = n; g.sbn = 1;
+            g.M = cap; g.N = n; g.K = n; g.alpha = 1.0; g.beta = 0.0; g.A = L.DeltaS; g.sam = n; g.sak = 1; g.sbk = n; g.sbn = 1;
             g.C = L.GS; g.ldc = n; g.batch = ngrp; g.strideA = (long long)g.M * n; g.strideC = g.strideA; g.m_limit = totv;
-            g.B = L.Ht + (ph ? (long long)u0 * L.nn : 0); g.strideB = ph ? L.nn : 0; g.khi_n = 1;
+            g.B = L.Hi + (ph ? (long long)u0 * L.nn : 0); g.strideB = ph ? L.nn : 0;
             g.tag = TBOA_PROF_F64_GRID;
             TB_TRY(gemm_f64(ctx, g));
             const long long srow = (long long)ngrp * cap;
@@ -783,7 +772,6 @@ int run_layer(Layer& L, const void* W, const float* H_in, const float* H_out, co
     if (L.fast_grid) {
         long long tot = nhin * nn, gb = (tot + 255) / 256; if (gb > 32768) gb = 32768;
         hipLaunchKernelGGL(hcat_kernel, dim3((unsigned)gb), dim3(256), 0, st, L.Hi, L.Hcat, n, tot, L.grid_blocked);
-        hipLaunchKernelGGL(tri_half_kernel, dim3((unsigned)gb), dim3(256), 0, st, L.Hi, L.Ht, n, tot);
         TB_KERNEL_CHECK(ctx);
     }
     // U_in, P and U_out are first needed by the first in-channel sweep; the grid search before it needs only W and H_in.
@@ -1085,12 +1073,11 @@ void plan_layer(Layer& L, bool H_out, bool R, Arena& ar) {
     L.T = H_out ? ar.get<double>((size_t)nh * dh * d->block) : nullptr;
     L.cand_s = ar.get<double>(grows * L.ncand); L.cand_z = ar.get<double>(grows * L.ncand); L.cost = ar.get<double>(grows * L.ncand);
     L.Delta = ar.get<double>(grows * L.ncand * L.gsz); L.G = ar.get<double>(grows * L.ncand * L.gsz);
-    L.DeltaS = L.GS = L.costS = L.lim = nullptr; L.sel = nullptr; L.Hcat = nullptr; L.Ht = nullptr;
+    L.DeltaS = L.GS = L.costS = L.lim = nullptr; L.sel = nullptr; L.Hcat = nullptr;
     if (L.fast_grid) {
         L.DeltaS = ar.get<double>(grows * GRID_KS * n); L.GS = ar.get<double>(grows * GRID_KS * n);
         L.costS = ar.get<double>(grows * GRID_KS); L.lim = ar.get<double>(grows); L.sel = ar.get<int>(grows * 3);
         L.Hcat = ar.get<__hip_bfloat16>((size_t)L.nhin * n * (GRID_TERMS * (size_t)n + GRID_PAD));
-        L.Ht = ar.get<double>((size_t)L.nhin * L.nn);
     }
     L.Wbar = ar.get<double>(wn); L.Abar = ar.get<double>(wn); L.Z = ar.get<double>(wn);
     L.WR = R ? ar.get<double>(wn) : nullptr;
