@@ -113,16 +113,16 @@ def cpu_baseline(blk, cfg, hessians, out):
                                                                         t_opair, pairs, t_oseq, cfg.n_seqs)}
 
 
-def roofline_probe(ctx, cfg, torch, tag, zero=False, reps=0, persistent=False):
+def roofline_probe(ctx, cfg, torch, tag, zero=False, reps=0, persistent=False, seqs=8):
     """The command the HBM-traffic counter runs are made with: one plain copy of 1 GiB (a kernel of known traffic, to scale
-    the counters), then ONE launch of the benchmark's dominant kernel in its launch shape, for all KV heads over a chunk of 8
+    the counters), then ONE launch of the benchmark's dominant kernel in its launch shape, for all KV heads over a chunk of `seqs` (8)
     sequences, accumulating into fp32, operands in 16 x 32 blocks at the benchmark's row pitch (random values):
       rv:      R_v[g] += alpha Z_g^T X  -- A = Z^T per KV head [d, 8 L], B = X^T [d, 8 L] shared by the heads, full product;
       hv_syrk: H_in^V[g] += T1_g^T X    -- the same operands, lower tiles only.
     zero: all-zero operands instead of random ones (same launch, same addresses: what the operand values alone do to the
     rate).  reps > 0: that many further launches, timed with events on the context's stream, their median printed."""
     import paper_2602_04929_amd as tb
-    G = 8
+    G = seqs
     K = G * cfg.seq_len
     n, Hkv = cfg.d_model, cfg.n_kv_heads
     g = torch.Generator(device="cuda"); g.manual_seed(1)
@@ -181,6 +181,7 @@ def main():
     ap.add_argument("--probe-tag", default="rv", choices=("rv", "hv_syrk"), help="with --roofline-probe: which launch")
     ap.add_argument("--probe-zero", action="store_true", help="with --roofline-probe: all-zero operands (same launch otherwise)")
     ap.add_argument("--probe-reps", type=int, default=0, help="with --roofline-probe: time this many further launches of the kernel")
+    ap.add_argument("--probe-seqs", type=int, default=8, help="with --roofline-probe: sequences per launch (the contraction is seqs x seq_len deep)")
     ap.add_argument("--probe-persistent", action="store_true", help="with --roofline-probe: the persistent form of the kernel (one resident workgroup per CU)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -201,7 +202,7 @@ def main():
     torch.cuda.set_device(0)
     if args.roofline_probe:
         ctx = tb.Context()
-        roofline_probe(ctx, cfg, torch, args.probe_tag, zero=args.probe_zero, reps=args.probe_reps, persistent=args.probe_persistent)
+        roofline_probe(ctx, cfg, torch, args.probe_tag, zero=args.probe_zero, reps=args.probe_reps, persistent=args.probe_persistent, seqs=args.probe_seqs)
         ctx.close()
         return
     blk = synth.make_block(cfg, seed=0, device="cuda:0")
