@@ -160,6 +160,14 @@ int tboa_swiglu_forward(tboa_ctx* ctx, int64_t n_tokens, int d, int d_ff, int x_
 int tboa_build_hout(tboa_ctx* ctx, int d_in, int n_heads, int rep, int head_dim, const float* H_in, int w_dtype, const void* W,
                     float* H_out);
 
+/* H_out of W_Q,h when the keys are held in a kv_bits-bit cache (Sec. 4.2, the setting with a quantized KV cache): G = K^_g in
+ * the W_Q row of Table 1, K^_g the per-token Min-Max fake-quant of the head vectors k_{g,t} = W_K,g x_t (the quantizer of
+ * tboa_act_fakequant with one scale and zero per token and KV head; levels decided in fp64).  X [n_seqs*seq_len, d_model] and
+ * W_K [n_kv_heads*head_dim, d_model] in desc->x_dtype; Hout_q [n_q_heads, head_dim, head_dim] fp32, the literal sum of
+ * k^ k^^T over all tokens, every query head of a KV group receiving its group's matrix.  kv_bits in 2 .. 8.  Nothing else of
+ * the Hessians changes with it: a caller replaces the Hout_q of tboa_build_hessians by this one. */
+int tboa_build_hout_q_kv_cache(tboa_ctx* ctx, const tboa_attn_desc* desc, const void* X, const void* Wk, int kv_bits, float* Hout_q);
+
 /* Forward pass of the block, for the driver that carries the two activation streams from one transformer block to the next
  * (Sec. 3.2: the deviation that Prop. 3.2 corrects is the one accumulated through the preceding quantized layers):
  * tboa_attention_forward: O[t, h dh + c] = sum_k A_h[t, k] V_g(h)[k, c], A_h = softmax(Q_h K_g^T / sqrt(d_h)) per sequence (the input of

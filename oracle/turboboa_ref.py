@@ -16,7 +16,8 @@ block=1, textbook OBS elimination for the in-channel sweep with R = 0, every ste
 of the sweep with R != 0 as the least-squares problem it solves (explicit X and
 X - X~, no factor of H), Algorithm 1 with R != 0 and per-head Hessians rebuilt from
 those pieces, the explicit quadratic in s for Prop. 3.3, exhaustive evaluation for
-the grid search, hand-computed rows for the activation quantizer.
+the grid search, hand-computed rows for the activation quantizer, a hand-computed
+Gram matrix for the keys of a quantized cache.
 
 parity unpinned:
   * the candidate list of the grid search and the group-wise (row, group)
@@ -167,6 +168,25 @@ def act_fakequant_per_token(X, bits):
     z = np.rint(-lo / s)
     q = np.clip(np.rint(X / s) + z, 0.0, maxq)
     return s * (q - z)
+
+
+def hout_q_kv_cache(X, Wk, n_q_heads, n_kv_heads, head_dim, kv_bits):
+    """H_out of W_Q,h when the keys are held in a kv_bits-bit cache (the KV4 setting of Sec. 4.2):
+    G = K^_g in the W_Q row of Table 1, K^_g the per-token Min-Max fake-quant of the head vectors
+    k_{g,t} = W_K,g x_t (one scale and zero per token and KV head), g = h // (Hq/Hkv).
+    Returns [Hq, dh, dh] = K^_g^T K^_g summed over all tokens."""
+    X = np.asarray(X, F64); Wk = np.asarray(Wk, F64)
+    X2 = X.reshape(-1, X.shape[-1])
+    Hq, Hkv, dh = n_q_heads, n_kv_heads, head_dim
+    rep = Hq // Hkv
+    out = np.zeros((Hq, dh, dh), F64)
+    for g in range(Hkv):
+        K = X2 @ Wk[g*dh:(g+1)*dh].T                      # [T, dh]
+        Kq = act_fakequant_per_token(K, kv_bits)
+        G = Kq.T @ Kq
+        for r in range(rep):
+            out[g * rep + r] = G
+    return out
 
 
 def hadamard_matrix(d):

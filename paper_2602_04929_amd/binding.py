@@ -66,6 +66,7 @@ def _load():
         "tboa_build_hessian_linear": ([vp, i64, i32, i32, f64, vp, vp, vp, vp], i32),
         "tboa_swiglu_forward": ([vp, i64, i32, i32, i32, vp, i32, vp, vp, vp], i32),
         "tboa_build_hout": ([vp, i32, i32, i32, i32, vp, i32, vp, vp], i32),
+        "tboa_build_hout_q_kv_cache": ([vp, C.POINTER(AttnDesc), vp, vp, i32, vp], i32),
         "tboa_attention_forward": ([vp, C.POINTER(AttnDesc), vp, i32, vp, vp, vp, vp], i32),
         "tboa_linear_forward": ([vp, i64, i32, i32, i32, vp, i32, vp, vp, vp], i32),
         "tboa_packed_words_per_row": ([i32, i32], i64),
@@ -316,6 +317,15 @@ class Context:
         _dev(H_in, torch.float32); _dev(W)
         out = torch.empty(n_heads, head_dim, head_dim, dtype=torch.float32, device=W.device)
         self._check(_lib.tboa_build_hout(self._h, H_in.shape[0], n_heads, rep, head_dim, _ptr(H_in), _dtype_code(W), _ptr(W), _ptr(out)))
+        return out
+
+    def build_hout_q_kv_cache(self, X, Wk, n_q_heads, n_kv_heads, head_dim, kv_bits):
+        """H_out of W_Q,h from the keys of a kv_bits-bit cache (fp32 [Hq, dh, dh]); X [S, L, d] and Wk in one type."""
+        _dev(X); _dev(Wk, X.dtype)
+        S, L, d = X.shape
+        desc = AttnDesc(d, n_q_heads, n_kv_heads, head_dim, S, L, _dtype_code(X), 1, 0.0, 0)
+        out = torch.empty(n_q_heads, head_dim, head_dim, dtype=torch.float32, device=X.device)
+        self._check(_lib.tboa_build_hout_q_kv_cache(self._h, C.byref(desc), _ptr(X), _ptr(Wk), kv_bits, _ptr(out)))
         return out
 
     def attention_forward(self, X, Wq, Wk, Wv, n_q_heads, n_kv_heads, head_dim, causal=True):

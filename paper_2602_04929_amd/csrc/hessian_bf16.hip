@@ -640,6 +640,28 @@ __global__ void bcast_heads_kernel(const double* __restrict__ src, float* __rest
     }
 }
 
+// out[row, :] = Min-Max fake-quant of in[row, :] (asymmetric, range extended to contain 0, a flat row takes [-1, 1]), one
+// wavefront per row of n elements, everything in fp64 in the order of operations of the activation quantizer of Sec. 4.2:
+// s = (hi - lo) / maxq, z = round(-lo / s), level = clamp(round(x / s) + z, 0, maxq), out = s (level - z).  In place is fine.
+template <typename TI>
+__global__ __launch_bounds__(256) void row_fakequant_f64_kernel(const TI* __restrict__ in, double* __restrict__ out, long long rows, int n, double maxq) {
+    const int lane = threadIdx.x & 63;
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const TI* x = in + row * n; double* y = out + row * n;
+    double lo = 0.0, hi = 0.0;
+    for (int c = lane; c < n; c += 64) { const double v = (double)x[c]; lo = fmin(lo, v); hi = fmax(hi, v); }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { lo = fmin(lo, __shfl_xor(lo, o, 64)); hi = fmax(hi, __shfl_xor(hi, o, 64)); }
+    if (lo == hi) { lo = -1.0; hi = 1.0; }
+    const double s = (hi - lo) / maxq, z = rint(-lo / s);
+    for (int c = lane; c < n; c += 64) {
+        const double v = (double)x[c];
+        const double q = fmin(fmax(rint(v / s) + z, 0.0), maxq);
+        y[c] = s * (q - z);
+    }
+}
+
 // Row pitches that are multiples of a few KB put every row of a tile into the same memory channel; 256 extra
 // elements per row spread them (measured: +10..20 % on the GEMMs).
 constexpr int PADE = 256;
@@ -1463,6 +1485,51 @@ extern "C" int tboa_build_hout(tboa_ctx* ctx, int d_in, int n_heads, int rep, in
         TB_TRY(gemm_f64(ctx, b));
     }
     return launch_cvt_f64_to_f32(ctx, Ho, H_out, (int64_t)n_heads * hh);
+}
+
+extern "C" int tboa_build_hout_q_kv_cache(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, const void* Wk, int kv_bits, float* Hout_q) {
+    if (!ctx) return TBOA_EINVAL;
+    TB_TRY(check_attn_desc(ctx, d));
+    if (!X || !Wk || !Hout_q) return tboa_fail(ctx, TBOA_EINVAL, "build_hout_q_kv_cache: null argument");
+    if (kv_bits < 2 || kv_bits > 8) return tboa_fail(ctx, TBOA_EINVAL, "build_hout_q_kv_cache: kv_bits=%d not in 2 .. 8", kv_bits);
+    const int dm = d->d_model, Hq = d->n_q_heads, Hkv = d->n_kv_heads, dh = d->head_dim, rep = Hq / Hkv, dkv = Hkv * dh;
+    const long long T = (long long)d->n_seqs * d->seq_len, hh = (long long)dh * dh;
+    const bool bf = d->x_dtype == TBOA_BF16;
+    if (bf && (dm % 8 || dkv % 8)) return tboa_fail(ctx, TBOA_EINVAL, "build_hout_q_kv_cache: d_model and n_kv_heads*head_dim must be multiples of 8 for bf16 inputs");
+    const long long chunk = T < 16384 ? T : 16384;
+    float* K32 = nullptr; double *K64, *Ho, *X64 = nullptr, *W64 = nullptr;
+    for (int pass = 0; pass < 2; ++pass) {
+        Arena ar(pass ? ctx->ws : nullptr);
+        K64 = ar.get<double>((size_t)chunk * dkv); Ho = ar.get<double>((size_t)Hkv * hh);
+        if (bf) K32 = ar.get<float>((size_t)chunk * dkv);
+        else { X64 = ar.get<double>((size_t)chunk * dm); W64 = ar.get<double>((size_t)dkv * dm); }
+        if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
+    }
+    const double maxq = (double)((1 << kv_bits) - 1);
+    if (!bf) TB_TRY(launch_cvt_to_f64(ctx, Wk, TBOA_F32, W64, (int64_t)dkv * dm));
+    for (long long t0 = 0; t0 < T; t0 += chunk) {
+        const int rows = (int)((T - t0 < chunk) ? T - t0 : chunk);
+        const long long qrows = (long long)rows * Hkv;
+        if (bf) {       // keys of the chunk: exact products of the bf16 inputs, fp32 accumulation
+            TB_TRY(gemm_bf16_nt(ctx, nt(rows, dkv, dm, 1.f, (const bf16*)X + t0 * dm, dm, (const bf16*)Wk, dm, K32, dkv, TBOA_F32, 0, 0)));
+            hipLaunchKernelGGL(row_fakequant_f64_kernel<float>, dim3((unsigned)((qrows + 3) / 4)), dim3(256), 0, ctx->stream, K32, K64, qrows, dh, maxq);
+        } else {
+            TB_TRY(launch_cvt_to_f64(ctx, (const float*)X + t0 * dm, TBOA_F32, X64, (int64_t)rows * dm));
+            GemmF64 k{};
+            k.M = rows; k.N = dkv; k.K = dm; k.alpha = 1.0; k.beta = 0.0; k.A = X64; k.sam = dm; k.sak = 1; k.B = W64; k.sbk = 1; k.sbn = dm;
+            k.C = K64; k.ldc = dkv; k.batch = 1;
+            TB_TRY(gemm_f64(ctx, k));
+            hipLaunchKernelGGL(row_fakequant_f64_kernel<double>, dim3((unsigned)((qrows + 3) / 4)), dim3(256), 0, ctx->stream, K64, K64, qrows, dh, maxq);
+        }
+        TB_KERNEL_CHECK(ctx);
+        GemmF64 c{};    // per KV head: Ho[g] += K^_g^T K^_g over the tokens of the chunk
+        c.M = dh; c.N = dh; c.K = rows; c.alpha = 1.0; c.beta = t0 ? 1.0 : 0.0; c.A = K64; c.sam = 1; c.sak = dkv; c.B = K64; c.sbk = dkv; c.sbn = 1;
+        c.C = Ho; c.ldc = dh; c.batch = Hkv; c.strideA = dh; c.strideB = dh; c.strideC = hh;
+        TB_TRY(gemm_f64(ctx, c));
+    }
+    hipLaunchKernelGGL(bcast_heads_kernel, dim3(g1(Hq * hh)), dim3(256), 0, ctx->stream, Ho, Hout_q, rep, hh, Hq * hh);
+    TB_KERNEL_CHECK(ctx);
+    return 0;
 }
 
 extern "C" int tboa_attention_forward(tboa_ctx* ctx, const tboa_attn_desc* d, const void* X, int w_dtype, const void* Wq, const void* Wk,

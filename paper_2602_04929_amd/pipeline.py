@@ -52,7 +52,7 @@ def _split_stacked(res, rows_q, heads_q):
 
 
 def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=True, cd_iters=1, adaptive_grid=True,
-                             damp=0.01, seq_chunk=0, timings=None, side_contexts=None, stack_qk=True, hout_k_from_quantized_q=False):
+                             damp=0.01, seq_chunk=0, timings=None, side_contexts=None, stack_qk=True, hout_k_from_quantized_q=False, kv_bits=0):
     """(rotation, activation fake-quant ->) Hessians -> W_Q, W_K, W_V -> output-projection Hessian -> W_O.
 
     blk: dict from synth.make_block (device tensors); cfg: synth.BlockConfig.  Returns dict of per-layer results
@@ -64,7 +64,9 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     over their heads).
     hout_k_from_quantized_q: the other reading of Algorithm 1 line 4 (Hessians formed inside the loop over the layers): W_Q is
     quantized first and H_out of W_K is sum_h Q_h^T Q_h with Q_h from the DEQUANTIZED W_Q (tboa_build_hout); W_Q and W_K then go
-    through tboa_quantize_layer one after the other (no stacking, no side contexts for them)."""
+    through tboa_quantize_layer one after the other (no stacking, no side contexts for them).
+    kv_bits > 0: the keys are held in a kv_bits-bit cache (Sec. 4.2): H_out of W_Q is built from the fake-quantized keys
+    (tboa_build_hout_q_kv_cache)."""
     Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     X_fp = blk["X_fp"]
     X = blk["X"]
@@ -91,6 +93,8 @@ def quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=True, with_R_v=Tru
     kw = dict(bits=cfg.bits, block=cfg.block, group=cfg.group, cd_iters=cd_iters, adaptive_grid=adaptive_grid, damp=damp)
     out = {"X": X, "X_fp": X_fp}
     Hs = stage("build_hessians", lambda: ctx.build_hessians(*hargs, **hkw))
+    if kv_bits:
+        Hs["Hout_q"] = stage("build_hout_q_kv_cache", lambda: ctx.build_hout_q_kv_cache(X, blk["Wk"], Hq, Hkv, dh, kv_bits))
     if hout_k_from_quantized_q:
         stack_qk = False
         out["q"] = stage("quantize_q", lambda: ctx.quantize_layer(blk["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq, **kw))

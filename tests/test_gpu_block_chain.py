@@ -150,3 +150,37 @@ def test_two_tiny_blocks_in_a_row(lib):
     dev0 = float((X.double() - Xf.double()).norm() / Xf.double().norm()); dev1 = float((res[0]["X_out"].double() - res[0]["X_fp_out"].double()).norm() / res[0]["X_fp_out"].double().norm())
     print("relative deviation of the two streams: %.3f entering block 1, %.3f entering block 2" % (dev0, dev1), flush=True)
     ctx.close()
+
+
+@pytest.mark.parametrize("name,kv_bits", [("tiny", 4), ("tiny", 2), ("llama2-7b", 4)])
+def test_hout_q_from_a_quantized_kv_cache(ctx, name, kv_bits):
+    """tboa_build_hout_q_kv_cache against the oracle: H_out of W_Q from per-token fake-quantized keys (Sec. 4.2, KV cache).
+    The levels are decided on fp64 keys by the oracle and on keys accumulated in fp32 (bf16 inputs) or fp64 (fp32 inputs) by
+    the library, so single levels can differ at ties: the sums over all tokens agree to 1e-5 (fp32 inputs: 1e-6)."""
+    cfg = synth.scaled(synth.CONFIGS[name], d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=3, seq_len=200, n_outlier=2)
+    b = synth.make_block(cfg, seed=6, device="cuda")
+    got = f64(ctx.build_hout_q_kv_cache(b["X"], b["Wk"], 4, 2, 32, kv_bits))
+    want = O.hout_q_kv_cache(f64(b["X"]), f64(b["Wk"]), 4, 2, 32, kv_bits)
+    plain = O.build_hessians(f64(b["X"]), None, f64(b["Wq"]), f64(b["Wk"]), f64(b["Wv"]), f64(b["Wo"]), 4, 2, 32)["Hout_q"]
+    err = np.abs(got - want).max() / np.abs(want).max()
+    print("H_out^Q from a %d-bit key cache (%s inputs): max |err| / max |entry| = %.2e" % (kv_bits, name, err), flush=True)
+    assert got.shape == (4, 32, 32) and err <= (1e-6 if name == "tiny" else 1e-5)
+    assert np.array_equal(got[0], got[1]) and np.array_equal(got[2], got[3]) and not np.array_equal(got[0], got[2])
+    assert np.abs(want[0] - plain[0]).max() > 1e-3 * np.abs(want).max(), "the cache should matter at this width"
+
+
+def test_tiny_block_with_kv_cache_end_to_end(ctx):
+    """The tiny configuration with H_out of W_Q from a 4-bit key cache, end to end against the oracle."""
+    from paper_2602_04929_amd.pipeline import quantize_attention_block
+    cfg = synth.CONFIGS["tiny"]
+    blk = synth.make_block(cfg, seed=0, device="cuda")
+    got = quantize_attention_block(ctx, blk, cfg, use_R=True, stack_qk=False, kv_bits=4)
+    torch.cuda.synchronize()
+    X, Xf = f64(blk["X"]), f64(blk["X_fp"])
+    W = {k: f64(blk[k]) for k in ("Wq", "Wk", "Wv", "Wo")}
+    Hq, Hkv, dh = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    Hs = O.build_hessians(X, Xf, W["Wq"], W["Wk"], W["Wv"], W["Wo"], Hq, Hkv, dh, alpha=0.25)
+    Hs["Hout_q"] = O.hout_q_kv_cache(X, W["Wk"], Hq, Hkv, dh, 4)
+    want = O.quantize_layer(W["Wq"], Hs["Hin_qk"], Hs["Hout_q"], Hs["R_qk"], Hq, bits=cfg.bits, block=cfg.block, group=cfg.group)
+    frac = compare_layer(got["q"], want, label="W_Q with a 4-bit key cache")
+    print("tiny, 4-bit key cache, W_Q: codes identical %.4f%%" % (100 * frac), flush=True)

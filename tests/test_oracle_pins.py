@@ -837,3 +837,26 @@ def test_hout_k_closed_form_and_from_other_query_weights(small_block):
             assert np.allclose(Hs["Hout_k"][g], want, rtol=1e-10)
     assert np.array_equal(Hs2["Hin_qk"], b["Hs"]["Hin_qk"]) and np.array_equal(Hs2["Hout_q"], b["Hs"]["Hout_q"])
     assert not np.allclose(Hs2["Hout_k"], b["Hs"]["Hout_k"], rtol=1e-3)
+
+
+def test_hout_q_kv_cache_hand_computed():
+    """H_out of W_Q from the keys of a 2-bit cache (Sec. 4.2, KV setting), rows worked out by hand: with W_K = I the keys
+    are the tokens.  [0, 3]: range [0, 3], step 1, zero 0 -> stays.  [-1, 2]: range [-1, 2], step 1, zero 1 -> stays.
+    [0.5, 2]: range [0, 2], step 2/3, zero 0, levels round(0.75) = 1 and 3 -> [2/3, 2].  Gram of the three rows."""
+    X = np.array([[[0.0, 3.0], [-1.0, 2.0], [0.5, 2.0]]])
+    H = O.hout_q_kv_cache(X, np.eye(2), 1, 1, 2, kv_bits=2)
+    want = np.array([[0.0 + 1.0 + 4.0 / 9.0, 0.0 - 2.0 + 4.0 / 3.0], [0.0 - 2.0 + 4.0 / 3.0, 9.0 + 4.0 + 4.0]])
+    np.testing.assert_allclose(H[0], want, rtol=1e-14)
+    # two query heads on one KV head read the same cache; a second KV head is quantized on its own (its own range per token)
+    Wk = np.array([[1.0, 0.0], [0.0, 1.0], [2.0, 0.0], [0.0, -1.0]])          # head 0: identity; head 1: (2 x0, -x1)
+    H2 = O.hout_q_kv_cache(X, Wk, 4, 2, 2, kv_bits=2)
+    np.testing.assert_allclose(H2[0], want, rtol=1e-14); np.testing.assert_allclose(H2[1], want, rtol=1e-14)
+    # head 1 keys: [0, -3] -> stays; [-2, -2] -> range [-2, 0], step 2/3, zero 3 -> stays; [1, -2] -> range [-2, 1], step 1, zero 2 -> stays
+    K1 = np.array([[0.0, -3.0], [-2.0, -2.0], [1.0, -2.0]])
+    np.testing.assert_allclose(H2[2], K1.T @ K1, rtol=1e-14); np.testing.assert_allclose(H2[3], K1.T @ K1, rtol=1e-14)
+    # keys that already lie on the grid of an 8-bit cache are kept, and the result is then the W_Q row of Table 1
+    rng = np.random.default_rng(5)
+    Xi = rng.integers(-100, 100, size=(2, 6, 4)).astype(np.float64)
+    Xi[:, :, 0] = -100.0; Xi[:, :, 1] = 155.0          # every token spans exactly 255 steps of 1
+    Hs = O.build_hessians(Xi, None, np.eye(4), np.eye(4), np.eye(4), np.eye(4), 1, 1, 4)
+    np.testing.assert_allclose(O.hout_q_kv_cache(Xi, np.eye(4), 1, 1, 4, kv_bits=8)[0], Hs["Hout_q"][0], rtol=1e-13)
