@@ -950,6 +950,9 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     // ---- H_in (and R) of W_V
     if (!Hin_v) return 0;
     TB_TRY(fits_half(ctx, X, rv ? X_fp : nullptr, (long long)T * dm, &D.f16));
+    // the Gram sums of the probabilities reach rep L where every query attends to one token (entry (i, i) of sum_h A_h^T A_h
+    // is at most the number of (head, query) pairs): beyond the range of half they are carried as bf16 pairs
+    if ((long long)rep * L >= 60000) D.f16 = 0;
     const int hf = D.f16 ? TBOA_GEMM_F16 : 0;
     TB_TRY(launch_fill_f32(ctx, Hin_v, (int64_t)Hkv * dd, 0.f));
     if (rv) TB_TRY(launch_fill_f32(ctx, R_v, (int64_t)Hkv * dd, 0.f));

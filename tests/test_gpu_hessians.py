@@ -69,16 +69,19 @@ def test_bf16_path_small(ctx, causal, hq, hkv):
     assert torch.equal(got["Hin_v"], got["Hin_v"].transpose(1, 2))
 
 
-@pytest.mark.parametrize("hq,hkv,d,L,S,with_fp", [(2, 2, 256, 256, 4, True), (8, 2, 256, 512, 3, True), (4, 1, 512, 256, 5, False)])
-def test_bf16_summed_form(ctx, hq, hkv, d, L, S, with_fp):
+@pytest.mark.parametrize("hq,hkv,d,L,S,with_fp,dh", [(2, 2, 256, 256, 4, True, 32), (8, 2, 256, 512, 3, True, 32), (4, 1, 512, 256, 5, False, 32),
+                                                     (16, 8, 256, 256, 2, True, 32), (2, 1, 256, 512, 2, True, 128), (8, 8, 512, 256, 2, False, 64),
+                                                     (3, 3, 256, 768, 2, True, 96)])
+def test_bf16_summed_form(ctx, hq, hkv, d, L, S, with_fp, dh):
     """Whole 256-tiles: the W_V Hessian takes the form that sums the heads of a KV group on L x L Gram matrices of the
     transposed probabilities, every intermediate an exact-to-twice-the-mantissa (hi, lo) pair: fp32-grade results (1, 2 and 4
-    query heads per KV head; several sequence chunks with a ragged last one; with and without the deviation term)."""
-    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=d, n_q_heads=hq, n_kv_heads=hkv, head_dim=32, n_seqs=S, seq_len=L, n_outlier=3)
+    query heads per KV head; several sequence chunks with a ragged last one; with and without the deviation term; every head
+    width the fused scores + softmax kernel is built for; eight KV heads, which that kernel deals to the XCDs group by group)."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=d, n_q_heads=hq, n_kv_heads=hkv, head_dim=dh, n_seqs=S, seq_len=L, n_outlier=3)
     b = synth.make_block(cfg, seed=7, device="cuda")
     Xf = b["X_fp"] if with_fp else None
-    got = ctx.build_hessians(b["X"], Xf, b["Wq"], b["Wk"], b["Wv"], b["Wo"], hq, hkv, 32, alpha=0.25, seq_chunk=2)
-    want = O.build_hessians(np64(b["X"]), np64(Xf) if with_fp else None, np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), hq, hkv, 32,
+    got = ctx.build_hessians(b["X"], Xf, b["Wq"], b["Wk"], b["Wv"], b["Wo"], hq, hkv, dh, alpha=0.25, seq_chunk=2)
+    want = O.build_hessians(np64(b["X"]), np64(Xf) if with_fp else None, np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), hq, hkv, dh,
                             alpha=0.25)
     # R_v is measured against its own largest entry and is noise-like on these inputs (X - X~ is independent of X), so the
     # 11 significant bits of the half-precision X - X~ show in it undiminished
@@ -134,20 +137,22 @@ def test_out_proj_fp32(ctx):
     assert rel_err(np64(Hin_o), wH) <= 1e-6 and rel_err(np64(R_o), wR) <= 1e-6
 
 
-def test_out_proj_bf16(ctx):
-    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=264, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=3, seq_len=320, n_outlier=3)
+@pytest.mark.parametrize("d,L,dh", [(264, 320, 32), (256, 512, 64), (256, 256, 128)])
+def test_out_proj_bf16(ctx, d, L, dh):
+    """L = 320: scores stored, softmax kernel; L a multiple of 256: probabilities from the fused scores + softmax kernel."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=d, n_q_heads=4, n_kv_heads=2, head_dim=dh, n_seqs=3, seq_len=L, n_outlier=3)
     b = synth.make_block(cfg, seed=4, device="cuda")
     g = torch.Generator(device="cuda"); g.manual_seed(1)
     deq = [w.float() * (1 + 0.05 * torch.randn(w.shape, generator=g, device="cuda")) for w in (b["Wq"], b["Wk"], b["Wv"])]
-    Hin_o, R_o = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, b["Wq"], b["Wk"], b["Wv"], 4, 2, 32, alpha=0.25, seq_chunk=2)
+    Hin_o, R_o = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, b["Wq"], b["Wk"], b["Wv"], 4, 2, dh, alpha=0.25, seq_chunk=2)
     wH, wR = O.build_hessian_out_proj(np64(b["X"]), np64(b["X_fp"]), *[np64(w) for w in deq], np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]),
-                                      4, 2, 32, alpha=0.25)
+                                      4, 2, dh, alpha=0.25)
     eH, eR = rel_err(np64(Hin_o), wH), rel_err(np64(R_o), wR)
     print("Hin_o %.2e R_o %.2e" % (eH, eR), flush=True)
     # probabilities, values and attention outputs are (hi, lo) pairs; the deviations are single half-precision values, and R_o
     # (noise-like here: measured against its own largest entry) shows their 11 bits
     assert eH <= 3e-5 and eR <= 1e-3
-    H2, R2 = ctx.build_hessian_out_proj(b["X"], None, *deq, None, None, None, 4, 2, 32, seq_chunk=3)
+    H2, R2 = ctx.build_hessian_out_proj(b["X"], None, *deq, None, None, None, 4, 2, dh, seq_chunk=3)
     assert R2 is None and rel_err(np64(H2), wH) <= 3e-5
 
 
