@@ -353,7 +353,7 @@ __global__ void grid_argmin_sel_kernel(const double* __restrict__ costS, const d
 __global__ void clear_words_kernel(int* p, int n) { if ((int)threadIdx.x < n) p[threadIdx.x] = 0; }
 
 // ------------------------------------------------------------------------------------------------ Algorithm 3
-constexpr int SWEEP_SP = 256;      // columns whose updates of the columns further right are applied in one product
+constexpr int SWEEP_SP = 512;      // columns whose updates of the columns further right are applied in one product
 struct SweepArgs {
     double* Wk; int n; int nbr; BlockMap map;
     const double* U; const double* P; int per_head;   // U, P: [n, n] or [n_heads, n, n]
