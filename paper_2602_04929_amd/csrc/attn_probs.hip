@@ -39,10 +39,13 @@ __device__ __forceinline__ float dec16(bf16 b, int f16) {
 }
 
 constexpr int BT = 128;        // queries per workgroup
-constexpr int EXP = BT + 8;    // floats per row of the exchange buffer: the two lane halves of a wavefront write rows 4 apart
+// floats per row of the exchange buffer.  Transposed result: the two lane halves of a wavefront write rows 4 apart (4 x 136 = 32 banks
+// apart) and the store phase reads 16-byte pieces of a row; row-major result: the store phase reads columns, eight lanes taking rows 8
+// apart (8 x 137 = 8 banks apart), the other lanes consecutive queries
+template <bool ROWS> constexpr int exch_pitch() { return ROWS ? BT + 9 : BT + 8; }
 
 template <int DH>
-constexpr int attn_lds_bytes() { return 4 * 64 * 2 * DH + 2 * 64 * EXP * 4 + 2 * 2 * 2 * BT * 4 + 2 * 2 * BT * 4; }
+constexpr int attn_lds_bytes() { return 4 * 64 * 2 * DH + 2 * 64 * (BT + 9) * 4 + 2 * 2 * 2 * BT * 4 + 2 * 2 * BT * 4; }
 
 // one 1 KB block global -> LDS: lane l moves the 16 bytes at base + voff (voff = 16 l) to lds_addr + 16 l
 __device__ __forceinline__ void lds_direct_16(unsigned voff, const char* base, unsigned lds_addr) {
@@ -61,6 +64,7 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
     constexpr int SEGB = 64 * 2 * DH;            // bytes of one (path, segment) image: [NCB][64 keys][32 elements], pieces swizzled
     constexpr int KB = 3 * DH / 32;              // 16 x 32 blocks per block row of Q^ / K^
     constexpr int NBLK = 2 * 2 * NCB * 4;        // 1 KB blocks of a tile, both paths
+    constexpr int EXP = exch_pitch<ROWS>();
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     unsigned char* kt = smem;                                // [path][k_hi, k_lo][NCB][64 keys][64 bytes]
     float* ex = (float*)(smem + 4 * SEGB);                   // [path][64 keys][EXP]: probabilities of the tile
@@ -227,25 +231,21 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
             if (it + 1 < live) issue(64 * (it + 1));
         }
         if constexpr (ROWS) {
-            // row-major result P[h][t][.] = [A_hi | A_lo | A_hi | A - A~] (segments of L columns): thread = (query, 16 consecutive keys)
-            const int tq2 = threadIdx.x & (BT - 1), ic = threadIdx.x >> 7;
-            float a[16], d[16];
+            // row-major result P[h][t][.] = [A_hi | A_lo | A_hi | A - A~] (segments of L columns): eight consecutive lanes take the 64
+            // keys of one query, 8 each, so that a wavefront store covers eight whole 128-byte rows; two queries per thread
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                a[e] = (it < live) ? ex[(16 * ic + e) * EXP + tq2] : 0.f;
-                d[e] = (it < live && two) ? a[e] - ex[(64 + 16 * ic + e) * EXP + tq2] : 0.f;
-            }
-            bf16* prow = out.hi + h * group_stride + (long long)(t0 + tq2) * ldp + i0 + 16 * ic;
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
+            for (int half = 0; half < 2; ++half) {
+                const int slot = threadIdx.x + 512 * half, i8 = slot & 7, tq2 = slot >> 3;
                 union { bf16 b[8]; uint4 u; } hi, lo, dd;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    hi.b[k] = enc16(a[8 * q + k], f16); lo.b[k] = enc16(a[8 * q + k] - dec16(hi.b[k], f16), f16);
-                    dd.b[k] = enc16(d[8 * q + k], f16);
+                for (int e = 0; e < 8; ++e) {
+                    const float a = (it < live) ? ex[(8 * i8 + e) * EXP + tq2] : 0.f;
+                    const float d = (it < live && two) ? a - ex[(64 + 8 * i8 + e) * EXP + tq2] : 0.f;
+                    hi.b[e] = enc16(a, f16); lo.b[e] = enc16(a - dec16(hi.b[e], f16), f16); dd.b[e] = enc16(d, f16);
                 }
-                *(uint4*)(prow + 8 * q) = hi.u; *(uint4*)(prow + L + 8 * q) = lo.u; *(uint4*)(prow + 2LL * L + 8 * q) = hi.u;
-                if (two) *(uint4*)(prow + 3LL * L + 8 * q) = dd.u;
+                bf16* prow = out.hi + h * group_stride + (long long)(t0 + tq2) * ldp + i0 + 8 * i8;
+                *(uint4*)prow = hi.u; *(uint4*)(prow + L) = lo.u; *(uint4*)(prow + 2LL * L) = hi.u;
+                if (two) *(uint4*)(prow + 3LL * L) = dd.u;
             }
         } else {
         float a[16], d[16];
