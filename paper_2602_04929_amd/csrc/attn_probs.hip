@@ -205,7 +205,6 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
     // ---- pass 2: probabilities, exchanged through LDS, written transposed
     bf16* dst[4] = {out.hi + g * group_stride, out.lo ? out.lo + g * group_stride : nullptr, out.dhi ? out.dhi + g * group_stride : nullptr,
                     out.dlo ? out.dlo + g * group_stride : nullptr};
-    const int ri = threadIdx.x >> 3, tc = (threadIdx.x & 7) * 16;      // store phase: key row of the tile, 16 consecutive queries
     issue(0);
     landed();
     for (int it = 0; it < tiles; ++it) {
@@ -248,33 +247,30 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
                 if (two) *(uint4*)(prow + 3LL * L) = dd.u;
             }
         } else {
-        float a[16], d[16];
-        if (it < live) {
+            // transposed blocked result: sixteen consecutive lanes take the 128 queries of one key row, 8 each (one 16-byte piece per
+            // output), so that a wavefront store covers four key rows of four blocks, 256 contiguous bytes in each; two rows per thread
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f4 v = *(const f4*)(ex + ri * EXP + tc + 4 * q);
-                f4 w = {0.f, 0.f, 0.f, 0.f};
-                if (two) w = *(const f4*)(ex + (64 + ri) * EXP + tc + 4 * q);
+            for (int half = 0; half < 2; ++half) {
+                const int slot = threadIdx.x + 512 * half, t8 = slot & 15, ri = slot >> 4;
+                union { bf16 b[8]; uint4 u; } hi, lo, dh, dl;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { a[4 * q + e] = v[e]; d[4 * q + e] = v[e] - w[e]; }
+                for (int q = 0; q < 2; ++q) {
+                    f4 v = {0.f, 0.f, 0.f, 0.f}, w = {0.f, 0.f, 0.f, 0.f};
+                    if (it < live) {
+                        v = *(const f4*)(ex + ri * EXP + 8 * t8 + 4 * q);
+                        if (two) w = *(const f4*)(ex + (64 + ri) * EXP + 8 * t8 + 4 * q);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float a = v[e], d = v[e] - w[e];
+                        hi.b[4 * q + e] = enc16(a, f16); lo.b[4 * q + e] = enc16(a - dec16(hi.b[4 * q + e], f16), f16);
+                        dh.b[4 * q + e] = enc16(d, f16); dl.b[4 * q + e] = enc16(d - dec16(dh.b[4 * q + e], f16), f16);
+                    }
+                }
+                const long long o = tboa_blocked_offset(i0 + ri, (long long)r * L + t0 + 8 * t8, ldp >> 5);
+                *(uint4*)(dst[0] + o) = hi.u; *(uint4*)(dst[1] + o) = lo.u;
+                if (two) { *(uint4*)(dst[2] + o) = dh.u; *(uint4*)(dst[3] + o) = dl.u; }
             }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) { a[e] = 0.f; d[e] = 0.f; }
-        }
-        const long long col = (long long)r * L + t0 + tc;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            union { bf16 b[8]; uint4 u; } hi, lo, dh, dl;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                hi.b[k] = enc16(a[8 * q + k], f16); lo.b[k] = enc16(a[8 * q + k] - dec16(hi.b[k], f16), f16);
-                dh.b[k] = enc16(d[8 * q + k], f16); dl.b[k] = enc16(d[8 * q + k] - dec16(dh.b[k], f16), f16);
-            }
-            const long long o = tboa_blocked_offset(i0 + ri, col + 8 * q, ldp >> 5);
-            *(uint4*)(dst[0] + o) = hi.u; *(uint4*)(dst[1] + o) = lo.u;
-            if (two) { *(uint4*)(dst[2] + o) = dh.u; *(uint4*)(dst[3] + o) = dl.u; }
-        }
         }
         if (it < live) landed();                           // next tile in LDS; the exchange buffer is free again
     }
