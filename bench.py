@@ -185,7 +185,7 @@ def main():
     ap.add_argument("--probe-persistent", action="store_true", help="with --roofline-probe: the persistent form of the kernel (one resident workgroup per CU)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (heads would shard across GPUs, see DESIGN.md); use --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (heads would shard across GPUs; that is not built); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
