@@ -20,9 +20,12 @@ the grid search, hand-computed rows for the activation quantizer, a hand-compute
 Gram matrix for the keys of a quantized cache.
 
 parity unpinned:
-  * the candidate list of the grid search and the group-wise (row, group)
-    extension are readings of ours, the paper gives only the objective; they are
-    checked against exhaustive loops over the same list only.
+  * the candidate list of the grid search (ranges, number and spacing of the
+    candidates) is a reading of ours, the paper gives only the objective; the search
+    over that list is checked against an exhaustive loop.
+The group-wise (row, group) extension is ours as well; it is checked against the
+per-row algorithm it extends (Hessians that couple no two groups) and against a
+step-wise least-squares sweep with exhaustive grids at group entry.
 """
 from __future__ import annotations
 

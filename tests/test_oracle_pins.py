@@ -860,3 +860,70 @@ def test_hout_q_kv_cache_hand_computed():
     Xi[:, :, 0] = -100.0; Xi[:, :, 1] = 155.0          # every token spans exactly 255 steps of 1
     Hs = O.build_hessians(Xi, None, np.eye(4), np.eye(4), np.eye(4), np.eye(4), 1, 1, 4)
     np.testing.assert_allclose(O.hout_q_kv_cache(Xi, np.eye(4), 1, 1, 4, kv_bits=8)[0], Hs["Hout_q"][0], rtol=1e-13)
+
+
+@pytest.mark.parametrize("with_R", [False, True])
+def test_groupwise_layer_with_block_diagonal_hin_is_the_per_row_layer_on_every_group(with_R):
+    """The (row, group) extension against the per-row algorithm it extends.  When H_in (and R) couple no two groups of
+    in-channels, nothing of Algorithm 1 crosses a group boundary: U and P are block diagonal, so the sweep inside one group
+    leaves the others alone; the grid of a group, searched when the sweep enters it, sees the columns as the step found
+    them; the compensation of the remaining rows acts column by column; the refinement's objective is a sum over the
+    groups.  The group-wise layer is then the per-row layer run on each group's columns by itself."""
+    r = rng(91)
+    n_heads, dh, g, ng, T = 2, 8, 8, 3, 64
+    n = g * ng
+    W = r.standard_normal((n_heads * dh, n)) * 0.02
+    Hin = np.zeros((n, n)); R = np.zeros((n, n))
+    for gi in range(ng):
+        Xg = r.standard_normal((T, g)); Xg[:, 1] *= 4
+        Hin[gi*g:(gi+1)*g, gi*g:(gi+1)*g] = Xg.T @ Xg
+        R[gi*g:(gi+1)*g, gi*g:(gi+1)*g] = 0.25 * (0.1 * r.standard_normal((T, g))).T @ Xg
+    G = [r.standard_normal((T, dh)) + 0.7 * r.standard_normal((T, 1)) for _ in range(n_heads)]
+    Hout = np.stack([x.T @ x for x in G])
+    Rq = R if with_R else None
+    kw = dict(bits=3, block=4, damp=0.0)
+    whole = O.quantize_layer(W, Hin, Hout, Rq, n_heads, group=g, **kw)
+    loss = 0.0
+    for gi in range(ng):
+        sl = slice(gi * g, (gi + 1) * g)
+        part = O.quantize_layer(W[:, sl], Hin[sl, sl], Hout, None if Rq is None else R[sl, sl], n_heads, **kw)
+        assert np.array_equal(whole["codes"][:, sl], part["codes"]), gi
+        np.testing.assert_allclose(whole["scales"][:, gi], part["scales"][:, 0], rtol=1e-9)
+        assert np.array_equal(whole["zeros"][:, gi], part["zeros"][:, 0])
+        np.testing.assert_allclose(whole["W_deq"][:, sl], part["W_deq"], rtol=1e-9, atol=1e-15)
+        loss += part["loss"]
+    np.testing.assert_allclose(whole["loss"], loss, rtol=1e-9)
+
+
+def test_groupwise_sweep_against_stepwise_least_squares_with_grids_at_group_entry():
+    """The in-channel sweep with (row, group) grids on coupled channels, re-derived without its factors: every step as the
+    least-squares problem it solves (explicit X and X - X~), and on entering a group of columns the row's grid for that group
+    from an exhaustive loop over the candidates on the columns as they stand THEN (the earlier groups' steps have moved
+    them), with that group's block of H_in."""
+    n, r_, L, g = 12, 4, 48, 4
+    r = rng(67)
+    X = r.standard_normal((n, L)); X[5] *= 3.0
+    X[6:] += 0.6 * X[:6]                                      # couples the groups
+    dX = 0.3 * r.standard_normal((n, L)) + 0.2 * X
+    H, R = X @ X.T, dX @ X.T
+    U = O.chol_inv_upper(H); P = O.sweep_P(R, U)
+    Wr = r.standard_normal((r_, n))
+    for bits in (2, 3):
+        maxq = 2 ** bits - 1
+        s = np.zeros((r_, n // g)); z = np.zeros((r_, n // g))
+        Q, codes = O.gptaq_sweep(Wr, U, P, s, z, bits, group=g, H_in=H, adaptive=True)
+        moved = 0
+        for i in range(r_):
+            w = Wr[i].copy()
+            for j in range(n):
+                if j % g == 0:
+                    G = slice(j, j + g)
+                    _, sj, zj = exhaustive_grid(w[G], H[G, G], bits)
+                    assert np.isclose(s[i, j // g], sj, rtol=1e-12) and z[i, j // g] == zj, (bits, i, j)
+                    moved += int(j > 0 and not np.allclose(w[G], Wr[i, G]))
+                wj = w[j]
+                q = min(max(np.rint(wj / sj) + zj, 0.0), maxq)
+                assert codes[i, j] == q and np.isclose(Q[i, j], sj * (q - zj), rtol=1e-12)
+                if j + 1 < n:
+                    w[j + 1:] += np.linalg.lstsq(X[j + 1:].T, -((sj * (q - zj) - wj) * X[j] + wj * dX[j]), rcond=None)[0]
+        assert moved > 0          # later groups were searched on columns that the sweep had already changed
