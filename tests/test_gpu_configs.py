@@ -165,20 +165,39 @@ def test_llama2_13b_shape_groupwise_int3(lib):
         release(c)
 
 
-def test_llama2_70b_shape_grouped_query(lib):
-    """64 query heads on 8 KV heads, N = 64, d = 8192: a head of W_Q (H_out of its KV group), a head of W_K (H_out summed over
-    the 8 query heads of its group), a head of W_V (H_in, R and H_out summed over the group), rows of W_O."""
+@pytest.fixture(scope="module")
+def c70(lib):
+    """The 70B-shaped block with its Hessians, shared by the tests below (each of them is a minute of fp64 work on the host:
+    kept apart so that the run reports progress between them)."""
     c = build(lib, "llama2-70b")
-    try:
-        check_qk_entries(c, 12)
-        check_group_entries(c, 5, 13)
-        quantize_block(c)
-        check_head(c, "q", 43)
-        check_head(c, "k", 5)
-        check_head(c, "v", 5)
-        check_out_proj_rows(c, 24, 23)
-    finally:
-        release(c)
+    yield c
+    release(c)
+
+
+def test_llama2_70b_shape_hessian_entries(c70):
+    """64 query heads on 8 KV heads, d = 8192: sampled entries of H_in / R of W_Q, W_K and of one KV group's H_out (W_Q: of its
+    KV group; W_K: summed over the 8 query heads of the group) and H_in, R of W_V (summed over the group)."""
+    check_qk_entries(c70, 12)
+    check_group_entries(c70, 5, 13)
+
+
+def test_llama2_70b_shape_quantize_block(c70):
+    quantize_block(c70)
+
+
+@pytest.mark.parametrize("layer,h", [("q", 43), ("k", 5), ("v", 5)])
+def test_llama2_70b_shape_grouped_query_head(c70, layer, h):
+    """N = 64: a head of W_Q (H_out of its KV group), a head of W_K (H_out summed over the 8 query heads of its group), a head
+    of W_V (H_in, R and H_out summed over the group)."""
+    if "out" not in c70:
+        quantize_block(c70)
+    check_head(c70, layer, h)
+
+
+def test_llama2_70b_shape_out_proj_rows(c70):
+    if "out" not in c70:
+        quantize_block(c70)
+    check_out_proj_rows(c70, 24, 23)
 
 
 def test_llama2_7b_w4a4_shape(lib):
