@@ -205,6 +205,8 @@ def main():
         roofline_probe(ctx, cfg, torch, args.probe_tag, zero=args.probe_zero, reps=args.probe_reps, persistent=args.probe_persistent, seqs=args.probe_seqs)
         ctx.close()
         return
+    note = lambda msg: print("bench.py: " + msg, file=sys.stderr, flush=True)      # progress on stderr; stdout carries the one JSON line
+    note("building the %s block" % cfg.name)
     blk = synth.make_block(cfg, seed=0, device="cuda:0")
     if args.correlated:
         synth.apply_mix(blk, synth.correlated_mix(cfg.d_model, seed=0, device="cuda:0"))
@@ -216,9 +218,11 @@ def main():
     def step(timings=None):
         return quantize_attention_block(ctx, blk, cfg, alpha=0.25, use_R=use_R, timings=timings, side_contexts=side, seq_chunk=args.seq_chunk)
 
+    note("%d warm-up step(s)" % args.warmup)
     for _ in range(args.warmup):
         out = step()
     torch.cuda.synchronize()
+    note("%d timed step(s)" % args.steps)
     ctxs = [ctx] + list(side or [])
     for c in ctxs:
         c.profile(True)
@@ -297,6 +301,7 @@ def main():
                       "note": "gate, up, down projections of the same block (H_out = I), outside `value`"}
         del mlp
     if not args.no_cpu_baseline:
+        note("timing the oracle on the host cores (bounded sample)")
         rec["cpu_baseline"] = cpu_baseline(blk, cfg, out["hessians"], out)
     print(json.dumps(rec))
 
