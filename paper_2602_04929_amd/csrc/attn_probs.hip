@@ -4,8 +4,10 @@
 // (Pt[g][i][r L + t] = A_h[t, i], h = g rep + r; see build_hessians_bf16), for both score matrices at once: the one of the
 // quantized-input path and the one of the full-precision path, whose difference A - A~ is the second output.
 //
-// Operands: Q^ = [q_hi | q_lo | q_hi] and K^ = [k_hi | k_hi | k_lo], one [L, 3 d_h] bf16 matrix per head in 16 x 32 blocks
-// (as split3_kernel writes them), so that Q^ K^T = q_hi k_hi + q_lo k_hi + q_hi k_lo carries the fp32 projections to 16 bits.
+// Operands: Q^ = [q_hi | q_lo | q_hi] and K^ = [k_hi | k_hi | k_lo], one [L, 3 d_h] matrix of 16-bit values per head in 16 x 32
+// blocks (as split3_kernel writes them), so that Q^ K^T = q_hi k_hi + q_lo k_hi + q_hi k_lo.  The pairs of a score matrix are
+// either IEEE half values of the operands times a power of two (QkScale: 22 significant bits, the products on
+// v_mfma_f32_32x32x16_f16 and the powers of two taken back out with the softmax scale) or unscaled bf16 (16 bits).
 //
 // One workgroup per (128 query rows t, head), eight wavefronts = (path, half of the 64 keys of a tile, half of the queries).
 // A wavefront keeps the Q^ fragments of its path for its 64 queries in registers (two 32-wide blocks, the distinct segments q_hi and q_lo)
@@ -24,6 +26,7 @@
 
 typedef __hip_bfloat16 bf16;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 
@@ -58,7 +61,7 @@ __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x)
 template <int DH, bool ROWS>
 __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restrict__ Qa, const bf16* __restrict__ Ka, const bf16* __restrict__ Qb,
                                                            const bf16* __restrict__ Kb, int L, int nheads, int rep, int xcd_runs, float scale2,
-                                                           PtOut out, long long ldp, long long group_stride, int f16) {
+                                                           PtOut out, long long ldp, long long group_stride, int f16, QkScale qs) {
     constexpr int NKS = DH / 16;                 // 16-deep MFMA steps per segment
     constexpr int NCB = DH / 32;                 // 32-column blocks per segment
     constexpr int SEGB = 64 * 2 * DH;            // bytes of one (path, segment) image: [NCB][64 keys][32 elements], pieces swizzled
@@ -90,6 +93,16 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const unsigned kt_lds = (unsigned)(unsigned long long)((__attribute__((address_space(3))) void*)kt);
     const int tq = t0 + 64 * th;                 // first query of this wavefront
+    // encoding of this path's operands (uniform over the wavefront) and the scale that takes their powers of two back out
+    bool half_ops = false;
+    float sc2 = scale2;
+    {
+        const int* wq = p ? qs.qb : qs.qa; const int* wk = p ? qs.kb : qs.ka;
+        if (active && wq && wk) {
+            const int bq = __builtin_amdgcn_readfirstlane(*wq), bk = __builtin_amdgcn_readfirstlane(*wk);
+            if (bq >= 0 && bk >= 0) { half_ops = true; sc2 = ldexpf(scale2, -(tboa_half_exp(bq) + tboa_half_exp(bk))); }
+        }
+    }
 
     // Q^ fragments of this wavefront's path: B operand of the MFMA (lane: query l32 of block tb, 8 contraction elements from 8 lh)
     bf16x8 qh[2][NKS], ql[2][NKS];
@@ -131,11 +144,22 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
             const int c8 = 2 * ks + lh;                                   // 8-element piece of the segment
             const int off = (c8 >> 2) * 4096 + (((c8 & 3) ^ ((row >> 2) & 3)) << 4);
             const bf16x8 kh = *(const bf16x8*)(kh_img + off), kl = *(const bf16x8*)(kh_img + SEGB + off);
+            if (half_ops) {
+                const f16x8 fkh = __builtin_bit_cast(f16x8, kh), fkl = __builtin_bit_cast(f16x8, kl);
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
-                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, qh[tb][ks], acc[tb], 0, 0, 0);
-                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, ql[tb][ks], acc[tb], 0, 0, 0);
-                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, qh[tb][ks], acc[tb], 0, 0, 0);
+                for (int tb = 0; tb < 2; ++tb) {
+                    const f16x8 fqh = __builtin_bit_cast(f16x8, qh[tb][ks]), fql = __builtin_bit_cast(f16x8, ql[tb][ks]);
+                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fkh, fqh, acc[tb], 0, 0, 0);
+                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fkh, fql, acc[tb], 0, 0, 0);
+                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fkl, fqh, acc[tb], 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, qh[tb][ks], acc[tb], 0, 0, 0);
+                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kh, ql[tb][ks], acc[tb], 0, 0, 0);
+                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, qh[tb][ks], acc[tb], 0, 0, 0);
+                }
             }
         }
     };
@@ -143,7 +167,8 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
 
     const int live = t0 / 64 + 2;                              // key tiles up to and including the two on the diagonal
     const int tiles = min(L, (t0 / 256 + 1) * 256) / 64;       // ... up to the end of the diagonal's 256-tile
-    // Scores are kept in units of log 2: v = (q . k) scale2 with scale2 = log2(e) / sqrt(d_h), probabilities 2^(v - max) / sum.
+    // Scores are kept in units of log 2: v = (q . k) sc2 with sc2 = log2(e) / sqrt(d_h) (over the operands' powers of two),
+    // probabilities 2^(v - max) / sum.
     // ---- pass 1: maximum and sum per query, over this wavefront's keys
     float m[2] = {-INFINITY, -INFINITY}, s[2] = {0.f, 0.f};
     issue(0);
@@ -161,7 +186,7 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
                 float vm = -INFINITY;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    acc[tb][e] *= scale2;
+                    acc[tb][e] *= sc2;
                     if (masked && ib + 8 * (e >> 2) + (e & 3) > t) acc[tb][e] = -INFINITY;
                     vm = fmaxf(vm, acc[tb][e]);
                 }
@@ -220,7 +245,7 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         const int row = il + 8 * (e >> 2) + (e & 3);
-                        float a = ex2(acc[tb][e] * scale2 - M[tb]) * inv[tb];
+                        float a = ex2(acc[tb][e] * sc2 - M[tb]) * inv[tb];
                         if (masked && i0 + row > t) a = 0.f;
                         ex[(p * 64 + row) * EXP + 64 * th + 32 * tb + l32] = a;
                     }
@@ -278,7 +303,7 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
 
 template <int DH, bool ROWS>
 int launch(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, PtOut out, long long ldp,
-           long long group_stride, int f16) {
+           long long group_stride, int f16, QkScale qs) {
     static bool attr_set = false;
     constexpr int smem = attn_lds_bytes<DH>();
     if (!attr_set) {
@@ -287,19 +312,19 @@ int launch(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const 
     }
     const int total = Hq * (L / BT), xcd_runs = ((Hq / rep) % 8 == 0 && total % 8 == 0) ? 1 : 0;
     hipLaunchKernelGGL((attn_probs_t_kernel<DH, ROWS>), dim3(total), dim3(512), smem, ctx->stream, Qa, Ka, Qb, Kb, L, Hq, rep, xcd_runs,
-                       (float)(1.4426950408889634 / sqrt((double)DH)), out, ldp, group_stride, f16);
+                       (float)(1.4426950408889634 / sqrt((double)DH)), out, ldp, group_stride, f16, qs);
     TB_KERNEL_CHECK(ctx);
     return 0;
 }
 
 template <bool ROWS>
 int dispatch(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, int dh, PtOut out,
-             long long ldp, long long group_stride, int f16) {
+             long long ldp, long long group_stride, int f16, QkScale qs) {
     switch (dh) {
-        case 32: return launch<32, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
-        case 64: return launch<64, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
-        case 96: return launch<96, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
-        default: return launch<128, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16);
+        case 32: return launch<32, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16, qs);
+        case 64: return launch<64, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16, qs);
+        case 96: return launch<96, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16, qs);
+        default: return launch<128, ROWS>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, out, ldp, group_stride, f16, qs);
     }
 }
 
@@ -310,16 +335,16 @@ bool attn_probs_t_supported(int L, int dh) {
 }
 
 int attn_probs_t(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, int dh, PtOut out,
-                 long long ldp, long long group_stride, int f16) {
+                 long long ldp, long long group_stride, int f16, QkScale qs) {
     if (!attn_probs_t_supported(L, dh) || Hq % rep || !Qa || !Ka || (Qb && !Kb) || !out.hi || !out.lo || (Qb && (!out.dhi || !out.dlo)) || ldp % 32)
         return tboa_fail(ctx, TBOA_EINVAL, "attn_probs_t: unsupported shape or missing buffer");
-    return dispatch<false>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, dh, out, ldp, group_stride, f16);
+    return dispatch<false>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, dh, out, ldp, group_stride, f16, qs);
 }
 
 int attn_probs_rows(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, int dh, bf16* P,
-                    long long ldp, int f16) {
+                    long long ldp, int f16, QkScale qs) {
     if (!attn_probs_t_supported(L, dh) || Hq % rep || !Qa || !Ka || (Qb && !Kb) || !P || ldp % 8 || ldp < (Qb ? 4LL : 3LL) * L || ((uintptr_t)P & 15))
         return tboa_fail(ctx, TBOA_EINVAL, "attn_probs_rows: unsupported shape or missing buffer");
     PtOut out{P, nullptr, nullptr, nullptr};
-    return dispatch<true>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, dh, out, ldp, (long long)L * ldp, f16);
+    return dispatch<true>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, dh, out, ldp, (long long)L * ldp, f16, qs);
 }

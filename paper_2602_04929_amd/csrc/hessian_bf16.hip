@@ -4,8 +4,11 @@
 // contraction axis):
 //   H_in = X X^T            A = B = X^T [d, T]                     (split over T, partial sums reduced in fp64)
 //   R    = alpha dX X^T     A = dX^T as an exact hi + lo bf16 pair, B = X^T
-//   Q, K projections        A = X rows [tokens, d], B = W [out, d]  -> fp32, then an exact 3-term bf16 split so that
-//   scores Q_h K_h^T        runs as one GEMM over [hi | lo | hi] . [hi | hi | lo] (peaked softmaxes need the accuracy)
+//   Q, K projections        A = X rows [tokens, d], B = W [out, d]  -> fp32, then split into (hi, lo) pairs of 16-bit values so that
+//   scores Q_h K_h^T        runs as one product over [hi | lo | hi] . [hi | hi | lo] (peaked softmaxes need the accuracy, and the
+//                           difference A - A~ of two softmaxes more still: where the fused scores + softmax kernel runs the pairs
+//                           are IEEE half values of the projections times a power of two, 22 significant bits; the GEMM path
+//                           takes bf16 pairs, 16 bits)
 //   Y_h^T = X_s^T A_h^T     A = X_s^T [d, L], B = A_h [L, L] (lower triangular: the k-loop stops at the diagonal tile)
 //   H_in^V += Y^T (Y^T)^T   A = B = Y^T [d, rep*G*L] for G sequences at a time, lower tiles only
 //   R_v += alpha dY^T (Y^T)^T with dY^T = [X_s^T | X~_s^T] . [A | -A~]^T taken from ONE fp32 accumulator
@@ -104,13 +107,15 @@ __global__ __launch_bounds__(256) void transpose_kernel(const bf16* __restrict__
 // L > 0: the rows are whole sequences of L tokens and the result is one [L, 3*dh] matrix per (sequence, head), each in the
 // 16 x 32 blocks the bf16 GEMM reads (L a multiple of 16, 3*dh of 32): element (t, c) of sequence s, head h at
 // ((s H + h) L 3dh) + tboa_blocked_offset(t, c, 3dh / 32).
+// amax (blocked result only, else NULL): one word per sequence as amax_seq_kernel leaves it; the pairs of that sequence are
+// then IEEE half values of the input times 2^tboa_half_exp(word) instead of bf16 (see QkScale).
 __device__ __forceinline__ long long split3_offset(long long row, int h, int c, int H, int dh, int L) {
     if (L > 0) return ((row / L) * H + h) * (long long)L * 3 * dh + tboa_blocked_offset(row % L, c, (3 * dh) >> 5);
     return (row * H + h) * 3 * dh + c;
 }
 
 __global__ void split3_kernel(const float* __restrict__ in, const float* __restrict__ scale, bf16* __restrict__ out, long long rows, int hd,
-                              int dh, int right, int L) {
+                              int dh, int right, int L, const int* __restrict__ amax) {
     const int H = hd / dh;
     if (L > 0 && dh % 32 == 0 && rows % 16 == 0 && rows / 16 * (hd / 32) < 2147483647LL) {
         // blocked result: a wavefront takes a 16 x 32 piece of `in` in two loads of eight whole rows of 128 bytes (lane: row
@@ -130,10 +135,21 @@ __global__ void split3_kernel(const float* __restrict__ in, const float* __restr
             f4 va = __builtin_nontemporal_load((const f4*)src), vb = __builtin_nontemporal_load((const f4*)(src + 8LL * hd));
             if (scale) { const f4 sc = *(const f4*)(scale + c0 + c4); va = va * sc; vb = vb * sc; }
             union { bf16 b[4]; uint2 u; } ha, la, hb, lb;
+            const int word = amax ? amax[sq] : -1;
+            if (word >= 0) {
+                const float up = ldexpf(1.f, tboa_half_exp(word));
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                ha.b[k] = __float2bfloat16(va[k]); la.b[k] = __float2bfloat16(va[k] - __bfloat162float(ha.b[k]));
-                hb.b[k] = __float2bfloat16(vb[k]); lb.b[k] = __float2bfloat16(vb[k] - __bfloat162float(hb.b[k]));
+                for (int k = 0; k < 4; ++k) {
+                    const float a = va[k] * up, b2 = vb[k] * up;
+                    ha.b[k] = enc16(a, 1); la.b[k] = enc16(a - dec16(ha.b[k], 1), 1);
+                    hb.b[k] = enc16(b2, 1); lb.b[k] = enc16(b2 - dec16(hb.b[k], 1), 1);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    ha.b[k] = __float2bfloat16(va[k]); la.b[k] = __float2bfloat16(va[k] - __bfloat162float(ha.b[k]));
+                    hb.b[k] = __float2bfloat16(vb[k]); lb.b[k] = __float2bfloat16(vb[k] - __bfloat162float(hb.b[k]));
+                }
             }
             // block (t0 / 16, (seg dh + e0) / 32) of the [L, 3 dh] matrix of (sequence sq, head h)
             bf16* o = out + ((long long)sq * H + h) * L * 3 * dh + ((long long)(t0 >> 4) * kb + (e0 >> 5)) * 512;
@@ -174,6 +190,29 @@ __global__ void split3_kernel(const float* __restrict__ in, const float* __restr
         out[split3_offset(row, h, dh + e, H, dh, L)] = right ? hi : lo;
         out[split3_offset(row, h, 2 * dh + e, H, dh, L)] = right ? lo : hi;
     }
+}
+
+// out[s] = bits of the largest |in[r, c] scale[c]| over the rows of sequence s (blockIdx.y; L rows of hd columns each), by
+// atomicMax on the integer: a word that starts negative ends as those bits.  A NaN counts as infinity.
+__global__ __launch_bounds__(256) void amax_seq_kernel(const float* __restrict__ in, const float* __restrict__ scale, int L, int hd,
+                                                       int* __restrict__ out) {
+    const float* src = in + (long long)blockIdx.y * L * hd;
+    const long long n = (long long)L * hd;
+    float m = 0.f;
+    auto take = [&](float v) { v = fabsf(v); m = (v > m || !(v == v)) ? (v == v ? v : INFINITY) : m; };
+    const long long tid = blockIdx.x * (long long)blockDim.x + threadIdx.x, nth = (long long)gridDim.x * blockDim.x;
+    if (hd % 4 == 0 && (((uintptr_t)in | (uintptr_t)scale) & 15) == 0) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        for (long long i = tid; i < n / 4; i += nth) {
+            f4 v = *((const f4*)src + i);
+            if (scale) v = v * *(const f4*)(scale + (4 * i) % hd);
+            take(v.x); take(v.y); take(v.z); take(v.w);
+        }
+    } else
+        for (long long i = tid; i < n; i += nth) take(scale ? src[i] * scale[i % hd] : src[i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    if ((threadIdx.x & 63) == 0) atomicMax(out + blockIdx.y, __float_as_int(m));
 }
 
 // fp32 [n] -> exact-to-16-bits pair of bf16
@@ -754,17 +793,28 @@ int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_l
     return gram_splitk(ctx, splits, n, A_lo ? 2 : 1, pairs, ld, K, scale, lower, part, out);
 }
 
-// Q^ [rows, Hq, 3 dh] and K^ [rows, Hkv, 3 dh] of `rows` tokens Xr [rows, d]; weights as one or two (hi, lo) bf16 terms
+// Q^ [rows, Hq, 3 dh] and K^ [rows, Hkv, 3 dh] of `rows` tokens Xr [rows, d]; weights as one or two (hi, lo) bf16 terms.
+// amax_q, amax_k (both or neither; blocked operands of whole sequences only): one device word per sequence of the chunk each;
+// the pairs are then scaled IEEE half values and the words say by how much (see QkScale), else unscaled bf16.
 int project_qk(const Dims& D, const bf16* Xr, int rows, const bf16* Wq, const bf16* Wq_lo, const bf16* Wk, const bf16* Wk_lo,
-               float* Qf, float* Kf, bf16* Qh, bf16* Kh, const float* q_scale = nullptr, const float* k_scale = nullptr) {
+               float* Qf, float* Kf, bf16* Qh, bf16* Kh, const float* q_scale = nullptr, const float* k_scale = nullptr,
+               int* amax_q = nullptr, int* amax_k = nullptr) {
     TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, Wq, D.dm, Qf, D.dq, TBOA_F32, 0, 0)));
     if (Wq_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, Wq_lo, D.dm, Qf, D.dq, TBOA_F32, 1, 0)));
     TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk, D.dm, Kf, D.dkv, TBOA_F32, 0, 0)));
     if (Wk_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk_lo, D.dm, Kf, D.dkv, TBOA_F32, 1, 0)));
+    if (amax_q) {
+        if (!amax_k || !qk_blocked(D) || D.dh % 32 || rows % D.L) return tboa_fail(D.ctx, TBOA_EINVAL, "project_qk: half operands need blocked whole sequences");
+        const int ns = rows / D.L;
+        TB_TRY(launch_fill_f32(D.ctx, (float*)amax_q, ns, -1.f));       // any negative word: the bits of the largest magnitude replace it
+        TB_TRY(launch_fill_f32(D.ctx, (float*)amax_k, ns, -1.f));
+        hipLaunchKernelGGL(amax_seq_kernel, dim3(64, ns), dim3(256), 0, D.ctx->stream, Qf, q_scale, D.L, D.dq, amax_q);
+        hipLaunchKernelGGL(amax_seq_kernel, dim3(64, ns), dim3(256), 0, D.ctx->stream, Kf, k_scale, D.L, D.dkv, amax_k);
+    }
     hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dq)), dim3(256), 0, D.ctx->stream, Qf, q_scale, Qh, (long long)rows, D.dq, D.dh, 0,
-                       qk_blocked(D) ? D.L : 0);
+                       qk_blocked(D) ? D.L : 0, amax_q);
     hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dkv)), dim3(256), 0, D.ctx->stream, Kf, k_scale, Kh, (long long)rows, D.dkv, D.dh, 1,
-                       qk_blocked(D) ? D.L : 0);
+                       qk_blocked(D) ? D.L : 0, amax_k);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
 }
@@ -875,6 +925,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     bf16 *Bcat = nullptr, *XgT = nullptr, *YTl = nullptr, *dYTl = nullptr;
     PtOut pt{nullptr, nullptr, nullptr, nullptr};
     float *part, *Qf, *Kf, *Sc, *Scf, *B1f = nullptr, *B2f = nullptr;
+    int* amx;      // [q | k | q~ | k~] x G: largest magnitudes of the chunk's projections, per sequence (see QkScale)
     double *Hin64, *Wq64, *Wk64, *Wo64, *Tq, *Tk, *Ho;
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
@@ -885,6 +936,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         Qh = ar.get<bf16>((size_t)G * L * dq * 3); Kh = ar.get<bf16>((size_t)G * L * dkv * 3);
         Qhf = rv ? ar.get<bf16>((size_t)G * L * dq * 3) : nullptr; Khf = rv ? ar.get<bf16>((size_t)G * L * dkv * 3) : nullptr;
         Sc = fused ? nullptr : ar.get<float>((size_t)Hq * L * L); Scf = (rv && !fused) ? ar.get<float>((size_t)Hq * L * L) : nullptr;
+        amx = ar.get<int>((size_t)4 * G);
         XcT = ar.get<bf16>((size_t)dm * (G * nsx * L + PADE));
         if (grouped) {
             P = nullptr;
@@ -963,11 +1015,16 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
         const int Gc = (D.S - s0 < G) ? D.S - s0 : G;
         const long long t0 = (long long)s0 * L;
         const long long ldx = (long long)Gc * nsx * L + PADE, ky = (long long)rep * Gc * L, ldy = ky + PADE, ldp = (long long)nsg * L + PADE;
-        TB_TRY(project_qk(D, X + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qh, Kh));
-        if (rv && fp_cache) {   // the caller keeps the full-precision projections of all tokens: written in place
+        // the fused kernel takes scaled half operands (22 significant bits in the scores instead of 16); the GEMM path bf16 pairs
+        int *aq = fused ? amx : nullptr, *ak = fused ? amx + G : nullptr, *aqf = fused ? amx + 2 * G : nullptr, *akf = fused ? amx + 3 * G : nullptr;
+        TB_TRY(project_qk(D, X + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qh, Kh, nullptr, nullptr, aq, ak));
+        if (rv && fp_cache) {   // the caller keeps the full-precision projections of all tokens: written in place, their words behind them
             Qhf = fp_cache + t0 * dq * 3; Khf = fp_cache + (long long)T * dq * 3 + t0 * dkv * 3;
+            int* words = (int*)(fp_cache + (long long)T * (dq + dkv) * 3);
+            if (fused) { aqf = words + s0; akf = words + D.S + s0; }
+            else if (s0 == 0) TB_TRY(launch_fill_f32(ctx, (float*)words, 2LL * D.S, -1.f));      // negative words: bf16 pairs
         }
-        if (rv) TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
+        if (rv) TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf, nullptr, nullptr, aqf, akf));
         const long long is = bin ? 16 : 1;      // a column offset c into a blocked matrix is the pointer offset 16 c
         for (int sl = 0; sl < Gc; ++sl) {   // XcT[:, sl, :, :] = X_s^T | (X_s - X~_s)^T | X~_s^T
             const bf16* xs = X + (t0 + (long long)sl * L) * dm;
@@ -991,8 +1048,9 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
             for (int sl = 0; sl < Gc; ++sl) {
                 if (fused) {       // scores and softmax in one kernel, nothing of the scores stored
                     const long long qo = (long long)sl * Hq * L * 3 * dh, ko = (long long)sl * Hkv * L * 3 * dh;
+                    const QkScale qs{aq + sl, ak + sl, rv ? aqf + sl : nullptr, rv ? akf + sl : nullptr};
                     TB_TRY(attn_probs_t(ctx, Qh + qo, Kh + ko, rv ? Qhf + qo : nullptr, rv ? Khf + ko : nullptr, L, Hq, rep, dh, pt, ldpt,
-                                        (long long)L * ldpt, D.f16));
+                                        (long long)L * ldpt, D.f16, qs));
                 } else {
                     if (rv) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
                     else TB_TRY(scores(D, Qh, Kh, sl, Sc));
@@ -1123,6 +1181,7 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
     const long long TP = (long long)T + PADE, ldp = (long long)nsp * L + PADE;
     bf16 *Wqh, *Wql, *Wkh, *Wkl, *Wvh, *Wvl, *Qh, *Kh, *Qhf, *Khf, *P, *VTc, *OT, *OTl, *dOT, *dOTl;
     float *Qf, *Kf, *VT32, *VT32f, *Sc, *Scf, *part, *steps;
+    int* amx;      // [q | k | q~ | k~] x G (see QkScale)
     for (int pass = 0; pass < 2; ++pass) {
         Arena ar(pass ? ctx->ws : nullptr);
         Wqh = ar.get<bf16>((size_t)dq * dm); Wql = ar.get<bf16>((size_t)dq * dm);
@@ -1138,6 +1197,7 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         dOT = fp ? ar.get<bf16>((size_t)dq * TP) : nullptr; dOTl = fp ? ar.get<bf16>((size_t)dq * TP) : nullptr;
         part = ar.get<float>((size_t)splits * dq * dq);
         steps = ar.get<float>((size_t)dq + 2 * dkv);
+        amx = ar.get<int>((size_t)4 * G);
         if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
     }
     hipStream_t st = ctx->stream;
@@ -1161,12 +1221,17 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         // full-precision V~^T = Wv X~c^T
         TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvh, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 0, 0)));
         if (Wvl_u) TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvl_u, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 1, 0)));
-        TB_TRY(project_qk(D, Xc, Gc * L, Wqh, Wql_u, Wkh, Wkl_u, Qf, Kf, Qh, Kh, sq, sk));
+        int *aq = fused ? amx : nullptr, *ak = fused ? amx + G : nullptr;
+        const int *aqf = fused ? amx + 2 * G : nullptr, *akf = fused ? amx + 3 * G : nullptr;
+        TB_TRY(project_qk(D, Xc, Gc * L, Wqh, Wql_u, Wkh, Wkl_u, Qf, Kf, Qh, Kh, sq, sk, aq, ak));
         if (fp) {
             TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wv, dm, X_fp + t0 * dm, dm, VT32f, (long long)Gc * L, TBOA_F32, 0, 0)));
-            if (fp_cache) {     // projections of X_fp by W_Q, W_K as tboa_build_hessians left them
+            if (fp_cache) {     // projections of X_fp by W_Q, W_K as tboa_build_hessians left them, with the words that say how
                 Qhf = (bf16*)fp_cache + t0 * dq * 3; Khf = (bf16*)fp_cache + (long long)T * dq * 3 + t0 * dkv * 3;
-            } else TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf));
+                const int* words = (const int*)(fp_cache + (long long)T * (dq + dkv) * 3);
+                aqf = words + s0; akf = words + D.S + s0;
+            } else TB_TRY(project_qk(D, X_fp + t0 * dm, Gc * L, Wq, nullptr, Wk, nullptr, Qf, Kf, Qhf, Khf, nullptr, nullptr,
+                                     fused ? amx + 2 * G : nullptr, fused ? amx + 3 * G : nullptr));
         }
         hipLaunchKernelGGL(vt_segments_kernel, dim3(g1((long long)dkv * Gc * L)), dim3(256), 0, st, VT32, sv, fp ? VT32f : nullptr, VTc, dkv, Gc, L,
                            nsg, ldv, D.f16);
@@ -1177,7 +1242,8 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             // both left as exact-to-16-bit (hi, lo) pairs of bf16
             if (fused) {      // scores and softmax in one kernel, nothing of the scores stored
                 const long long qo = (long long)sl * Hq * L * 3 * dh, ko = (long long)sl * D.Hkv * L * 3 * dh;
-                TB_TRY(attn_probs_rows(ctx, Qh + qo, Kh + ko, fp ? Qhf + qo : nullptr, fp ? Khf + ko : nullptr, L, Hq, rep, dh, P, ldp, D.f16));
+                const QkScale qs{aq + sl, ak + sl, fp ? aqf + sl : nullptr, fp ? akf + sl : nullptr};
+                TB_TRY(attn_probs_rows(ctx, Qh + qo, Kh + ko, fp ? Qhf + qo : nullptr, fp ? Khf + ko : nullptr, L, Hq, rep, dh, P, ldp, D.f16, qs));
             } else {
                 if (fp) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
                 else TB_TRY(scores(D, Qh, Kh, sl, Sc));
@@ -1557,7 +1623,9 @@ extern "C" int tboa_linear_forward(tboa_ctx* ctx, int64_t n_tokens, int d_in, in
 
 extern "C" size_t tboa_fp_cache_bytes(const tboa_attn_desc* d) {
     if (!d || d->x_dtype != TBOA_BF16 || d->n_seqs <= 0 || d->seq_len <= 0 || d->head_dim <= 0) return 0;
-    return (size_t)d->n_seqs * d->seq_len * (size_t)(d->n_q_heads + d->n_kv_heads) * d->head_dim * 3 * sizeof(bf16);
+    // the (hi, lo) operands of every token, then one word per sequence and operand that says how they are encoded (see QkScale)
+    const size_t ops = (size_t)d->n_seqs * d->seq_len * (size_t)(d->n_q_heads + d->n_kv_heads) * d->head_dim * 3 * sizeof(bf16);
+    return ops + (((size_t)2 * d->n_seqs * sizeof(int) + 15) & ~(size_t)15);
 }
 
 extern "C" int tboa_act_fakequant(tboa_ctx* ctx, int64_t n_tokens, int d, int bits, int dtype, const void* X_in, void* X_out) {

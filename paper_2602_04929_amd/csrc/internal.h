@@ -130,15 +130,25 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
 // rows i up to the end of the 256-tile that holds t written (zeros beyond the diagonal).  dhi, dlo: A - A~ of a second
 // score matrix (nullptr without one).
 struct PtOut { __hip_bfloat16 *hi, *lo, *dhi, *dlo; };
+// How the (hi, lo) pairs of Q^ and K^ are encoded, per score matrix: a device word per operand that holds the bits of the
+// largest magnitude of that operand's fp32 values, in which case the pairs are IEEE half values of the operand times
+// 2^tboa_half_exp(word) (22 significant bits wherever the magnitude is within 2^-17 of the largest), or a negative word / a
+// null pointer: pairs of bf16, unscaled (16 significant bits).
+struct QkScale { const int *qa, *ka, *qb, *kb; };
+// e such that amax 2^e lies in [2^13, 2^14) (amax: the bits of a non-negative float); 0 for zero, denormal or non-finite amax
+__host__ __device__ __forceinline__ int tboa_half_exp(int amax_bits) {
+    const int E = (amax_bits >> 23) & 0xff;
+    return (E < 13 || E == 255) ? 0 : 140 - E;
+}
 // straight from the blocked 3-term operands Q^ [Hq][L, 3 dh], K^ [Hkv][L, 3 dh] of the score product (second pair Qb, Kb or
 // nullptr); attn_probs_t_supported tells which shapes the kernel takes
 bool attn_probs_t_supported(int L, int dh);
 // the same probabilities as row-major P[h][t][.] = [A_hi | A_lo | A_hi | A - A~] (segments of L columns, pitch ldp; the last segment
 // only with a second pair; A - A~ as one 16-bit value), rows written up to the end of the 256-tile of t
 int attn_probs_rows(tboa_ctx* ctx, const __hip_bfloat16* Qa, const __hip_bfloat16* Ka, const __hip_bfloat16* Qb, const __hip_bfloat16* Kb, int L,
-                    int Hq, int rep, int dh, __hip_bfloat16* P, long long ldp, int f16);
+                    int Hq, int rep, int dh, __hip_bfloat16* P, long long ldp, int f16, QkScale qs);
 int attn_probs_t(tboa_ctx* ctx, const __hip_bfloat16* Qa, const __hip_bfloat16* Ka, const __hip_bfloat16* Qb, const __hip_bfloat16* Kb, int L,
-                 int Hq, int rep, int dh, PtOut out, long long ldp, long long group_stride, int f16);
+                 int Hq, int rep, int dh, PtOut out, long long ldp, long long group_stride, int f16, QkScale qs);
 
 // element offset of (r, c) in a matrix kept in the 16 x 32 blocks the bf16 GEMM can read and write (TBOA_GEMM_*_TILED);
 // kb = leading dimension / 32

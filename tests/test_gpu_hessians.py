@@ -83,9 +83,10 @@ def test_bf16_summed_form(ctx, hq, hkv, d, L, S, with_fp, dh):
     got = ctx.build_hessians(b["X"], Xf, b["Wq"], b["Wk"], b["Wv"], b["Wo"], hq, hkv, dh, alpha=0.25, seq_chunk=2)
     want = O.build_hessians(np64(b["X"]), np64(Xf) if with_fp else None, np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), hq, hkv, dh,
                             alpha=0.25)
-    # R_v is measured against its own largest entry and is noise-like on these inputs (X - X~ is independent of X), so the
-    # 11 significant bits of the half-precision X - X~ show in it undiminished
-    check_all(got, want, 1e-5, 1e-5, 5e-4)
+    # R_v is measured against its own largest entry and is noise-like on these inputs (X - X~ is independent of X: its entries
+    # are sums that cancel), so the fp32 rounding of the scores, 2^-24 of logits of a few tens against differences A - A~ of a
+    # few percent of A, shows in it as 1e-5 to 2e-5 (with the scores from 16-bit pairs of Q and K it was 1e-4)
+    check_all(got, want, 1e-5, 1e-5, 6e-5)
     assert torch.equal(got["Hin_v"], got["Hin_v"].transpose(1, 2))
 
 
@@ -156,22 +157,29 @@ def test_out_proj_bf16(ctx, d, L, dh):
     assert R2 is None and rel_err(np64(H2), wH) <= 3e-5
 
 
-def test_out_proj_reuses_fp_projections(ctx, lib):
+@pytest.mark.parametrize("dm,L", [(264, 320), (256, 256), (264, 256)])
+def test_out_proj_reuses_fp_projections(ctx, lib, dm, L):
     """The projections of X_fp by the full-precision W_Q, W_K kept by tboa_build_hessians (fp_cache) give the output-projection
-    Hessian the same bits as recomputing them; W_Q, W_K may then be omitted."""
-    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=264, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=5, seq_len=320, n_outlier=3)
+    Hessian the same bits as recomputing them; W_Q, W_K may then be omitted.  The cache says how its operands are encoded:
+    bf16 pairs from the builds that form the scores with the GEMM kernel (L = 320), scaled half pairs from the fused scores +
+    softmax kernel (d = L = 256); with d = 264 the first call leaves bf16 pairs and the second reads them in the fused kernel."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=dm, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=5, seq_len=L, n_outlier=3)
     b = synth.make_block(cfg, seed=8, device="cuda")
     g = torch.Generator(device="cuda"); g.manual_seed(1)
     deq = [w.float() * (1 + 0.05 * torch.randn(w.shape, generator=g, device="cuda")) for w in (b["Wq"], b["Wk"], b["Wv"])]
     Hs = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 4, 2, 32, alpha=0.25, seq_chunk=2, keep_fp_projections=True)
     cache = Hs["fp_cache"]
-    assert cache is not None and cache.numel() == 5 * 320 * (4 + 2) * 32 * 3 * 2
+    # the operands of every token, then one word per (sequence, operand) that says how they are encoded (whole 16-byte pieces)
+    assert cache is not None and cache.numel() == 5 * L * (4 + 2) * 32 * 3 * 2 + 48
     plain = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 4, 2, 32, alpha=0.25, seq_chunk=2)
     for k in ("Hin_qk", "R_qk", "Hin_v", "R_v", "Hout_q", "Hout_k", "Hout_v"):
         assert torch.equal(Hs[k], plain[k]), k
     H0, R0 = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, b["Wq"], b["Wk"], b["Wv"], 4, 2, 32, alpha=0.25, seq_chunk=3)
     H1, R1 = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, None, None, b["Wv"], 4, 2, 32, alpha=0.25, seq_chunk=3, fp_cache=cache)
-    assert torch.equal(H0, H1) and torch.equal(R0, R1)
+    if (dm, L) == (264, 256):       # the cache holds 16-bit pairs where the recomputation takes 22-bit ones: close, not equal
+        assert torch.equal(H0, H1) and rel_err(np64(R1), np64(R0)) <= 1e-3 and not torch.equal(R0, R1)
+    else:
+        assert torch.equal(H0, H1) and torch.equal(R0, R1)
     with pytest.raises(lib.TurboBoAError):       # neither the cache nor the weights to recompute it
         ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, None, None, b["Wv"], 4, 2, 32, alpha=0.25)
     # fp32 inputs: the library has no use for a cache
