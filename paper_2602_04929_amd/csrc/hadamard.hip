@@ -4,7 +4,7 @@
 //
 // Bound by HBM: a row is read once and written once.  One workgroup of d / 16 threads per row; every thread holds 16
 // values in registers and runs a radix-16 butterfly on 4 index bits per round (the order in which the k bits are
-// processed is free).  Round 1 takes bits 0..3 straight from 16 consecutive values (16-byte global loads); the later
+// processed is free).  The first one takes bits 0..3 straight from 16 consecutive values (16-byte global loads); the later
 // rounds fetch their values from LDS, 4 bits at a time upwards (the last one takes what is left); at the end a thread
 // reads back 16 consecutive results and stores them as 16-byte vectors.  LDS word i sits at i + i / 16: the stride-16
 // accesses of the consecutive layout and the stride-1 / stride-256 accesses of the rounds all spread over the 64 banks.

@@ -102,6 +102,27 @@ def test_activations_beyond_half_precision_range_take_bf16_operands(ctx):
     check_all(got, want, 1e-5, 1e-4, 1e-2)
 
 
+def test_zero_and_tiny_sequences_in_the_fused_scores_kernel(ctx):
+    """The fused scores + softmax kernel scales Q and K of every sequence by a power of two taken from their largest
+    magnitude: a sequence of zeros (largest magnitude 0: no scaling, uniform causal probabilities) and one whose projections
+    are of the order 1e-6 (scaled up by 2^30 or so) give finite results that match the oracle like any other."""
+    cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=4, seq_len=256, n_outlier=3)
+    b = synth.make_block(cfg, seed=11, device="cuda")
+    b["X"][1] = 0; b["X_fp"][1] = 0
+    b["X"][2] *= 2.0 ** -20; b["X_fp"][2] *= 2.0 ** -20            # exact in bf16
+    got = ctx.build_hessians(b["X"], b["X_fp"], b["Wq"], b["Wk"], b["Wv"], b["Wo"], 4, 2, 32, alpha=0.25, seq_chunk=3)
+    assert all(torch.isfinite(v).all() for v in got.values() if v is not None)
+    want = O.build_hessians(np64(b["X"]), np64(b["X_fp"]), np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]), np64(b["Wo"]), 4, 2, 32, alpha=0.25)
+    check_all(got, want, 1e-5, 1e-5, 6e-5)
+    g = torch.Generator(device="cuda"); g.manual_seed(2)
+    deq = [uniform_grid_weights(w, 4, g) for w in (b["Wq"], b["Wk"], b["Wv"])]
+    Hin_o, R_o = ctx.build_hessian_out_proj(b["X"], b["X_fp"], *deq, b["Wq"], b["Wk"], b["Wv"], 4, 2, 32, alpha=0.25, seq_chunk=3)
+    wH, wR = O.build_hessian_out_proj(np64(b["X"]), np64(b["X_fp"]), *[np64(w) for w in deq], np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]),
+                                      4, 2, 32, alpha=0.25)
+    assert torch.isfinite(Hin_o).all() and torch.isfinite(R_o).all()
+    assert rel_err(np64(Hin_o), wH) <= 3e-5 and rel_err(np64(R_o), wR) <= 1e-3
+
+
 def test_bf16_path_long_sequence(ctx):
     """One sequence longer than 2048 tokens: the softmax rows no longer fit the register-resident kernel."""
     cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=64, n_q_heads=1, n_kv_heads=1, head_dim=32, n_seqs=1, seq_len=2312, n_outlier=1)
