@@ -227,7 +227,10 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
             M[tb] = fin[(p * 2 + 0) * BT + tl]; inv[tb] = fin[(p * 2 + 1) * BT + tl];
         }
     }
-    // ---- pass 2: probabilities, exchanged through LDS, written transposed
+    // ---- pass 2: probabilities, exchanged through LDS, written transposed.  As IEEE half they are written times 2^14
+    // (ATTN_PROBS_HALF_SCALE): the lo half of a pair then stays a normal number down to probabilities of 2^-17, where unscaled it
+    // would be subnormal below 2^-3 (an absolute error of 3e-8 on every entry); the products that read them take the factor out.
+    const float osc = f16 ? ATTN_PROBS_HALF_SCALE : 1.f;
     bf16* dst[4] = {out.hi + g * group_stride, out.lo ? out.lo + g * group_stride : nullptr, out.dhi ? out.dhi + g * group_stride : nullptr,
                     out.dlo ? out.dlo + g * group_stride : nullptr};
     issue(0);
@@ -263,8 +266,8 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
                 union { bf16 b[8]; uint4 u; } hi, lo, dd;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float a = (it < live) ? ex[(8 * i8 + e) * EXP + tq2] : 0.f;
-                    const float d = (it < live && two) ? a - ex[(64 + 8 * i8 + e) * EXP + tq2] : 0.f;
+                    const float a1 = (it < live) ? ex[(8 * i8 + e) * EXP + tq2] : 0.f;
+                    const float a = a1 * osc, d = (it < live && two) ? (a1 - ex[(64 + 8 * i8 + e) * EXP + tq2]) * osc : 0.f;
                     hi.b[e] = enc16(a, f16); lo.b[e] = enc16(a - dec16(hi.b[e], f16), f16); dd.b[e] = enc16(d, f16);
                 }
                 bf16* prow = out.hi + h * group_stride + (long long)(t0 + tq2) * ldp + i0 + 8 * i8;
@@ -287,7 +290,7 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
                     }
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float a = v[e], d = v[e] - w[e];
+                        const float a = v[e] * osc, d = (v[e] - w[e]) * osc;
                         hi.b[4 * q + e] = enc16(a, f16); lo.b[4 * q + e] = enc16(a - dec16(hi.b[4 * q + e], f16), f16);
                         dh.b[4 * q + e] = enc16(d, f16); dl.b[4 * q + e] = enc16(d - dec16(dh.b[4 * q + e], f16), f16);
                     }

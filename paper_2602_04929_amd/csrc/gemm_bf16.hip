@@ -117,13 +117,21 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// four results as 16-bit values (8 bytes): bf16, or IEEE half when the launch carries TBOA_GEMM_F16
+// whether the 16-bit results are IEEE half: single values follow the operands (TBOA_GEMM_F16), (hi, lo) pairs their own flag
+__device__ __forceinline__ bool half_results(const Args& g) {
+    return (g.flags & TBOA_GEMM_C_HILO) ? (g.flags & TBOA_GEMM_C_HILO_HALF) != 0 : (g.flags & TBOA_GEMM_F16) != 0;
+}
+// four results as 16-bit values (8 bytes)
 __device__ __forceinline__ uint2 pack16x4(const Args& g, f32x4 r) {
-    if ((g.flags & TBOA_GEMM_F16) && !(g.flags & TBOA_GEMM_C_HILO)) return __builtin_bit_cast(uint2, __builtin_convertvector(r, f16x4));
+    if (half_results(g)) return __builtin_bit_cast(uint2, __builtin_convertvector(r, f16x4));
     return __builtin_bit_cast(uint2, __builtin_convertvector(r, bf16x4));
 }
-// TBOA_GEMM_C_HILO: the result leaves as an exact-to-16-bit pair of bf16 values, hi into C and lo = bf16(r - hi) into C2
-__device__ __forceinline__ uint2 pack_lo4(f32x4 r) {
+// TBOA_GEMM_C_HILO: the result leaves as a (hi, lo) pair of 16-bit values, hi into C and lo = r - hi (rounded) into C2
+__device__ __forceinline__ uint2 pack_lo4(const Args& g, f32x4 r) {
+    if (g.flags & TBOA_GEMM_C_HILO_HALF) {
+        const f16x4 hi = __builtin_convertvector(r, f16x4);
+        return __builtin_bit_cast(uint2, __builtin_convertvector(r - __builtin_convertvector(hi, f32x4), f16x4));
+    }
     const bf16x4 hi = __builtin_convertvector(r, bf16x4);
     return __builtin_bit_cast(uint2, __builtin_convertvector(r - __builtin_convertvector(hi, f32x4), bf16x4));
 }
@@ -147,7 +155,7 @@ __device__ __forceinline__ void store_acc_interior(const Args& g, const f32x16 (
                 if (SCALE) r *= g.alpha;
                 if (g.c_bf16) {
                     *(uint2*)p = pack16x4(g, r);
-                    if (g.flags & TBOA_GEMM_C_HILO) *(uint2*)((char*)g.C2 + (p - (char*)g.C)) = pack_lo4(r);
+                    if (g.flags & TBOA_GEMM_C_HILO) *(uint2*)((char*)g.C2 + (p - (char*)g.C)) = pack_lo4(g, r);
                 }
                 else {
                     if (g.accumulate) r += *(const f32x4*)p;
@@ -175,7 +183,7 @@ __device__ __forceinline__ void store_acc_tiled(const Args& g, const f32x16 (&ac
                 if (SCALE) r *= g.alpha;
                 __hip_bfloat16* p = base + ((long long)(2 * i + (b >> 1)) * kb + j) * 512 + off;
                 *(uint2*)p = pack16x4(g, r);
-                if (g.flags & TBOA_GEMM_C_HILO) *(uint2*)((__hip_bfloat16*)g.C2 + (p - (__hip_bfloat16*)g.C)) = pack_lo4(r);
+                if (g.flags & TBOA_GEMM_C_HILO) *(uint2*)((__hip_bfloat16*)g.C2 + (p - (__hip_bfloat16*)g.C)) = pack_lo4(g, r);
             }
         }
 }
@@ -208,7 +216,10 @@ __device__ __forceinline__ void store_acc(const Args& g, const f32x16 (&acc)[4][
                     const long long idx = coff + (long long)row * g.ldc + col + e;
                     const float r = g.alpha * acc[i][j][4 * b + e];
                     if (g.c_bf16) {
-                        if (g.flags & TBOA_GEMM_C_HILO) {
+                        if (g.flags & TBOA_GEMM_C_HILO_HALF) {
+                            const _Float16 hi = (_Float16)r;
+                            ((_Float16*)g.C)[idx] = hi; ((_Float16*)g.C2)[idx] = (_Float16)(r - (float)hi);
+                        } else if (g.flags & TBOA_GEMM_C_HILO) {
                             const __hip_bfloat16 hi = __float2bfloat16(r);
                             ((__hip_bfloat16*)g.C)[idx] = hi; ((__hip_bfloat16*)g.C2)[idx] = __float2bfloat16(r - __bfloat162float(hi));
                         } else if (g.flags & TBOA_GEMM_F16) ((_Float16*)g.C)[idx] = (_Float16)r;
@@ -808,7 +819,7 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     }
     if (q.flags & TBOA_GEMM_C_HILO) {
         if (q.c_dtype != TBOA_BF16 || !q.C2 || ((uintptr_t)q.C2 & 7)) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: a (hi, lo) result needs a 16-bit C and a second buffer");
-    }
+    } else if (q.flags & TBOA_GEMM_C_HILO_HALF) return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: half pairs are a kind of (hi, lo) result");
     if (q.flags & TBOA_GEMM_C_TILED) {
         if (q.c_dtype != TBOA_BF16 || q.accumulate || q.M % 256 || q.N % 256 || q.ldc % 32 || q.strideC % 4 || q.strideC2 % 4 || ((uintptr_t)q.C & 7))
             return tboa_fail(ctx, TBOA_EINVAL, "gemm_bf16: a blocked C must be bf16 without accumulation, M and N multiples of 256, ldc a multiple of 32");

@@ -1060,7 +1060,9 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
                 }
                 // B1 = sum_h A_h^T A_h and B2^T = sum_h A_h^T (A_h - A~_h): contraction over (head of the group, t >= max(i, j)) and
                 // over the three products of (hi, lo) parts, in one pass.  B1 is symmetric: only its tiles on or below the diagonal
-                GemmBf16 b = nt(L, L, 3 * (rep / parts) * L, 1.f, pt.hi, ldpt, pt.hi, ldpt, B1f, L, TBOA_F32, 0, tiled | TBOA_GEMM_KLO | TBOA_GEMM_LOWER | hf);
+                // (half probabilities from the fused kernel carry ATTN_PROBS_HALF_SCALE each)
+                const float pa = (fused && D.f16) ? 1.f / (ATTN_PROBS_HALF_SCALE * ATTN_PROBS_HALF_SCALE) : 1.f;
+                GemmBf16 b = nt(L, L, 3 * (rep / parts) * L, pa, pt.hi, ldpt, pt.hi, ldpt, B1f, L, TBOA_F32, 0, tiled | TBOA_GEMM_KLO | TBOA_GEMM_LOWER | hf);
                 b.kseg = L; b.batch = Hkv * parts; b.batch_inner = parts; b.tag = TBOA_PROF_ATA;
                 b.strideA = (long long)L * ldpt; b.strideA2 = 16LL * (rep / parts) * L; b.strideB = b.strideA; b.strideB2 = b.strideA2;
                 b.strideC = (long long)L * L; b.strideC2 = (long long)Hkv * L * L;
@@ -1145,9 +1147,9 @@ int weight_operands(tboa_ctx* ctx, const float* W, int rows, int n, bf16* hi, bf
     return 0;
 }
 
-// sums the (hi, lo) halves of a transposed attention output OT [dq, T (+ pad)] into token-major rows O [T, dq] (bf16)
+// sums the (hi, lo) halves of a transposed attention output OT [dq, T (+ pad)] (IEEE half when f16) into token-major rows O [T, dq] (bf16)
 __global__ __launch_bounds__(256) void ot_rows_kernel(const bf16* __restrict__ OTh, const bf16* __restrict__ OTl, long long ld, int dq,
-                                                      long long T, bf16* __restrict__ O) {
+                                                      long long T, bf16* __restrict__ O, int f16) {
     __shared__ float t[64][65];
     const long long t0 = (long long)blockIdx.x * 64; const int c0 = blockIdx.y * 64;
     for (int i = threadIdx.x; i < 64 * 64; i += 256) {
@@ -1155,7 +1157,7 @@ __global__ __launch_bounds__(256) void ot_rows_kernel(const bf16* __restrict__ O
         float v = 0.f;
         if (c0 + c < dq && t0 + tt < T) {
             const long long o = (long long)(c0 + c) * ld + t0 + tt;
-            v = __bfloat162float(OTh[o]) + __bfloat162float(OTl[o]);
+            v = dec16(OTh[o], f16) + dec16(OTl[o], f16);
         }
         t[c][tt] = v;
     }
@@ -1250,7 +1252,10 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
                 TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, ldp, 2 * L, L, 3 * L));
             }
             const long long co = t0 + (long long)sl * L;
-            GemmBf16 o = nt(dh, L, 3 * L, 1.f, VTc + (long long)sl * nsg * L, ldv, P, ldp, OT + co, TP, TBOA_BF16, 0, cflag | TBOA_GEMM_C_HILO);
+            const float pa = (fused && D.f16) ? 1.f / ATTN_PROBS_HALF_SCALE : 1.f;       // half probabilities from the fused kernel are scaled
+            // (an attention output is a convex combination of values: it fits half where they do, and then leaves as a pair of halves)
+            GemmBf16 o = nt(dh, L, 3 * L, pa, VTc + (long long)sl * nsg * L, ldv, P, ldp, OT + co, TP, TBOA_BF16, 0,
+                            cflag | TBOA_GEMM_C_HILO | (D.f16 ? TBOA_GEMM_C_HILO_HALF : 0));
             o.C2 = OTl + co;
             o.kseg = L; o.batch = Hq; o.batch_inner = rep; o.tag = TBOA_PROF_PV;
             o.strideA = (long long)dh * ldv; o.strideA2 = 0;
@@ -1264,16 +1269,16 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         }
     }
     if (O_rows) {
-        hipLaunchKernelGGL(ot_rows_kernel, dim3((unsigned)((T + 63) / 64), (dq + 63) / 64), dim3(256), 0, st, OT, OTl, TP, dq, (long long)T, O_rows);
+        hipLaunchKernelGGL(ot_rows_kernel, dim3((unsigned)((T + 63) / 64), (dq + 63) / 64), dim3(256), 0, st, OT, OTl, TP, dq, (long long)T, O_rows, D.f16);
         TB_KERNEL_CHECK(ctx);
         if (!Hin_o) return 0;
     }
-    // H_in^O = (O_hi + O_lo)^T (O_hi + O_lo), R_o = alpha (dO_hi + dO_lo)^T (O_hi + O_lo), without the lo.lo terms
+    // H_in^O = (O_hi + O_lo)^T (O_hi + O_lo), R_o = alpha (dO_hi + dO_lo)^T (O_hi + O_lo), without the lo.lo terms (half or bf16 pairs)
     const GramPair ho[3] = {{OT, OT}, {OTl, OT}, {OT, OTl}};
-    TB_TRY(gram_splitk(ctx, splits, dq, 3, ho, TP, T, 1.0, 1, part, Hin_o));
+    TB_TRY(gram_splitk(ctx, splits, dq, 3, ho, TP, T, 1.0, 1, part, Hin_o, D.f16));
     if (fp) {
         const GramPair ro[3] = {{dOT, OT}, {dOTl, OT}, {dOT, OTl}};
-        TB_TRY(gram_splitk(ctx, splits, dq, 3, ro, TP, T, d->alpha, 0, part, R_o));
+        TB_TRY(gram_splitk(ctx, splits, dq, 3, ro, TP, T, d->alpha, 0, part, R_o, D.f16));
     }
     return 0;
 }

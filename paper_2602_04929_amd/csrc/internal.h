@@ -123,6 +123,7 @@ struct GemmBf16 {
 };
 // internal flag: a 16-bit result leaves as an exact-to-16-bit pair of bf16 values (hi into C, lo into C2), whatever the operands
 #define TBOA_GEMM_C_HILO 0x10000
+#define TBOA_GEMM_C_HILO_HALF 0x20000     // (with C_HILO) the pair is IEEE half, 22 significant bits, instead of bf16, 16: for values known to fit half
 int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
 
 // Transposed causal attention probabilities of all heads of one sequence as (hi, lo) pairs of 16-bit values (IEEE half
@@ -130,6 +131,8 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& g);
 // rows i up to the end of the 256-tile that holds t written (zeros beyond the diagonal).  dhi, dlo: A - A~ of a second
 // score matrix (nullptr without one).
 struct PtOut { __hip_bfloat16 *hi, *lo, *dhi, *dlo; };
+// factor on the probabilities attn_probs_t / attn_probs_rows write as IEEE half (f16 set); bf16 results are unscaled
+#define ATTN_PROBS_HALF_SCALE 16384.f
 // How the (hi, lo) pairs of Q^ and K^ are encoded, per score matrix: a device word per operand that holds the bits of the
 // largest magnitude of that operand's fp32 values, in which case the pairs are IEEE half values of the operand times
 // 2^tboa_half_exp(word) (22 significant bits wherever the magnitude is within 2^-17 of the largest), or a negative word / a
