@@ -64,7 +64,7 @@ const char* tboa_last_error(const tboa_ctx* ctx);
  * candidate need none).
  * TBOA_CTR_WEIGHTS_INT_FORM / TBOA_CTR_WEIGHTS_HILO: dequantized fp32 weight matrices handed to
  * tboa_build_hessian_out_proj or tboa_swiglu_forward that were found to be integer multiples of one step per row (one
- * bf16 GEMM with exact operands per product) / that were not and went through the general two-term split. */
+ * bf16 GEMM with exact operands per product) / that were not and were split into bf16 terms (two or three). */
 enum tboa_counter_id { TBOA_CTR_GRID_PASSES = 0, TBOA_CTR_GRID_FALLBACKS = 1, TBOA_CTR_GRID_EXACT_ROWS = 2, TBOA_CTR_GRID_SURVIVORS = 3,
                        TBOA_CTR_WEIGHTS_INT_FORM = 4, TBOA_CTR_WEIGHTS_HILO = 5 };
 int64_t tboa_counter(const tboa_ctx* ctx, int which);
@@ -126,7 +126,7 @@ int tboa_build_hessians(tboa_ctx* ctx, const tboa_attn_desc* desc,
  *   Hin_o [Hq*dh, Hq*dh] fp32;  R_o same shape or NULL (then X_fp, Wq, Wk, Wv may be NULL).
  * On the bf16 path a dequantized weight whose rows are integer multiples (|k| <= 256) of one step per row, as the W_deq
  * of tboa_quantize_layer with per-row grids is, enters its products as those integers (exact in bf16) with the steps
- * applied to the result; any other fp32 weight as an exact-to-16-bit (hi, lo) bf16 pair.  Synchronises the stream.
+ * applied to the result; any other fp32 weight as three bf16 terms that carry its 24 bits.  Synchronises the stream.
  *   fp_cache  NULL, or the buffer a tboa_build_hessians call with the same desc, X_fp, Wq, Wk filled (bf16 path, R_o
  *             requested): the projections of X_fp are then read from it and Wq, Wk may be NULL.
  */

@@ -215,6 +215,17 @@ __global__ __launch_bounds__(256) void amax_seq_kernel(const float* __restrict__
     if ((threadIdx.x & 63) == 0) atomicMax(out + blockIdx.y, __float_as_int(m));
 }
 
+// fp32 [n] -> three bf16 terms whose sum is the value to 24 bits
+__global__ void split_three_kernel(const float* __restrict__ in, bf16* __restrict__ hi, bf16* __restrict__ mid, bf16* __restrict__ lo, long long n) {
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
+        const float v = in[i];
+        const bf16 h = __float2bfloat16(v);
+        const float r = v - __bfloat162float(h);
+        const bf16 m = __float2bfloat16(r);
+        hi[i] = h; mid[i] = m; lo[i] = __float2bfloat16(r - __bfloat162float(m));
+    }
+}
+
 // fp32 [n] -> exact-to-16-bits pair of bf16
 __global__ void split_hilo_kernel(const float* __restrict__ in, bf16* __restrict__ hi, bf16* __restrict__ lo, long long n) {
     for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x) {
@@ -281,7 +292,7 @@ __global__ __launch_bounds__(256) void int_form_kernel(const float* __restrict__
 }
 
 // V^T fp32 [rows, G*L] (times row_scale, if given) -> per-sequence segments of length L: (hi, hi, lo) of V^T in segments
-// 0, 1, 2 and, when the full-precision V~^T is given, V^T - V~^T in segment 3 and V~^T in segment 4
+// 0, 1, 2 and, when the full-precision V~^T is given, (hi, hi, lo) of V~^T in segments 3, 4, 5
 __global__ void vt_segments_kernel(const float* __restrict__ in, const float* __restrict__ row_scale, const float* __restrict__ in_fp,
                                    bf16* __restrict__ out, int rows, int G, int L, int nseg, long long ld, int f16) {
     const long long tot = (long long)rows * G * L;
@@ -293,15 +304,15 @@ __global__ void vt_segments_kernel(const float* __restrict__ in, const float* __
             if (row_scale) v = v * row_scale[row];
             f4 w = {0.f, 0.f, 0.f, 0.f};
             if (in_fp) w = __builtin_nontemporal_load((const f4*)(in_fp + i));
-            union { bf16 b[4]; uint2 u; } h, l, dv, wf;
+            union { bf16 b[4]; uint2 u; } h, l, wh, wl;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 h.b[j] = enc16(v[j], f16); l.b[j] = enc16(v[j] - dec16(h.b[j], f16), f16);
-                dv.b[j] = enc16(v[j] - w[j], f16); wf.b[j] = enc16(w[j], f16);
+                wh.b[j] = enc16(w[j], f16); wl.b[j] = enc16(w[j] - dec16(wh.b[j], f16), f16);
             }
             bf16* o = out + row * ld + ((long long)s * nseg) * L + t;
             *(uint2*)o = h.u; *(uint2*)(o + L) = h.u; *(uint2*)(o + 2 * L) = l.u;
-            if (in_fp) { *(uint2*)(o + 3 * L) = dv.u; *(uint2*)(o + 4 * L) = wf.u; }
+            if (in_fp) { *(uint2*)(o + 3 * L) = wh.u; *(uint2*)(o + 4 * L) = wh.u; *(uint2*)(o + 5 * L) = wl.u; }
         }
         return;
     }
@@ -311,16 +322,18 @@ __global__ void vt_segments_kernel(const float* __restrict__ in, const float* __
         const bf16 h = enc16(v, f16);
         bf16* o = out + row * ld + ((long long)s * nseg) * L + t;
         o[0] = h; o[L] = h; o[2 * L] = enc16(v - dec16(h, f16), f16);
-        if (in_fp) { const float w = in_fp[i]; o[3 * L] = enc16(v - w, f16); o[4 * L] = enc16(w, f16); }
+        if (in_fp) { const float w = in_fp[i]; const bf16 wh = enc16(w, f16); o[3 * L] = wh; o[4 * L] = wh; o[5 * L] = enc16(w - dec16(wh, f16), f16); }
     }
 }
 
 // P[t, k] = A[t, k] (and once more at column hi2col + k, and its low part A - P[t, k] at locol + k, when those are not
 // negative), A = softmax over the first t+1 (causal) or L entries of the score row; with a
-// second score matrix S2 also P[t, dcol + k] = A[t, k] - A2[t, k], the difference taken in fp32 before rounding.
+// second score matrix S2 also P[t, dcol + k] = A[t, k] - A2[t, k], the difference taken in fp32 before rounding, or
+// (pair2) A2 itself as (hi, lo, hi) in the three segments of L columns from dcol.
 // Zero up to the next multiple of 256 (the k-loop of the consumer stops there).  One wavefront per row, y = head.
 __global__ __launch_bounds__(256) void softmax_bf16_kernel(const float* __restrict__ S, const float* __restrict__ S2, int L, int causal,
-                                                           bf16* __restrict__ P, long long ldp, long long head_stride, int hi2col, int locol, int dcol, int f16) {
+                                                           bf16* __restrict__ P, long long ldp, long long head_stride, int hi2col, int locol, int dcol, int f16,
+                                                           int pair2) {
     const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= L) return;
     const long long so = ((long long)blockIdx.y * L + t) * L;
@@ -343,7 +356,11 @@ __global__ __launch_bounds__(256) void softmax_bf16_kernel(const float* __restri
         p[k] = v;
         if (hi2col >= 0) p[hi2col + k] = v;
         if (locol >= 0) p[locol + k] = enc16(a - dec16(v, f16), f16);
-        if (s2) p[dcol + k] = enc16(k < kend ? a - __expf(s2[k] - m2) * inv2 : 0.f, f16);
+        if (s2) {
+            const float a2 = k < kend ? __expf(s2[k] - m2) * inv2 : 0.f;
+            if (pair2) { const bf16 v2 = enc16(a2, f16); p[dcol + k] = v2; p[dcol + L + k] = enc16(a2 - dec16(v2, f16), f16); p[dcol + 2 * L + k] = v2; }
+            else p[dcol + k] = enc16(a - a2, f16);
+        }
     }
 }
 
@@ -353,7 +370,7 @@ __global__ __launch_bounds__(256) void softmax_bf16_kernel(const float* __restri
 template <int NCH>
 __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __restrict__ S, const float* __restrict__ S2, int L, int causal,
                                                                 bf16* __restrict__ P, long long ldp, long long head_stride, int hi2col, int locol, int dcol,
-                                                                int blocked, int f16) {
+                                                                int blocked, int f16, int pair2) {
     const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= L) return;
     // heads from the last to the first: the score product wrote them in ascending order, so the last ones are the part of the
@@ -400,24 +417,30 @@ __global__ __launch_bounds__(256) void softmax_bf16_regs_kernel(const float* __r
     for (int c = 0; c < NCH; ++c) {
         const int k = c * 256 + lane * 4;
         if (k >= kz) continue;
-        union { bf16 h[4]; uint2 u; } pa, pl, pd;
+        union { bf16 h[4]; uint2 u; } pa, pl, pd, pe;       // pd: A - A2, or (pair2) the high part of A2 with its low part in pe
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float a = v[c][i] * inv;
+            const float a = v[c][i] * inv, a2 = s2 ? w[c][i] * inv2 : 0.f;
             pa.h[i] = enc16(a, f16);
             pl.h[i] = enc16(a - dec16(pa.h[i], f16), f16);
-            pd.h[i] = enc16(s2 ? a - w[c][i] * inv2 : 0.f, f16);
+            pd.h[i] = enc16(pair2 ? a2 : (s2 ? a - a2 : 0.f), f16);
+            pe.h[i] = enc16(a2 - dec16(pd.h[i], f16), f16);
         }
         if (blocked) {     // the head's [L, ldp] matrix in 16 x 32 blocks: 4 consecutive columns stay together
             *(uint2*)(p + tboa_blocked_offset(t, k, ldp >> 5)) = pa.u;
             if (hi2col >= 0) *(uint2*)(p + tboa_blocked_offset(t, (long long)hi2col + k, ldp >> 5)) = pa.u;
             if (locol >= 0) *(uint2*)(p + tboa_blocked_offset(t, (long long)locol + k, ldp >> 5)) = pl.u;
             if (s2) *(uint2*)(p + tboa_blocked_offset(t, dcol + k, ldp >> 5)) = pd.u;
+            if (s2 && pair2) {
+                *(uint2*)(p + tboa_blocked_offset(t, (long long)dcol + L + k, ldp >> 5)) = pe.u;
+                *(uint2*)(p + tboa_blocked_offset(t, (long long)dcol + 2 * L + k, ldp >> 5)) = pd.u;
+            }
         } else {
             *(uint2*)(p + k) = pa.u;
             if (hi2col >= 0) *(uint2*)(p + hi2col + k) = pa.u;
             if (locol >= 0) *(uint2*)(p + locol + k) = pl.u;
             if (s2) *(uint2*)(p + dcol + k) = pd.u;
+            if (s2 && pair2) { *(uint2*)(p + dcol + L + k) = pe.u; *(uint2*)(p + dcol + 2 * L + k) = pd.u; }
         }
     }
 }
@@ -793,16 +816,18 @@ int gram_splitk(tboa_ctx* ctx, int splits, int n, const bf16* A, const bf16* A_l
     return gram_splitk(ctx, splits, n, A_lo ? 2 : 1, pairs, ld, K, scale, lower, part, out);
 }
 
-// Q^ [rows, Hq, 3 dh] and K^ [rows, Hkv, 3 dh] of `rows` tokens Xr [rows, d]; weights as one or two (hi, lo) bf16 terms.
+// Q^ [rows, Hq, 3 dh] and K^ [rows, Hkv, 3 dh] of `rows` tokens Xr [rows, d]; weights as one, two or three bf16 terms.
 // amax_q, amax_k (both or neither; blocked operands of whole sequences only): one device word per sequence of the chunk each;
 // the pairs are then scaled IEEE half values and the words say by how much (see QkScale), else unscaled bf16.
 int project_qk(const Dims& D, const bf16* Xr, int rows, const bf16* Wq, const bf16* Wq_lo, const bf16* Wk, const bf16* Wk_lo,
                float* Qf, float* Kf, bf16* Qh, bf16* Kh, const float* q_scale = nullptr, const float* k_scale = nullptr,
-               int* amax_q = nullptr, int* amax_k = nullptr) {
-    TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, Wq, D.dm, Qf, D.dq, TBOA_F32, 0, 0)));
-    if (Wq_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, Wq_lo, D.dm, Qf, D.dq, TBOA_F32, 1, 0)));
-    TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk, D.dm, Kf, D.dkv, TBOA_F32, 0, 0)));
-    if (Wk_lo) TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, Wk_lo, D.dm, Kf, D.dkv, TBOA_F32, 1, 0)));
+               int* amax_q = nullptr, int* amax_k = nullptr, const bf16* Wq_lo2 = nullptr, const bf16* Wk_lo2 = nullptr) {
+    // (the smallest term first: the sum then rounds where the largest term does)
+    const bf16* tq[3] = {Wq_lo2, Wq_lo, Wq}; const bf16* tk[3] = {Wk_lo2, Wk_lo, Wk};
+    int first = 1;
+    for (const bf16* w : tq) if (w) { TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dq, D.dm, 1.f, Xr, D.dm, w, D.dm, Qf, D.dq, TBOA_F32, first ? 0 : 1, 0))); first = 0; }
+    first = 1;
+    for (const bf16* w : tk) if (w) { TB_TRY(gemm_bf16_nt(D.ctx, nt(rows, D.dkv, D.dm, 1.f, Xr, D.dm, w, D.dm, Kf, D.dkv, TBOA_F32, first ? 0 : 1, 0))); first = 0; }
     if (amax_q) {
         if (!amax_k || !qk_blocked(D) || D.dh % 32 || rows % D.L) return tboa_fail(D.ctx, TBOA_EINVAL, "project_qk: half operands need blocked whole sequences");
         const int ns = rows / D.L;
@@ -857,14 +882,14 @@ int scores_pair(const Dims& D, const bf16* Qh, const bf16* Kh, const bf16* Qhf, 
 }
 
 // probabilities in 16 x 32 blocks (per head) when `blocked`: see blocked_inputs
-int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long ldp, int hi2col, int locol, int dcol, int blocked = 0) {
+int softmax(const Dims& D, const float* Sc, const float* Sc2, bf16* P, long long ldp, int hi2col, int locol, int dcol, int blocked = 0, int pair2 = 0) {
     if (D.L % 4 == 0 && D.L <= 2048 && ldp % 4 == 0 && dcol % 4 == 0)
         hipLaunchKernelGGL(softmax_bf16_regs_kernel<8>, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P,
-                           ldp, (long long)D.L * ldp, hi2col, locol, dcol, blocked, D.f16);
+                           ldp, (long long)D.L * ldp, hi2col, locol, dcol, blocked, D.f16, pair2);
     else if (blocked) return tboa_fail(D.ctx, TBOA_EINVAL, "softmax: blocked probabilities need the in-register kernel");
     else
         hipLaunchKernelGGL(softmax_bf16_kernel, dim3((D.L + 3) / 4, D.Hq), dim3(256), 0, D.ctx->stream, Sc, Sc2, D.L, D.d->causal, P, ldp,
-                           (long long)D.L * ldp, hi2col, locol, dcol, D.f16);
+                           (long long)D.L * ldp, hi2col, locol, dcol, D.f16, pair2);
     TB_HIP(D.ctx, hipGetLastError());
     return 0;
 }
@@ -1131,10 +1156,13 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
 }
 
 // Operands for products with a dequantized weight W [rows, n] fp32: the integer form (hi = K, lo = NULL, *scale = step per
-// row) when every row has it, else the general exact-to-16-bits pair (hi, lo), *scale = NULL.  Synchronises once.
-int weight_operands(tboa_ctx* ctx, const float* W, int rows, int n, bf16* hi, bf16* lo, float* step, const bf16** lo_out, const float** scale) {
+// row) when every row has it, else the general exact-to-16-bits pair (hi, lo), *scale = NULL; with lo2 given, three terms
+// (hi, lo, lo2) that carry all 24 bits.  Synchronises once.
+int weight_operands(tboa_ctx* ctx, const float* W, int rows, int n, bf16* hi, bf16* lo, float* step, const bf16** lo_out, const float** scale,
+                    bf16* lo2 = nullptr, const bf16** lo2_out = nullptr) {
     int* flag = ctx->d_status + 4;
     *lo_out = lo; *scale = nullptr;
+    if (lo2_out) *lo2_out = nullptr;
     TB_HIP(ctx, hipMemsetAsync(flag, 0, sizeof(int), ctx->stream));
     hipLaunchKernelGGL(int_form_kernel, dim3(rows), dim3(256), 0, ctx->stream, W, n, hi, step, flag);
     TB_KERNEL_CHECK(ctx);
@@ -1142,9 +1170,35 @@ int weight_operands(tboa_ctx* ctx, const float* W, int rows, int n, bf16* hi, bf
     TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (ctx->h_status[4] == 0) { *lo_out = nullptr; *scale = step; ++ctx->counters[TBOA_CTR_WEIGHTS_INT_FORM]; return 0; }
     ++ctx->counters[TBOA_CTR_WEIGHTS_HILO];
+    if (lo2 && lo2_out) {
+        *lo2_out = lo2;
+        hipLaunchKernelGGL(split_three_kernel, dim3(g1((long long)rows * n)), dim3(256), 0, ctx->stream, W, hi, lo, lo2, (long long)rows * n);
+    } else
     hipLaunchKernelGGL(split_hilo_kernel, dim3(g1((long long)rows * n)), dim3(256), 0, ctx->stream, W, hi, lo, (long long)rows * n);
     TB_KERNEL_CHECK(ctx);
     return 0;
+}
+
+// (d_hi, d_lo) <- the (hi, lo) pair of (a_hi + a_lo) - (d_hi + d_lo), element by element (16-bit values: IEEE half when f16)
+__global__ void pair_minus_kernel(const bf16* __restrict__ a_hi, const bf16* __restrict__ a_lo, bf16* __restrict__ d_hi, bf16* __restrict__ d_lo,
+                                  long long n, int f16) {
+    const long long tid = blockIdx.x * (long long)blockDim.x + threadIdx.x, nth = (long long)gridDim.x * blockDim.x;
+    const long long n8 = ((((uintptr_t)a_hi | (uintptr_t)a_lo | (uintptr_t)d_hi | (uintptr_t)d_lo) & 15) == 0) ? n / 8 : 0;
+    for (long long i = tid; i < n8; i += nth) {
+        union { uint4 u; bf16 b[8]; } ah, al, dh, dl;
+        ah.u = ((const uint4*)a_hi)[i]; al.u = ((const uint4*)a_lo)[i]; dh.u = ((const uint4*)d_hi)[i]; dl.u = ((const uint4*)d_lo)[i];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float r = (dec16(ah.b[k], f16) - dec16(dh.b[k], f16)) + (dec16(al.b[k], f16) - dec16(dl.b[k], f16));
+            dh.b[k] = enc16(r, f16); dl.b[k] = enc16(r - dec16(dh.b[k], f16), f16);
+        }
+        ((uint4*)d_hi)[i] = dh.u; ((uint4*)d_lo)[i] = dl.u;
+    }
+    for (long long i = 8 * n8 + tid; i < n; i += nth) {
+        const float r = (dec16(a_hi[i], f16) - dec16(d_hi[i], f16)) + (dec16(a_lo[i], f16) - dec16(d_lo[i], f16));
+        const bf16 h = enc16(r, f16);
+        d_hi[i] = h; d_lo[i] = enc16(r - dec16(h, f16), f16);
+    }
 }
 
 // sums the (hi, lo) halves of a transposed attention output OT [dq, T (+ pad)] (IEEE half when f16) into token-major rows O [T, dq] (bf16)
@@ -1178,10 +1232,12 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
     const int T = D.T, dm = D.dm, Hq = D.Hq, dh = D.dh, L = D.L, dq = D.dq, dkv = D.dkv, rep = D.rep;
     const bool fp = X_fp && R_o;
     int G = d->seq_chunk > 0 ? d->seq_chunk : 8; if (G > D.S) G = D.S;
-    const int nsg = fp ? 5 : 3, nsp = fp ? 4 : 3, splits = pick_splits(D.S);   // segments of V^T / of P
     const bool fused = d->causal && qk_blocked(D) && attn_probs_t_supported(D.L, D.dh);     // no score matrices in memory
+    // segments of V^T ((hi, hi, lo) per path) and of P (the same, or (hi, lo) per path from the fused kernel: its products name
+    // their three operand pairs instead of reading a repeated segment)
+    const int nsg = fp ? 6 : 3, nsp = fused ? (fp ? 4 : 2) : (fp ? 6 : 3), splits = pick_splits(D.S);
     const long long TP = (long long)T + PADE, ldp = (long long)nsp * L + PADE;
-    bf16 *Wqh, *Wql, *Wkh, *Wkl, *Wvh, *Wvl, *Qh, *Kh, *Qhf, *Khf, *P, *VTc, *OT, *OTl, *dOT, *dOTl;
+    bf16 *Wqh, *Wql, *Wkh, *Wkl, *Wvh, *Wvl, *Wq3, *Wk3, *Wv3, *Qh, *Kh, *Qhf, *Khf, *P, *VTc, *OT, *OTl, *dOT, *dOTl;
     float *Qf, *Kf, *VT32, *VT32f, *Sc, *Scf, *part, *steps;
     int* amx;      // [q | k | q~ | k~] x G (see QkScale)
     for (int pass = 0; pass < 2; ++pass) {
@@ -1189,6 +1245,7 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         Wqh = ar.get<bf16>((size_t)dq * dm); Wql = ar.get<bf16>((size_t)dq * dm);
         Wkh = ar.get<bf16>((size_t)dkv * dm); Wkl = ar.get<bf16>((size_t)dkv * dm);
         Wvh = ar.get<bf16>((size_t)dkv * dm); Wvl = ar.get<bf16>((size_t)dkv * dm);
+        Wq3 = ar.get<bf16>((size_t)dq * dm); Wk3 = ar.get<bf16>((size_t)dkv * dm); Wv3 = ar.get<bf16>((size_t)dkv * dm);
         Qf = ar.get<float>((size_t)G * L * dq); Kf = ar.get<float>((size_t)G * L * dkv); VT32 = ar.get<float>((size_t)dkv * G * L);
         VT32f = fp ? ar.get<float>((size_t)dkv * G * L) : nullptr; Scf = (fp && !fused) ? ar.get<float>((size_t)Hq * L * L) : nullptr;
         Qh = ar.get<bf16>((size_t)G * L * dq * 3); Kh = ar.get<bf16>((size_t)G * L * dkv * 3);
@@ -1203,12 +1260,14 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         if (!pass) TB_TRY(tboa_ws_reserve(ctx, ar.off));
     }
     hipStream_t st = ctx->stream;
-    // dequantized weights in integer form (one GEMM per product) or as exact-to-16-bits (hi, lo) bf16 pairs (two)
-    const bf16 *Wql_u = nullptr, *Wkl_u = nullptr, *Wvl_u = nullptr; const float *sq = nullptr, *sk = nullptr, *sv = nullptr;
+    // dequantized weights in integer form (one GEMM per product) or as three bf16 terms that carry all 24 bits (three: with two
+    // terms the 2^-17 they leave out reaches the scores, and A' with them, at 1e-4)
+    const bf16 *Wql_u = nullptr, *Wkl_u = nullptr, *Wvl_u = nullptr, *Wq3_u = nullptr, *Wk3_u = nullptr, *Wv3_u = nullptr;
+    const float *sq = nullptr, *sk = nullptr, *sv = nullptr;
     if (wq_dtype == TBOA_F32) {
-        TB_TRY(weight_operands(ctx, (const float*)Wq_deq, dq, dm, Wqh, Wql, steps, &Wql_u, &sq));
-        TB_TRY(weight_operands(ctx, (const float*)Wk_deq, dkv, dm, Wkh, Wkl, steps + dq, &Wkl_u, &sk));
-        TB_TRY(weight_operands(ctx, (const float*)Wv_deq, dkv, dm, Wvh, Wvl, steps + dq + dkv, &Wvl_u, &sv));
+        TB_TRY(weight_operands(ctx, (const float*)Wq_deq, dq, dm, Wqh, Wql, steps, &Wql_u, &sq, Wq3, &Wq3_u));
+        TB_TRY(weight_operands(ctx, (const float*)Wk_deq, dkv, dm, Wkh, Wkl, steps + dq, &Wkl_u, &sk, Wk3, &Wk3_u));
+        TB_TRY(weight_operands(ctx, (const float*)Wv_deq, dkv, dm, Wvh, Wvl, steps + dq + dkv, &Wvl_u, &sv, Wv3, &Wv3_u));
     } else { Wqh = (bf16*)Wq_deq; Wkh = (bf16*)Wk_deq; Wvh = (bf16*)Wv_deq; }      // bf16 weights are exact operands as they are
     // half operands when the activations fit half; a value V = W_v x beyond the range of half (|x|_max ||w||_1 > 65504) would
     // turn infinite there and surface as a non-finite Hessian, which tboa_quantize_layer rejects
@@ -1221,11 +1280,14 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
         const bf16* Xc = X + t0 * dm;
         // V'^T = Wv_deq Xc^T (fp32; the row steps of the integer form are applied by vt_segments_kernel) and the
         // full-precision V~^T = Wv X~c^T
-        TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvh, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 0, 0)));
-        if (Wvl_u) TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wvl_u, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, 1, 0)));
+        {
+            const bf16* tv[3] = {Wv3_u, Wvl_u, Wvh};       // the smallest term first
+            int first = 1;
+            for (const bf16* w : tv) if (w) { TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, w, dm, Xc, dm, VT32, (long long)Gc * L, TBOA_F32, first ? 0 : 1, 0))); first = 0; }
+        }
         int *aq = fused ? amx : nullptr, *ak = fused ? amx + G : nullptr;
         const int *aqf = fused ? amx + 2 * G : nullptr, *akf = fused ? amx + 3 * G : nullptr;
-        TB_TRY(project_qk(D, Xc, Gc * L, Wqh, Wql_u, Wkh, Wkl_u, Qf, Kf, Qh, Kh, sq, sk, aq, ak));
+        TB_TRY(project_qk(D, Xc, Gc * L, Wqh, Wql_u, Wkh, Wkl_u, Qf, Kf, Qh, Kh, sq, sk, aq, ak, Wq3_u, Wk3_u));
         if (fp) {
             TB_TRY(gemm_bf16_nt(ctx, nt(dkv, Gc * L, dm, 1.f, Wv, dm, X_fp + t0 * dm, dm, VT32f, (long long)Gc * L, TBOA_F32, 0, 0)));
             if (fp_cache) {     // projections of X_fp by W_Q, W_K as tboa_build_hessians left them, with the words that say how
@@ -1239,9 +1301,10 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
                            nsg, ldv, D.f16);
         TB_KERNEL_CHECK(ctx);
         for (int sl = 0; sl < Gc; ++sl) {
-            // V^T segments [V'hi | V'hi | V'lo | V' - V~ | V~], P = [A'hi | A'lo | A'hi | A' - A~]:
-            // O^T_h = [V'hi | V'hi | V'lo] [A'hi | A'lo | A'hi]^T ;  (O - O~)^T_h = [V' - V~ | V~] [A'hi | A' - A~]^T,
-            // both left as exact-to-16-bit (hi, lo) pairs of bf16
+            // V^T segments [V'hi | V'hi | V'lo | V~hi | V~hi | V~lo], P = [A'hi | A'lo | A'hi | A~hi | A~lo | A~hi] ([A'hi | A'lo | A~hi | A~lo] fused):
+            // O^T_h = [V'hi | V'hi | V'lo] [A'hi | A'lo | A'hi]^T and O~^T_h likewise from the second halves, both left as (hi, lo)
+            // pairs; the deviation O - O~ is taken from the two pairs afterwards (its 22 bits then hold 1e-5 of a difference that
+            // is a few percent of either: products of single half values of V' - V~, V~ and A' - A~ left 1e-4)
             if (fused) {      // scores and softmax in one kernel, nothing of the scores stored
                 const long long qo = (long long)sl * Hq * L * 3 * dh, ko = (long long)sl * D.Hkv * L * 3 * dh;
                 const QkScale qs{aq + sl, ak + sl, fp ? aqf + sl : nullptr, fp ? akf + sl : nullptr};
@@ -1249,7 +1312,7 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             } else {
                 if (fp) TB_TRY(scores_pair(D, Qh, Kh, Qhf, Khf, sl, Sc, Scf));
                 else TB_TRY(scores(D, Qh, Kh, sl, Sc));
-                TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, ldp, 2 * L, L, 3 * L));
+                TB_TRY(softmax(D, Sc, fp ? Scf : nullptr, P, ldp, 2 * L, L, 3 * L, 0, 1));
             }
             const long long co = t0 + (long long)sl * L;
             const float pa = (fused && D.f16) ? 1.f / ATTN_PROBS_HALF_SCALE : 1.f;       // half probabilities from the fused kernel are scaled
@@ -1261,12 +1324,25 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             o.strideA = (long long)dh * ldv; o.strideA2 = 0;
             o.strideB = (long long)rep * L * ldp; o.strideB2 = (long long)L * ldp;
             o.strideC = (long long)rep * dh * TP; o.strideC2 = (long long)dh * TP;
+            if (fused) {
+                o.nterms = 3;
+                o.termA[0] = o.A; o.termA[1] = o.A; o.termA[2] = o.A + 2 * L;
+                o.termB[0] = P; o.termB[1] = P + L; o.termB[2] = P;
+            }
             TB_TRY(gemm_bf16_nt(ctx, o));
-            if (fp) {
-                o.A = VTc + ((long long)sl * nsg + 3) * L; o.B = P + 2 * L; o.K = 2 * L; o.C = dOT + co; o.C2 = dOTl + co;
+            if (fp) {       // O~^T for now
+                o.A = VTc + ((long long)sl * nsg + 3) * L; o.B = P + (fused ? 2 : 3) * L; o.C = dOT + co; o.C2 = dOTl + co;
+                if (fused) {
+                    o.termA[0] = o.A; o.termA[1] = o.A; o.termA[2] = o.A + 2 * L;
+                    o.termB[0] = o.B; o.termB[1] = o.B + L; o.termB[2] = o.B;
+                }
                 TB_TRY(gemm_bf16_nt(ctx, o));
             }
         }
+    }
+    if (fp) {     // (dOT, dOTl) <- O^T - O~^T
+        hipLaunchKernelGGL(pair_minus_kernel, dim3(g1((long long)dq * TP / 8)), dim3(256), 0, st, OT, OTl, dOT, dOTl, (long long)dq * TP, D.f16);
+        TB_KERNEL_CHECK(ctx);
     }
     if (O_rows) {
         hipLaunchKernelGGL(ot_rows_kernel, dim3((unsigned)((T + 63) / 64), (dq + 63) / 64), dim3(256), 0, st, OT, OTl, TP, dq, (long long)T, O_rows, D.f16);

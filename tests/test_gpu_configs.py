@@ -150,6 +150,30 @@ def check_out_proj_rows(c, n_rows, seed):
     check_returned_loss(out["o"], blk["Wo"], out["Hin_o"], None, out["R_o"], 1, label="o")
 
 
+def check_out_proj_block(c, h):
+    """The d_h x d_h diagonal block of query head h of H_in^O = O^T O and of R_o = alpha (O - O~)^T O against the oracle's sums
+    over all sequences: O_h = A'_h V'_g from the DEQUANTIZED W_Q, W_K, W_V the library returned, on X; O~_h from the
+    full-precision weights on X~ (Table 1, layer-wise row, with the attention output as the layer's input)."""
+    cfg, blk, out = c["cfg"], c["blk"], c["out"]
+    dh, rep_ = cfg.head_dim, cfg.n_q_heads // cfg.n_kv_heads
+    g = h // rep_
+    qr, kr = slice(h * dh, (h + 1) * dh), slice(g * dh, (g + 1) * dh)
+    wq_d, wk_d, wv_d = f64(out["q"]["W_deq"][qr]), f64(out["k"]["W_deq"][kr]), f64(out["v"]["W_deq"][kr])
+    wq, wk, wv = f64(blk["Wq"][qr]), f64(blk["Wk"][kr]), f64(blk["Wv"][kr])
+    H = np.zeros((dh, dh)); R = np.zeros((dh, dh)); dd = np.zeros((dh, dh))
+    print("  oracle attention outputs of query head %d" % h, flush=True)
+    for s_ in range(cfg.n_seqs):
+        xs, xf = f64(blk["X"][s_]), f64(blk["X_fp"][s_])
+        A, _, _ = O.attention_probs(xs, wq_d, wk_d)
+        Af, _, _ = O.attention_probs(xf, wq, wk)
+        Oh = A @ (xs @ wv_d.T); dO = Oh - Af @ (xf @ wv.T)
+        H += Oh.T @ Oh; R += ALPHA * dO.T @ Oh; dd += dO.T @ dO
+    eH = (np.abs(f64(out["Hin_o"][qr, qr]) - H) / np.sqrt(np.outer(np.diag(H), np.diag(H)))).max()
+    eR = (np.abs(f64(out["R_o"][qr, qr]) - R) / (ALPHA * np.sqrt(np.outer(np.diag(dd), np.diag(H))))).max()
+    print("  head %d block of H_in^O: rel err %.2e, of R_o: %.2e" % (h, eH, eR), flush=True)
+    assert eH <= 2e-6 and eR <= 1e-5
+
+
 def test_llama2_13b_shape_groupwise_int3(lib):
     """INT3 with groups of 128 in-channels at d = 5120: a head of W_Q, a head of W_V (per-head H_in: its group grids use that
     head's own Hessian blocks), rows of W_O (group-wise grids without out-channel coupling); sampled Hessian entries."""
@@ -161,6 +185,7 @@ def test_llama2_13b_shape_groupwise_int3(lib):
         check_head(c, "q", 21)
         check_head(c, "v", 17)
         check_out_proj_rows(c, 24, 22)
+        check_out_proj_block(c, 30)
     finally:
         release(c)
 
@@ -200,6 +225,12 @@ def test_llama2_70b_shape_out_proj_rows(c70):
     check_out_proj_rows(c70, 24, 23)
 
 
+def test_llama2_70b_shape_out_proj_hessian_block(c70):
+    if "out" not in c70:
+        quantize_block(c70)
+    check_out_proj_block(c70, 43)
+
+
 def test_llama2_7b_w4a4_shape(lib):
     c = build(lib, "llama2-7b-w4a4")
     try:
@@ -215,5 +246,6 @@ def test_llama2_7b_w4a4_shape(lib):
         check_head(c, "q", 3)
         check_head(c, "v", 9)
         check_out_proj_rows(c, 24, 24)
+        check_out_proj_block(c, 9)
     finally:
         release(c)

@@ -120,7 +120,9 @@ def test_zero_and_tiny_sequences_in_the_fused_scores_kernel(ctx):
     wH, wR = O.build_hessian_out_proj(np64(b["X"]), np64(b["X_fp"]), *[np64(w) for w in deq], np64(b["Wq"]), np64(b["Wk"]), np64(b["Wv"]),
                                       4, 2, 32, alpha=0.25)
     assert torch.isfinite(Hin_o).all() and torch.isfinite(R_o).all()
-    assert rel_err(np64(Hin_o), wH) <= 3e-5 and rel_err(np64(R_o), wR) <= 1e-3
+    eH, eR = rel_err(np64(Hin_o), wH), rel_err(np64(R_o), wR)
+    print("zero and tiny sequences: Hin_o %.2e R_o %.2e" % (eH, eR), flush=True)
+    assert eH <= 1e-6 and eR <= 1e-5
 
 
 def test_bf16_path_long_sequence(ctx):
@@ -171,11 +173,14 @@ def test_out_proj_bf16(ctx, d, L, dh):
                                       4, 2, dh, alpha=0.25)
     eH, eR = rel_err(np64(Hin_o), wH), rel_err(np64(R_o), wR)
     print("Hin_o %.2e R_o %.2e" % (eH, eR), flush=True)
-    # probabilities, values and attention outputs are (hi, lo) pairs; the deviations are single half-precision values, and R_o
-    # (noise-like here: measured against its own largest entry) shows their 11 bits
-    assert eH <= 3e-5 and eR <= 1e-3
+    # probabilities, values and attention outputs of both paths are (hi, lo) pairs, the deviation O - O~ is taken from the two
+    # attention outputs, and these weights (no grid structure) enter as three bf16 terms, all 24 bits.  With the fused scores +
+    # softmax kernel the scores come from 22-bit operands; the stored-scores path (L = 320) multiplies 16-bit pairs of Q and K,
+    # and the 1e-4 that leaves on a logit shows in the deviation term (noise-like here, measured against its own largest entry)
+    fused = L % 256 == 0
+    assert eH <= (2e-6 if fused else 1e-5) and eR <= (1e-5 if fused else 3e-4)
     H2, R2 = ctx.build_hessian_out_proj(b["X"], None, *deq, None, None, None, 4, 2, dh, seq_chunk=3)
-    assert R2 is None and rel_err(np64(H2), wH) <= 3e-5
+    assert R2 is None and rel_err(np64(H2), wH) <= 1e-5
 
 
 @pytest.mark.parametrize("dm,L", [(264, 320), (256, 256), (264, 256)])
@@ -221,7 +226,7 @@ def uniform_grid_weights(w, bits, g):
 @pytest.mark.parametrize("bits", [2, 4])
 def test_out_proj_bf16_integer_form_weights(ctx, lib, bits):
     """Dequantized weights that sit on a per-row uniform grid enter their products as exact small integers (one bf16 GEMM,
-    steps applied afterwards); a weight without that structure in the same call keeps the two-term split."""
+    steps applied afterwards); a weight without that structure in the same call is split into bf16 terms."""
     cfg = synth.scaled(synth.CONFIGS["llama2-7b"], d_model=264, n_q_heads=4, n_kv_heads=2, head_dim=32, n_seqs=3, seq_len=320, n_outlier=3)
     b = synth.make_block(cfg, seed=6, device="cuda")
     g = torch.Generator(device="cuda"); g.manual_seed(2)
@@ -233,7 +238,7 @@ def test_out_proj_bf16_integer_form_weights(ctx, lib, bits):
                                       4, 2, 32, alpha=0.25)
     eH, eR = rel_err(np64(Hin_o), wH), rel_err(np64(R_o), wR)
     print("integer-form weights, %d bits: Hin_o %.2e R_o %.2e" % (bits, eH, eR), flush=True)
-    assert eH <= 2e-5 and eR <= 1e-3
+    assert eH <= 1e-5 and eR <= 5e-5        # exact weight operands: what is left is the scores' 16-bit pairs of Q and K (stored-scores path)
     deq[1] = deq[1] * (1 + 0.01 * torch.randn(deq[1].shape, generator=g, device="cuda"))     # W_K off the grid
     H2, _ = ctx.build_hessian_out_proj(b["X"], None, *deq, None, None, None, 4, 2, 32, seq_chunk=3)
     assert ctx.counter(4) == n_int + 5 and ctx.counter(5) == n_split + 1
