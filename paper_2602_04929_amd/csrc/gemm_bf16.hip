@@ -45,6 +45,7 @@ struct Args {
     const __hip_bfloat16* B; long long ldb;
     void* C; long long ldc;
     void* C2;                   // TBOA_GEMM_C_HILO: receives the low parts, same layout as C
+    float lo_scale;             // ... times this factor (half pairs: keeps the low parts out of the subnormal range)
     int c_bf16, accumulate, flags;   // c_bf16: C holds 16-bit values (bf16, or IEEE half with TBOA_GEMM_F16)
     int vec_c;                  // C rows and batch offsets allow 16-byte (fp32) / 8-byte (bf16) accesses at columns that are multiples of 4
     int batch_inner, kseg;
@@ -130,7 +131,7 @@ __device__ __forceinline__ uint2 pack16x4(const Args& g, f32x4 r) {
 __device__ __forceinline__ uint2 pack_lo4(const Args& g, f32x4 r) {
     if (g.flags & TBOA_GEMM_C_HILO_HALF) {
         const f16x4 hi = __builtin_convertvector(r, f16x4);
-        return __builtin_bit_cast(uint2, __builtin_convertvector(r - __builtin_convertvector(hi, f32x4), f16x4));
+        return __builtin_bit_cast(uint2, __builtin_convertvector((r - __builtin_convertvector(hi, f32x4)) * g.lo_scale, f16x4));
     }
     const bf16x4 hi = __builtin_convertvector(r, bf16x4);
     return __builtin_bit_cast(uint2, __builtin_convertvector(r - __builtin_convertvector(hi, f32x4), bf16x4));
@@ -218,7 +219,7 @@ __device__ __forceinline__ void store_acc(const Args& g, const f32x16 (&acc)[4][
                     if (g.c_bf16) {
                         if (g.flags & TBOA_GEMM_C_HILO_HALF) {
                             const _Float16 hi = (_Float16)r;
-                            ((_Float16*)g.C)[idx] = hi; ((_Float16*)g.C2)[idx] = (_Float16)(r - (float)hi);
+                            ((_Float16*)g.C)[idx] = hi; ((_Float16*)g.C2)[idx] = (_Float16)((r - (float)hi) * g.lo_scale);
                         } else if (g.flags & TBOA_GEMM_C_HILO) {
                             const __hip_bfloat16 hi = __float2bfloat16(r);
                             ((__hip_bfloat16*)g.C)[idx] = hi; ((__hip_bfloat16*)g.C2)[idx] = __float2bfloat16(r - __bfloat162float(hi));
@@ -841,7 +842,7 @@ int gemm_bf16_nt(tboa_ctx* ctx, const GemmBf16& q) {
     Args a{};
     a.sched = nullptr; a.rounds = 0;
     a.M = q.M; a.N = q.N; a.K = q.K; a.alpha = q.alpha;
-    a.A = q.A; a.lda = q.lda; a.B = q.B; a.ldb = q.ldb; a.C = q.C; a.ldc = q.ldc; a.C2 = q.C2;
+    a.A = q.A; a.lda = q.lda; a.B = q.B; a.ldb = q.ldb; a.C = q.C; a.ldc = q.ldc; a.C2 = q.C2; a.lo_scale = q.lo_scale;
     a.c_bf16 = (q.c_dtype == TBOA_BF16); a.accumulate = q.accumulate; a.flags = q.flags;
     a.vec_c = q.ldc % 4 == 0 && q.strideC % 4 == 0 && q.strideC2 % 4 == 0 && ((uintptr_t)q.C & 15) == 0;
     a.batch_inner = q.batch_inner > 0 ? q.batch_inner : 1;

@@ -751,7 +751,7 @@ int pick_splits(int n_seqs) {
 }
 
 // Whether the activations fit IEEE half (|x| < 2^15, finite): one reduction over each array, one read-back.
-int fits_half(tboa_ctx* ctx, const bf16* X, const bf16* X_fp, long long n, int* fits) {
+int fits_half(tboa_ctx* ctx, const bf16* X, const bf16* X_fp, long long n, int* fits, float* amax = nullptr) {
     int* w = ctx->d_status + 5;
     TB_HIP(ctx, hipMemsetAsync(w, 0, sizeof(int), ctx->stream));
     hipLaunchKernelGGL(absmax_bf16_kernel, dim3(2048), dim3(256), 0, ctx->stream, X, n, w);
@@ -761,6 +761,7 @@ int fits_half(tboa_ctx* ctx, const bf16* X, const bf16* X_fp, long long n, int* 
     TB_HIP(ctx, hipStreamSynchronize(ctx->stream));
     float m; memcpy(&m, ctx->h_status + 5, sizeof(float));
     *fits = (m < 32768.f) ? 1 : 0;
+    if (amax) *amax = m;
     return 0;
 }
 
@@ -947,7 +948,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     // the far corner over 256, so with few batch entries the longest tile alone would set the time of the launch
     const int parts = (Hkv < 32 && rep % 2 == 0) ? 2 : 1;
     bf16 *XT, *dXh, *dXl, *Qh, *Kh, *Qhf, *Khf, *P, *XcT, *YT, *dYT;
-    bf16 *Bcat = nullptr, *XgT = nullptr, *YTl = nullptr, *dYTl = nullptr;
+    bf16 *Bcat = nullptr, *XgT = nullptr, *XgTh = nullptr, *YTl = nullptr, *dYTl = nullptr;
     PtOut pt{nullptr, nullptr, nullptr, nullptr};
     float *part, *Qf, *Kf, *Sc, *Scf, *B1f = nullptr, *B2f = nullptr;
     int* amx;      // [q | k | q~ | k~] x G: largest magnitudes of the chunk's projections, per sequence (see QkScale)
@@ -969,7 +970,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
             pt.dhi = rv ? ar.get<bf16>((size_t)Hkv * L * ldpt) : nullptr; pt.dlo = rv ? ar.get<bf16>((size_t)Hkv * L * ldpt) : nullptr;
             B1f = ar.get<float>((size_t)parts * Hkv * L * L); B2f = rv ? ar.get<float>((size_t)parts * Hkv * L * L) : nullptr;
             Bcat = ar.get<bf16>((size_t)Hkv * L * ldbc);
-            XgT = ar.get<bf16>((size_t)dm * ldg);
+            XgT = ar.get<bf16>((size_t)dm * ldg); XgTh = ar.get<bf16>((size_t)dm * ldg);
             YT = ar.get<bf16>((size_t)Hkv * dm * ldg); YTl = ar.get<bf16>((size_t)Hkv * dm * ldg);
             dYT = rv ? ar.get<bf16>((size_t)Hkv * dm * ldg) : nullptr; dYTl = rv ? ar.get<bf16>((size_t)Hkv * dm * ldg) : nullptr;
         } else {
@@ -1026,11 +1027,25 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
     }
     // ---- H_in (and R) of W_V
     if (!Hin_v) return 0;
-    TB_TRY(fits_half(ctx, X, rv ? X_fp : nullptr, (long long)T * dm, &D.f16));
+    float xmax = 0.f;
+    TB_TRY(fits_half(ctx, X, rv ? X_fp : nullptr, (long long)T * dm, &D.f16, &xmax));
     // the Gram sums of the probabilities reach rep L where every query attends to one token (entry (i, i) of sum_h A_h^T A_h
     // is at most the number of (head, query) pairs): beyond the range of half they are carried as bf16 pairs
     if ((long long)rep * L >= 60000) D.f16 = 0;
     const int hf = D.f16 ? TBOA_GEMM_F16 : 0;
+    // Summed form with half operands: T1 = B1 X and Z leave their products as pairs of halves (22 bits; as pairs of bf16, 16
+    // bits, their rounding was what limited H_in^V), so the last products read a half copy of X^T (exact: bf16 has fewer
+    // bits).  |T1| <= (row sum of B1) max|X| <= rep L max|X| and |Z| <= 3 times that (B1 dX + B2^T X~, |dX| <= 2 max, row sums of
+    // |B2| <= 2 rep L): the products scale their results by a power of two that brings this bound under 2^15, and store the
+    // low parts times 2^11 (the low part of a half is at most 2^-12 of it: no overflow, and normal numbers wherever the
+    // high part is above 2^-13); the last products take the factors back out.
+    const bool half_y = grouped && D.f16;
+    int ey = 0, ez = 0;
+    if (half_y) {
+        const double bound = (double)rep * L * (xmax > 0.f ? xmax : 1.f);
+        while (ldexp(bound, -ey) >= 32768.0) ++ey;
+        ez = ey + 2;
+    }
     TB_TRY(launch_fill_f32(ctx, Hin_v, (int64_t)Hkv * dd, 0.f));
     if (rv) TB_TRY(launch_fill_f32(ctx, R_v, (int64_t)Hkv * dd, 0.f));
     const int cflag = d->causal ? TBOA_GEMM_CAUSAL_K : 0;
@@ -1061,6 +1076,7 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
                     if (rv) TB_TRY(transpose(D, xf, nullptr, dm, L, dm, o + 16LL * (4 + c) * L, nullptr, nullptr, ldx, 1, D.f16));
                 }
                 TB_TRY(transpose(D, xs, nullptr, dm, L, dm, XgT + 16LL * sl * L, nullptr, nullptr, ldg, 1, 0));
+                if (half_y) TB_TRY(transpose(D, xs, nullptr, dm, L, dm, XgTh + 16LL * sl * L, nullptr, nullptr, ldg, 1, 1));
             } else if (!rv) TB_TRY(transpose(D, xs, nullptr, dm, L, dm, o, nullptr, nullptr, ldx, bin, D.f16));
             else {
                 const bf16* xf = X_fp + (t0 + (long long)sl * L) * dm;
@@ -1104,27 +1120,31 @@ int build_hessians_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf16* X, c
                                    (long long)L * ldbc, D.f16);
                 TB_KERNEL_CHECK(ctx);
                 // T1^T = [X_s^T | X_s^T] [B1_hi | B1_lo]^T and Z^T = [dX_s^T | dX_s^T | X~_s^T | X~_s^T] [B1_hi | B1_lo | B2^T_hi | B2^T_lo]^T,
-                // each left as a (hi, lo) pair of bf16
-                GemmBf16 y = nt(dm, L, 2 * L, 1.f, XcT + 16LL * sl * nsx * L, ldx, Bcat, ldbc, YT + 16LL * sl * L, ldg, TBOA_BF16, 0,
-                                tiled | TBOA_GEMM_C_TILED | TBOA_GEMM_C_HILO | hf);
-                y.C2 = YTl + 16LL * sl * L;
+                // each left as a (hi, lo) pair: scaled halves (see half_y above), or bf16
+                GemmBf16 y = nt(dm, L, 2 * L, half_y ? (float)ldexp(1.0, -ey) : 1.f, XcT + 16LL * sl * nsx * L, ldx, Bcat, ldbc, YT + 16LL * sl * L, ldg,
+                                TBOA_BF16, 0, tiled | TBOA_GEMM_C_TILED | TBOA_GEMM_C_HILO | hf | (half_y ? TBOA_GEMM_C_HILO_HALF : 0));
+                y.C2 = YTl + 16LL * sl * L; y.lo_scale = half_y ? 2048.f : 1.f;
                 y.batch = Hkv; y.strideA = 0; y.strideB = (long long)L * ldbc; y.strideC = (long long)dm * ldg; y.tag = TBOA_PROF_AX;
                 TB_TRY(gemm_bf16_nt(ctx, y));
                 if (rv) {
                     y.A = XcT + 16LL * ((long long)sl * nsx + 2) * L; y.K = 4 * L; y.C = dYT + 16LL * sl * L; y.C2 = dYTl + 16LL * sl * L;
+                    if (half_y) y.alpha = (float)ldexp(1.0, -ez);
                     TB_TRY(gemm_bf16_nt(ctx, y));
                 }
             }
-            // over the chunk: H_in^V[g] += (T1_hi + T1_lo)^T X,  R_v[g] += alpha (Z_hi + Z_lo)^T X   (bf16 operands: X is exact)
-            GemmBf16 h = nt(dm, dm, Gc * L, 1.f, YT, ldg, XgT, ldg, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER | tiled);
+            // over the chunk: H_in^V[g] += (T1_hi + T1_lo)^T X,  R_v[g] += alpha (Z_hi + Z_lo)^T X   (X is exact, as bf16 or as half)
+            const int hy = half_y ? TBOA_GEMM_F16 : 0;
+            GemmBf16 h = nt(dm, dm, Gc * L, (float)ldexp(1.0, ey), YT, ldg, half_y ? XgTh : XgT, ldg, Hin_v, dm, TBOA_F32, 1, TBOA_GEMM_LOWER | tiled | hy);
             h.batch = Hkv; h.strideA = (long long)dm * ldg; h.strideB = 0; h.strideC = dd; h.tag = TBOA_PROF_HV_SYRK;
             h.flags &= ~TBOA_GEMM_PERSISTENT;
             TB_TRY(gemm_bf16_nt(ctx, h));
-            h.A = YTl; TB_TRY(gemm_bf16_nt(ctx, h));
+            h.A = YTl; if (half_y) h.alpha = (float)ldexp(1.0, ey - 11);
+            TB_TRY(gemm_bf16_nt(ctx, h));
             if (rv) {
-                h.tag = TBOA_PROF_RV; h.C = R_v; h.flags = tiled; h.alpha = (float)d->alpha;
+                h.tag = TBOA_PROF_RV; h.C = R_v; h.flags = tiled | hy; h.alpha = (float)ldexp(d->alpha, ez);
                 h.A = dYT; TB_TRY(gemm_bf16_nt(ctx, h));
-                h.A = dYTl; TB_TRY(gemm_bf16_nt(ctx, h));
+                h.A = dYTl; if (half_y) h.alpha = (float)ldexp(d->alpha, ez - 11);
+                TB_TRY(gemm_bf16_nt(ctx, h));
             }
             continue;
         }

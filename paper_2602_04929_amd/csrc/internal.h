@@ -111,6 +111,7 @@ struct GemmBf16 {
     const __hip_bfloat16* B; int64_t ldb;
     void* C; int64_t ldc; int c_dtype; int accumulate; int flags;
     void* C2 = nullptr;   // with TBOA_GEMM_C_HILO: second 16-bit result buffer (the low parts), laid out as C
+    float lo_scale = 1.f; // with TBOA_GEMM_C_HILO_HALF: the low parts are stored times this (a power of two that keeps them normal numbers)
     int batch; int64_t strideA, strideB, strideC;
     // two-level batch: z -> (z / batch_inner, z % batch_inner); the *2 strides apply to the inner index
     int batch_inner = 1; int64_t strideA2 = 0, strideB2 = 0, strideC2 = 0;

@@ -137,7 +137,7 @@ def test_bf16_block_end_to_end(lib, case, seed):
         g, w = f64(Hs[k]), Hw[k]
         e = np.abs(g - w).max() / np.abs(w).max()
         print("  %s seed %d %s: max |err| / max |entry| = %.2e" % (name, seed, k, e), flush=True)
-        assert e <= (6e-5 if k.startswith("R_v") else 1e-5), (k, e)
+        assert e <= (6e-5 if k.startswith("R_v") else 2e-6), (k, e)
     Xn, Xfn = f64(blk["X"]), f64(blk["X_fp"])
     wq, wk, wv = (f64(got[k]["W_deq"]) for k in ("q", "k", "v"))       # the oracle's Table 1 sums from the library's own W_deq
     Ho_w, Ro_w = O.build_hessian_out_proj(Xn, Xfn, wq, wk, wv, f64(blk["Wq"]), f64(blk["Wk"]), f64(blk["Wv"]), hq, hkv, dh, alpha=0.25)

@@ -85,8 +85,9 @@ def test_bf16_summed_form(ctx, hq, hkv, d, L, S, with_fp, dh):
                             alpha=0.25)
     # R_v is measured against its own largest entry and is noise-like on these inputs (X - X~ is independent of X: its entries
     # are sums that cancel), so the fp32 rounding of the scores, 2^-24 of logits of a few tens against differences A - A~ of a
-    # few percent of A, shows in it as 1e-5 to 2e-5 (with the scores from 16-bit pairs of Q and K it was 1e-4)
-    check_all(got, want, 1e-5, 1e-5, 6e-5)
+    # few percent of A, shows in it as 1e-5 to 2e-5 (with the scores from 16-bit pairs of Q and K it was 1e-4).  H_in^V: 2e-7 to
+    # 1e-6 with T1 = B1 X as pairs of halves (as pairs of bf16: up to 4e-6).
+    check_all(got, want, 1e-5, 2e-6, 6e-5)
     assert torch.equal(got["Hin_v"], got["Hin_v"].transpose(1, 2))
 
 
