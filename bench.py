@@ -113,10 +113,11 @@ def cpu_baseline(blk, cfg, hessians, out):
                                                                         t_opair, pairs, t_oseq, cfg.n_seqs)}
 
 
-def roofline_probe(ctx, cfg, torch, tag, zero=False, reps=0, persistent=False, seqs=8):
+def roofline_probe(ctx, cfg, torch, tag, zero=False, reps=0, persistent=False, seqs=8, bf16=False):
     """The command the HBM-traffic counter runs are made with: one plain copy of 1 GiB (a kernel of known traffic, to scale
     the counters), then ONE launch of the benchmark's dominant kernel in its launch shape, for all KV heads over a chunk of `seqs` (8)
-    sequences, accumulating into fp32, operands in 16 x 32 blocks at the benchmark's row pitch (random values):
+    sequences, accumulating into fp32, operands in 16 x 32 blocks at the benchmark's row pitch (random values; IEEE half, as the
+    build has them when the activations fit half, or bf16: the same kernel instantiated for the other MFMA):
       rv:      R_v[g] += alpha Z_g^T X  -- A = Z^T per KV head [d, 8 L], B = X^T [d, 8 L] shared by the heads, full product;
       hv_syrk: H_in^V[g] += T1_g^T X    -- the same operands, lower tiles only.
     zero: all-zero operands instead of random ones (same launch, same addresses: what the operand values alone do to the
@@ -128,10 +129,11 @@ def roofline_probe(ctx, cfg, torch, tag, zero=False, reps=0, persistent=False, s
     g = torch.Generator(device="cuda"); g.manual_seed(1)
     src = torch.randn(1 << 28, generator=g, device="cuda")                    # 1 GiB
     dst = torch.empty_like(src)
-    ZT = torch.empty(Hkv, n, K + 256, dtype=torch.bfloat16, device="cuda")
+    dt = torch.bfloat16 if bf16 else torch.float16
+    ZT = torch.empty(Hkv, n, K + 256, dtype=dt, device="cuda")
     for h in range(Hkv):
-        ZT[h] = torch.randn(n, K + 256, generator=g, device="cuda").to(torch.bfloat16)
-    XT = torch.randn(n, K + 256, generator=g, device="cuda").to(torch.bfloat16)
+        ZT[h] = torch.randn(n, K + 256, generator=g, device="cuda").to(dt)
+    XT = torch.randn(n, K + 256, generator=g, device="cuda").to(torch.bfloat16).to(dt)      # the input: bf16 values in either type
     if zero:
         ZT.zero_(); XT.zero_()
     C = torch.zeros(Hkv, n, n, device="cuda")
@@ -144,7 +146,8 @@ def roofline_probe(ctx, cfg, torch, tag, zero=False, reps=0, persistent=False, s
     torch.cuda.synchronize()
     cells = n * (n + 1) // 2 if tag == "hv_syrk" else n * n
     alg = Hkv * n * K * 2 + n * K * 2 + Hkv * 2 * 4 * cells                   # A read once, B read once, C read + written
-    rec = {"probe": "copy 1 GiB, then gemm_bf16_nt accumulate (%s), blocked operands, B shared by the batch" % tag, "copy_bytes_read": src.numel() * 4,
+    rec = {"probe": "copy 1 GiB, then gemm_bf16_nt accumulate (%s, %s operands), blocked operands, B shared by the batch" % (tag, "bf16" if bf16 else "half"),
+           "copy_bytes_read": src.numel() * 4,
            "copy_bytes_written": src.numel() * 4, "gemm_batch": Hkv, "gemm_M": n, "gemm_K": K,
            "gemm_algorithmic_bytes": alg, "operands": "zero" if zero else "random"}
     if reps > 0:
@@ -182,6 +185,7 @@ def main():
     ap.add_argument("--probe-zero", action="store_true", help="with --roofline-probe: all-zero operands (same launch otherwise)")
     ap.add_argument("--probe-reps", type=int, default=0, help="with --roofline-probe: time this many further launches of the kernel")
     ap.add_argument("--probe-seqs", type=int, default=8, help="with --roofline-probe: sequences per launch (the contraction is seqs x seq_len deep)")
+    ap.add_argument("--probe-bf16", action="store_true", help="with --roofline-probe: bf16 operands (what the build takes when an activation exceeds the range of half)")
     ap.add_argument("--probe-persistent", action="store_true", help="with --roofline-probe: the persistent form of the kernel (one resident workgroup per CU)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -202,7 +206,7 @@ def main():
     torch.cuda.set_device(0)
     if args.roofline_probe:
         ctx = tb.Context()
-        roofline_probe(ctx, cfg, torch, args.probe_tag, zero=args.probe_zero, reps=args.probe_reps, persistent=args.probe_persistent, seqs=args.probe_seqs)
+        roofline_probe(ctx, cfg, torch, args.probe_tag, zero=args.probe_zero, reps=args.probe_reps, persistent=args.probe_persistent, seqs=args.probe_seqs, bf16=args.probe_bf16)
         ctx.close()
         return
     note = lambda msg: print("bench.py: " + msg, file=sys.stderr, flush=True)      # progress on stderr; stdout carries the one JSON line
