@@ -231,6 +231,34 @@ def test_llama2_70b_shape_out_proj_hessian_block(c70):
     check_out_proj_block(c70, 43)
 
 
+def test_llama2_70b_full_size_is_the_sum_of_its_parts(lib):
+    """The benchmark's workload at its full size (128 sequences: 16 passes of the 8-sequence chunks, token offsets beyond
+    2^31 elements): every Hessian is a sum over the sequences, so the build over all 128 must equal the sum of the builds over
+    the eight disjoint runs of 16 sequences, each of which is the shape the tests above compare with the oracle.  Same
+    kernels on both sides: what this checks is the chunk loop, its offsets and its accumulation at the full size."""
+    cfg = synth.CONFIGS["llama2-70b"]
+    print("building the full llama2-70b block (128 sequences)", flush=True)
+    blk = synth.make_block(cfg, seed=0, device="cuda")
+    ctx = lib.Context()
+    args = (blk["Wq"], blk["Wk"], blk["Wv"], blk["Wo"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+    keys = ("Hin_qk", "R_qk", "Hout_q", "Hout_k", "Hin_v", "R_v")
+    full = ctx.build_hessians(blk["X"], blk["X_fp"], *args, alpha=ALPHA)
+    full = {k: full[k].clone() for k in keys}
+    acc = {k: torch.zeros_like(full[k], dtype=torch.float64) for k in keys}
+    for p in range(0, cfg.n_seqs, N_SEQS):
+        part = ctx.build_hessians(blk["X"][p:p + N_SEQS], blk["X_fp"][p:p + N_SEQS], *args, alpha=ALPHA)
+        for k in keys:
+            acc[k] += part[k].double()
+        print("  sequences %d .. %d" % (p, p + N_SEQS - 1), flush=True)
+    for k in keys:
+        e = float((full[k].double() - acc[k]).abs().max() / acc[k].abs().max())
+        print("  %s: max |whole - sum of parts| / max |entry| = %.2e" % (k, e), flush=True)
+        assert e <= 2e-6, (k, e)
+    ctx.close()
+    del blk, full, acc
+    torch.cuda.empty_cache()
+
+
 def test_llama2_7b_w4a4_shape(lib):
     c = build(lib, "llama2-7b-w4a4")
     try:
