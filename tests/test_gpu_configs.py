@@ -254,8 +254,23 @@ def test_llama2_70b_full_size_is_the_sum_of_its_parts(lib):
         e = float((full[k].double() - acc[k]).abs().max() / acc[k].abs().max())
         print("  %s: max |whole - sum of parts| / max |entry| = %.2e" % (k, e), flush=True)
         assert e <= 2e-6, (k, e)
+    del full, acc
+    # the W_O Hessians likewise (weights without grid structure: the three-term operands), the whole reading the projections of
+    # X~ that a build over all sequences left in its cache, the parts recomputing them
+    deq = [blk[k].float() for k in ("Wq", "Wk", "Wv")]
+    cache = ctx.build_hessians(blk["X"], blk["X_fp"], *args, alpha=ALPHA, keep_fp_projections=True)["fp_cache"]
+    wargs = (*deq, blk["Wq"], blk["Wk"], blk["Wv"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+    Ho, Ro = ctx.build_hessian_out_proj(blk["X"], blk["X_fp"], *wargs, alpha=ALPHA, fp_cache=cache)
+    aH = torch.zeros_like(Ho, dtype=torch.float64); aR = torch.zeros_like(Ro, dtype=torch.float64)
+    for p in range(0, cfg.n_seqs, 2 * N_SEQS):
+        h, r = ctx.build_hessian_out_proj(blk["X"][p:p + 2 * N_SEQS], blk["X_fp"][p:p + 2 * N_SEQS], *wargs, alpha=ALPHA)
+        aH += h.double(); aR += r.double()
+    for k, g, w in (("Hin_o", Ho, aH), ("R_o", Ro, aR)):
+        e = float((g.double() - w).abs().max() / w.abs().max())
+        print("  %s: max |whole - sum of parts| / max |entry| = %.2e" % (k, e), flush=True)
+        assert e <= 2e-6, (k, e)
     ctx.close()
-    del blk, full, acc
+    del blk, cache
     torch.cuda.empty_cache()
 
 
