@@ -123,6 +123,9 @@ def test_gemm_bf16_flags_and_batch(ctx, lib):
     (2304, 2048, 256, 5, 0),          # 360 tiles: several rounds per workgroup, short tiles back to back
     (1280, 1280, 512, 9, 1),          # symmetric product, lower tiles only
     (520, 1536, 1536, 7, 2),          # causal limit: tiles of 8 different lengths, balanced lists
+    (128, 1536, 1536, 12, 2),         # results of 128 rows (an attention output of one head): the lower half of every tile idles
+    (96, 700, 640, 5, 0),             # ... fewer rows than that, ragged columns
+    (64, 512, 256, 300, 0),           # ... many batch entries: several tiles per workgroup
 ])
 def test_gemm_bf16_persistent_matches_dispatched(ctx, lib, M, N, K, batch, flags):
     """The persistent kernel (one resident workgroup per compute unit, one stream of stages across tiles) accumulates every
