@@ -258,8 +258,8 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
             if (it + 1 < live) issue(64 * (it + 1));
         }
         if constexpr (ROWS) {
-            // row-major result P[h][t][.] = [A_hi | A_lo | A~_hi | A~_lo] (segments of L columns): eight consecutive lanes take the 64
-            // keys of one query, 8 each, so that a wavefront store covers eight whole 128-byte rows; two queries per thread
+            // per-head result P[h][t][.] = [A_hi | A_lo | A~_hi | A~_lo] (segments of L columns), queries as rows: eight consecutive
+            // lanes take the 64 keys of one query, 8 each; two queries per thread
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int slot = threadIdx.x + 512 * half, i8 = slot & 7, tq2 = slot >> 3;
@@ -271,9 +271,11 @@ __global__ __launch_bounds__(512) void attn_probs_t_kernel(const bf16* __restric
                     hi.b[e] = enc16(a, f16); lo.b[e] = enc16(a - dec16(hi.b[e], f16), f16);
                     h2.b[e] = enc16(a2, f16); l2.b[e] = enc16(a2 - dec16(h2.b[e], f16), f16);
                 }
-                bf16* prow = out.hi + h * group_stride + (long long)(t0 + tq2) * ldp + i0 + 8 * i8;
-                *(uint4*)prow = hi.u; *(uint4*)(prow + L) = lo.u;
-                if (two) { *(uint4*)(prow + 2LL * L) = h2.u; *(uint4*)(prow + 3LL * L) = l2.u; }
+                // (the head's [L, ldp] matrix in 16 x 32 blocks: the eight queries of a wavefront store are 512 contiguous bytes per block)
+                bf16* ph = out.hi + h * group_stride;
+                const long long kb = ldp >> 5, tq3 = t0 + tq2, col = i0 + 8 * i8;
+                *(uint4*)(ph + tboa_blocked_offset(tq3, col, kb)) = hi.u; *(uint4*)(ph + tboa_blocked_offset(tq3, L + col, kb)) = lo.u;
+                if (two) { *(uint4*)(ph + tboa_blocked_offset(tq3, 2LL * L + col, kb)) = h2.u; *(uint4*)(ph + tboa_blocked_offset(tq3, 3LL * L + col, kb)) = l2.u; }
             }
         } else {
             // transposed blocked result: sixteen consecutive lanes take the 128 queries of one key row, 8 each (one 16-byte piece per
@@ -347,7 +349,7 @@ int attn_probs_t(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, 
 
 int attn_probs_rows(tboa_ctx* ctx, const bf16* Qa, const bf16* Ka, const bf16* Qb, const bf16* Kb, int L, int Hq, int rep, int dh, bf16* P,
                     long long ldp, int f16, QkScale qs) {
-    if (!attn_probs_t_supported(L, dh) || Hq % rep || !Qa || !Ka || (Qb && !Kb) || !P || ldp % 8 || ldp < (Qb ? 4LL : 2LL) * L || ((uintptr_t)P & 15))
+    if (!attn_probs_t_supported(L, dh) || Hq % rep || !Qa || !Ka || (Qb && !Kb) || !P || ldp % 32 || ldp < (Qb ? 4LL : 2LL) * L || ((uintptr_t)P & 15))
         return tboa_fail(ctx, TBOA_EINVAL, "attn_probs_rows: unsupported shape or missing buffer");
     PtOut out{P, nullptr, nullptr, nullptr};
     return dispatch<true>(ctx, Qa, Ka, Qb, Kb, L, Hq, rep, dh, out, ldp, (long long)L * ldp, f16, qs);

@@ -1344,17 +1344,18 @@ int build_hessian_out_proj_bf16(tboa_ctx* ctx, const tboa_attn_desc* d, const bf
             o.strideA = (long long)dh * ldv; o.strideA2 = 0;
             o.strideB = (long long)rep * L * ldp; o.strideB2 = (long long)L * ldp;
             o.strideC = (long long)rep * dh * TP; o.strideC2 = (long long)dh * TP;
-            if (fused) {
+            if (fused) {       // (the fused kernel leaves P in 16 x 32 blocks: a column offset c is the pointer offset 16 c)
+                o.flags |= TBOA_GEMM_B_TILED;
                 o.nterms = 3;
                 o.termA[0] = o.A; o.termA[1] = o.A; o.termA[2] = o.A + 2 * L;
-                o.termB[0] = P; o.termB[1] = P + L; o.termB[2] = P;
+                o.termB[0] = P; o.termB[1] = P + 16LL * L; o.termB[2] = P;
             }
             TB_TRY(gemm_bf16_nt(ctx, o));
             if (fp) {       // O~^T for now
-                o.A = VTc + ((long long)sl * nsg + 3) * L; o.B = P + (fused ? 2 : 3) * L; o.C = dOT + co; o.C2 = dOTl + co;
+                o.A = VTc + ((long long)sl * nsg + 3) * L; o.B = P + (fused ? 16LL * 2 : 3) * L; o.C = dOT + co; o.C2 = dOTl + co;
                 if (fused) {
                     o.termA[0] = o.A; o.termA[1] = o.A; o.termA[2] = o.A + 2 * L;
-                    o.termB[0] = o.B; o.termB[1] = o.B + L; o.termB[2] = o.B;
+                    o.termB[0] = o.B; o.termB[1] = o.B + 16LL * L; o.termB[2] = o.B;
                 }
                 TB_TRY(gemm_bf16_nt(ctx, o));
             }

@@ -147,8 +147,9 @@ __host__ __device__ __forceinline__ int tboa_half_exp(int amax_bits) {
 // straight from the blocked 3-term operands Q^ [Hq][L, 3 dh], K^ [Hkv][L, 3 dh] of the score product (second pair Qb, Kb or
 // nullptr); attn_probs_t_supported tells which shapes the kernel takes
 bool attn_probs_t_supported(int L, int dh);
-// the same probabilities as row-major P[h][t][.] = [A_hi | A_lo | A~_hi | A~_lo] (segments of L columns, pitch ldp; the last two
-// only with a second pair: the probabilities of the second score matrix), rows written up to the end of the 256-tile of t
+// the same probabilities with the queries as rows, P[h][t][.] = [A_hi | A_lo | A~_hi | A~_lo] (segments of L columns, pitch ldp, a
+// multiple of 32: every head's [L, ldp] matrix in 16 x 32 blocks; the last two segments only with a second pair: the
+// probabilities of the second score matrix), rows written up to the end of the 256-tile of t
 int attn_probs_rows(tboa_ctx* ctx, const __hip_bfloat16* Qa, const __hip_bfloat16* Ka, const __hip_bfloat16* Qb, const __hip_bfloat16* Kb, int L,
                     int Hq, int rep, int dh, __hip_bfloat16* P, long long ldp, int f16, QkScale qs);
 int attn_probs_t(tboa_ctx* ctx, const __hip_bfloat16* Qa, const __hip_bfloat16* Ka, const __hip_bfloat16* Qb, const __hip_bfloat16* Kb, int L,
