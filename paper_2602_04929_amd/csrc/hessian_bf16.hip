@@ -212,7 +212,10 @@ __global__ __launch_bounds__(256) void amax_seq_kernel(const float* __restrict__
         for (long long i = tid; i < n; i += nth) take(scale ? src[i] * scale[i % hd] : src[i]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-    if ((threadIdx.x & 63) == 0) atomicMax(out + blockIdx.y, __float_as_int(m));
+    __shared__ float red[4];      // one atomic per workgroup: they all land on the sequence's one word
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicMax(out + blockIdx.y, __float_as_int(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
 }
 
 // fp32 [n] -> three bf16 terms whose sum is the value to 24 bits
@@ -834,8 +837,8 @@ int project_qk(const Dims& D, const bf16* Xr, int rows, const bf16* Wq, const bf
         const int ns = rows / D.L;
         TB_TRY(launch_fill_f32(D.ctx, (float*)amax_q, ns, -1.f));       // any negative word: the bits of the largest magnitude replace it
         TB_TRY(launch_fill_f32(D.ctx, (float*)amax_k, ns, -1.f));
-        hipLaunchKernelGGL(amax_seq_kernel, dim3(64, ns), dim3(256), 0, D.ctx->stream, Qf, q_scale, D.L, D.dq, amax_q);
-        hipLaunchKernelGGL(amax_seq_kernel, dim3(64, ns), dim3(256), 0, D.ctx->stream, Kf, k_scale, D.L, D.dkv, amax_k);
+        hipLaunchKernelGGL(amax_seq_kernel, dim3(256, ns), dim3(256), 0, D.ctx->stream, Qf, q_scale, D.L, D.dq, amax_q);
+        hipLaunchKernelGGL(amax_seq_kernel, dim3(256, ns), dim3(256), 0, D.ctx->stream, Kf, k_scale, D.L, D.dkv, amax_k);
     }
     hipLaunchKernelGGL(split3_kernel, dim3(g1((long long)rows * D.dq)), dim3(256), 0, D.ctx->stream, Qf, q_scale, Qh, (long long)rows, D.dq, D.dh, 0,
                        qk_blocked(D) ? D.L : 0, amax_q);
